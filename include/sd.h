@@ -1,0 +1,192 @@
+/*
+ * sd.h - C ABI of the draft-then-verify hot path of speculative decoding on one
+ * AMD MI355X (gfx950).  Every step of the path runs in HIP kernels of this
+ * library; there is no CPU fallback.
+ *
+ * Paper: arXiv 2505.08600.  Section 1 / Figure 1 define the two phases (a draft
+ * model decodes gamma candidates autoregressively; the target model scores them in
+ * one parallel pass), Section 2.1 / 2.4 the routing of a prompt to one of several
+ * heterogeneous drafts, Section 3.1 the verification rule (speculative sampling;
+ * greedy decoding as its argmax limit) and the LLaMA model family.
+ *
+ * State convention.  A context (sd_ctx) holds B sequences.  Sequence b has tokens
+ * x_0..x_{n-1} in a device buffer of fixed capacity.  For every model attached to
+ * the context there is a KV cache; the target's covers positions [0, n-1) between
+ * calls (the last token is "pending": it is fed by the next verify), a draft's
+ * covers [0, m) with m <= n-1.  All per-sequence lengths live in device memory, so
+ * the draft -> verify -> draft loop needs no host synchronisation.
+ *
+ * Conventions for every call:
+ *   - returns SD_OK (0) or a negative sd_status; sd_last_error() gives the text of
+ *     the calling thread's last failure.  Nothing throws or aborts.
+ *   - "dev" pointers are device memory owned by the caller and must stay valid
+ *     until the work queued on `stream` has finished; "host" pointers are read
+ *     before the call returns.
+ *   - `stream` is a hipStream_t (NULL = the default stream).  sd_draft, sd_verify,
+ *     sd_commit and sd_route only enqueue work; they never synchronise.
+ *   - a model owns one activation workspace: at most one forward of a given model
+ *     may be in flight at a time (calls on one stream are naturally ordered).
+ *   - seq_ids (dev, int32[n_seq], or NULL for 0..n_seq-1) selects the sequences of
+ *     the context a call works on; ids must be distinct.
+ */
+#ifndef SD_H
+#define SD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sd_model sd_model; /* opaque: one target or draft model */
+typedef struct sd_ctx sd_ctx;     /* opaque: B sequences, their tokens and KV caches */
+
+typedef enum {
+    SD_OK = 0,
+    SD_EINVAL = -1, /* null pointer, bad shape, unsupported configuration */
+    SD_ECAP = -2,   /* rows, gamma, batch or sequence capacity exceeded */
+    SD_EHIP = -3,   /* HIP runtime failure; text in sd_last_error() */
+    SD_ESTATE = -4  /* device-side consistency flag raised (see sd_ctx_sync) */
+} sd_status;
+
+enum { SD_FP32 = 0, SD_BF16 = 1 };
+
+/* LLaMA-style decoder shape (Section 3.1 "Models"): pre-norm blocks with RMSNorm,
+ * rotary embedding (rotate-half pairing, angle pos * rope_base^(-2i/head_dim)),
+ * multi-head causal attention (n_kv_heads == n_heads), SwiGLU FFN, untied LM head,
+ * no biases.  n_heads * head_dim must equal d_model; head_dim is 64 or 128.
+ * dtype SD_BF16: weights, KV cache and GEMM input activations are bf16, all
+ * accumulation, the residual stream, softmax and logits are fp32.
+ * dtype SD_FP32: everything fp32.
+ * max_rows: largest number of token rows one forward may carry
+ *           (verify: n_seq * (gamma + 1); draft: 2 * n_seq; prefill chunks adapt).
+ * max_pos : largest position + 1 (size of the rotary table). */
+typedef struct {
+    int32_t n_layers, d_model, n_heads, head_dim, d_ffn, vocab;
+    int32_t dtype;
+    float rope_base, rms_eps;
+    int32_t max_rows, max_pos;
+} sd_model_config;
+
+/* Device pointers to the weights, each matrix row-major [out][in] in the model's
+ * dtype; RMSNorm gains are fp32 in both dtypes.  The per-layer members are HOST
+ * arrays of n_layers DEVICE pointers.  Pointers are borrowed: the caller keeps the
+ * memory alive until sd_free_model.  Matrices must be 16-byte aligned. */
+typedef struct {
+    const void *embed;         /* [vocab][d_model] */
+    const void *lm_head;       /* [vocab][d_model] */
+    const float *final_norm;   /* [d_model] */
+    const void *const *wq;     /* [d_model][d_model] per layer */
+    const void *const *wk;
+    const void *const *wv;
+    const void *const *wo;     /* [d_model][d_model] */
+    const void *const *wgate;  /* [d_ffn][d_model] */
+    const void *const *wup;    /* [d_ffn][d_model] */
+    const void *const *wdown;  /* [d_model][d_ffn] */
+    const float *const *norm_attn; /* [d_model] */
+    const float *const *norm_ffn;  /* [d_model] */
+} sd_weights;
+
+/* Validate the configuration, record the borrowed weight pointers, build the
+ * rotary table and allocate the activation workspace on the current device.
+ * Synchronises.  SD_EINVAL on unsupported shapes. */
+int sd_load_model(const sd_model_config *cfg, const sd_weights *w, sd_model **out);
+int sd_free_model(sd_model *m);
+
+/* A context of `batch` sequences; caps (host, int32[batch]) is each sequence's
+ * capacity in tokens (prompt + everything generated + gamma + 1 slack).  Allocates
+ * the token buffers.  Synchronises. */
+int sd_ctx_create(int32_t batch, const int32_t *caps, sd_ctx **out);
+int sd_ctx_free(sd_ctx *c);
+
+/* Allocate model m's KV cache for every sequence of the context (K as
+ * [layer][head][token][head_dim], V transposed as [layer][head][head_dim][token],
+ * tokens of all sequences concatenated at their capacity offsets).  At most 8
+ * models per context.  Synchronises. */
+int sd_ctx_attach(sd_ctx *c, sd_model *m);
+
+/* Replace the tokens of sequences seq_ids (HOST int32[n_seq], or NULL) with the
+ * concatenation in tokens (host), lens (host int32[n_seq], each >= 1), and reset
+ * every attached model's cache length for them to 0.  Synchronises. */
+int sd_ctx_set_tokens(sd_ctx *c, const int32_t *tokens, const int32_t *lens, const int32_t *seq_ids,
+                      int32_t n_seq);
+
+/* Feed model m with every token of the selected sequences that its cache does
+ * not cover yet, except the pending last one (the step before the hot path; here
+ * it reuses the verify kernels in row chunks).  max_new (host) is the largest
+ * number of tokens any selected sequence still has to feed; it fixes the number
+ * of chunks.  Enqueues on stream. */
+int sd_prefill(sd_model *m, sd_ctx *c, const int32_t *seq_ids /*dev*/, int32_t n_seq, int32_t max_new,
+               void *stream);
+
+/* Draft phase (Section 1, Figure 1a).  For each selected sequence: feed the
+ * catch-up rows (tokens the draft's cache lacks, at most 2 once prefilled), then
+ * decode gamma candidates autoregressively.  temperature > 0: candidate i is
+ * drawn by inverse CDF in index order from q_i = softmax(logits_i / T) with
+ * uniforms[j][i]; q[j][i][:] receives the full fp32 distribution.  temperature
+ * == 0 (greedy): candidate = argmax (ties to the lowest id); q and uniforms are
+ * not touched and may be NULL.  The last candidate is not fed to the draft.
+ *   uniforms dev fp32 [n_seq][gamma], cand dev int32 [n_seq][gamma],
+ *   q dev fp32 [n_seq][gamma][vocab].  1 <= gamma <= 15. */
+int sd_draft(sd_model *draft, sd_ctx *c, const int32_t *seq_ids /*dev*/, int32_t n_seq, int32_t gamma,
+             float temperature, const float *uniforms, int32_t *cand, float *q, void *stream);
+
+/* Verify phase (Section 1, Figure 1b; rule of Section 3.1).  For each selected
+ * sequence the target scores the gamma+1 rows (pending token, cand_1..cand_gamma)
+ * in one forward pass against its cache, with a causal mask over the new rows.
+ * With p_i = softmax(logits_i / T): candidate i is accepted iff
+ * uniforms[j][i] < p_i(cand_i) / q_i(cand_i), scanning i = 1..gamma and stopping
+ * at the first rejection; n_accepted counts the accepted ones.  The next token is
+ * drawn with uniforms[j][gamma] by inverse CDF from norm(max(0, p - q)) of the
+ * rejected position, or from p_{gamma+1} if all were accepted.  temperature == 0:
+ * accept iff cand_i == argmax logits_i, next = argmax of the first unmatched row.
+ * gamma == 0 is one plain autoregressive step of the target.
+ * commit != 0 also performs sd_commit's update inside the same kernel.
+ *   cand dev int32 [n_seq][gamma]; q dev fp32 [n_seq][gamma][vocab] (NULL if
+ *   greedy); uniforms dev fp32 [n_seq][gamma+1] (NULL if greedy);
+ *   n_accepted, next_token dev int32 [n_seq].  0 <= gamma <= 15. */
+int sd_verify(sd_model *target, sd_ctx *c, const int32_t *seq_ids /*dev*/, int32_t n_seq, int32_t gamma,
+              float temperature, const int32_t *cand, const float *q, const float *uniforms,
+              int32_t *n_accepted, int32_t *next_token, int32_t commit, void *stream);
+
+/* Commit / KV rollback: append cand[0..n_accepted) and next_token to each selected
+ * sequence, then set every attached model's cache length to
+ * min(its length, new token count - 1).  No cache data moves: rows of rejected
+ * candidates are dead and get overwritten by the next append. */
+int sd_commit(sd_ctx *c, const int32_t *seq_ids /*dev*/, int32_t n_seq, int32_t gamma, const int32_t *cand,
+              const int32_t *n_accepted, const int32_t *next_token, void *stream);
+
+/* Routing (Sections 2.1, 2.4): draft_id[i] = argmax_k (W[k] . prompt_emb[i] + b[k]),
+ * ties to the lowest id.  All pointers dev; b may be NULL.
+ *   W fp32 [n_drafts][emb_dim], prompt_emb fp32 [n][emb_dim], draft_id int32 [n]. */
+int sd_route(const float *W, const float *b, int32_t n_drafts, int32_t emb_dim, const float *prompt_emb,
+             int32_t n, int32_t *draft_id, void *stream);
+
+/* ---- inspection and test hooks (synchronising; not on the hot path) ---- */
+
+/* Copy token counts (and model m's cache lengths, if m and kv_len are non-NULL) to
+ * host arrays int32[batch]; refresh the host-side length bounds used for launch
+ * sizing; return SD_ESTATE if a kernel flagged an inconsistency (row beyond
+ * capacity, verify on a sequence whose cache is not at n-1). */
+int sd_ctx_sync(sd_ctx *c, sd_model *m, int32_t *n_tokens, int32_t *kv_len);
+/* Copy up to max_tokens tokens of sequence seq to host; *n_out = its length. */
+int sd_ctx_get_tokens(sd_ctx *c, int32_t seq, int32_t *out, int32_t max_tokens, int32_t *n_out);
+/* Load synthetic cache rows for one layer and sequence: k, v HOST arrays
+ * [len][n_heads][head_dim] in the model's dtype; sets that model's cache length
+ * for the sequence to len. */
+int sd_ctx_set_kv(sd_ctx *c, sd_model *m, int32_t layer, int32_t seq, const void *k, const void *v, int32_t len);
+/* KV rollback by hand: set model m's cache length for sequence seq to
+ * min(current, len).  Rows beyond stay in memory and are overwritten later. */
+int sd_ctx_truncate(sd_ctx *c, sd_model *m, int32_t seq, int32_t len);
+/* Copy the fp32 logits [rows][vocab] of model m's last forward into out (dev,
+ * room for max_rows rows); *rows = rows copied. */
+int sd_last_logits(sd_model *m, float *out, int32_t max_rows, int32_t *rows);
+/* option "force_generic" = 1 routes every op through the simple reference kernels. */
+int sd_set_option(const char *name, int32_t value);
+
+const char *sd_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SD_H */

@@ -1,0 +1,236 @@
+"""Thin Python binding of libsd (include/sd.h): argument marshalling only.
+
+PyTorch is used for device memory and streams; every step of the draft/verify
+path runs in the HIP kernels of libsd.so.  There is no fallback: if the library
+is missing, importing a symbol from it raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsd.so")
+_lib = None
+
+SD_OK, SD_EINVAL, SD_ECAP, SD_EHIP, SD_ESTATE = 0, -1, -2, -3, -4
+SD_FP32, SD_BF16 = 0, 1
+
+EXPORTS = ["sd_load_model", "sd_free_model", "sd_ctx_create", "sd_ctx_free", "sd_ctx_attach", "sd_ctx_set_tokens",
+           "sd_prefill", "sd_draft", "sd_verify", "sd_commit", "sd_route", "sd_ctx_sync", "sd_ctx_get_tokens",
+           "sd_ctx_set_kv", "sd_ctx_truncate", "sd_last_logits", "sd_set_option", "sd_last_error"]
+
+
+class SdError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libsd error {code}: {msg}")
+        self.code = code
+
+
+class _Config(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("d_ffn", C.c_int32), ("vocab", C.c_int32), ("dtype", C.c_int32), ("rope_base", C.c_float),
+                ("rms_eps", C.c_float), ("max_rows", C.c_int32), ("max_pos", C.c_int32)]
+
+
+class _Weights(C.Structure):
+    _fields_ = [("embed", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p)] + \
+               [(n, C.POINTER(C.c_void_p)) for n in ("wq", "wk", "wv", "wo", "wgate", "wup", "wdown",
+                                                     "norm_attn", "norm_ffn")]
+
+
+def lib():
+    """Load libsd.so (built in-tree by paper_2505_08600_amd.build); never falls back."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2505_08600_amd.build` "
+                              "(there is no CPU fallback for the draft/verify path)")
+        L = C.CDLL(LIB_PATH)
+        vp, i32 = C.c_void_p, C.c_int32
+        L.sd_load_model.argtypes = [C.POINTER(_Config), C.POINTER(_Weights), C.POINTER(vp)]
+        L.sd_free_model.argtypes = [vp]
+        L.sd_ctx_create.argtypes = [i32, vp, C.POINTER(vp)]
+        L.sd_ctx_free.argtypes = [vp]
+        L.sd_ctx_attach.argtypes = [vp, vp]
+        L.sd_ctx_set_tokens.argtypes = [vp, vp, vp, vp, i32]
+        L.sd_prefill.argtypes = [vp, vp, vp, i32, i32, vp]
+        L.sd_draft.argtypes = [vp, vp, vp, i32, i32, C.c_float, vp, vp, vp, vp]
+        L.sd_verify.argtypes = [vp, vp, vp, i32, i32, C.c_float, vp, vp, vp, vp, vp, i32, vp]
+        L.sd_commit.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp]
+        L.sd_route.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp]
+        L.sd_ctx_sync.argtypes = [vp, vp, vp, vp]
+        L.sd_ctx_get_tokens.argtypes = [vp, i32, vp, i32, C.POINTER(i32)]
+        L.sd_ctx_set_kv.argtypes = [vp, vp, i32, i32, vp, vp, i32]
+        L.sd_ctx_truncate.argtypes = [vp, vp, i32, i32]
+        L.sd_last_logits.argtypes = [vp, vp, i32, C.POINTER(i32)]
+        L.sd_set_option.argtypes = [C.c_char_p, i32]
+        L.sd_last_error.restype = C.c_char_p
+        _lib = L
+    return _lib
+
+
+def _check(rc: int) -> None:
+    if rc != SD_OK:
+        raise SdError(rc, lib().sd_last_error().decode())
+
+
+def _dp(t: Optional[torch.Tensor]):
+    """Device pointer of a contiguous tensor (None -> NULL)."""
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous()
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream() -> C.c_void_p:
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _np_i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def set_option(name: str, value: int) -> None:
+    _check(lib().sd_set_option(name.encode(), int(value)))
+
+
+def to_device(a: np.ndarray, device="cuda") -> torch.Tensor:
+    """Upload a numpy array; uint16 bf16 bit patterns travel as int16."""
+    if a.dtype == np.uint16:
+        a = a.view(np.int16)
+    return torch.from_numpy(np.ascontiguousarray(a)).to(device)
+
+
+class Model:
+    """sd_load_model / sd_free_model.  Keeps the weight tensors alive (the library borrows them)."""
+
+    def __init__(self, shape, weights: Dict[str, object], max_rows: int, max_pos: int, device="cuda"):
+        self.shape = shape
+        self.device = device
+        self.t: Dict[str, object] = {}
+        for k, v in weights.items():
+            self.t[k] = [to_device(a, device) for a in v] if isinstance(v, list) else to_device(v, device)
+        L = shape.n_layers
+        self._arrs = {}
+        w = _Weights()
+        w.embed, w.lm_head, w.final_norm = (self.t[n].data_ptr() for n in ("embed", "lm_head", "final_norm"))
+        for n in ("wq", "wk", "wv", "wo", "wgate", "wup", "wdown", "norm_attn", "norm_ffn"):
+            arr = (C.c_void_p * L)(*[t.data_ptr() for t in self.t[n]])
+            self._arrs[n] = arr
+            setattr(w, n, C.cast(arr, C.POINTER(C.c_void_p)))
+        cfg = _Config(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.d_ffn, shape.vocab,
+                      shape.dtype, shape.rope_base, shape.rms_eps, max_rows, max_pos)
+        self.max_rows = max_rows
+        h = C.c_void_p()
+        with torch.cuda.device(device):
+            _check(lib().sd_load_model(C.byref(cfg), C.byref(w), C.byref(h)))
+        self.h = h
+
+    def close(self):
+        if getattr(self, "h", None):
+            lib().sd_free_model(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def last_logits(self) -> torch.Tensor:
+        """Copy of the fp32 logits [rows][vocab] of the last forward (synchronises)."""
+        out = torch.empty((self.max_rows, self.shape.vocab), dtype=torch.float32, device=self.device)
+        rows = C.c_int32()
+        _check(lib().sd_last_logits(self.h, _dp(out), self.max_rows, C.byref(rows)))
+        return out[:rows.value]
+
+
+class Context:
+    """sd_ctx_*: B sequences with per-sequence capacities."""
+
+    def __init__(self, caps: Sequence[int]):
+        self.caps = _np_i32(caps)
+        self.B = len(self.caps)
+        h = C.c_void_p()
+        _check(lib().sd_ctx_create(self.B, self.caps.ctypes.data_as(C.c_void_p), C.byref(h)))
+        self.h = h
+        self._models: List[Model] = []
+
+    def close(self):
+        if getattr(self, "h", None):
+            lib().sd_ctx_free(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def attach(self, m: Model) -> None:
+        _check(lib().sd_ctx_attach(self.h, m.h))
+        self._models.append(m)
+
+    def set_tokens(self, seqs: Sequence[Sequence[int]], seq_ids: Optional[Sequence[int]] = None) -> None:
+        lens = _np_i32([len(s) for s in seqs])
+        flat = _np_i32(np.concatenate([np.asarray(s, dtype=np.int32) for s in seqs]))
+        ids = _np_i32(seq_ids) if seq_ids is not None else None
+        _check(lib().sd_ctx_set_tokens(self.h, flat.ctypes.data_as(C.c_void_p), lens.ctypes.data_as(C.c_void_p),
+                                       ids.ctypes.data_as(C.c_void_p) if ids is not None else None, len(seqs)))
+
+    def sync(self, m: Optional[Model] = None):
+        """-> (n_tokens[B], kv_len[B] or None); raises SdError(SD_ESTATE) on a device flag."""
+        nt = np.zeros(self.B, np.int32)
+        kv = np.zeros(self.B, np.int32) if m is not None else None
+        _check(lib().sd_ctx_sync(self.h, m.h if m is not None else None, nt.ctypes.data_as(C.c_void_p),
+                                 kv.ctypes.data_as(C.c_void_p) if kv is not None else None))
+        return nt, kv
+
+    def get_tokens(self, seq: int) -> np.ndarray:
+        out = np.zeros(int(self.caps[seq]) + 64, np.int32)
+        n = C.c_int32()
+        _check(lib().sd_ctx_get_tokens(self.h, seq, out.ctypes.data_as(C.c_void_p), out.shape[0], C.byref(n)))
+        return out[:n.value].copy()
+
+    def truncate(self, m: Model, seq: int, length: int) -> None:
+        _check(lib().sd_ctx_truncate(self.h, m.h, seq, length))
+
+    def set_kv(self, m: Model, layer: int, seq: int, k: np.ndarray, v: np.ndarray) -> None:
+        k, v = np.ascontiguousarray(k), np.ascontiguousarray(v)
+        _check(lib().sd_ctx_set_kv(self.h, m.h, layer, seq, k.ctypes.data_as(C.c_void_p),
+                                   v.ctypes.data_as(C.c_void_p), k.shape[0]))
+
+
+def sd_prefill(m: Model, ctx: Context, seq_ids: Optional[torch.Tensor], n_seq: int, max_new: int) -> None:
+    _check(lib().sd_prefill(m.h, ctx.h, _dp(seq_ids), n_seq, max_new, _stream()))
+
+
+def sd_draft(draft: Model, ctx: Context, seq_ids: Optional[torch.Tensor], n_seq: int, gamma: int,
+             temperature: float, uniforms: Optional[torch.Tensor], cand: torch.Tensor,
+             q: Optional[torch.Tensor]) -> None:
+    _check(lib().sd_draft(draft.h, ctx.h, _dp(seq_ids), n_seq, gamma, temperature, _dp(uniforms), _dp(cand), _dp(q),
+                          _stream()))
+
+
+def sd_verify(target: Model, ctx: Context, seq_ids: Optional[torch.Tensor], n_seq: int, gamma: int,
+              temperature: float, cand: Optional[torch.Tensor], q: Optional[torch.Tensor],
+              uniforms: Optional[torch.Tensor], n_accepted: torch.Tensor, next_token: torch.Tensor,
+              commit: bool = True) -> None:
+    _check(lib().sd_verify(target.h, ctx.h, _dp(seq_ids), n_seq, gamma, temperature, _dp(cand), _dp(q),
+                           _dp(uniforms), _dp(n_accepted), _dp(next_token), int(commit), _stream()))
+
+
+def sd_commit(ctx: Context, seq_ids: Optional[torch.Tensor], n_seq: int, gamma: int, cand: Optional[torch.Tensor],
+              n_accepted: torch.Tensor, next_token: torch.Tensor) -> None:
+    _check(lib().sd_commit(ctx.h, _dp(seq_ids), n_seq, gamma, _dp(cand), _dp(n_accepted), _dp(next_token),
+                           _stream()))
+
+
+def sd_route(W: torch.Tensor, b: Optional[torch.Tensor], prompt_emb: torch.Tensor, draft_id: torch.Tensor) -> None:
+    _check(lib().sd_route(_dp(W), _dp(b), W.shape[0], W.shape[1], _dp(prompt_emb), prompt_emb.shape[0],
+                          _dp(draft_id), _stream()))

@@ -1,0 +1,833 @@
+// Reference-quality HIP kernels of the draft/verify path: they work for every
+// supported shape in fp32 and bf16.  The fp32 (tiny) configuration runs on these
+// alone; bf16 models use the MFMA kernels of the other files where their shape
+// constraints hold and fall back here otherwise.
+//
+// Paper (arXiv 2505.08600): Section 1 / Figure 1 (draft rows, verify rows),
+// Section 3.1 (LLaMA blocks; speculative-sampling verification, greedy limit).
+#include "sd_internal.h"
+
+#define WAVE 64
+
+// ---------------------------------------------------------------- block helpers
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = WAVE / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = WAVE / 2; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
+    return v;
+}
+
+// Sum over the block; every thread gets the result.  red: >= 32 floats of LDS.
+__device__ float block_sum(float v, float *red)
+{
+    int w = threadIdx.x / WAVE, l = threadIdx.x % WAVE, nw = (blockDim.x + WAVE - 1) / WAVE;
+    v = wave_sum(v);
+    __syncthreads();
+    if (l == 0) red[w] = v;
+    __syncthreads();
+    float t = 0.f;
+    for (int i = 0; i < nw; i++) t += red[i];
+    return t;
+}
+__device__ float block_max(float v, float *red)
+{
+    int w = threadIdx.x / WAVE, l = threadIdx.x % WAVE, nw = (blockDim.x + WAVE - 1) / WAVE;
+    v = wave_max(v);
+    __syncthreads();
+    if (l == 0) red[w] = v;
+    __syncthreads();
+    float t = red[0];
+    for (int i = 1; i < nw; i++) t = fmaxf(t, red[i]);
+    return t;
+}
+
+// Block-wide (value, index) argmax, ties to the lowest index.
+__device__ void block_argmax(float &v, int &idx, float *redv, int *redi)
+{
+    int w = threadIdx.x / WAVE, l = threadIdx.x % WAVE, nw = (blockDim.x + WAVE - 1) / WAVE;
+#pragma unroll
+    for (int o = WAVE / 2; o > 0; o >>= 1) {
+        float ov = __shfl_xor(v, o, WAVE);
+        int oi = __shfl_xor(idx, o, WAVE);
+        if (ov > v || (ov == v && oi < idx)) {
+            v = ov;
+            idx = oi;
+        }
+    }
+    __syncthreads();
+    if (l == 0) {
+        redv[w] = v;
+        redi[w] = idx;
+    }
+    __syncthreads();
+    v = redv[0];
+    idx = redi[0];
+    for (int i = 1; i < nw; i++)
+        if (redv[i] > v || (redv[i] == v && redi[i] < idx)) {
+            v = redv[i];
+            idx = redi[i];
+        }
+}
+
+// Exclusive prefix sum of one value per thread over the block.  scratch: >= 32 floats.
+__device__ float block_excl_scan(float v, float *scratch)
+{
+    int w = threadIdx.x / WAVE, l = threadIdx.x % WAVE, nw = (blockDim.x + WAVE - 1) / WAVE;
+    float inc = v;
+#pragma unroll
+    for (int o = 1; o < WAVE; o <<= 1) {
+        float t = __shfl_up(inc, o, WAVE);
+        if (l >= o) inc += t;
+    }
+    __syncthreads();
+    if (l == WAVE - 1) scratch[w] = inc;
+    __syncthreads();
+    float base = 0.f;
+    for (int i = 0; i < w && i < nw; i++) base += scratch[i];
+    return base + inc - v;
+}
+
+// ---------------------------------------------------------------- row plan
+// Builds the row list of one forward from the device-resident sequence state and
+// advances the model's cache length.  One thread per selected sequence.
+__global__ void plan_kernel(int mode, int R, int n_seq, const int32_t *seq_ids, CtxView cv, int slot, int upto_off,
+                            const int32_t *cand, int gamma, int cand_idx, int vocab, PlanView pv)
+{
+    for (int j = blockIdx.x * blockDim.x + threadIdx.x; j < n_seq; j += gridDim.x * blockDim.x) {
+        int b = seq_ids ? seq_ids[j] : j;
+        if (b < 0 || b >= cv.B) { // refuse out-of-range ids: mark every row unused
+            atomicOr(cv.status, 4);
+            pv.seq_b[j] = 0;
+            pv.seq_kv0[j] = 0;
+            pv.seq_nq[j] = 0;
+            for (int r = 0; r < R; r++) {
+                pv.row_tok[j * R + r] = 0;
+                pv.row_pos[j * R + r] = 0;
+                pv.row_b[j * R + r] = 0;
+                pv.row_valid[j * R + r] = 0;
+            }
+            pv.lm_row[j] = j * R;
+            continue;
+        }
+        int n = cv.ntok[b];
+        int *kvp = cv.kvlen + (size_t)slot * cv.B + b;
+        int kv = *kvp;
+        int cap = cv.cap[b];
+        int64_t off = cv.off[b];
+        int nq = 0, kv0 = kv;
+        if (mode == PLAN_CATCHUP) {
+            int avail = (n - upto_off) - kv;
+            nq = avail < 0 ? 0 : (avail > R ? R : avail);
+        } else if (mode == PLAN_CAND) {
+            nq = 1;
+        } else { // PLAN_VERIFY: rows (pending token, candidates) at positions n-1 ..
+            nq = R;
+            if (kv != n - 1) atomicOr(cv.status, 2);
+            kv0 = n - 1;
+        }
+        if (n < 1) { // an empty sequence has no pending token
+            atomicOr(cv.status, 2);
+            nq = 0;
+        }
+        if (kv0 < 0) kv0 = 0;
+        if (kv0 + nq > cap) { // never write beyond the sequence's cache rows
+            atomicOr(cv.status, 1);
+            nq = cap - kv0 > 0 ? cap - kv0 : 0;
+            if (mode == PLAN_VERIFY && nq < R) nq = 0;
+        }
+        for (int r = 0; r < R; r++) {
+            int row = j * R + r;
+            int valid = r < nq;
+            int tok = 0;
+            if (valid) {
+                if (mode == PLAN_CATCHUP) tok = cv.tokens[off + kv0 + r];
+                else if (mode == PLAN_CAND) tok = cand[j * gamma + cand_idx];
+                else tok = r == 0 ? cv.tokens[off + n - 1] : cand[j * gamma + (r - 1)];
+                if (tok < 0 || tok >= vocab) { // never index the embedding table out of range
+                    atomicOr(cv.status, 16);
+                    tok = 0;
+                }
+            }
+            pv.row_tok[row] = tok;
+            pv.row_pos[row] = kv0 + r;
+            pv.row_b[row] = b;
+            pv.row_valid[row] = valid;
+        }
+        pv.seq_b[j] = b;
+        pv.seq_kv0[j] = kv0;
+        pv.seq_nq[j] = nq;
+        if (mode == PLAN_VERIFY) {
+            for (int r = 0; r < R; r++) pv.lm_row[j * R + r] = j * R + r;
+        } else {
+            pv.lm_row[j] = j * R + (nq > 0 ? nq - 1 : 0);
+        }
+        *kvp = kv0 + nq;
+    }
+}
+
+hipError_t launch_plan(hipStream_t s, int mode, int R, int n_seq, const int32_t *seq_ids, CtxView cv, int slot,
+                       int upto_off, const int32_t *cand, int gamma, int cand_idx, int vocab, PlanView pv)
+{
+    int threads = 256, blocks = (n_seq + threads - 1) / threads;
+    hipLaunchKernelGGL(plan_kernel, dim3(blocks), dim3(threads), 0, s, mode, R, n_seq, seq_ids, cv, slot, upto_off,
+                       cand, gamma, cand_idx, vocab, pv);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- embedding gather
+template <typename T>
+__global__ void embed_kernel(const T *E, const int32_t *row_tok, int d, float *x)
+{
+    int r = blockIdx.x;
+    const T *src = E + (size_t)row_tok[r] * d;
+    for (int i = threadIdx.x; i < d; i += blockDim.x) x[(size_t)r * d + i] = to_float(src[i]);
+}
+
+hipError_t launch_embed(hipStream_t s, int dtype, const void *E, const int32_t *row_tok, int M, int d, float *x)
+{
+    if (dtype == SD_BF16)
+        hipLaunchKernelGGL(embed_kernel<bf16_t>, dim3(M), dim3(256), 0, s, (const bf16_t *)E, row_tok, d, x);
+    else
+        hipLaunchKernelGGL(embed_kernel<float>, dim3(M), dim3(256), 0, s, (const float *)E, row_tok, d, x);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- RMSNorm
+// out[j] = T( x[src] * rsqrt(mean(x[src]^2) + eps) * g ), src = row_map ? row_map[j] : j.
+template <typename T>
+__global__ void rmsnorm_kernel(const float *x, const float *g, const int32_t *row_map, int d, float eps, T *out)
+{
+    __shared__ float red[32];
+    int j = blockIdx.x;
+    int src = row_map ? row_map[j] : j;
+    const float *xr = x + (size_t)src * d;
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < d; i += blockDim.x) ss += xr[i] * xr[i];
+    ss = block_sum(ss, red);
+    float inv = 1.0f / sqrtf(ss / (float)d + eps);
+    for (int i = threadIdx.x; i < d; i += blockDim.x) out[(size_t)j * d + i] = from_float<T>(xr[i] * inv * g[i]);
+}
+
+hipError_t launch_rmsnorm(hipStream_t s, int dtype, const float *x, const float *g, const int32_t *row_map,
+                          int n_rows, int d, float eps, void *out)
+{
+    if (dtype == SD_BF16)
+        hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3(n_rows), dim3(256), 0, s, x, g, row_map, d, eps,
+                           (bf16_t *)out);
+    else
+        hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(n_rows), dim3(256), 0, s, x, g, row_map, d, eps,
+                           (float *)out);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- generic GEMM  C = A . W^T
+// One wave per output column n, 16 rows of A per block row; lanes stride over K.
+template <typename T, int MODE>
+__global__ __launch_bounds__(256) void gemm_generic_kernel(const T *A, WeightSeg w, int M, int N, int K, float *C,
+                                                           T *Cact)
+{
+    int n = blockIdx.x * 4 + threadIdx.x / WAVE;
+    int lane = threadIdx.x % WAVE;
+    int m0 = blockIdx.y * 16;
+    if (n >= N) return;
+    const T *W0, *W1 = nullptr;
+    if (MODE == GEMM_SWIGLU) {
+        W0 = (const T *)w.p[0] + (size_t)n * K;
+        W1 = (const T *)w.p[1] + (size_t)n * K;
+    } else {
+        int seg = n / w.n_per_seg;
+        W0 = (const T *)w.p[seg] + (size_t)(n - seg * w.n_per_seg) * K;
+    }
+    float acc[16], acc2[16];
+#pragma unroll
+    for (int m = 0; m < 16; m++) acc[m] = acc2[m] = 0.f;
+    int mcount = M - m0 < 16 ? M - m0 : 16;
+    for (int k = lane; k < K; k += WAVE) {
+        float wv = to_float(W0[k]);
+        float wv2 = MODE == GEMM_SWIGLU ? to_float(W1[k]) : 0.f;
+#pragma unroll
+        for (int m = 0; m < 16; m++) {
+            if (m < mcount) {
+                float a = to_float(A[(size_t)(m0 + m) * K + k]);
+                acc[m] += a * wv;
+                if (MODE == GEMM_SWIGLU) acc2[m] += a * wv2;
+            }
+        }
+    }
+#pragma unroll
+    for (int m = 0; m < 16; m++) {
+        acc[m] = wave_sum(acc[m]);
+        if (MODE == GEMM_SWIGLU) acc2[m] = wave_sum(acc2[m]);
+    }
+    if (lane == 0) {
+        for (int m = 0; m < mcount; m++) {
+            size_t o = (size_t)(m0 + m) * N + n;
+            if (MODE == GEMM_STORE) C[o] = acc[m];
+            else if (MODE == GEMM_RESID) C[o] += acc[m];
+            else {
+                float g = acc[m];
+                Cact[o] = from_float<T>(g / (1.0f + expf(-g)) * acc2[m]);
+            }
+        }
+    }
+}
+
+template <typename T>
+static void gemm_generic_dispatch(hipStream_t s, int mode, const void *A, WeightSeg w, int M, int N, int K, float *C,
+                                  void *Cact)
+{
+    dim3 grid((N + 3) / 4, (M + 15) / 16), block(256);
+    if (mode == GEMM_STORE)
+        hipLaunchKernelGGL((gemm_generic_kernel<T, GEMM_STORE>), grid, block, 0, s, (const T *)A, w, M, N, K, C,
+                           (T *)Cact);
+    else if (mode == GEMM_RESID)
+        hipLaunchKernelGGL((gemm_generic_kernel<T, GEMM_RESID>), grid, block, 0, s, (const T *)A, w, M, N, K, C,
+                           (T *)Cact);
+    else
+        hipLaunchKernelGGL((gemm_generic_kernel<T, GEMM_SWIGLU>), grid, block, 0, s, (const T *)A, w, M, N, K, C,
+                           (T *)Cact);
+}
+
+hipError_t launch_gemm_generic(hipStream_t s, int dtype, int mode, const void *A, WeightSeg w, int M, int N, int K,
+                               float *C, void *Cact)
+{
+    if (dtype == SD_BF16) gemm_generic_dispatch<bf16_t>(s, mode, A, w, M, N, K, C, Cact);
+    else gemm_generic_dispatch<float>(s, mode, A, w, M, N, K, C, Cact);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- RoPE + KV append
+// qkv: fp32 [M][3*HD] (q | k | v).  Rotates q and k of every valid row at its
+// position (rotate-half pairing), writes q to qbuf and k, v into the cache in
+// place: K[head][off+pos][hd], Vt[head][hd][off+pos].
+template <typename T>
+__global__ void rope_append_kernel(const float *qkv, PlanView pv, CtxView cv, int H, int hd, const float2 *rope,
+                                   int max_pos, T *qbuf, T *Kl, T *Vtl, int64_t total_cap)
+{
+    int r = blockIdx.x;
+    int HD = H * hd, half = hd / 2;
+    int valid = pv.row_valid[r];
+    int pos = pv.row_pos[r];
+    if (pos >= max_pos) {
+        if (threadIdx.x == 0 && valid) atomicOr(cv.status, 8);
+        valid = 0;
+    }
+    const float *row = qkv + (size_t)r * 3 * HD;
+    int64_t off = cv.off[pv.row_b[r]];
+    for (int i = threadIdx.x; i < H * half; i += blockDim.x) {
+        int h = i / half, e = i % half;
+        if (!valid) {
+            qbuf[(size_t)r * HD + h * hd + e] = from_float<T>(0.f);
+            qbuf[(size_t)r * HD + h * hd + e + half] = from_float<T>(0.f);
+            continue;
+        }
+        float2 cs = rope[(size_t)pos * half + e];
+        float q0 = row[h * hd + e], q1 = row[h * hd + e + half];
+        float k0 = row[HD + h * hd + e], k1 = row[HD + h * hd + e + half];
+        float v0 = row[2 * HD + h * hd + e], v1 = row[2 * HD + h * hd + e + half];
+        qbuf[(size_t)r * HD + h * hd + e] = from_float<T>(q0 * cs.x - q1 * cs.y);
+        qbuf[(size_t)r * HD + h * hd + e + half] = from_float<T>(q1 * cs.x + q0 * cs.y);
+        T *kd = Kl + ((size_t)h * total_cap + off + pos) * hd;
+        kd[e] = from_float<T>(k0 * cs.x - k1 * cs.y);
+        kd[e + half] = from_float<T>(k1 * cs.x + k0 * cs.y);
+        T *vd = Vtl + (size_t)h * hd * total_cap + off + pos;
+        vd[(size_t)e * total_cap] = from_float<T>(v0);
+        vd[(size_t)(e + half) * total_cap] = from_float<T>(v1);
+    }
+}
+
+hipError_t launch_rope_append(hipStream_t s, int dtype, const float *qkv, PlanView pv, CtxView cv, int M, int H,
+                              int hd, const float2 *rope, int max_pos, void *qbuf, void *Kl, void *Vtl,
+                              int64_t total_cap)
+{
+    if (dtype == SD_BF16)
+        hipLaunchKernelGGL(rope_append_kernel<bf16_t>, dim3(M), dim3(256), 0, s, qkv, pv, cv, H, hd, rope, max_pos,
+                           (bf16_t *)qbuf, (bf16_t *)Kl, (bf16_t *)Vtl, total_cap);
+    else
+        hipLaunchKernelGGL(rope_append_kernel<float>, dim3(M), dim3(256), 0, s, qkv, pv, cv, H, hd, rope, max_pos,
+                           (float *)qbuf, (float *)Kl, (float *)Vtl, total_cap);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- generic attention
+// One block per (row slot i, head, selected sequence): query row i sees cache rows
+// [0, kv0 + i].  Scores live in dynamic LDS (len_upper floats).
+template <typename T>
+__global__ __launch_bounds__(256) void attn_generic_kernel(const T *qbuf, const T *Kl, const T *Vtl, PlanView pv,
+                                                           CtxView cv, int R, int H, int hd, int64_t total_cap,
+                                                           int lds_len, T *obuf)
+{
+    extern __shared__ float sc[]; // [lds_len] scores, then [256] partials, [hd] q, [32] red
+    float *part = sc + lds_len;
+    float *qs = part + 256;
+    float *red = qs + hd;
+    int i = blockIdx.x, h = blockIdx.y, j = blockIdx.z;
+    int r = j * R + i;
+    int HD = H * hd;
+    if (i >= pv.seq_nq[j]) {
+        for (int d = threadIdx.x; d < hd; d += blockDim.x) obuf[(size_t)r * HD + h * hd + d] = from_float<T>(0.f);
+        return;
+    }
+    int Lk = pv.seq_kv0[j] + i + 1;
+    if (Lk > lds_len) Lk = lds_len; // host sizes lds_len from an upper bound; never exceeded
+    int64_t off = cv.off[pv.seq_b[j]];
+    const T *K = Kl + ((size_t)h * total_cap + off) * hd;
+    const T *Vt = Vtl + (size_t)h * hd * total_cap + off;
+    for (int d = threadIdx.x; d < hd; d += blockDim.x) qs[d] = to_float(qbuf[(size_t)r * HD + h * hd + d]);
+    __syncthreads();
+    float scale = 1.0f / sqrtf((float)hd);
+    float mx = -3.0e38f;
+    for (int t = threadIdx.x; t < Lk; t += blockDim.x) {
+        const T *kt = K + (size_t)t * hd;
+        float dot = 0.f;
+        for (int d = 0; d < hd; d++) dot += qs[d] * to_float(kt[d]);
+        dot *= scale;
+        sc[t] = dot;
+        mx = fmaxf(mx, dot);
+    }
+    mx = block_max(mx, red);
+    float z = 0.f;
+    for (int t = threadIdx.x; t < Lk; t += blockDim.x) {
+        float e = expf(sc[t] - mx);
+        sc[t] = e;
+        z += e;
+    }
+    z = block_sum(z, red);
+    __syncthreads();
+    int G = blockDim.x / hd; // hd is 64 or 128, blockDim 256
+    int d = threadIdx.x % hd, g = threadIdx.x / hd;
+    float acc = 0.f;
+    const T *vrow = Vt + (size_t)d * total_cap;
+    for (int t = g; t < Lk; t += G) acc += sc[t] * to_float(vrow[t]);
+    part[threadIdx.x] = acc;
+    __syncthreads();
+    if (g == 0) {
+        for (int gg = 1; gg < G; gg++) acc += part[gg * hd + d];
+        obuf[(size_t)r * HD + h * hd + d] = from_float<T>(acc / z);
+    }
+}
+
+hipError_t launch_attn_generic(hipStream_t s, int dtype, const void *qbuf, const void *Kl, const void *Vtl,
+                               PlanView pv, CtxView cv, int R, int n_seq, int H, int hd, int64_t total_cap,
+                               int len_upper, void *obuf)
+{
+    size_t lds = ((size_t)len_upper + 256 + hd + 32) * sizeof(float);
+    if (lds > 64 * 1024) return hipErrorNotSupported;
+    dim3 grid(R, H, n_seq), block(256);
+    if (dtype == SD_BF16)
+        hipLaunchKernelGGL(attn_generic_kernel<bf16_t>, grid, block, lds, s, (const bf16_t *)qbuf,
+                           (const bf16_t *)Kl, (const bf16_t *)Vtl, pv, cv, R, H, hd, total_cap, len_upper,
+                           (bf16_t *)obuf);
+    else
+        hipLaunchKernelGGL(attn_generic_kernel<float>, grid, block, lds, s, (const float *)qbuf, (const float *)Kl,
+                           (const float *)Vtl, pv, cv, R, H, hd, total_cap, len_upper, (float *)obuf);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- inverse-CDF pick
+// Chooses the smallest index k with sum_{x<=k} w(x) > u * sum_x w(x) for weights
+// produced on the fly by wfun(v) -> float4 of elements 4v..4v+3 (zero beyond V).
+// All threads of a 1024-thread block must call it; the result is returned to all.
+// If rounding leaves no such k, the last index with positive weight is returned.
+struct PickScratch {
+    float seg[64];
+    float red[32];
+    float base;
+    float target;
+    int seg_idx;
+    int pick;
+    int last_pos;
+};
+
+template <typename F>
+__device__ int block_pick_cdf(F wfun, int V, float u, PickScratch *ps, float *total_out)
+{
+    const int T = blockDim.x;
+    int nvec = (V + 3) / 4;
+    int nseg = (nvec + T - 1) / T;
+    if (threadIdx.x == 0) {
+        ps->pick = 0x7fffffff;
+        ps->last_pos = 0;
+    }
+    __syncthreads();
+    int lastp = -1;
+    for (int it = 0; it < nseg; it++) {
+        int v = it * T + threadIdx.x;
+        float4 f = v < nvec ? wfun(v) : make_float4(0.f, 0.f, 0.f, 0.f);
+        if (f.x > 0.f) lastp = 4 * v;
+        if (f.y > 0.f) lastp = 4 * v + 1;
+        if (f.z > 0.f) lastp = 4 * v + 2;
+        if (f.w > 0.f) lastp = 4 * v + 3;
+        float loc = ((f.x + f.y) + f.z) + f.w;
+        float ssum = block_sum(loc, ps->red);
+        if (threadIdx.x == 0) ps->seg[it] = ssum;
+    }
+    if (lastp >= 0) atomicMax(&ps->last_pos, lastp);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float Z = 0.f;
+        for (int it = 0; it < nseg; it++) Z += ps->seg[it];
+        float target = u * Z;
+        float cum = 0.f;
+        int found = -1;
+        for (int it = 0; it < nseg; it++) {
+            if (cum + ps->seg[it] > target) {
+                found = it;
+                break;
+            }
+            cum += ps->seg[it];
+        }
+        ps->seg_idx = found;
+        ps->base = cum;
+        ps->target = target;
+        if (total_out) *total_out = Z;
+    }
+    __syncthreads();
+    int it = ps->seg_idx;
+    if (it >= 0) {
+        int v = it * T + threadIdx.x;
+        float4 f = v < nvec ? wfun(v) : make_float4(0.f, 0.f, 0.f, 0.f);
+        float loc = ((f.x + f.y) + f.z) + f.w;
+        float pre = block_excl_scan(loc, ps->red);
+        float cum = ps->base + pre, target = ps->target;
+        if (cum <= target) {
+            int k = -1;
+            cum += f.x;
+            if (cum > target) k = 4 * v;
+            else {
+                cum += f.y;
+                if (cum > target) k = 4 * v + 1;
+                else {
+                    cum += f.z;
+                    if (cum > target) k = 4 * v + 2;
+                    else {
+                        cum += f.w;
+                        if (cum > target) k = 4 * v + 3;
+                    }
+                }
+            }
+            if (k >= 0 && k < V) atomicMin(&ps->pick, k);
+        }
+    }
+    __syncthreads();
+    int pick = ps->pick;
+    if (pick == 0x7fffffff) pick = ps->last_pos;
+    __syncthreads();
+    return pick;
+}
+
+__device__ __forceinline__ float4 load4_guard(const float *row, int v, int V, float fill)
+{
+    if (4 * v + 3 < V) return *(const float4 *)(row + 4 * v);
+    float4 f = make_float4(fill, fill, fill, fill);
+    if (4 * v < V) f.x = row[4 * v];
+    if (4 * v + 1 < V) f.y = row[4 * v + 1];
+    if (4 * v + 2 < V) f.z = row[4 * v + 2];
+    return f;
+}
+
+// max and lowest-index argmax of one fp32 row (block-wide)
+__device__ void row_max_argmax(const float *row, int V, float *redv, int *redi, float &mx, int &am)
+{
+    float bv = -3.0e38f;
+    int bi = 0x7fffffff;
+    int nvec = (V + 3) / 4;
+    for (int v = threadIdx.x; v < nvec; v += blockDim.x) {
+        float4 f = load4_guard(row, v, V, -3.0e38f);
+        if (f.x > bv) { bv = f.x; bi = 4 * v; }
+        if (f.y > bv) { bv = f.y; bi = 4 * v + 1; }
+        if (f.z > bv) { bv = f.z; bi = 4 * v + 2; }
+        if (f.w > bv) { bv = f.w; bi = 4 * v + 3; }
+    }
+    block_argmax(bv, bi, redv, redi);
+    mx = bv;
+    am = bi;
+}
+
+// sum_x exp((row[x] - mx) * invT) (block-wide)
+__device__ float row_sumexp(const float *row, int V, float mx, float invT, float *red)
+{
+    float z = 0.f;
+    int nvec = (V + 3) / 4;
+    for (int v = threadIdx.x; v < nvec; v += blockDim.x) {
+        float4 f = load4_guard(row, v, V, -3.0e38f);
+        z += expf((f.x - mx) * invT);
+        if (4 * v + 1 < V) z += expf((f.y - mx) * invT);
+        if (4 * v + 2 < V) z += expf((f.z - mx) * invT);
+        if (4 * v + 3 < V) z += expf((f.w - mx) * invT);
+    }
+    return block_sum(z, red);
+}
+
+// ---------------------------------------------------------------- draft: softmax + sample
+// One block per sequence.  T > 0: q = softmax(logits / T) is written in full and
+// the candidate drawn by inverse CDF; T == 0: candidate = argmax.
+__global__ __launch_bounds__(1024) void draft_sample_kernel(const float *logits, int V, float T, const float *u,
+                                                            int gamma, int idx, int32_t *cand, float *q)
+{
+    __shared__ PickScratch ps;
+    __shared__ float redv[32];
+    __shared__ int redi[32];
+    int j = blockIdx.x;
+    const float *row = logits + (size_t)j * V;
+    float mx;
+    int am;
+    row_max_argmax(row, V, redv, redi, mx, am);
+    if (T == 0.f) {
+        if (threadIdx.x == 0) cand[j * gamma + idx] = am;
+        return;
+    }
+    float invT = 1.0f / T;
+    float z = row_sumexp(row, V, mx, invT, redv);
+    float invZ = 1.0f / z;
+    float *qrow = q + ((size_t)j * gamma + idx) * V;
+    int nvec = (V + 3) / 4;
+    for (int v = threadIdx.x; v < nvec; v += blockDim.x) {
+        float4 f = load4_guard(row, v, V, -3.0e38f);
+        float4 p;
+        p.x = expf((f.x - mx) * invT) * invZ;
+        p.y = expf((f.y - mx) * invT) * invZ;
+        p.z = expf((f.z - mx) * invT) * invZ;
+        p.w = expf((f.w - mx) * invT) * invZ;
+        if (4 * v + 3 < V) *(float4 *)(qrow + 4 * v) = p;
+        else {
+            if (4 * v < V) qrow[4 * v] = p.x;
+            if (4 * v + 1 < V) qrow[4 * v + 1] = p.y;
+            if (4 * v + 2 < V) qrow[4 * v + 2] = p.z;
+        }
+    }
+    __syncthreads(); // q row of this block is complete and visible to the block
+    auto wfun = [&](int v) {
+        float4 f = load4_guard(row, v, V, -3.0e38f);
+        float4 p;
+        p.x = expf((f.x - mx) * invT) * invZ;
+        p.y = 4 * v + 1 < V ? expf((f.y - mx) * invT) * invZ : 0.f;
+        p.z = 4 * v + 2 < V ? expf((f.z - mx) * invT) * invZ : 0.f;
+        p.w = 4 * v + 3 < V ? expf((f.w - mx) * invT) * invZ : 0.f;
+        return p;
+    };
+    int pick = block_pick_cdf(wfun, V, u[j * gamma + idx], &ps, nullptr);
+    if (threadIdx.x == 0) cand[j * gamma + idx] = pick;
+}
+
+hipError_t launch_draft_sample(hipStream_t s, const float *logits, int n_seq, int V, float T, const float *u,
+                               int gamma, int idx, int32_t *cand, float *q)
+{
+    hipLaunchKernelGGL(draft_sample_kernel, dim3(n_seq), dim3(1024), 0, s, logits, V, T, u, gamma, idx, cand, q);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- commit (KV rollback)
+__device__ void commit_one(CtxView cv, int b, int gamma, const int32_t *cand_j, int n_acc, int next_tok)
+{
+    int n = cv.ntok[b];
+    int64_t off = cv.off[b];
+    int cap = cv.cap[b];
+    if (n_acc < 0) n_acc = 0;
+    if (n_acc > gamma) n_acc = gamma;
+    if (n + n_acc + 1 > cap) {
+        atomicOr(cv.status, 1);
+        return;
+    }
+    for (int i = 0; i < n_acc; i++) cv.tokens[off + n + i] = cand_j[i];
+    cv.tokens[off + n + n_acc] = next_tok;
+    int nn = n + n_acc + 1;
+    cv.ntok[b] = nn;
+    for (int sl = 0; sl < cv.n_slots; sl++) {
+        int *kv = cv.kvlen + (size_t)sl * cv.B + b;
+        if (*kv > nn - 1) *kv = nn - 1;
+    }
+}
+
+__global__ void commit_kernel(CtxView cv, const int32_t *seq_ids, int n_seq, int gamma, const int32_t *cand,
+                              const int32_t *n_acc, const int32_t *next_tok)
+{
+    int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= n_seq) return;
+    int b = seq_ids ? seq_ids[j] : j;
+    if (b < 0 || b >= cv.B) {
+        atomicOr(cv.status, 4);
+        return;
+    }
+    commit_one(cv, b, gamma, cand + (size_t)j * gamma, n_acc[j], next_tok[j]);
+}
+
+hipError_t launch_commit(hipStream_t s, CtxView cv, const int32_t *seq_ids, int n_seq, int gamma,
+                         const int32_t *cand, const int32_t *n_acc, const int32_t *next_tok)
+{
+    hipLaunchKernelGGL(commit_kernel, dim3((n_seq + 255) / 256), dim3(256), 0, s, cv, seq_ids, n_seq, gamma, cand,
+                       n_acc, next_tok);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- verify tail
+// Fused vocabulary softmax + accept scan + residual + resample, one block per
+// sequence.  Row statistics (max, sum of exponentials, argmax) of the gamma+1
+// logit rows are block reductions; the accept scan runs on thread 0; only the
+// row that decides the next token is traversed again.
+__global__ __launch_bounds__(1024) void verify_tail_kernel(const float *logits, int gamma, int V, float T,
+                                                           const int32_t *cand, const float *q, const float *u,
+                                                           const int32_t *seq_ids, int32_t *n_acc_out,
+                                                           int32_t *next_out, int commit, CtxView cv)
+{
+    __shared__ PickScratch ps;
+    __shared__ float redv[32];
+    __shared__ int redi[32];
+    __shared__ float s_mx[SD_MAX_GAMMA + 1], s_z[SD_MAX_GAMMA + 1];
+    __shared__ int s_am[SD_MAX_GAMMA + 1];
+    __shared__ int s_nacc;
+    __shared__ float s_zr;
+    int j = blockIdx.x;
+    const float *rows = logits + (size_t)j * (gamma + 1) * V;
+    const int32_t *cj = cand + (size_t)j * gamma;
+    float invT = T > 0.f ? 1.0f / T : 0.f;
+    for (int i = 0; i <= gamma; i++) {
+        float mx;
+        int am;
+        row_max_argmax(rows + (size_t)i * V, V, redv, redi, mx, am);
+        float z = 1.f;
+        if (T > 0.f) z = row_sumexp(rows + (size_t)i * V, V, mx, invT, redv);
+        if (threadIdx.x == 0) {
+            s_mx[i] = mx;
+            s_z[i] = z;
+            s_am[i] = am;
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int n_acc = 0;
+        for (int i = 0; i < gamma; i++) {
+            int c = cj[i];
+            bool ok;
+            if (T == 0.f) ok = c == s_am[i];
+            else if (c < 0 || c >= V) ok = false;
+            else {
+                float p = expf((rows[(size_t)i * V + c] - s_mx[i]) * invT) / s_z[i];
+                float qc = q[((size_t)j * gamma + i) * V + c];
+                qc = fmaxf(qc, 1.17549435e-38f);
+                ok = u[j * (gamma + 1) + i] < p / qc;
+            }
+            if (!ok) break;
+            n_acc++;
+        }
+        s_nacc = n_acc;
+    }
+    __syncthreads();
+    int n_acc = s_nacc;
+    int next;
+    if (T == 0.f) {
+        next = s_am[n_acc];
+    } else {
+        const float *row = rows + (size_t)n_acc * V;
+        float mx = s_mx[n_acc], invZ = 1.0f / s_z[n_acc];
+        float uu = u[j * (gamma + 1) + gamma];
+        auto pfun = [&](int v) {
+            float4 f = load4_guard(row, v, V, -3.0e38f);
+            float4 p;
+            p.x = expf((f.x - mx) * invT) * invZ;
+            p.y = 4 * v + 1 < V ? expf((f.y - mx) * invT) * invZ : 0.f;
+            p.z = 4 * v + 2 < V ? expf((f.z - mx) * invT) * invZ : 0.f;
+            p.w = 4 * v + 3 < V ? expf((f.w - mx) * invT) * invZ : 0.f;
+            return p;
+        };
+        bool use_p = n_acc >= gamma;
+        if (!use_p) {
+            const float *qrow = q + ((size_t)j * gamma + n_acc) * V;
+            auto rfun = [&](int v) {
+                float4 p = pfun(v);
+                float4 qq = load4_guard(qrow, v, V, 0.f);
+                return make_float4(fmaxf(p.x - qq.x, 0.f), fmaxf(p.y - qq.y, 0.f), fmaxf(p.z - qq.z, 0.f),
+                                   fmaxf(p.w - qq.w, 0.f));
+            };
+            float zr = 0.f;
+            next = block_pick_cdf(rfun, V, uu, &ps, &zr);
+            if (threadIdx.x == 0) s_zr = zr;
+            __syncthreads();
+            if (!(s_zr > 0.f)) use_p = true; // numerically empty residual: draw from p
+            __syncthreads();
+        }
+        if (use_p) next = block_pick_cdf(pfun, V, uu, &ps, nullptr);
+    }
+    if (threadIdx.x == 0) {
+        n_acc_out[j] = n_acc;
+        next_out[j] = next;
+        if (commit) {
+            int b = seq_ids ? seq_ids[j] : j;
+            if (b >= 0 && b < cv.B) commit_one(cv, b, gamma, cj, n_acc, next);
+            else atomicOr(cv.status, 4);
+        }
+    }
+}
+
+hipError_t launch_verify_tail(hipStream_t s, const float *logits, int n_seq, int gamma, int V, float T,
+                              const int32_t *cand, const float *q, const float *u, const int32_t *seq_ids,
+                              int32_t *n_acc, int32_t *next_tok, int commit, CtxView cv)
+{
+    hipLaunchKernelGGL(verify_tail_kernel, dim3(n_seq), dim3(1024), 0, s, logits, gamma, V, T, cand, q, u, seq_ids,
+                       n_acc, next_tok, commit, cv);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- routing
+__global__ void route_kernel(const float *W, const float *b, int n_drafts, int emb, const float *e, int n,
+                             int32_t *id)
+{
+    int i = blockIdx.x;
+    int lane = threadIdx.x;
+    float best = -3.0e38f;
+    int bi = 0;
+    for (int k = 0; k < n_drafts; k++) {
+        float acc = 0.f;
+        for (int t = lane; t < emb; t += WAVE) acc += W[(size_t)k * emb + t] * e[(size_t)i * emb + t];
+        acc = wave_sum(acc) + (b ? b[k] : 0.f);
+        if (acc > best) {
+            best = acc;
+            bi = k;
+        }
+    }
+    if (lane == 0) id[i] = bi;
+}
+
+hipError_t launch_route(hipStream_t s, const float *W, const float *b, int n_drafts, int emb, const float *e, int n,
+                        int32_t *id)
+{
+    hipLaunchKernelGGL(route_kernel, dim3(n), dim3(WAVE), 0, s, W, b, n_drafts, emb, e, n, id);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- synthetic cache load
+template <typename T>
+__global__ void set_kv_kernel(const T *k_rows, const T *v_rows, int len, int H, int hd, int64_t seq_off,
+                              int64_t total_cap, T *Kl, T *Vtl)
+{
+    size_t n = (size_t)len * H * hd;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+        int d = i % hd;
+        int h = (i / hd) % H;
+        int t = i / ((size_t)hd * H);
+        Kl[((size_t)h * total_cap + seq_off + t) * hd + d] = k_rows[i];
+        Vtl[((size_t)h * hd + d) * total_cap + seq_off + t] = v_rows[i];
+    }
+}
+
+hipError_t launch_set_kv(hipStream_t s, int dtype, const void *k_rows, const void *v_rows, int len, int H, int hd,
+                         int64_t seq_off, int64_t total_cap, void *Kl, void *Vtl)
+{
+    size_t n = (size_t)len * H * hd;
+    int blocks = (int)((n + 255) / 256);
+    if (blocks > 65535) blocks = 65535;
+    if (blocks < 1) blocks = 1;
+    if (dtype == SD_BF16)
+        hipLaunchKernelGGL(set_kv_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, (const bf16_t *)k_rows,
+                           (const bf16_t *)v_rows, len, H, hd, seq_off, total_cap, (bf16_t *)Kl, (bf16_t *)Vtl);
+    else
+        hipLaunchKernelGGL(set_kv_kernel<float>, dim3(blocks), dim3(256), 0, s, (const float *)k_rows,
+                           (const float *)v_rows, len, H, hd, seq_off, total_cap, (float *)Kl, (float *)Vtl);
+    return hipGetLastError();
+}

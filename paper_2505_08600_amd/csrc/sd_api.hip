@@ -1,0 +1,500 @@
+// C ABI of libsd and the host-side launch schedule of one decoder forward.
+// See include/sd.h for the contract of every entry point.
+#include <math.h>
+#include <string.h>
+
+#include <algorithm>
+
+#include "sd_internal.h"
+
+static thread_local std::string g_err;
+int g_force_generic = 0;
+
+void sd_set_error(const std::string &s) { g_err = s; }
+int sd_fail(int code, const std::string &s)
+{
+    g_err = s;
+    return code;
+}
+
+extern "C" const char *sd_last_error(void) { return g_err.c_str(); }
+
+extern "C" int sd_set_option(const char *name, int32_t value)
+{
+    if (!name) return sd_fail(SD_EINVAL, "sd_set_option: null name");
+    if (!strcmp(name, "force_generic")) {
+        g_force_generic = value;
+        return SD_OK;
+    }
+    return sd_fail(SD_EINVAL, std::string("sd_set_option: unknown option ") + name);
+}
+
+// ---------------------------------------------------------------- model
+static size_t attn_part_floats(const sd_model_config &c) { return (size_t)3072 * 16 * (c.head_dim + 2); }
+
+extern "C" int sd_load_model(const sd_model_config *cfg, const sd_weights *w, sd_model **out)
+{
+    if (!cfg || !w || !out) return sd_fail(SD_EINVAL, "sd_load_model: null argument");
+    const sd_model_config &c = *cfg;
+    if (c.n_layers < 1 || c.d_model < 1 || c.n_heads < 1 || c.d_ffn < 1 || c.vocab < 1)
+        return sd_fail(SD_EINVAL, "sd_load_model: non-positive dimension");
+    if (c.n_heads * c.head_dim != c.d_model) return sd_fail(SD_EINVAL, "sd_load_model: n_heads*head_dim != d_model");
+    if (c.head_dim != 16 && c.head_dim != 32 && c.head_dim != 64 && c.head_dim != 128)
+        return sd_fail(SD_EINVAL, "sd_load_model: head_dim must be 16, 32, 64 or 128");
+    if (c.vocab % 4 != 0) return sd_fail(SD_EINVAL, "sd_load_model: vocab must be a multiple of 4");
+    if (c.dtype != SD_FP32 && c.dtype != SD_BF16) return sd_fail(SD_EINVAL, "sd_load_model: bad dtype");
+    if (c.max_rows < 2 || c.max_pos < 2) return sd_fail(SD_EINVAL, "sd_load_model: max_rows/max_pos too small");
+    if (!(c.rope_base > 1.f) || !(c.rms_eps >= 0.f)) return sd_fail(SD_EINVAL, "sd_load_model: bad rope_base/rms_eps");
+    if (!w->embed || !w->lm_head || !w->final_norm || !w->wq || !w->wk || !w->wv || !w->wo || !w->wgate ||
+        !w->wup || !w->wdown || !w->norm_attn || !w->norm_ffn)
+        return sd_fail(SD_EINVAL, "sd_load_model: null weight pointer");
+    for (int l = 0; l < c.n_layers; l++)
+        if (!w->wq[l] || !w->wk[l] || !w->wv[l] || !w->wo[l] || !w->wgate[l] || !w->wup[l] || !w->wdown[l] ||
+            !w->norm_attn[l] || !w->norm_ffn[l])
+            return sd_fail(SD_EINVAL, "sd_load_model: null per-layer weight pointer");
+    sd_model *m = new sd_model();
+    m->cfg = c;
+    m->embed = w->embed;
+    m->lm_head = w->lm_head;
+    m->final_norm = w->final_norm;
+    for (int l = 0; l < c.n_layers; l++) {
+        m->wq.push_back(w->wq[l]);
+        m->wk.push_back(w->wk[l]);
+        m->wv.push_back(w->wv[l]);
+        m->wo.push_back(w->wo[l]);
+        m->wgate.push_back(w->wgate[l]);
+        m->wup.push_back(w->wup[l]);
+        m->wdown.push_back(w->wdown[l]);
+        m->norm_attn.push_back(w->norm_attn[l]);
+        m->norm_ffn.push_back(w->norm_ffn[l]);
+    }
+    m->esz = c.dtype == SD_BF16 ? 2 : 4;
+    m->last_lm_rows = 0;
+    size_t M = c.max_rows, d = c.d_model;
+    m->part_floats = attn_part_floats(c);
+    hipError_t e = hipSuccess;
+    auto alloc = [&](void **p, size_t bytes) {
+        if (e == hipSuccess) e = hipMalloc(p, bytes);
+    };
+    m->x = nullptr;
+    alloc((void **)&m->x, M * d * 4);
+    alloc(&m->abuf, M * d * m->esz);
+    alloc((void **)&m->qkv, M * 3 * d * 4);
+    alloc(&m->qbuf, M * d * m->esz);
+    alloc(&m->obuf, M * d * m->esz);
+    alloc(&m->act, M * (size_t)c.d_ffn * m->esz);
+    alloc((void **)&m->logits, M * (size_t)c.vocab * 4);
+    alloc((void **)&m->part, m->part_floats * 4);
+    alloc((void **)&m->rope, (size_t)c.max_pos * (c.head_dim / 2) * sizeof(float2));
+    alloc((void **)&m->plan_mem, (5 * M + 3 * M) * sizeof(int32_t));
+    if (e != hipSuccess) {
+        delete m;
+        return sd_fail(SD_EHIP, std::string("sd_load_model: hipMalloc: ") + hipGetErrorString(e));
+    }
+    int32_t *pm = m->plan_mem;
+    m->plan.row_tok = pm;
+    m->plan.row_pos = pm + M;
+    m->plan.row_b = pm + 2 * M;
+    m->plan.row_valid = pm + 3 * M;
+    m->plan.lm_row = pm + 4 * M;
+    m->plan.seq_b = pm + 5 * M;
+    m->plan.seq_kv0 = pm + 6 * M;
+    m->plan.seq_nq = pm + 7 * M;
+    // rotary table in double on the host: angle = pos * base^(-2i/hd)
+    int half = c.head_dim / 2;
+    std::vector<float2> tab((size_t)c.max_pos * half);
+    for (int i = 0; i < half; i++) {
+        double theta = pow((double)c.rope_base, -2.0 * i / c.head_dim);
+        for (int p = 0; p < c.max_pos; p++) {
+            double a = p * theta;
+            tab[(size_t)p * half + i] = make_float2((float)cos(a), (float)sin(a));
+        }
+    }
+    SD_HIP(hipMemcpy(m->rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice));
+    SD_HIP(hipDeviceSynchronize());
+    *out = m;
+    return SD_OK;
+}
+
+extern "C" int sd_free_model(sd_model *m)
+{
+    if (!m) return SD_OK;
+    (void)hipDeviceSynchronize();
+    (void)hipFree(m->x);
+    (void)hipFree(m->abuf);
+    (void)hipFree(m->qkv);
+    (void)hipFree(m->qbuf);
+    (void)hipFree(m->obuf);
+    (void)hipFree(m->act);
+    (void)hipFree(m->logits);
+    (void)hipFree(m->part);
+    (void)hipFree(m->rope);
+    (void)hipFree(m->plan_mem);
+    delete m;
+    return SD_OK;
+}
+
+// ---------------------------------------------------------------- context
+extern "C" int sd_ctx_create(int32_t batch, const int32_t *caps, sd_ctx **out)
+{
+    if (batch < 1 || !caps || !out) return sd_fail(SD_EINVAL, "sd_ctx_create: bad argument");
+    sd_ctx *c = new sd_ctx();
+    c->B = batch;
+    c->n_slots = 0;
+    c->len_upper = 0;
+    int64_t tot = 0;
+    for (int b = 0; b < batch; b++) {
+        if (caps[b] < 1) {
+            delete c;
+            return sd_fail(SD_EINVAL, "sd_ctx_create: capacity < 1");
+        }
+        int32_t cp = (caps[b] + 63) / 64 * 64; // 64-token granules keep cache rows 128-byte aligned
+        c->cap.push_back(cp);
+        c->off.push_back(tot);
+        tot += cp;
+    }
+    c->total_cap = tot;
+    for (int s = 0; s < SD_MAX_SLOTS; s++) c->models[s] = nullptr, c->kcache[s] = c->vcache[s] = nullptr;
+    hipError_t e = hipMalloc((void **)&c->d_off, sizeof(int64_t) * batch);
+    if (e == hipSuccess) e = hipMalloc((void **)&c->d_cap, sizeof(int32_t) * batch);
+    if (e == hipSuccess) e = hipMalloc((void **)&c->d_tokens, sizeof(int32_t) * tot);
+    if (e == hipSuccess) e = hipMalloc((void **)&c->d_ntok, sizeof(int32_t) * batch);
+    if (e == hipSuccess) e = hipMalloc((void **)&c->d_kvlen, sizeof(int32_t) * batch * SD_MAX_SLOTS);
+    if (e == hipSuccess) e = hipMalloc((void **)&c->d_status, sizeof(int32_t));
+    if (e != hipSuccess) {
+        delete c;
+        return sd_fail(SD_EHIP, std::string("sd_ctx_create: hipMalloc: ") + hipGetErrorString(e));
+    }
+    SD_HIP(hipMemcpy(c->d_off, c->off.data(), sizeof(int64_t) * batch, hipMemcpyHostToDevice));
+    SD_HIP(hipMemcpy(c->d_cap, c->cap.data(), sizeof(int32_t) * batch, hipMemcpyHostToDevice));
+    SD_HIP(hipMemset(c->d_tokens, 0, sizeof(int32_t) * tot));
+    SD_HIP(hipMemset(c->d_ntok, 0, sizeof(int32_t) * batch));
+    SD_HIP(hipMemset(c->d_kvlen, 0, sizeof(int32_t) * batch * SD_MAX_SLOTS));
+    SD_HIP(hipMemset(c->d_status, 0, sizeof(int32_t)));
+    SD_HIP(hipDeviceSynchronize());
+    *out = c;
+    return SD_OK;
+}
+
+extern "C" int sd_ctx_free(sd_ctx *c)
+{
+    if (!c) return SD_OK;
+    (void)hipDeviceSynchronize();
+    for (int s = 0; s < c->n_slots; s++) {
+        (void)hipFree(c->kcache[s]);
+        (void)hipFree(c->vcache[s]);
+    }
+    (void)hipFree(c->d_off);
+    (void)hipFree(c->d_cap);
+    (void)hipFree(c->d_tokens);
+    (void)hipFree(c->d_ntok);
+    (void)hipFree(c->d_kvlen);
+    (void)hipFree(c->d_status);
+    delete c;
+    return SD_OK;
+}
+
+static int find_slot(const sd_ctx *c, const sd_model *m)
+{
+    for (int s = 0; s < c->n_slots; s++)
+        if (c->models[s] == m) return s;
+    return -1;
+}
+
+extern "C" int sd_ctx_attach(sd_ctx *c, sd_model *m)
+{
+    if (!c || !m) return sd_fail(SD_EINVAL, "sd_ctx_attach: null argument");
+    if (find_slot(c, m) >= 0) return SD_OK;
+    if (c->n_slots >= SD_MAX_SLOTS) return sd_fail(SD_ECAP, "sd_ctx_attach: too many models");
+    size_t bytes = (size_t)m->cfg.n_layers * m->cfg.d_model * c->total_cap * m->esz;
+    void *k = nullptr, *v = nullptr;
+    hipError_t e = hipMalloc(&k, bytes);
+    if (e == hipSuccess) e = hipMalloc(&v, bytes);
+    if (e != hipSuccess) {
+        if (k) (void)hipFree(k);
+        return sd_fail(SD_EHIP, std::string("sd_ctx_attach: hipMalloc KV cache: ") + hipGetErrorString(e));
+    }
+    // zero-fill so that never-written rows hold finite values
+    SD_HIP(hipMemset(k, 0, bytes));
+    SD_HIP(hipMemset(v, 0, bytes));
+    SD_HIP(hipDeviceSynchronize());
+    int s = c->n_slots++;
+    c->models[s] = m;
+    c->kcache[s] = k;
+    c->vcache[s] = v;
+    return SD_OK;
+}
+
+extern "C" int sd_ctx_set_tokens(sd_ctx *c, const int32_t *tokens, const int32_t *lens, const int32_t *seq_ids,
+                                 int32_t n_seq)
+{
+    if (!c || !tokens || !lens || n_seq < 1 || n_seq > c->B) return sd_fail(SD_EINVAL, "sd_ctx_set_tokens: bad argument");
+    SD_HIP(hipDeviceSynchronize());
+    size_t pos = 0;
+    std::vector<int32_t> zero(SD_MAX_SLOTS, 0);
+    for (int j = 0; j < n_seq; j++) {
+        int b = seq_ids ? seq_ids[j] : j;
+        if (b < 0 || b >= c->B) return sd_fail(SD_EINVAL, "sd_ctx_set_tokens: sequence id out of range");
+        if (lens[j] < 1 || lens[j] > c->cap[b]) return sd_fail(SD_ECAP, "sd_ctx_set_tokens: length beyond capacity");
+        SD_HIP(hipMemcpy(c->d_tokens + c->off[b], tokens + pos, sizeof(int32_t) * lens[j], hipMemcpyHostToDevice));
+        SD_HIP(hipMemcpy(c->d_ntok + b, &lens[j], sizeof(int32_t), hipMemcpyHostToDevice));
+        for (int s = 0; s < SD_MAX_SLOTS; s++)
+            SD_HIP(hipMemcpy(c->d_kvlen + (size_t)s * c->B + b, &zero[0], sizeof(int32_t), hipMemcpyHostToDevice));
+        pos += lens[j];
+        c->len_upper = std::max(c->len_upper, lens[j]);
+    }
+    SD_HIP(hipDeviceSynchronize());
+    return SD_OK;
+}
+
+extern "C" int sd_ctx_sync(sd_ctx *c, sd_model *m, int32_t *n_tokens, int32_t *kv_len)
+{
+    if (!c) return sd_fail(SD_EINVAL, "sd_ctx_sync: null context");
+    SD_HIP(hipDeviceSynchronize());
+    std::vector<int32_t> nt(c->B);
+    SD_HIP(hipMemcpy(nt.data(), c->d_ntok, sizeof(int32_t) * c->B, hipMemcpyDeviceToHost));
+    c->len_upper = *std::max_element(nt.begin(), nt.end());
+    if (n_tokens) memcpy(n_tokens, nt.data(), sizeof(int32_t) * c->B);
+    if (m && kv_len) {
+        int s = find_slot(c, m);
+        if (s < 0) return sd_fail(SD_EINVAL, "sd_ctx_sync: model not attached");
+        SD_HIP(hipMemcpy(kv_len, c->d_kvlen + (size_t)s * c->B, sizeof(int32_t) * c->B, hipMemcpyDeviceToHost));
+    }
+    int32_t st = 0;
+    SD_HIP(hipMemcpy(&st, c->d_status, sizeof(int32_t), hipMemcpyDeviceToHost));
+    if (st) {
+        SD_HIP(hipMemset(c->d_status, 0, sizeof(int32_t)));
+        std::string msg = "device status:";
+        if (st & 1) msg += " capacity exceeded;";
+        if (st & 2) msg += " verify on a sequence whose cache is not at n-1;";
+        if (st & 4) msg += " sequence id out of range;";
+        if (st & 8) msg += " position beyond the rotary table;";
+        if (st & 16) msg += " token id outside the vocabulary;";
+        return sd_fail(SD_ESTATE, msg);
+    }
+    return SD_OK;
+}
+
+extern "C" int sd_ctx_get_tokens(sd_ctx *c, int32_t seq, int32_t *out, int32_t max_tokens, int32_t *n_out)
+{
+    if (!c || seq < 0 || seq >= c->B || !out || max_tokens < 0) return sd_fail(SD_EINVAL, "sd_ctx_get_tokens: bad argument");
+    SD_HIP(hipDeviceSynchronize());
+    int32_t n = 0;
+    SD_HIP(hipMemcpy(&n, c->d_ntok + seq, sizeof(int32_t), hipMemcpyDeviceToHost));
+    int32_t k = std::min(n, max_tokens);
+    if (k > 0) SD_HIP(hipMemcpy(out, c->d_tokens + c->off[seq], sizeof(int32_t) * k, hipMemcpyDeviceToHost));
+    if (n_out) *n_out = n;
+    return SD_OK;
+}
+
+extern "C" int sd_ctx_set_kv(sd_ctx *c, sd_model *m, int32_t layer, int32_t seq, const void *k, const void *v,
+                             int32_t len)
+{
+    if (!c || !m || !k || !v) return sd_fail(SD_EINVAL, "sd_ctx_set_kv: null argument");
+    int s = find_slot(c, m);
+    if (s < 0) return sd_fail(SD_EINVAL, "sd_ctx_set_kv: model not attached");
+    if (layer < 0 || layer >= m->cfg.n_layers || seq < 0 || seq >= c->B) return sd_fail(SD_EINVAL, "sd_ctx_set_kv: bad index");
+    if (len < 0 || len > c->cap[seq]) return sd_fail(SD_ECAP, "sd_ctx_set_kv: length beyond capacity");
+    size_t bytes = (size_t)len * m->cfg.d_model * m->esz;
+    void *dk = nullptr, *dv = nullptr;
+    if (len > 0) {
+        SD_HIP(hipMalloc(&dk, bytes));
+        SD_HIP(hipMalloc(&dv, bytes));
+        SD_HIP(hipMemcpy(dk, k, bytes, hipMemcpyHostToDevice));
+        SD_HIP(hipMemcpy(dv, v, bytes, hipMemcpyHostToDevice));
+        size_t lstride = (size_t)m->cfg.d_model * c->total_cap * m->esz;
+        hipError_t e = launch_set_kv(0, m->cfg.dtype, dk, dv, len, m->cfg.n_heads, m->cfg.head_dim, c->off[seq],
+                                     c->total_cap, (char *)c->kcache[s] + layer * lstride,
+                                     (char *)c->vcache[s] + layer * lstride);
+        hipError_t e2 = hipDeviceSynchronize();
+        (void)hipFree(dk);
+        (void)hipFree(dv);
+        SD_HIP(e);
+        SD_HIP(e2);
+    }
+    SD_HIP(hipMemcpy(c->d_kvlen + (size_t)s * c->B + seq, &len, sizeof(int32_t), hipMemcpyHostToDevice));
+    return SD_OK;
+}
+
+extern "C" int sd_ctx_truncate(sd_ctx *c, sd_model *m, int32_t seq, int32_t len)
+{
+    if (!c || !m || seq < 0 || seq >= c->B || len < 0) return sd_fail(SD_EINVAL, "sd_ctx_truncate: bad argument");
+    int s = find_slot(c, m);
+    if (s < 0) return sd_fail(SD_EINVAL, "sd_ctx_truncate: model not attached");
+    SD_HIP(hipDeviceSynchronize());
+    int32_t cur = 0;
+    SD_HIP(hipMemcpy(&cur, c->d_kvlen + (size_t)s * c->B + seq, sizeof(int32_t), hipMemcpyDeviceToHost));
+    if (len < cur) SD_HIP(hipMemcpy(c->d_kvlen + (size_t)s * c->B + seq, &len, sizeof(int32_t), hipMemcpyHostToDevice));
+    return SD_OK;
+}
+
+extern "C" int sd_last_logits(sd_model *m, float *out, int32_t max_rows, int32_t *rows)
+{
+    if (!m || !out || max_rows < 0) return sd_fail(SD_EINVAL, "sd_last_logits: bad argument");
+    SD_HIP(hipDeviceSynchronize());
+    int n = std::min(m->last_lm_rows, max_rows);
+    if (n > 0) SD_HIP(hipMemcpy(out, m->logits, (size_t)n * m->cfg.vocab * sizeof(float), hipMemcpyDeviceToDevice));
+    if (rows) *rows = n;
+    return SD_OK;
+}
+
+// ---------------------------------------------------------------- one decoder forward
+static hipError_t gemm(sd_model *m, hipStream_t s, int mode, const void *A, WeightSeg w, int M, int N, int K,
+                       float *C, void *Cact)
+{
+    if (m->cfg.dtype == SD_BF16 && !g_force_generic) {
+        hipError_t e = launch_gemm_skinny_bf16(s, mode, A, w, M, N, K, C, Cact);
+        if (e != hipErrorNotSupported) return e;
+    }
+    return launch_gemm_generic(s, m->cfg.dtype, mode, A, w, M, N, K, C, Cact);
+}
+
+#define FWD(expr)                                                                                  \
+    do {                                                                                           \
+        hipError_t e__ = (expr);                                                                   \
+        if (e__ != hipSuccess)                                                                     \
+            return sd_fail(SD_EHIP, std::string("forward: ") + #expr + ": " + hipGetErrorString(e__)); \
+    } while (0)
+
+// Rows are laid out as R slots per selected sequence.  Logits are produced for
+// n_lm rows (every row for verify, the last valid row of each sequence for
+// draft, none when want_logits is false).
+static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, int R, int n_seq,
+                   const int32_t *seq_ids, int upto_off, const int32_t *cand, int gamma, int cand_idx,
+                   bool want_logits)
+{
+    const sd_model_config &cf = m->cfg;
+    const int M = n_seq * R, d = cf.d_model, H = cf.n_heads, hd = cf.head_dim, F = cf.d_ffn, V = cf.vocab;
+    if (M > cf.max_rows) return sd_fail(SD_ECAP, "forward: rows exceed the model's max_rows");
+    CtxView cv = c->view();
+    PlanView pv = m->plan;
+    int kv_upper = c->len_upper + SD_MAX_GAMMA + 1;
+    size_t lstride = (size_t)d * c->total_cap * m->esz;
+    FWD(launch_plan(s, mode, R, n_seq, seq_ids, cv, slot, upto_off, cand, gamma, cand_idx, V, pv));
+    FWD(launch_embed(s, cf.dtype, m->embed, pv.row_tok, M, d, m->x));
+    for (int l = 0; l < cf.n_layers; l++) {
+        void *Kl = (char *)c->kcache[slot] + l * lstride, *Vtl = (char *)c->vcache[slot] + l * lstride;
+        FWD(launch_rmsnorm(s, cf.dtype, m->x, m->norm_attn[l], nullptr, M, d, cf.rms_eps, m->abuf));
+        WeightSeg wqkv = {{m->wq[l], m->wk[l], m->wv[l]}, d};
+        FWD(gemm(m, s, GEMM_STORE, m->abuf, wqkv, M, 3 * d, d, m->qkv, nullptr));
+        FWD(launch_rope_append(s, cf.dtype, m->qkv, pv, cv, M, H, hd, m->rope, cf.max_pos, m->qbuf, Kl, Vtl,
+                               c->total_cap));
+        hipError_t ea = hipErrorNotSupported;
+        if (cf.dtype == SD_BF16 && !g_force_generic)
+            ea = launch_attn_mfma_bf16(s, m->qbuf, Kl, Vtl, pv, cv, R, n_seq, H, hd, c->total_cap, kv_upper, m->part,
+                                       m->part_floats, m->obuf);
+        if (ea == hipErrorNotSupported)
+            ea = launch_attn_generic(s, cf.dtype, m->qbuf, Kl, Vtl, pv, cv, R, n_seq, H, hd, c->total_cap, kv_upper,
+                                     m->obuf);
+        if (ea == hipErrorNotSupported) return sd_fail(SD_ECAP, "forward: context too long for the generic attention kernel");
+        FWD(ea);
+        WeightSeg wo = {{m->wo[l], nullptr, nullptr}, d};
+        FWD(gemm(m, s, GEMM_RESID, m->obuf, wo, M, d, d, m->x, nullptr));
+        FWD(launch_rmsnorm(s, cf.dtype, m->x, m->norm_ffn[l], nullptr, M, d, cf.rms_eps, m->abuf));
+        WeightSeg wgu = {{m->wgate[l], m->wup[l], nullptr}, F};
+        FWD(gemm(m, s, GEMM_SWIGLU, m->abuf, wgu, M, F, d, nullptr, m->act));
+        WeightSeg wd = {{m->wdown[l], nullptr, nullptr}, d};
+        FWD(gemm(m, s, GEMM_RESID, m->act, wd, M, d, F, m->x, nullptr));
+    }
+    if (want_logits) {
+        int n_lm = mode == PLAN_VERIFY ? M : n_seq;
+        FWD(launch_rmsnorm(s, cf.dtype, m->x, m->final_norm, pv.lm_row, n_lm, d, cf.rms_eps, m->abuf));
+        WeightSeg wl = {{m->lm_head, nullptr, nullptr}, V};
+        FWD(gemm(m, s, GEMM_STORE, m->abuf, wl, n_lm, V, d, m->logits, nullptr));
+        m->last_lm_rows = n_lm;
+    }
+    return SD_OK;
+}
+
+static int check_call(const char *who, sd_model *m, sd_ctx *c, int n_seq, int *slot)
+{
+    if (!m || !c) return sd_fail(SD_EINVAL, std::string(who) + ": null model or context");
+    if (n_seq < 1 || n_seq > c->B) return sd_fail(SD_EINVAL, std::string(who) + ": n_seq out of range");
+    *slot = find_slot(c, m);
+    if (*slot < 0) return sd_fail(SD_EINVAL, std::string(who) + ": model not attached to this context");
+    return SD_OK;
+}
+
+extern "C" int sd_prefill(sd_model *m, sd_ctx *c, const int32_t *seq_ids, int32_t n_seq, int32_t max_new,
+                          void *stream)
+{
+    int slot;
+    int rc = check_call("sd_prefill", m, c, n_seq, &slot);
+    if (rc) return rc;
+    if (max_new < 0) return sd_fail(SD_EINVAL, "sd_prefill: max_new < 0");
+    int R = std::min(m->cfg.max_rows / n_seq, 16);
+    if (R < 1) return sd_fail(SD_ECAP, "sd_prefill: n_seq exceeds the model's max_rows");
+    for (int done = 0; done < max_new; done += R) {
+        rc = forward(m, c, slot, (hipStream_t)stream, PLAN_CATCHUP, R, n_seq, seq_ids, 1, nullptr, 0, 0, false);
+        if (rc) return rc;
+    }
+    return SD_OK;
+}
+
+extern "C" int sd_draft(sd_model *draft, sd_ctx *c, const int32_t *seq_ids, int32_t n_seq, int32_t gamma,
+                        float temperature, const float *uniforms, int32_t *cand, float *q, void *stream)
+{
+    int slot;
+    int rc = check_call("sd_draft", draft, c, n_seq, &slot);
+    if (rc) return rc;
+    if (gamma < 1 || gamma > SD_MAX_GAMMA) return sd_fail(SD_ECAP, "sd_draft: gamma must be in [1, 15]");
+    if (!cand) return sd_fail(SD_EINVAL, "sd_draft: null cand");
+    if (!(temperature >= 0.f)) return sd_fail(SD_EINVAL, "sd_draft: negative temperature");
+    if (temperature > 0.f && (!uniforms || !q)) return sd_fail(SD_EINVAL, "sd_draft: sampling needs uniforms and q");
+    if (2 * n_seq > draft->cfg.max_rows) return sd_fail(SD_ECAP, "sd_draft: 2*n_seq exceeds the model's max_rows");
+    hipStream_t s = (hipStream_t)stream;
+    for (int i = 0; i < gamma; i++) {
+        if (i == 0) rc = forward(draft, c, slot, s, PLAN_CATCHUP, 2, n_seq, seq_ids, 0, nullptr, gamma, 0, true);
+        else rc = forward(draft, c, slot, s, PLAN_CAND, 1, n_seq, seq_ids, 0, cand, gamma, i - 1, true);
+        if (rc) return rc;
+        hipError_t e = launch_draft_sample(s, draft->logits, n_seq, draft->cfg.vocab, temperature, uniforms, gamma, i,
+                                           cand, q);
+        if (e != hipSuccess) return sd_fail(SD_EHIP, std::string("sd_draft: sample: ") + hipGetErrorString(e));
+    }
+    return SD_OK;
+}
+
+extern "C" int sd_verify(sd_model *target, sd_ctx *c, const int32_t *seq_ids, int32_t n_seq, int32_t gamma,
+                         float temperature, const int32_t *cand, const float *q, const float *uniforms,
+                         int32_t *n_accepted, int32_t *next_token, int32_t commit, void *stream)
+{
+    int slot;
+    int rc = check_call("sd_verify", target, c, n_seq, &slot);
+    if (rc) return rc;
+    if (gamma < 0 || gamma > SD_MAX_GAMMA) return sd_fail(SD_ECAP, "sd_verify: gamma must be in [0, 15]");
+    if (!n_accepted || !next_token) return sd_fail(SD_EINVAL, "sd_verify: null output");
+    if (gamma > 0 && !cand) return sd_fail(SD_EINVAL, "sd_verify: null cand");
+    if (!(temperature >= 0.f)) return sd_fail(SD_EINVAL, "sd_verify: negative temperature");
+    if (temperature > 0.f && (!uniforms || (gamma > 0 && !q)))
+        return sd_fail(SD_EINVAL, "sd_verify: sampling needs uniforms and q");
+    if (n_seq * (gamma + 1) > target->cfg.max_rows) return sd_fail(SD_ECAP, "sd_verify: rows exceed the model's max_rows");
+    hipStream_t s = (hipStream_t)stream;
+    rc = forward(target, c, slot, s, PLAN_VERIFY, gamma + 1, n_seq, seq_ids, 0, cand, gamma, 0, true);
+    if (rc) return rc;
+    hipError_t e = launch_verify_tail(s, target->logits, n_seq, gamma, target->cfg.vocab, temperature, cand, q,
+                                      uniforms, seq_ids, n_accepted, next_token, commit, c->view());
+    if (e != hipSuccess) return sd_fail(SD_EHIP, std::string("sd_verify: tail: ") + hipGetErrorString(e));
+    if (commit) c->len_upper += gamma + 1;
+    return SD_OK;
+}
+
+extern "C" int sd_commit(sd_ctx *c, const int32_t *seq_ids, int32_t n_seq, int32_t gamma, const int32_t *cand,
+                         const int32_t *n_accepted, const int32_t *next_token, void *stream)
+{
+    if (!c || !n_accepted || !next_token || (gamma > 0 && !cand)) return sd_fail(SD_EINVAL, "sd_commit: null argument");
+    if (n_seq < 1 || n_seq > c->B || gamma < 0 || gamma > SD_MAX_GAMMA) return sd_fail(SD_EINVAL, "sd_commit: bad n_seq or gamma");
+    hipError_t e = launch_commit((hipStream_t)stream, c->view(), seq_ids, n_seq, gamma, cand, n_accepted, next_token);
+    if (e != hipSuccess) return sd_fail(SD_EHIP, std::string("sd_commit: ") + hipGetErrorString(e));
+    c->len_upper += gamma + 1;
+    return SD_OK;
+}
+
+extern "C" int sd_route(const float *W, const float *b, int32_t n_drafts, int32_t emb_dim, const float *prompt_emb,
+                        int32_t n, int32_t *draft_id, void *stream)
+{
+    if (!W || !prompt_emb || !draft_id) return sd_fail(SD_EINVAL, "sd_route: null argument");
+    if (n_drafts < 1 || emb_dim < 1 || n < 1) return sd_fail(SD_EINVAL, "sd_route: non-positive size");
+    hipError_t e = launch_route((hipStream_t)stream, W, b, n_drafts, emb_dim, prompt_emb, n, draft_id);
+    if (e != hipSuccess) return sd_fail(SD_EHIP, std::string("sd_route: ") + hipGetErrorString(e));
+    return SD_OK;
+}

@@ -1,0 +1,172 @@
+// Internal declarations shared by the HIP sources of libsd (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "../../include/sd.h"
+
+#define SD_MAX_SLOTS 8
+#define SD_MAX_GAMMA 15
+#define SD_ATTN_MAX_SPLITS 32
+
+// ---------------------------------------------------------------- element types
+struct bf16_t {
+    uint16_t v;
+};
+
+__device__ __forceinline__ float to_float(float x) { return x; }
+__device__ __forceinline__ float to_float(bf16_t x) { return __uint_as_float((uint32_t)x.v << 16); }
+
+// fp32 -> bf16, round to nearest, ties to even (finite inputs).
+__device__ __forceinline__ uint16_t bf16_bits_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+template <typename T>
+__device__ __forceinline__ T from_float(float f);
+template <>
+__device__ __forceinline__ float from_float<float>(float f) { return f; }
+template <>
+__device__ __forceinline__ bf16_t from_float<bf16_t>(float f)
+{
+    bf16_t r;
+    r.v = bf16_bits_rne(f);
+    return r;
+}
+
+// ---------------------------------------------------------------- views passed to kernels
+// Device-side view of a context.  kvlen is [SD_MAX_SLOTS][B].
+struct CtxView {
+    int32_t B;
+    int32_t n_slots;
+    const int64_t *off; // [B] token / cache-row offset of each sequence
+    const int32_t *cap; // [B]
+    int32_t *tokens;    // [total_cap]
+    int32_t *ntok;      // [B]
+    int32_t *kvlen;     // [SD_MAX_SLOTS][B]
+    int32_t *status;    // [1] sticky error bits
+};
+
+// Row plan of one forward: R row slots per selected sequence j (rows j*R .. j*R+R-1).
+struct PlanView {
+    int32_t *row_tok;   // [M] token id fed in this row
+    int32_t *row_pos;   // [M] position (= cache row it is appended to)
+    int32_t *row_b;     // [M] sequence index in the context
+    int32_t *row_valid; // [M] 0 for unused slots
+    int32_t *seq_b;     // [n_seq]
+    int32_t *seq_kv0;   // [n_seq] cache length before this forward
+    int32_t *seq_nq;    // [n_seq] valid rows of this sequence
+    int32_t *lm_row;    // [n_lm] source row of each logits row
+};
+
+enum PlanMode { PLAN_CATCHUP = 0, PLAN_CAND = 1, PLAN_VERIFY = 2 };
+
+struct WeightSeg { // up to three matrices stacked along N (q,k,v or gate,up)
+    const void *p[3];
+    int32_t n_per_seg;
+};
+
+enum GemmMode { GEMM_STORE = 0, GEMM_RESID = 1, GEMM_SWIGLU = 2 };
+
+// ---------------------------------------------------------------- host-side objects
+struct sd_model {
+    sd_model_config cfg;
+    std::vector<const void *> wq, wk, wv, wo, wgate, wup, wdown;
+    std::vector<const float *> norm_attn, norm_ffn;
+    const void *embed, *lm_head;
+    const float *final_norm;
+    int esz; // bytes per weight / activation element
+    // workspace (device)
+    float *x;       // [max_rows][d] residual stream
+    void *abuf;     // [max_rows][d] normed GEMM input
+    float *qkv;     // [max_rows][3*d]
+    void *qbuf;     // [max_rows][d] rotated queries
+    void *obuf;     // [max_rows][d] attention output
+    void *act;      // [max_rows][d_ffn]
+    float *logits;  // [max_rows][vocab]
+    float *part;    // split-K / split-KV partial results
+    size_t part_floats;
+    float2 *rope;   // [max_pos][head_dim/2] (cos, sin)
+    int32_t *plan_mem;
+    PlanView plan;
+    int last_lm_rows;
+};
+
+struct sd_ctx {
+    int B;
+    int64_t total_cap;
+    std::vector<int32_t> cap;
+    std::vector<int64_t> off;
+    int64_t *d_off;
+    int32_t *d_cap, *d_tokens, *d_ntok, *d_kvlen, *d_status;
+    int n_slots;
+    sd_model *models[SD_MAX_SLOTS];
+    void *kcache[SD_MAX_SLOTS];
+    void *vcache[SD_MAX_SLOTS];
+    int len_upper; // host upper bound of the longest sequence (tokens)
+    CtxView view() const
+    {
+        CtxView v;
+        v.B = B;
+        v.n_slots = n_slots;
+        v.off = d_off;
+        v.cap = d_cap;
+        v.tokens = d_tokens;
+        v.ntok = d_ntok;
+        v.kvlen = d_kvlen;
+        v.status = d_status;
+        return v;
+    }
+};
+
+// ---------------------------------------------------------------- error plumbing
+void sd_set_error(const std::string &s);
+int sd_fail(int code, const std::string &s);
+#define SD_HIP(expr)                                                                          \
+    do {                                                                                      \
+        hipError_t e__ = (expr);                                                              \
+        if (e__ != hipSuccess)                                                                \
+            return sd_fail(SD_EHIP, std::string(#expr) + ": " + hipGetErrorString(e__));      \
+    } while (0)
+
+extern int g_force_generic;
+
+// ---------------------------------------------------------------- kernel launchers
+// (each returns a hipError_t from hipGetLastError after the launch)
+hipError_t launch_plan(hipStream_t s, int mode, int R, int n_seq, const int32_t *seq_ids, CtxView cv, int slot,
+                       int upto_off, const int32_t *cand, int gamma, int cand_idx, int vocab, PlanView pv);
+hipError_t launch_embed(hipStream_t s, int dtype, const void *E, const int32_t *row_tok, int M, int d, float *x);
+hipError_t launch_rmsnorm(hipStream_t s, int dtype, const float *x, const float *g, const int32_t *row_map,
+                          int n_rows, int d, float eps, void *out);
+hipError_t launch_gemm_generic(hipStream_t s, int dtype, int mode, const void *A, WeightSeg w, int M, int N, int K,
+                               float *C, void *Cact);
+hipError_t launch_rope_append(hipStream_t s, int dtype, const float *qkv, PlanView pv, CtxView cv, int M, int H,
+                              int hd, const float2 *rope, int max_pos, void *qbuf, void *Kl, void *Vtl,
+                              int64_t total_cap);
+hipError_t launch_attn_generic(hipStream_t s, int dtype, const void *qbuf, const void *Kl, const void *Vtl,
+                               PlanView pv, CtxView cv, int R, int n_seq, int H, int hd, int64_t total_cap,
+                               int len_upper, void *obuf);
+hipError_t launch_draft_sample(hipStream_t s, const float *logits, int n_seq, int V, float T, const float *u,
+                               int gamma, int idx, int32_t *cand, float *q);
+hipError_t launch_verify_tail(hipStream_t s, const float *logits, int n_seq, int gamma, int V, float T,
+                              const int32_t *cand, const float *q, const float *u, const int32_t *seq_ids,
+                              int32_t *n_acc, int32_t *next_tok, int commit, CtxView cv);
+hipError_t launch_commit(hipStream_t s, CtxView cv, const int32_t *seq_ids, int n_seq, int gamma,
+                         const int32_t *cand, const int32_t *n_acc, const int32_t *next_tok);
+hipError_t launch_route(hipStream_t s, const float *W, const float *b, int n_drafts, int emb, const float *e, int n,
+                        int32_t *id);
+hipError_t launch_set_kv(hipStream_t s, int dtype, const void *k_rows, const void *v_rows, int len, int H, int hd,
+                         int64_t seq_off, int64_t total_cap, void *Kl, void *Vtl);
+
+// optimised bf16 paths (return hipErrorNotSupported when the shape is outside their domain)
+hipError_t launch_gemm_skinny_bf16(hipStream_t s, int mode, const void *A, WeightSeg w, int M, int N, int K,
+                                   float *C, void *Cact);
+hipError_t launch_attn_mfma_bf16(hipStream_t s, const void *qbuf, const void *Kl, const void *Vtl, PlanView pv,
+                                 CtxView cv, int R, int n_seq, int H, int hd, int64_t total_cap, int len_upper,
+                                 float *part, size_t part_floats, void *obuf);

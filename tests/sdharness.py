@@ -1,0 +1,200 @@
+"""Shared helpers of the GPU parity tests: run the oracle's trajectory first, then
+teacher-force the HIP path along it step by step.
+
+Parity bar: candidate ids, n_accepted and next tokens bit-exact; a step may be
+*flagged* instead only when the oracle's own decision margin is below the
+threshold (accept test: |u - p/q|; inverse-CDF draw: distance of u from the
+chosen token's interval edge as a fraction of the mass; greedy: top-1/top-2
+logit gap).  Logits: max |gpu - oracle| / max |oracle| per row below the
+dtype's tolerance.  No expected value ever comes from the HIP path: after every
+step the HIP context is committed with the ORACLE's result.
+"""
+from __future__ import annotations
+
+import dataclasses
+from typing import List, Optional
+
+import numpy as np
+import torch
+
+import oracle
+from paper_2505_08600_amd import api
+from paper_2505_08600_amd import datagen as dg
+
+LOGIT_TOL = {dg.FP32: 1e-4, dg.BF16: 2e-2}     # max relative error of a logits row
+MARGIN_THR = {dg.FP32: 1e-5, dg.BF16: 1e-3}    # probability-space decision margins
+# greedy decisions: a step may be flagged iff the oracle's top-1/top-2 logit gap is below the
+# absolute logit error the dtype's tolerance allows at the logit scales of these tests (|logit| <~ 25)
+GREEDY_GAP_THR = {dg.FP32: 2.5e-3, dg.BF16: 0.1}
+
+
+@dataclasses.dataclass
+class ParityStats:
+    steps: int = 0
+    flagged: int = 0
+    max_logit_rel: float = 0.0
+    max_q_abs: float = 0.0
+    n_acc: List[int] = dataclasses.field(default_factory=list)
+
+    def merge_logits(self, gpu: np.ndarray, ref: np.ndarray):
+        rel = float(np.max(np.abs(gpu.astype(np.float64) - ref) / np.max(np.abs(ref), axis=-1, keepdims=True)))
+        self.max_logit_rel = max(self.max_logit_rel, rel)
+        return rel
+
+
+def uf(seed, stream, seq=0):
+    return lambda step, n: dg.make_uniforms(seed, stream, seq, step, n)
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+class Pair:
+    """Target + draft, the same weights loaded into the oracle and into libsd."""
+
+    def __init__(self, shape_t, shape_d, seed, lm_scale=1.0, draft_weights=None, target_weights=None,
+                 max_rows=32, max_pos=256):
+        self.shape_t, self.shape_d = shape_t, shape_d
+        self.wt = target_weights if target_weights is not None else dg.make_weights(shape_t, seed, lm_scale)
+        self.wd = draft_weights if draft_weights is not None else dg.make_weights(shape_d, seed + 1, lm_scale)
+        self.ot = oracle.OracleModel(shape_t, self.wt)
+        self.od = oracle.OracleModel(shape_d, self.wd)
+        self.gt = api.Model(shape_t, self.wt, max_rows=max_rows, max_pos=max_pos)
+        self.gd = api.Model(shape_d, self.wd, max_rows=max_rows, max_pos=max_pos)
+
+    def close(self):
+        self.gt.close()
+        self.gd.close()
+
+
+def oracle_trajectory(pair: Pair, prompt, gamma, T, n_tokens, seed, seq=0, keep_logits=True):
+    cap = len(prompt) + n_tokens + 2 * gamma + 4
+    toks, steps = oracle.sd_generate(pair.ot.new_seq(cap), pair.od.new_seq(cap), prompt, gamma, T, n_tokens,
+                                     uf(seed, dg.DRAFT_STREAM, seq), uf(seed, dg.VERIFY_STREAM, seq),
+                                     keep_logits=keep_logits)
+    return toks, steps, cap
+
+
+def gpu_prefill(ctx: api.Context, models, prompts, seq_ids=None):
+    ctx.set_tokens(prompts, seq_ids)
+    n = len(prompts)
+    ids = dev(np.asarray(seq_ids, np.int32)) if seq_ids is not None else None
+    mx = max(len(p) for p in prompts) - 1
+    for m in models:
+        api.sd_prefill(m, ctx, ids, n, mx)
+    torch.cuda.synchronize()
+
+
+def teacher_forced_parity(pair: Pair, prompt, gamma, T, n_tokens, seed, check_logits=True) -> ParityStats:
+    """One sequence: HIP draft and verify are compared with the oracle at every step
+    of the oracle's own trajectory."""
+    dtype = pair.shape_t.dtype
+    thr = MARGIN_THR[dtype]
+    toks, steps, cap = oracle_trajectory(pair, prompt, gamma, T, n_tokens, seed, keep_logits=check_logits)
+    V = pair.shape_t.vocab
+    ctx = api.Context([cap])
+    ctx.attach(pair.gt)
+    ctx.attach(pair.gd)
+    gpu_prefill(ctx, [pair.gt, pair.gd], [list(prompt)])
+    st = ParityStats()
+    cand_g = torch.zeros((1, gamma), dtype=torch.int32, device="cuda")
+    q_g = torch.zeros((1, gamma, V), dtype=torch.float32, device="cuda") if T > 0 else None
+    nacc_g = torch.zeros(1, dtype=torch.int32, device="cuda")
+    next_g = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for k, s in enumerate(steps):
+        # ---- draft (Figure 1a)
+        ud = dev(s.u_draft[None]) if T > 0 else None
+        api.sd_draft(pair.gd, ctx, None, 1, gamma, T, ud, cand_g, q_g)
+        cg = cand_g.cpu().numpy()[0]
+        flagged = False
+        first_bad = None
+        for i in range(gamma):
+            if cg[i] != s.cand[i]:
+                first_bad = i
+                break
+        if first_bad is not None:
+            mg = s.draft_margins[first_bad]
+            lim = thr if T > 0 else GREEDY_GAP_THR[dtype]
+            assert mg < lim, f"step {k}: draft candidate {first_bad} differs ({cg} vs {s.cand}), margin {mg}"
+            flagged = True
+        if T > 0:
+            upto = gamma if first_bad is None else first_bad + 1
+            qg = q_g.cpu().numpy()[0]
+            dq = float(np.abs(qg[:upto] - s.q[:upto]).max())
+            st.max_q_abs = max(st.max_q_abs, dq)
+            assert dq <= 50 * LOGIT_TOL[dtype], f"step {k}: draft q differs by {dq}"
+        # ---- verify (Figure 1b) on the ORACLE's candidates and q
+        cand_in = dev(s.cand[None].astype(np.int32))
+        q_in = dev(s.q[None]) if T > 0 else None
+        uv = dev(s.u_verify[None]) if T > 0 else None
+        api.sd_verify(pair.gt, ctx, None, 1, gamma, T, cand_in, q_in, uv, nacc_g, next_g, commit=False)
+        na, nx = int(nacc_g.item()), int(next_g.item())
+        if check_logits:
+            lg = pair.gt.last_logits().cpu().numpy()
+            rel = st.merge_logits(lg, s.logits.astype(np.float64))
+            assert rel <= LOGIT_TOL[dtype], f"step {k}: logits rel err {rel}"
+        if (na, nx) != (s.n_acc, s.next_token):
+            examined = s.verify_margins[:min(s.n_acc, na) + 1] if na != s.n_acc else s.verify_margins[gamma:]
+            mg = float(np.min(examined))
+            lim = thr if T > 0 else GREEDY_GAP_THR[dtype]
+            assert mg < lim, (f"step {k}: verify differs: gpu ({na},{nx}) oracle ({s.n_acc},{s.next_token}), "
+                              f"margins {s.verify_margins}")
+            flagged = True
+        # ---- commit the oracle's result (teacher forcing)
+        api.sd_commit(ctx, None, 1, gamma, cand_in, dev(np.array([s.n_acc], np.int32)),
+                      dev(np.array([s.next_token], np.int32)))
+        if first_bad is not None:  # the draft cache holds rows of other candidates: roll back and re-feed
+            torch.cuda.synchronize()
+            ctx.truncate(pair.gd, 0, s.n_ctx - 1 + first_bad)
+            api.sd_prefill(pair.gd, ctx, None, 1, gamma + 2)
+        st.steps += 1
+        st.flagged += int(flagged)
+        st.n_acc.append(s.n_acc)
+    torch.cuda.synchronize()
+    nt, kv = ctx.sync(pair.gt)
+    n_expected = len(prompt) + sum(s.n_acc + 1 for s in steps)
+    assert nt[0] == n_expected and kv[0] == n_expected - 1
+    got = ctx.get_tokens(0)
+    ref_all = list(prompt)
+    for s in steps:
+        ref_all += [int(c) for c in s.cand[:s.n_acc]] + [s.next_token]
+    assert list(got) == ref_all
+    ctx.close()
+    return st
+
+
+def free_running(pair: Pair, prompt, gamma, T, n_tokens, seed):
+    """The production loop: draft -> verify(commit) with no host reads in between.
+    -> (gpu tokens, n_steps)"""
+    cap = len(prompt) + n_tokens + 2 * gamma + 4
+    V = pair.shape_t.vocab
+    ctx = api.Context([cap])
+    ctx.attach(pair.gt)
+    ctx.attach(pair.gd)
+    gpu_prefill(ctx, [pair.gt, pair.gd], [list(prompt)])
+    cand_g = torch.zeros((1, gamma), dtype=torch.int32, device="cuda")
+    q_g = torch.zeros((1, gamma, V), dtype=torch.float32, device="cuda") if T > 0 else None
+    nacc_g = torch.zeros(1, dtype=torch.int32, device="cuda")
+    next_g = torch.zeros(1, dtype=torch.int32, device="cuda")
+    max_steps = n_tokens
+    uds = [dev(dg.make_uniforms(seed, dg.DRAFT_STREAM, 0, k, gamma)[None]) for k in range(max_steps)]
+    uvs = [dev(dg.make_uniforms(seed, dg.VERIFY_STREAM, 0, k, gamma + 1)[None]) for k in range(max_steps)]
+    n_acc_log = []
+    steps = 0
+    while True:
+        api.sd_draft(pair.gd, ctx, None, 1, gamma, T, uds[steps] if T > 0 else None, cand_g, q_g)
+        api.sd_verify(pair.gt, ctx, None, 1, gamma, T, cand_g, q_g, uvs[steps] if T > 0 else None, nacc_g, next_g,
+                      commit=True)
+        steps += 1
+        n_acc_log.append(nacc_g.clone())
+        if steps % 8 == 0 or steps >= max_steps:
+            nt, _ = ctx.sync()
+            if nt[0] - len(prompt) >= n_tokens or steps >= max_steps:
+                break
+    toks = ctx.get_tokens(0)[len(prompt):len(prompt) + n_tokens]
+    ctx.close()
+    return [int(t) for t in toks], steps, [int(t.item()) for t in n_acc_log]

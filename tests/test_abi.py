@@ -1,0 +1,58 @@
+"""The C-ABI library loads and exports every symbol include/sd.h declares, and its
+argument checks fail cleanly without touching a GPU (CPU only)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2505_08600_amd import api
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    txt = open(os.path.join(ROOT, "include", "sd.h")).read()
+    txt = re.sub(r"/\*.*?\*/", "", txt, flags=re.S)
+    return sorted(set(re.findall(r"\b(sd_[a-z_0-9]+)\s*\(", txt)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared()
+    assert "sd_load_model" in names and "sd_draft" in names and "sd_verify" in names and "sd_route" in names
+    L = C.CDLL(api.LIB_PATH)
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(api.EXPORTS) == names
+
+
+def test_argument_errors_do_not_need_a_gpu():
+    L = api.lib()
+    assert L.sd_set_option(b"no_such_option", 1) == api.SD_EINVAL
+    assert b"unknown option" in L.sd_last_error()
+    assert L.sd_set_option(None, 1) == api.SD_EINVAL
+    assert L.sd_load_model(None, None, None) == api.SD_EINVAL
+    cfg = api._Config(2, 64, 4, 16, 96, 50, 0, 10000.0, 1e-5, 16, 64)
+    w = api._Weights()
+    h = C.c_void_p()
+    assert L.sd_load_model(C.byref(cfg), C.byref(w), C.byref(h)) == api.SD_EINVAL  # vocab % 4, null weights
+    cfg.n_heads = 3
+    assert L.sd_load_model(C.byref(cfg), C.byref(w), C.byref(h)) == api.SD_EINVAL
+    assert b"n_heads" in L.sd_last_error()
+    assert L.sd_ctx_create(0, None, None) == api.SD_EINVAL
+    assert L.sd_draft(None, None, None, 1, 4, 1.0, None, None, None, None) == api.SD_EINVAL
+    assert L.sd_verify(None, None, None, 1, 4, 1.0, None, None, None, None, None, 1, None) == api.SD_EINVAL
+    assert L.sd_commit(None, None, 1, 4, None, None, None, None) == api.SD_EINVAL
+    assert L.sd_route(None, None, 4, 256, None, 1, None, None) == api.SD_EINVAL
+    assert L.sd_prefill(None, None, None, 1, 1, None) == api.SD_EINVAL
+    assert L.sd_free_model(None) == api.SD_OK and L.sd_ctx_free(None) == api.SD_OK
+
+
+def test_product_package_does_not_import_the_oracle():
+    """The HIP path must not route through the CPU oracle."""
+    import glob
+    pk = os.path.join(ROOT, "paper_2505_08600_amd")
+    for f in glob.glob(os.path.join(pk, "**", "*"), recursive=True):
+        if f.endswith((".py", ".hip", ".h", ".cpp")):
+            src = open(f).read()
+            assert "oracle" not in src.lower() or f.endswith("datagen.py"), f
