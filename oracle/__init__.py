@@ -9,6 +9,8 @@ from .binding import (  # noqa: F401
     accept,
     argmax,
     build,
+    cdf_distance,
+    next_weights,
     rmsnorm,
     rope,
     round_bf16,

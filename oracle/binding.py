@@ -57,6 +57,10 @@ def _load():
         lib.orc_sample_cdf.argtypes = [vp, C.c_int, C.c_double, vp]
         lib.orc_route.argtypes = [vp, vp, C.c_int, C.c_int, vp, C.c_int, vp]
         lib.orc_route.restype = None
+        lib.orc_next_weights.argtypes = [C.c_int, C.c_int, C.c_double, vp, vp, C.c_int, vp]
+        lib.orc_next_weights.restype = None
+        lib.orc_cdf_distance.argtypes = [vp, C.c_int, C.c_double, C.c_int]
+        lib.orc_cdf_distance.restype = C.c_double
         lib.orc_round_bf16.argtypes = [C.c_float]
         lib.orc_round_bf16.restype = C.c_float
         _lib = lib
@@ -232,3 +236,19 @@ def route(W: np.ndarray, b: Optional[np.ndarray], emb: np.ndarray) -> np.ndarray
 
 def round_bf16(x: float) -> float:
     return float(_load().orc_round_bf16(float(x)))
+
+
+def next_weights(logits: np.ndarray, q: Optional[np.ndarray], n_acc: int, T: float) -> np.ndarray:
+    """Weights the next token is drawn from after n_acc accepted candidates (T > 0)."""
+    logits = _f32(logits)
+    gamma, V = logits.shape[0] - 1, logits.shape[1]
+    qq = _f32(q) if (q is not None and gamma > 0) else None
+    w = np.empty(V, dtype=np.float64)
+    _load().orc_next_weights(V, gamma, float(T), _p(logits), _p(qq), int(n_acc), _p(w))
+    return w
+
+
+def cdf_distance(w: np.ndarray, u: float, k: int) -> float:
+    """Distance of u from token k's inverse-CDF interval, as a fraction of the mass."""
+    w = np.ascontiguousarray(w, dtype=np.float64)
+    return float(_load().orc_cdf_distance(_p(w), w.shape[0], float(u), int(k)))

@@ -384,6 +384,42 @@ int orc_forward(const orc_model *m, orc_seq *s, const int32_t *tokens, int n_row
     return 0;
 }
 
+/* Weights the next token is drawn from after n_acc accepted candidates (T > 0):
+ * the residual max(0, p - q) of the rejected position, or p itself when every
+ * candidate was accepted or the residual is numerically empty. */
+void orc_next_weights(int V, int gamma, double T, const float *logits, const float *q, int n_acc, double *w)
+{
+    float *p = (float *)malloc(sizeof(float) * (size_t)V);
+    orc_softmax_T(logits + (size_t)n_acc * V, V, T, p);
+    double Z = 0.0;
+    if (n_acc < gamma) {
+        const float *qj = q + (size_t)n_acc * V;
+        for (int x = 0; x < V; x++) {
+            double r = (double)p[x] - (double)qj[x];
+            w[x] = r > 0.0 ? r : 0.0;
+            Z += w[x];
+        }
+    }
+    if (!(Z > 0.0))
+        for (int x = 0; x < V; x++) w[x] = (double)p[x];
+    free(p);
+}
+
+/* How far u lies outside token k's interval of the inverse CDF of w, as a
+ * fraction of the total mass (0 when k is the token orc_sample_cdf picks, or u
+ * sits exactly on its edge).  Used to decide whether another implementation's
+ * pick is within rounding of this one's. */
+double orc_cdf_distance(const double *w, int V, double u, int k)
+{
+    double Z = 0.0, lo = 0.0;
+    for (int i = 0; i < V; i++) Z += w[i];
+    for (int i = 0; i < k; i++) lo += w[i];
+    double hi = lo + w[k], target = u * Z;
+    if (target < lo) return (lo - target) / Z;
+    if (target > hi) return (target - hi) / Z;
+    return 0.0;
+}
+
 /* ---------- acceptance rule (Section 3.1; rule restated in the header) ---------- */
 
 /* logits: [(gamma+1)][V] fp32 target logits for rows (pending token, c_1..c_gamma);
@@ -419,19 +455,8 @@ void orc_accept(int V, int gamma, double T, const float *logits, const float *q,
         if (!(u[i] < ratio)) break; /* u in [0,1): min(1, ratio) is implicit */
         n_acc++;
     }
-    orc_softmax_T(logits + (size_t)n_acc * V, V, T, p);
-    double Z = 0.0;
-    if (n_acc < gamma) {
-        const float *qj = q + (size_t)n_acc * V;
-        for (int x = 0; x < V; x++) {
-            double r = (double)p[x] - (double)qj[x];
-            w[x] = r > 0.0 ? r : 0.0;
-            Z += w[x];
-        }
-    }
-    if (!(Z > 0.0)) /* all accepted, or a numerically empty residual: draw from p */
-        for (int x = 0; x < V; x++) w[x] = (double)p[x];
     *n_acc_out = n_acc;
+    orc_next_weights(V, gamma, T, logits, q, n_acc, w);
     *next_out = orc_sample_cdf(w, V, (double)u[gamma], &margins[gamma]);
     free(p);
     free(w);

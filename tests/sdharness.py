@@ -117,8 +117,12 @@ def teacher_forced_parity(pair: Pair, prompt, gamma, T, n_tokens, seed, check_lo
                 first_bad = i
                 break
         if first_bad is not None:
-            mg = s.draft_margins[first_bad]
-            lim = thr if T > 0 else GREEDY_GAP_THR[dtype]
+            if T > 0:  # valid iff u is within thr (in CDF space) of the HIP token's interval
+                mg = oracle.cdf_distance(s.q[first_bad], s.u_draft[first_bad], int(cg[first_bad])) \
+                    if 0 <= cg[first_bad] < V else 1.0
+                lim = thr
+            else:
+                mg, lim = s.draft_margins[first_bad], GREEDY_GAP_THR[dtype]
             assert mg < lim, f"step {k}: draft candidate {first_bad} differs ({cg} vs {s.cand}), margin {mg}"
             flagged = True
         if T > 0:
@@ -138,9 +142,14 @@ def teacher_forced_parity(pair: Pair, prompt, gamma, T, n_tokens, seed, check_lo
             rel = st.merge_logits(lg, s.logits.astype(np.float64))
             assert rel <= LOGIT_TOL[dtype], f"step {k}: logits rel err {rel}"
         if (na, nx) != (s.n_acc, s.next_token):
-            examined = s.verify_margins[:min(s.n_acc, na) + 1] if na != s.n_acc else s.verify_margins[gamma:]
-            mg = float(np.min(examined))
             lim = thr if T > 0 else GREEDY_GAP_THR[dtype]
+            if na != s.n_acc:      # the accept test (or argmax match) at the first differing position
+                mg = float(s.verify_margins[min(s.n_acc, na)])
+            elif T > 0:            # same prefix, other next token: must be within thr in CDF space
+                w = oracle.next_weights(s.logits, s.q, s.n_acc, T)
+                mg = oracle.cdf_distance(w, s.u_verify[gamma], nx) if 0 <= nx < V else 1.0
+            else:
+                mg = float(s.verify_margins[gamma])
             assert mg < lim, (f"step {k}: verify differs: gpu ({na},{nx}) oracle ({s.n_acc},{s.next_token}), "
                               f"margins {s.verify_margins}")
             flagged = True

@@ -52,7 +52,9 @@ def test_config1_tiny_fp32_free_running(tiny_pair, T):
     prompt = dg.make_prompt(11, 1, 32, TINY_T.vocab)
     toks, steps, _ = H.oracle_trajectory(tiny_pair, prompt, 4, T, 64, seed=21, keep_logits=False)
     got, n_steps, n_acc = H.free_running(tiny_pair, prompt, 4, T, 64, seed=21)
-    thr = H.MARGIN_THR[dg.FP32] if T > 0 else H.GREEDY_GAP_THR[dg.FP32]
+    # fp32 inverse-CDF sums differ from the oracle's fp64 ones by ~1e-7 of the mass; a step whose
+    # margin is above 2e-6 cannot legitimately differ
+    thr = 2e-6 if T > 0 else H.GREEDY_GAP_THR[dg.FP32]
     safe = 0
     for s in steps:
         if min(s.draft_margins.min(), s.verify_margins.min()) < thr:

@@ -278,3 +278,21 @@ def test_route_is_argmax_of_linear_scores():
     np.testing.assert_array_equal(oracle.route(W, b, e), ref)
     # ties go to the lowest id
     assert oracle.route(np.ones((3, 2)), np.zeros(3), np.ones((1, 2)))[0] == 0
+
+
+def test_cdf_distance_and_next_weights():
+    w = np.array([0.25, 0.25, 0.0, 0.5])
+    assert oracle.cdf_distance(w, 0.3, 1) == 0.0
+    assert abs(oracle.cdf_distance(w, 0.3, 0) - 0.05) < 1e-12
+    assert abs(oracle.cdf_distance(w, 0.3, 3) - 0.2) < 1e-12
+    assert oracle.cdf_distance(w, 0.5, 1) == 0.0 and oracle.cdf_distance(w, 0.5, 3) == 0.0  # on the edge
+    rng = np.random.default_rng(8)
+    logits = (rng.standard_normal((3, 12)) * 2).astype(np.float32)
+    q = scipy.special.softmax(rng.standard_normal((2, 12)), axis=1).astype(np.float32)
+    p = scipy.special.softmax(logits.astype(np.float64) / 0.7, axis=1)
+    np.testing.assert_allclose(oracle.next_weights(logits, q, 1, 0.7), np.maximum(p[1] - q[1], 0), atol=1e-7)
+    np.testing.assert_allclose(oracle.next_weights(logits, q, 2, 0.7), p[2], atol=1e-7)
+    for u in (0.1, 0.6, 0.95):   # the token the rule picks is the one at distance 0
+        na, nx, _ = oracle.accept(logits, q, [0, 1], np.array([0.999999, 0.0, u], np.float32), 0.7)
+        if na == 0:
+            assert oracle.cdf_distance(oracle.next_weights(logits, q, 0, 0.7), u, nx) == 0.0
