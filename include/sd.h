@@ -181,8 +181,14 @@ int sd_ctx_truncate(sd_ctx *c, sd_model *m, int32_t seq, int32_t len);
 /* Copy the fp32 logits [rows][vocab] of model m's last forward into out (dev,
  * room for max_rows rows); *rows = rows copied. */
 int sd_last_logits(sd_model *m, float *out, int32_t max_rows, int32_t *rows);
-/* option "force_generic" = 1 routes every op through the simple reference kernels. */
+/* option "force_generic" = 1 routes every op through the simple reference kernels.
+ * option "profile" = 1 starts bracketing every kernel launch of the forward with HIP
+ * events on its stream (a measurement mode: it adds event overhead), 0 stops. */
 int sd_set_option(const char *name, int32_t value);
+/* Per-kernel-class totals gathered under option "profile": idx = 0,1,.. until
+ * SD_EINVAL; *name is a static string, *count launches, *total_ms their summed
+ * event-to-event duration.  Synchronises on the recorded events. */
+int sd_profile_read(int32_t idx, const char **name, int32_t *count, float *total_ms);
 
 const char *sd_last_error(void);
 

@@ -22,7 +22,7 @@ SD_FP32, SD_BF16 = 0, 1
 
 EXPORTS = ["sd_load_model", "sd_free_model", "sd_ctx_create", "sd_ctx_free", "sd_ctx_attach", "sd_ctx_set_tokens",
            "sd_prefill", "sd_draft", "sd_verify", "sd_commit", "sd_route", "sd_ctx_sync", "sd_ctx_get_tokens",
-           "sd_ctx_set_kv", "sd_ctx_truncate", "sd_last_logits", "sd_set_option", "sd_last_error"]
+           "sd_ctx_set_kv", "sd_ctx_truncate", "sd_last_logits", "sd_set_option", "sd_profile_read", "sd_last_error"]
 
 
 class SdError(RuntimeError):
@@ -69,6 +69,7 @@ def lib():
         L.sd_ctx_truncate.argtypes = [vp, vp, i32, i32]
         L.sd_last_logits.argtypes = [vp, vp, i32, C.POINTER(i32)]
         L.sd_set_option.argtypes = [C.c_char_p, i32]
+        L.sd_profile_read.argtypes = [i32, C.POINTER(C.c_char_p), C.POINTER(i32), C.POINTER(C.c_float)]
         L.sd_last_error.restype = C.c_char_p
         _lib = L
     return _lib
@@ -97,6 +98,19 @@ def _np_i32(a) -> np.ndarray:
 
 def set_option(name: str, value: int) -> None:
     _check(lib().sd_set_option(name.encode(), int(value)))
+
+
+def profile_read() -> Dict[str, tuple]:
+    """{kernel class: (launches, total ms)} gathered under set_option("profile", 1)."""
+    out = {}
+    i = 0
+    while True:
+        name, cnt, ms = C.c_char_p(), C.c_int32(), C.c_float()
+        if lib().sd_profile_read(i, C.byref(name), C.byref(cnt), C.byref(ms)) != SD_OK:
+            break
+        out[name.value.decode()] = (cnt.value, ms.value)
+        i += 1
+    return out
 
 
 def to_device(a: np.ndarray, device="cuda") -> torch.Tensor:

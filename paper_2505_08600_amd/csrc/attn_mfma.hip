@@ -1,0 +1,231 @@
+// bf16 multi-query-token decode attention on the matrix cores.
+//
+// For each (sequence, head) the R <= 16 new query rows (gamma+1 in verify, 1-2 in
+// draft steps, up to 16 in prefill chunks) attend to the cached keys/values plus
+// the rows appended in this forward, with a causal mask over the new positions:
+// query row i sees cache rows [0, kv0 + i].  The work is streaming K and V once
+// from HBM; the query rows ride along as one 16-wide MFMA operand, so the cost per
+// cached token does not depend on gamma.
+//
+// Layout trick: scores are produced transposed, S^T[token][q] = K . Q^T, with the
+// 16 rows of each K operand tile permuted (tile a: tokens 8*(i/4) + i%4, tile b:
+// the same + 4).  The MFMA result then leaves every lane holding 8 consecutive
+// tokens of one query row - exactly the operand layout of the second product
+// O^T[d][q] = V^T[d][tokens] . P^T[tokens][q], whose V^T operand is a plain 16-byte
+// load from the transposed value cache.  No LDS, no shuffles between the two MFMAs.
+// Probabilities are split into a bf16 high and low part (two MFMAs) so that P.V
+// carries ~16 mantissa bits; the softmax statistics stay in fp32.
+//
+// The KV range is split over blocks (flash-decoding style) and over the 4 waves
+// of a block; partial (max, sum, O) triples are merged in LDS and, if there are
+// several splits, by a small combine kernel.
+//
+// Paper (arXiv 2505.08600): Section 1, Figure 1b (parallel verification of the
+// gamma candidates) and Figure 1a (draft steps).
+#include "sd_internal.h"
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+#define AT_WAVES 4
+#define AT_TILE 32
+#define AT_NEG (-1.0e30f)
+
+union Pack8 {
+    bf16x8 v;
+    uint16_t u[8];
+};
+
+template <int HD>
+__global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restrict__ qbuf,
+                                                        const uint16_t *__restrict__ Kl,
+                                                        const uint16_t *__restrict__ Vtl, PlanView pv, CtxView cv,
+                                                        int R, int H, int64_t total_cap, int S,
+                                                        float *__restrict__ part, uint16_t *__restrict__ obuf)
+{
+    constexpr int NC = HD / 32; // 32-wide chunks of the head dimension (QK^T contraction)
+    constexpr int ND = HD / 16; // 16-row tiles of V^T / O^T
+    __shared__ float sO[AT_WAVES][ND][64][4];
+    __shared__ float sM[AT_WAVES][16], sL[AT_WAVES][16];
+    const int s = blockIdx.x, h = blockIdx.y, j = blockIdx.z;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int qi = lane & 15, grp = lane >> 4;
+    const int nq = pv.seq_nq[j], kv0 = pv.seq_kv0[j];
+    const int Lk = kv0 + nq;
+    const int64_t off = cv.off[pv.seq_b[j]];
+    const int HDm = H * HD;
+    const uint16_t *K = Kl + ((size_t)h * total_cap + off) * HD;
+    const uint16_t *Vt = Vtl + (size_t)h * HD * total_cap + off;
+    // this block's tile range
+    const int n_tiles = nq > 0 ? (Lk + AT_TILE - 1) / AT_TILE : 0; // nothing to do for unused sequences
+    const int per = (n_tiles + S - 1) / S;
+    const int t_begin = s * per, t_end = min(n_tiles, t_begin + per);
+    // Q^T operand: lane (q, grp) holds Q[q][grp*(HD/4) + c*8 .. +8], matching the K loads below
+    bf16x8 qv[NC];
+    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int c = 0; c < NC; c++) {
+        const bf16x8 *p = (const bf16x8 *)(qbuf + (size_t)(j * R + (qi < R ? qi : 0)) * HDm + h * HD + grp * (HD / 4) + c * 8);
+        qv[c] = qi < nq ? *p : zero;
+    }
+    const float scale = 1.0f / sqrtf((float)HD);
+    const int vis = kv0 + qi; // last visible token of this lane's query row
+    float m_run = AT_NEG, l_run = 0.f;
+    f32x4 o[ND];
+#pragma unroll
+    for (int d = 0; d < ND; d++) o[d] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    // K operand rows: lane row i holds token 8*(i/4) + i%4 (tile a) or that + 4 (tile b)
+    const int krow = 8 * (qi >> 2) + (qi & 3);
+    for (int t = t_begin + wave; t < t_end; t += AT_WAVES) {
+        const int t0 = t * AT_TILE;
+        bf16x8 ka[NC], kb[NC], vv[ND];
+        const uint16_t *kpa = K + (size_t)(t0 + krow) * HD + grp * (HD / 4);
+        const uint16_t *kpb = kpa + 4 * HD;
+#pragma unroll
+        for (int c = 0; c < NC; c++) {
+            ka[c] = *(const bf16x8 *)(kpa + c * 8);
+            kb[c] = *(const bf16x8 *)(kpb + c * 8);
+        }
+#pragma unroll
+        for (int d = 0; d < ND; d++) vv[d] = *(const bf16x8 *)(Vt + (size_t)(d * 16 + qi) * total_cap + t0 + grp * 8);
+        f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < NC; c++) {
+            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[c], qv[c], sa, 0, 0, 0);
+            sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[c], qv[c], sb, 0, 0, 0);
+        }
+        // lane (q, grp) now holds scores of tokens t0 + 8*grp + e, e = 0..7 (sa: e<4, sb: e>=4)
+        float sc[8];
+        float mx = AT_NEG;
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+            float v = (e < 4 ? sa[e] : sb[e - 4]) * scale;
+            int tok = t0 + 8 * grp + e;
+            v = tok <= vis ? v : AT_NEG;
+            sc[e] = v;
+            mx = fmaxf(mx, v);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run, mx);
+        const float corr = expf(m_run - m_new); // 1 when nothing changed, 0 from the initial state
+        Pack8 ph, pl;
+        float psum = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+            float p = sc[e] > 0.5f * AT_NEG ? expf(sc[e] - m_new) : 0.f;
+            psum += p;
+            uint16_t hi = bf16_bits_rne(p);
+            float rem = p - __uint_as_float((uint32_t)hi << 16);
+            ph.u[e] = hi;
+            pl.u[e] = bf16_bits_rne(rem);
+        }
+        l_run = l_run * corr + psum;
+        m_run = m_new;
+#pragma unroll
+        for (int d = 0; d < ND; d++) {
+            f32x4 acc = o[d];
+            acc[0] *= corr;
+            acc[1] *= corr;
+            acc[2] *= corr;
+            acc[3] *= corr;
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv[d], ph.v, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv[d], pl.v, acc, 0, 0, 0);
+            o[d] = acc;
+        }
+    }
+    // row sums were kept per k-group: finish them
+    l_run += __shfl_xor(l_run, 16, 64);
+    l_run += __shfl_xor(l_run, 32, 64);
+#pragma unroll
+    for (int d = 0; d < ND; d++)
+#pragma unroll
+        for (int r = 0; r < 4; r++) sO[wave][d][lane][r] = o[d][r];
+    if (grp == 0) {
+        sM[wave][qi] = m_run;
+        sL[wave][qi] = l_run;
+    }
+    __syncthreads();
+    // merge the 4 waves: element (d, slot, r) is O^T[dim = 16*d + 4*(slot/16) + r][q = slot%16]
+    for (int e = threadIdx.x; e < ND * 256; e += 256) {
+        const int d = e >> 8, slot = (e >> 2) & 63, r = e & 3;
+        const int q = slot & 15, dim = 16 * d + 4 * (slot >> 4) + r;
+        float M = AT_NEG;
+#pragma unroll
+        for (int w = 0; w < AT_WAVES; w++) M = fmaxf(M, sM[w][q]);
+        float O = 0.f, L = 0.f;
+#pragma unroll
+        for (int w = 0; w < AT_WAVES; w++) {
+            float f = expf(sM[w][q] - M);
+            O += sO[w][d][slot][r] * f;
+            L += sL[w][q] * f;
+        }
+        if (q >= R) continue;
+        if (S == 1) {
+            float out = (q < nq && L > 0.f) ? O / L : 0.f;
+            obuf[(size_t)(j * R + q) * HDm + h * HD + dim] = bf16_bits_rne(out);
+        } else {
+            float *pp = part + ((size_t)(j * H + h) * S + s) * 16 * (HD + 2);
+            pp[q * HD + dim] = O;
+            if (dim == 0) {
+                pp[16 * HD + q] = M;
+                pp[16 * HD + 16 + q] = L;
+            }
+        }
+    }
+}
+
+// Merge the S split partials of each (sequence, head): one block per (head, sequence).
+template <int HD>
+__global__ void attn_combine_kernel(const float *__restrict__ part, PlanView pv, int R, int H, int S,
+                                    uint16_t *__restrict__ obuf)
+{
+    const int h = blockIdx.x, j = blockIdx.y;
+    const int nq = pv.seq_nq[j];
+    const float *base = part + (size_t)(j * H + h) * S * 16 * (HD + 2);
+    for (int e = threadIdx.x; e < R * HD; e += blockDim.x) {
+        const int q = e / HD, dim = e % HD;
+        float M = AT_NEG;
+        for (int s = 0; s < S; s++) M = fmaxf(M, base[(size_t)s * 16 * (HD + 2) + 16 * HD + q]);
+        float O = 0.f, L = 0.f;
+        for (int s = 0; s < S; s++) {
+            const float *pp = base + (size_t)s * 16 * (HD + 2);
+            float f = expf(pp[16 * HD + q] - M);
+            O += pp[q * HD + dim] * f;
+            L += pp[16 * HD + 16 + q] * f;
+        }
+        float out = (q < nq && L > 0.f) ? O / L : 0.f;
+        obuf[(size_t)(j * R + q) * (H * HD) + h * HD + dim] = bf16_bits_rne(out);
+    }
+}
+
+hipError_t launch_attn_mfma_bf16(hipStream_t s, const void *qbuf, const void *Kl, const void *Vtl, PlanView pv,
+                                 CtxView cv, int R, int n_seq, int H, int hd, int64_t total_cap, int len_upper,
+                                 float *part, size_t part_floats, void *obuf)
+{
+    if (R < 1 || R > 16 || (hd != 64 && hd != 128)) return hipErrorNotSupported;
+    if (n_seq > 65535 || H > 65535) return hipErrorNotSupported;
+    int tiles_upper = (len_upper + AT_TILE - 1) / AT_TILE;
+    int S = (tiles_upper + AT_WAVES - 1) / AT_WAVES;                  // at least one tile per wave
+    int want = (512 + n_seq * H - 1) / (n_seq * H);                   // enough blocks to fill the chip
+    if (S > want) S = want;
+    if (S > SD_ATTN_MAX_SPLITS) S = SD_ATTN_MAX_SPLITS;
+    while (S > 1 && (size_t)n_seq * H * S * 16 * (hd + 2) > part_floats) S--;
+    if (S < 1) S = 1;
+    dim3 grid(S, H, n_seq), block(256);
+    if (hd == 128)
+        hipLaunchKernelGGL(attn_mfma_kernel<128>, grid, block, 0, s, (const uint16_t *)qbuf, (const uint16_t *)Kl,
+                           (const uint16_t *)Vtl, pv, cv, R, H, total_cap, S, part, (uint16_t *)obuf);
+    else
+        hipLaunchKernelGGL(attn_mfma_kernel<64>, grid, block, 0, s, (const uint16_t *)qbuf, (const uint16_t *)Kl,
+                           (const uint16_t *)Vtl, pv, cv, R, H, total_cap, S, part, (uint16_t *)obuf);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || S == 1) return e;
+    if (hd == 128)
+        hipLaunchKernelGGL(attn_combine_kernel<128>, dim3(H, n_seq), dim3(256), 0, s, part, pv, R, H, S,
+                           (uint16_t *)obuf);
+    else
+        hipLaunchKernelGGL(attn_combine_kernel<64>, dim3(H, n_seq), dim3(256), 0, s, part, pv, R, H, S,
+                           (uint16_t *)obuf);
+    return hipGetLastError();
+}

