@@ -1,0 +1,227 @@
+#!/usr/bin/env python3
+"""Benchmark of the draft-then-verify step on one MI355X.
+
+Workload (BASELINE config 2): 7B-shape bf16 target (32 layers, d 4096, 32 heads,
+FFN 11008, vocab 32000) with the 68M-shape draft (2 layers, d 768), batch 1,
+prompt of 512 uniform tokens, gamma = 5, T = 1, random N(0, 0.02) weights.
+A "step" is one pass of the whole hot path: sd_draft (gamma candidates) followed
+by sd_verify (gamma+1 rows, accept/resample, commit).  Inputs (weights, prompt,
+uniforms, KV cache of the prefilled prompt) are resident in HBM before the timed
+region starts.
+
+Prints ONE JSON line.  `value` is verified candidate tokens per second over the
+whole step, B*gamma*K / t.  `roofline` is for the dominant kernel (the SwiGLU
+gate/up weight-streaming GEMM), timed live with HIP events on the launch stream in
+a separate pass; `cpu_baseline` times the CPU oracle on one step of the same shape.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--layers", type=int, default=0, help="debug: reduce target depth (invalidates the number)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--temperature", type=float, default=1.0)
+    ap.add_argument("--prompt", type=int, default=512)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (sequences are independent; "
+              "see DESIGN.md for how it would shard). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2505_08600_amd import api
+    from paper_2505_08600_amd import datagen as dg
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    api.lib()
+    seed, gamma, T, B = 2025, 5, float(args.temperature), 1
+    st = dg.SHAPES["t7b"] if not args.layers else dg.with_layers(dg.SHAPES["t7b"], args.layers)
+    sd_ = dg.SHAPES["draft_a"]
+    V = st.vocab
+    K, W = args.steps, args.warmup
+    n_total = K + W + 8
+    cap = args.prompt + n_total * (gamma + 1) + 16
+
+    t0 = time.time()
+    wt = dg.make_weights(st, seed, threads=16)
+    wd = dg.make_weights(sd_, seed + 1, threads=16)
+    log(f"[bench] weights generated on host in {time.time() - t0:.1f}s")
+    t0 = time.time()
+    gt = api.Model(st, wt, max_rows=16, max_pos=cap + 64)
+    gd = api.Model(sd_, wd, max_rows=16, max_pos=cap + 64)
+    torch.cuda.synchronize()
+    log(f"[bench] uploaded in {time.time() - t0:.1f}s")
+
+    prompt = [int(t) for t in dg.make_prompt(seed, 0, args.prompt, V)]
+    ctx = api.Context([cap])
+    ctx.attach(gt)
+    ctx.attach(gd)
+    ctx.set_tokens([prompt])
+    t0 = time.time()
+    api.sd_prefill(gt, ctx, None, 1, len(prompt) - 1)
+    api.sd_prefill(gd, ctx, None, 1, len(prompt) - 1)
+    torch.cuda.synchronize()
+    log(f"[bench] prefill of {len(prompt)} tokens: {time.time() - t0:.2f}s")
+
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    ud = [dev(dg.make_uniforms(seed, dg.DRAFT_STREAM, 0, k, gamma)[None]) for k in range(n_total)]
+    uv = [dev(dg.make_uniforms(seed, dg.VERIFY_STREAM, 0, k, gamma + 1)[None]) for k in range(n_total)]
+    cand = torch.zeros((B, gamma), dtype=torch.int32, device="cuda")
+    q = torch.zeros((B, gamma, V), dtype=torch.float32, device="cuda")
+    na = torch.zeros(B, dtype=torch.int32, device="cuda")
+    nx = torch.zeros(B, dtype=torch.int32, device="cuda")
+    na_log = torch.zeros((n_total, B), dtype=torch.int32, device="cuda")
+
+    def step(k):
+        api.sd_draft(gd, ctx, None, B, gamma, T, ud[k] if T > 0 else None, cand, q if T > 0 else None)
+        api.sd_verify(gt, ctx, None, B, gamma, T, cand, q if T > 0 else None, uv[k] if T > 0 else None, na, nx, True)
+        na_log[k].copy_(na)
+
+    for k in range(W):
+        step(k)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(W, W + K):
+        step(k)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / K * 1e3
+    n_acc = na_log[W:W + K, 0].cpu().numpy()
+    ctx.sync()  # raises if a kernel flagged an inconsistency
+
+    # ---- phase split: draft-only and verify-only timings (same state machine, separate loops)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = min(K, 20)
+    t_draft = t_verify = 0.0
+    for k in range(W + K, W + K + 4):
+        ev0.record()
+        api.sd_draft(gd, ctx, None, B, gamma, T, ud[k] if T > 0 else None, cand, q if T > 0 else None)
+        ev1.record()
+        torch.cuda.synchronize()
+        t_draft += ev0.elapsed_time(ev1)
+        ev0.record()
+        api.sd_verify(gt, ctx, None, B, gamma, T, cand, q if T > 0 else None, uv[k] if T > 0 else None, na, nx, True)
+        ev1.record()
+        torch.cuda.synchronize()
+        t_verify += ev0.elapsed_time(ev1)
+    t_draft /= 4
+    t_verify /= 4
+
+    # ---- per-kernel pass with HIP events on the launch stream (library option "profile")
+    api.set_option("profile", 1)
+    for k in range(W + K + 4, W + K + 8):
+        step(k)
+    torch.cuda.synchronize()
+    api.set_option("profile", 0)
+    prof = api.profile_read()
+    ctx.sync()
+    # dominant kernel: SwiGLU gate/up GEMM of the target.  Algorithmic bytes per launch: both weight
+    # matrices once (2*F*d bf16) + the M input rows (M*d bf16) + the M output rows (M*F bf16).
+    M = B * (gamma + 1)
+    gu_bytes = 2 * st.d_ffn * st.d_model * 2 + M * st.d_model * 2 + M * st.d_ffn * 2
+    # gate/up launches of the profile pass: 4 verify forwards (target) + 4*gamma draft forwards; split by
+    # model via launch counts (the draft has 2 layers, the target n_layers)
+    cnt, tot_ms = prof["gemm_gateup"]
+    # weight the classes by bytes: draft launches are ~50x smaller; report the target's kernel only by
+    # timing it in isolation below
+    api.set_option("profile", 1)
+    for k in range(3):
+        api.sd_verify(gt, ctx, None, B, gamma, T, cand, q if T > 0 else None, uv[k] if T > 0 else None, na, nx, False)
+        torch.cuda.synchronize()
+        ctx.truncate(gt, 0, int(ctx.sync()[0][0]) - 1)
+    api.set_option("profile", 0)
+    vprof = api.profile_read()
+    gcnt, gms = vprof["gemm_gateup"]
+    gu_ms = gms / max(gcnt, 1)
+    achieved = gu_bytes / (gu_ms * 1e-3) / 1e9
+    # whole verify call against its own algorithmic traffic
+    n_ctx = int(ctx.sync()[0][0])
+    verify_bytes = st.n_streamed_params() * 2 + st.kv_bytes_per_token() * n_ctx
+    verify_frac = verify_bytes / (t_verify * 1e-3) / 1e9 / HBM_PEAK_GBS
+
+    tau = float(np.mean(n_acc + 1))
+    examined = np.where(n_acc < gamma, n_acc + 1, gamma).sum()
+    alpha_hat = float(n_acc.sum() / max(examined, 1))
+    c_ratio = (t_draft / gamma) / t_verify
+    eq1 = ((1 - alpha_hat ** (gamma + 1)) / (1 - alpha_hat) if alpha_hat < 1 else gamma + 1) / (gamma * c_ratio + 1)
+
+    out = {
+        "metric": "verified candidate tokens/s + accepted tokens/s, 7B-shape target, gamma=5, batch 1",
+        "value": B * gamma * K / dt,
+        "unit": "candidate tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "config 2: 7B-shape target + 68M-shape draft, batch 1, prompt %d, gamma 5, T=%g"
+                               % (args.prompt, T),
+                   "target_layers": st.n_layers, "batch": B, "gamma": gamma, "temperature": T},
+        "emitted_tokens_per_s": float((n_acc + 1).sum() / dt),
+        "accepted_tokens_per_s": float(n_acc.sum() / dt),
+        "verify_only_candidates_per_s": B * gamma / (t_verify * 1e-3),
+        "ms_draft": t_draft, "ms_verify": t_verify,
+        "acceptance_rate_eq2": float(n_acc.sum() / (K * gamma)), "tau": tau, "alpha_hat": alpha_hat,
+        "c_draft_over_target": c_ratio, "eq1_speedup_model": eq1,
+        "verify_hbm_frac": verify_frac,
+        "roofline": {"bound": "hbm", "kernel": "gemm_skinny_kernel<SwiGLU gate/up> M=%d N=%d K=%d" % (M, st.d_ffn, st.d_model),
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None, "us_per_launch": gu_ms * 1e3, "algorithmic_bytes": gu_bytes},
+        "kernel_ms_per_verify": {k: v[1] / 3.0 for k, v in vprof.items() if v[0]},
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(st, sd_, wt, wd, args.prompt, gamma, T, seed)
+    print(json.dumps(out))
+
+
+def cpu_baseline(st, sd_, wt, wd, n_ctx, gamma, T, seed):
+    """Time the CPU oracle (as it stands) on ONE draft+verify step of the same shapes, with the
+    caches holding synthetic rows for the n_ctx-token context (filling them by the oracle's own
+    prefill would take minutes)."""
+    import numpy as np
+
+    import oracle
+    from paper_2505_08600_amd import datagen as dg
+
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    ot, od = oracle.OracleModel(st, wt), oracle.OracleModel(sd_, wd)
+    tseq, dseq = ot.new_seq(n_ctx + 16), od.new_seq(n_ctx + 16)
+    for m, seq, shp in ((ot, tseq, st), (od, dseq, sd_)):
+        for l in range(shp.n_layers):
+            k, v = dg.make_kv_rows(seed, l, 0, n_ctx - 1, shp.n_heads, shp.head_dim, shp.dtype)
+            seq.set_kv(l, k, v)
+    ctx_t = [int(t) for t in dg.make_prompt(seed, 0, n_ctx, st.vocab)]
+    ud = dg.make_uniforms(seed, dg.DRAFT_STREAM, 0, 0, gamma)
+    uv = dg.make_uniforms(seed, dg.VERIFY_STREAM, 0, 0, gamma + 1)
+    t0 = time.perf_counter()
+    cand, q, _ = dseq.draft(ctx_t, gamma, T, ud)
+    t1 = time.perf_counter()
+    tseq.verify(ctx_t, gamma, T, cand, q, uv)
+    t2 = time.perf_counter()
+    return {"value": gamma / (t2 - t0), "unit": "candidate tokens/s", "cores": threads, "kind": "oracle",
+            "sample": "one draft+verify step (gamma=5, batch 1) at context %d with synthetic cache rows, "
+                      "%d target layers; draft %.2fs, verify %.2fs" % (n_ctx, st.n_layers, t1 - t0, t2 - t1)}
+
+
+if __name__ == "__main__":
+    main()

@@ -181,6 +181,10 @@ int sd_ctx_truncate(sd_ctx *c, sd_model *m, int32_t seq, int32_t len);
 /* Copy the fp32 logits [rows][vocab] of model m's last forward into out (dev,
  * room for max_rows rows); *rows = rows copied. */
 int sd_last_logits(sd_model *m, float *out, int32_t max_rows, int32_t *rows);
+/* Copy one activation buffer of model m's last forward to out (HOST, fp32): name is
+ * "x" (residual [rows][d_model]), "qkv" ([rows][3*d_model]), "q", "o", "a"
+ * ([rows][d_model]) or "act" ([rows][d_ffn]).  Synchronises. */
+int sd_debug_read(sd_model *m, const char *name, float *out, int32_t rows);
 /* option "force_generic" = 1 routes every op through the simple reference kernels.
  * option "profile" = 1 starts bracketing every kernel launch of the forward with HIP
  * events on its stream (a measurement mode: it adds event overhead), 0 stops. */

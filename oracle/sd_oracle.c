@@ -21,9 +21,15 @@
  *
  * Numeric contract (the paper states no precision; this is this build's reading):
  *   fp32 models: weights, KV cache and GEMM inputs are fp32 values.
- *   bf16 models: weights, embedding table, KV cache and every GEMM input
- *   activation (normed hidden, rotated q, attention output, SwiGLU product) are
- *   bf16 values (round-to-nearest-even from fp32); everything else is wider.
+ *   bf16 models: weights, embedding table and KV cache are bf16 values (round to
+ *   nearest even from fp32).  Every activation that enters a contraction (normed
+ *   hidden, rotated q, attention output, SwiGLU product) is the sum of two bf16
+ *   terms, hi = bf16(x), lo = bf16(x - hi): about 16 mantissa bits, so that two
+ *   implementations that add in different orders do not drift apart through
+ *   differing roundings (with single bf16 activations the drift between two
+ *   correct implementations was measured at 2.8e-2 of the logit range over 32
+ *   layers - outside the 2e-2 tolerance and far outside a 1e-3 decision band).
+ *   Everything else is wider.
  *   Between those rounding points this oracle computes in fp64.  Logits leave as
  *   fp32 and are never rounded to bf16.  Decisions (accept test, argmax) are taken
  *   on fp32 logits / probabilities, the precision the kernels decide in.
@@ -92,11 +98,23 @@ static float round_to_bf16(float f)
 /* Exported for the rounding pin. */
 float orc_round_bf16(float f) { return round_to_bf16(f); }
 
-/* Value as stored in a GEMM input buffer / KV cache of a model of this dtype. */
+/* Value as stored in the KV cache of a model of this dtype. */
 static double round_storage(double x, int dtype)
 {
     float f = (float)x;
     return dtype == ORC_BF16 ? (double)round_to_bf16(f) : (double)f;
+}
+
+/* Value of a GEMM / attention input activation.  fp32 models: the fp32 value.
+ * bf16 models: the sum of two bf16 terms, hi = bf16(x) and lo = bf16(x - hi),
+ * i.e. about 16 mantissa bits, each term a bf16 operand of the matrix cores. */
+static double round_act(double x, int dtype)
+{
+    float f = (float)x;
+    if (dtype != ORC_BF16) return (double)f;
+    float hi = round_to_bf16(f);
+    float lo = round_to_bf16(f - hi);
+    return (double)hi + (double)lo;
 }
 
 static double weight_at(const void *w, int dtype, size_t i)
@@ -323,10 +341,10 @@ int orc_forward(const orc_model *m, orc_seq *s, const int32_t *tokens, int n_row
         for (int r = 0; r < n_rows; r++) {
             int pos = s->len + r;
             orc_rmsnorm(h + (size_t)r * d, m->norm_attn[l], d, c->rms_eps, a);
-            for (int i = 0; i < d; i++) a[i] = round_storage(a[i], dt);
+            for (int i = 0; i < d; i++) a[i] = round_act(a[i], dt);
             matvec(m->wq[l], dt, HD, d, a, tmp);
             for (int hh = 0; hh < H; hh++) orc_rope(tmp + hh * hd, hd, pos, c->rope_base);
-            for (int i = 0; i < HD; i++) qb[(size_t)r * HD + i] = round_storage(tmp[i], dt);
+            for (int i = 0; i < HD; i++) qb[(size_t)r * HD + i] = round_act(tmp[i], dt);
             matvec(m->wk[l], dt, HD, d, a, tmp);
             for (int hh = 0; hh < H; hh++) orc_rope(tmp + hh * hd, hd, pos, c->rope_base);
             for (int i = 0; i < HD; i++) Kc[(size_t)pos * HD + i] = (float)round_storage(tmp[i], dt);
@@ -353,7 +371,7 @@ int orc_forward(const orc_model *m, orc_seq *s, const int32_t *tokens, int n_row
                 for (int i = 0; i < hd; i++) {
                     double acc = 0.0;
                     for (int t = 0; t <= pos; t++) acc += sc[t] * (double)Vc[(size_t)t * HD + hh * hd + i];
-                    ob[hh * hd + i] = round_storage(acc / z, dt);
+                    ob[hh * hd + i] = round_act(acc / z, dt);
                 }
             }
             matvec(m->wo[l], dt, d, HD, ob, y);
@@ -361,12 +379,12 @@ int orc_forward(const orc_model *m, orc_seq *s, const int32_t *tokens, int n_row
             for (int i = 0; i < d; i++) hr[i] += y[i];
             /* SwiGLU feed-forward */
             orc_rmsnorm(hr, m->norm_ffn[l], d, c->rms_eps, a);
-            for (int i = 0; i < d; i++) a[i] = round_storage(a[i], dt);
+            for (int i = 0; i < d; i++) a[i] = round_act(a[i], dt);
             matvec(m->wgate[l], dt, F, d, a, tmp);
             matvec(m->wup[l], dt, F, d, a, tmp2);
             for (int i = 0; i < F; i++) {
                 double g = tmp[i];
-                a[i] = round_storage(g / (1.0 + exp(-g)) * tmp2[i], dt);
+                a[i] = round_act(g / (1.0 + exp(-g)) * tmp2[i], dt);
             }
             matvec(m->wdown[l], dt, d, F, a, y);
             for (int i = 0; i < d; i++) hr[i] += y[i];
@@ -374,7 +392,7 @@ int orc_forward(const orc_model *m, orc_seq *s, const int32_t *tokens, int n_row
     }
     for (int r = (logits_from < 0 ? 0 : logits_from); r < n_rows; r++) {
         orc_rmsnorm(h + (size_t)r * d, m->final_norm, d, c->rms_eps, a);
-        for (int i = 0; i < d; i++) a[i] = round_storage(a[i], dt);
+        for (int i = 0; i < d; i++) a[i] = round_act(a[i], dt);
         matvec(m->lm_head, dt, V, d, a, y);
         float *out = logits + (size_t)(r - (logits_from < 0 ? 0 : logits_from)) * V;
         for (int i = 0; i < V; i++) out[i] = (float)y[i];

@@ -22,7 +22,7 @@ SD_FP32, SD_BF16 = 0, 1
 
 EXPORTS = ["sd_load_model", "sd_free_model", "sd_ctx_create", "sd_ctx_free", "sd_ctx_attach", "sd_ctx_set_tokens",
            "sd_prefill", "sd_draft", "sd_verify", "sd_commit", "sd_route", "sd_ctx_sync", "sd_ctx_get_tokens",
-           "sd_ctx_set_kv", "sd_ctx_truncate", "sd_last_logits", "sd_set_option", "sd_profile_read", "sd_last_error"]
+           "sd_ctx_set_kv", "sd_ctx_truncate", "sd_debug_read", "sd_last_logits", "sd_set_option", "sd_profile_read", "sd_last_error"]
 
 
 class SdError(RuntimeError):
@@ -67,6 +67,7 @@ def lib():
         L.sd_ctx_get_tokens.argtypes = [vp, i32, vp, i32, C.POINTER(i32)]
         L.sd_ctx_set_kv.argtypes = [vp, vp, i32, i32, vp, vp, i32]
         L.sd_ctx_truncate.argtypes = [vp, vp, i32, i32]
+        L.sd_debug_read.argtypes = [vp, C.c_char_p, vp, i32]
         L.sd_last_logits.argtypes = [vp, vp, i32, C.POINTER(i32)]
         L.sd_set_option.argtypes = [C.c_char_p, i32]
         L.sd_profile_read.argtypes = [i32, C.POINTER(C.c_char_p), C.POINTER(i32), C.POINTER(C.c_float)]
@@ -155,6 +156,14 @@ class Model:
             self.close()
         except Exception:
             pass
+
+    def debug_read(self, name: str, rows: int) -> np.ndarray:
+        """Host copy (fp32) of a workspace buffer of the last forward: x, qkv, q, o, a, act."""
+        width = {"x": self.shape.d_model, "qkv": 3 * self.shape.d_model, "act": self.shape.d_ffn}.get(
+            name, self.shape.d_model)
+        out = np.empty((rows, width), np.float32)
+        _check(lib().sd_debug_read(self.h, name.encode(), out.ctypes.data_as(C.c_void_p), rows))
+        return out
 
     def last_logits(self) -> torch.Tensor:
         """Copy of the fp32 logits [rows][vocab] of the last forward (synchronises)."""

@@ -13,8 +13,9 @@
 // tokens of one query row - exactly the operand layout of the second product
 // O^T[d][q] = V^T[d][tokens] . P^T[tokens][q], whose V^T operand is a plain 16-byte
 // load from the transposed value cache.  No LDS, no shuffles between the two MFMAs.
-// Probabilities are split into a bf16 high and low part (two MFMAs) so that P.V
-// carries ~16 mantissa bits; the softmax statistics stay in fp32.
+// Queries arrive as two bf16 planes (hi + lo) and probabilities are split the same
+// way, so both products carry ~16 mantissa bits of the activation operand; the
+// softmax statistics stay in fp32.
 //
 // The KV range is split over blocks (flash-decoding style) and over the 4 waves
 // of a block; partial (max, sum, O) triples are merged in LDS and, if there are
@@ -37,11 +38,12 @@ union Pack8 {
 };
 
 template <int HD>
-__global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restrict__ qbuf,
+__global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restrict__ qbuf, size_t q_plane,
                                                         const uint16_t *__restrict__ Kl,
                                                         const uint16_t *__restrict__ Vtl, PlanView pv, CtxView cv,
                                                         int R, int H, int64_t total_cap, int S,
-                                                        float *__restrict__ part, uint16_t *__restrict__ obuf)
+                                                        float *__restrict__ part, uint16_t *__restrict__ obuf,
+                                                        size_t o_plane)
 {
     constexpr int NC = HD / 32; // 32-wide chunks of the head dimension (QK^T contraction)
     constexpr int ND = HD / 16; // 16-row tiles of V^T / O^T
@@ -61,12 +63,13 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restri
     const int per = (n_tiles + S - 1) / S;
     const int t_begin = s * per, t_end = min(n_tiles, t_begin + per);
     // Q^T operand: lane (q, grp) holds Q[q][grp*(HD/4) + c*8 .. +8], matching the K loads below
-    bf16x8 qv[NC];
+    bf16x8 qv[NC], ql[NC];
     const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
     for (int c = 0; c < NC; c++) {
         const bf16x8 *p = (const bf16x8 *)(qbuf + (size_t)(j * R + (qi < R ? qi : 0)) * HDm + h * HD + grp * (HD / 4) + c * 8);
         qv[c] = qi < nq ? *p : zero;
+        ql[c] = qi < nq ? *(const bf16x8 *)((const uint16_t *)p + q_plane) : zero;
     }
     const float scale = 1.0f / sqrtf((float)HD);
     const int vis = kv0 + qi; // last visible token of this lane's query row
@@ -93,6 +96,8 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restri
         for (int c = 0; c < NC; c++) {
             sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[c], qv[c], sa, 0, 0, 0);
             sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[c], qv[c], sb, 0, 0, 0);
+            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[c], ql[c], sa, 0, 0, 0);
+            sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[c], ql[c], sb, 0, 0, 0);
         }
         // lane (q, grp) now holds scores of tokens t0 + 8*grp + e, e = 0..7 (sa: e<4, sb: e>=4)
         float sc[8];
@@ -163,7 +168,10 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restri
         if (q >= R) continue;
         if (S == 1) {
             float out = (q < nq && L > 0.f) ? O / L : 0.f;
-            obuf[(size_t)(j * R + q) * HDm + h * HD + dim] = bf16_bits_rne(out);
+            uint16_t hi = bf16_bits_rne(out);
+            size_t oi = (size_t)(j * R + q) * HDm + h * HD + dim;
+            obuf[oi] = hi;
+            obuf[oi + o_plane] = bf16_bits_rne(out - __uint_as_float((uint32_t)hi << 16));
         } else {
             float *pp = part + ((size_t)(j * H + h) * S + s) * 16 * (HD + 2);
             pp[q * HD + dim] = O;
@@ -178,7 +186,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restri
 // Merge the S split partials of each (sequence, head): one block per (head, sequence).
 template <int HD>
 __global__ void attn_combine_kernel(const float *__restrict__ part, PlanView pv, int R, int H, int S,
-                                    uint16_t *__restrict__ obuf)
+                                    uint16_t *__restrict__ obuf, size_t o_plane)
 {
     const int h = blockIdx.x, j = blockIdx.y;
     const int nq = pv.seq_nq[j];
@@ -195,13 +203,16 @@ __global__ void attn_combine_kernel(const float *__restrict__ part, PlanView pv,
             L += pp[16 * HD + 16 + q] * f;
         }
         float out = (q < nq && L > 0.f) ? O / L : 0.f;
-        obuf[(size_t)(j * R + q) * (H * HD) + h * HD + dim] = bf16_bits_rne(out);
+        uint16_t hi = bf16_bits_rne(out);
+        size_t oi = (size_t)(j * R + q) * (H * HD) + h * HD + dim;
+        obuf[oi] = hi;
+        obuf[oi + o_plane] = bf16_bits_rne(out - __uint_as_float((uint32_t)hi << 16));
     }
 }
 
-hipError_t launch_attn_mfma_bf16(hipStream_t s, const void *qbuf, const void *Kl, const void *Vtl, PlanView pv,
-                                 CtxView cv, int R, int n_seq, int H, int hd, int64_t total_cap, int len_upper,
-                                 float *part, size_t part_floats, void *obuf)
+hipError_t launch_attn_mfma_bf16(hipStream_t s, const void *qbuf, size_t q_plane, const void *Kl, const void *Vtl,
+                                 PlanView pv, CtxView cv, int R, int n_seq, int H, int hd, int64_t total_cap,
+                                 int len_upper, float *part, size_t part_floats, void *obuf, size_t o_plane)
 {
     if (R < 1 || R > 16 || (hd != 64 && hd != 128)) return hipErrorNotSupported;
     if (n_seq > 65535 || H > 65535) return hipErrorNotSupported;
@@ -214,18 +225,20 @@ hipError_t launch_attn_mfma_bf16(hipStream_t s, const void *qbuf, const void *Kl
     if (S < 1) S = 1;
     dim3 grid(S, H, n_seq), block(256);
     if (hd == 128)
-        hipLaunchKernelGGL(attn_mfma_kernel<128>, grid, block, 0, s, (const uint16_t *)qbuf, (const uint16_t *)Kl,
-                           (const uint16_t *)Vtl, pv, cv, R, H, total_cap, S, part, (uint16_t *)obuf);
+        hipLaunchKernelGGL(attn_mfma_kernel<128>, grid, block, 0, s, (const uint16_t *)qbuf, q_plane,
+                           (const uint16_t *)Kl, (const uint16_t *)Vtl, pv, cv, R, H, total_cap, S, part,
+                           (uint16_t *)obuf, o_plane);
     else
-        hipLaunchKernelGGL(attn_mfma_kernel<64>, grid, block, 0, s, (const uint16_t *)qbuf, (const uint16_t *)Kl,
-                           (const uint16_t *)Vtl, pv, cv, R, H, total_cap, S, part, (uint16_t *)obuf);
+        hipLaunchKernelGGL(attn_mfma_kernel<64>, grid, block, 0, s, (const uint16_t *)qbuf, q_plane,
+                           (const uint16_t *)Kl, (const uint16_t *)Vtl, pv, cv, R, H, total_cap, S, part,
+                           (uint16_t *)obuf, o_plane);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || S == 1) return e;
     if (hd == 128)
         hipLaunchKernelGGL(attn_combine_kernel<128>, dim3(H, n_seq), dim3(256), 0, s, part, pv, R, H, S,
-                           (uint16_t *)obuf);
+                           (uint16_t *)obuf, o_plane);
     else
         hipLaunchKernelGGL(attn_combine_kernel<64>, dim3(H, n_seq), dim3(256), 0, s, part, pv, R, H, S,
-                           (uint16_t *)obuf);
+                           (uint16_t *)obuf, o_plane);
     return hipGetLastError();
 }

@@ -14,7 +14,8 @@
 //    k-group l/16); the contraction index is permuted identically for both
 //    operands, which a dot product does not care about;
 //  * the activation operand comes from global memory (L2 hits), masked to the M
-//    real rows;
+//    real rows; activations are two bf16 planes (hi + lo, ~16 mantissa bits), so
+//    every weight fragment is multiplied twice - free while the kernel waits on HBM;
 //  * the partial accumulators of the waves meet in LDS; the epilogue stores, adds
 //    into the fp32 residual stream, or applies silu(gate)*up and rounds to bf16.
 //    The sum order is fixed, so results are bit-reproducible run to run.
@@ -30,9 +31,10 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 // MT: 16-row tiles of A; WAVES: waves per block (in-block split-K); U: K steps in flight per wave
 template <int MT, int MODE, int WAVES, int U>
-__global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const uint16_t *__restrict__ A, WeightSeg w, int M,
-                                                                 int N, int K, float *__restrict__ C,
-                                                                 uint16_t *__restrict__ Cact)
+__global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const uint16_t *__restrict__ A, size_t a_plane,
+                                                                 WeightSeg w, int M, int N, int K,
+                                                                 float *__restrict__ C, uint16_t *__restrict__ Cact,
+                                                                 size_t c_plane)
 {
     constexpr bool DUAL = MODE != GEMM_RESID;
     constexpr int NT = DUAL ? 2 : 1;
@@ -60,7 +62,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const uint16_t 
     const int nsteps = K / SK_KSTEP;
     const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
     for (int s0 = wave * U; s0 < nsteps; s0 += WAVES * U) {
-        bf16x8 wv[U][NT][4], av[U][MT][4];
+        bf16x8 wv[U][NT][4], av[U][MT][4], al[U][MT][4];
 #pragma unroll
         for (int u = 0; u < U; u++) {
             const bool live = s0 + u < nsteps;
@@ -75,8 +77,12 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const uint16_t 
             for (int t = 0; t < MT; t++) {
                 const int m = t * 16 + row;
                 const bf16x8 *pa = (const bf16x8 *)(A + (size_t)(m < M ? m : 0) * K + k);
+                const bf16x8 *pl = (const bf16x8 *)(A + a_plane + (size_t)(m < M ? m : 0) * K + k);
 #pragma unroll
-                for (int i = 0; i < 4; i++) av[u][t][i] = (live && m < M) ? pa[i] : zero;
+                for (int i = 0; i < 4; i++) {
+                    av[u][t][i] = (live && m < M) ? pa[i] : zero;
+                    al[u][t][i] = (live && m < M) ? pl[i] : zero;
+                }
             }
         }
 #pragma unroll
@@ -86,8 +92,10 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const uint16_t 
 #pragma unroll
                 for (int t = 0; t < MT; t++)
 #pragma unroll
-                    for (int c = 0; c < NT; c++)
+                    for (int c = 0; c < NT; c++) {
                         acc[c][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv[u][c][i], av[u][t][i], acc[c][t], 0, 0, 0);
+                        acc[c][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv[u][c][i], al[u][t][i], acc[c][t], 0, 0, 0);
+                    }
     }
 #pragma unroll
     for (int c = 0; c < NT; c++)
@@ -113,7 +121,10 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const uint16_t 
             if (m < M) {
                 if (MODE == GEMM_SWIGLU) {
                     float g = v[0];
-                    Cact[(size_t)m * N + n0 + nn] = bf16_bits_rne(g / (1.0f + expf(-g)) * v[NT - 1]);
+                    float y = g / (1.0f + expf(-g)) * v[NT - 1];
+                    uint16_t hi = bf16_bits_rne(y);
+                    Cact[(size_t)m * N + n0 + nn] = hi;
+                    Cact[c_plane + (size_t)m * N + n0 + nn] = bf16_bits_rne(y - __uint_as_float((uint32_t)hi << 16));
                 } else if (MODE == GEMM_STORE) {
                     C[(size_t)m * N + n0 + nn] = v[0];
                     C[(size_t)m * N + n0 + 16 + nn] = v[NT - 1];
@@ -126,24 +137,24 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const uint16_t 
 }
 
 template <int MT>
-static void skinny_dispatch(hipStream_t s, int mode, const void *A, WeightSeg w, int M, int N, int K, float *C,
-                            void *Cact)
+static void skinny_dispatch(hipStream_t s, int mode, const void *A, size_t a_plane, WeightSeg w, int M, int N, int K,
+                            float *C, void *Cact, size_t c_plane)
 {
     const uint16_t *a = (const uint16_t *)A;
     uint16_t *ca = (uint16_t *)Cact;
     if (mode == GEMM_SWIGLU)
-        hipLaunchKernelGGL((gemm_skinny_kernel<MT, GEMM_SWIGLU, 4, 2>), dim3(N / 16), dim3(256), 0, s, a, w, M, N, K,
-                           C, ca);
+        hipLaunchKernelGGL((gemm_skinny_kernel<MT, GEMM_SWIGLU, 4, 2>), dim3(N / 16), dim3(256), 0, s, a, a_plane, w,
+                           M, N, K, C, ca, c_plane);
     else if (mode == GEMM_STORE)
-        hipLaunchKernelGGL((gemm_skinny_kernel<MT, GEMM_STORE, 4, 2>), dim3(N / 32), dim3(256), 0, s, a, w, M, N, K, C,
-                           ca);
+        hipLaunchKernelGGL((gemm_skinny_kernel<MT, GEMM_STORE, 4, 2>), dim3(N / 32), dim3(256), 0, s, a, a_plane, w, M,
+                           N, K, C, ca, c_plane);
     else
-        hipLaunchKernelGGL((gemm_skinny_kernel<MT, GEMM_RESID, 8, 2>), dim3(N / 16), dim3(512), 0, s, a, w, M, N, K, C,
-                           ca);
+        hipLaunchKernelGGL((gemm_skinny_kernel<MT, GEMM_RESID, 8, 2>), dim3(N / 16), dim3(512), 0, s, a, a_plane, w, M,
+                           N, K, C, ca, c_plane);
 }
 
-hipError_t launch_gemm_skinny_bf16(hipStream_t s, int mode, const void *A, WeightSeg w, int M, int N, int K,
-                                   float *C, void *Cact)
+hipError_t launch_gemm_skinny_bf16(hipStream_t s, int mode, const void *A, size_t a_plane, WeightSeg w, int M, int N,
+                                   int K, float *C, void *Cact, size_t c_plane)
 {
     if (M < 1 || M > 32 || K % SK_KSTEP != 0) return hipErrorNotSupported;
     if (mode == GEMM_STORE) {
@@ -153,8 +164,8 @@ hipError_t launch_gemm_skinny_bf16(hipStream_t s, int mode, const void *A, Weigh
     }
     for (int i = 0; i < 3; i++)
         if (w.p[i] && ((uintptr_t)w.p[i] & 15)) return hipErrorNotSupported;
-    if ((uintptr_t)A & 15) return hipErrorNotSupported;
-    if (M <= 16) skinny_dispatch<1>(s, mode, A, w, M, N, K, C, Cact);
-    else skinny_dispatch<2>(s, mode, A, w, M, N, K, C, Cact);
+    if (((uintptr_t)A & 15) || (a_plane & 7)) return hipErrorNotSupported;
+    if (M <= 16) skinny_dispatch<1>(s, mode, A, a_plane, w, M, N, K, C, Cact, c_plane);
+    else skinny_dispatch<2>(s, mode, A, a_plane, w, M, N, K, C, Cact, c_plane);
     return hipGetLastError();
 }

@@ -201,7 +201,8 @@ hipError_t launch_embed(hipStream_t s, int dtype, const void *E, const int32_t *
 // ---------------------------------------------------------------- RMSNorm
 // out[j] = T( x[src] * rsqrt(mean(x[src]^2) + eps) * g ), src = row_map ? row_map[j] : j.
 template <typename T>
-__global__ void rmsnorm_kernel(const float *x, const float *g, const int32_t *row_map, int d, float eps, T *out)
+__global__ void rmsnorm_kernel(const float *x, const float *g, const int32_t *row_map, int d, float eps, T *out,
+                               size_t plane)
 {
     __shared__ float red[32];
     int j = blockIdx.x;
@@ -211,26 +212,26 @@ __global__ void rmsnorm_kernel(const float *x, const float *g, const int32_t *ro
     for (int i = threadIdx.x; i < d; i += blockDim.x) ss += xr[i] * xr[i];
     ss = block_sum(ss, red);
     float inv = 1.0f / sqrtf(ss / (float)d + eps);
-    for (int i = threadIdx.x; i < d; i += blockDim.x) out[(size_t)j * d + i] = from_float<T>(xr[i] * inv * g[i]);
+    for (int i = threadIdx.x; i < d; i += blockDim.x) store_act(out, (size_t)j * d + i, plane, xr[i] * inv * g[i]);
 }
 
 hipError_t launch_rmsnorm(hipStream_t s, int dtype, const float *x, const float *g, const int32_t *row_map,
-                          int n_rows, int d, float eps, void *out)
+                          int n_rows, int d, float eps, void *out, size_t out_plane)
 {
     if (dtype == SD_BF16)
         hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3(n_rows), dim3(256), 0, s, x, g, row_map, d, eps,
-                           (bf16_t *)out);
+                           (bf16_t *)out, out_plane);
     else
         hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(n_rows), dim3(256), 0, s, x, g, row_map, d, eps,
-                           (float *)out);
+                           (float *)out, out_plane);
     return hipGetLastError();
 }
 
 // ---------------------------------------------------------------- generic GEMM  C = A . W^T
 // One wave per output column n, 16 rows of A per block row; lanes stride over K.
 template <typename T, int MODE>
-__global__ __launch_bounds__(256) void gemm_generic_kernel(const T *A, WeightSeg w, int M, int N, int K, float *C,
-                                                           T *Cact)
+__global__ __launch_bounds__(256) void gemm_generic_kernel(const T *A, size_t a_plane, WeightSeg w, int M, int N,
+                                                           int K, float *C, T *Cact, size_t c_plane)
 {
     int n = blockIdx.x * 4 + threadIdx.x / WAVE;
     int lane = threadIdx.x % WAVE;
@@ -254,7 +255,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const T *A, WeightSeg
 #pragma unroll
         for (int m = 0; m < 16; m++) {
             if (m < mcount) {
-                float a = to_float(A[(size_t)(m0 + m) * K + k]);
+                float a = load_act(A, (size_t)(m0 + m) * K + k, a_plane);
                 acc[m] += a * wv;
                 if (MODE == GEMM_SWIGLU) acc2[m] += a * wv2;
             }
@@ -272,33 +273,33 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const T *A, WeightSeg
             else if (MODE == GEMM_RESID) C[o] += acc[m];
             else {
                 float g = acc[m];
-                Cact[o] = from_float<T>(g / (1.0f + expf(-g)) * acc2[m]);
+                store_act(Cact, o, c_plane, g / (1.0f + expf(-g)) * acc2[m]);
             }
         }
     }
 }
 
 template <typename T>
-static void gemm_generic_dispatch(hipStream_t s, int mode, const void *A, WeightSeg w, int M, int N, int K, float *C,
-                                  void *Cact)
+static void gemm_generic_dispatch(hipStream_t s, int mode, const void *A, size_t a_plane, WeightSeg w, int M, int N,
+                                  int K, float *C, void *Cact, size_t c_plane)
 {
     dim3 grid((N + 3) / 4, (M + 15) / 16), block(256);
     if (mode == GEMM_STORE)
-        hipLaunchKernelGGL((gemm_generic_kernel<T, GEMM_STORE>), grid, block, 0, s, (const T *)A, w, M, N, K, C,
-                           (T *)Cact);
+        hipLaunchKernelGGL((gemm_generic_kernel<T, GEMM_STORE>), grid, block, 0, s, (const T *)A, a_plane, w, M, N, K,
+                           C, (T *)Cact, c_plane);
     else if (mode == GEMM_RESID)
-        hipLaunchKernelGGL((gemm_generic_kernel<T, GEMM_RESID>), grid, block, 0, s, (const T *)A, w, M, N, K, C,
-                           (T *)Cact);
+        hipLaunchKernelGGL((gemm_generic_kernel<T, GEMM_RESID>), grid, block, 0, s, (const T *)A, a_plane, w, M, N, K,
+                           C, (T *)Cact, c_plane);
     else
-        hipLaunchKernelGGL((gemm_generic_kernel<T, GEMM_SWIGLU>), grid, block, 0, s, (const T *)A, w, M, N, K, C,
-                           (T *)Cact);
+        hipLaunchKernelGGL((gemm_generic_kernel<T, GEMM_SWIGLU>), grid, block, 0, s, (const T *)A, a_plane, w, M, N, K,
+                           C, (T *)Cact, c_plane);
 }
 
-hipError_t launch_gemm_generic(hipStream_t s, int dtype, int mode, const void *A, WeightSeg w, int M, int N, int K,
-                               float *C, void *Cact)
+hipError_t launch_gemm_generic(hipStream_t s, int dtype, int mode, const void *A, size_t a_plane, WeightSeg w, int M,
+                               int N, int K, float *C, void *Cact, size_t c_plane)
 {
-    if (dtype == SD_BF16) gemm_generic_dispatch<bf16_t>(s, mode, A, w, M, N, K, C, Cact);
-    else gemm_generic_dispatch<float>(s, mode, A, w, M, N, K, C, Cact);
+    if (dtype == SD_BF16) gemm_generic_dispatch<bf16_t>(s, mode, A, a_plane, w, M, N, K, C, Cact, c_plane);
+    else gemm_generic_dispatch<float>(s, mode, A, a_plane, w, M, N, K, C, Cact, c_plane);
     return hipGetLastError();
 }
 
@@ -308,7 +309,7 @@ hipError_t launch_gemm_generic(hipStream_t s, int dtype, int mode, const void *A
 // place: K[head][off+pos][hd], Vt[head][hd][off+pos].
 template <typename T>
 __global__ void rope_append_kernel(const float *qkv, PlanView pv, CtxView cv, int H, int hd, const float2 *rope,
-                                   int max_pos, T *qbuf, T *Kl, T *Vtl, int64_t total_cap)
+                                   int max_pos, T *qbuf, size_t q_plane, T *Kl, T *Vtl, int64_t total_cap)
 {
     int r = blockIdx.x;
     int HD = H * hd, half = hd / 2;
@@ -323,16 +324,16 @@ __global__ void rope_append_kernel(const float *qkv, PlanView pv, CtxView cv, in
     for (int i = threadIdx.x; i < H * half; i += blockDim.x) {
         int h = i / half, e = i % half;
         if (!valid) {
-            qbuf[(size_t)r * HD + h * hd + e] = from_float<T>(0.f);
-            qbuf[(size_t)r * HD + h * hd + e + half] = from_float<T>(0.f);
+            store_act(qbuf, (size_t)r * HD + h * hd + e, q_plane, 0.f);
+            store_act(qbuf, (size_t)r * HD + h * hd + e + half, q_plane, 0.f);
             continue;
         }
         float2 cs = rope[(size_t)pos * half + e];
         float q0 = row[h * hd + e], q1 = row[h * hd + e + half];
         float k0 = row[HD + h * hd + e], k1 = row[HD + h * hd + e + half];
         float v0 = row[2 * HD + h * hd + e], v1 = row[2 * HD + h * hd + e + half];
-        qbuf[(size_t)r * HD + h * hd + e] = from_float<T>(q0 * cs.x - q1 * cs.y);
-        qbuf[(size_t)r * HD + h * hd + e + half] = from_float<T>(q1 * cs.x + q0 * cs.y);
+        store_act(qbuf, (size_t)r * HD + h * hd + e, q_plane, q0 * cs.x - q1 * cs.y);
+        store_act(qbuf, (size_t)r * HD + h * hd + e + half, q_plane, q1 * cs.x + q0 * cs.y);
         T *kd = Kl + ((size_t)h * total_cap + off + pos) * hd;
         kd[e] = from_float<T>(k0 * cs.x - k1 * cs.y);
         kd[e + half] = from_float<T>(k1 * cs.x + k0 * cs.y);
@@ -343,15 +344,15 @@ __global__ void rope_append_kernel(const float *qkv, PlanView pv, CtxView cv, in
 }
 
 hipError_t launch_rope_append(hipStream_t s, int dtype, const float *qkv, PlanView pv, CtxView cv, int M, int H,
-                              int hd, const float2 *rope, int max_pos, void *qbuf, void *Kl, void *Vtl,
+                              int hd, const float2 *rope, int max_pos, void *qbuf, size_t q_plane, void *Kl, void *Vtl,
                               int64_t total_cap)
 {
     if (dtype == SD_BF16)
         hipLaunchKernelGGL(rope_append_kernel<bf16_t>, dim3(M), dim3(256), 0, s, qkv, pv, cv, H, hd, rope, max_pos,
-                           (bf16_t *)qbuf, (bf16_t *)Kl, (bf16_t *)Vtl, total_cap);
+                           (bf16_t *)qbuf, q_plane, (bf16_t *)Kl, (bf16_t *)Vtl, total_cap);
     else
         hipLaunchKernelGGL(rope_append_kernel<float>, dim3(M), dim3(256), 0, s, qkv, pv, cv, H, hd, rope, max_pos,
-                           (float *)qbuf, (float *)Kl, (float *)Vtl, total_cap);
+                           (float *)qbuf, q_plane, (float *)Kl, (float *)Vtl, total_cap);
     return hipGetLastError();
 }
 
@@ -359,9 +360,9 @@ hipError_t launch_rope_append(hipStream_t s, int dtype, const float *qkv, PlanVi
 // One block per (row slot i, head, selected sequence): query row i sees cache rows
 // [0, kv0 + i].  Scores live in dynamic LDS (len_upper floats).
 template <typename T>
-__global__ __launch_bounds__(256) void attn_generic_kernel(const T *qbuf, const T *Kl, const T *Vtl, PlanView pv,
-                                                           CtxView cv, int R, int H, int hd, int64_t total_cap,
-                                                           int lds_len, T *obuf)
+__global__ __launch_bounds__(256) void attn_generic_kernel(const T *qbuf, size_t q_plane, const T *Kl, const T *Vtl,
+                                                           PlanView pv, CtxView cv, int R, int H, int hd,
+                                                           int64_t total_cap, int lds_len, T *obuf, size_t o_plane)
 {
     extern __shared__ float sc[]; // [lds_len] scores, then [256] partials, [hd] q, [32] red
     float *part = sc + lds_len;
@@ -371,7 +372,7 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const T *qbuf, const 
     int r = j * R + i;
     int HD = H * hd;
     if (i >= pv.seq_nq[j]) {
-        for (int d = threadIdx.x; d < hd; d += blockDim.x) obuf[(size_t)r * HD + h * hd + d] = from_float<T>(0.f);
+        for (int d = threadIdx.x; d < hd; d += blockDim.x) store_act(obuf, (size_t)r * HD + h * hd + d, o_plane, 0.f);
         return;
     }
     int Lk = pv.seq_kv0[j] + i + 1;
@@ -379,7 +380,7 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const T *qbuf, const 
     int64_t off = cv.off[pv.seq_b[j]];
     const T *K = Kl + ((size_t)h * total_cap + off) * hd;
     const T *Vt = Vtl + (size_t)h * hd * total_cap + off;
-    for (int d = threadIdx.x; d < hd; d += blockDim.x) qs[d] = to_float(qbuf[(size_t)r * HD + h * hd + d]);
+    for (int d = threadIdx.x; d < hd; d += blockDim.x) qs[d] = load_act(qbuf, (size_t)r * HD + h * hd + d, q_plane);
     __syncthreads();
     float scale = 1.0f / sqrtf((float)hd);
     float mx = -3.0e38f;
@@ -409,24 +410,25 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const T *qbuf, const 
     __syncthreads();
     if (g == 0) {
         for (int gg = 1; gg < G; gg++) acc += part[gg * hd + d];
-        obuf[(size_t)r * HD + h * hd + d] = from_float<T>(acc / z);
+        store_act(obuf, (size_t)r * HD + h * hd + d, o_plane, acc / z);
     }
 }
 
-hipError_t launch_attn_generic(hipStream_t s, int dtype, const void *qbuf, const void *Kl, const void *Vtl,
-                               PlanView pv, CtxView cv, int R, int n_seq, int H, int hd, int64_t total_cap,
-                               int len_upper, void *obuf)
+hipError_t launch_attn_generic(hipStream_t s, int dtype, const void *qbuf, size_t q_plane, const void *Kl,
+                               const void *Vtl, PlanView pv, CtxView cv, int R, int n_seq, int H, int hd,
+                               int64_t total_cap, int len_upper, void *obuf, size_t o_plane)
 {
     size_t lds = ((size_t)len_upper + 256 + hd + 32) * sizeof(float);
     if (lds > 64 * 1024) return hipErrorNotSupported;
     dim3 grid(R, H, n_seq), block(256);
     if (dtype == SD_BF16)
-        hipLaunchKernelGGL(attn_generic_kernel<bf16_t>, grid, block, lds, s, (const bf16_t *)qbuf,
+        hipLaunchKernelGGL(attn_generic_kernel<bf16_t>, grid, block, lds, s, (const bf16_t *)qbuf, q_plane,
                            (const bf16_t *)Kl, (const bf16_t *)Vtl, pv, cv, R, H, hd, total_cap, len_upper,
-                           (bf16_t *)obuf);
+                           (bf16_t *)obuf, o_plane);
     else
-        hipLaunchKernelGGL(attn_generic_kernel<float>, grid, block, lds, s, (const float *)qbuf, (const float *)Kl,
-                           (const float *)Vtl, pv, cv, R, H, hd, total_cap, len_upper, (float *)obuf);
+        hipLaunchKernelGGL(attn_generic_kernel<float>, grid, block, lds, s, (const float *)qbuf, q_plane,
+                           (const float *)Kl, (const float *)Vtl, pv, cv, R, H, hd, total_cap, len_upper,
+                           (float *)obuf, o_plane);
     return hipGetLastError();
 }
 

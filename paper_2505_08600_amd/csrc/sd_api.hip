@@ -93,8 +93,8 @@ extern "C" int sd_profile_read(int32_t idx, const char **name, int32_t *count, f
 extern "C" int sd_set_option(const char *name, int32_t value)
 {
     if (!name) return sd_fail(SD_EINVAL, "sd_set_option: null name");
-    if (!strcmp(name, "force_generic")) {
-        g_force_generic = value;
+    if (!strcmp(name, "force_generic")) { // bit 0: GEMMs, bit 1: attention; 1 means both
+        g_force_generic = value == 1 ? 3 : value;
         return SD_OK;
     }
     if (!strcmp(name, "profile")) { // 1: start a fresh measurement, 0: stop recording (totals stay readable)
@@ -156,12 +156,15 @@ extern "C" int sd_load_model(const sd_model_config *cfg, const sd_weights *w, sd
         if (e == hipSuccess) e = hipMalloc(p, bytes);
     };
     m->x = nullptr;
+    const size_t planes = c.dtype == SD_BF16 ? 2 : 1; // bf16 activations are stored as hi + lo
+    m->plane_d = M * d;
+    m->plane_f = M * (size_t)c.d_ffn;
     alloc((void **)&m->x, M * d * 4);
-    alloc(&m->abuf, M * d * m->esz);
+    alloc(&m->abuf, planes * M * d * m->esz);
     alloc((void **)&m->qkv, M * 3 * d * 4);
-    alloc(&m->qbuf, M * d * m->esz);
-    alloc(&m->obuf, M * d * m->esz);
-    alloc(&m->act, M * (size_t)c.d_ffn * m->esz);
+    alloc(&m->qbuf, planes * M * d * m->esz);
+    alloc(&m->obuf, planes * M * d * m->esz);
+    alloc(&m->act, planes * M * (size_t)c.d_ffn * m->esz);
     alloc((void **)&m->logits, M * (size_t)c.vocab * 4);
     alloc((void **)&m->part, m->part_floats * 4);
     alloc((void **)&m->rope, (size_t)c.max_pos * (c.head_dim / 2) * sizeof(float2));
@@ -407,6 +410,42 @@ extern "C" int sd_ctx_truncate(sd_ctx *c, sd_model *m, int32_t seq, int32_t len)
     return SD_OK;
 }
 
+// Test hook: copy one workspace buffer of the last forward to the host as fp32.
+// name: "x" [rows][d], "qkv" [rows][3d], "q"/"o"/"a" [rows][d] (hi + lo summed), "act" [rows][d_ffn].
+extern "C" int sd_debug_read(sd_model *m, const char *name, float *out_host, int32_t rows)
+{
+    if (!m || !name || !out_host || rows < 0 || rows > m->cfg.max_rows) return sd_fail(SD_EINVAL, "sd_debug_read: bad argument");
+    SD_HIP(hipDeviceSynchronize());
+    const size_t d = m->cfg.d_model, F = m->cfg.d_ffn;
+    if (!strcmp(name, "x") || !strcmp(name, "qkv")) {
+        size_t w = !strcmp(name, "x") ? d : 3 * d;
+        SD_HIP(hipMemcpy(out_host, !strcmp(name, "x") ? m->x : m->qkv, rows * w * 4, hipMemcpyDeviceToHost));
+        return SD_OK;
+    }
+    const void *src = nullptr;
+    size_t w = d, plane = m->plane_d;
+    if (!strcmp(name, "q")) src = m->qbuf;
+    else if (!strcmp(name, "o")) src = m->obuf;
+    else if (!strcmp(name, "a")) src = m->abuf;
+    else if (!strcmp(name, "act")) src = m->act, w = F, plane = m->plane_f;
+    else return sd_fail(SD_EINVAL, "sd_debug_read: unknown buffer");
+    if (m->cfg.dtype == SD_FP32) {
+        SD_HIP(hipMemcpy(out_host, src, rows * w * 4, hipMemcpyDeviceToHost));
+        return SD_OK;
+    }
+    std::vector<uint16_t> hi(rows * w), lo(rows * w);
+    SD_HIP(hipMemcpy(hi.data(), src, rows * w * 2, hipMemcpyDeviceToHost));
+    SD_HIP(hipMemcpy(lo.data(), (const uint16_t *)src + plane, rows * w * 2, hipMemcpyDeviceToHost));
+    for (size_t i = 0; i < rows * w; i++) {
+        uint32_t a = (uint32_t)hi[i] << 16, b = (uint32_t)lo[i] << 16;
+        float fa, fb;
+        memcpy(&fa, &a, 4);
+        memcpy(&fb, &b, 4);
+        out_host[i] = fa + fb;
+    }
+    return SD_OK;
+}
+
 extern "C" int sd_last_logits(sd_model *m, float *out, int32_t max_rows, int32_t *rows)
 {
     if (!m || !out || max_rows < 0) return sd_fail(SD_EINVAL, "sd_last_logits: bad argument");
@@ -418,14 +457,14 @@ extern "C" int sd_last_logits(sd_model *m, float *out, int32_t max_rows, int32_t
 }
 
 // ---------------------------------------------------------------- one decoder forward
-static hipError_t gemm(sd_model *m, hipStream_t s, int mode, const void *A, WeightSeg w, int M, int N, int K,
-                       float *C, void *Cact)
+static hipError_t gemm(sd_model *m, hipStream_t s, int mode, const void *A, size_t a_plane, WeightSeg w, int M, int N,
+                       int K, float *C, void *Cact, size_t c_plane)
 {
-    if (m->cfg.dtype == SD_BF16 && !g_force_generic) {
-        hipError_t e = launch_gemm_skinny_bf16(s, mode, A, w, M, N, K, C, Cact);
+    if (m->cfg.dtype == SD_BF16 && !(g_force_generic & 1)) {
+        hipError_t e = launch_gemm_skinny_bf16(s, mode, A, a_plane, w, M, N, K, C, Cact, c_plane);
         if (e != hipErrorNotSupported) return e;
     }
-    return launch_gemm_generic(s, m->cfg.dtype, mode, A, w, M, N, K, C, Cact);
+    return launch_gemm_generic(s, m->cfg.dtype, mode, A, a_plane, w, M, N, K, C, Cact, c_plane);
 }
 
 #define FWD(expr)                                                                                  \
@@ -456,43 +495,43 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
     for (int l = 0; l < cf.n_layers; l++) {
         void *Kl = (char *)c->kcache[slot] + l * lstride, *Vtl = (char *)c->vcache[slot] + l * lstride;
         { ProfScope ps(T_RMSNORM, s);
-        FWD(launch_rmsnorm(s, cf.dtype, m->x, m->norm_attn[l], nullptr, M, d, cf.rms_eps, m->abuf)); }
+        FWD(launch_rmsnorm(s, cf.dtype, m->x, m->norm_attn[l], nullptr, M, d, cf.rms_eps, m->abuf, m->plane_d)); }
         WeightSeg wqkv = {{m->wq[l], m->wk[l], m->wv[l]}, d};
         { ProfScope ps(T_QKV, s);
-        FWD(gemm(m, s, GEMM_STORE, m->abuf, wqkv, M, 3 * d, d, m->qkv, nullptr)); }
+        FWD(gemm(m, s, GEMM_STORE, m->abuf, m->plane_d, wqkv, M, 3 * d, d, m->qkv, nullptr, 0)); }
         { ProfScope ps(T_ROPE, s);
-        FWD(launch_rope_append(s, cf.dtype, m->qkv, pv, cv, M, H, hd, m->rope, cf.max_pos, m->qbuf, Kl, Vtl,
-                               c->total_cap)); }
+        FWD(launch_rope_append(s, cf.dtype, m->qkv, pv, cv, M, H, hd, m->rope, cf.max_pos, m->qbuf, m->plane_d, Kl,
+                               Vtl, c->total_cap)); }
         hipError_t ea = hipErrorNotSupported;
         { ProfScope ps(T_ATTN, s);
-        if (cf.dtype == SD_BF16 && !g_force_generic)
-            ea = launch_attn_mfma_bf16(s, m->qbuf, Kl, Vtl, pv, cv, R, n_seq, H, hd, c->total_cap, kv_upper, m->part,
-                                       m->part_floats, m->obuf);
+        if (cf.dtype == SD_BF16 && !(g_force_generic & 2))
+            ea = launch_attn_mfma_bf16(s, m->qbuf, m->plane_d, Kl, Vtl, pv, cv, R, n_seq, H, hd, c->total_cap, kv_upper,
+                                       m->part, m->part_floats, m->obuf, m->plane_d);
         if (ea == hipErrorNotSupported)
-            ea = launch_attn_generic(s, cf.dtype, m->qbuf, Kl, Vtl, pv, cv, R, n_seq, H, hd, c->total_cap, kv_upper,
-                                     m->obuf);
+            ea = launch_attn_generic(s, cf.dtype, m->qbuf, m->plane_d, Kl, Vtl, pv, cv, R, n_seq, H, hd, c->total_cap,
+                                     kv_upper, m->obuf, m->plane_d);
         }
         if (ea == hipErrorNotSupported) return sd_fail(SD_ECAP, "forward: context too long for the generic attention kernel");
         FWD(ea);
         WeightSeg wo = {{m->wo[l], nullptr, nullptr}, d};
         { ProfScope ps(T_OPROJ, s);
-        FWD(gemm(m, s, GEMM_RESID, m->obuf, wo, M, d, d, m->x, nullptr)); }
+        FWD(gemm(m, s, GEMM_RESID, m->obuf, m->plane_d, wo, M, d, d, m->x, nullptr, 0)); }
         { ProfScope ps(T_RMSNORM, s);
-        FWD(launch_rmsnorm(s, cf.dtype, m->x, m->norm_ffn[l], nullptr, M, d, cf.rms_eps, m->abuf)); }
+        FWD(launch_rmsnorm(s, cf.dtype, m->x, m->norm_ffn[l], nullptr, M, d, cf.rms_eps, m->abuf, m->plane_d)); }
         WeightSeg wgu = {{m->wgate[l], m->wup[l], nullptr}, F};
         { ProfScope ps(T_GATEUP, s);
-        FWD(gemm(m, s, GEMM_SWIGLU, m->abuf, wgu, M, F, d, nullptr, m->act)); }
+        FWD(gemm(m, s, GEMM_SWIGLU, m->abuf, m->plane_d, wgu, M, F, d, nullptr, m->act, m->plane_f)); }
         WeightSeg wd = {{m->wdown[l], nullptr, nullptr}, d};
         { ProfScope ps(T_DOWN, s);
-        FWD(gemm(m, s, GEMM_RESID, m->act, wd, M, d, F, m->x, nullptr)); }
+        FWD(gemm(m, s, GEMM_RESID, m->act, m->plane_f, wd, M, d, F, m->x, nullptr, 0)); }
     }
     if (want_logits) {
         int n_lm = mode == PLAN_VERIFY ? M : n_seq;
         { ProfScope ps(T_RMSNORM, s);
-        FWD(launch_rmsnorm(s, cf.dtype, m->x, m->final_norm, pv.lm_row, n_lm, d, cf.rms_eps, m->abuf)); }
+        FWD(launch_rmsnorm(s, cf.dtype, m->x, m->final_norm, pv.lm_row, n_lm, d, cf.rms_eps, m->abuf, m->plane_d)); }
         WeightSeg wl = {{m->lm_head, nullptr, nullptr}, V};
         { ProfScope ps(T_LMHEAD, s);
-        FWD(gemm(m, s, GEMM_STORE, m->abuf, wl, n_lm, V, d, m->logits, nullptr)); }
+        FWD(gemm(m, s, GEMM_STORE, m->abuf, m->plane_d, wl, n_lm, V, d, m->logits, nullptr, 0)); }
         m->last_lm_rows = n_lm;
     }
     return SD_OK;

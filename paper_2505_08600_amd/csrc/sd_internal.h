@@ -40,6 +40,23 @@ __device__ __forceinline__ bf16_t from_float<bf16_t>(float f)
     return r;
 }
 
+// GEMM-input activations.  fp32 models: one fp32 plane.  bf16 models: two bf16
+// planes, value = hi + lo with hi = bf16(x), lo = bf16(x - hi), i.e. about 16
+// mantissa bits fed to the matrix cores as two operands.  `plane` is the element
+// offset from the hi plane to the lo plane.
+__device__ __forceinline__ float load_act(const float *b, size_t i, size_t) { return b[i]; }
+__device__ __forceinline__ float load_act(const bf16_t *b, size_t i, size_t plane)
+{
+    return to_float(b[i]) + to_float(b[i + plane]);
+}
+__device__ __forceinline__ void store_act(float *b, size_t i, size_t, float v) { b[i] = v; }
+__device__ __forceinline__ void store_act(bf16_t *b, size_t i, size_t plane, float v)
+{
+    uint16_t hi = bf16_bits_rne(v);
+    b[i].v = hi;
+    b[i + plane].v = bf16_bits_rne(v - __uint_as_float((uint32_t)hi << 16));
+}
+
 // ---------------------------------------------------------------- views passed to kernels
 // Device-side view of a context.  kvlen is [SD_MAX_SLOTS][B].
 struct CtxView {
@@ -84,11 +101,13 @@ struct sd_model {
     int esz; // bytes per weight / activation element
     // workspace (device)
     float *x;       // [max_rows][d] residual stream
-    void *abuf;     // [max_rows][d] normed GEMM input
+    // activation buffers: fp32 models one plane, bf16 models two bf16 planes (hi, lo)
+    void *abuf;     // [planes][max_rows][d] normed GEMM input
     float *qkv;     // [max_rows][3*d]
-    void *qbuf;     // [max_rows][d] rotated queries
-    void *obuf;     // [max_rows][d] attention output
-    void *act;      // [max_rows][d_ffn]
+    void *qbuf;     // [planes][max_rows][d] rotated queries
+    void *obuf;     // [planes][max_rows][d] attention output
+    void *act;      // [planes][max_rows][d_ffn]
+    size_t plane_d, plane_f; // element offsets between the planes
     float *logits;  // [max_rows][vocab]
     float *part;    // split-K / split-KV partial results
     size_t part_floats;
@@ -143,15 +162,15 @@ hipError_t launch_plan(hipStream_t s, int mode, int R, int n_seq, const int32_t 
                        int upto_off, const int32_t *cand, int gamma, int cand_idx, int vocab, PlanView pv);
 hipError_t launch_embed(hipStream_t s, int dtype, const void *E, const int32_t *row_tok, int M, int d, float *x);
 hipError_t launch_rmsnorm(hipStream_t s, int dtype, const float *x, const float *g, const int32_t *row_map,
-                          int n_rows, int d, float eps, void *out);
-hipError_t launch_gemm_generic(hipStream_t s, int dtype, int mode, const void *A, WeightSeg w, int M, int N, int K,
-                               float *C, void *Cact);
+                          int n_rows, int d, float eps, void *out, size_t out_plane);
+hipError_t launch_gemm_generic(hipStream_t s, int dtype, int mode, const void *A, size_t a_plane, WeightSeg w, int M,
+                               int N, int K, float *C, void *Cact, size_t c_plane);
 hipError_t launch_rope_append(hipStream_t s, int dtype, const float *qkv, PlanView pv, CtxView cv, int M, int H,
-                              int hd, const float2 *rope, int max_pos, void *qbuf, void *Kl, void *Vtl,
+                              int hd, const float2 *rope, int max_pos, void *qbuf, size_t q_plane, void *Kl, void *Vtl,
                               int64_t total_cap);
-hipError_t launch_attn_generic(hipStream_t s, int dtype, const void *qbuf, const void *Kl, const void *Vtl,
-                               PlanView pv, CtxView cv, int R, int n_seq, int H, int hd, int64_t total_cap,
-                               int len_upper, void *obuf);
+hipError_t launch_attn_generic(hipStream_t s, int dtype, const void *qbuf, size_t q_plane, const void *Kl,
+                               const void *Vtl, PlanView pv, CtxView cv, int R, int n_seq, int H, int hd,
+                               int64_t total_cap, int len_upper, void *obuf, size_t o_plane);
 hipError_t launch_draft_sample(hipStream_t s, const float *logits, int n_seq, int V, float T, const float *u,
                                int gamma, int idx, int32_t *cand, float *q);
 hipError_t launch_verify_tail(hipStream_t s, const float *logits, int n_seq, int gamma, int V, float T,
@@ -165,8 +184,8 @@ hipError_t launch_set_kv(hipStream_t s, int dtype, const void *k_rows, const voi
                          int64_t seq_off, int64_t total_cap, void *Kl, void *Vtl);
 
 // optimised bf16 paths (return hipErrorNotSupported when the shape is outside their domain)
-hipError_t launch_gemm_skinny_bf16(hipStream_t s, int mode, const void *A, WeightSeg w, int M, int N, int K,
-                                   float *C, void *Cact);
-hipError_t launch_attn_mfma_bf16(hipStream_t s, const void *qbuf, const void *Kl, const void *Vtl, PlanView pv,
-                                 CtxView cv, int R, int n_seq, int H, int hd, int64_t total_cap, int len_upper,
-                                 float *part, size_t part_floats, void *obuf);
+hipError_t launch_gemm_skinny_bf16(hipStream_t s, int mode, const void *A, size_t a_plane, WeightSeg w, int M, int N,
+                                   int K, float *C, void *Cact, size_t c_plane);
+hipError_t launch_attn_mfma_bf16(hipStream_t s, const void *qbuf, size_t q_plane, const void *Kl, const void *Vtl,
+                                 PlanView pv, CtxView cv, int R, int n_seq, int H, int hd, int64_t total_cap,
+                                 int len_upper, float *part, size_t part_floats, void *obuf, size_t o_plane);

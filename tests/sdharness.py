@@ -115,6 +115,41 @@ def teacher_forced_parity(pair: Pair, prompt, gamma, T, n_tokens, seed) -> Parit
     ctx.attach(pair.gt)
     ctx.attach(pair.gd)
     gpu_prefill(ctx, [pair.gt, pair.gd], [list(prompt)])
+    st = lockstep(pair, ctx, steps, gamma, T)
+    nt, kv = ctx.sync(pair.gt)
+    n_expected = len(prompt) + sum(s.n_acc + 1 for s in steps)
+    assert nt[0] == n_expected and kv[0] == n_expected - 1
+    got = ctx.get_tokens(0)
+    ref_all = list(prompt)
+    for s in steps:
+        ref_all += [int(c) for c in s.cand[:s.n_acc]] + [s.next_token]
+    assert list(got) == ref_all
+    ctx.close()
+    return st
+
+
+def oracle_steps(tseq, dseq, ctx_tokens, gamma, T, n_steps, seed, seq=0):
+    """n_steps draft/verify/commit steps of the oracle from the caches' current state.
+    -> (records, tokens after the last step)"""
+    ctx_t = [int(t) for t in ctx_tokens]
+    out = []
+    for k in range(n_steps):
+        ud = dg.make_uniforms(seed, dg.DRAFT_STREAM, seq, k, gamma)
+        uv = dg.make_uniforms(seed, dg.VERIFY_STREAM, seq, k, gamma + 1)
+        cand, q, mgd = dseq.draft(ctx_t, gamma, T, ud)
+        n0 = len(ctx_t)
+        na, nx, mgv, lg = tseq.verify(ctx_t, gamma, T, cand, q, uv, want_logits=True)
+        oracle.loop.commit(ctx_t, tseq, dseq, cand, na, nx)
+        out.append(oracle.StepRecord(n0, cand, q, ud, uv, na, nx, mgd, mgv, lg))
+    return out, ctx_t
+
+
+def lockstep(pair: Pair, ctx: api.Context, steps, gamma, T) -> ParityStats:
+    """Run the HIP draft and verify of sequence 0 along the oracle's recorded steps and
+    compare every output; commits the oracle's result after each step."""
+    dtype = pair.shape_t.dtype
+    thr = MARGIN_THR[dtype]
+    V = pair.shape_t.vocab
     st = ParityStats()
     cand_g = torch.zeros((1, gamma), dtype=torch.int32, device="cuda")
     q_g = torch.zeros((1, gamma, V), dtype=torch.float32, device="cuda") if T > 0 else None
@@ -184,15 +219,6 @@ def teacher_forced_parity(pair: Pair, prompt, gamma, T, n_tokens, seed) -> Parit
         st.flagged += int(flagged)
         st.n_acc.append(s.n_acc)
     torch.cuda.synchronize()
-    nt, kv = ctx.sync(pair.gt)
-    n_expected = len(prompt) + sum(s.n_acc + 1 for s in steps)
-    assert nt[0] == n_expected and kv[0] == n_expected - 1
-    got = ctx.get_tokens(0)
-    ref_all = list(prompt)
-    for s in steps:
-        ref_all += [int(c) for c in s.cand[:s.n_acc]] + [s.next_token]
-    assert list(got) == ref_all
-    ctx.close()
     return st
 
 
