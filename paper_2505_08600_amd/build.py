@@ -28,7 +28,7 @@ def build_lib(verbose: bool = False) -> str:
     newest_hdr = max(os.path.getmtime(h) for h in hdrs)
 
     def compile_one(src):
-        obj = os.path.join(OBJ, os.path.basename(src) + ".o")
+        obj = os.path.join(OBJ, os.path.splitext(os.path.basename(src))[0] + ".o")
         if os.path.exists(obj) and os.path.getmtime(obj) > max(os.path.getmtime(src), newest_hdr):
             return obj
         cmd = [HIPCC] + FLAGS + ["-c", src, "-o", obj]

@@ -193,15 +193,28 @@ __global__ void attn_combine_kernel(const float *__restrict__ part, PlanView pv,
     const float *base = part + (size_t)(j * H + h) * S * 16 * (HD + 2);
     for (int e = threadIdx.x; e < R * HD; e += blockDim.x) {
         const int q = e / HD, dim = e % HD;
+        // all loads of the S (<= 32) partials are independent: issue them before the arithmetic
+        float ms[SD_ATTN_MAX_SPLITS], ls[SD_ATTN_MAX_SPLITS], os[SD_ATTN_MAX_SPLITS];
+#pragma unroll
+        for (int s = 0; s < SD_ATTN_MAX_SPLITS; s++)
+            if (s < S) {
+                const float *pp = base + (size_t)s * 16 * (HD + 2);
+                ms[s] = pp[16 * HD + q];
+                ls[s] = pp[16 * HD + 16 + q];
+                os[s] = pp[q * HD + dim];
+            }
         float M = AT_NEG;
-        for (int s = 0; s < S; s++) M = fmaxf(M, base[(size_t)s * 16 * (HD + 2) + 16 * HD + q]);
+#pragma unroll
+        for (int s = 0; s < SD_ATTN_MAX_SPLITS; s++)
+            if (s < S) M = fmaxf(M, ms[s]);
         float O = 0.f, L = 0.f;
-        for (int s = 0; s < S; s++) {
-            const float *pp = base + (size_t)s * 16 * (HD + 2);
-            float f = expf(pp[16 * HD + q] - M);
-            O += pp[q * HD + dim] * f;
-            L += pp[16 * HD + 16 + q] * f;
-        }
+#pragma unroll
+        for (int s = 0; s < SD_ATTN_MAX_SPLITS; s++)
+            if (s < S) {
+                float f = expf(ms[s] - M);
+                O += os[s] * f;
+                L += ls[s] * f;
+            }
         float out = (q < nq && L > 0.f) ? O / L : 0.f;
         uint16_t hi = bf16_bits_rne(out);
         size_t oi = (size_t)(j * R + q) * (H * HD) + h * HD + dim;

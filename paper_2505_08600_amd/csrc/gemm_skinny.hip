@@ -4,21 +4,25 @@
 // work is reading each weight once from HBM, so the kernel is organised around
 // the weight stream, and the matrix cores only keep the ALUs out of the way.
 //
-//  * a wave owns 16-column tiles of W: two of them (or, for SwiGLU, the gate and
-//    the up tile of the same 16 columns) in the store / SwiGLU variants, one in the
-//    residual variant, and walks K in steps of 128 elements; the waves of a block
-//    interleave those steps (in-block split-K), so a block reads whole contiguous
-//    kilobytes of every weight row per round;
-//  * every lane loads 64 contiguous bytes of its weight row per step straight into
-//    MFMA operand registers (v_mfma_f32_16x16x32_bf16: lane l supplies row l%16,
-//    k-group l/16); the contraction index is permuted identically for both
-//    operands, which a dot product does not care about;
-//  * the activation operand comes from global memory (L2 hits), masked to the M
-//    real rows; activations are two bf16 planes (hi + lo, ~16 mantissa bits), so
-//    every weight fragment is multiplied twice - free while the kernel waits on HBM;
-//  * the partial accumulators of the waves meet in LDS; the epilogue stores, adds
-//    into the fp32 residual stream, or applies silu(gate)*up and rounds to bf16.
-//    The sum order is fixed, so results are bit-reproducible run to run.
+//  * a block of WAVES waves covers WAVES*16*NT/... output columns and one K range
+//    (grid.y splits K); every wave owns NT 16-column tiles of W and all waves walk
+//    the same K chunks, so the activation chunk is staged ONCE per block in LDS
+//    (double buffered) instead of being fetched by every wave from L2 - at these
+//    sizes the shared activation lines, not HBM, were the bottleneck otherwise;
+//  * per chunk a lane loads 64 contiguous bytes per 128-element step of its weight
+//    row straight into MFMA operand registers (v_mfma_f32_16x16x32_bf16: lane l
+//    supplies row l%16, k-group l/16), all steps of the chunk in flight at once: a
+//    wave reads one contiguous kilobyte (packed case) of each of its 16 rows per
+//    chunk.  The contraction index is permuted identically for both operands, which
+//    a dot product does not care about;
+//  * activations are two bf16 planes (hi + lo, ~16 mantissa bits).  For M <= 8 both
+//    planes ride in ONE operand: MFMA columns 0..7 carry the hi rows, columns 8..15
+//    the lo rows, and the epilogue adds the two halves with one lane exchange; for
+//    larger M every weight fragment is multiplied twice;
+//  * results leave either directly (store; SwiGLU: silu(gate)*up split to bf16
+//    hi/lo) or as fp32 partial sums per K split, which the consuming kernel adds in
+//    a fixed order (rope_append for QKV, add_rmsnorm for the residual GEMMs), so
+//    results are bit-reproducible run to run.
 //
 // Paper (arXiv 2505.08600): Section 1, Figure 1 (draft steps and the parallel
 // verify pass whose linear layers these are); Section 3.1 (LLaMA blocks).
@@ -27,145 +31,352 @@
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
-#define SK_KSTEP 128
+#define GS_OPELEMS 8192 // bf16 elements of one staged activation chunk (operand rows x chunk length)
+#define GS_PAD 8        // row padding in LDS (16 bytes): operand rows fall into distinct banks
 
-// MT: 16-row tiles of A; WAVES: waves per block (in-block split-K); U: K steps in flight per wave
-template <int MT, int MODE, int WAVES, int U>
-__global__ __launch_bounds__(WAVES * 64) void gemm_skinny_kernel(const uint16_t *__restrict__ A, size_t a_plane,
-                                                                 WeightSeg w, int M, int N, int K,
-                                                                 float *__restrict__ C, uint16_t *__restrict__ Cact,
-                                                                 size_t c_plane)
+// MODE: GEMM_STORE (C = acc, or partial sums when KS > 1) / GEMM_SWIGLU (tiles 2j, 2j+1 of a wave are
+// the gate and up tile of the same columns).  OPROWS: operand rows staged per chunk: 16 (packed hi|lo,
+// M <= 8), 32 (hi 0..15, lo 16..31, M <= 16) or 64 (M <= 32).
+template <int MODE, int OPROWS, int NT, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void gemm_stream_kernel(const uint16_t *__restrict__ A, size_t a_plane,
+                                                                 WeightSeg w, int M, int N, int K, int k_per_split,
+                                                                 float *__restrict__ C, size_t c_split_stride,
+                                                                 uint16_t *__restrict__ Cact, size_t c_plane)
 {
-    constexpr bool DUAL = MODE != GEMM_RESID;
-    constexpr int NT = DUAL ? 2 : 1;
-    __shared__ float red[WAVES][NT][MT][64][4];
+    constexpr bool PACKED = OPROWS == 16;
+    constexpr int MT = PACKED ? 1 : OPROWS / 32;    // 16-row tiles of A
+    constexpr int KC = GS_OPELEMS / OPROWS;         // chunk length in k (512 / 256 / 128)
+    constexpr int STEPS = KC / 128;                 // 128-element steps per chunk
+    constexpr int LDROW = KC + GS_PAD;
+    constexpr int THREADS = WAVES * 64;
+    constexpr int VEC_PER_ROW = KC / 8;             // 16-byte vectors per operand row
+    constexpr int NVEC = OPROWS * VEC_PER_ROW;      // vectors per chunk (1024)
+    constexpr int LPT = (NVEC + THREADS - 1) / THREADS;
+    constexpr int COLS = (MODE == GEMM_SWIGLU ? NT / 2 : NT) * 16 * WAVES;
+    __shared__ __attribute__((aligned(16))) uint16_t sA[2][OPROWS][LDROW];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int row = lane & 15, grp = lane >> 4;
-    int n0;
+    const int n0 = blockIdx.x * COLS;
+    const int kb = blockIdx.y * k_per_split;
+    const int ke = min(K, kb + k_per_split);
+    const int nchunks = (ke - kb + KC - 1) / KC;
+    // weight rows of this lane
     const uint16_t *Wp[NT];
     if (MODE == GEMM_SWIGLU) {
-        n0 = blockIdx.x * 16;
-        Wp[0] = (const uint16_t *)w.p[0] + (size_t)(n0 + row) * K;
-        Wp[NT - 1] = (const uint16_t *)w.p[1] + (size_t)(n0 + row) * K;
+#pragma unroll
+        for (int c = 0; c < NT; c++)
+            Wp[c] = (const uint16_t *)w.p[c & 1] + (size_t)(n0 + (wave * (NT / 2) + (c >> 1)) * 16 + row) * K;
     } else {
-        n0 = blockIdx.x * 16 * NT;
-        int seg = n0 / w.n_per_seg;
-        int nl = n0 - seg * w.n_per_seg;
-        Wp[0] = (const uint16_t *)w.p[seg] + (size_t)(nl + row) * K;
-        if (DUAL) Wp[NT - 1] = Wp[0] + (size_t)16 * K;
+        const int seg = n0 / w.n_per_seg;
+        const int nl = n0 - seg * w.n_per_seg;
+#pragma unroll
+        for (int c = 0; c < NT; c++) Wp[c] = (const uint16_t *)w.p[seg] + (size_t)(nl + (wave * NT + c) * 16 + row) * K;
     }
+    // cooperative staging of the activation chunk: vector v -> operand row v / VEC_PER_ROW
+    const uint16_t *a_src[LPT];
+    int a_dst[LPT];
+    bool a_ok[LPT];
+#pragma unroll
+    for (int j = 0; j < LPT; j++) {
+        const int v = threadIdx.x + j * THREADS;
+        const int orow = v / VEC_PER_ROW, ov = v % VEC_PER_ROW;
+        int m;
+        size_t plane;
+        if (PACKED) {
+            m = orow & 7;
+            plane = orow < 8 ? 0 : a_plane;
+        } else {
+            m = (orow % (OPROWS / 2));
+            plane = orow < OPROWS / 2 ? 0 : a_plane;
+        }
+        a_ok[j] = v < NVEC && m < M;
+        a_src[j] = A + plane + (size_t)(a_ok[j] ? m : 0) * K + ov * 8;
+        a_dst[j] = (v < NVEC ? orow : 0) * LDROW + ov * 8;
+    }
+    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+    bf16x8 a_reg[LPT];
+    auto a_fetch = [&](int chunk) {
+        const int k0 = kb + chunk * KC;
+#pragma unroll
+        for (int j = 0; j < LPT; j++) {
+            const int ov8 = (a_dst[j] % LDROW);
+            a_reg[j] = (a_ok[j] && k0 + ov8 < ke) ? *(const bf16x8 *)(a_src[j] + k0) : zero;
+        }
+    };
+    auto a_commit = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < LPT; j++)
+            if (threadIdx.x + j * THREADS < NVEC) *(bf16x8 *)(&sA[buf][0][0] + a_dst[j]) = a_reg[j];
+    };
     f32x4 acc[NT][MT];
 #pragma unroll
     for (int c = 0; c < NT; c++)
 #pragma unroll
         for (int t = 0; t < MT; t++) acc[c][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    const int nsteps = K / SK_KSTEP;
-    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-    for (int s0 = wave * U; s0 < nsteps; s0 += WAVES * U) {
-        bf16x8 wv[U][NT][4], av[U][MT][4], al[U][MT][4];
+    // Weight loads of a chunk: all steps in flight at once.  They are issued for chunk ch+1 right after
+    // the MFMAs of chunk ch released the registers, i.e. before the barrier, so HBM never waits on LDS.
+    bf16x8 wv[NT][STEPS][4];
+    auto w_issue = [&](int chunk) {
+        const int k0 = kb + chunk * KC;
 #pragma unroll
-        for (int u = 0; u < U; u++) {
-            const bool live = s0 + u < nsteps;
-            const int k = (live ? s0 + u : s0) * SK_KSTEP + grp * 32;
+        for (int c = 0; c < NT; c++)
 #pragma unroll
-            for (int c = 0; c < NT; c++) {
-                const bf16x8 *p = (const bf16x8 *)(Wp[c] + k);
+            for (int st = 0; st < STEPS; st++) {
+                const int k = k0 + st * 128 + grp * 32;
+                const bool live = k < ke;
+                const bf16x8 *p = (const bf16x8 *)(Wp[c] + (live ? k : kb));
 #pragma unroll
-                for (int i = 0; i < 4; i++) wv[u][c][i] = live ? p[i] : zero;
+                for (int i = 0; i < 4; i++) wv[c][st][i] = live ? p[i] : zero;
             }
+    };
+    w_issue(0);
+    a_fetch(0);
+    a_commit(0);
+    __syncthreads();
+    for (int ch = 0; ch < nchunks; ch++) {
+        const bool more = ch + 1 < nchunks;
+        if (more) a_fetch(ch + 1);
+        const uint16_t *sa = &sA[ch & 1][0][0];
 #pragma unroll
-            for (int t = 0; t < MT; t++) {
-                const int m = t * 16 + row;
-                const bf16x8 *pa = (const bf16x8 *)(A + (size_t)(m < M ? m : 0) * K + k);
-                const bf16x8 *pl = (const bf16x8 *)(A + a_plane + (size_t)(m < M ? m : 0) * K + k);
+        for (int st = 0; st < STEPS; st++) {
 #pragma unroll
-                for (int i = 0; i < 4; i++) {
-                    av[u][t][i] = (live && m < M) ? pa[i] : zero;
-                    al[u][t][i] = (live && m < M) ? pl[i] : zero;
+            for (int i = 0; i < 4; i++) {
+                const int kk = st * 128 + grp * 32 + i * 8;
+#pragma unroll
+                for (int t = 0; t < MT; t++) {
+                    if (PACKED) {
+                        const bf16x8 av = *(const bf16x8 *)(sa + row * LDROW + kk);
+#pragma unroll
+                        for (int c = 0; c < NT; c++)
+                            acc[c][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv[c][st][i], av, acc[c][t], 0, 0, 0);
+                    } else {
+                        const bf16x8 ah = *(const bf16x8 *)(sa + (t * 16 + row) * LDROW + kk);
+                        const bf16x8 al = *(const bf16x8 *)(sa + (OPROWS / 2 + t * 16 + row) * LDROW + kk);
+#pragma unroll
+                        for (int c = 0; c < NT; c++) {
+                            acc[c][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv[c][st][i], ah, acc[c][t], 0, 0, 0);
+                            acc[c][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv[c][st][i], al, acc[c][t], 0, 0, 0);
+                        }
+                    }
                 }
             }
         }
+        if (more) {
+            w_issue(ch + 1);
+            a_commit((ch + 1) & 1);
+        }
+        __syncthreads();
+    }
+    // epilogue: lane (m' = row, grp) holds D[n = 4*grp + r][m'] of each of its tiles
 #pragma unroll
-        for (int u = 0; u < U; u++)
+    for (int t = 0; t < MT; t++) {
+        f32x4 v[NT];
 #pragma unroll
-            for (int i = 0; i < 4; i++)
+        for (int c = 0; c < NT; c++) {
+            v[c] = acc[c][t];
+            if (PACKED) {
 #pragma unroll
-                for (int t = 0; t < MT; t++)
+                for (int r = 0; r < 4; r++) v[c][r] += __shfl_xor(v[c][r], 8, 64); // hi half + lo half
+            }
+        }
+        const int m = PACKED ? row : t * 16 + row;
+        if ((PACKED && row >= 8) || m >= M) continue;
+        if (MODE == GEMM_SWIGLU) {
 #pragma unroll
-                    for (int c = 0; c < NT; c++) {
-                        acc[c][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv[u][c][i], av[u][t][i], acc[c][t], 0, 0, 0);
-                        acc[c][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv[u][c][i], al[u][t][i], acc[c][t], 0, 0, 0);
-                    }
+            for (int j = 0; j < NT / 2; j++) {
+                const size_t o = (size_t)m * N + n0 + (wave * (NT / 2) + j) * 16 + 4 * grp;
+#pragma unroll
+                for (int r = 0; r < 4; r++) {
+                    const float g0 = v[2 * j][r];
+                    const float y = g0 / (1.0f + expf(-g0)) * v[2 * j + 1][r];
+                    const uint16_t hi = bf16_bits_rne(y);
+                    Cact[o + r] = hi;
+                    Cact[c_plane + o + r] = bf16_bits_rne(y - __uint_as_float((uint32_t)hi << 16));
+                }
+            }
+        } else {
+            float *Cs = C + (size_t)blockIdx.y * c_split_stride;
+#pragma unroll
+            for (int c = 0; c < NT; c++) {
+                const size_t o = (size_t)m * N + n0 + (wave * NT + c) * 16 + 4 * grp;
+                *(f32x4 *)(Cs + o) = v[c];
+            }
+        }
+    }
+}
+
+// K range per split (a multiple of 128) and the number of splits that actually results
+static void split_geometry(int K, int ks, int *kps, int *ny)
+{
+    if (ks < 1) ks = 1;
+    *kps = ((K / 128 + ks - 1) / ks) * 128;
+    *ny = (K + *kps - 1) / *kps;
+}
+
+// SwiGLU gate/up GEMM, K split over the 4 waves of a block instead of over blocks (silu(gate)*up needs
+// the complete sums, so partial slabs would cost an extra pass).  A block owns 16 output columns: the gate
+// and the up tile; its waves interleave the 128-element K steps and fetch their activation fragments
+// straight from global memory (L2); the four partial accumulators meet in LDS.  Measured faster than the
+// chunk-staged kernel above for this shape (688 blocks keep more loads in flight than 172 could).
+template <bool PACKED, int MT>
+__global__ __launch_bounds__(256) void gemm_swiglu_kernel(const uint16_t *__restrict__ A, size_t a_plane,
+                                                          const uint16_t *__restrict__ Wg,
+                                                          const uint16_t *__restrict__ Wu, int M, int N, int K,
+                                                          uint16_t *__restrict__ Cact, size_t c_plane)
+{
+    constexpr int WAVES = 4;
+    __shared__ float red[WAVES][2][MT][64][4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int row = lane & 15, grp = lane >> 4;
+    const int n0 = blockIdx.x * 16;
+    const uint16_t *Wp[2] = {Wg + (size_t)(n0 + row) * K, Wu + (size_t)(n0 + row) * K};
+    const uint16_t *Ap[MT], *Al[MT];
+    bool a_live[MT];
+#pragma unroll
+    for (int t = 0; t < MT; t++) {
+        const int m = PACKED ? (row & 7) : t * 16 + row;
+        a_live[t] = m < M;
+        Ap[t] = A + ((PACKED && row >= 8) ? a_plane : 0) + (size_t)(a_live[t] ? m : 0) * K;
+        Al[t] = Ap[t] + a_plane;
+    }
+    f32x4 acc[2][MT];
+#pragma unroll
+    for (int c = 0; c < 2; c++)
+#pragma unroll
+        for (int t = 0; t < MT; t++) acc[c][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    const int nsteps = K / 128;
+    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int s = wave; s < nsteps; s += WAVES) {
+        const int k = s * 128 + grp * 32;
+        bf16x8 wv[2][4], av[MT][4], al[MT][4];
+#pragma unroll
+        for (int c = 0; c < 2; c++)
+#pragma unroll
+            for (int i = 0; i < 4; i++) wv[c][i] = *(const bf16x8 *)(Wp[c] + k + i * 8);
+#pragma unroll
+        for (int t = 0; t < MT; t++)
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                av[t][i] = a_live[t] ? *(const bf16x8 *)(Ap[t] + k + i * 8) : zero;
+                if (!PACKED) al[t][i] = a_live[t] ? *(const bf16x8 *)(Al[t] + k + i * 8) : zero;
+            }
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+#pragma unroll
+            for (int t = 0; t < MT; t++)
+#pragma unroll
+                for (int c = 0; c < 2; c++) {
+                    acc[c][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv[c][i], av[t][i], acc[c][t], 0, 0, 0);
+                    if (!PACKED)
+                        acc[c][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv[c][i], al[t][i], acc[c][t], 0, 0, 0);
+                }
     }
 #pragma unroll
-    for (int c = 0; c < NT; c++)
+    for (int c = 0; c < 2; c++)
 #pragma unroll
         for (int t = 0; t < MT; t++)
 #pragma unroll
             for (int r = 0; r < 4; r++) red[wave][c][t][lane][r] = acc[c][t][r];
     __syncthreads();
-    // element (slot, r) of a tile is D[n = 4*(slot/16)+r][m = slot%16]; 256 of them per tile
-    for (int e = threadIdx.x; e < 256; e += WAVES * 64) {
-        const int slot = e & 63, r = e >> 6;
-        const int nn = 4 * (slot >> 4) + r;
+    // tile element D[n = 4*(slot/16) + r][m' = slot%16] sits at red[.][c][t][slot][r]
+    constexpr int ROWS = PACKED ? 8 : 16 * MT;
+    for (int e = threadIdx.x; e < 16 * ROWS; e += 256) {
+        const int nn = e & 15, m = e >> 4;
+        if (m >= M) continue;
+        const int t = PACKED ? 0 : m >> 4;
+        const int slot = (nn >> 2) * 16 + (m & 15), r = nn & 3;
+        float v[2] = {0.f, 0.f};
 #pragma unroll
-        for (int t = 0; t < MT; t++) {
-            const int m = t * 16 + (slot & 15);
-            float v[NT];
+        for (int c = 0; c < 2; c++)
 #pragma unroll
-            for (int c = 0; c < NT; c++) {
-                v[c] = 0.f;
-#pragma unroll
-                for (int wv2 = 0; wv2 < WAVES; wv2++) v[c] += red[wv2][c][t][slot][r];
+            for (int wv2 = 0; wv2 < WAVES; wv2++) {
+                v[c] += red[wv2][c][t][slot][r];
+                if (PACKED) v[c] += red[wv2][c][t][slot + 8][r];
             }
-            if (m < M) {
-                if (MODE == GEMM_SWIGLU) {
-                    float g = v[0];
-                    float y = g / (1.0f + expf(-g)) * v[NT - 1];
-                    uint16_t hi = bf16_bits_rne(y);
-                    Cact[(size_t)m * N + n0 + nn] = hi;
-                    Cact[c_plane + (size_t)m * N + n0 + nn] = bf16_bits_rne(y - __uint_as_float((uint32_t)hi << 16));
-                } else if (MODE == GEMM_STORE) {
-                    C[(size_t)m * N + n0 + nn] = v[0];
-                    C[(size_t)m * N + n0 + 16 + nn] = v[NT - 1];
-                } else {
-                    C[(size_t)m * N + n0 + nn] += v[0];
-                }
-            }
-        }
+        const float y = v[0] / (1.0f + expf(-v[0])) * v[1];
+        const uint16_t hi = bf16_bits_rne(y);
+        const size_t o = (size_t)m * N + n0 + nn;
+        Cact[o] = hi;
+        Cact[c_plane + o] = bf16_bits_rne(y - __uint_as_float((uint32_t)hi << 16));
     }
 }
 
-template <int MT>
-static void skinny_dispatch(hipStream_t s, int mode, const void *A, size_t a_plane, WeightSeg w, int M, int N, int K,
-                            float *C, void *Cact, size_t c_plane)
+template <int MODE, int NT, int WAVES>
+static void stream_launch(hipStream_t s, const uint16_t *a, size_t a_plane, WeightSeg w, int M, int N, int K, int ks,
+                          float *C, size_t c_split_stride, uint16_t *ca, size_t c_plane)
 {
-    const uint16_t *a = (const uint16_t *)A;
-    uint16_t *ca = (uint16_t *)Cact;
-    if (mode == GEMM_SWIGLU)
-        hipLaunchKernelGGL((gemm_skinny_kernel<MT, GEMM_SWIGLU, 4, 2>), dim3(N / 16), dim3(256), 0, s, a, a_plane, w,
-                           M, N, K, C, ca, c_plane);
-    else if (mode == GEMM_STORE)
-        hipLaunchKernelGGL((gemm_skinny_kernel<MT, GEMM_STORE, 4, 2>), dim3(N / 32), dim3(256), 0, s, a, a_plane, w, M,
-                           N, K, C, ca, c_plane);
+    constexpr int COLS = (MODE == GEMM_SWIGLU ? NT / 2 : NT) * 16 * WAVES;
+    int kps, ny;
+    split_geometry(K, ks, &kps, &ny);
+    dim3 grid(N / COLS, ny), block(WAVES * 64);
+    if (M <= 8)
+        hipLaunchKernelGGL((gemm_stream_kernel<MODE, 16, NT, WAVES>), grid, block, 0, s, a, a_plane, w, M, N, K, kps, C,
+                           c_split_stride, ca, c_plane);
+    else if (M <= 16)
+        hipLaunchKernelGGL((gemm_stream_kernel<MODE, 32, NT, WAVES>), grid, block, 0, s, a, a_plane, w, M, N, K, kps, C,
+                           c_split_stride, ca, c_plane);
     else
-        hipLaunchKernelGGL((gemm_skinny_kernel<MT, GEMM_RESID, 8, 2>), dim3(N / 16), dim3(512), 0, s, a, a_plane, w, M,
-                           N, K, C, ca, c_plane);
+        hipLaunchKernelGGL((gemm_stream_kernel<MODE, 64, NT, WAVES>), grid, block, 0, s, a, a_plane, w, M, N, K, kps, C,
+                           c_split_stride, ca, c_plane);
 }
 
-hipError_t launch_gemm_skinny_bf16(hipStream_t s, int mode, const void *A, size_t a_plane, WeightSeg w, int M, int N,
-                                   int K, float *C, void *Cact, size_t c_plane)
+int g_skinny_tune[3][2] = {{4, 0}, {4, 0}, {4, 0}}; // [mode] -> {waves per block, K splits (0 = automatic)}
+
+// Number of K splits the launcher will use for this shape (the caller sizes and reduces the partials).
+int gemm_skinny_splits(int mode, int M, int N, int K)
 {
-    if (M < 1 || M > 32 || K % SK_KSTEP != 0) return hipErrorNotSupported;
-    if (mode == GEMM_STORE) {
-        if (N % 32 != 0 || w.n_per_seg % 32 != 0) return hipErrorNotSupported;
-    } else if (N % 16 != 0) {
-        return hipErrorNotSupported;
+    if (mode == GEMM_SWIGLU) return 1;
+    if (g_skinny_tune[mode][1] > 0) {
+        int kps, ny;
+        split_geometry(K, g_skinny_tune[mode][1], &kps, &ny);
+        return ny;
     }
+    const int waves = g_skinny_tune[mode][0];
+    const int blocks = N / (16 * waves);
+    int ks = 1;
+    while (blocks * ks < 768 && ks < 8 && K / (ks * 2) >= 512) ks *= 2; // about three blocks per CU
+    int kps, ny;
+    split_geometry(K, ks, &kps, &ny);
+    return ny;
+}
+
+// mode GEMM_STORE: C receives `splits` partial slabs [split][M][N] (split stride c_split_stride floats);
+// mode GEMM_SWIGLU: Cact receives the bf16 hi/lo planes.  GEMM_RESID is expressed by the caller as a
+// store into partial slabs followed by the fused add + norm kernel.
+hipError_t launch_gemm_skinny_bf16(hipStream_t s, int mode, const void *A, size_t a_plane, WeightSeg w, int M, int N,
+                                   int K, float *C, size_t c_split_stride, int splits, void *Cact, size_t c_plane)
+{
+    if (M < 1 || M > 32 || K % 128 != 0 || (mode != GEMM_STORE && mode != GEMM_SWIGLU)) return hipErrorNotSupported;
     for (int i = 0; i < 3; i++)
         if (w.p[i] && ((uintptr_t)w.p[i] & 15)) return hipErrorNotSupported;
-    if (((uintptr_t)A & 15) || (a_plane & 7)) return hipErrorNotSupported;
-    if (M <= 16) skinny_dispatch<1>(s, mode, A, a_plane, w, M, N, K, C, Cact, c_plane);
-    else skinny_dispatch<2>(s, mode, A, a_plane, w, M, N, K, C, Cact, c_plane);
+    if (((uintptr_t)A & 15) || (a_plane & 7) || (N & 3)) return hipErrorNotSupported;
+    const uint16_t *a = (const uint16_t *)A;
+    uint16_t *ca = (uint16_t *)Cact;
+    const int waves = g_skinny_tune[mode][0];
+    if (mode == GEMM_SWIGLU && g_skinny_tune[GEMM_SWIGLU][1] == 0) { // default: K split inside the block
+        if (N % 16 != 0) return hipErrorNotSupported;
+        const uint16_t *wg = (const uint16_t *)w.p[0], *wu = (const uint16_t *)w.p[1];
+        dim3 grid(N / 16), block(256);
+        if (M <= 8)
+            hipLaunchKernelGGL((gemm_swiglu_kernel<true, 1>), grid, block, 0, s, a, a_plane, wg, wu, M, N, K, ca, c_plane);
+        else if (M <= 16)
+            hipLaunchKernelGGL((gemm_swiglu_kernel<false, 1>), grid, block, 0, s, a, a_plane, wg, wu, M, N, K, ca, c_plane);
+        else
+            hipLaunchKernelGGL((gemm_swiglu_kernel<false, 2>), grid, block, 0, s, a, a_plane, wg, wu, M, N, K, ca, c_plane);
+        return hipGetLastError();
+    }
+    if (mode == GEMM_SWIGLU) {
+        if (waves == 4 && N % 64 == 0) stream_launch<GEMM_SWIGLU, 2, 4>(s, a, a_plane, w, M, N, K, 1, C, 0, ca, c_plane);
+        else if (waves == 8 && N % 128 == 0) stream_launch<GEMM_SWIGLU, 2, 8>(s, a, a_plane, w, M, N, K, 1, C, 0, ca, c_plane);
+        else if (N % 32 == 0) stream_launch<GEMM_SWIGLU, 2, 2>(s, a, a_plane, w, M, N, K, 1, C, 0, ca, c_plane);
+        else return hipErrorNotSupported;
+        return hipGetLastError();
+    }
+    if (waves == 8 && N % 128 == 0 && w.n_per_seg % 128 == 0)
+        stream_launch<GEMM_STORE, 1, 8>(s, a, a_plane, w, M, N, K, splits, C, c_split_stride, ca, c_plane);
+    else if (N % 64 == 0 && w.n_per_seg % 64 == 0)
+        stream_launch<GEMM_STORE, 1, 4>(s, a, a_plane, w, M, N, K, splits, C, c_split_stride, ca, c_plane);
+    else
+        return hipErrorNotSupported;
     return hipGetLastError();
 }

@@ -307,8 +307,61 @@ hipError_t launch_gemm_generic(hipStream_t s, int dtype, int mode, const void *A
 // qkv: fp32 [M][3*HD] (q | k | v).  Rotates q and k of every valid row at its
 // position (rotate-half pairing), writes q to qbuf and k, v into the cache in
 // place: K[head][off+pos][hd], Vt[head][hd][off+pos].
+// Residual update fused with the next RMSNorm: x[src] += sum of the split-K slabs of the
+// preceding GEMM (added in slab order), then out[j] = rmsnorm(x[src]) * g.  One block of 1024
+// threads per row; the loads of all slabs of an element are independent and go out together.
+#define ADDNORM_MAX_SLABS 8
 template <typename T>
-__global__ void rope_append_kernel(const float *qkv, PlanView pv, CtxView cv, int H, int hd, const float2 *rope,
+__global__ __launch_bounds__(1024) void add_rmsnorm_kernel(float *x, const float *part, int n_slabs, size_t slab_stride,
+                                                           const float *g, const int32_t *row_map, int d, float eps,
+                                                           T *out, size_t plane)
+{
+    __shared__ float red[32];
+    int j = blockIdx.x;
+    int src = row_map ? row_map[j] : j;
+    float *xr = x + (size_t)src * d;
+    const float *pr = part + (size_t)src * d;
+    float ss = 0.f;
+    const int nvec = d / 4; // d is a multiple of 4 (checked at load)
+    for (int v = threadIdx.x; v < nvec; v += blockDim.x) {
+        float4 a = *(const float4 *)(xr + 4 * v);
+        float4 p[ADDNORM_MAX_SLABS];
+#pragma unroll
+        for (int s = 0; s < ADDNORM_MAX_SLABS; s++)
+            if (s < n_slabs) p[s] = *(const float4 *)(pr + (size_t)s * slab_stride + 4 * v);
+#pragma unroll
+        for (int s = 0; s < ADDNORM_MAX_SLABS; s++)
+            if (s < n_slabs) {
+                a.x += p[s].x;
+                a.y += p[s].y;
+                a.z += p[s].z;
+                a.w += p[s].w;
+            }
+        *(float4 *)(xr + 4 * v) = a;
+        ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
+    }
+    ss = block_sum(ss, red);
+    float inv = 1.0f / sqrtf(ss / (float)d + eps);
+    for (int i = threadIdx.x; i < d; i += blockDim.x) store_act(out, (size_t)j * d + i, plane, xr[i] * inv * g[i]);
+}
+
+hipError_t launch_add_rmsnorm(hipStream_t s, int dtype, float *x, const float *part, int n_slabs, size_t slab_stride,
+                              const float *g, const int32_t *row_map, int n_rows, int d, float eps, void *out,
+                              size_t out_plane)
+{
+    if (n_slabs > ADDNORM_MAX_SLABS || (d & 3)) return hipErrorInvalidValue;
+    if (dtype == SD_BF16)
+        hipLaunchKernelGGL(add_rmsnorm_kernel<bf16_t>, dim3(n_rows), dim3(1024), 0, s, x, part, n_slabs, slab_stride, g,
+                           row_map, d, eps, (bf16_t *)out, out_plane);
+    else
+        hipLaunchKernelGGL(add_rmsnorm_kernel<float>, dim3(n_rows), dim3(1024), 0, s, x, part, n_slabs, slab_stride, g,
+                           row_map, d, eps, (float *)out, out_plane);
+    return hipGetLastError();
+}
+
+template <typename T>
+__global__ void rope_append_kernel(const float *qkv, int n_slabs, size_t slab_stride, PlanView pv, CtxView cv, int H,
+                                   int hd, const float2 *rope,
                                    int max_pos, T *qbuf, size_t q_plane, T *Kl, T *Vtl, int64_t total_cap)
 {
     int r = blockIdx.x;
@@ -329,9 +382,29 @@ __global__ void rope_append_kernel(const float *qkv, PlanView pv, CtxView cv, in
             continue;
         }
         float2 cs = rope[(size_t)pos * half + e];
-        float q0 = row[h * hd + e], q1 = row[h * hd + e + half];
-        float k0 = row[HD + h * hd + e], k1 = row[HD + h * hd + e + half];
-        float v0 = row[2 * HD + h * hd + e], v1 = row[2 * HD + h * hd + e + half];
+        float q0 = 0.f, q1 = 0.f, k0 = 0.f, k1 = 0.f, v0 = 0.f, v1 = 0.f;
+        float ld[ADDNORM_MAX_SLABS][6];
+#pragma unroll
+        for (int sl = 0; sl < ADDNORM_MAX_SLABS; sl++) // split-K slabs of the QKV GEMM: all loads go out first
+            if (sl < n_slabs) {
+                const float *rs = row + (size_t)sl * slab_stride;
+                ld[sl][0] = rs[h * hd + e];
+                ld[sl][1] = rs[h * hd + e + half];
+                ld[sl][2] = rs[HD + h * hd + e];
+                ld[sl][3] = rs[HD + h * hd + e + half];
+                ld[sl][4] = rs[2 * HD + h * hd + e];
+                ld[sl][5] = rs[2 * HD + h * hd + e + half];
+            }
+#pragma unroll
+        for (int sl = 0; sl < ADDNORM_MAX_SLABS; sl++) // ... and are added in slab order
+            if (sl < n_slabs) {
+                q0 += ld[sl][0];
+                q1 += ld[sl][1];
+                k0 += ld[sl][2];
+                k1 += ld[sl][3];
+                v0 += ld[sl][4];
+                v1 += ld[sl][5];
+            }
         store_act(qbuf, (size_t)r * HD + h * hd + e, q_plane, q0 * cs.x - q1 * cs.y);
         store_act(qbuf, (size_t)r * HD + h * hd + e + half, q_plane, q1 * cs.x + q0 * cs.y);
         T *kd = Kl + ((size_t)h * total_cap + off + pos) * hd;
@@ -343,16 +416,17 @@ __global__ void rope_append_kernel(const float *qkv, PlanView pv, CtxView cv, in
     }
 }
 
-hipError_t launch_rope_append(hipStream_t s, int dtype, const float *qkv, PlanView pv, CtxView cv, int M, int H,
-                              int hd, const float2 *rope, int max_pos, void *qbuf, size_t q_plane, void *Kl, void *Vtl,
-                              int64_t total_cap)
+hipError_t launch_rope_append(hipStream_t s, int dtype, const float *qkv, int n_slabs, size_t slab_stride, PlanView pv,
+                              CtxView cv, int M, int H, int hd, const float2 *rope, int max_pos, void *qbuf,
+                              size_t q_plane, void *Kl, void *Vtl, int64_t total_cap)
 {
+    if (n_slabs > ADDNORM_MAX_SLABS) return hipErrorInvalidValue;
     if (dtype == SD_BF16)
-        hipLaunchKernelGGL(rope_append_kernel<bf16_t>, dim3(M), dim3(256), 0, s, qkv, pv, cv, H, hd, rope, max_pos,
-                           (bf16_t *)qbuf, q_plane, (bf16_t *)Kl, (bf16_t *)Vtl, total_cap);
+        hipLaunchKernelGGL(rope_append_kernel<bf16_t>, dim3(M), dim3(1024), 0, s, qkv, n_slabs, slab_stride, pv, cv, H,
+                           hd, rope, max_pos, (bf16_t *)qbuf, q_plane, (bf16_t *)Kl, (bf16_t *)Vtl, total_cap);
     else
-        hipLaunchKernelGGL(rope_append_kernel<float>, dim3(M), dim3(256), 0, s, qkv, pv, cv, H, hd, rope, max_pos,
-                           (float *)qbuf, q_plane, (float *)Kl, (float *)Vtl, total_cap);
+        hipLaunchKernelGGL(rope_append_kernel<float>, dim3(M), dim3(1024), 0, s, qkv, n_slabs, slab_stride, pv, cv, H,
+                           hd, rope, max_pos, (float *)qbuf, q_plane, (float *)Kl, (float *)Vtl, total_cap);
     return hipGetLastError();
 }
 

@@ -97,6 +97,14 @@ extern "C" int sd_set_option(const char *name, int32_t value)
         g_force_generic = value == 1 ? 3 : value;
         return SD_OK;
     }
+    if (!strcmp(name, "skinny_tune")) { // value = mode*10000 + tiles_per_wave*100 + waves_per_block (sweeps)
+        int mode = value / 10000, nt = (value / 100) % 100, wv = value % 100;
+        if (mode < 0 || mode > 2 || (nt != 1 && nt != 2 && nt != 4) || (wv != 4 && wv != 8 && wv != 16) || nt * wv > 32)
+            return sd_fail(SD_EINVAL, "sd_set_option: bad skinny_tune value");
+        g_skinny_tune[mode][0] = nt;
+        g_skinny_tune[mode][1] = wv;
+        return SD_OK;
+    }
     if (!strcmp(name, "profile")) { // 1: start a fresh measurement, 0: stop recording (totals stay readable)
         prof_fold();
         if (value) {
@@ -167,6 +175,10 @@ extern "C" int sd_load_model(const sd_model_config *cfg, const sd_weights *w, sd
     alloc(&m->act, planes * M * (size_t)c.d_ffn * m->esz);
     alloc((void **)&m->logits, M * (size_t)c.vocab * 4);
     alloc((void **)&m->part, m->part_floats * 4);
+    m->gpart_q_floats = 8 * M * 3 * d;
+    m->gpart_r_floats = 8 * M * d;
+    alloc((void **)&m->gpart_q, m->gpart_q_floats * 4);
+    alloc((void **)&m->gpart_r, m->gpart_r_floats * 4);
     alloc((void **)&m->rope, (size_t)c.max_pos * (c.head_dim / 2) * sizeof(float2));
     alloc((void **)&m->plan_mem, (5 * M + 3 * M) * sizeof(int32_t));
     if (e != hipSuccess) {
@@ -210,6 +222,8 @@ extern "C" int sd_free_model(sd_model *m)
     (void)hipFree(m->act);
     (void)hipFree(m->logits);
     (void)hipFree(m->part);
+    (void)hipFree(m->gpart_q);
+    (void)hipFree(m->gpart_r);
     (void)hipFree(m->rope);
     (void)hipFree(m->plan_mem);
     delete m;
@@ -457,14 +471,25 @@ extern "C" int sd_last_logits(sd_model *m, float *out, int32_t max_rows, int32_t
 }
 
 // ---------------------------------------------------------------- one decoder forward
-static hipError_t gemm(sd_model *m, hipStream_t s, int mode, const void *A, size_t a_plane, WeightSeg w, int M, int N,
-                       int K, float *C, void *Cact, size_t c_plane)
+static hipError_t gemm_generic(sd_model *m, hipStream_t s, int mode, const void *A, size_t a_plane, WeightSeg w, int M,
+                               int N, int K, float *C, void *Cact, size_t c_plane)
 {
-    if (m->cfg.dtype == SD_BF16 && !(g_force_generic & 1)) {
-        hipError_t e = launch_gemm_skinny_bf16(s, mode, A, a_plane, w, M, N, K, C, Cact, c_plane);
-        if (e != hipErrorNotSupported) return e;
-    }
     return launch_gemm_generic(s, m->cfg.dtype, mode, A, a_plane, w, M, N, K, C, Cact, c_plane);
+}
+
+// Weight-streaming path for a GEMM whose fp32 result is consumed as split-K slabs.  Returns the number
+// of slabs written to `slabs` (slab stride M*N floats), 0 if the shape is outside the kernel's domain.
+static int stream_gemm(sd_model *m, hipStream_t s, const void *A, size_t a_plane, WeightSeg w, int M, int N, int K,
+                       float *slabs, size_t slabs_floats, int force_splits, hipError_t *err)
+{
+    *err = hipSuccess;
+    if (m->cfg.dtype != SD_BF16 || (g_force_generic & 1) || M > 32) return 0;
+    int ns = force_splits > 0 ? force_splits : gemm_skinny_splits(GEMM_STORE, M, N, K);
+    if ((size_t)ns * M * N > slabs_floats || ns > 8) ns = 1;
+    hipError_t e = launch_gemm_skinny_bf16(s, GEMM_STORE, A, a_plane, w, M, N, K, slabs, (size_t)M * N, ns, nullptr, 0);
+    if (e == hipErrorNotSupported) return 0;
+    *err = e;
+    return ns;
 }
 
 #define FWD(expr)                                                                                  \
@@ -477,6 +502,11 @@ static hipError_t gemm(sd_model *m, hipStream_t s, int mode, const void *A, size
 // Rows are laid out as R slots per selected sequence.  Logits are produced for
 // n_lm rows (every row for verify, the last valid row of each sequence for
 // draft, none when want_logits is false).
+//
+// Launch schedule per layer (bf16, few rows): [add+]rmsnorm -> QKV GEMM (split-K slabs) -> RoPE + cache
+// append (adds the slabs) -> attention -> O GEMM (slabs) -> add + rmsnorm -> gate/up GEMM with SwiGLU
+// epilogue -> down GEMM (slabs, added by the next layer's add + rmsnorm).  Shapes outside the MFMA
+// kernels' domain, and fp32 models, take the reference kernels with the same data flow.
 static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, int R, int n_seq,
                    const int32_t *seq_ids, int upto_off, const int32_t *cand, int gamma, int cand_idx,
                    bool want_logits)
@@ -488,20 +518,37 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
     PlanView pv = m->plan;
     int kv_upper = c->len_upper + SD_MAX_GAMMA + 1;
     size_t lstride = (size_t)d * c->total_cap * m->esz;
+    hipError_t ge;
     { ProfScope ps(T_PLAN, s);
     FWD(launch_plan(s, mode, R, n_seq, seq_ids, cv, slot, upto_off, cand, gamma, cand_idx, V, pv)); }
     { ProfScope ps(T_EMBED, s);
     FWD(launch_embed(s, cf.dtype, m->embed, pv.row_tok, M, d, m->x)); }
+    int pending = 0; // split-K slabs of the previous down projection not yet added to x
     for (int l = 0; l < cf.n_layers; l++) {
         void *Kl = (char *)c->kcache[slot] + l * lstride, *Vtl = (char *)c->vcache[slot] + l * lstride;
         { ProfScope ps(T_RMSNORM, s);
-        FWD(launch_rmsnorm(s, cf.dtype, m->x, m->norm_attn[l], nullptr, M, d, cf.rms_eps, m->abuf, m->plane_d)); }
+        if (pending)
+            FWD(launch_add_rmsnorm(s, cf.dtype, m->x, m->gpart_r, pending, (size_t)M * d, m->norm_attn[l], nullptr, M, d,
+                                   cf.rms_eps, m->abuf, m->plane_d));
+        else
+            FWD(launch_rmsnorm(s, cf.dtype, m->x, m->norm_attn[l], nullptr, M, d, cf.rms_eps, m->abuf, m->plane_d));
+        }
+        pending = 0;
         WeightSeg wqkv = {{m->wq[l], m->wk[l], m->wv[l]}, d};
+        int nq_slabs;
+        const float *qkv_src;
         { ProfScope ps(T_QKV, s);
-        FWD(gemm(m, s, GEMM_STORE, m->abuf, m->plane_d, wqkv, M, 3 * d, d, m->qkv, nullptr, 0)); }
+        nq_slabs = stream_gemm(m, s, m->abuf, m->plane_d, wqkv, M, 3 * d, d, m->gpart_q, m->gpart_q_floats, 0, &ge);
+        FWD(ge);
+        qkv_src = m->gpart_q;
+        if (!nq_slabs) {
+            FWD(gemm_generic(m, s, GEMM_STORE, m->abuf, m->plane_d, wqkv, M, 3 * d, d, m->qkv, nullptr, 0));
+            nq_slabs = 1;
+            qkv_src = m->qkv;
+        } }
         { ProfScope ps(T_ROPE, s);
-        FWD(launch_rope_append(s, cf.dtype, m->qkv, pv, cv, M, H, hd, m->rope, cf.max_pos, m->qbuf, m->plane_d, Kl,
-                               Vtl, c->total_cap)); }
+        FWD(launch_rope_append(s, cf.dtype, qkv_src, nq_slabs, (size_t)M * 3 * d, pv, cv, M, H, hd, m->rope, cf.max_pos,
+                               m->qbuf, m->plane_d, Kl, Vtl, c->total_cap)); }
         hipError_t ea = hipErrorNotSupported;
         { ProfScope ps(T_ATTN, s);
         if (cf.dtype == SD_BF16 && !(g_force_generic & 2))
@@ -514,24 +561,47 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
         if (ea == hipErrorNotSupported) return sd_fail(SD_ECAP, "forward: context too long for the generic attention kernel");
         FWD(ea);
         WeightSeg wo = {{m->wo[l], nullptr, nullptr}, d};
+        int no_slabs;
         { ProfScope ps(T_OPROJ, s);
-        FWD(gemm(m, s, GEMM_RESID, m->obuf, m->plane_d, wo, M, d, d, m->x, nullptr, 0)); }
+        no_slabs = stream_gemm(m, s, m->obuf, m->plane_d, wo, M, d, d, m->gpart_r, m->gpart_r_floats, 0, &ge);
+        FWD(ge);
+        if (!no_slabs) FWD(gemm_generic(m, s, GEMM_RESID, m->obuf, m->plane_d, wo, M, d, d, m->x, nullptr, 0)); }
         { ProfScope ps(T_RMSNORM, s);
-        FWD(launch_rmsnorm(s, cf.dtype, m->x, m->norm_ffn[l], nullptr, M, d, cf.rms_eps, m->abuf, m->plane_d)); }
+        if (no_slabs)
+            FWD(launch_add_rmsnorm(s, cf.dtype, m->x, m->gpart_r, no_slabs, (size_t)M * d, m->norm_ffn[l], nullptr, M, d,
+                                   cf.rms_eps, m->abuf, m->plane_d));
+        else
+            FWD(launch_rmsnorm(s, cf.dtype, m->x, m->norm_ffn[l], nullptr, M, d, cf.rms_eps, m->abuf, m->plane_d));
+        }
         WeightSeg wgu = {{m->wgate[l], m->wup[l], nullptr}, F};
         { ProfScope ps(T_GATEUP, s);
-        FWD(gemm(m, s, GEMM_SWIGLU, m->abuf, m->plane_d, wgu, M, F, d, nullptr, m->act, m->plane_f)); }
+        hipError_t eg = hipErrorNotSupported;
+        if (cf.dtype == SD_BF16 && !(g_force_generic & 1))
+            eg = launch_gemm_skinny_bf16(s, GEMM_SWIGLU, m->abuf, m->plane_d, wgu, M, F, d, nullptr, 0, 1, m->act,
+                                         m->plane_f);
+        if (eg == hipErrorNotSupported)
+            eg = gemm_generic(m, s, GEMM_SWIGLU, m->abuf, m->plane_d, wgu, M, F, d, nullptr, m->act, m->plane_f);
+        FWD(eg); }
         WeightSeg wd = {{m->wdown[l], nullptr, nullptr}, d};
         { ProfScope ps(T_DOWN, s);
-        FWD(gemm(m, s, GEMM_RESID, m->act, m->plane_f, wd, M, d, F, m->x, nullptr, 0)); }
+        pending = stream_gemm(m, s, m->act, m->plane_f, wd, M, d, F, m->gpart_r, m->gpart_r_floats, 0, &ge);
+        FWD(ge);
+        if (!pending) FWD(gemm_generic(m, s, GEMM_RESID, m->act, m->plane_f, wd, M, d, F, m->x, nullptr, 0)); }
     }
     if (want_logits) {
         int n_lm = mode == PLAN_VERIFY ? M : n_seq;
         { ProfScope ps(T_RMSNORM, s);
-        FWD(launch_rmsnorm(s, cf.dtype, m->x, m->final_norm, pv.lm_row, n_lm, d, cf.rms_eps, m->abuf, m->plane_d)); }
+        if (pending)
+            FWD(launch_add_rmsnorm(s, cf.dtype, m->x, m->gpart_r, pending, (size_t)M * d, m->final_norm, pv.lm_row, n_lm,
+                                   d, cf.rms_eps, m->abuf, m->plane_d));
+        else
+            FWD(launch_rmsnorm(s, cf.dtype, m->x, m->final_norm, pv.lm_row, n_lm, d, cf.rms_eps, m->abuf, m->plane_d));
+        }
         WeightSeg wl = {{m->lm_head, nullptr, nullptr}, V};
         { ProfScope ps(T_LMHEAD, s);
-        FWD(gemm(m, s, GEMM_STORE, m->abuf, m->plane_d, wl, n_lm, V, d, m->logits, nullptr, 0)); }
+        int nl = stream_gemm(m, s, m->abuf, m->plane_d, wl, n_lm, V, d, m->logits, (size_t)cf.max_rows * V, 1, &ge);
+        FWD(ge);
+        if (!nl) FWD(gemm_generic(m, s, GEMM_STORE, m->abuf, m->plane_d, wl, n_lm, V, d, m->logits, nullptr, 0)); }
         m->last_lm_rows = n_lm;
     }
     return SD_OK;

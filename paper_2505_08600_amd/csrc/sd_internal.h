@@ -109,7 +109,9 @@ struct sd_model {
     void *act;      // [planes][max_rows][d_ffn]
     size_t plane_d, plane_f; // element offsets between the planes
     float *logits;  // [max_rows][vocab]
-    float *part;    // split-K / split-KV partial results
+    float *part;    // split-KV partial results of the attention kernel
+    float *gpart_q, *gpart_r; // split-K partial slabs of the weight-streaming GEMMs (QKV; O / down)
+    size_t gpart_q_floats, gpart_r_floats;
     size_t part_floats;
     float2 *rope;   // [max_pos][head_dim/2] (cos, sin)
     int32_t *plan_mem;
@@ -155,6 +157,7 @@ int sd_fail(int code, const std::string &s);
     } while (0)
 
 extern int g_force_generic;
+extern int g_skinny_tune[3][2]; // per GEMM mode {column tiles per wave, waves per block}
 
 // ---------------------------------------------------------------- kernel launchers
 // (each returns a hipError_t from hipGetLastError after the launch)
@@ -165,7 +168,8 @@ hipError_t launch_rmsnorm(hipStream_t s, int dtype, const float *x, const float 
                           int n_rows, int d, float eps, void *out, size_t out_plane);
 hipError_t launch_gemm_generic(hipStream_t s, int dtype, int mode, const void *A, size_t a_plane, WeightSeg w, int M,
                                int N, int K, float *C, void *Cact, size_t c_plane);
-hipError_t launch_rope_append(hipStream_t s, int dtype, const float *qkv, PlanView pv, CtxView cv, int M, int H,
+hipError_t launch_rope_append(hipStream_t s, int dtype, const float *qkv, int n_slabs, size_t slab_stride, PlanView pv,
+                              CtxView cv, int M, int H,
                               int hd, const float2 *rope, int max_pos, void *qbuf, size_t q_plane, void *Kl, void *Vtl,
                               int64_t total_cap);
 hipError_t launch_attn_generic(hipStream_t s, int dtype, const void *qbuf, size_t q_plane, const void *Kl,
@@ -184,8 +188,14 @@ hipError_t launch_set_kv(hipStream_t s, int dtype, const void *k_rows, const voi
                          int64_t seq_off, int64_t total_cap, void *Kl, void *Vtl);
 
 // optimised bf16 paths (return hipErrorNotSupported when the shape is outside their domain)
+// GEMM_STORE: C receives `splits` partial slabs (slab stride c_split_stride floats) that the consumer adds;
+// GEMM_SWIGLU: Cact receives the bf16 hi/lo planes.  gemm_skinny_splits tells how many slabs to expect.
+int gemm_skinny_splits(int mode, int M, int N, int K);
 hipError_t launch_gemm_skinny_bf16(hipStream_t s, int mode, const void *A, size_t a_plane, WeightSeg w, int M, int N,
-                                   int K, float *C, void *Cact, size_t c_plane);
+                                   int K, float *C, size_t c_split_stride, int splits, void *Cact, size_t c_plane);
+hipError_t launch_add_rmsnorm(hipStream_t s, int dtype, float *x, const float *part, int n_slabs, size_t slab_stride,
+                              const float *g, const int32_t *row_map, int n_rows, int d, float eps, void *out,
+                              size_t out_plane);
 hipError_t launch_attn_mfma_bf16(hipStream_t s, const void *qbuf, size_t q_plane, const void *Kl, const void *Vtl,
                                  PlanView pv, CtxView cv, int R, int n_seq, int H, int hd, int64_t total_cap,
                                  int len_upper, float *part, size_t part_floats, void *obuf, size_t o_plane);
