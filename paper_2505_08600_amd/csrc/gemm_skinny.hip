@@ -209,6 +209,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_stream_kernel(const uint16_t 
 static void split_geometry(int K, int ks, int *kps, int *ny)
 {
     if (ks < 1) ks = 1;
+    if (K < 128) K = 128;
     *kps = ((K / 128 + ks - 1) / ks) * 128;
     *ny = (K + *kps - 1) / *kps;
 }
@@ -325,7 +326,7 @@ int g_skinny_tune[3][2] = {{4, 0}, {4, 0}, {4, 0}}; // [mode] -> {waves per bloc
 // Number of K splits the launcher will use for this shape (the caller sizes and reduces the partials).
 int gemm_skinny_splits(int mode, int M, int N, int K)
 {
-    if (mode == GEMM_SWIGLU) return 1;
+    if (mode == GEMM_SWIGLU || K < 128 || K % 128 != 0) return 1; // (the launcher rejects such K)
     if (g_skinny_tune[mode][1] > 0) {
         int kps, ny;
         split_geometry(K, g_skinny_tune[mode][1], &kps, &ny);

@@ -144,11 +144,64 @@ def oracle_steps(tseq, dseq, ctx_tokens, gamma, T, n_steps, seed, seq=0):
     return out, ctx_t
 
 
+def check_draft_step(s, cg, qg, T, dtype, V):
+    """Compare one sequence's HIP draft output (cand cg [gamma], q qg [gamma][V] or None) with the
+    oracle's step record.  -> (flagged, first differing candidate index or None, max |dq|)"""
+    thr = MARGIN_THR[dtype]
+    gamma = len(s.cand)
+    first_bad = None
+    for i in range(gamma):
+        if cg[i] != s.cand[i]:
+            first_bad = i
+            break
+    if first_bad is not None:
+        if T > 0:  # valid iff u is within base + L1(q_gpu, q_oracle) of the HIP token's interval
+            l1 = float(np.abs(qg[first_bad].astype(np.float64) - s.q[first_bad]).sum())
+            mg = oracle.cdf_distance(s.q[first_bad], s.u_draft[first_bad], int(cg[first_bad])) \
+                if 0 <= cg[first_bad] < V else 1.0
+            lim = thr + l1
+        else:
+            mg, lim = s.draft_margins[first_bad], GREEDY_GAP_THR[dtype]
+        assert mg < lim, f"draft candidate {first_bad} differs ({cg} vs {s.cand}), margin {mg} lim {lim}"
+    dq = 0.0
+    if T > 0:
+        upto = gamma if first_bad is None else first_bad + 1
+        dq = float(np.abs(qg[:upto] - s.q[:upto]).max())
+        assert dq <= 50 * LOGIT_TOL[dtype], f"draft q differs by {dq}"
+    return first_bad is not None, first_bad, dq
+
+
+def check_verify_step(s, na, nx, lg, T, dtype, V):
+    """Compare one sequence's HIP verify output (n_acc, next token, logits [gamma+1][V]) with the
+    oracle's step record.  -> (flagged, margin beyond the base threshold, logits rel err)"""
+    thr = MARGIN_THR[dtype]
+    gamma = len(s.cand)
+    ref = s.logits.astype(np.float64)
+    rel = float(np.max(np.abs(lg.astype(np.float64) - ref) / np.max(np.abs(ref), axis=-1, keepdims=True)))
+    assert rel <= LOGIT_TOL[dtype], f"logits rel err {rel}"
+    if (na, nx) == (s.n_acc, s.next_token):
+        return False, False, rel
+    delta = float(np.abs(lg.astype(np.float64) - ref).max())
+    eta = float(np.expm1(2.0 * delta / T)) if T > 0 else 0.0
+    if na != s.n_acc:      # the accept test (or argmax match) at the first differing position
+        i = min(s.n_acc, na)
+        mg = float(s.verify_margins[i])
+        lim = thr + (float(s.u_verify[i]) + mg) * eta if T > 0 else 2.0 * delta
+    elif T > 0:            # same prefix, other next token
+        w = oracle.next_weights(s.logits, s.q, s.n_acc, T)
+        mg = oracle.cdf_distance(w, s.u_verify[gamma], nx) if 0 <= nx < V else 1.0
+        lim = thr + 2.0 * eta / float(w.sum())
+    else:
+        mg, lim = float(s.verify_margins[gamma]), 2.0 * delta
+    assert mg < lim, (f"verify differs: gpu ({na},{nx}) oracle ({s.n_acc},{s.next_token}), "
+                      f"margin {mg} lim {lim} delta {delta}")
+    return True, mg >= (thr if T > 0 else 0.0), rel
+
+
 def lockstep(pair: Pair, ctx: api.Context, steps, gamma, T) -> ParityStats:
     """Run the HIP draft and verify of sequence 0 along the oracle's recorded steps and
     compare every output; commits the oracle's result after each step."""
     dtype = pair.shape_t.dtype
-    thr = MARGIN_THR[dtype]
     V = pair.shape_t.vocab
     st = ParityStats()
     cand_g = torch.zeros((1, gamma), dtype=torch.int32, device="cuda")
@@ -160,28 +213,12 @@ def lockstep(pair: Pair, ctx: api.Context, steps, gamma, T) -> ParityStats:
         ud = dev(s.u_draft[None]) if T > 0 else None
         api.sd_draft(pair.gd, ctx, None, 1, gamma, T, ud, cand_g, q_g)
         cg = cand_g.cpu().numpy()[0]
-        flagged = False
-        first_bad = None
-        for i in range(gamma):
-            if cg[i] != s.cand[i]:
-                first_bad = i
-                break
-        if first_bad is not None:
-            if T > 0:  # valid iff u is within base + L1(q_gpu, q_oracle) of the HIP token's interval
-                l1 = float(np.abs(q_g[0, first_bad].cpu().numpy().astype(np.float64) - s.q[first_bad]).sum())
-                mg = oracle.cdf_distance(s.q[first_bad], s.u_draft[first_bad], int(cg[first_bad])) \
-                    if 0 <= cg[first_bad] < V else 1.0
-                lim = thr + l1
-            else:
-                mg, lim = s.draft_margins[first_bad], GREEDY_GAP_THR[dtype]
-            assert mg < lim, f"step {k}: draft candidate {first_bad} differs ({cg} vs {s.cand}), margin {mg} lim {lim}"
-            flagged = True
-        if T > 0:
-            upto = gamma if first_bad is None else first_bad + 1
-            qg = q_g.cpu().numpy()[0]
-            dq = float(np.abs(qg[:upto] - s.q[:upto]).max())
-            st.max_q_abs = max(st.max_q_abs, dq)
-            assert dq <= 50 * LOGIT_TOL[dtype], f"step {k}: draft q differs by {dq}"
+        qg = q_g.cpu().numpy()[0] if T > 0 else None
+        try:
+            f1, first_bad, dq = check_draft_step(s, cg, qg, T, dtype, V)
+        except AssertionError as e:
+            raise AssertionError(f"step {k}: {e}") from None
+        st.max_q_abs = max(st.max_q_abs, dq)
         # ---- verify (Figure 1b) on the ORACLE's candidates and q
         cand_in = dev(s.cand[None].astype(np.int32))
         q_in = dev(s.q[None]) if T > 0 else None
@@ -189,25 +226,12 @@ def lockstep(pair: Pair, ctx: api.Context, steps, gamma, T) -> ParityStats:
         api.sd_verify(pair.gt, ctx, None, 1, gamma, T, cand_in, q_in, uv, nacc_g, next_g, commit=False)
         na, nx = int(nacc_g.item()), int(next_g.item())
         lg = pair.gt.last_logits().cpu().numpy()
-        rel = st.merge_logits(lg, s.logits.astype(np.float64))
-        assert rel <= LOGIT_TOL[dtype], f"step {k}: logits rel err {rel}"
-        if (na, nx) != (s.n_acc, s.next_token):
-            delta = float(np.abs(lg.astype(np.float64) - s.logits).max())
-            eta = float(np.expm1(2.0 * delta / T)) if T > 0 else 0.0
-            if na != s.n_acc:      # the accept test (or argmax match) at the first differing position
-                i = min(s.n_acc, na)
-                mg = float(s.verify_margins[i])
-                lim = thr + (float(s.u_verify[i]) + mg) * eta if T > 0 else 2.0 * delta
-            elif T > 0:            # same prefix, other next token
-                w = oracle.next_weights(s.logits, s.q, s.n_acc, T)
-                mg = oracle.cdf_distance(w, s.u_verify[gamma], nx) if 0 <= nx < V else 1.0
-                lim = thr + 2.0 * eta / float(w.sum())
-            else:
-                mg, lim = float(s.verify_margins[gamma]), 2.0 * delta
-            assert mg < lim, (f"step {k}: verify differs: gpu ({na},{nx}) oracle ({s.n_acc},{s.next_token}), "
-                              f"margin {mg} lim {lim} delta {delta}")
-            flagged = True
-            st.beyond_base += int(mg >= (thr if T > 0 else 0.0))
+        try:
+            f2, beyond, rel = check_verify_step(s, na, nx, lg, T, dtype, V)
+        except AssertionError as e:
+            raise AssertionError(f"step {k}: {e}") from None
+        st.max_logit_rel = max(st.max_logit_rel, rel)
+        st.beyond_base += int(beyond)
         # ---- commit the oracle's result (teacher forcing)
         api.sd_commit(ctx, None, 1, gamma, cand_in, dev(np.array([s.n_acc], np.int32)),
                       dev(np.array([s.next_token], np.int32)))
@@ -216,7 +240,7 @@ def lockstep(pair: Pair, ctx: api.Context, steps, gamma, T) -> ParityStats:
             ctx.truncate(pair.gd, 0, s.n_ctx - 1 + first_bad)
             api.sd_prefill(pair.gd, ctx, None, 1, gamma + 2)
         st.steps += 1
-        st.flagged += int(flagged)
+        st.flagged += int(f1 or f2)
         st.n_acc.append(s.n_acc)
     torch.cuda.synchronize()
     return st

@@ -298,3 +298,90 @@ def test_capacity_and_state_errors_are_reported_not_faulted(tiny_pair):
     nt, _ = ctx.sync()
     assert nt[0] <= 64
     ctx.close()
+
+
+def test_config3_routed_heterogeneous_drafts_small():
+    """BASELINE config 3's structure at small widths: a batch of ragged prompts, each routed by the
+    linear classifier to one of four drafts of different shapes; every draft decodes its group
+    (seq_ids), the target verifies all sequences in one call (T = 0.7, gamma = 5).  Every
+    sequence must behave exactly as it does alone in the oracle."""
+    _say("config 3 (small): routed heterogeneous drafts")
+    gamma, T, B, n_tok, seed = 5, 0.7, 10, 18, 91
+    st_ = dg.SHAPES["small_target_bf16"]
+    V = st_.vocab
+    dshapes = [dg.ModelShape("d_a", 1, 128, 2, 64, 384, V, dg.BF16), dg.ModelShape("d_b", 2, 128, 2, 64, 256, V, dg.BF16),
+               dg.ModelShape("d_c", 1, 256, 4, 64, 512, V, dg.BF16), dg.ModelShape("d_d", 1, 64, 1, 64, 128, V, dg.BF16)]
+    wt = dg.make_weights(st_, seed, BF16_LM_SCALE)
+    wds = [dg.make_weights(sh, seed + 1 + i, BF16_LM_SCALE) for i, sh in enumerate(dshapes)]
+    ot = oracle.OracleModel(st_, wt)
+    ods = [oracle.OracleModel(sh, w) for sh, w in zip(dshapes, wds)]
+    gt = api.Model(st_, wt, max_rows=B * (gamma + 1), max_pos=256)
+    gds = [api.Model(sh, w, max_rows=2 * B, max_pos=256) for sh, w in zip(dshapes, wds)]
+    # routing: GPU classifier vs oracle
+    Wr, br = dg.make_router(seed)
+    emb = dg.make_prompt_embeddings(seed, B)
+    ids_g = torch.zeros(B, dtype=torch.int32, device="cuda")
+    api.sd_route(H.dev(Wr), H.dev(br), H.dev(emb), ids_g)
+    route = oracle.route(Wr, br, emb)
+    assert np.array_equal(ids_g.cpu().numpy(), route)
+    groups = [[b for b in range(B) if route[b] == g] for g in range(4)]
+    assert sum(1 for g in groups if g) >= 3, groups
+    lens = dg.make_prompt_lengths(seed, B, 16, 120)
+    prompts = [[int(t) for t in dg.make_prompt(seed, b, int(lens[b]), V)] for b in range(B)]
+    # oracle: every sequence on its own
+    trajs = []
+    for b in range(B):
+        cap = len(prompts[b]) + n_tok + 2 * gamma + 4
+        toks, steps = oracle.sd_generate(ot.new_seq(cap), ods[route[b]].new_seq(cap), prompts[b], gamma, T, n_tok,
+                                         H.uf(seed, dg.DRAFT_STREAM, b), H.uf(seed, dg.VERIFY_STREAM, b),
+                                         keep_logits=True)
+        trajs.append(steps)
+    n_steps = min(len(t) for t in trajs)
+    ctx = api.Context([len(p) + (n_steps + 1) * (gamma + 1) + 8 for p in prompts])
+    ctx.attach(gt)
+    for gd in gds:
+        ctx.attach(gd)
+    ctx.set_tokens(prompts)
+    api.sd_prefill(gt, ctx, None, B, max(len(p) for p in prompts) - 1)
+    gid = [H.dev(np.array(g, np.int32)) if g else None for g in groups]
+    for g in range(4):
+        if groups[g]:
+            api.sd_prefill(gds[g], ctx, gid[g], len(groups[g]), max(len(prompts[b]) for b in groups[g]) - 1)
+    na = torch.zeros(B, dtype=torch.int32, device="cuda")
+    nx = torch.zeros(B, dtype=torch.int32, device="cuda")
+    flagged = 0
+    for k in range(n_steps):
+        for g in range(4):
+            if not groups[g]:
+                continue
+            ng = len(groups[g])
+            ud = H.dev(np.stack([trajs[b][k].u_draft for b in groups[g]]))
+            cand = torch.zeros((ng, gamma), dtype=torch.int32, device="cuda")
+            q = torch.zeros((ng, gamma, V), dtype=torch.float32, device="cuda")
+            api.sd_draft(gds[g], ctx, gid[g], ng, gamma, T, ud, cand, q)
+            cg, qg = cand.cpu().numpy(), q.cpu().numpy()
+            for j, b in enumerate(groups[g]):
+                f, first_bad, _ = H.check_draft_step(trajs[b][k], cg[j], qg[j], T, dg.BF16, V)
+                flagged += int(f)
+                assert first_bad is None, "a flagged draft candidate would need a per-sequence re-feed here"
+        cand_all = H.dev(np.stack([trajs[b][k].cand for b in range(B)]).astype(np.int32))
+        q_all = H.dev(np.stack([trajs[b][k].q for b in range(B)]))
+        uv = H.dev(np.stack([trajs[b][k].u_verify for b in range(B)]))
+        api.sd_verify(gt, ctx, None, B, gamma, T, cand_all, q_all, uv, na, nx, commit=False)
+        lg = gt.last_logits().cpu().numpy().reshape(B, gamma + 1, V)
+        na_h, nx_h = na.cpu().numpy(), nx.cpu().numpy()
+        for b in range(B):
+            f, _, _ = H.check_verify_step(trajs[b][k], int(na_h[b]), int(nx_h[b]), lg[b], T, dg.BF16, V)
+            flagged += int(f)
+        api.sd_commit(ctx, None, B, gamma, cand_all, H.dev(np.array([trajs[b][k].n_acc for b in range(B)], np.int32)),
+                      H.dev(np.array([trajs[b][k].next_token for b in range(B)], np.int32)))
+    nt, kv = ctx.sync(gt)
+    for b in range(B):
+        assert nt[b] == len(prompts[b]) + sum(s.n_acc + 1 for s in trajs[b][:n_steps]) and kv[b] == nt[b] - 1
+    _say(f"  groups={[len(g) for g in groups]} steps={n_steps} flagged={flagged} "
+         f"n_acc={[trajs[b][0].n_acc for b in range(B)]}")
+    assert flagged <= 2
+    ctx.close()
+    gt.close()
+    for gd in gds:
+        gd.close()
