@@ -37,26 +37,40 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 // MODE: GEMM_STORE (C = acc, or partial sums when KS > 1) / GEMM_SWIGLU (tiles 2j, 2j+1 of a wave are
 // the gate and up tile of the same columns).  OPROWS: operand rows staged per chunk: 16 (packed hi|lo,
 // M <= 8), 32 (hi 0..15, lo 16..31, M <= 16) or 64 (M <= 32).
-template <int MODE, int OPROWS, int NT, int WAVES>
+// For M > 32 the rows are cut into blocks of OPROWS/2 = 48 rows (n_mblocks >= 1 of them; n_mblocks == 0
+// selects the plain mapping block = column tile, with an exact grid); the row blocks of
+// one column tile re-read the same weights, so they are mapped to the SAME XCD and to adjacent dispatch
+// slots: the re-reads then hit that XCD's L2 and HBM still sees every weight once.
+template <int MODE, int OPROWS, int KC, int NT, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void gemm_stream_kernel(const uint16_t *__restrict__ A, size_t a_plane,
                                                                  WeightSeg w, int M, int N, int K, int k_per_split,
+                                                                 int n_mblocks, int n_ntiles,
                                                                  float *__restrict__ C, size_t c_split_stride,
                                                                  uint16_t *__restrict__ Cact, size_t c_plane)
 {
     constexpr bool PACKED = OPROWS == 16;
     constexpr int MT = PACKED ? 1 : OPROWS / 32;    // 16-row tiles of A
-    constexpr int KC = GS_OPELEMS / OPROWS;         // chunk length in k (512 / 256 / 128)
+    constexpr int BM = PACKED ? 8 : OPROWS / 2;     // rows of A per block
     constexpr int STEPS = KC / 128;                 // 128-element steps per chunk
     constexpr int LDROW = KC + GS_PAD;
     constexpr int THREADS = WAVES * 64;
     constexpr int VEC_PER_ROW = KC / 8;             // 16-byte vectors per operand row
-    constexpr int NVEC = OPROWS * VEC_PER_ROW;      // vectors per chunk (1024)
+    constexpr int NVEC = OPROWS * VEC_PER_ROW;      // vectors per chunk
     constexpr int LPT = (NVEC + THREADS - 1) / THREADS;
     constexpr int COLS = (MODE == GEMM_SWIGLU ? NT / 2 : NT) * 16 * WAVES;
     __shared__ __attribute__((aligned(16))) uint16_t sA[2][OPROWS][LDROW];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int row = lane & 15, grp = lane >> 4;
-    const int n0 = blockIdx.x * COLS;
+    // block -> (column tile, row block): id = xcd + 8 * (row block + n_mblocks * (tile / 8))
+    int ntile = blockIdx.x, mblk = 0;
+    if (n_mblocks >= 1) { // row-blocked launch: the grid is padded, so the tile index must be checked
+        const int r = blockIdx.x >> 3;
+        mblk = r % n_mblocks;
+        ntile = (r / n_mblocks) * 8 + (blockIdx.x & 7);
+        if (ntile >= n_ntiles) return; // grid is padded to a multiple of 8 tiles
+    }
+    const int n0 = ntile * COLS;
+    const int m0 = mblk * BM;
     const int kb = blockIdx.y * k_per_split;
     const int ke = min(K, kb + k_per_split);
     const int nchunks = (ke - kb + KC - 1) / KC;
@@ -86,7 +100,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_stream_kernel(const uint16_t 
             m = orow & 7;
             plane = orow < 8 ? 0 : a_plane;
         } else {
-            m = (orow % (OPROWS / 2));
+            m = m0 + (orow % (OPROWS / 2));
             plane = orow < OPROWS / 2 ? 0 : a_plane;
         }
         a_ok[j] = v < NVEC && m < M;
@@ -179,7 +193,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_stream_kernel(const uint16_t 
                 for (int r = 0; r < 4; r++) v[c][r] += __shfl_xor(v[c][r], 8, 64); // hi half + lo half
             }
         }
-        const int m = PACKED ? row : t * 16 + row;
+        const int m = PACKED ? row : m0 + t * 16 + row;
         if ((PACKED && row >= 8) || m >= M) continue;
         if (MODE == GEMM_SWIGLU) {
 #pragma unroll
@@ -309,16 +323,23 @@ static void stream_launch(hipStream_t s, const uint16_t *a, size_t a_plane, Weig
     constexpr int COLS = (MODE == GEMM_SWIGLU ? NT / 2 : NT) * 16 * WAVES;
     int kps, ny;
     split_geometry(K, ks, &kps, &ny);
-    dim3 grid(N / COLS, ny), block(WAVES * 64);
+    const int ntiles = N / COLS;
+    dim3 block(WAVES * 64);
     if (M <= 8)
-        hipLaunchKernelGGL((gemm_stream_kernel<MODE, 16, NT, WAVES>), grid, block, 0, s, a, a_plane, w, M, N, K, kps, C,
-                           c_split_stride, ca, c_plane);
+        hipLaunchKernelGGL((gemm_stream_kernel<MODE, 16, 512, NT, WAVES>), dim3(ntiles, ny), block, 0, s, a, a_plane, w,
+                           M, N, K, kps, 0, ntiles, C, c_split_stride, ca, c_plane);
     else if (M <= 16)
-        hipLaunchKernelGGL((gemm_stream_kernel<MODE, 32, NT, WAVES>), grid, block, 0, s, a, a_plane, w, M, N, K, kps, C,
-                           c_split_stride, ca, c_plane);
-    else
-        hipLaunchKernelGGL((gemm_stream_kernel<MODE, 64, NT, WAVES>), grid, block, 0, s, a, a_plane, w, M, N, K, kps, C,
-                           c_split_stride, ca, c_plane);
+        hipLaunchKernelGGL((gemm_stream_kernel<MODE, 32, 256, NT, WAVES>), dim3(ntiles, ny), block, 0, s, a, a_plane, w,
+                           M, N, K, kps, 0, ntiles, C, c_split_stride, ca, c_plane);
+    else if (M <= 32)
+        hipLaunchKernelGGL((gemm_stream_kernel<MODE, 64, 128, NT, WAVES>), dim3(ntiles, ny), block, 0, s, a, a_plane, w,
+                           M, N, K, kps, 0, ntiles, C, c_split_stride, ca, c_plane);
+    else {
+        const int nmb = (M + 47) / 48;
+        const int gx = ((ntiles + 7) / 8) * 8 * nmb;
+        hipLaunchKernelGGL((gemm_stream_kernel<MODE, 96, 128, NT, WAVES>), dim3(gx, ny), block, 0, s, a, a_plane, w, M,
+                           N, K, kps, nmb, ntiles, C, c_split_stride, ca, c_plane);
+    }
 }
 
 int g_skinny_tune[3][2] = {{4, 0}, {4, 0}, {4, 0}}; // [mode] -> {waves per block, K splits (0 = automatic)}
@@ -327,16 +348,21 @@ int g_skinny_tune[3][2] = {{4, 0}, {4, 0}, {4, 0}}; // [mode] -> {waves per bloc
 int gemm_skinny_splits(int mode, int M, int N, int K)
 {
     if (mode == GEMM_SWIGLU || K < 128 || K % 128 != 0) return 1; // (the launcher rejects such K)
+    int kps, ny;
     if (g_skinny_tune[mode][1] > 0) {
-        int kps, ny;
         split_geometry(K, g_skinny_tune[mode][1], &kps, &ny);
         return ny;
     }
-    const int waves = g_skinny_tune[mode][0];
-    const int blocks = N / (16 * waves);
+    int blocks, target;
+    if (M <= 32) {
+        blocks = N / (16 * g_skinny_tune[mode][0]);
+        target = 768; // about three blocks per CU
+    } else {
+        blocks = (N / 128) * ((M + 47) / 48); // 2 waves x 4 tiles = 128 columns per block, 48-row blocks
+        target = 384;                          // partial slabs cost M*N*4 bytes each here: split sparingly
+    }
     int ks = 1;
-    while (blocks * ks < 768 && ks < 8 && K / (ks * 2) >= 512) ks *= 2; // about three blocks per CU
-    int kps, ny;
+    while (blocks * ks < target && ks < 8 && K / (ks * 2) >= 512) ks *= 2;
     split_geometry(K, ks, &kps, &ny);
     return ny;
 }
@@ -347,13 +373,23 @@ int gemm_skinny_splits(int mode, int M, int N, int K)
 hipError_t launch_gemm_skinny_bf16(hipStream_t s, int mode, const void *A, size_t a_plane, WeightSeg w, int M, int N,
                                    int K, float *C, size_t c_split_stride, int splits, void *Cact, size_t c_plane)
 {
-    if (M < 1 || M > 32 || K % 128 != 0 || (mode != GEMM_STORE && mode != GEMM_SWIGLU)) return hipErrorNotSupported;
+    if (M < 1 || K % 128 != 0 || K < 128 || (mode != GEMM_STORE && mode != GEMM_SWIGLU)) return hipErrorNotSupported;
     for (int i = 0; i < 3; i++)
         if (w.p[i] && ((uintptr_t)w.p[i] & 15)) return hipErrorNotSupported;
     if (((uintptr_t)A & 15) || (a_plane & 7) || (N & 3)) return hipErrorNotSupported;
     const uint16_t *a = (const uint16_t *)A;
     uint16_t *ca = (uint16_t *)Cact;
     const int waves = g_skinny_tune[mode][0];
+    if (M > 32) { // row-blocked: 2 waves x 4 tiles per block
+        if (mode == GEMM_SWIGLU) {
+            if (N % 64 != 0) return hipErrorNotSupported;
+            stream_launch<GEMM_SWIGLU, 4, 2>(s, a, a_plane, w, M, N, K, 1, C, 0, ca, c_plane);
+        } else {
+            if (N % 128 != 0 || w.n_per_seg % 128 != 0) return hipErrorNotSupported;
+            stream_launch<GEMM_STORE, 4, 2>(s, a, a_plane, w, M, N, K, splits, C, c_split_stride, ca, c_plane);
+        }
+        return hipGetLastError();
+    }
     if (mode == GEMM_SWIGLU && g_skinny_tune[GEMM_SWIGLU][1] == 0) { // default: K split inside the block
         if (N % 16 != 0) return hipErrorNotSupported;
         const uint16_t *wg = (const uint16_t *)w.p[0], *wu = (const uint16_t *)w.p[1];

@@ -483,7 +483,7 @@ static int stream_gemm(sd_model *m, hipStream_t s, const void *A, size_t a_plane
                        float *slabs, size_t slabs_floats, int force_splits, hipError_t *err)
 {
     *err = hipSuccess;
-    if (m->cfg.dtype != SD_BF16 || (g_force_generic & 1) || M > 32) return 0;
+    if (m->cfg.dtype != SD_BF16 || (g_force_generic & 1)) return 0;
     int ns = force_splits > 0 ? force_splits : gemm_skinny_splits(GEMM_STORE, M, N, K);
     if ((size_t)ns * M * N > slabs_floats || ns > 8) ns = 1;
     hipError_t e = launch_gemm_skinny_bf16(s, GEMM_STORE, A, a_plane, w, M, N, K, slabs, (size_t)M * N, ns, nullptr, 0);
