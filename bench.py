@@ -26,6 +26,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+GATEUP_TRAFFIC_BYTES = 184.7e6  # measured with rocprofv3 --pmc, see profiles/config2_b1_7b_hbm_traffic.md
 
 
 def log(*a):
@@ -41,6 +42,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--temperature", type=float, default=1.0)
     ap.add_argument("--prompt", type=int, default=512)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device copy three times (known traffic, to scale HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (sequences are independent; "
@@ -54,6 +57,15 @@ def main():
     from paper_2505_08600_amd import datagen as dg
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.copy_calibration:
+        n = 1 << 30
+        src = torch.ones(n, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": n, "copy_bytes_written": n, "launches": 3}))
+        return
     api.lib()
     seed, gamma, T, B = 2025, 5, float(args.temperature), 1
     st = dg.SHAPES["t7b"] if not args.layers else dg.with_layers(dg.SHAPES["t7b"], args.layers)
@@ -183,9 +195,12 @@ def main():
         "acceptance_rate_eq2": float(n_acc.sum() / (K * gamma)), "tau": tau, "alpha_hat": alpha_hat,
         "c_draft_over_target": c_ratio, "eq1_speedup_model": eq1,
         "verify_hbm_frac": verify_frac,
-        "roofline": {"bound": "hbm", "kernel": "gemm_skinny_kernel<SwiGLU gate/up> M=%d N=%d K=%d" % (M, st.d_ffn, st.d_model),
+        "roofline": {"bound": "hbm", "kernel": "gemm_swiglu_kernel<true,1> (gate/up + SiLU*mul) M=%d N=%d K=%d" % (M, st.d_ffn, st.d_model),
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None, "us_per_launch": gu_ms * 1e3, "algorithmic_bytes": gu_bytes},
+                     # FETCH_SIZE + WRITE_SIZE per launch of this kernel at this shape, scaled by a plain copy
+                     # (profiles/config2_b1_7b_hbm_traffic.md); only meaningful for the default workload
+                     "traffic": GATEUP_TRAFFIC_BYTES if (not args.layers and args.prompt == 512) else None,
+                     "us_per_launch": gu_ms * 1e3, "algorithmic_bytes": gu_bytes},
         "kernel_ms_per_verify": {k: v[1] / 3.0 for k, v in vprof.items() if v[0]},
     }
 

@@ -323,7 +323,10 @@ __global__ __launch_bounds__(1024) void add_rmsnorm_kernel(float *x, const float
     const float *pr = part + (size_t)src * d;
     float ss = 0.f;
     const int nvec = d / 4; // d is a multiple of 4 (checked at load)
-    for (int v = threadIdx.x; v < nvec; v += blockDim.x) {
+    constexpr int KEEP = 2; // vectors of the row a thread keeps in registers (d <= 8192)
+    float4 keep[KEEP];
+    int it = 0;
+    for (int v = threadIdx.x; v < nvec; v += blockDim.x, it++) {
         float4 a = *(const float4 *)(xr + 4 * v);
         float4 p[ADDNORM_MAX_SLABS];
 #pragma unroll
@@ -338,11 +341,21 @@ __global__ __launch_bounds__(1024) void add_rmsnorm_kernel(float *x, const float
                 a.w += p[s].w;
             }
         *(float4 *)(xr + 4 * v) = a;
+        if (it < KEEP) keep[it] = a;
         ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
     }
     ss = block_sum(ss, red);
     float inv = 1.0f / sqrtf(ss / (float)d + eps);
-    for (int i = threadIdx.x; i < d; i += blockDim.x) store_act(out, (size_t)j * d + i, plane, xr[i] * inv * g[i]);
+    it = 0;
+    for (int v = threadIdx.x; v < nvec; v += blockDim.x, it++) {
+        const float4 a = it < KEEP ? keep[it] : *(const float4 *)(xr + 4 * v);
+        const float4 gg = *(const float4 *)(g + 4 * v);
+        const size_t o = (size_t)j * d + 4 * v;
+        store_act(out, o, plane, a.x * inv * gg.x);
+        store_act(out, o + 1, plane, a.y * inv * gg.y);
+        store_act(out, o + 2, plane, a.z * inv * gg.z);
+        store_act(out, o + 3, plane, a.w * inv * gg.w);
+    }
 }
 
 hipError_t launch_add_rmsnorm(hipStream_t s, int dtype, float *x, const float *part, int n_slabs, size_t slab_stride,
