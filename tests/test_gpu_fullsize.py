@@ -73,7 +73,7 @@ def _batched_case(name, target_shape, draft_shapes, B, lens, gamma, T, seed, che
     print(f"{name}: weights in {time.time() - t0:.1f}s", flush=True)
     max_len = int(max(lens))
     gt = api.Model(target_shape, wt, max_rows=B * (gamma + 1), max_pos=max_len + 64)
-    gds = [api.Model(sh, w, max_rows=max(2 * B, 16 * B if B <= 4 else 2 * B), max_pos=max_len + 64)
+    gds = [api.Model(sh, w, max_rows=16 * B, max_pos=max_len + 64)
            for sh, w in zip(draft_shapes, wds)]
     ot = oracle.OracleModel(target_shape, wt)
     ods = [oracle.OracleModel(sh, w) for sh, w in zip(draft_shapes, wds)]
@@ -186,3 +186,17 @@ def test_config4_13b_batch32_context2048():
     seed, B = 4044, 32
     lens = np.full(B, 2048, np.int32)
     _batched_case("config4", dg.SHAPES["t13b"], [dg.SHAPES["draft_a"]], B, lens, 8, 1.0, seed, [5])
+
+
+@pytest.mark.timeout(1500)
+def test_config5_batch64_long_ragged_contexts():
+    """BASELINE config 5 shapes: 7B-shape target, batch 64, per-sequence contexts uniform in
+    [1024, 8192], gamma = 8 (M = 576 rows), T = 1: long ragged KV (about 150 GB of cache), split
+    attention and per-sequence rollback.  Proposals come from the 68M-shape draft here (the synthetic
+    rho-mixed q of this config is exercised at full vocabulary in test_gpu_parity); oracle on the
+    shortest sequence and on one of median length."""
+    seed, B = 5055, 64
+    lens = dg.make_prompt_lengths(seed, B, 1024, 8192)
+    order = np.argsort(lens)
+    _batched_case("config5", dg.SHAPES["t7b"], [dg.SHAPES["draft_a"]], B, lens, 8, 1.0, seed,
+                  [int(order[0]), int(order[B // 2])])
