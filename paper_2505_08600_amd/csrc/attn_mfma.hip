@@ -37,51 +37,24 @@ union Pack8 {
     uint16_t u[8];
 };
 
+// Online-softmax pass of one wave over the KV tiles t_begin, t_begin + t_stride, ... < t_end.
+// qv/ql: hi and lo planes of the Q^T operand; vis: last visible token of this lane's query row.
 template <int HD>
-__global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restrict__ qbuf, size_t q_plane,
-                                                        const uint16_t *__restrict__ Kl,
-                                                        const uint16_t *__restrict__ Vtl, PlanView pv, CtxView cv,
-                                                        int R, int H, int64_t total_cap, int S,
-                                                        float *__restrict__ part, uint16_t *__restrict__ obuf,
-                                                        size_t o_plane)
+__device__ __forceinline__ void attn_tiles(const uint16_t *__restrict__ K, const uint16_t *__restrict__ Vt,
+                                           int64_t total_cap, const bf16x8 *qv, const bf16x8 *ql, int vis, int t_begin,
+                                           int t_end, int t_stride, float &m_run, float &l_run, f32x4 *o)
 {
-    constexpr int NC = HD / 32; // 32-wide chunks of the head dimension (QK^T contraction)
-    constexpr int ND = HD / 16; // 16-row tiles of V^T / O^T
-    __shared__ float sO[AT_WAVES][ND][64][4];
-    __shared__ float sM[AT_WAVES][16], sL[AT_WAVES][16];
-    const int s = blockIdx.x, h = blockIdx.y, j = blockIdx.z;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    constexpr int NC = HD / 32;
+    constexpr int ND = HD / 16;
+    const int lane = threadIdx.x & 63;
     const int qi = lane & 15, grp = lane >> 4;
-    const int nq = pv.seq_nq[j], kv0 = pv.seq_kv0[j];
-    const int Lk = kv0 + nq;
-    const int64_t off = cv.off[pv.seq_b[j]];
-    const int HDm = H * HD;
-    const uint16_t *K = Kl + ((size_t)h * total_cap + off) * HD;
-    const uint16_t *Vt = Vtl + (size_t)h * HD * total_cap + off;
-    // this block's tile range
-    const int n_tiles = nq > 0 ? (Lk + AT_TILE - 1) / AT_TILE : 0; // nothing to do for unused sequences
-    const int per = (n_tiles + S - 1) / S;
-    const int t_begin = s * per, t_end = min(n_tiles, t_begin + per);
-    // Q^T operand: lane (q, grp) holds Q[q][grp*(HD/4) + c*8 .. +8], matching the K loads below
-    bf16x8 qv[NC], ql[NC];
-    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-    for (int c = 0; c < NC; c++) {
-        const bf16x8 *p = (const bf16x8 *)(qbuf + (size_t)(j * R + (qi < R ? qi : 0)) * HDm + h * HD + grp * (HD / 4) + c * 8);
-        qv[c] = qi < nq ? *p : zero;
-        ql[c] = qi < nq ? *(const bf16x8 *)((const uint16_t *)p + q_plane) : zero;
-    }
     const float scale = 1.0f / sqrtf((float)HD);
-    const int vis = kv0 + qi; // last visible token of this lane's query row
-    float m_run = AT_NEG, l_run = 0.f;
-    f32x4 o[ND];
-#pragma unroll
-    for (int d = 0; d < ND; d++) o[d] = (f32x4){0.f, 0.f, 0.f, 0.f};
     // K operand rows: lane row i holds token 8*(i/4) + i%4 (tile a) or that + 4 (tile b)
     const int krow = 8 * (qi >> 2) + (qi & 3);
-    for (int t = t_begin + wave; t < t_end; t += AT_WAVES) {
+    // two register buffers: the loads of the next tile are in flight while the current one is consumed
+    bf16x8 ka0[NC], kb0[NC], vv0[ND], ka1[NC], kb1[NC], vv1[ND];
+    auto load_tile = [&](int t, bf16x8 *ka, bf16x8 *kb, bf16x8 *vv) {
         const int t0 = t * AT_TILE;
-        bf16x8 ka[NC], kb[NC], vv[ND];
         const uint16_t *kpa = K + (size_t)(t0 + krow) * HD + grp * (HD / 4);
         const uint16_t *kpb = kpa + 4 * HD;
 #pragma unroll
@@ -91,6 +64,9 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restri
         }
 #pragma unroll
         for (int d = 0; d < ND; d++) vv[d] = *(const bf16x8 *)(Vt + (size_t)(d * 16 + qi) * total_cap + t0 + grp * 8);
+    };
+    auto compute_tile = [&](int t, const bf16x8 *ka, const bf16x8 *kb, const bf16x8 *vv) {
+        const int t0 = t * AT_TILE;
         f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int c = 0; c < NC; c++) {
@@ -138,7 +114,61 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restri
             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv[d], pl.v, acc, 0, 0, 0);
             o[d] = acc;
         }
+    };
+    int t = t_begin;
+    if (t < t_end) load_tile(t, ka0, kb0, vv0);
+    while (t < t_end) {
+        const int tn = t + t_stride;
+        if (tn < t_end) load_tile(tn, ka1, kb1, vv1);
+        compute_tile(t, ka0, kb0, vv0);
+        if (tn >= t_end) break;
+        const int tnn = tn + t_stride;
+        if (tnn < t_end) load_tile(tnn, ka0, kb0, vv0);
+        compute_tile(tn, ka1, kb1, vv1);
+        t = tnn;
     }
+}
+
+template <int HD>
+__global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restrict__ qbuf, size_t q_plane,
+                                                        const uint16_t *__restrict__ Kl,
+                                                        const uint16_t *__restrict__ Vtl, PlanView pv, CtxView cv,
+                                                        int R, int H, int64_t total_cap, int S,
+                                                        float *__restrict__ part, uint16_t *__restrict__ obuf,
+                                                        size_t o_plane)
+{
+    constexpr int NC = HD / 32; // 32-wide chunks of the head dimension (QK^T contraction)
+    constexpr int ND = HD / 16; // 16-row tiles of V^T / O^T
+    __shared__ float sO[AT_WAVES][ND][64][4];
+    __shared__ float sM[AT_WAVES][16], sL[AT_WAVES][16];
+    const int s = blockIdx.x, h = blockIdx.y, j = blockIdx.z;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int qi = lane & 15, grp = lane >> 4;
+    const int nq = pv.seq_nq[j], kv0 = pv.seq_kv0[j];
+    const int Lk = kv0 + nq;
+    const int64_t off = cv.off[pv.seq_b[j]];
+    const int HDm = H * HD;
+    const uint16_t *K = Kl + ((size_t)h * total_cap + off) * HD;
+    const uint16_t *Vt = Vtl + (size_t)h * HD * total_cap + off;
+    // this block's tile range
+    const int n_tiles = nq > 0 ? (Lk + AT_TILE - 1) / AT_TILE : 0; // nothing to do for unused sequences
+    const int per = (n_tiles + S - 1) / S;
+    const int t_begin = s * per, t_end = min(n_tiles, t_begin + per);
+    // Q^T operand: lane (q, grp) holds Q[q][grp*(HD/4) + c*8 .. +8], matching the K loads below
+    bf16x8 qv[NC], ql[NC];
+    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int c = 0; c < NC; c++) {
+        const bf16x8 *p = (const bf16x8 *)(qbuf + (size_t)(j * R + (qi < R ? qi : 0)) * HDm + h * HD + grp * (HD / 4) + c * 8);
+        qv[c] = qi < nq ? *p : zero;
+        ql[c] = qi < nq ? *(const bf16x8 *)((const uint16_t *)p + q_plane) : zero;
+    }
+    const int vis = kv0 + qi; // last visible token of this lane's query row
+    float m_run = AT_NEG, l_run = 0.f;
+    f32x4 o[ND];
+#pragma unroll
+    for (int d = 0; d < ND; d++) o[d] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    attn_tiles<HD>(K, Vt, total_cap, qv, ql, vis, t_begin + wave, t_end, AT_WAVES, m_run, l_run, o);
     // row sums were kept per k-group: finish them
     l_run += __shfl_xor(l_run, 16, 64);
     l_run += __shfl_xor(l_run, 32, 64);
@@ -221,6 +251,180 @@ __global__ void attn_combine_kernel(const float *__restrict__ part, PlanView pv,
         obuf[oi] = hi;
         obuf[oi + o_plane] = bf16_bits_rne(out - __uint_as_float((uint32_t)hi << 16));
     }
+}
+
+// Fused RoPE + cache append + attention for one (sequence, head) per block, no KV split: used when
+// there are enough (sequence, head) pairs to fill the chip or the context is short, where the split
+// kernel plus its combine pass and the separate RoPE kernel are three latency-bound launches.
+// The block first adds the split-K slabs of the QKV GEMM for its head, rotates q and k, writes the new
+// K / V rows into the cache in place and q (hi, lo) into LDS; after a barrier its 8 waves stream the
+// cache (including the rows just written) tile by tile, and merge pairwise, then four ways, in LDS.
+#define AF_WAVES 8
+template <int HD>
+__global__ __launch_bounds__(AF_WAVES * 64) void attn_fused_kernel(const float *__restrict__ qkv, int n_slabs,
+                                                                   size_t slab_stride, PlanView pv, CtxView cv, int R,
+                                                                   int H, const float2 *__restrict__ rope, int max_pos,
+                                                                   uint16_t *__restrict__ Kl, uint16_t *__restrict__ Vtl,
+                                                                   int64_t total_cap, uint16_t *__restrict__ obuf,
+                                                                   size_t o_plane)
+{
+    constexpr int NC = HD / 32;
+    constexpr int ND = HD / 16;
+    constexpr int HALF = HD / 2;
+    __shared__ float sO[4][ND][64][4];
+    __shared__ float sM[4][16], sL[4][16];
+    __shared__ __attribute__((aligned(16))) uint16_t sQ[2][16][HD];
+    const int h = blockIdx.x, j = blockIdx.y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int qi = lane & 15, grp = lane >> 4;
+    const int nq = pv.seq_nq[j], kv0 = pv.seq_kv0[j];
+    const int Lk = kv0 + nq;
+    const int64_t off = cv.off[pv.seq_b[j]];
+    const int HDm = H * HD;
+    uint16_t *K = Kl + ((size_t)h * total_cap + off) * HD;
+    uint16_t *Vt = Vtl + (size_t)h * HD * total_cap + off;
+    // ---- prologue: slabs -> q, k, v of this head; RoPE; append
+    for (int idx = threadIdx.x; idx < 16 * HALF; idx += AF_WAVES * 64) {
+        const int r = idx / HALF, e = idx % HALF;
+        const int row = j * R + (r < R ? r : 0);
+        const int pos = kv0 + r;
+        bool valid = r < nq && pos < max_pos;
+        if (r < nq && pos >= max_pos && e == 0) atomicOr(cv.status, 8);
+        float q0 = 0.f, q1 = 0.f, k0 = 0.f, k1 = 0.f, v0 = 0.f, v1 = 0.f;
+        if (valid) {
+            const float *base = qkv + (size_t)row * 3 * HDm + h * HD + e;
+            float ld[8][6];
+#pragma unroll
+            for (int sl = 0; sl < 8; sl++)
+                if (sl < n_slabs) {
+                    const float *rs = base + (size_t)sl * slab_stride;
+                    ld[sl][0] = rs[0];
+                    ld[sl][1] = rs[HALF];
+                    ld[sl][2] = rs[HDm];
+                    ld[sl][3] = rs[HDm + HALF];
+                    ld[sl][4] = rs[2 * HDm];
+                    ld[sl][5] = rs[2 * HDm + HALF];
+                }
+#pragma unroll
+            for (int sl = 0; sl < 8; sl++)
+                if (sl < n_slabs) {
+                    q0 += ld[sl][0];
+                    q1 += ld[sl][1];
+                    k0 += ld[sl][2];
+                    k1 += ld[sl][3];
+                    v0 += ld[sl][4];
+                    v1 += ld[sl][5];
+                }
+            const float2 cs = rope[(size_t)pos * HALF + e];
+            const float qa = q0 * cs.x - q1 * cs.y, qb = q1 * cs.x + q0 * cs.y;
+            const float ka = k0 * cs.x - k1 * cs.y, kb = k1 * cs.x + k0 * cs.y;
+            q0 = qa;
+            q1 = qb;
+            uint16_t *kd = K + (size_t)pos * HD;
+            kd[e] = bf16_bits_rne(ka);
+            kd[e + HALF] = bf16_bits_rne(kb);
+            Vt[(size_t)e * total_cap + pos] = bf16_bits_rne(v0);
+            Vt[(size_t)(e + HALF) * total_cap + pos] = bf16_bits_rne(v1);
+        }
+        const uint16_t h0 = bf16_bits_rne(q0), h1 = bf16_bits_rne(q1);
+        sQ[0][r][e] = h0;
+        sQ[0][r][e + HALF] = h1;
+        sQ[1][r][e] = bf16_bits_rne(q0 - __uint_as_float((uint32_t)h0 << 16));
+        sQ[1][r][e + HALF] = bf16_bits_rne(q1 - __uint_as_float((uint32_t)h1 << 16));
+    }
+    __syncthreads(); // q in LDS; the new cache rows are visible to this block's later loads
+    bf16x8 qv[NC], ql[NC];
+#pragma unroll
+    for (int c = 0; c < NC; c++) {
+        qv[c] = *(const bf16x8 *)(&sQ[0][qi][grp * (HD / 4) + c * 8]);
+        ql[c] = *(const bf16x8 *)(&sQ[1][qi][grp * (HD / 4) + c * 8]);
+    }
+    const int n_tiles = nq > 0 ? (Lk + AT_TILE - 1) / AT_TILE : 0;
+    const int vis = kv0 + qi;
+    float m_run = AT_NEG, l_run = 0.f;
+    f32x4 o[ND];
+#pragma unroll
+    for (int d = 0; d < ND; d++) o[d] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    attn_tiles<HD>(K, Vt, total_cap, qv, ql, vis, wave, n_tiles, AF_WAVES, m_run, l_run, o);
+    l_run += __shfl_xor(l_run, 16, 64);
+    l_run += __shfl_xor(l_run, 32, 64);
+    // ---- merge round 1: waves 4..7 hand their state to waves 0..3
+    if (wave >= 4) {
+#pragma unroll
+        for (int d = 0; d < ND; d++)
+#pragma unroll
+            for (int r = 0; r < 4; r++) sO[wave - 4][d][lane][r] = o[d][r];
+        if (grp == 0) {
+            sM[wave - 4][qi] = m_run;
+            sL[wave - 4][qi] = l_run;
+        }
+    }
+    __syncthreads();
+    if (wave < 4) {
+        const float m2 = sM[wave][qi], l2 = sL[wave][qi];
+        const float M = fmaxf(m_run, m2);
+        const float f1 = expf(m_run - M), f2 = expf(m2 - M);
+#pragma unroll
+        for (int d = 0; d < ND; d++)
+#pragma unroll
+            for (int r = 0; r < 4; r++) o[d][r] = o[d][r] * f1 + sO[wave][d][lane][r] * f2;
+        l_run = l_run * f1 + l2 * f2;
+        m_run = M;
+    }
+    __syncthreads();
+    // ---- merge round 2: the four survivors meet in LDS
+    if (wave < 4) {
+#pragma unroll
+        for (int d = 0; d < ND; d++)
+#pragma unroll
+            for (int r = 0; r < 4; r++) sO[wave][d][lane][r] = o[d][r];
+        if (grp == 0) {
+            sM[wave][qi] = m_run;
+            sL[wave][qi] = l_run;
+        }
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < ND * 256; e += AF_WAVES * 64) {
+        const int d = e >> 8, slot = (e >> 2) & 63, r = e & 3;
+        const int q = slot & 15, dim = 16 * d + 4 * (slot >> 4) + r;
+        if (q >= R) continue;
+        float M = AT_NEG;
+#pragma unroll
+        for (int w = 0; w < 4; w++) M = fmaxf(M, sM[w][q]);
+        float O = 0.f, L = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; w++) {
+            const float f = expf(sM[w][q] - M);
+            O += sO[w][d][slot][r] * f;
+            L += sL[w][q] * f;
+        }
+        const float out = (q < nq && L > 0.f) ? O / L : 0.f;
+        const uint16_t hi = bf16_bits_rne(out);
+        const size_t oi = (size_t)(j * R + q) * HDm + h * HD + dim;
+        obuf[oi] = hi;
+        obuf[oi + o_plane] = bf16_bits_rne(out - __uint_as_float((uint32_t)hi << 16));
+    }
+}
+
+// Returns hipErrorNotSupported when the split path (RoPE kernel + split attention + combine) should run.
+hipError_t launch_attn_fused_bf16(hipStream_t s, const float *qkv, int n_slabs, size_t slab_stride, PlanView pv,
+                                  CtxView cv, int R, int n_seq, int H, int hd, const float2 *rope, int max_pos,
+                                  void *Kl, void *Vtl, int64_t total_cap, int len_upper, void *obuf, size_t o_plane)
+{
+    if (R < 1 || R > 16 || (hd != 64 && hd != 128) || n_slabs < 1 || n_slabs > 8) return hipErrorNotSupported;
+    if (n_seq > 65535 || H > 65535) return hipErrorNotSupported;
+    const int tiles_upper = (len_upper + AT_TILE - 1) / AT_TILE;
+    // one block per (sequence, head): fine when those alone fill the chip, or when every wave has
+    // at most a few tiles anyway
+    if (!((long)n_seq * H >= 512 || tiles_upper <= 6 * AF_WAVES)) return hipErrorNotSupported;
+    dim3 grid(H, n_seq), block(AF_WAVES * 64);
+    if (hd == 128)
+        hipLaunchKernelGGL(attn_fused_kernel<128>, grid, block, 0, s, qkv, n_slabs, slab_stride, pv, cv, R, H, rope,
+                           max_pos, (uint16_t *)Kl, (uint16_t *)Vtl, total_cap, (uint16_t *)obuf, o_plane);
+    else
+        hipLaunchKernelGGL(attn_fused_kernel<64>, grid, block, 0, s, qkv, n_slabs, slab_stride, pv, cv, R, H, rope,
+                           max_pos, (uint16_t *)Kl, (uint16_t *)Vtl, total_cap, (uint16_t *)obuf, o_plane);
+    return hipGetLastError();
 }
 
 hipError_t launch_attn_mfma_bf16(hipStream_t s, const void *qbuf, size_t q_plane, const void *Kl, const void *Vtl,

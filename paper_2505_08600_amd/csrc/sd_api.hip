@@ -546,17 +546,23 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
             nq_slabs = 1;
             qkv_src = m->qkv;
         } }
-        { ProfScope ps(T_ROPE, s);
-        FWD(launch_rope_append(s, cf.dtype, qkv_src, nq_slabs, (size_t)M * 3 * d, pv, cv, M, H, hd, m->rope, cf.max_pos,
-                               m->qbuf, m->plane_d, Kl, Vtl, c->total_cap)); }
         hipError_t ea = hipErrorNotSupported;
-        { ProfScope ps(T_ATTN, s);
-        if (cf.dtype == SD_BF16 && !(g_force_generic & 2))
-            ea = launch_attn_mfma_bf16(s, m->qbuf, m->plane_d, Kl, Vtl, pv, cv, R, n_seq, H, hd, c->total_cap, kv_upper,
-                                       m->part, m->part_floats, m->obuf, m->plane_d);
-        if (ea == hipErrorNotSupported)
-            ea = launch_attn_generic(s, cf.dtype, m->qbuf, m->plane_d, Kl, Vtl, pv, cv, R, n_seq, H, hd, c->total_cap,
-                                     kv_upper, m->obuf, m->plane_d);
+        if (cf.dtype == SD_BF16 && !(g_force_generic & 2)) { // RoPE + append + attention in one launch
+            ProfScope ps(T_ATTN, s);
+            ea = launch_attn_fused_bf16(s, qkv_src, nq_slabs, (size_t)M * 3 * d, pv, cv, R, n_seq, H, hd, m->rope,
+                                        cf.max_pos, Kl, Vtl, c->total_cap, kv_upper, m->obuf, m->plane_d);
+        }
+        if (ea == hipErrorNotSupported) {
+            { ProfScope ps(T_ROPE, s);
+            FWD(launch_rope_append(s, cf.dtype, qkv_src, nq_slabs, (size_t)M * 3 * d, pv, cv, M, H, hd, m->rope,
+                                   cf.max_pos, m->qbuf, m->plane_d, Kl, Vtl, c->total_cap)); }
+            ProfScope ps(T_ATTN, s);
+            if (cf.dtype == SD_BF16 && !(g_force_generic & 2))
+                ea = launch_attn_mfma_bf16(s, m->qbuf, m->plane_d, Kl, Vtl, pv, cv, R, n_seq, H, hd, c->total_cap,
+                                           kv_upper, m->part, m->part_floats, m->obuf, m->plane_d);
+            if (ea == hipErrorNotSupported)
+                ea = launch_attn_generic(s, cf.dtype, m->qbuf, m->plane_d, Kl, Vtl, pv, cv, R, n_seq, H, hd,
+                                         c->total_cap, kv_upper, m->obuf, m->plane_d);
         }
         if (ea == hipErrorNotSupported) return sd_fail(SD_ECAP, "forward: context too long for the generic attention kernel");
         FWD(ea);

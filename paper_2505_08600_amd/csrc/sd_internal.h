@@ -196,6 +196,9 @@ hipError_t launch_gemm_skinny_bf16(hipStream_t s, int mode, const void *A, size_
 hipError_t launch_add_rmsnorm(hipStream_t s, int dtype, float *x, const float *part, int n_slabs, size_t slab_stride,
                               const float *g, const int32_t *row_map, int n_rows, int d, float eps, void *out,
                               size_t out_plane);
+hipError_t launch_attn_fused_bf16(hipStream_t s, const float *qkv, int n_slabs, size_t slab_stride, PlanView pv,
+                                  CtxView cv, int R, int n_seq, int H, int hd, const float2 *rope, int max_pos,
+                                  void *Kl, void *Vtl, int64_t total_cap, int len_upper, void *obuf, size_t o_plane);
 hipError_t launch_attn_mfma_bf16(hipStream_t s, const void *qbuf, size_t q_plane, const void *Kl, const void *Vtl,
                                  PlanView pv, CtxView cv, int R, int n_seq, int H, int hd, int64_t total_cap,
                                  int len_upper, float *part, size_t part_floats, void *obuf, size_t o_plane);
