@@ -27,6 +27,7 @@
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8; // explicit LDS address space: ds_read, not flat loads
 
 #define AT_WAVES 4
 #define AT_TILE 32
@@ -39,7 +40,9 @@ union Pack8 {
 
 // Online-softmax pass of one wave over the KV tiles t_begin, t_begin + t_stride, ... < t_end.
 // qv/ql: hi and lo planes of the Q^T operand; vis: last visible token of this lane's query row.
-template <int HD>
+// With Q_LDS the two planes are re-read from shared memory for every tile instead of living in
+// registers (32 registers less, which is what lets an 8-wave block keep two tile buffers unspilled).
+template <int HD, bool Q_LDS = false>
 __device__ __forceinline__ void attn_tiles(const uint16_t *__restrict__ K, const uint16_t *__restrict__ Vt,
                                            int64_t total_cap, const bf16x8 *qv, const bf16x8 *ql, int vis, int t_begin,
                                            int t_end, int t_stride, float &m_run, float &l_run, f32x4 *o)
@@ -70,10 +73,12 @@ __device__ __forceinline__ void attn_tiles(const uint16_t *__restrict__ K, const
         f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int c = 0; c < NC; c++) {
-            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[c], qv[c], sa, 0, 0, 0);
-            sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[c], qv[c], sb, 0, 0, 0);
-            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[c], ql[c], sa, 0, 0, 0);
-            sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[c], ql[c], sb, 0, 0, 0);
+            const bf16x8 qh = Q_LDS ? *(const volatile lds_bf16x8 *)(const lds_bf16x8 *)&qv[c] : qv[c];
+            const bf16x8 qo = Q_LDS ? *(const volatile lds_bf16x8 *)(const lds_bf16x8 *)&ql[c] : ql[c];
+            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[c], qh, sa, 0, 0, 0);
+            sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[c], qh, sb, 0, 0, 0);
+            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[c], qo, sa, 0, 0, 0);
+            sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[c], qo, sb, 0, 0, 0);
         }
         // lane (q, grp) now holds scores of tokens t0 + 8*grp + e, e = 0..7 (sa: e<4, sb: e>=4)
         float sc[8];
@@ -333,19 +338,16 @@ __global__ __launch_bounds__(AF_WAVES * 64) void attn_fused_kernel(const float *
         sQ[1][r][e + HALF] = bf16_bits_rne(q1 - __uint_as_float((uint32_t)h1 << 16));
     }
     __syncthreads(); // q in LDS; the new cache rows are visible to this block's later loads
-    bf16x8 qv[NC], ql[NC];
-#pragma unroll
-    for (int c = 0; c < NC; c++) {
-        qv[c] = *(const bf16x8 *)(&sQ[0][qi][grp * (HD / 4) + c * 8]);
-        ql[c] = *(const bf16x8 *)(&sQ[1][qi][grp * (HD / 4) + c * 8]);
-    }
+    // the Q^T operand stays in LDS: lane (q, grp) reads Q[q][grp*(HD/4) + c*8 .. +8] per tile
+    const bf16x8 *qv = (const bf16x8 *)(&sQ[0][qi][grp * (HD / 4)]);
+    const bf16x8 *ql = (const bf16x8 *)(&sQ[1][qi][grp * (HD / 4)]);
     const int n_tiles = nq > 0 ? (Lk + AT_TILE - 1) / AT_TILE : 0;
     const int vis = kv0 + qi;
     float m_run = AT_NEG, l_run = 0.f;
     f32x4 o[ND];
 #pragma unroll
     for (int d = 0; d < ND; d++) o[d] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    attn_tiles<HD>(K, Vt, total_cap, qv, ql, vis, wave, n_tiles, AF_WAVES, m_run, l_run, o);
+    attn_tiles<HD, true>(K, Vt, total_cap, qv, ql, vis, wave, n_tiles, AF_WAVES, m_run, l_run, o);
     l_run += __shfl_xor(l_run, 16, 64);
     l_run += __shfl_xor(l_run, 32, 64);
     // ---- merge round 1: waves 4..7 hand their state to waves 0..3
