@@ -70,8 +70,10 @@ typedef struct {
 
 /* Device pointers to the weights, each matrix row-major [out][in] in the model's
  * dtype; RMSNorm gains are fp32 in both dtypes.  The per-layer members are HOST
- * arrays of n_layers DEVICE pointers.  Pointers are borrowed: the caller keeps the
- * memory alive until sd_free_model.  Matrices must be 16-byte aligned. */
+ * arrays of n_layers DEVICE pointers.  sd_load_model copies every array into
+ * memory the model owns (bf16 matrices are re-ordered into the tile order its
+ * GEMM kernels stream), so the caller may release its buffers as soon as
+ * sd_load_model has returned.  Matrices must be 16-byte aligned. */
 typedef struct {
     const void *embed;         /* [vocab][d_model] */
     const void *lm_head;       /* [vocab][d_model] */
@@ -87,9 +89,11 @@ typedef struct {
     const float *const *norm_ffn;  /* [d_model] */
 } sd_weights;
 
-/* Validate the configuration, record the borrowed weight pointers, build the
- * rotary table and allocate the activation workspace on the current device.
- * Synchronises.  SD_EINVAL on unsupported shapes. */
+/* Validate the configuration, copy the weights into the model's own device
+ * memory (one allocation of about the size of the weights), build the rotary
+ * table and allocate the activation workspace on the current device.
+ * Synchronises.  SD_EINVAL on unsupported shapes, SD_EHIP if an allocation or
+ * copy fails (nothing is leaked). */
 int sd_load_model(const sd_model_config *cfg, const sd_weights *w, sd_model **out);
 int sd_free_model(sd_model *m);
 
@@ -171,9 +175,9 @@ int sd_route(const float *W, const float *b, int32_t n_drafts, int32_t emb_dim, 
 int sd_ctx_sync(sd_ctx *c, sd_model *m, int32_t *n_tokens, int32_t *kv_len);
 /* Copy up to max_tokens tokens of sequence seq to host; *n_out = its length. */
 int sd_ctx_get_tokens(sd_ctx *c, int32_t seq, int32_t *out, int32_t max_tokens, int32_t *n_out);
-/* Load synthetic cache rows for one layer and sequence: k, v HOST arrays
- * [len][n_heads][head_dim] in the model's dtype; sets that model's cache length
- * for the sequence to len. */
+/* Load synthetic cache rows for one layer and sequence: k, v arrays
+ * [len][n_heads][head_dim] in the model's dtype, in HOST or DEVICE memory; sets
+ * that model's cache length for the sequence to len. */
 int sd_ctx_set_kv(sd_ctx *c, sd_model *m, int32_t layer, int32_t seq, const void *k, const void *v, int32_t len);
 /* KV rollback by hand: set model m's cache length for sequence seq to
  * min(current, len).  Rows beyond stay in memory and are overwritten later. */

@@ -122,7 +122,8 @@ def to_device(a: np.ndarray, device="cuda") -> torch.Tensor:
 
 
 class Model:
-    """sd_load_model / sd_free_model.  Keeps the weight tensors alive (the library borrows them)."""
+    """sd_load_model / sd_free_model.  The library copies the weights at load, so the staging
+    tensors are released right after."""
 
     def __init__(self, shape, weights: Dict[str, object], max_rows: int, max_pos: int, device="cuda"):
         self.shape = shape
@@ -145,6 +146,8 @@ class Model:
         with torch.cuda.device(device):
             _check(lib().sd_load_model(C.byref(cfg), C.byref(w), C.byref(h)))
         self.h = h
+        self.t.clear()
+        self._arrs.clear()
 
     def close(self):
         if getattr(self, "h", None):
@@ -223,7 +226,12 @@ class Context:
     def truncate(self, m: Model, seq: int, length: int) -> None:
         _check(lib().sd_ctx_truncate(self.h, m.h, seq, length))
 
-    def set_kv(self, m: Model, layer: int, seq: int, k: np.ndarray, v: np.ndarray) -> None:
+    def set_kv(self, m: Model, layer: int, seq: int, k, v) -> None:
+        """k, v: [len][n_heads][head_dim] numpy arrays (host) or contiguous torch tensors (device)."""
+        if isinstance(k, torch.Tensor):
+            assert k.is_contiguous() and v.is_contiguous()
+            _check(lib().sd_ctx_set_kv(self.h, m.h, layer, seq, _dp(k), _dp(v), k.shape[0]))
+            return
         k, v = np.ascontiguousarray(k), np.ascontiguousarray(v)
         _check(lib().sd_ctx_set_kv(self.h, m.h, layer, seq, k.ctypes.data_as(C.c_void_p),
                                    v.ctypes.data_as(C.c_void_p), k.shape[0]))

@@ -273,7 +273,6 @@ __global__ __launch_bounds__(AF_WAVES * 64) void attn_fused_kernel(const float *
                                                                    int64_t total_cap, uint16_t *__restrict__ obuf,
                                                                    size_t o_plane)
 {
-    constexpr int NC = HD / 32;
     constexpr int ND = HD / 16;
     constexpr int HALF = HD / 2;
     __shared__ float sO[4][ND][64][4];

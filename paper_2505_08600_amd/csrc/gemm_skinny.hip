@@ -9,12 +9,12 @@
 //    the same K chunks, so the activation chunk is staged ONCE per block in LDS
 //    (double buffered) instead of being fetched by every wave from L2 - at these
 //    sizes the shared activation lines, not HBM, were the bottleneck otherwise;
-//  * per chunk a lane loads 64 contiguous bytes per 128-element step of its weight
-//    row straight into MFMA operand registers (v_mfma_f32_16x16x32_bf16: lane l
-//    supplies row l%16, k-group l/16), all steps of the chunk in flight at once: a
-//    wave reads one contiguous kilobyte (packed case) of each of its 16 rows per
-//    chunk.  The contraction index is permuted identically for both operands, which
-//    a dot product does not care about;
+//  * weights are stored in 16-row x 128-element tiles in MFMA operand order, so each
+//    of the four load instructions of a K step reads one contiguous kilobyte straight
+//    into operand registers (v_mfma_f32_16x16x32_bf16: lane l supplies row l%16,
+//    k-group l/16), all steps of a chunk in flight at once.  Row-major weights would
+//    spread every such load over 16 rows 2K bytes apart, which lands on one L2 channel
+//    and limits a compute unit to about a third of the rate it reaches on the tiles;
 //  * activations are two bf16 planes (hi + lo, ~16 mantissa bits).  For M <= 8 both
 //    planes ride in ONE operand: MFMA columns 0..7 carry the hi rows, columns 8..15
 //    the lo rows, and the epilogue adds the two halves with one lane exchange; for
@@ -74,17 +74,20 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_stream_kernel(const uint16_t 
     const int kb = blockIdx.y * k_per_split;
     const int ke = min(K, kb + k_per_split);
     const int nchunks = (ke - kb + KC - 1) / KC;
-    // weight rows of this lane
+    // this lane's 16 bytes inside the first K step of each of the wave's 16-row weight tiles (tiled order:
+    // a tile's steps are 2048 elements apart, the four load instructions of a step 512 elements)
+    const size_t tile_elems = (size_t)(K >> 7) * 2048;
     const uint16_t *Wp[NT];
     if (MODE == GEMM_SWIGLU) {
 #pragma unroll
         for (int c = 0; c < NT; c++)
-            Wp[c] = (const uint16_t *)w.p[c & 1] + (size_t)(n0 + (wave * (NT / 2) + (c >> 1)) * 16 + row) * K;
+            Wp[c] = (const uint16_t *)w.p[c & 1] + (size_t)(n0 / 16 + wave * (NT / 2) + (c >> 1)) * tile_elems + lane * 8;
     } else {
         const int seg = n0 / w.n_per_seg;
         const int nl = n0 - seg * w.n_per_seg;
 #pragma unroll
-        for (int c = 0; c < NT; c++) Wp[c] = (const uint16_t *)w.p[seg] + (size_t)(nl + (wave * NT + c) * 16 + row) * K;
+        for (int c = 0; c < NT; c++)
+            Wp[c] = (const uint16_t *)w.p[seg] + (size_t)(nl / 16 + wave * NT + c) * tile_elems + lane * 8;
     }
     // cooperative staging of the activation chunk: vector v -> operand row v / VEC_PER_ROW
     const uint16_t *a_src[LPT];
@@ -136,11 +139,11 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_stream_kernel(const uint16_t 
         for (int c = 0; c < NT; c++)
 #pragma unroll
             for (int st = 0; st < STEPS; st++) {
-                const int k = k0 + st * 128 + grp * 32;
+                const int k = k0 + st * 128;
                 const bool live = k < ke;
-                const bf16x8 *p = (const bf16x8 *)(Wp[c] + (live ? k : kb));
+                const uint16_t *p = Wp[c] + (size_t)((live ? k : kb) >> 7) * 2048;
 #pragma unroll
-                for (int i = 0; i < 4; i++) wv[c][st][i] = live ? p[i] : zero;
+                for (int i = 0; i < 4; i++) wv[c][st][i] = live ? *(const bf16x8 *)(p + i * 512) : zero;
             }
     };
     w_issue(0);
@@ -155,7 +158,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_stream_kernel(const uint16_t 
         for (int st = 0; st < STEPS; st++) {
 #pragma unroll
             for (int i = 0; i < 4; i++) {
-                const int kk = st * 128 + grp * 32 + i * 8;
+                const int kk = st * 128 + i * 32 + grp * 8; // MFMA i contracts elements 32*i .. 32*i+31 of the step
 #pragma unroll
                 for (int t = 0; t < MT; t++) {
                     if (PACKED) {
@@ -228,66 +231,92 @@ static void split_geometry(int K, int ks, int *kps, int *ny)
     *ny = (K + *kps - 1) / *kps;
 }
 
-// SwiGLU gate/up GEMM, K split over the 4 waves of a block instead of over blocks (silu(gate)*up needs
-// the complete sums, so partial slabs would cost an extra pass).  A block owns 16 output columns: the gate
-// and the up tile; its waves interleave the 128-element K steps and fetch their activation fragments
-// straight from global memory (L2); the four partial accumulators meet in LDS.  Measured faster than the
-// chunk-staged kernel above for this shape (688 blocks keep more loads in flight than 172 could).
-template <bool PACKED, int MT>
-__global__ __launch_bounds__(256) void gemm_swiglu_kernel(const uint16_t *__restrict__ A, size_t a_plane,
-                                                          const uint16_t *__restrict__ Wg,
-                                                          const uint16_t *__restrict__ Wu, int M, int N, int K,
+// Few-row GEMM with the K range split over the 4 waves of a block (and optionally over grid.y).
+// A block owns NTW 16-column tiles of NMAT matrices: NMAT = 1 stores fp32 sums (one slab per grid.y
+// split), NMAT = 2 is the gate/up pair of the same columns with the SwiGLU epilogue (silu(gate)*up needs
+// complete sums, so there grid.y is 1).  The waves interleave the 128-element K steps, fetch their
+// activation fragments straight from global memory (L2) - no barrier inside the K loop - and keep the
+// loads of U steps in flight in registers; the four partial accumulators meet in LDS.
+template <int NMAT, bool PACKED, int MT, int U, int NTW>
+__global__ __launch_bounds__(256) void gemm_ksplit_kernel(const uint16_t *__restrict__ A, size_t a_plane, WeightSeg w,
+                                                          int M, int N, int K, int steps_per_split,
+                                                          float *__restrict__ C, size_t c_split_stride,
                                                           uint16_t *__restrict__ Cact, size_t c_plane)
 {
     constexpr int WAVES = 4;
-    __shared__ float red[WAVES][2][MT][64][4];
+    constexpr int NW = NMAT * NTW; // weight tiles per wave and step
+    __shared__ float red[WAVES][NW][MT][64][4];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int row = lane & 15, grp = lane >> 4;
-    const int n0 = blockIdx.x * 16;
-    const uint16_t *Wp[2] = {Wg + (size_t)(n0 + row) * K, Wu + (size_t)(n0 + row) * K};
+    const int n0 = blockIdx.x * 16 * NTW;
+    // tiled weights: step st of a tile starts 2048*st elements after the tile, instruction i of a step
+    // 512*i after that; tile j of matrix c is Wp[c] + j * tile_elems
+    const size_t tile_elems = (size_t)(K >> 7) * 2048;
+    const uint16_t *Wp[NMAT];
+    if (NMAT == 2) {
+#pragma unroll
+        for (int c = 0; c < NMAT; c++) Wp[c] = (const uint16_t *)w.p[c] + (size_t)(n0 / 16) * tile_elems + lane * 8;
+    } else {
+        const int seg = n0 / w.n_per_seg;
+        Wp[0] = (const uint16_t *)w.p[seg] + (size_t)((n0 - seg * w.n_per_seg) / 16) * tile_elems + lane * 8;
+    }
     const uint16_t *Ap[MT], *Al[MT];
     bool a_live[MT];
 #pragma unroll
     for (int t = 0; t < MT; t++) {
         const int m = PACKED ? (row & 7) : t * 16 + row;
         a_live[t] = m < M;
-        Ap[t] = A + ((PACKED && row >= 8) ? a_plane : 0) + (size_t)(a_live[t] ? m : 0) * K;
+        Ap[t] = A + ((PACKED && row >= 8) ? a_plane : 0) + (size_t)(a_live[t] ? m : 0) * K + grp * 8;
         Al[t] = Ap[t] + a_plane;
     }
-    f32x4 acc[2][MT];
+    f32x4 acc[NW][MT];
 #pragma unroll
-    for (int c = 0; c < 2; c++)
+    for (int c = 0; c < NW; c++)
 #pragma unroll
         for (int t = 0; t < MT; t++) acc[c][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    const int nsteps = K / 128;
+    const int s_begin = blockIdx.y * steps_per_split;
+    const int s_end = min(K / 128, s_begin + steps_per_split);
     const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-    for (int s = wave; s < nsteps; s += WAVES) {
-        const int k = s * 128 + grp * 32;
-        bf16x8 wv[2][4], av[MT][4], al[MT][4];
-#pragma unroll
-        for (int c = 0; c < 2; c++)
-#pragma unroll
-            for (int i = 0; i < 4; i++) wv[c][i] = *(const bf16x8 *)(Wp[c] + k + i * 8);
+    // U register buffers: the loads of the wave's next U-1 steps are in flight while one step is consumed
+    bf16x8 wv[U][NW][4], av[U][MT][4], al[U][PACKED ? 1 : MT][4];
+    auto issue = [&](int st, int b) {
 #pragma unroll
         for (int t = 0; t < MT; t++)
 #pragma unroll
             for (int i = 0; i < 4; i++) {
-                av[t][i] = a_live[t] ? *(const bf16x8 *)(Ap[t] + k + i * 8) : zero;
-                if (!PACKED) al[t][i] = a_live[t] ? *(const bf16x8 *)(Al[t] + k + i * 8) : zero;
+                av[b][t][i] = a_live[t] ? *(const bf16x8 *)(Ap[t] + st * 128 + i * 32) : zero;
+                if (!PACKED) al[b][t][i] = a_live[t] ? *(const bf16x8 *)(Al[t] + st * 128 + i * 32) : zero;
             }
 #pragma unroll
-        for (int i = 0; i < 4; i++)
+        for (int c = 0; c < NW; c++)
 #pragma unroll
-            for (int t = 0; t < MT; t++)
+            for (int i = 0; i < 4; i++)
+                wv[b][c][i] = *(const bf16x8 *)(Wp[c % NMAT] + (size_t)(c / NMAT) * tile_elems + (size_t)st * 2048 + i * 512);
+    };
 #pragma unroll
-                for (int c = 0; c < 2; c++) {
-                    acc[c][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv[c][i], av[t][i], acc[c][t], 0, 0, 0);
-                    if (!PACKED)
-                        acc[c][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv[c][i], al[t][i], acc[c][t], 0, 0, 0);
-                }
+    for (int u = 0; u < U; u++)
+        if (s_begin + wave + u * WAVES < s_end) issue(s_begin + wave + u * WAVES, u);
+    for (int s = s_begin + wave; s < s_end; s += U * WAVES) {
+#pragma unroll
+        for (int u = 0; u < U; u++) {
+            const int cur = s + u * WAVES;
+            if (cur < s_end) {
+#pragma unroll
+                for (int i = 0; i < 4; i++)
+#pragma unroll
+                    for (int t = 0; t < MT; t++)
+#pragma unroll
+                        for (int c = 0; c < NW; c++) {
+                            acc[c][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv[u][c][i], av[u][t][i], acc[c][t], 0, 0, 0);
+                            if (!PACKED)
+                                acc[c][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv[u][c][i], al[u][t][i], acc[c][t], 0, 0, 0);
+                        }
+                if (cur + U * WAVES < s_end) issue(cur + U * WAVES, u);
+            }
+        }
     }
 #pragma unroll
-    for (int c = 0; c < 2; c++)
+    for (int c = 0; c < NW; c++)
 #pragma unroll
         for (int t = 0; t < MT; t++)
 #pragma unroll
@@ -295,24 +324,30 @@ __global__ __launch_bounds__(256) void gemm_swiglu_kernel(const uint16_t *__rest
     __syncthreads();
     // tile element D[n = 4*(slot/16) + r][m' = slot%16] sits at red[.][c][t][slot][r]
     constexpr int ROWS = PACKED ? 8 : 16 * MT;
-    for (int e = threadIdx.x; e < 16 * ROWS; e += 256) {
-        const int nn = e & 15, m = e >> 4;
+    for (int e = threadIdx.x; e < 16 * NTW * ROWS; e += 256) {
+        const int nn = e & 15, j = (e >> 4) % NTW, m = e / (16 * NTW);
         if (m >= M) continue;
         const int t = PACKED ? 0 : m >> 4;
         const int slot = (nn >> 2) * 16 + (m & 15), r = nn & 3;
-        float v[2] = {0.f, 0.f};
+        float v[NMAT];
 #pragma unroll
-        for (int c = 0; c < 2; c++)
+        for (int c = 0; c < NMAT; c++) {
+            v[c] = 0.f;
 #pragma unroll
             for (int wv2 = 0; wv2 < WAVES; wv2++) {
-                v[c] += red[wv2][c][t][slot][r];
-                if (PACKED) v[c] += red[wv2][c][t][slot + 8][r];
+                v[c] += red[wv2][j * NMAT + c][t][slot][r];
+                if (PACKED) v[c] += red[wv2][j * NMAT + c][t][slot + 8][r];
             }
-        const float y = v[0] / (1.0f + expf(-v[0])) * v[1];
-        const uint16_t hi = bf16_bits_rne(y);
-        const size_t o = (size_t)m * N + n0 + nn;
-        Cact[o] = hi;
-        Cact[c_plane + o] = bf16_bits_rne(y - __uint_as_float((uint32_t)hi << 16));
+        }
+        const size_t o = (size_t)m * N + n0 + j * 16 + nn;
+        if (NMAT == 2) {
+            const float y = v[0] / (1.0f + expf(-v[0])) * v[NMAT - 1];
+            const uint16_t hi = bf16_bits_rne(y);
+            Cact[o] = hi;
+            Cact[c_plane + o] = bf16_bits_rne(y - __uint_as_float((uint32_t)hi << 16));
+        } else {
+            C[(size_t)blockIdx.y * c_split_stride + o] = v[0];
+        }
     }
 }
 
@@ -354,6 +389,14 @@ int gemm_skinny_splits(int mode, int M, int N, int K)
         return ny;
     }
     int blocks, target;
+    if (M <= 16 && g_skinny_tune[mode][0] == 4) { // K-split kernel: 32 columns per block, each wave at least 2 steps
+        blocks = N / 32;
+        const int steps = K / 128;
+        int ks = steps >= 16 ? 2 : 1; // measured: two half-length blocks per tile stream faster than one
+        while (blocks * ks < 256 && ks < 8 && steps / (ks * 2) >= 4) ks *= 2;
+        split_geometry(K, ks, &kps, &ny);
+        return ny;
+    }
     if (M <= 32) {
         blocks = N / (16 * g_skinny_tune[mode][0]);
         target = 768; // about three blocks per CU
@@ -374,6 +417,7 @@ hipError_t launch_gemm_skinny_bf16(hipStream_t s, int mode, const void *A, size_
                                    int K, float *C, size_t c_split_stride, int splits, void *Cact, size_t c_plane)
 {
     if (M < 1 || K % 128 != 0 || K < 128 || (mode != GEMM_STORE && mode != GEMM_SWIGLU)) return hipErrorNotSupported;
+    if (!w.tiled) return hipErrorNotSupported; // these kernels read the 16 x 128 tile order only
     for (int i = 0; i < 3; i++)
         if (w.p[i] && ((uintptr_t)w.p[i] & 15)) return hipErrorNotSupported;
     if (((uintptr_t)A & 15) || (a_plane & 7) || (N & 3)) return hipErrorNotSupported;
@@ -392,14 +436,21 @@ hipError_t launch_gemm_skinny_bf16(hipStream_t s, int mode, const void *A, size_
     }
     if (mode == GEMM_SWIGLU && g_skinny_tune[GEMM_SWIGLU][1] == 0) { // default: K split inside the block
         if (N % 16 != 0) return hipErrorNotSupported;
-        const uint16_t *wg = (const uint16_t *)w.p[0], *wu = (const uint16_t *)w.p[1];
         dim3 grid(N / 16), block(256);
-        if (M <= 8)
-            hipLaunchKernelGGL((gemm_swiglu_kernel<true, 1>), grid, block, 0, s, a, a_plane, wg, wu, M, N, K, ca, c_plane);
-        else if (M <= 16)
-            hipLaunchKernelGGL((gemm_swiglu_kernel<false, 1>), grid, block, 0, s, a, a_plane, wg, wu, M, N, K, ca, c_plane);
-        else
-            hipLaunchKernelGGL((gemm_swiglu_kernel<false, 2>), grid, block, 0, s, a, a_plane, wg, wu, M, N, K, ca, c_plane);
+#define SD_KSPLIT(NMAT, PACKED, MT, U, NTW, GRID, SPS)                                                              \
+    hipLaunchKernelGGL((gemm_ksplit_kernel<NMAT, PACKED, MT, U, NTW>), GRID, dim3(256), 0, s, a, a_plane, w, M, N, K, \
+                       SPS, C, c_split_stride, ca, c_plane)
+        if (M <= 8) SD_KSPLIT(2, true, 1, 2, 1, grid, K / 128);
+        else if (M <= 16) SD_KSPLIT(2, false, 1, 2, 1, grid, K / 128);
+        else SD_KSPLIT(2, false, 2, 1, 1, grid, K / 128);
+        return hipGetLastError();
+    }
+    if (mode == GEMM_STORE && waves == 4 && M <= 16 && N % 32 == 0 && w.n_per_seg % 32 == 0) {
+        int kps, ny;
+        split_geometry(K, splits, &kps, &ny);
+        dim3 grid(N / 32, ny);
+        if (M <= 8) SD_KSPLIT(1, true, 1, 2, 2, grid, kps / 128);
+        else SD_KSPLIT(1, false, 1, 2, 2, grid, kps / 128);
         return hipGetLastError();
     }
     if (mode == GEMM_SWIGLU) {

@@ -6,6 +6,7 @@
 // Paper (arXiv 2505.08600): Section 1 / Figure 1 (draft rows, verify rows),
 // Section 3.1 (LLaMA blocks; speculative-sampling verification, greedy limit).
 #include "sd_internal.h"
+#include <algorithm>
 
 #define WAVE 64
 
@@ -238,20 +239,23 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const T *A, size_t a_
     int m0 = blockIdx.y * 16;
     if (n >= N) return;
     const T *W0, *W1 = nullptr;
+    int nl = n; // row inside its segment
     if (MODE == GEMM_SWIGLU) {
-        W0 = (const T *)w.p[0] + (size_t)n * K;
-        W1 = (const T *)w.p[1] + (size_t)n * K;
+        W0 = (const T *)w.p[0];
+        W1 = (const T *)w.p[1];
     } else {
         int seg = n / w.n_per_seg;
-        W0 = (const T *)w.p[seg] + (size_t)(n - seg * w.n_per_seg) * K;
+        nl = n - seg * w.n_per_seg;
+        W0 = (const T *)w.p[seg];
     }
     float acc[16], acc2[16];
 #pragma unroll
     for (int m = 0; m < 16; m++) acc[m] = acc2[m] = 0.f;
     int mcount = M - m0 < 16 ? M - m0 : 16;
     for (int k = lane; k < K; k += WAVE) {
-        float wv = to_float(W0[k]);
-        float wv2 = MODE == GEMM_SWIGLU ? to_float(W1[k]) : 0.f;
+        const size_t wi = weight_index(nl, k, K, w.tiled);
+        float wv = to_float(W0[wi]);
+        float wv2 = MODE == GEMM_SWIGLU ? to_float(W1[wi]) : 0.f;
 #pragma unroll
         for (int m = 0; m < 16; m++) {
             if (m < mcount) {
@@ -277,6 +281,31 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const T *A, size_t a_
             }
         }
     }
+}
+
+// Row-major -> tiled weight order, one 16-byte piece per thread (destination-linear, so stores coalesce).
+__global__ __launch_bounds__(256) void retile_bf16_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst,
+                                                          int N, int K)
+{
+    const size_t n_vec = (size_t)N * K / 8;
+    for (size_t v = (size_t)blockIdx.x * 256 + threadIdx.x; v < n_vec; v += (size_t)gridDim.x * 256) {
+        const size_t step = v >> 8;            // 256 pieces per 16 x 128 step
+        const int piece = (int)(v & 255);
+        const int i = piece >> 6, g = (piece >> 4) & 3, r = piece & 15;
+        const size_t steps_per_tile = (size_t)(K >> 7);
+        const size_t n = (step / steps_per_tile) * 16 + r;
+        const size_t k = (step % steps_per_tile) * 128 + i * 32 + g * 8;
+        dst[v] = src[(n * K + k) / 8];
+    }
+}
+
+hipError_t launch_retile_bf16(hipStream_t s, const void *src, void *dst, int N, int K)
+{
+    if (N % 16 != 0 || K % 128 != 0) return hipErrorInvalidValue;
+    const size_t n_vec = (size_t)N * K / 8;
+    const int blocks = (int)std::min<size_t>((n_vec + 255) / 256, 8192);
+    hipLaunchKernelGGL(retile_bf16_kernel, dim3(blocks), dim3(256), 0, s, (const uint4 *)src, (uint4 *)dst, N, K);
+    return hipGetLastError();
 }
 
 template <typename T>

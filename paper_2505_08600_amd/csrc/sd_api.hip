@@ -141,21 +141,60 @@ extern "C" int sd_load_model(const sd_model_config *cfg, const sd_weights *w, sd
             return sd_fail(SD_EINVAL, "sd_load_model: null per-layer weight pointer");
     sd_model *m = new sd_model();
     m->cfg = c;
-    m->embed = w->embed;
-    m->lm_head = w->lm_head;
-    m->final_norm = w->final_norm;
-    for (int l = 0; l < c.n_layers; l++) {
-        m->wq.push_back(w->wq[l]);
-        m->wk.push_back(w->wk[l]);
-        m->wv.push_back(w->wv[l]);
-        m->wo.push_back(w->wo[l]);
-        m->wgate.push_back(w->wgate[l]);
-        m->wup.push_back(w->wup[l]);
-        m->wdown.push_back(w->wdown[l]);
-        m->norm_attn.push_back(w->norm_attn[l]);
-        m->norm_ffn.push_back(w->norm_ffn[l]);
-    }
     m->esz = c.dtype == SD_BF16 ? 2 : 4;
+    // ---- weights: one arena owned by the model.  bf16 matrices whose shape allows it are re-ordered into
+    // 16 x 128 tiles on the way (the streaming GEMMs read those); everything else is copied as is.
+    {
+        const size_t d = c.d_model, F = c.d_ffn, V = c.vocab, esz = m->esz;
+        auto can_tile = [&](size_t N, size_t K) { return c.dtype == SD_BF16 && N % 16 == 0 && K % 128 == 0; };
+        m->tiled_dd = can_tile(d, d);
+        m->tiled_fd = can_tile(F, d);
+        m->tiled_df = can_tile(d, F);
+        m->tiled_lm = can_tile(V, d);
+        auto pad = [](size_t b) { return (b + 255) & ~(size_t)255; };
+        const size_t b_dd = pad(d * d * esz), b_fd = pad(F * d * esz), b_vd = pad(V * d * esz), b_g = pad(d * 4);
+        const size_t total = 2 * b_vd + b_g + (size_t)c.n_layers * (4 * b_dd + 3 * b_fd + 2 * b_g);
+        hipError_t we = hipMalloc(&m->wmem, total);
+        if (we != hipSuccess) {
+            delete m;
+            return sd_fail(SD_EHIP, std::string("sd_load_model: hipMalloc(weights): ") + hipGetErrorString(we));
+        }
+        char *cur = (char *)m->wmem;
+        auto put = [&](const void *src, size_t N, size_t K, size_t bytes, int tiled) -> const void * {
+            void *dst = cur;
+            cur += bytes;
+            if (we != hipSuccess) return dst;
+            if (tiled) we = launch_retile_bf16(0, src, dst, (int)N, (int)K);
+            else we = hipMemcpyAsync(dst, src, N * K * esz, hipMemcpyDeviceToDevice, 0);
+            return dst;
+        };
+        auto put_gain = [&](const float *src) -> const float * {
+            void *dst = cur;
+            cur += b_g;
+            if (we == hipSuccess) we = hipMemcpyAsync(dst, src, d * 4, hipMemcpyDeviceToDevice, 0);
+            return (const float *)dst;
+        };
+        m->embed = put(w->embed, V, d, b_vd, 0); // gathered by row: stays row-major
+        m->lm_head = put(w->lm_head, V, d, b_vd, m->tiled_lm);
+        m->final_norm = put_gain(w->final_norm);
+        for (int l = 0; l < c.n_layers; l++) {
+            m->wq.push_back(put(w->wq[l], d, d, b_dd, m->tiled_dd));
+            m->wk.push_back(put(w->wk[l], d, d, b_dd, m->tiled_dd));
+            m->wv.push_back(put(w->wv[l], d, d, b_dd, m->tiled_dd));
+            m->wo.push_back(put(w->wo[l], d, d, b_dd, m->tiled_dd));
+            m->wgate.push_back(put(w->wgate[l], F, d, b_fd, m->tiled_fd));
+            m->wup.push_back(put(w->wup[l], F, d, b_fd, m->tiled_fd));
+            m->wdown.push_back(put(w->wdown[l], d, F, b_fd, m->tiled_df));
+            m->norm_attn.push_back(put_gain(w->norm_attn[l]));
+            m->norm_ffn.push_back(put_gain(w->norm_ffn[l]));
+        }
+        if (we == hipSuccess) we = hipStreamSynchronize(0);
+        if (we != hipSuccess) {
+            (void)hipFree(m->wmem);
+            delete m;
+            return sd_fail(SD_EHIP, std::string("sd_load_model: weight copy: ") + hipGetErrorString(we));
+        }
+    }
     m->last_lm_rows = 0;
     size_t M = c.max_rows, d = c.d_model;
     m->part_floats = attn_part_floats(c);
@@ -182,7 +221,7 @@ extern "C" int sd_load_model(const sd_model_config *cfg, const sd_weights *w, sd
     alloc((void **)&m->rope, (size_t)c.max_pos * (c.head_dim / 2) * sizeof(float2));
     alloc((void **)&m->plan_mem, (5 * M + 3 * M) * sizeof(int32_t));
     if (e != hipSuccess) {
-        delete m;
+        sd_free_model(m);
         return sd_fail(SD_EHIP, std::string("sd_load_model: hipMalloc: ") + hipGetErrorString(e));
     }
     int32_t *pm = m->plan_mem;
@@ -226,6 +265,7 @@ extern "C" int sd_free_model(sd_model *m)
     (void)hipFree(m->gpart_r);
     (void)hipFree(m->rope);
     (void)hipFree(m->plan_mem);
+    (void)hipFree(m->wmem);
     delete m;
     return SD_OK;
 }
@@ -396,8 +436,8 @@ extern "C" int sd_ctx_set_kv(sd_ctx *c, sd_model *m, int32_t layer, int32_t seq,
     if (len > 0) {
         SD_HIP(hipMalloc(&dk, bytes));
         SD_HIP(hipMalloc(&dv, bytes));
-        SD_HIP(hipMemcpy(dk, k, bytes, hipMemcpyHostToDevice));
-        SD_HIP(hipMemcpy(dv, v, bytes, hipMemcpyHostToDevice));
+        SD_HIP(hipMemcpy(dk, k, bytes, hipMemcpyDefault)); // host or device source
+        SD_HIP(hipMemcpy(dv, v, bytes, hipMemcpyDefault));
         size_t lstride = (size_t)m->cfg.d_model * c->total_cap * m->esz;
         hipError_t e = launch_set_kv(0, m->cfg.dtype, dk, dv, len, m->cfg.n_heads, m->cfg.head_dim, c->off[seq],
                                      c->total_cap, (char *)c->kcache[s] + layer * lstride,
@@ -534,7 +574,7 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
             FWD(launch_rmsnorm(s, cf.dtype, m->x, m->norm_attn[l], nullptr, M, d, cf.rms_eps, m->abuf, m->plane_d));
         }
         pending = 0;
-        WeightSeg wqkv = {{m->wq[l], m->wk[l], m->wv[l]}, d};
+        WeightSeg wqkv = {{m->wq[l], m->wk[l], m->wv[l]}, d, m->tiled_dd};
         int nq_slabs;
         const float *qkv_src;
         { ProfScope ps(T_QKV, s);
@@ -566,7 +606,7 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
         }
         if (ea == hipErrorNotSupported) return sd_fail(SD_ECAP, "forward: context too long for the generic attention kernel");
         FWD(ea);
-        WeightSeg wo = {{m->wo[l], nullptr, nullptr}, d};
+        WeightSeg wo = {{m->wo[l], nullptr, nullptr}, d, m->tiled_dd};
         int no_slabs;
         { ProfScope ps(T_OPROJ, s);
         no_slabs = stream_gemm(m, s, m->obuf, m->plane_d, wo, M, d, d, m->gpart_r, m->gpart_r_floats, 0, &ge);
@@ -579,7 +619,7 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
         else
             FWD(launch_rmsnorm(s, cf.dtype, m->x, m->norm_ffn[l], nullptr, M, d, cf.rms_eps, m->abuf, m->plane_d));
         }
-        WeightSeg wgu = {{m->wgate[l], m->wup[l], nullptr}, F};
+        WeightSeg wgu = {{m->wgate[l], m->wup[l], nullptr}, F, m->tiled_fd};
         { ProfScope ps(T_GATEUP, s);
         hipError_t eg = hipErrorNotSupported;
         if (cf.dtype == SD_BF16 && !(g_force_generic & 1))
@@ -588,7 +628,7 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
         if (eg == hipErrorNotSupported)
             eg = gemm_generic(m, s, GEMM_SWIGLU, m->abuf, m->plane_d, wgu, M, F, d, nullptr, m->act, m->plane_f);
         FWD(eg); }
-        WeightSeg wd = {{m->wdown[l], nullptr, nullptr}, d};
+        WeightSeg wd = {{m->wdown[l], nullptr, nullptr}, d, m->tiled_df};
         { ProfScope ps(T_DOWN, s);
         pending = stream_gemm(m, s, m->act, m->plane_f, wd, M, d, F, m->gpart_r, m->gpart_r_floats, 0, &ge);
         FWD(ge);
@@ -603,7 +643,7 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
         else
             FWD(launch_rmsnorm(s, cf.dtype, m->x, m->final_norm, pv.lm_row, n_lm, d, cf.rms_eps, m->abuf, m->plane_d));
         }
-        WeightSeg wl = {{m->lm_head, nullptr, nullptr}, V};
+        WeightSeg wl = {{m->lm_head, nullptr, nullptr}, V, m->tiled_lm};
         { ProfScope ps(T_LMHEAD, s);
         int nl = stream_gemm(m, s, m->abuf, m->plane_d, wl, n_lm, V, d, m->logits, (size_t)cf.max_rows * V, 1, &ge);
         FWD(ge);

@@ -87,7 +87,28 @@ enum PlanMode { PLAN_CATCHUP = 0, PLAN_CAND = 1, PLAN_VERIFY = 2 };
 struct WeightSeg { // up to three matrices stacked along N (q,k,v or gate,up)
     const void *p[3];
     int32_t n_per_seg;
+    int32_t tiled; // 1: every segment is stored in the 16 x 128 tile order below instead of row-major
 };
+
+// Tiled weight order (bf16 matrices [N][K] with N % 16 == 0 and K % 128 == 0).  The 4 KiB that one wave
+// consumes per 128-element K step - 16 rows x 128 elements - are contiguous, steps of a 16-row tile
+// follow each other along K, and inside a step the 16-byte pieces are in MFMA operand order: piece
+// (i, g, r) = row r, elements 32*i + 8*g .. +8, at byte offset 1024*i + 16*(16*g + r).  A wave's load
+// instruction i therefore reads one contiguous kilobyte (lane = 16*g + r).  Row-major rows of 2*K bytes
+// put the 16 rows of such a load at a stride that maps to a single L2 channel, which caps one compute
+// unit at ~37 GB/s; the tiled order streams at ~100 GB/s per unit.
+#define SD_TILE_ROWS 16
+#define SD_TILE_K 128
+__host__ __device__ __forceinline__ size_t tiled_index(int n, int k, int K)
+{
+    const size_t step = (size_t)(n >> 4) * (size_t)(K >> 7) + (size_t)(k >> 7);
+    const int kk = k & 127;
+    return step * 2048 + (size_t)((kk >> 5) * 512 + ((((kk >> 3) & 3) * 16 + (n & 15)) * 8) + (kk & 7));
+}
+__host__ __device__ __forceinline__ size_t weight_index(int n, int k, int K, int tiled)
+{
+    return tiled ? tiled_index(n, k, K) : (size_t)n * K + k;
+}
 
 enum GemmMode { GEMM_STORE = 0, GEMM_RESID = 1, GEMM_SWIGLU = 2 };
 
@@ -98,6 +119,8 @@ struct sd_model {
     std::vector<const float *> norm_attn, norm_ffn;
     const void *embed, *lm_head;
     const float *final_norm;
+    void *wmem;     // arena holding the model's own copy of every weight
+    int tiled_dd, tiled_fd, tiled_df, tiled_lm; // tile order used for [d][d], [F][d], [d][F], [V][d] matrices
     int esz; // bytes per weight / activation element
     // workspace (device)
     float *x;       // [max_rows][d] residual stream
@@ -166,6 +189,8 @@ hipError_t launch_plan(hipStream_t s, int mode, int R, int n_seq, const int32_t 
 hipError_t launch_embed(hipStream_t s, int dtype, const void *E, const int32_t *row_tok, int M, int d, float *x);
 hipError_t launch_rmsnorm(hipStream_t s, int dtype, const float *x, const float *g, const int32_t *row_map,
                           int n_rows, int d, float eps, void *out, size_t out_plane);
+// row-major bf16 [N][K] -> tiled order (N % 16 == 0, K % 128 == 0); src and dst must not overlap
+hipError_t launch_retile_bf16(hipStream_t s, const void *src, void *dst, int N, int K);
 hipError_t launch_gemm_generic(hipStream_t s, int dtype, int mode, const void *A, size_t a_plane, WeightSeg w, int M,
                                int N, int K, float *C, void *Cact, size_t c_plane);
 hipError_t launch_rope_append(hipStream_t s, int dtype, const float *qkv, int n_slabs, size_t slab_stride, PlanView pv,

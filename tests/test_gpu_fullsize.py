@@ -98,8 +98,9 @@ def _batched_case(name, target_shape, draft_shapes, B, lens, gamma, T, seed, che
     tseqs = {b: ot.new_seq(int(lens[b]) + (n_steps + 1) * (gamma + 1) + 8) for b in check_ids}
     for l in range(target_shape.n_layers):
         k, v = dg.make_kv_rows(seed, l, 0, max_len - 1, target_shape.n_heads, target_shape.head_dim, target_shape.dtype)
+        kd, vd = H.dev(k.view(np.int16)), H.dev(v.view(np.int16))  # one upload per layer; rows are bf16 bit patterns
         for b in range(B):
-            ctx.set_kv(gt, l, b, k[:lens[b] - 1], v[:lens[b] - 1])
+            ctx.set_kv(gt, l, b, kd[:lens[b] - 1], vd[:lens[b] - 1])
         for b in check_ids:
             tseqs[b].set_kv(l, k[:lens[b] - 1], v[:lens[b] - 1])
     print(f"{name}: target caches loaded in {time.time() - t0:.1f}s", flush=True)
@@ -194,9 +195,10 @@ def test_config5_batch64_long_ragged_contexts():
     [1024, 8192], gamma = 8 (M = 576 rows), T = 1: long ragged KV (about 150 GB of cache), split
     attention and per-sequence rollback.  Proposals come from the 68M-shape draft here (the synthetic
     rho-mixed q of this config is exercised at full vocabulary in test_gpu_parity); oracle on the
-    shortest sequence and on one of median length."""
+    shortest sequence and on one at the lower quartile of length (the oracle's draft prefill
+    grows quadratically with the context; these two keep the test under two minutes of CPU work)."""
     seed, B = 5055, 64
     lens = dg.make_prompt_lengths(seed, B, 1024, 8192)
     order = np.argsort(lens)
     _batched_case("config5", dg.SHAPES["t7b"], [dg.SHAPES["draft_a"]], B, lens, 8, 1.0, seed,
-                  [int(order[0]), int(order[B // 2])])
+                  [int(order[0]), int(order[B // 4])])
