@@ -135,12 +135,12 @@ __device__ __forceinline__ void attn_tiles(const uint16_t *__restrict__ K, const
 }
 
 template <int HD>
-__global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restrict__ qbuf, size_t q_plane,
+__global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restrict__ qbuf, ActView q_av,
                                                         const uint16_t *__restrict__ Kl,
                                                         const uint16_t *__restrict__ Vtl, PlanView pv, CtxView cv,
                                                         int R, int H, int64_t total_cap, int S,
                                                         float *__restrict__ part, uint16_t *__restrict__ obuf,
-                                                        size_t o_plane)
+                                                        ActView o_av)
 {
     constexpr int NC = HD / 32; // 32-wide chunks of the head dimension (QK^T contraction)
     constexpr int ND = HD / 16; // 16-row tiles of V^T / O^T
@@ -164,9 +164,10 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restri
     const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
     for (int c = 0; c < NC; c++) {
-        const bf16x8 *p = (const bf16x8 *)(qbuf + (size_t)(j * R + (qi < R ? qi : 0)) * HDm + h * HD + grp * (HD / 4) + c * 8);
+        // 8 consecutive columns never straddle a 128-column step
+        const bf16x8 *p = (const bf16x8 *)(qbuf + act_index(q_av, j * R + (qi < R ? qi : 0), h * HD + grp * (HD / 4) + c * 8, HDm));
         qv[c] = qi < nq ? *p : zero;
-        ql[c] = qi < nq ? *(const bf16x8 *)((const uint16_t *)p + q_plane) : zero;
+        ql[c] = qi < nq ? *(const bf16x8 *)((const uint16_t *)p + q_av.plane) : zero;
     }
     const int vis = kv0 + qi; // last visible token of this lane's query row
     float m_run = AT_NEG, l_run = 0.f;
@@ -204,9 +205,9 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restri
         if (S == 1) {
             float out = (q < nq && L > 0.f) ? O / L : 0.f;
             uint16_t hi = bf16_bits_rne(out);
-            size_t oi = (size_t)(j * R + q) * HDm + h * HD + dim;
+            size_t oi = act_index(o_av, j * R + q, h * HD + dim, HDm);
             obuf[oi] = hi;
-            obuf[oi + o_plane] = bf16_bits_rne(out - __uint_as_float((uint32_t)hi << 16));
+            obuf[oi + o_av.plane] = bf16_bits_rne(out - __uint_as_float((uint32_t)hi << 16));
         } else {
             float *pp = part + ((size_t)(j * H + h) * S + s) * 16 * (HD + 2);
             pp[q * HD + dim] = O;
@@ -221,7 +222,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restri
 // Merge the S split partials of each (sequence, head): one block per (head, sequence).
 template <int HD>
 __global__ void attn_combine_kernel(const float *__restrict__ part, PlanView pv, int R, int H, int S,
-                                    uint16_t *__restrict__ obuf, size_t o_plane)
+                                    uint16_t *__restrict__ obuf, ActView o_av)
 {
     const int h = blockIdx.x, j = blockIdx.y;
     const int nq = pv.seq_nq[j];
@@ -252,9 +253,9 @@ __global__ void attn_combine_kernel(const float *__restrict__ part, PlanView pv,
             }
         float out = (q < nq && L > 0.f) ? O / L : 0.f;
         uint16_t hi = bf16_bits_rne(out);
-        size_t oi = (size_t)(j * R + q) * (H * HD) + h * HD + dim;
+        size_t oi = act_index(o_av, j * R + q, h * HD + dim, H * HD);
         obuf[oi] = hi;
-        obuf[oi + o_plane] = bf16_bits_rne(out - __uint_as_float((uint32_t)hi << 16));
+        obuf[oi + o_av.plane] = bf16_bits_rne(out - __uint_as_float((uint32_t)hi << 16));
     }
 }
 
@@ -271,7 +272,7 @@ __global__ __launch_bounds__(AF_WAVES * 64) void attn_fused_kernel(const float *
                                                                    int H, const float2 *__restrict__ rope, int max_pos,
                                                                    uint16_t *__restrict__ Kl, uint16_t *__restrict__ Vtl,
                                                                    int64_t total_cap, uint16_t *__restrict__ obuf,
-                                                                   size_t o_plane)
+                                                                   ActView o_av)
 {
     constexpr int ND = HD / 16;
     constexpr int HALF = HD / 2;
@@ -401,16 +402,16 @@ __global__ __launch_bounds__(AF_WAVES * 64) void attn_fused_kernel(const float *
         }
         const float out = (q < nq && L > 0.f) ? O / L : 0.f;
         const uint16_t hi = bf16_bits_rne(out);
-        const size_t oi = (size_t)(j * R + q) * HDm + h * HD + dim;
+        const size_t oi = act_index(o_av, j * R + q, h * HD + dim, HDm);
         obuf[oi] = hi;
-        obuf[oi + o_plane] = bf16_bits_rne(out - __uint_as_float((uint32_t)hi << 16));
+        obuf[oi + o_av.plane] = bf16_bits_rne(out - __uint_as_float((uint32_t)hi << 16));
     }
 }
 
 // Returns hipErrorNotSupported when the split path (RoPE kernel + split attention + combine) should run.
 hipError_t launch_attn_fused_bf16(hipStream_t s, const float *qkv, int n_slabs, size_t slab_stride, PlanView pv,
                                   CtxView cv, int R, int n_seq, int H, int hd, const float2 *rope, int max_pos,
-                                  void *Kl, void *Vtl, int64_t total_cap, int len_upper, void *obuf, size_t o_plane)
+                                  void *Kl, void *Vtl, int64_t total_cap, int len_upper, void *obuf, ActView o_av)
 {
     if (R < 1 || R > 16 || (hd != 64 && hd != 128) || n_slabs < 1 || n_slabs > 8) return hipErrorNotSupported;
     if (n_seq > 65535 || H > 65535) return hipErrorNotSupported;
@@ -421,16 +422,16 @@ hipError_t launch_attn_fused_bf16(hipStream_t s, const float *qkv, int n_slabs, 
     dim3 grid(H, n_seq), block(AF_WAVES * 64);
     if (hd == 128)
         hipLaunchKernelGGL(attn_fused_kernel<128>, grid, block, 0, s, qkv, n_slabs, slab_stride, pv, cv, R, H, rope,
-                           max_pos, (uint16_t *)Kl, (uint16_t *)Vtl, total_cap, (uint16_t *)obuf, o_plane);
+                           max_pos, (uint16_t *)Kl, (uint16_t *)Vtl, total_cap, (uint16_t *)obuf, o_av);
     else
         hipLaunchKernelGGL(attn_fused_kernel<64>, grid, block, 0, s, qkv, n_slabs, slab_stride, pv, cv, R, H, rope,
-                           max_pos, (uint16_t *)Kl, (uint16_t *)Vtl, total_cap, (uint16_t *)obuf, o_plane);
+                           max_pos, (uint16_t *)Kl, (uint16_t *)Vtl, total_cap, (uint16_t *)obuf, o_av);
     return hipGetLastError();
 }
 
-hipError_t launch_attn_mfma_bf16(hipStream_t s, const void *qbuf, size_t q_plane, const void *Kl, const void *Vtl,
+hipError_t launch_attn_mfma_bf16(hipStream_t s, const void *qbuf, ActView q_av, const void *Kl, const void *Vtl,
                                  PlanView pv, CtxView cv, int R, int n_seq, int H, int hd, int64_t total_cap,
-                                 int len_upper, float *part, size_t part_floats, void *obuf, size_t o_plane)
+                                 int len_upper, float *part, size_t part_floats, void *obuf, ActView o_av)
 {
     if (R < 1 || R > 16 || (hd != 64 && hd != 128)) return hipErrorNotSupported;
     if (n_seq > 65535 || H > 65535) return hipErrorNotSupported;
@@ -443,20 +444,20 @@ hipError_t launch_attn_mfma_bf16(hipStream_t s, const void *qbuf, size_t q_plane
     if (S < 1) S = 1;
     dim3 grid(S, H, n_seq), block(256);
     if (hd == 128)
-        hipLaunchKernelGGL(attn_mfma_kernel<128>, grid, block, 0, s, (const uint16_t *)qbuf, q_plane,
+        hipLaunchKernelGGL(attn_mfma_kernel<128>, grid, block, 0, s, (const uint16_t *)qbuf, q_av,
                            (const uint16_t *)Kl, (const uint16_t *)Vtl, pv, cv, R, H, total_cap, S, part,
-                           (uint16_t *)obuf, o_plane);
+                           (uint16_t *)obuf, o_av);
     else
-        hipLaunchKernelGGL(attn_mfma_kernel<64>, grid, block, 0, s, (const uint16_t *)qbuf, q_plane,
+        hipLaunchKernelGGL(attn_mfma_kernel<64>, grid, block, 0, s, (const uint16_t *)qbuf, q_av,
                            (const uint16_t *)Kl, (const uint16_t *)Vtl, pv, cv, R, H, total_cap, S, part,
-                           (uint16_t *)obuf, o_plane);
+                           (uint16_t *)obuf, o_av);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || S == 1) return e;
     if (hd == 128)
         hipLaunchKernelGGL(attn_combine_kernel<128>, dim3(H, n_seq), dim3(256), 0, s, part, pv, R, H, S,
-                           (uint16_t *)obuf, o_plane);
+                           (uint16_t *)obuf, o_av);
     else
         hipLaunchKernelGGL(attn_combine_kernel<64>, dim3(H, n_seq), dim3(256), 0, s, part, pv, R, H, S,
-                           (uint16_t *)obuf, o_plane);
+                           (uint16_t *)obuf, o_av);
     return hipGetLastError();
 }

@@ -1,28 +1,27 @@
-// bf16 weight-streaming GEMM for few rows (M <= 32): C[M][N] = A[M][K] . W[N][K]^T.
+// bf16 weight-streaming GEMMs: C[M][N] = A[M][K] . W[N][K]^T for the decoder's linear layers.
 //
-// This is the verify forward at batch 1 (M = gamma+1) and every draft step: the
-// work is reading each weight once from HBM, so the kernel is organised around
-// the weight stream, and the matrix cores only keep the ALUs out of the way.
+// At batch 1 (M = gamma+1 verify rows, or one draft row) the work is reading each
+// weight once from HBM, so the kernels are organised around the weight stream and
+// the matrix cores only keep the ALUs out of the way; at batch 32-64 (M = 192-576)
+// the same weight stream feeds enough rows for the matrix cores to matter.
 //
-//  * a block of WAVES waves covers WAVES*16*NT/... output columns and one K range
-//    (grid.y splits K); every wave owns NT 16-column tiles of W and all waves walk
-//    the same K chunks, so the activation chunk is staged ONCE per block in LDS
-//    (double buffered) instead of being fetched by every wave from L2 - at these
-//    sizes the shared activation lines, not HBM, were the bottleneck otherwise;
 //  * weights are stored in 16-row x 128-element tiles in MFMA operand order, so each
 //    of the four load instructions of a K step reads one contiguous kilobyte straight
 //    into operand registers (v_mfma_f32_16x16x32_bf16: lane l supplies row l%16,
-//    k-group l/16), all steps of a chunk in flight at once.  Row-major weights would
-//    spread every such load over 16 rows 2K bytes apart, which lands on one L2 channel
-//    and limits a compute unit to about a third of the rate it reaches on the tiles;
+//    k-group l/16).  Row-major weights would spread every such load over 16 rows 2K
+//    bytes apart, which lands on one L2 channel and limits a compute unit to about a
+//    third of the rate it reaches on the tiles;
 //  * activations are two bf16 planes (hi + lo, ~16 mantissa bits).  For M <= 8 both
 //    planes ride in ONE operand: MFMA columns 0..7 carry the hi rows, columns 8..15
-//    the lo rows, and the epilogue adds the two halves with one lane exchange; for
-//    larger M every weight fragment is multiplied twice;
+//    the lo rows, and the epilogue adds the two halves; for larger M every weight
+//    fragment is multiplied twice;
+//  * M <= 32 (gemm_ksplit_kernel): the waves of a block split K, fetch their
+//    activation fragments straight from L2 and meet in LDS - no barrier in the K loop;
+//    M > 32 (gemm_tile_kernel): 48-row blocks share a staged activation chunk in LDS;
 //  * results leave either directly (store; SwiGLU: silu(gate)*up split to bf16
 //    hi/lo) or as fp32 partial sums per K split, which the consuming kernel adds in
-//    a fixed order (rope_append for QKV, add_rmsnorm for the residual GEMMs), so
-//    results are bit-reproducible run to run.
+//    a fixed order (the fused attention prologue for QKV, add_rmsnorm for the residual
+//    GEMMs), so results are bit-reproducible run to run.
 //
 // Paper (arXiv 2505.08600): Section 1, Figure 1 (draft steps and the parallel
 // verify pass whose linear layers these are); Section 3.1 (LLaMA blocks).
@@ -31,65 +30,70 @@
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
-#define GS_OPELEMS 8192 // bf16 elements of one staged activation chunk (operand rows x chunk length)
-#define GS_PAD 8        // row padding in LDS (16 bytes): operand rows fall into distinct banks
+// Pins the program order of the memory operations around it, for the optimiser and the scheduler alike.
+#define SD_ORDER()                          \
+    do {                                    \
+        asm volatile("" ::: "memory");       \
+        __builtin_amdgcn_sched_barrier(0);  \
+    } while (0)
+#define GS_PAD 8 // row padding in LDS (16 bytes): operand rows fall into distinct banks
 
-// MODE: GEMM_STORE (C = acc, or partial sums when KS > 1) / GEMM_SWIGLU (tiles 2j, 2j+1 of a wave are
-// the gate and up tile of the same columns).  OPROWS: operand rows staged per chunk: 16 (packed hi|lo,
-// M <= 8), 32 (hi 0..15, lo 16..31, M <= 16) or 64 (M <= 32).
-// For M > 32 the rows are cut into blocks of OPROWS/2 = 48 rows (n_mblocks >= 1 of them; n_mblocks == 0
-// selects the plain mapping block = column tile, with an exact grid); the row blocks of
-// one column tile re-read the same weights, so they are mapped to the SAME XCD and to adjacent dispatch
-// slots: the re-reads then hit that XCD's L2 and HBM still sees every weight once.
-template <int MODE, int OPROWS, int KC, int NT, int WAVES>
-__global__ __launch_bounds__(WAVES * 64) void gemm_stream_kernel(const uint16_t *__restrict__ A, size_t a_plane,
-                                                                 WeightSeg w, int M, int N, int K, int k_per_split,
-                                                                 int n_mblocks, int n_ntiles,
-                                                                 float *__restrict__ C, size_t c_split_stride,
-                                                                 uint16_t *__restrict__ Cact, size_t c_plane)
+// Row-blocked GEMM for M > 32 (batched verify, prefill chunks of many sequences).
+// MODE: GEMM_STORE (C = acc, or partial sums when grid.y > 1) / GEMM_SWIGLU (tiles 2j, 2j+1 of a wave are
+// the gate and up tile of the same columns).  A block owns BM rows (hi plane in operand rows 0..BM-1, lo
+// plane in BM..2BM-1 of the staged chunk) and WAVES * NT 16-column weight tiles; every wave keeps its NT
+// weight fragments of a 128-element K step in registers (loaded straight from the tiled weights, two steps
+// in flight) and all waves share the activation chunk, staged once per block in LDS (double buffered).
+// The row blocks of one column tile re-read the same weights, so they are mapped to the SAME XCD and to
+// adjacent dispatch slots: block id = xcd + 8 * (row block + n_mblocks * (tile / 8)); the re-reads then
+// hit that XCD's L2 and HBM still sees every weight once.  The grid is padded to a multiple of 8 tiles.
+template <int MODE, int BM, int NT, int WAVES, int NB>
+__global__ __launch_bounds__(WAVES * 64) void gemm_tile_kernel(const uint16_t *A, ActView a_av,
+                                                               WeightSeg w, int M, int N, int K, int k_per_split,
+                                                               int n_mblocks, int n_ntiles, float *__restrict__ C,
+                                                               size_t c_split_stride, uint16_t *__restrict__ Cact,
+                                                               ActView c_av)
 {
-    constexpr bool PACKED = OPROWS == 16;
-    constexpr int MT = PACKED ? 1 : OPROWS / 32;    // 16-row tiles of A
-    constexpr int BM = PACKED ? 8 : OPROWS / 2;     // rows of A per block
-    constexpr int STEPS = KC / 128;                 // 128-element steps per chunk
+    constexpr int MT = BM / 16;      // 16-row tiles of A
+    constexpr int OPROWS = 2 * BM;   // staged operand rows (hi | lo)
+    constexpr int KC = 128;          // one K step per chunk
     constexpr int LDROW = KC + GS_PAD;
     constexpr int THREADS = WAVES * 64;
-    constexpr int VEC_PER_ROW = KC / 8;             // 16-byte vectors per operand row
-    constexpr int NVEC = OPROWS * VEC_PER_ROW;      // vectors per chunk
-    constexpr int LPT = (NVEC + THREADS - 1) / THREADS;
+    constexpr int VEC_PER_ROW = KC / 8; // 16-byte vectors per operand row
+    constexpr int NVEC = OPROWS * VEC_PER_ROW;
+    constexpr int LPT = NVEC / THREADS;
+    static_assert(NVEC % THREADS == 0, "staging must divide evenly");
     constexpr int COLS = (MODE == GEMM_SWIGLU ? NT / 2 : NT) * 16 * WAVES;
     __shared__ __attribute__((aligned(16))) uint16_t sA[2][OPROWS][LDROW];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int row = lane & 15, grp = lane >> 4;
-    // block -> (column tile, row block): id = xcd + 8 * (row block + n_mblocks * (tile / 8))
-    int ntile = blockIdx.x, mblk = 0;
-    if (n_mblocks >= 1) { // row-blocked launch: the grid is padded, so the tile index must be checked
-        const int r = blockIdx.x >> 3;
-        mblk = r % n_mblocks;
-        ntile = (r / n_mblocks) * 8 + (blockIdx.x & 7);
-        if (ntile >= n_ntiles) return; // grid is padded to a multiple of 8 tiles
-    }
+    const int r8 = blockIdx.x >> 3;
+    const int mblk = r8 % n_mblocks;
+    const int ntile = (r8 / n_mblocks) * 8 + (blockIdx.x & 7);
+    if (ntile >= n_ntiles) return; // padded grid
     const int n0 = ntile * COLS;
     const int m0 = mblk * BM;
     const int kb = blockIdx.y * k_per_split;
     const int ke = min(K, kb + k_per_split);
-    const int nchunks = (ke - kb + KC - 1) / KC;
-    // this lane's 16 bytes inside the first K step of each of the wave's 16-row weight tiles (tiled order:
-    // a tile's steps are 2048 elements apart, the four load instructions of a step 512 elements)
+    const int nchunks = (ke - kb) / KC; // k_per_split and K are multiples of 128
+    // this lane's 16 bytes inside the first K step of each of the wave's weight tiles
     const size_t tile_elems = (size_t)(K >> 7) * 2048;
     const uint16_t *Wp[NT];
     if (MODE == GEMM_SWIGLU) {
 #pragma unroll
         for (int c = 0; c < NT; c++)
-            Wp[c] = (const uint16_t *)w.p[c & 1] + (size_t)(n0 / 16 + wave * (NT / 2) + (c >> 1)) * tile_elems + lane * 8;
+            Wp[c] = (const uint16_t *)w.p[c & 1] + (size_t)(n0 / 16 + wave * (NT / 2) + (c >> 1)) * tile_elems +
+                    (size_t)(kb >> 7) * 2048 + lane * 8;
     } else {
         const int seg = n0 / w.n_per_seg;
         const int nl = n0 - seg * w.n_per_seg;
 #pragma unroll
         for (int c = 0; c < NT; c++)
-            Wp[c] = (const uint16_t *)w.p[seg] + (size_t)(nl / 16 + wave * NT + c) * tile_elems + lane * 8;
+            Wp[c] = (const uint16_t *)w.p[seg] + (size_t)(nl / 16 + wave * NT + c) * tile_elems +
+                    (size_t)(kb >> 7) * 2048 + lane * 8;
     }
-    // cooperative staging of the activation chunk: vector v -> operand row v / VEC_PER_ROW
+    // cooperative staging of the activation chunk: vector v -> operand row v / VEC_PER_ROW.  Rows past M
+    // are fetched from row M-1 (always a valid address) and zeroed in registers: no divergent loads.
     const uint16_t *a_src[LPT];
     int a_dst[LPT];
     bool a_ok[LPT];
@@ -97,118 +101,111 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_stream_kernel(const uint16_t 
     for (int j = 0; j < LPT; j++) {
         const int v = threadIdx.x + j * THREADS;
         const int orow = v / VEC_PER_ROW, ov = v % VEC_PER_ROW;
-        int m;
-        size_t plane;
-        if (PACKED) {
-            m = orow & 7;
-            plane = orow < 8 ? 0 : a_plane;
-        } else {
-            m = m0 + (orow % (OPROWS / 2));
-            plane = orow < OPROWS / 2 ? 0 : a_plane;
-        }
-        a_ok[j] = v < NVEC && m < M;
-        a_src[j] = A + plane + (size_t)(a_ok[j] ? m : 0) * K + ov * 8;
-        a_dst[j] = (v < NVEC ? orow : 0) * LDROW + ov * 8;
+        const int m = m0 + (orow % BM);
+        a_ok[j] = m < M;
+        a_src[j] = A + (orow < BM ? 0 : a_av.plane) + ((size_t)(kb >> 7) * a_av.rows + (a_ok[j] ? m : M - 1)) * 128 + ov * 8;
+        a_dst[j] = orow * LDROW + ov * 8;
     }
     const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+    const size_t step_stride = (size_t)a_av.rows * 128; // step-major activations
+    // Chunks past the end of the K range (the loop below runs a multiple of NB chunks) re-read the last
+    // chunk's addresses and contribute zeros: every iteration issues the same loads, which keeps the
+    // compiler's outstanding-load counts exact.
     bf16x8 a_reg[LPT];
+    bool a_zero = false;
     auto a_fetch = [&](int chunk) {
-        const int k0 = kb + chunk * KC;
+        a_zero = chunk >= nchunks;
+        const int cc = min(chunk, nchunks - 1);
 #pragma unroll
-        for (int j = 0; j < LPT; j++) {
-            const int ov8 = (a_dst[j] % LDROW);
-            a_reg[j] = (a_ok[j] && k0 + ov8 < ke) ? *(const bf16x8 *)(a_src[j] + k0) : zero;
-        }
+        for (int j = 0; j < LPT; j++) a_reg[j] = *(const bf16x8 *)(a_src[j] + (size_t)cc * step_stride);
     };
     auto a_commit = [&](int buf) {
 #pragma unroll
-        for (int j = 0; j < LPT; j++)
-            if (threadIdx.x + j * THREADS < NVEC) *(bf16x8 *)(&sA[buf][0][0] + a_dst[j]) = a_reg[j];
+        for (int j = 0; j < LPT; j++) *(bf16x8 *)(&sA[buf][0][0] + a_dst[j]) = (a_ok[j] && !a_zero) ? a_reg[j] : zero;
     };
     f32x4 acc[NT][MT];
 #pragma unroll
     for (int c = 0; c < NT; c++)
 #pragma unroll
         for (int t = 0; t < MT; t++) acc[c][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    // Weight loads of a chunk: all steps in flight at once.  They are issued for chunk ch+1 right after
-    // the MFMAs of chunk ch released the registers, i.e. before the barrier, so HBM never waits on LDS.
-    bf16x8 wv[NT][STEPS][4];
-    auto w_issue = [&](int chunk) {
-        const int k0 = kb + chunk * KC;
+    bf16x8 wv[NB][NT][4];
+    auto w_issue = [&](int chunk, int b) {
+        const int cc = min(chunk, nchunks - 1);
 #pragma unroll
         for (int c = 0; c < NT; c++)
 #pragma unroll
-            for (int st = 0; st < STEPS; st++) {
-                const int k = k0 + st * 128;
-                const bool live = k < ke;
-                const uint16_t *p = Wp[c] + (size_t)((live ? k : kb) >> 7) * 2048;
-#pragma unroll
-                for (int i = 0; i < 4; i++) wv[c][st][i] = live ? *(const bf16x8 *)(p + i * 512) : zero;
-            }
+            for (int i = 0; i < 4; i++) wv[b][c][i] = *(const bf16x8 *)(Wp[c] + (size_t)cc * 2048 + i * 512);
     };
-    w_issue(0);
-    a_fetch(0);
-    a_commit(0);
-    __syncthreads();
-    for (int ch = 0; ch < nchunks; ch++) {
-        const bool more = ch + 1 < nchunks;
-        if (more) a_fetch(ch + 1);
-        const uint16_t *sa = &sA[ch & 1][0][0];
+    auto compute = [&](int b, int lb) {
+        const uint16_t *sa = &sA[lb][0][0] + row * LDROW + grp * 8;
+        // activation fragments of MFMA i+1 are read from LDS while MFMA group i runs
+        bf16x8 fh[2][MT], fl[2][MT];
+        auto frags = [&](int i, int fb) {
 #pragma unroll
-        for (int st = 0; st < STEPS; st++) {
+            for (int t = 0; t < MT; t++) {
+                fh[fb][t] = *(const bf16x8 *)(sa + t * 16 * LDROW + i * 32);
+                fl[fb][t] = *(const bf16x8 *)(sa + (BM + t * 16) * LDROW + i * 32);
+            }
+        };
+        frags(0, 0);
 #pragma unroll
-            for (int i = 0; i < 4; i++) {
-                const int kk = st * 128 + i * 32 + grp * 8; // MFMA i contracts elements 32*i .. 32*i+31 of the step
+        for (int i = 0; i < 4; i++) { // MFMA i contracts elements 32*i .. 32*i+31 of the step
+            if (i < 3) frags(i + 1, (i + 1) & 1);
 #pragma unroll
-                for (int t = 0; t < MT; t++) {
-                    if (PACKED) {
-                        const bf16x8 av = *(const bf16x8 *)(sa + row * LDROW + kk);
+            for (int t = 0; t < MT; t++) {
 #pragma unroll
-                        for (int c = 0; c < NT; c++)
-                            acc[c][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv[c][st][i], av, acc[c][t], 0, 0, 0);
-                    } else {
-                        const bf16x8 ah = *(const bf16x8 *)(sa + (t * 16 + row) * LDROW + kk);
-                        const bf16x8 al = *(const bf16x8 *)(sa + (OPROWS / 2 + t * 16 + row) * LDROW + kk);
+                for (int c = 0; c < NT; c++)
+                    acc[c][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv[b][c][i], fh[i & 1][t], acc[c][t], 0, 0, 0);
 #pragma unroll
-                        for (int c = 0; c < NT; c++) {
-                            acc[c][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv[c][st][i], ah, acc[c][t], 0, 0, 0);
-                            acc[c][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv[c][st][i], al, acc[c][t], 0, 0, 0);
-                        }
-                    }
-                }
+                for (int c = 0; c < NT; c++)
+                    acc[c][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv[b][c][i], fl[i & 1][t], acc[c][t], 0, 0, 0);
             }
         }
-        if (more) {
-            w_issue(ch + 1);
-            a_commit((ch + 1) & 1);
+    };
+    // Pipeline: the weights of the next NB-1 chunks are in flight (registers) while chunk ch is
+    // multiplied; the activation rows of chunk ch+2 are fetched (L2) right after the barrier and written
+    // to LDS one iteration later.  Activation loads are always issued BEFORE the weight loads of the
+    // same iteration, so waiting for them never waits for the (much slower) weight stream.
+    a_fetch(0);
+    SD_ORDER();
+    w_issue(0, 0);
+    SD_ORDER();
+    a_commit(0);
+    a_fetch(1);
+    SD_ORDER();
+#pragma unroll
+    for (int b = 1; b < NB; b++) w_issue(b, b);
+    SD_ORDER();
+    __syncthreads();
+    for (int ch0 = 0; ch0 < nchunks; ch0 += NB) {
+#pragma unroll
+        for (int b = 0; b < NB; b++) {
+            const int ch = ch0 + b;
+            compute(b, ch & 1);
+            a_commit((ch + 1) & 1); // rows of chunk ch+1, fetched one iteration ago
+            __syncthreads();
+            a_fetch(ch + 2);
+            SD_ORDER(); // keep the activation loads ahead of the weight loads
+            w_issue(ch + NB, b);
+            SD_ORDER();
         }
-        __syncthreads();
     }
     // epilogue: lane (m' = row, grp) holds D[n = 4*grp + r][m'] of each of its tiles
 #pragma unroll
     for (int t = 0; t < MT; t++) {
-        f32x4 v[NT];
-#pragma unroll
-        for (int c = 0; c < NT; c++) {
-            v[c] = acc[c][t];
-            if (PACKED) {
-#pragma unroll
-                for (int r = 0; r < 4; r++) v[c][r] += __shfl_xor(v[c][r], 8, 64); // hi half + lo half
-            }
-        }
-        const int m = PACKED ? row : m0 + t * 16 + row;
-        if ((PACKED && row >= 8) || m >= M) continue;
+        const int m = m0 + t * 16 + row;
+        if (m >= M) continue;
         if (MODE == GEMM_SWIGLU) {
 #pragma unroll
             for (int j = 0; j < NT / 2; j++) {
-                const size_t o = (size_t)m * N + n0 + (wave * (NT / 2) + j) * 16 + 4 * grp;
+                const size_t o = act_index(c_av, m, n0 + (wave * (NT / 2) + j) * 16 + 4 * grp, N);
 #pragma unroll
                 for (int r = 0; r < 4; r++) {
-                    const float g0 = v[2 * j][r];
-                    const float y = g0 / (1.0f + expf(-g0)) * v[2 * j + 1][r];
+                    const float g0 = acc[2 * j][t][r];
+                    const float y = g0 / (1.0f + expf(-g0)) * acc[2 * j + 1][t][r];
                     const uint16_t hi = bf16_bits_rne(y);
                     Cact[o + r] = hi;
-                    Cact[c_plane + o + r] = bf16_bits_rne(y - __uint_as_float((uint32_t)hi << 16));
+                    Cact[c_av.plane + o + r] = bf16_bits_rne(y - __uint_as_float((uint32_t)hi << 16));
                 }
             }
         } else {
@@ -216,7 +213,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_stream_kernel(const uint16_t 
 #pragma unroll
             for (int c = 0; c < NT; c++) {
                 const size_t o = (size_t)m * N + n0 + (wave * NT + c) * 16 + 4 * grp;
-                *(f32x4 *)(Cs + o) = v[c];
+                *(f32x4 *)(Cs + o) = acc[c][t];
             }
         }
     }
@@ -238,10 +235,10 @@ static void split_geometry(int K, int ks, int *kps, int *ny)
 // activation fragments straight from global memory (L2) - no barrier inside the K loop - and keep the
 // loads of U steps in flight in registers; the four partial accumulators meet in LDS.
 template <int NMAT, bool PACKED, int MT, int U, int NTW>
-__global__ __launch_bounds__(256) void gemm_ksplit_kernel(const uint16_t *__restrict__ A, size_t a_plane, WeightSeg w,
+__global__ __launch_bounds__(256) void gemm_ksplit_kernel(const uint16_t *__restrict__ A, ActView a_av, WeightSeg w,
                                                           int M, int N, int K, int steps_per_split,
                                                           float *__restrict__ C, size_t c_split_stride,
-                                                          uint16_t *__restrict__ Cact, size_t c_plane)
+                                                          uint16_t *__restrict__ Cact, ActView c_av)
 {
     constexpr int WAVES = 4;
     constexpr int NW = NMAT * NTW; // weight tiles per wave and step
@@ -266,9 +263,11 @@ __global__ __launch_bounds__(256) void gemm_ksplit_kernel(const uint16_t *__rest
     for (int t = 0; t < MT; t++) {
         const int m = PACKED ? (row & 7) : t * 16 + row;
         a_live[t] = m < M;
-        Ap[t] = A + ((PACKED && row >= 8) ? a_plane : 0) + (size_t)(a_live[t] ? m : 0) * K + grp * 8;
-        Al[t] = Ap[t] + a_plane;
+        // step-major activations: row m of K step st starts at (st * rows + m) * 128
+        Ap[t] = A + ((PACKED && row >= 8) ? a_av.plane : 0) + (size_t)(a_live[t] ? m : 0) * 128 + grp * 8;
+        Al[t] = Ap[t] + a_av.plane;
     }
+    const size_t step_stride = (size_t)a_av.rows * 128;
     f32x4 acc[NW][MT];
 #pragma unroll
     for (int c = 0; c < NW; c++)
@@ -284,8 +283,8 @@ __global__ __launch_bounds__(256) void gemm_ksplit_kernel(const uint16_t *__rest
         for (int t = 0; t < MT; t++)
 #pragma unroll
             for (int i = 0; i < 4; i++) {
-                av[b][t][i] = a_live[t] ? *(const bf16x8 *)(Ap[t] + st * 128 + i * 32) : zero;
-                if (!PACKED) al[b][t][i] = a_live[t] ? *(const bf16x8 *)(Al[t] + st * 128 + i * 32) : zero;
+                av[b][t][i] = a_live[t] ? *(const bf16x8 *)(Ap[t] + step_stride * st + i * 32) : zero;
+                if (!PACKED) al[b][t][i] = a_live[t] ? *(const bf16x8 *)(Al[t] + step_stride * st + i * 32) : zero;
             }
 #pragma unroll
         for (int c = 0; c < NW; c++)
@@ -339,45 +338,34 @@ __global__ __launch_bounds__(256) void gemm_ksplit_kernel(const uint16_t *__rest
                 if (PACKED) v[c] += red[wv2][j * NMAT + c][t][slot + 8][r];
             }
         }
-        const size_t o = (size_t)m * N + n0 + j * 16 + nn;
         if (NMAT == 2) {
             const float y = v[0] / (1.0f + expf(-v[0])) * v[NMAT - 1];
             const uint16_t hi = bf16_bits_rne(y);
+            const size_t o = act_index(c_av, m, n0 + j * 16 + nn, N);
             Cact[o] = hi;
-            Cact[c_plane + o] = bf16_bits_rne(y - __uint_as_float((uint32_t)hi << 16));
+            Cact[c_av.plane + o] = bf16_bits_rne(y - __uint_as_float((uint32_t)hi << 16));
         } else {
-            C[(size_t)blockIdx.y * c_split_stride + o] = v[0];
+            C[(size_t)blockIdx.y * c_split_stride + (size_t)m * N + n0 + j * 16 + nn] = v[0];
         }
     }
 }
 
 template <int MODE, int NT, int WAVES>
-static void stream_launch(hipStream_t s, const uint16_t *a, size_t a_plane, WeightSeg w, int M, int N, int K, int ks,
-                          float *C, size_t c_split_stride, uint16_t *ca, size_t c_plane)
+static void tile_launch(hipStream_t s, const uint16_t *a, ActView a_av, WeightSeg w, int M, int N, int K, int ks,
+                        float *C, size_t c_split_stride, uint16_t *ca, ActView c_av)
 {
     constexpr int COLS = (MODE == GEMM_SWIGLU ? NT / 2 : NT) * 16 * WAVES;
+    constexpr int BM = 48;
     int kps, ny;
     split_geometry(K, ks, &kps, &ny);
     const int ntiles = N / COLS;
-    dim3 block(WAVES * 64);
-    if (M <= 8)
-        hipLaunchKernelGGL((gemm_stream_kernel<MODE, 16, 512, NT, WAVES>), dim3(ntiles, ny), block, 0, s, a, a_plane, w,
-                           M, N, K, kps, 0, ntiles, C, c_split_stride, ca, c_plane);
-    else if (M <= 16)
-        hipLaunchKernelGGL((gemm_stream_kernel<MODE, 32, 256, NT, WAVES>), dim3(ntiles, ny), block, 0, s, a, a_plane, w,
-                           M, N, K, kps, 0, ntiles, C, c_split_stride, ca, c_plane);
-    else if (M <= 32)
-        hipLaunchKernelGGL((gemm_stream_kernel<MODE, 64, 128, NT, WAVES>), dim3(ntiles, ny), block, 0, s, a, a_plane, w,
-                           M, N, K, kps, 0, ntiles, C, c_split_stride, ca, c_plane);
-    else {
-        const int nmb = (M + 47) / 48;
-        const int gx = ((ntiles + 7) / 8) * 8 * nmb;
-        hipLaunchKernelGGL((gemm_stream_kernel<MODE, 96, 128, NT, WAVES>), dim3(gx, ny), block, 0, s, a, a_plane, w, M,
-                           N, K, kps, nmb, ntiles, C, c_split_stride, ca, c_plane);
-    }
+    const int nmb = (M + BM - 1) / BM;
+    const int gx = ((ntiles + 7) / 8) * 8 * nmb;
+    hipLaunchKernelGGL((gemm_tile_kernel<MODE, BM, NT, WAVES, 3>), dim3(gx, ny), dim3(WAVES * 64), 0, s, a, a_av, w, M,
+                       N, K, kps, nmb, ntiles, C, c_split_stride, ca, c_av);
 }
 
-int g_skinny_tune[3][2] = {{4, 0}, {4, 0}, {4, 0}}; // [mode] -> {waves per block, K splits (0 = automatic)}
+int g_skinny_tune[3][2] = {{4, 0}, {4, 0}, {4, 0}}; // [mode] -> {unused, K splits (0 = automatic)}
 
 // Number of K splits the launcher will use for this shape (the caller sizes and reduces the partials).
 int gemm_skinny_splits(int mode, int M, int N, int K)
@@ -388,24 +376,17 @@ int gemm_skinny_splits(int mode, int M, int N, int K)
         split_geometry(K, g_skinny_tune[mode][1], &kps, &ny);
         return ny;
     }
-    int blocks, target;
-    if (M <= 16 && g_skinny_tune[mode][0] == 4) { // K-split kernel: 32 columns per block, each wave at least 2 steps
-        blocks = N / 32;
-        const int steps = K / 128;
-        int ks = steps >= 16 ? 2 : 1; // measured: two half-length blocks per tile stream faster than one
+    const int steps = K / 128;
+    int ks;
+    if (M <= 32) { // K-split kernel: 32 columns per block, each wave at least 2 steps
+        const int blocks = N / 32;
+        ks = steps >= 16 ? 2 : 1; // measured: two half-length blocks per tile stream faster than one
         while (blocks * ks < 256 && ks < 8 && steps / (ks * 2) >= 4) ks *= 2;
-        split_geometry(K, ks, &kps, &ny);
-        return ny;
+    } else { // row-blocked kernel: 128 columns x 48 rows per block; partial slabs cost M*N*4 bytes each
+        const int blocks = (N / 128) * ((M + 47) / 48);
+        ks = 1;
+        while (blocks * ks < 384 && ks < 8 && K / (ks * 2) >= 512) ks *= 2;
     }
-    if (M <= 32) {
-        blocks = N / (16 * g_skinny_tune[mode][0]);
-        target = 768; // about three blocks per CU
-    } else {
-        blocks = (N / 128) * ((M + 47) / 48); // 2 waves x 4 tiles = 128 columns per block, 48-row blocks
-        target = 384;                          // partial slabs cost M*N*4 bytes each here: split sparingly
-    }
-    int ks = 1;
-    while (blocks * ks < target && ks < 8 && K / (ks * 2) >= 512) ks *= 2;
     split_geometry(K, ks, &kps, &ny);
     return ny;
 }
@@ -413,58 +394,52 @@ int gemm_skinny_splits(int mode, int M, int N, int K)
 // mode GEMM_STORE: C receives `splits` partial slabs [split][M][N] (split stride c_split_stride floats);
 // mode GEMM_SWIGLU: Cact receives the bf16 hi/lo planes.  GEMM_RESID is expressed by the caller as a
 // store into partial slabs followed by the fused add + norm kernel.
-hipError_t launch_gemm_skinny_bf16(hipStream_t s, int mode, const void *A, size_t a_plane, WeightSeg w, int M, int N,
-                                   int K, float *C, size_t c_split_stride, int splits, void *Cact, size_t c_plane)
+hipError_t launch_gemm_skinny_bf16(hipStream_t s, int mode, const void *A, ActView a_av, WeightSeg w, int M, int N,
+                                   int K, float *C, size_t c_split_stride, int splits, void *Cact, ActView c_av)
 {
     if (M < 1 || K % 128 != 0 || K < 128 || (mode != GEMM_STORE && mode != GEMM_SWIGLU)) return hipErrorNotSupported;
     if (!w.tiled) return hipErrorNotSupported; // these kernels read the 16 x 128 tile order only
     for (int i = 0; i < 3; i++)
         if (w.p[i] && ((uintptr_t)w.p[i] & 15)) return hipErrorNotSupported;
-    if (((uintptr_t)A & 15) || (a_plane & 7) || (N & 3)) return hipErrorNotSupported;
+    if (((uintptr_t)A & 15) || (a_av.plane & 7) || (N & 3) || !a_av.sm || a_av.rows < M) return hipErrorNotSupported;
+    if (mode == GEMM_SWIGLU && (!c_av.sm || (c_av.plane & 7) || N % 128 != 0)) return hipErrorNotSupported;
     const uint16_t *a = (const uint16_t *)A;
     uint16_t *ca = (uint16_t *)Cact;
-    const int waves = g_skinny_tune[mode][0];
     if (M > 32) { // row-blocked: 2 waves x 4 tiles per block
         if (mode == GEMM_SWIGLU) {
             if (N % 64 != 0) return hipErrorNotSupported;
-            stream_launch<GEMM_SWIGLU, 4, 2>(s, a, a_plane, w, M, N, K, 1, C, 0, ca, c_plane);
+            tile_launch<GEMM_SWIGLU, 4, 2>(s, a, a_av, w, M, N, K, 1, C, 0, ca, c_av);
         } else {
             if (N % 128 != 0 || w.n_per_seg % 128 != 0) return hipErrorNotSupported;
-            stream_launch<GEMM_STORE, 4, 2>(s, a, a_plane, w, M, N, K, splits, C, c_split_stride, ca, c_plane);
+            tile_launch<GEMM_STORE, 4, 2>(s, a, a_av, w, M, N, K, splits, C, c_split_stride, ca, c_av);
         }
         return hipGetLastError();
     }
-    if (mode == GEMM_SWIGLU && g_skinny_tune[GEMM_SWIGLU][1] == 0) { // default: K split inside the block
-        if (N % 16 != 0) return hipErrorNotSupported;
-        dim3 grid(N / 16), block(256);
 #define SD_KSPLIT(NMAT, PACKED, MT, U, NTW, GRID, SPS)                                                              \
-    hipLaunchKernelGGL((gemm_ksplit_kernel<NMAT, PACKED, MT, U, NTW>), GRID, dim3(256), 0, s, a, a_plane, w, M, N, K, \
-                       SPS, C, c_split_stride, ca, c_plane)
+    hipLaunchKernelGGL((gemm_ksplit_kernel<NMAT, PACKED, MT, U, NTW>), GRID, dim3(256), 0, s, a, a_av, w, M, N, K, \
+                       SPS, C, c_split_stride, ca, c_av)
+    if (mode == GEMM_SWIGLU) { // K split inside the block only
+        if (N % 16 != 0) return hipErrorNotSupported;
+        dim3 grid(N / 16);
         if (M <= 8) SD_KSPLIT(2, true, 1, 2, 1, grid, K / 128);
         else if (M <= 16) SD_KSPLIT(2, false, 1, 2, 1, grid, K / 128);
         else SD_KSPLIT(2, false, 2, 1, 1, grid, K / 128);
         return hipGetLastError();
     }
-    if (mode == GEMM_STORE && waves == 4 && M <= 16 && N % 32 == 0 && w.n_per_seg % 32 == 0) {
-        int kps, ny;
-        split_geometry(K, splits, &kps, &ny);
+    int kps, ny;
+    split_geometry(K, splits, &kps, &ny);
+    if (N % 32 == 0 && w.n_per_seg % 32 == 0) {
         dim3 grid(N / 32, ny);
         if (M <= 8) SD_KSPLIT(1, true, 1, 2, 2, grid, kps / 128);
-        else SD_KSPLIT(1, false, 1, 2, 2, grid, kps / 128);
-        return hipGetLastError();
-    }
-    if (mode == GEMM_SWIGLU) {
-        if (waves == 4 && N % 64 == 0) stream_launch<GEMM_SWIGLU, 2, 4>(s, a, a_plane, w, M, N, K, 1, C, 0, ca, c_plane);
-        else if (waves == 8 && N % 128 == 0) stream_launch<GEMM_SWIGLU, 2, 8>(s, a, a_plane, w, M, N, K, 1, C, 0, ca, c_plane);
-        else if (N % 32 == 0) stream_launch<GEMM_SWIGLU, 2, 2>(s, a, a_plane, w, M, N, K, 1, C, 0, ca, c_plane);
-        else return hipErrorNotSupported;
-        return hipGetLastError();
-    }
-    if (waves == 8 && N % 128 == 0 && w.n_per_seg % 128 == 0)
-        stream_launch<GEMM_STORE, 1, 8>(s, a, a_plane, w, M, N, K, splits, C, c_split_stride, ca, c_plane);
-    else if (N % 64 == 0 && w.n_per_seg % 64 == 0)
-        stream_launch<GEMM_STORE, 1, 4>(s, a, a_plane, w, M, N, K, splits, C, c_split_stride, ca, c_plane);
-    else
+        else if (M <= 16) SD_KSPLIT(1, false, 1, 2, 2, grid, kps / 128);
+        else SD_KSPLIT(1, false, 2, 1, 2, grid, kps / 128);
+    } else if (N % 16 == 0 && w.n_per_seg % 16 == 0) {
+        dim3 grid(N / 16, ny);
+        if (M <= 8) SD_KSPLIT(1, true, 1, 2, 1, grid, kps / 128);
+        else if (M <= 16) SD_KSPLIT(1, false, 1, 2, 1, grid, kps / 128);
+        else SD_KSPLIT(1, false, 2, 1, 1, grid, kps / 128);
+    } else {
         return hipErrorNotSupported;
+    }
     return hipGetLastError();
 }

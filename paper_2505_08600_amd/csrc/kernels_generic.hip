@@ -203,7 +203,7 @@ hipError_t launch_embed(hipStream_t s, int dtype, const void *E, const int32_t *
 // out[j] = T( x[src] * rsqrt(mean(x[src]^2) + eps) * g ), src = row_map ? row_map[j] : j.
 template <typename T>
 __global__ void rmsnorm_kernel(const float *x, const float *g, const int32_t *row_map, int d, float eps, T *out,
-                               size_t plane)
+                               ActView av)
 {
     __shared__ float red[32];
     int j = blockIdx.x;
@@ -213,26 +213,26 @@ __global__ void rmsnorm_kernel(const float *x, const float *g, const int32_t *ro
     for (int i = threadIdx.x; i < d; i += blockDim.x) ss += xr[i] * xr[i];
     ss = block_sum(ss, red);
     float inv = 1.0f / sqrtf(ss / (float)d + eps);
-    for (int i = threadIdx.x; i < d; i += blockDim.x) store_act(out, (size_t)j * d + i, plane, xr[i] * inv * g[i]);
+    for (int i = threadIdx.x; i < d; i += blockDim.x) store_act(out, act_index(av, j, i, d), av.plane, xr[i] * inv * g[i]);
 }
 
 hipError_t launch_rmsnorm(hipStream_t s, int dtype, const float *x, const float *g, const int32_t *row_map,
-                          int n_rows, int d, float eps, void *out, size_t out_plane)
+                          int n_rows, int d, float eps, void *out, ActView out_av)
 {
     if (dtype == SD_BF16)
         hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3(n_rows), dim3(256), 0, s, x, g, row_map, d, eps,
-                           (bf16_t *)out, out_plane);
+                           (bf16_t *)out, out_av);
     else
         hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(n_rows), dim3(256), 0, s, x, g, row_map, d, eps,
-                           (float *)out, out_plane);
+                           (float *)out, out_av);
     return hipGetLastError();
 }
 
 // ---------------------------------------------------------------- generic GEMM  C = A . W^T
 // One wave per output column n, 16 rows of A per block row; lanes stride over K.
 template <typename T, int MODE>
-__global__ __launch_bounds__(256) void gemm_generic_kernel(const T *A, size_t a_plane, WeightSeg w, int M, int N,
-                                                           int K, float *C, T *Cact, size_t c_plane)
+__global__ __launch_bounds__(256) void gemm_generic_kernel(const T *A, ActView a_av, WeightSeg w, int M, int N,
+                                                           int K, float *C, T *Cact, ActView c_av)
 {
     int n = blockIdx.x * 4 + threadIdx.x / WAVE;
     int lane = threadIdx.x % WAVE;
@@ -259,7 +259,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const T *A, size_t a_
 #pragma unroll
         for (int m = 0; m < 16; m++) {
             if (m < mcount) {
-                float a = load_act(A, (size_t)(m0 + m) * K + k, a_plane);
+                float a = load_act(A, act_index(a_av, m0 + m, k, K), a_av.plane);
                 acc[m] += a * wv;
                 if (MODE == GEMM_SWIGLU) acc2[m] += a * wv2;
             }
@@ -277,7 +277,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const T *A, size_t a_
             else if (MODE == GEMM_RESID) C[o] += acc[m];
             else {
                 float g = acc[m];
-                store_act(Cact, o, c_plane, g / (1.0f + expf(-g)) * acc2[m]);
+                store_act(Cact, act_index(c_av, m0 + m, n, N), c_av.plane, g / (1.0f + expf(-g)) * acc2[m]);
             }
         }
     }
@@ -309,26 +309,26 @@ hipError_t launch_retile_bf16(hipStream_t s, const void *src, void *dst, int N, 
 }
 
 template <typename T>
-static void gemm_generic_dispatch(hipStream_t s, int mode, const void *A, size_t a_plane, WeightSeg w, int M, int N,
-                                  int K, float *C, void *Cact, size_t c_plane)
+static void gemm_generic_dispatch(hipStream_t s, int mode, const void *A, ActView a_av, WeightSeg w, int M, int N,
+                                  int K, float *C, void *Cact, ActView c_av)
 {
     dim3 grid((N + 3) / 4, (M + 15) / 16), block(256);
     if (mode == GEMM_STORE)
-        hipLaunchKernelGGL((gemm_generic_kernel<T, GEMM_STORE>), grid, block, 0, s, (const T *)A, a_plane, w, M, N, K,
-                           C, (T *)Cact, c_plane);
+        hipLaunchKernelGGL((gemm_generic_kernel<T, GEMM_STORE>), grid, block, 0, s, (const T *)A, a_av, w, M, N, K,
+                           C, (T *)Cact, c_av);
     else if (mode == GEMM_RESID)
-        hipLaunchKernelGGL((gemm_generic_kernel<T, GEMM_RESID>), grid, block, 0, s, (const T *)A, a_plane, w, M, N, K,
-                           C, (T *)Cact, c_plane);
+        hipLaunchKernelGGL((gemm_generic_kernel<T, GEMM_RESID>), grid, block, 0, s, (const T *)A, a_av, w, M, N, K,
+                           C, (T *)Cact, c_av);
     else
-        hipLaunchKernelGGL((gemm_generic_kernel<T, GEMM_SWIGLU>), grid, block, 0, s, (const T *)A, a_plane, w, M, N, K,
-                           C, (T *)Cact, c_plane);
+        hipLaunchKernelGGL((gemm_generic_kernel<T, GEMM_SWIGLU>), grid, block, 0, s, (const T *)A, a_av, w, M, N, K,
+                           C, (T *)Cact, c_av);
 }
 
-hipError_t launch_gemm_generic(hipStream_t s, int dtype, int mode, const void *A, size_t a_plane, WeightSeg w, int M,
-                               int N, int K, float *C, void *Cact, size_t c_plane)
+hipError_t launch_gemm_generic(hipStream_t s, int dtype, int mode, const void *A, ActView a_av, WeightSeg w, int M,
+                               int N, int K, float *C, void *Cact, ActView c_av)
 {
-    if (dtype == SD_BF16) gemm_generic_dispatch<bf16_t>(s, mode, A, a_plane, w, M, N, K, C, Cact, c_plane);
-    else gemm_generic_dispatch<float>(s, mode, A, a_plane, w, M, N, K, C, Cact, c_plane);
+    if (dtype == SD_BF16) gemm_generic_dispatch<bf16_t>(s, mode, A, a_av, w, M, N, K, C, Cact, c_av);
+    else gemm_generic_dispatch<float>(s, mode, A, a_av, w, M, N, K, C, Cact, c_av);
     return hipGetLastError();
 }
 
@@ -343,7 +343,7 @@ hipError_t launch_gemm_generic(hipStream_t s, int dtype, int mode, const void *A
 template <typename T>
 __global__ __launch_bounds__(1024) void add_rmsnorm_kernel(float *x, const float *part, int n_slabs, size_t slab_stride,
                                                            const float *g, const int32_t *row_map, int d, float eps,
-                                                           T *out, size_t plane)
+                                                           T *out, ActView av)
 {
     __shared__ float red[32];
     int j = blockIdx.x;
@@ -379,32 +379,32 @@ __global__ __launch_bounds__(1024) void add_rmsnorm_kernel(float *x, const float
     for (int v = threadIdx.x; v < nvec; v += blockDim.x, it++) {
         const float4 a = it < KEEP ? keep[it] : *(const float4 *)(xr + 4 * v);
         const float4 gg = *(const float4 *)(g + 4 * v);
-        const size_t o = (size_t)j * d + 4 * v;
-        store_act(out, o, plane, a.x * inv * gg.x);
-        store_act(out, o + 1, plane, a.y * inv * gg.y);
-        store_act(out, o + 2, plane, a.z * inv * gg.z);
-        store_act(out, o + 3, plane, a.w * inv * gg.w);
+        const size_t o = act_index(av, j, 4 * v, d); // 4 consecutive columns stay inside one K step
+        store_act(out, o, av.plane, a.x * inv * gg.x);
+        store_act(out, o + 1, av.plane, a.y * inv * gg.y);
+        store_act(out, o + 2, av.plane, a.z * inv * gg.z);
+        store_act(out, o + 3, av.plane, a.w * inv * gg.w);
     }
 }
 
 hipError_t launch_add_rmsnorm(hipStream_t s, int dtype, float *x, const float *part, int n_slabs, size_t slab_stride,
                               const float *g, const int32_t *row_map, int n_rows, int d, float eps, void *out,
-                              size_t out_plane)
+                              ActView out_av)
 {
     if (n_slabs > ADDNORM_MAX_SLABS || (d & 3)) return hipErrorInvalidValue;
     if (dtype == SD_BF16)
         hipLaunchKernelGGL(add_rmsnorm_kernel<bf16_t>, dim3(n_rows), dim3(1024), 0, s, x, part, n_slabs, slab_stride, g,
-                           row_map, d, eps, (bf16_t *)out, out_plane);
+                           row_map, d, eps, (bf16_t *)out, out_av);
     else
         hipLaunchKernelGGL(add_rmsnorm_kernel<float>, dim3(n_rows), dim3(1024), 0, s, x, part, n_slabs, slab_stride, g,
-                           row_map, d, eps, (float *)out, out_plane);
+                           row_map, d, eps, (float *)out, out_av);
     return hipGetLastError();
 }
 
 template <typename T>
 __global__ void rope_append_kernel(const float *qkv, int n_slabs, size_t slab_stride, PlanView pv, CtxView cv, int H,
                                    int hd, const float2 *rope,
-                                   int max_pos, T *qbuf, size_t q_plane, T *Kl, T *Vtl, int64_t total_cap)
+                                   int max_pos, T *qbuf, ActView q_av, T *Kl, T *Vtl, int64_t total_cap)
 {
     int r = blockIdx.x;
     int HD = H * hd, half = hd / 2;
@@ -419,8 +419,8 @@ __global__ void rope_append_kernel(const float *qkv, int n_slabs, size_t slab_st
     for (int i = threadIdx.x; i < H * half; i += blockDim.x) {
         int h = i / half, e = i % half;
         if (!valid) {
-            store_act(qbuf, (size_t)r * HD + h * hd + e, q_plane, 0.f);
-            store_act(qbuf, (size_t)r * HD + h * hd + e + half, q_plane, 0.f);
+            store_act(qbuf, act_index(q_av, r, h * hd + e, HD), q_av.plane, 0.f);
+            store_act(qbuf, act_index(q_av, r, h * hd + e + half, HD), q_av.plane, 0.f);
             continue;
         }
         float2 cs = rope[(size_t)pos * half + e];
@@ -447,8 +447,8 @@ __global__ void rope_append_kernel(const float *qkv, int n_slabs, size_t slab_st
                 v0 += ld[sl][4];
                 v1 += ld[sl][5];
             }
-        store_act(qbuf, (size_t)r * HD + h * hd + e, q_plane, q0 * cs.x - q1 * cs.y);
-        store_act(qbuf, (size_t)r * HD + h * hd + e + half, q_plane, q1 * cs.x + q0 * cs.y);
+        store_act(qbuf, act_index(q_av, r, h * hd + e, HD), q_av.plane, q0 * cs.x - q1 * cs.y);
+        store_act(qbuf, act_index(q_av, r, h * hd + e + half, HD), q_av.plane, q1 * cs.x + q0 * cs.y);
         T *kd = Kl + ((size_t)h * total_cap + off + pos) * hd;
         kd[e] = from_float<T>(k0 * cs.x - k1 * cs.y);
         kd[e + half] = from_float<T>(k1 * cs.x + k0 * cs.y);
@@ -460,15 +460,15 @@ __global__ void rope_append_kernel(const float *qkv, int n_slabs, size_t slab_st
 
 hipError_t launch_rope_append(hipStream_t s, int dtype, const float *qkv, int n_slabs, size_t slab_stride, PlanView pv,
                               CtxView cv, int M, int H, int hd, const float2 *rope, int max_pos, void *qbuf,
-                              size_t q_plane, void *Kl, void *Vtl, int64_t total_cap)
+                              ActView q_av, void *Kl, void *Vtl, int64_t total_cap)
 {
     if (n_slabs > ADDNORM_MAX_SLABS) return hipErrorInvalidValue;
     if (dtype == SD_BF16)
         hipLaunchKernelGGL(rope_append_kernel<bf16_t>, dim3(M), dim3(1024), 0, s, qkv, n_slabs, slab_stride, pv, cv, H,
-                           hd, rope, max_pos, (bf16_t *)qbuf, q_plane, (bf16_t *)Kl, (bf16_t *)Vtl, total_cap);
+                           hd, rope, max_pos, (bf16_t *)qbuf, q_av, (bf16_t *)Kl, (bf16_t *)Vtl, total_cap);
     else
         hipLaunchKernelGGL(rope_append_kernel<float>, dim3(M), dim3(1024), 0, s, qkv, n_slabs, slab_stride, pv, cv, H,
-                           hd, rope, max_pos, (float *)qbuf, q_plane, (float *)Kl, (float *)Vtl, total_cap);
+                           hd, rope, max_pos, (float *)qbuf, q_av, (float *)Kl, (float *)Vtl, total_cap);
     return hipGetLastError();
 }
 
@@ -476,9 +476,9 @@ hipError_t launch_rope_append(hipStream_t s, int dtype, const float *qkv, int n_
 // One block per (row slot i, head, selected sequence): query row i sees cache rows
 // [0, kv0 + i].  Scores live in dynamic LDS (len_upper floats).
 template <typename T>
-__global__ __launch_bounds__(256) void attn_generic_kernel(const T *qbuf, size_t q_plane, const T *Kl, const T *Vtl,
+__global__ __launch_bounds__(256) void attn_generic_kernel(const T *qbuf, ActView q_av, const T *Kl, const T *Vtl,
                                                            PlanView pv, CtxView cv, int R, int H, int hd,
-                                                           int64_t total_cap, int lds_len, T *obuf, size_t o_plane)
+                                                           int64_t total_cap, int lds_len, T *obuf, ActView o_av)
 {
     extern __shared__ float sc[]; // [lds_len] scores, then [256] partials, [hd] q, [32] red
     float *part = sc + lds_len;
@@ -488,7 +488,7 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const T *qbuf, size_t
     int r = j * R + i;
     int HD = H * hd;
     if (i >= pv.seq_nq[j]) {
-        for (int d = threadIdx.x; d < hd; d += blockDim.x) store_act(obuf, (size_t)r * HD + h * hd + d, o_plane, 0.f);
+        for (int d = threadIdx.x; d < hd; d += blockDim.x) store_act(obuf, act_index(o_av, r, h * hd + d, HD), o_av.plane, 0.f);
         return;
     }
     int Lk = pv.seq_kv0[j] + i + 1;
@@ -496,7 +496,7 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const T *qbuf, size_t
     int64_t off = cv.off[pv.seq_b[j]];
     const T *K = Kl + ((size_t)h * total_cap + off) * hd;
     const T *Vt = Vtl + (size_t)h * hd * total_cap + off;
-    for (int d = threadIdx.x; d < hd; d += blockDim.x) qs[d] = load_act(qbuf, (size_t)r * HD + h * hd + d, q_plane);
+    for (int d = threadIdx.x; d < hd; d += blockDim.x) qs[d] = load_act(qbuf, act_index(q_av, r, h * hd + d, HD), q_av.plane);
     __syncthreads();
     float scale = 1.0f / sqrtf((float)hd);
     float mx = -3.0e38f;
@@ -526,25 +526,25 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const T *qbuf, size_t
     __syncthreads();
     if (g == 0) {
         for (int gg = 1; gg < G; gg++) acc += part[gg * hd + d];
-        store_act(obuf, (size_t)r * HD + h * hd + d, o_plane, acc / z);
+        store_act(obuf, act_index(o_av, r, h * hd + d, HD), o_av.plane, acc / z);
     }
 }
 
-hipError_t launch_attn_generic(hipStream_t s, int dtype, const void *qbuf, size_t q_plane, const void *Kl,
+hipError_t launch_attn_generic(hipStream_t s, int dtype, const void *qbuf, ActView q_av, const void *Kl,
                                const void *Vtl, PlanView pv, CtxView cv, int R, int n_seq, int H, int hd,
-                               int64_t total_cap, int len_upper, void *obuf, size_t o_plane)
+                               int64_t total_cap, int len_upper, void *obuf, ActView o_av)
 {
     size_t lds = ((size_t)len_upper + 256 + hd + 32) * sizeof(float);
     if (lds > 64 * 1024) return hipErrorNotSupported;
     dim3 grid(R, H, n_seq), block(256);
     if (dtype == SD_BF16)
-        hipLaunchKernelGGL(attn_generic_kernel<bf16_t>, grid, block, lds, s, (const bf16_t *)qbuf, q_plane,
+        hipLaunchKernelGGL(attn_generic_kernel<bf16_t>, grid, block, lds, s, (const bf16_t *)qbuf, q_av,
                            (const bf16_t *)Kl, (const bf16_t *)Vtl, pv, cv, R, H, hd, total_cap, len_upper,
-                           (bf16_t *)obuf, o_plane);
+                           (bf16_t *)obuf, o_av);
     else
-        hipLaunchKernelGGL(attn_generic_kernel<float>, grid, block, lds, s, (const float *)qbuf, q_plane,
+        hipLaunchKernelGGL(attn_generic_kernel<float>, grid, block, lds, s, (const float *)qbuf, q_av,
                            (const float *)Kl, (const float *)Vtl, pv, cv, R, H, hd, total_cap, len_upper,
-                           (float *)obuf, o_plane);
+                           (float *)obuf, o_av);
     return hipGetLastError();
 }
 

@@ -487,16 +487,23 @@ extern "C" int sd_debug_read(sd_model *m, const char *name, float *out_host, int
         SD_HIP(hipMemcpy(out_host, src, rows * w * 4, hipMemcpyDeviceToHost));
         return SD_OK;
     }
-    std::vector<uint16_t> hi(rows * w), lo(rows * w);
-    SD_HIP(hipMemcpy(hi.data(), src, rows * w * 2, hipMemcpyDeviceToHost));
-    SD_HIP(hipMemcpy(lo.data(), (const uint16_t *)src + plane, rows * w * 2, hipMemcpyDeviceToHost));
-    for (size_t i = 0; i < rows * w; i++) {
-        uint32_t a = (uint32_t)hi[i] << 16, b = (uint32_t)lo[i] << 16;
-        float fa, fb;
-        memcpy(&fa, &a, 4);
-        memcpy(&fb, &b, 4);
-        out_host[i] = fa + fb;
-    }
+    // the buffer is laid out for the row count of the forward that wrote it
+    const int frows = !strcmp(name, "a") ? m->last_a_rows : m->last_rows;
+    if (rows > frows) return sd_fail(SD_EINVAL, "sd_debug_read: more rows than the last forward wrote");
+    const ActView av = {plane, frows, (int32_t)(w % 128 == 0)};
+    const size_t n = (size_t)frows * w;
+    std::vector<uint16_t> hi(n), lo(n);
+    SD_HIP(hipMemcpy(hi.data(), src, n * 2, hipMemcpyDeviceToHost));
+    SD_HIP(hipMemcpy(lo.data(), (const uint16_t *)src + plane, n * 2, hipMemcpyDeviceToHost));
+    for (int r = 0; r < rows; r++)
+        for (size_t k = 0; k < w; k++) {
+            const size_t i = act_index(av, r, (int)k, (int)w);
+            uint32_t a = (uint32_t)hi[i] << 16, b = (uint32_t)lo[i] << 16;
+            float fa, fb;
+            memcpy(&fa, &a, 4);
+            memcpy(&fb, &b, 4);
+            out_host[(size_t)r * w + k] = fa + fb;
+        }
     return SD_OK;
 }
 
@@ -511,22 +518,23 @@ extern "C" int sd_last_logits(sd_model *m, float *out, int32_t max_rows, int32_t
 }
 
 // ---------------------------------------------------------------- one decoder forward
-static hipError_t gemm_generic(sd_model *m, hipStream_t s, int mode, const void *A, size_t a_plane, WeightSeg w, int M,
-                               int N, int K, float *C, void *Cact, size_t c_plane)
+static hipError_t gemm_generic(sd_model *m, hipStream_t s, int mode, const void *A, ActView a_av, WeightSeg w, int M,
+                               int N, int K, float *C, void *Cact, ActView c_av)
 {
-    return launch_gemm_generic(s, m->cfg.dtype, mode, A, a_plane, w, M, N, K, C, Cact, c_plane);
+    return launch_gemm_generic(s, m->cfg.dtype, mode, A, a_av, w, M, N, K, C, Cact, c_av);
 }
 
 // Weight-streaming path for a GEMM whose fp32 result is consumed as split-K slabs.  Returns the number
 // of slabs written to `slabs` (slab stride M*N floats), 0 if the shape is outside the kernel's domain.
-static int stream_gemm(sd_model *m, hipStream_t s, const void *A, size_t a_plane, WeightSeg w, int M, int N, int K,
+static int stream_gemm(sd_model *m, hipStream_t s, const void *A, ActView a_av, WeightSeg w, int M, int N, int K,
                        float *slabs, size_t slabs_floats, int force_splits, hipError_t *err)
 {
     *err = hipSuccess;
     if (m->cfg.dtype != SD_BF16 || (g_force_generic & 1)) return 0;
     int ns = force_splits > 0 ? force_splits : gemm_skinny_splits(GEMM_STORE, M, N, K);
     if ((size_t)ns * M * N > slabs_floats || ns > 8) ns = 1;
-    hipError_t e = launch_gemm_skinny_bf16(s, GEMM_STORE, A, a_plane, w, M, N, K, slabs, (size_t)M * N, ns, nullptr, 0);
+    const ActView none = {0, 0, 0};
+    hipError_t e = launch_gemm_skinny_bf16(s, GEMM_STORE, A, a_av, w, M, N, K, slabs, (size_t)M * N, ns, nullptr, none);
     if (e == hipErrorNotSupported) return 0;
     *err = e;
     return ns;
@@ -554,6 +562,11 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
     const sd_model_config &cf = m->cfg;
     const int M = n_seq * R, d = cf.d_model, H = cf.n_heads, hd = cf.head_dim, F = cf.d_ffn, V = cf.vocab;
     if (M > cf.max_rows) return sd_fail(SD_ECAP, "forward: rows exceed the model's max_rows");
+    // activation buffers of bf16 models are step-major when their width allows it
+    const int sm_d = cf.dtype == SD_BF16 && d % 128 == 0, sm_f = cf.dtype == SD_BF16 && F % 128 == 0;
+    const ActView avd = {m->plane_d, M, sm_d}, avf = {m->plane_f, M, sm_f}, av0 = {0, 0, 0};
+    m->last_rows = M;
+    m->last_a_rows = M;
     CtxView cv = c->view();
     PlanView pv = m->plan;
     int kv_upper = c->len_upper + SD_MAX_GAMMA + 1;
@@ -569,20 +582,20 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
         { ProfScope ps(T_RMSNORM, s);
         if (pending)
             FWD(launch_add_rmsnorm(s, cf.dtype, m->x, m->gpart_r, pending, (size_t)M * d, m->norm_attn[l], nullptr, M, d,
-                                   cf.rms_eps, m->abuf, m->plane_d));
+                                   cf.rms_eps, m->abuf, avd));
         else
-            FWD(launch_rmsnorm(s, cf.dtype, m->x, m->norm_attn[l], nullptr, M, d, cf.rms_eps, m->abuf, m->plane_d));
+            FWD(launch_rmsnorm(s, cf.dtype, m->x, m->norm_attn[l], nullptr, M, d, cf.rms_eps, m->abuf, avd));
         }
         pending = 0;
         WeightSeg wqkv = {{m->wq[l], m->wk[l], m->wv[l]}, d, m->tiled_dd};
         int nq_slabs;
         const float *qkv_src;
         { ProfScope ps(T_QKV, s);
-        nq_slabs = stream_gemm(m, s, m->abuf, m->plane_d, wqkv, M, 3 * d, d, m->gpart_q, m->gpart_q_floats, 0, &ge);
+        nq_slabs = stream_gemm(m, s, m->abuf, avd, wqkv, M, 3 * d, d, m->gpart_q, m->gpart_q_floats, 0, &ge);
         FWD(ge);
         qkv_src = m->gpart_q;
         if (!nq_slabs) {
-            FWD(gemm_generic(m, s, GEMM_STORE, m->abuf, m->plane_d, wqkv, M, 3 * d, d, m->qkv, nullptr, 0));
+            FWD(gemm_generic(m, s, GEMM_STORE, m->abuf, avd, wqkv, M, 3 * d, d, m->qkv, nullptr, av0));
             nq_slabs = 1;
             qkv_src = m->qkv;
         } }
@@ -590,64 +603,66 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
         if (cf.dtype == SD_BF16 && !(g_force_generic & 2)) { // RoPE + append + attention in one launch
             ProfScope ps(T_ATTN, s);
             ea = launch_attn_fused_bf16(s, qkv_src, nq_slabs, (size_t)M * 3 * d, pv, cv, R, n_seq, H, hd, m->rope,
-                                        cf.max_pos, Kl, Vtl, c->total_cap, kv_upper, m->obuf, m->plane_d);
+                                        cf.max_pos, Kl, Vtl, c->total_cap, kv_upper, m->obuf, avd);
         }
         if (ea == hipErrorNotSupported) {
             { ProfScope ps(T_ROPE, s);
             FWD(launch_rope_append(s, cf.dtype, qkv_src, nq_slabs, (size_t)M * 3 * d, pv, cv, M, H, hd, m->rope,
-                                   cf.max_pos, m->qbuf, m->plane_d, Kl, Vtl, c->total_cap)); }
+                                   cf.max_pos, m->qbuf, avd, Kl, Vtl, c->total_cap)); }
             ProfScope ps(T_ATTN, s);
             if (cf.dtype == SD_BF16 && !(g_force_generic & 2))
-                ea = launch_attn_mfma_bf16(s, m->qbuf, m->plane_d, Kl, Vtl, pv, cv, R, n_seq, H, hd, c->total_cap,
-                                           kv_upper, m->part, m->part_floats, m->obuf, m->plane_d);
+                ea = launch_attn_mfma_bf16(s, m->qbuf, avd, Kl, Vtl, pv, cv, R, n_seq, H, hd, c->total_cap,
+                                           kv_upper, m->part, m->part_floats, m->obuf, avd);
             if (ea == hipErrorNotSupported)
-                ea = launch_attn_generic(s, cf.dtype, m->qbuf, m->plane_d, Kl, Vtl, pv, cv, R, n_seq, H, hd,
-                                         c->total_cap, kv_upper, m->obuf, m->plane_d);
+                ea = launch_attn_generic(s, cf.dtype, m->qbuf, avd, Kl, Vtl, pv, cv, R, n_seq, H, hd,
+                                         c->total_cap, kv_upper, m->obuf, avd);
         }
         if (ea == hipErrorNotSupported) return sd_fail(SD_ECAP, "forward: context too long for the generic attention kernel");
         FWD(ea);
         WeightSeg wo = {{m->wo[l], nullptr, nullptr}, d, m->tiled_dd};
         int no_slabs;
         { ProfScope ps(T_OPROJ, s);
-        no_slabs = stream_gemm(m, s, m->obuf, m->plane_d, wo, M, d, d, m->gpart_r, m->gpart_r_floats, 0, &ge);
+        no_slabs = stream_gemm(m, s, m->obuf, avd, wo, M, d, d, m->gpart_r, m->gpart_r_floats, 0, &ge);
         FWD(ge);
-        if (!no_slabs) FWD(gemm_generic(m, s, GEMM_RESID, m->obuf, m->plane_d, wo, M, d, d, m->x, nullptr, 0)); }
+        if (!no_slabs) FWD(gemm_generic(m, s, GEMM_RESID, m->obuf, avd, wo, M, d, d, m->x, nullptr, av0)); }
         { ProfScope ps(T_RMSNORM, s);
         if (no_slabs)
             FWD(launch_add_rmsnorm(s, cf.dtype, m->x, m->gpart_r, no_slabs, (size_t)M * d, m->norm_ffn[l], nullptr, M, d,
-                                   cf.rms_eps, m->abuf, m->plane_d));
+                                   cf.rms_eps, m->abuf, avd));
         else
-            FWD(launch_rmsnorm(s, cf.dtype, m->x, m->norm_ffn[l], nullptr, M, d, cf.rms_eps, m->abuf, m->plane_d));
+            FWD(launch_rmsnorm(s, cf.dtype, m->x, m->norm_ffn[l], nullptr, M, d, cf.rms_eps, m->abuf, avd));
         }
         WeightSeg wgu = {{m->wgate[l], m->wup[l], nullptr}, F, m->tiled_fd};
         { ProfScope ps(T_GATEUP, s);
         hipError_t eg = hipErrorNotSupported;
         if (cf.dtype == SD_BF16 && !(g_force_generic & 1))
-            eg = launch_gemm_skinny_bf16(s, GEMM_SWIGLU, m->abuf, m->plane_d, wgu, M, F, d, nullptr, 0, 1, m->act,
-                                         m->plane_f);
+            eg = launch_gemm_skinny_bf16(s, GEMM_SWIGLU, m->abuf, avd, wgu, M, F, d, nullptr, 0, 1, m->act,
+                                         avf);
         if (eg == hipErrorNotSupported)
-            eg = gemm_generic(m, s, GEMM_SWIGLU, m->abuf, m->plane_d, wgu, M, F, d, nullptr, m->act, m->plane_f);
+            eg = gemm_generic(m, s, GEMM_SWIGLU, m->abuf, avd, wgu, M, F, d, nullptr, m->act, avf);
         FWD(eg); }
         WeightSeg wd = {{m->wdown[l], nullptr, nullptr}, d, m->tiled_df};
         { ProfScope ps(T_DOWN, s);
-        pending = stream_gemm(m, s, m->act, m->plane_f, wd, M, d, F, m->gpart_r, m->gpart_r_floats, 0, &ge);
+        pending = stream_gemm(m, s, m->act, avf, wd, M, d, F, m->gpart_r, m->gpart_r_floats, 0, &ge);
         FWD(ge);
-        if (!pending) FWD(gemm_generic(m, s, GEMM_RESID, m->act, m->plane_f, wd, M, d, F, m->x, nullptr, 0)); }
+        if (!pending) FWD(gemm_generic(m, s, GEMM_RESID, m->act, avf, wd, M, d, F, m->x, nullptr, av0)); }
     }
     if (want_logits) {
         int n_lm = mode == PLAN_VERIFY ? M : n_seq;
+        const ActView avlm = {m->plane_d, n_lm, sm_d};
+        m->last_a_rows = n_lm;
         { ProfScope ps(T_RMSNORM, s);
         if (pending)
             FWD(launch_add_rmsnorm(s, cf.dtype, m->x, m->gpart_r, pending, (size_t)M * d, m->final_norm, pv.lm_row, n_lm,
-                                   d, cf.rms_eps, m->abuf, m->plane_d));
+                                   d, cf.rms_eps, m->abuf, avlm));
         else
-            FWD(launch_rmsnorm(s, cf.dtype, m->x, m->final_norm, pv.lm_row, n_lm, d, cf.rms_eps, m->abuf, m->plane_d));
+            FWD(launch_rmsnorm(s, cf.dtype, m->x, m->final_norm, pv.lm_row, n_lm, d, cf.rms_eps, m->abuf, avlm));
         }
         WeightSeg wl = {{m->lm_head, nullptr, nullptr}, V, m->tiled_lm};
         { ProfScope ps(T_LMHEAD, s);
-        int nl = stream_gemm(m, s, m->abuf, m->plane_d, wl, n_lm, V, d, m->logits, (size_t)cf.max_rows * V, 1, &ge);
+        int nl = stream_gemm(m, s, m->abuf, avlm, wl, n_lm, V, d, m->logits, (size_t)cf.max_rows * V, 1, &ge);
         FWD(ge);
-        if (!nl) FWD(gemm_generic(m, s, GEMM_STORE, m->abuf, m->plane_d, wl, n_lm, V, d, m->logits, nullptr, 0)); }
+        if (!nl) FWD(gemm_generic(m, s, GEMM_STORE, m->abuf, avlm, wl, n_lm, V, d, m->logits, nullptr, av0)); }
         m->last_lm_rows = n_lm;
     }
     return SD_OK;

@@ -57,6 +57,20 @@ __device__ __forceinline__ void store_act(bf16_t *b, size_t i, size_t plane, flo
     b[i + plane].v = bf16_bits_rne(v - __uint_as_float((uint32_t)hi << 16));
 }
 
+// Where element (row m, column k) of a GEMM-input activation buffer of width K lives.  Row-major, or
+// (bf16 buffers whose width is a multiple of 128) "step-major": the 128 columns of K step k/128 of all
+// rows of this forward are contiguous, [k/128][m][k%128].  A GEMM block then finds the rows it needs for
+// one K step in one contiguous piece instead of at a stride of 2K bytes (which lands on one L2 channel).
+struct ActView {
+    size_t plane;  // element offset from the hi plane to the lo plane (unused for fp32)
+    int32_t rows;  // rows of this forward (the row stride of a step in the step-major order)
+    int32_t sm;    // 1 = step-major
+};
+__host__ __device__ __forceinline__ size_t act_index(ActView v, int m, int k, int K)
+{
+    return v.sm ? ((size_t)(k >> 7) * v.rows + m) * 128 + (k & 127) : (size_t)m * K + k;
+}
+
 // ---------------------------------------------------------------- views passed to kernels
 // Device-side view of a context.  kvlen is [SD_MAX_SLOTS][B].
 struct CtxView {
@@ -140,6 +154,7 @@ struct sd_model {
     int32_t *plan_mem;
     PlanView plan;
     int last_lm_rows;
+    int last_rows, last_a_rows; // rows of the last forward (layout of the step-major buffers); of abuf
 };
 
 struct sd_ctx {
@@ -188,18 +203,18 @@ hipError_t launch_plan(hipStream_t s, int mode, int R, int n_seq, const int32_t 
                        int upto_off, const int32_t *cand, int gamma, int cand_idx, int vocab, PlanView pv);
 hipError_t launch_embed(hipStream_t s, int dtype, const void *E, const int32_t *row_tok, int M, int d, float *x);
 hipError_t launch_rmsnorm(hipStream_t s, int dtype, const float *x, const float *g, const int32_t *row_map,
-                          int n_rows, int d, float eps, void *out, size_t out_plane);
+                          int n_rows, int d, float eps, void *out, ActView out_av);
 // row-major bf16 [N][K] -> tiled order (N % 16 == 0, K % 128 == 0); src and dst must not overlap
 hipError_t launch_retile_bf16(hipStream_t s, const void *src, void *dst, int N, int K);
-hipError_t launch_gemm_generic(hipStream_t s, int dtype, int mode, const void *A, size_t a_plane, WeightSeg w, int M,
-                               int N, int K, float *C, void *Cact, size_t c_plane);
+hipError_t launch_gemm_generic(hipStream_t s, int dtype, int mode, const void *A, ActView a_av, WeightSeg w, int M,
+                               int N, int K, float *C, void *Cact, ActView c_av);
 hipError_t launch_rope_append(hipStream_t s, int dtype, const float *qkv, int n_slabs, size_t slab_stride, PlanView pv,
                               CtxView cv, int M, int H,
-                              int hd, const float2 *rope, int max_pos, void *qbuf, size_t q_plane, void *Kl, void *Vtl,
+                              int hd, const float2 *rope, int max_pos, void *qbuf, ActView q_av, void *Kl, void *Vtl,
                               int64_t total_cap);
-hipError_t launch_attn_generic(hipStream_t s, int dtype, const void *qbuf, size_t q_plane, const void *Kl,
+hipError_t launch_attn_generic(hipStream_t s, int dtype, const void *qbuf, ActView q_av, const void *Kl,
                                const void *Vtl, PlanView pv, CtxView cv, int R, int n_seq, int H, int hd,
-                               int64_t total_cap, int len_upper, void *obuf, size_t o_plane);
+                               int64_t total_cap, int len_upper, void *obuf, ActView o_av);
 hipError_t launch_draft_sample(hipStream_t s, const float *logits, int n_seq, int V, float T, const float *u,
                                int gamma, int idx, int32_t *cand, float *q);
 hipError_t launch_verify_tail(hipStream_t s, const float *logits, int n_seq, int gamma, int V, float T,
@@ -216,14 +231,14 @@ hipError_t launch_set_kv(hipStream_t s, int dtype, const void *k_rows, const voi
 // GEMM_STORE: C receives `splits` partial slabs (slab stride c_split_stride floats) that the consumer adds;
 // GEMM_SWIGLU: Cact receives the bf16 hi/lo planes.  gemm_skinny_splits tells how many slabs to expect.
 int gemm_skinny_splits(int mode, int M, int N, int K);
-hipError_t launch_gemm_skinny_bf16(hipStream_t s, int mode, const void *A, size_t a_plane, WeightSeg w, int M, int N,
-                                   int K, float *C, size_t c_split_stride, int splits, void *Cact, size_t c_plane);
+hipError_t launch_gemm_skinny_bf16(hipStream_t s, int mode, const void *A, ActView a_av, WeightSeg w, int M, int N,
+                                   int K, float *C, size_t c_split_stride, int splits, void *Cact, ActView c_av);
 hipError_t launch_add_rmsnorm(hipStream_t s, int dtype, float *x, const float *part, int n_slabs, size_t slab_stride,
                               const float *g, const int32_t *row_map, int n_rows, int d, float eps, void *out,
-                              size_t out_plane);
+                              ActView out_av);
 hipError_t launch_attn_fused_bf16(hipStream_t s, const float *qkv, int n_slabs, size_t slab_stride, PlanView pv,
                                   CtxView cv, int R, int n_seq, int H, int hd, const float2 *rope, int max_pos,
-                                  void *Kl, void *Vtl, int64_t total_cap, int len_upper, void *obuf, size_t o_plane);
-hipError_t launch_attn_mfma_bf16(hipStream_t s, const void *qbuf, size_t q_plane, const void *Kl, const void *Vtl,
+                                  void *Kl, void *Vtl, int64_t total_cap, int len_upper, void *obuf, ActView o_av);
+hipError_t launch_attn_mfma_bf16(hipStream_t s, const void *qbuf, ActView q_av, const void *Kl, const void *Vtl,
                                  PlanView pv, CtxView cv, int R, int n_seq, int H, int hd, int64_t total_cap,
-                                 int len_upper, float *part, size_t part_floats, void *obuf, size_t o_plane);
+                                 int len_upper, float *part, size_t part_floats, void *obuf, ActView o_av);
