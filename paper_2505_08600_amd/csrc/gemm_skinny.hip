@@ -47,7 +47,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 // The row blocks of one column tile re-read the same weights, so they are mapped to the SAME XCD and to
 // adjacent dispatch slots: block id = xcd + 8 * (row block + n_mblocks * (tile / 8)); the re-reads then
 // hit that XCD's L2 and HBM still sees every weight once.  The grid is padded to a multiple of 8 tiles.
-template <int MODE, int BM, int NT, int WAVES, int NB>
+template <int MODE, int BM, int KC, int NT, int WAVES, int NB>
 __global__ __launch_bounds__(WAVES * 64) void gemm_tile_kernel(const uint16_t *A, ActView a_av,
                                                                WeightSeg w, int M, int N, int K, int k_per_split,
                                                                int n_mblocks, int n_ntiles, float *__restrict__ C,
@@ -56,7 +56,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_tile_kernel(const uint16_t *A
 {
     constexpr int MT = BM / 16;      // 16-row tiles of A
     constexpr int OPROWS = 2 * BM;   // staged operand rows (hi | lo)
-    constexpr int KC = 128;          // one K step per chunk
+    constexpr int NI = KC / 32;      // MFMA k-groups per chunk (KC = 128: a whole K step, 64: half of one)
+    static_assert(KC == 64 || KC == 128, "chunk is a K step or half of one");
     constexpr int LDROW = KC + GS_PAD;
     constexpr int THREADS = WAVES * 64;
     constexpr int VEC_PER_ROW = KC / 8; // 16-byte vectors per operand row
@@ -93,48 +94,44 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_tile_kernel(const uint16_t *A
                     (size_t)(kb >> 7) * 2048 + lane * 8;
     }
     // cooperative staging of the activation chunk: vector v -> operand row v / VEC_PER_ROW.  Rows past M
-    // are fetched from row M-1 (always a valid address) and zeroed in registers: no divergent loads.
-    const uint16_t *a_src[LPT];
+    // are loaded like any other (the buffers are over-allocated by SD_ACT_PAD_ROWS rows, so the addresses
+    // are valid); whatever they hold only reaches accumulator rows that are never stored.
+    uint32_t a_off[LPT];
     int a_dst[LPT];
-    bool a_ok[LPT];
 #pragma unroll
     for (int j = 0; j < LPT; j++) {
         const int v = threadIdx.x + j * THREADS;
         const int orow = v / VEC_PER_ROW, ov = v % VEC_PER_ROW;
-        const int m = m0 + (orow % BM);
-        a_ok[j] = m < M;
-        a_src[j] = A + (orow < BM ? 0 : a_av.plane) + ((size_t)(kb >> 7) * a_av.rows + (a_ok[j] ? m : M - 1)) * 128 + ov * 8;
+        a_off[j] = (uint32_t)((orow < BM ? 0 : a_av.plane) + (size_t)(m0 + orow % BM) * 128 + ov * 8);
         a_dst[j] = orow * LDROW + ov * 8;
     }
-    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
     const size_t step_stride = (size_t)a_av.rows * 128; // step-major activations
-    // Chunks past the end of the K range (the loop below runs a multiple of NB chunks) re-read the last
-    // chunk's addresses and contribute zeros: every iteration issues the same loads, which keeps the
-    // compiler's outstanding-load counts exact.
+    // Loads for chunks past the end of the K range (issued by the last iterations so that every
+    // iteration issues the same loads, which keeps the compiler's outstanding-load counts exact)
+    // re-read the last chunk; their data is never used.
     bf16x8 a_reg[LPT];
-    bool a_zero = false;
     auto a_fetch = [&](int chunk) {
-        a_zero = chunk >= nchunks;
-        const int cc = min(chunk, nchunks - 1);
+        const int k0 = min(chunk, nchunks - 1) * KC; // offset inside this block's K range
+        const uint16_t *base = A + ((size_t)(kb >> 7) + (k0 >> 7)) * step_stride + (k0 & 127);
 #pragma unroll
-        for (int j = 0; j < LPT; j++) a_reg[j] = *(const bf16x8 *)(a_src[j] + (size_t)cc * step_stride);
+        for (int j = 0; j < LPT; j++) a_reg[j] = *(const bf16x8 *)(base + a_off[j]);
     };
     auto a_commit = [&](int buf) {
 #pragma unroll
-        for (int j = 0; j < LPT; j++) *(bf16x8 *)(&sA[buf][0][0] + a_dst[j]) = (a_ok[j] && !a_zero) ? a_reg[j] : zero;
+        for (int j = 0; j < LPT; j++) *(bf16x8 *)(&sA[buf][0][0] + a_dst[j]) = a_reg[j];
     };
     f32x4 acc[NT][MT];
 #pragma unroll
     for (int c = 0; c < NT; c++)
 #pragma unroll
         for (int t = 0; t < MT; t++) acc[c][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    bf16x8 wv[NB][NT][4];
+    bf16x8 wv[NB][NT][NI];
     auto w_issue = [&](int chunk, int b) {
         const int cc = min(chunk, nchunks - 1);
 #pragma unroll
         for (int c = 0; c < NT; c++)
 #pragma unroll
-            for (int i = 0; i < 4; i++) wv[b][c][i] = *(const bf16x8 *)(Wp[c] + (size_t)cc * 2048 + i * 512);
+            for (int i = 0; i < NI; i++) wv[b][c][i] = *(const bf16x8 *)(Wp[c] + ((size_t)cc * NI + i) * 512);
     };
     auto compute = [&](int b, int lb) {
         const uint16_t *sa = &sA[lb][0][0] + row * LDROW + grp * 8;
@@ -149,8 +146,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_tile_kernel(const uint16_t *A
         };
         frags(0, 0);
 #pragma unroll
-        for (int i = 0; i < 4; i++) { // MFMA i contracts elements 32*i .. 32*i+31 of the step
-            if (i < 3) frags(i + 1, (i + 1) & 1);
+        for (int i = 0; i < NI; i++) { // MFMA group i contracts elements 32*i .. 32*i+31 of the chunk
+            if (i < NI - 1) frags(i + 1, (i + 1) & 1);
 #pragma unroll
             for (int t = 0; t < MT; t++) {
 #pragma unroll
@@ -162,10 +159,15 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_tile_kernel(const uint16_t *A
             }
         }
     };
-    // Pipeline: the weights of the next NB-1 chunks are in flight (registers) while chunk ch is
-    // multiplied; the activation rows of chunk ch+2 are fetched (L2) right after the barrier and written
-    // to LDS one iteration later.  Activation loads are always issued BEFORE the weight loads of the
-    // same iteration, so waiting for them never waits for the (much slower) weight stream.
+    // Pipeline, iteration ch (weight buffer b = ch % NB):
+    //   1. the activation rows of chunk ch+1 (fetched into registers during iteration ch-1) go to the
+    //      other LDS buffer;
+    //   2. chunk ch is multiplied, and in between its MFMAs the loads of later chunks are issued: the
+    //      activation rows of chunk ch+2 first, then the weights of chunk ch+NB-1 into the buffer that
+    //      iteration ch-1 released (so NB-1 weight chunks are in flight or in use at any time);
+    //   3. barrier.
+    // Every iteration issues the same loads in the same order, activation rows before weights: waiting
+    // for the rows never waits for the (much slower) weight stream, and the wait counts stay exact.
     a_fetch(0);
     SD_ORDER();
     w_issue(0, 0);
@@ -174,22 +176,33 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_tile_kernel(const uint16_t *A
     a_fetch(1);
     SD_ORDER();
 #pragma unroll
-    for (int b = 1; b < NB; b++) w_issue(b, b);
+    for (int b = 1; b < NB - 1; b++) w_issue(b, b);
     SD_ORDER();
     __syncthreads();
     for (int ch0 = 0; ch0 < nchunks; ch0 += NB) {
 #pragma unroll
         for (int b = 0; b < NB; b++) {
             const int ch = ch0 + b;
-            compute(b, ch & 1);
-            a_commit((ch + 1) & 1); // rows of chunk ch+1, fetched one iteration ago
-            __syncthreads();
-            a_fetch(ch + 2);
-            SD_ORDER(); // keep the activation loads ahead of the weight loads
-            w_issue(ch + NB, b);
+            if (ch >= nchunks) goto k_done; // leaves the loop: no path merges back into the steady state
+            a_commit((ch + 1) & 1);
             SD_ORDER();
+            a_fetch(ch + 2);
+            w_issue(ch + NB - 1, (b + NB - 1) % NB);
+            compute(b, ch & 1);
+            // instruction order of this block: the LDS reads of the first fragment group, then one global
+            // load (activation rows first) and one LDS read after every third MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 2 * MT, 0);
+#pragma unroll
+            for (int k = 0; k < (NT * MT * 2 * NI) / 3; k++) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 3, 0); // MFMA
+                if (k < LPT + NT * NI) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);     // VMEM read
+                if (k < 2 * MT * (NI - 1)) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); // DS read
+            }
+            SD_ORDER();
+            __syncthreads();
         }
     }
+k_done:
     // epilogue: lane (m' = row, grp) holds D[n = 4*grp + r][m'] of each of its tiles
 #pragma unroll
     for (int t = 0; t < MT; t++) {
@@ -350,19 +363,36 @@ __global__ __launch_bounds__(256) void gemm_ksplit_kernel(const uint16_t *__rest
     }
 }
 
-template <int MODE, int NT, int WAVES>
-static void tile_launch(hipStream_t s, const uint16_t *a, ActView a_av, WeightSeg w, int M, int N, int K, int ks,
-                        float *C, size_t c_split_stride, uint16_t *ca, ActView c_av)
+// Row blocks of 96 rows x 256 columns (4 waves; chunks of half a K step) when there are more than 48 rows:
+// the bytes a block pulls through L2 per MFMA halve against the 48 x 128 shape, which is what bounds
+// these GEMMs; up to 48 rows one 48-row block (2 waves x 128 columns) wastes less.
+#define SD_TILE_BIG_COLS 256
+#define SD_TILE_SMALL_COLS 128
+template <int MODE>
+static hipError_t tile_launch(hipStream_t s, const uint16_t *a, ActView a_av, WeightSeg w, int M, int N, int K, int ks,
+                              float *C, size_t c_split_stride, uint16_t *ca, ActView c_av)
 {
-    constexpr int COLS = (MODE == GEMM_SWIGLU ? NT / 2 : NT) * 16 * WAVES;
-    constexpr int BM = 48;
     int kps, ny;
     split_geometry(K, ks, &kps, &ny);
-    const int ntiles = N / COLS;
-    const int nmb = (M + BM - 1) / BM;
-    const int gx = ((ntiles + 7) / 8) * 8 * nmb;
-    hipLaunchKernelGGL((gemm_tile_kernel<MODE, BM, NT, WAVES, 3>), dim3(gx, ny), dim3(WAVES * 64), 0, s, a, a_av, w, M,
-                       N, K, kps, nmb, ntiles, C, c_split_stride, ca, c_av);
+    constexpr int OUT_PER_COL = MODE == GEMM_SWIGLU ? 2 : 1; // weight rows per output column
+    const bool big = M > 64 && N % (SD_TILE_BIG_COLS / OUT_PER_COL) == 0 &&
+                     (MODE == GEMM_SWIGLU || w.n_per_seg % SD_TILE_BIG_COLS == 0);
+    if (big) {
+        const int ntiles = N / (SD_TILE_BIG_COLS / OUT_PER_COL);
+        const int nmb = (M + 95) / 96;
+        const int gx = ((ntiles + 7) / 8) * 8 * nmb;
+        hipLaunchKernelGGL((gemm_tile_kernel<MODE, 96, 64, 4, 4, 3>), dim3(gx, ny), dim3(256), 0, s, a, a_av, w, M, N, K,
+                           kps, nmb, ntiles, C, c_split_stride, ca, c_av);
+    } else {
+        if (N % (SD_TILE_SMALL_COLS / OUT_PER_COL) != 0 || (MODE != GEMM_SWIGLU && w.n_per_seg % SD_TILE_SMALL_COLS != 0))
+            return hipErrorNotSupported;
+        const int ntiles = N / (SD_TILE_SMALL_COLS / OUT_PER_COL);
+        const int nmb = (M + 47) / 48;
+        const int gx = ((ntiles + 7) / 8) * 8 * nmb;
+        hipLaunchKernelGGL((gemm_tile_kernel<MODE, 48, 128, 4, 2, 3>), dim3(gx, ny), dim3(128), 0, s, a, a_av, w, M, N, K,
+                           kps, nmb, ntiles, C, c_split_stride, ca, c_av);
+    }
+    return hipGetLastError();
 }
 
 int g_skinny_tune[3][2] = {{4, 0}, {4, 0}, {4, 0}}; // [mode] -> {unused, K splits (0 = automatic)}
@@ -382,10 +412,14 @@ int gemm_skinny_splits(int mode, int M, int N, int K)
         const int blocks = N / 32;
         ks = steps >= 16 ? 2 : 1; // measured: two half-length blocks per tile stream faster than one
         while (blocks * ks < 256 && ks < 8 && steps / (ks * 2) >= 4) ks *= 2;
-    } else { // row-blocked kernel: 128 columns x 48 rows per block; partial slabs cost M*N*4 bytes each
-        const int blocks = (N / 128) * ((M + 47) / 48);
+    } else { // row-blocked kernel: one block per compute unit and round; partial slabs cost M*N*4 bytes each
+        const bool big = M > 64 && N % SD_TILE_BIG_COLS == 0;
+        const int blocks = big ? (N / SD_TILE_BIG_COLS) * ((M + 95) / 96) : (N / SD_TILE_SMALL_COLS) * ((M + 47) / 48);
+        const int slots = big ? 256 : 512; // blocks resident at once
+        // measured at M = 192: a block costs about five K steps of fixed time, so one round of blocks with the
+        // K range cut as finely as that allows beats several rounds of shorter blocks
         ks = 1;
-        while (blocks * ks < 384 && ks < 8 && K / (ks * 2) >= 512) ks *= 2;
+        while (ks < 8 && blocks * (ks + 1) <= slots && (steps + ks) / (ks + 1) >= 4) ks++;
     }
     split_geometry(K, ks, &kps, &ny);
     return ny;
@@ -402,18 +436,13 @@ hipError_t launch_gemm_skinny_bf16(hipStream_t s, int mode, const void *A, ActVi
     for (int i = 0; i < 3; i++)
         if (w.p[i] && ((uintptr_t)w.p[i] & 15)) return hipErrorNotSupported;
     if (((uintptr_t)A & 15) || (a_av.plane & 7) || (N & 3) || !a_av.sm || a_av.rows < M) return hipErrorNotSupported;
+    if (2 * a_av.plane + (size_t)SD_ACT_PAD_ROWS * 128 >= ((size_t)1 << 32)) return hipErrorNotSupported; // 32-bit offsets
     if (mode == GEMM_SWIGLU && (!c_av.sm || (c_av.plane & 7) || N % 128 != 0)) return hipErrorNotSupported;
     const uint16_t *a = (const uint16_t *)A;
     uint16_t *ca = (uint16_t *)Cact;
-    if (M > 32) { // row-blocked: 2 waves x 4 tiles per block
-        if (mode == GEMM_SWIGLU) {
-            if (N % 64 != 0) return hipErrorNotSupported;
-            tile_launch<GEMM_SWIGLU, 4, 2>(s, a, a_av, w, M, N, K, 1, C, 0, ca, c_av);
-        } else {
-            if (N % 128 != 0 || w.n_per_seg % 128 != 0) return hipErrorNotSupported;
-            tile_launch<GEMM_STORE, 4, 2>(s, a, a_av, w, M, N, K, splits, C, c_split_stride, ca, c_av);
-        }
-        return hipGetLastError();
+    if (M > 32) { // row-blocked
+        if (mode == GEMM_SWIGLU) return tile_launch<GEMM_SWIGLU>(s, a, a_av, w, M, N, K, 1, C, 0, ca, c_av);
+        return tile_launch<GEMM_STORE>(s, a, a_av, w, M, N, K, splits, C, c_split_stride, ca, c_av);
     }
 #define SD_KSPLIT(NMAT, PACKED, MT, U, NTW, GRID, SPS)                                                              \
     hipLaunchKernelGGL((gemm_ksplit_kernel<NMAT, PACKED, MT, U, NTW>), GRID, dim3(256), 0, s, a, a_av, w, M, N, K, \

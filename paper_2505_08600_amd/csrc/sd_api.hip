@@ -207,11 +207,12 @@ extern "C" int sd_load_model(const sd_model_config *cfg, const sd_weights *w, sd
     m->plane_d = M * d;
     m->plane_f = M * (size_t)c.d_ffn;
     alloc((void **)&m->x, M * d * 4);
-    alloc(&m->abuf, planes * M * d * m->esz);
+    const size_t act_pad = (size_t)SD_ACT_PAD_ROWS * 128 * m->esz; // slack read (never used) by the row-blocked GEMM
+    alloc(&m->abuf, planes * M * d * m->esz + act_pad);
     alloc((void **)&m->qkv, M * 3 * d * 4);
-    alloc(&m->qbuf, planes * M * d * m->esz);
-    alloc(&m->obuf, planes * M * d * m->esz);
-    alloc(&m->act, planes * M * (size_t)c.d_ffn * m->esz);
+    alloc(&m->qbuf, planes * M * d * m->esz + act_pad);
+    alloc(&m->obuf, planes * M * d * m->esz + act_pad);
+    alloc(&m->act, planes * M * (size_t)c.d_ffn * m->esz + act_pad);
     alloc((void **)&m->logits, M * (size_t)c.vocab * 4);
     alloc((void **)&m->part, m->part_floats * 4);
     m->gpart_q_floats = 8 * M * 3 * d;
