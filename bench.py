@@ -40,6 +40,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--layers", type=int, default=0, help="debug: reduce target depth (invalidates the number)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-batch32", action="store_true", help="skip the secondary batch-32 verify measurement")
     ap.add_argument("--temperature", type=float, default=1.0)
     ap.add_argument("--prompt", type=int, default=512)
     ap.add_argument("--copy-calibration", action="store_true",
@@ -80,7 +81,8 @@ def main():
     wd = dg.make_weights(sd_, seed + 1, threads=16)
     log(f"[bench] weights generated on host in {time.time() - t0:.1f}s")
     t0 = time.time()
-    gt = api.Model(st, wt, max_rows=16, max_pos=cap + 64)
+    B32, LEN32 = 32, (128, 1024)  # secondary measurement: the verify pass of config 3's batch (32 prompts, gamma 5)
+    gt = api.Model(st, wt, max_rows=max(16, B32 * (gamma + 1)), max_pos=max(cap, LEN32[1] + 64) + 64)
     gd = api.Model(sd_, wd, max_rows=16, max_pos=cap + 64)
     torch.cuda.synchronize()
     log(f"[bench] uploaded in {time.time() - t0:.1f}s")
@@ -195,7 +197,7 @@ def main():
         "acceptance_rate_eq2": float(n_acc.sum() / (K * gamma)), "tau": tau, "alpha_hat": alpha_hat,
         "c_draft_over_target": c_ratio, "eq1_speedup_model": eq1,
         "verify_hbm_frac": verify_frac,
-        "roofline": {"bound": "hbm", "kernel": "gemm_swiglu_kernel<true,1> (gate/up + SiLU*mul) M=%d N=%d K=%d" % (M, st.d_ffn, st.d_model),
+        "roofline": {"bound": "hbm", "kernel": "gemm_ksplit_kernel<2,true,1,2,1> (gate/up + SiLU*mul) M=%d N=%d K=%d" % (M, st.d_ffn, st.d_model),
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      # FETCH_SIZE + WRITE_SIZE per launch of this kernel at this shape, scaled by a plain copy
                      # (profiles/config2_b1_7b_hbm_traffic.md); only meaningful for the default workload
@@ -204,9 +206,50 @@ def main():
         "kernel_ms_per_verify": {k: v[1] / 3.0 for k, v in vprof.items() if v[0]},
     }
 
+    if not args.no_batch32:
+        out["batch32_verify"] = batch32_verify(api, dg, torch, np, gt, st, seed, B32, LEN32, gamma)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(st, sd_, wt, wd, args.prompt, gamma, T, seed)
     print(json.dumps(out))
+
+
+def batch32_verify(api, dg, torch, np, gt, st, seed, B, len_range, gamma, T=0.7, reps=10):
+    """Verify pass alone at config 3's batch: B prompts with lengths uniform in len_range, gamma + 1 rows each
+    (M = B * (gamma + 1) rows through every GEMM).  Reports the matrix-core rate: every weight is multiplied
+    with the hi and the lo plane of each row, so 4 * M flops per streamed parameter are executed."""
+    V = st.vocab
+    lens = dg.make_prompt_lengths(seed + 7, B, len_range[0], len_range[1])
+    prompts = [[int(t) for t in dg.make_prompt(seed + 7, b, int(lens[b]), V)] for b in range(B)]
+    ctx = api.Context([int(l) + 4 * (gamma + 1) for l in lens])
+    ctx.attach(gt)
+    ctx.set_tokens(prompts)
+    api.sd_prefill(gt, ctx, None, B, int(lens.max()) - 1)
+    torch.cuda.synchronize()
+    g = torch.Generator(device="cuda").manual_seed(seed)
+    cand = torch.randint(0, V, (B, gamma), dtype=torch.int32, device="cuda", generator=g)
+    q = torch.softmax(torch.randn((B, gamma, V), device="cuda", generator=g), dim=-1).contiguous()
+    u = torch.rand((B, gamma + 1), device="cuda", generator=g)
+    na = torch.zeros(B, dtype=torch.int32, device="cuda")
+    nx = torch.zeros(B, dtype=torch.int32, device="cuda")
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ms = 0.0
+    for r in range(reps + 2):  # commit=False, then roll the cache lengths back: every repetition verifies the same state
+        ev0.record()
+        api.sd_verify(gt, ctx, None, B, gamma, T, cand, q, u, na, nx, False)
+        ev1.record()
+        torch.cuda.synchronize()
+        if r >= 2:
+            ms += ev0.elapsed_time(ev1) / reps
+        for b in range(B):
+            ctx.truncate(gt, b, int(lens[b]) - 1)
+    ctx.sync()
+    M = B * (gamma + 1)
+    flops = 4.0 * M * st.n_streamed_params()
+    return {"workload": "config 3 shape: %d prompts, lengths U[%d,%d], gamma %d, T=%g, verify pass only" %
+                        (B, len_range[0], len_range[1], gamma, T),
+            "rows": M, "ms_verify": ms, "candidates_per_s": B * gamma / (ms * 1e-3),
+            "mfma_tflops": flops / (ms * 1e-3) / 1e12, "mfma_peak_tflops": 2500.0,
+            "mfma_frac": flops / (ms * 1e-3) / 1e12 / 2500.0}
 
 
 def cpu_baseline(st, sd_, wt, wd, n_ctx, gamma, T, seed):

@@ -12,7 +12,8 @@
 // the same + 4).  The MFMA result then leaves every lane holding 8 consecutive
 // tokens of one query row - exactly the operand layout of the second product
 // O^T[d][q] = V^T[d][tokens] . P^T[tokens][q], whose V^T operand is a plain 16-byte
-// load from the transposed value cache.  No LDS, no shuffles between the two MFMAs.
+// load from the value cache, which is kept in transposed 32-token tiles ([head_dim][32],
+// contiguous per tile).  No LDS, no shuffles between the two MFMAs.
 // Queries arrive as two bf16 planes (hi + lo) and probabilities are split the same
 // way, so both products carry ~16 mantissa bits of the activation operand; the
 // softmax statistics stay in fp32.
@@ -32,6 +33,10 @@ typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8; // explicit LDS add
 #define AT_WAVES 4
 #define AT_TILE 32
 #define AT_NEG (-1.0e30f)
+
+// exp via the hardware 2^x: relative error of a few 1e-7 over the range softmax uses (arguments <= 0),
+// far below the 2^-16 of the hi/lo split the probabilities go through next; -1e30 gives exactly 0.
+__device__ __forceinline__ float fast_exp(float x) { return __builtin_amdgcn_exp2f(x * 1.44269504088896341f); }
 
 union Pack8 {
     bf16x8 v;
@@ -58,23 +63,25 @@ __device__ __forceinline__ void attn_tiles(const uint16_t *__restrict__ K, const
     bf16x8 ka0[NC], kb0[NC], vv0[ND], ka1[NC], kb1[NC], vv1[ND];
     auto load_tile = [&](int t, bf16x8 *ka, bf16x8 *kb, bf16x8 *vv) {
         const int t0 = t * AT_TILE;
-        const uint16_t *kpa = K + (size_t)(t0 + krow) * HD + grp * (HD / 4);
+        // MFMA c contracts head dimensions 32*c .. 32*c+31 (k-group grp takes 8 of them): each load
+        // instruction reads 64 contiguous bytes of every row
+        const uint16_t *kpa = K + (size_t)(t0 + krow) * HD + grp * 8;
         const uint16_t *kpb = kpa + 4 * HD;
 #pragma unroll
         for (int c = 0; c < NC; c++) {
-            ka[c] = *(const bf16x8 *)(kpa + c * 8);
-            kb[c] = *(const bf16x8 *)(kpb + c * 8);
+            ka[c] = *(const bf16x8 *)(kpa + c * 32);
+            kb[c] = *(const bf16x8 *)(kpb + c * 32);
         }
 #pragma unroll
-        for (int d = 0; d < ND; d++) vv[d] = *(const bf16x8 *)(Vt + (size_t)(d * 16 + qi) * total_cap + t0 + grp * 8);
+        for (int d = 0; d < ND; d++) vv[d] = *(const bf16x8 *)(Vt + (size_t)t * (AT_TILE * HD) + (d * 16 + qi) * AT_TILE + grp * 8);
     };
     auto compute_tile = [&](int t, const bf16x8 *ka, const bf16x8 *kb, const bf16x8 *vv) {
         const int t0 = t * AT_TILE;
         f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int c = 0; c < NC; c++) {
-            const bf16x8 qh = Q_LDS ? *(const volatile lds_bf16x8 *)(const lds_bf16x8 *)&qv[c] : qv[c];
-            const bf16x8 qo = Q_LDS ? *(const volatile lds_bf16x8 *)(const lds_bf16x8 *)&ql[c] : ql[c];
+            const bf16x8 qh = Q_LDS ? *(const volatile lds_bf16x8 *)(const lds_bf16x8 *)&qv[c * 4] : qv[c];
+            const bf16x8 qo = Q_LDS ? *(const volatile lds_bf16x8 *)(const lds_bf16x8 *)&ql[c * 4] : ql[c];
             sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[c], qh, sa, 0, 0, 0);
             sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[c], qh, sb, 0, 0, 0);
             sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[c], qo, sa, 0, 0, 0);
@@ -94,12 +101,12 @@ __device__ __forceinline__ void attn_tiles(const uint16_t *__restrict__ K, const
         mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
         const float m_new = fmaxf(m_run, mx);
-        const float corr = expf(m_run - m_new); // 1 when nothing changed, 0 from the initial state
+        const float corr = fast_exp(m_run - m_new); // 1 when nothing changed, 0 from the initial state
         Pack8 ph, pl;
         float psum = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; e++) {
-            float p = sc[e] > 0.5f * AT_NEG ? expf(sc[e] - m_new) : 0.f;
+            float p = sc[e] > 0.5f * AT_NEG ? fast_exp(sc[e] - m_new) : 0.f;
             psum += p;
             uint16_t hi = bf16_bits_rne(p);
             float rem = p - __uint_as_float((uint32_t)hi << 16);
@@ -154,18 +161,18 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restri
     const int64_t off = cv.off[pv.seq_b[j]];
     const int HDm = H * HD;
     const uint16_t *K = Kl + ((size_t)h * total_cap + off) * HD;
-    const uint16_t *Vt = Vtl + (size_t)h * HD * total_cap + off;
+    const uint16_t *Vt = Vtl + ((size_t)h * total_cap + off) * HD; // this sequence's first 32-token tile
     // this block's tile range
     const int n_tiles = nq > 0 ? (Lk + AT_TILE - 1) / AT_TILE : 0; // nothing to do for unused sequences
     const int per = (n_tiles + S - 1) / S;
     const int t_begin = s * per, t_end = min(n_tiles, t_begin + per);
-    // Q^T operand: lane (q, grp) holds Q[q][grp*(HD/4) + c*8 .. +8], matching the K loads below
+    // Q^T operand: lane (q, grp) holds Q[q][32*c + 8*grp .. +8], matching the K loads
     bf16x8 qv[NC], ql[NC];
     const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
     for (int c = 0; c < NC; c++) {
         // 8 consecutive columns never straddle a 128-column step
-        const bf16x8 *p = (const bf16x8 *)(qbuf + act_index(q_av, j * R + (qi < R ? qi : 0), h * HD + grp * (HD / 4) + c * 8, HDm));
+        const bf16x8 *p = (const bf16x8 *)(qbuf + act_index(q_av, j * R + (qi < R ? qi : 0), h * HD + c * 32 + grp * 8, HDm));
         qv[c] = qi < nq ? *p : zero;
         ql[c] = qi < nq ? *(const bf16x8 *)((const uint16_t *)p + q_av.plane) : zero;
     }
@@ -197,7 +204,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restri
         float O = 0.f, L = 0.f;
 #pragma unroll
         for (int w = 0; w < AT_WAVES; w++) {
-            float f = expf(sM[w][q] - M);
+            float f = fast_exp(sM[w][q] - M);
             O += sO[w][d][slot][r] * f;
             L += sL[w][q] * f;
         }
@@ -247,7 +254,7 @@ __global__ void attn_combine_kernel(const float *__restrict__ part, PlanView pv,
 #pragma unroll
         for (int s = 0; s < SD_ATTN_MAX_SPLITS; s++)
             if (s < S) {
-                float f = expf(ms[s] - M);
+                float f = fast_exp(ms[s] - M);
                 O += os[s] * f;
                 L += ls[s] * f;
             }
@@ -287,7 +294,7 @@ __global__ __launch_bounds__(AF_WAVES * 64) void attn_fused_kernel(const float *
     const int64_t off = cv.off[pv.seq_b[j]];
     const int HDm = H * HD;
     uint16_t *K = Kl + ((size_t)h * total_cap + off) * HD;
-    uint16_t *Vt = Vtl + (size_t)h * HD * total_cap + off;
+    uint16_t *Vt = Vtl + ((size_t)h * total_cap + off) * HD; // this sequence's first 32-token tile
     // ---- prologue: slabs -> q, k, v of this head; RoPE; append
     for (int idx = threadIdx.x; idx < 16 * HALF; idx += AF_WAVES * 64) {
         const int r = idx / HALF, e = idx % HALF;
@@ -328,8 +335,8 @@ __global__ __launch_bounds__(AF_WAVES * 64) void attn_fused_kernel(const float *
             uint16_t *kd = K + (size_t)pos * HD;
             kd[e] = bf16_bits_rne(ka);
             kd[e + HALF] = bf16_bits_rne(kb);
-            Vt[(size_t)e * total_cap + pos] = bf16_bits_rne(v0);
-            Vt[(size_t)(e + HALF) * total_cap + pos] = bf16_bits_rne(v1);
+            Vt[vt_offset(HD, pos, e)] = bf16_bits_rne(v0);
+            Vt[vt_offset(HD, pos, e + HALF)] = bf16_bits_rne(v1);
         }
         const uint16_t h0 = bf16_bits_rne(q0), h1 = bf16_bits_rne(q1);
         sQ[0][r][e] = h0;
@@ -338,9 +345,9 @@ __global__ __launch_bounds__(AF_WAVES * 64) void attn_fused_kernel(const float *
         sQ[1][r][e + HALF] = bf16_bits_rne(q1 - __uint_as_float((uint32_t)h1 << 16));
     }
     __syncthreads(); // q in LDS; the new cache rows are visible to this block's later loads
-    // the Q^T operand stays in LDS: lane (q, grp) reads Q[q][grp*(HD/4) + c*8 .. +8] per tile
-    const bf16x8 *qv = (const bf16x8 *)(&sQ[0][qi][grp * (HD / 4)]);
-    const bf16x8 *ql = (const bf16x8 *)(&sQ[1][qi][grp * (HD / 4)]);
+    // the Q^T operand stays in LDS: lane (q, grp) reads Q[q][32*c + 8*grp .. +8] per tile
+    const bf16x8 *qv = (const bf16x8 *)(&sQ[0][qi][grp * 8]);
+    const bf16x8 *ql = (const bf16x8 *)(&sQ[1][qi][grp * 8]);
     const int n_tiles = nq > 0 ? (Lk + AT_TILE - 1) / AT_TILE : 0;
     const int vis = kv0 + qi;
     float m_run = AT_NEG, l_run = 0.f;
@@ -365,7 +372,7 @@ __global__ __launch_bounds__(AF_WAVES * 64) void attn_fused_kernel(const float *
     if (wave < 4) {
         const float m2 = sM[wave][qi], l2 = sL[wave][qi];
         const float M = fmaxf(m_run, m2);
-        const float f1 = expf(m_run - M), f2 = expf(m2 - M);
+        const float f1 = fast_exp(m_run - M), f2 = fast_exp(m2 - M);
 #pragma unroll
         for (int d = 0; d < ND; d++)
 #pragma unroll
@@ -396,7 +403,7 @@ __global__ __launch_bounds__(AF_WAVES * 64) void attn_fused_kernel(const float *
         float O = 0.f, L = 0.f;
 #pragma unroll
         for (int w = 0; w < 4; w++) {
-            const float f = expf(sM[w][q] - M);
+            const float f = fast_exp(sM[w][q] - M);
             O += sO[w][d][slot][r] * f;
             L += sL[w][q] * f;
         }

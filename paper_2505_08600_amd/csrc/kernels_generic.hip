@@ -335,7 +335,7 @@ hipError_t launch_gemm_generic(hipStream_t s, int dtype, int mode, const void *A
 // ---------------------------------------------------------------- RoPE + KV append
 // qkv: fp32 [M][3*HD] (q | k | v).  Rotates q and k of every valid row at its
 // position (rotate-half pairing), writes q to qbuf and k, v into the cache in
-// place: K[head][off+pos][hd], Vt[head][hd][off+pos].
+// place: K[head][off+pos][hd], V in 32-token transposed tiles (vt_offset).
 // Residual update fused with the next RMSNorm: x[src] += sum of the split-K slabs of the
 // preceding GEMM (added in slab order), then out[j] = rmsnorm(x[src]) * g.  One block of 1024
 // threads per row; the loads of all slabs of an element are independent and go out together.
@@ -452,9 +452,9 @@ __global__ void rope_append_kernel(const float *qkv, int n_slabs, size_t slab_st
         T *kd = Kl + ((size_t)h * total_cap + off + pos) * hd;
         kd[e] = from_float<T>(k0 * cs.x - k1 * cs.y);
         kd[e + half] = from_float<T>(k1 * cs.x + k0 * cs.y);
-        T *vd = Vtl + (size_t)h * hd * total_cap + off + pos;
-        vd[(size_t)e * total_cap] = from_float<T>(v0);
-        vd[(size_t)(e + half) * total_cap] = from_float<T>(v1);
+        T *vh = Vtl + (size_t)h * hd * total_cap;
+        vh[vt_offset(hd, off + pos, e)] = from_float<T>(v0);
+        vh[vt_offset(hd, off + pos, e + half)] = from_float<T>(v1);
     }
 }
 
@@ -495,7 +495,7 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const T *qbuf, ActVie
     if (Lk > lds_len) Lk = lds_len; // host sizes lds_len from an upper bound; never exceeded
     int64_t off = cv.off[pv.seq_b[j]];
     const T *K = Kl + ((size_t)h * total_cap + off) * hd;
-    const T *Vt = Vtl + (size_t)h * hd * total_cap + off;
+    const T *Vh = Vtl + (size_t)h * hd * total_cap;
     for (int d = threadIdx.x; d < hd; d += blockDim.x) qs[d] = load_act(qbuf, act_index(q_av, r, h * hd + d, HD), q_av.plane);
     __syncthreads();
     float scale = 1.0f / sqrtf((float)hd);
@@ -520,8 +520,7 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const T *qbuf, ActVie
     int G = blockDim.x / hd; // hd is 64 or 128, blockDim 256
     int d = threadIdx.x % hd, g = threadIdx.x / hd;
     float acc = 0.f;
-    const T *vrow = Vt + (size_t)d * total_cap;
-    for (int t = g; t < Lk; t += G) acc += sc[t] * to_float(vrow[t]);
+    for (int t = g; t < Lk; t += G) acc += sc[t] * to_float(Vh[vt_offset(hd, off + t, d)]);
     part[threadIdx.x] = acc;
     __syncthreads();
     if (g == 0) {
@@ -930,7 +929,7 @@ __global__ void set_kv_kernel(const T *k_rows, const T *v_rows, int len, int H, 
         int h = (i / hd) % H;
         int t = i / ((size_t)hd * H);
         Kl[((size_t)h * total_cap + seq_off + t) * hd + d] = k_rows[i];
-        Vtl[((size_t)h * hd + d) * total_cap + seq_off + t] = v_rows[i];
+        Vtl[(size_t)h * hd * total_cap + vt_offset(hd, seq_off + t, d)] = v_rows[i];
     }
 }
 

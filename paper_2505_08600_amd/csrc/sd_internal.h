@@ -73,6 +73,14 @@ __host__ __device__ __forceinline__ size_t act_index(ActView v, int m, int k, in
     return v.sm ? ((size_t)(k >> 7) * v.rows + m) * 128 + (k & 127) : (size_t)m * K + k;
 }
 
+// Value cache of one head: 32-token tiles, each stored transposed as [head_dim][32], so that the V^T
+// tile a wave multiplies (head_dim x 32 tokens) is one contiguous piece.  t is the row inside the head's
+// cache (sequence offset + position; sequence offsets are multiples of 64).
+__host__ __device__ __forceinline__ size_t vt_offset(int hd, int64_t t, int d)
+{
+    return (size_t)(t >> 5) * (size_t)(32 * hd) + (size_t)d * 32 + (size_t)(t & 31);
+}
+
 // ---------------------------------------------------------------- views passed to kernels
 // Device-side view of a context.  kvlen is [SD_MAX_SLOTS][B].
 struct CtxView {
