@@ -682,6 +682,209 @@ __device__ float row_sumexp(const float *row, int V, float mx, float invT, float
     return block_sum(z, red);
 }
 
+// ---------------------------------------------------------------- register-resident vocabulary rows
+// For V <= 32768 a 1024-thread block holds a whole fp32 row in registers: thread t keeps the float4s
+// number it*1024 + t, it < ROW_NSEG - the same element-to-thread assignment, and therefore the same
+// summation order, as the strided loops of the general kernels above, so both give identical results.
+// One pass over memory per row and a handful of barriers instead of one block reduction per 4096
+// elements.
+#define ROW_NSEG 8
+#define ROW_THREADS 1024
+struct RowRegs {
+    float4 f[ROW_NSEG];
+};
+struct FastScratch {
+    float wsum[ROW_THREADS / WAVE][ROW_NSEG];
+    float seg[ROW_NSEG];
+    float red[32];
+    int redi[32];
+    float base, target;
+    int seg_idx, pick, last_pos;
+};
+
+__device__ __forceinline__ void row_load(const float *row, int V, float fill, RowRegs &r)
+{
+    const int nvec = (V + 3) / 4;
+#pragma unroll
+    for (int it = 0; it < ROW_NSEG; it++) {
+        const int v = it * ROW_THREADS + threadIdx.x;
+        r.f[it] = v < nvec ? load4_guard(row, v, V, fill) : make_float4(fill, fill, fill, fill);
+    }
+}
+
+// max, lowest-index argmax and (T > 0) z = sum of e(x) = exp((x - max) / T) of the row in r (filled with
+// -3e38 past V).  For T > 0 the row is replaced by e(x) (exactly 0 past V), so that the probabilities
+// e(x) / z need no second exponential.
+__device__ void row_stats_regs(RowRegs &r, float invT, FastScratch *fs, float &mx, int &am, float &z)
+{
+    float bv = -3.0e38f;
+    int bi = 0x7fffffff;
+#pragma unroll
+    for (int it = 0; it < ROW_NSEG; it++) {
+        const int v = it * ROW_THREADS + threadIdx.x;
+        const float4 f = r.f[it];
+        if (f.x > bv) { bv = f.x; bi = 4 * v; }
+        if (f.y > bv) { bv = f.y; bi = 4 * v + 1; }
+        if (f.z > bv) { bv = f.z; bi = 4 * v + 2; }
+        if (f.w > bv) { bv = f.w; bi = 4 * v + 3; }
+    }
+    block_argmax(bv, bi, fs->red, fs->redi);
+    mx = bv;
+    am = bi;
+    z = 1.f;
+    if (invT > 0.f) {
+        float zl = 0.f;
+#pragma unroll
+        for (int it = 0; it < ROW_NSEG; it++) {
+            float4 f = r.f[it];
+            f.x = expf((f.x - mx) * invT);
+            f.y = expf((f.y - mx) * invT);
+            f.z = expf((f.z - mx) * invT);
+            f.w = expf((f.w - mx) * invT);
+            zl += f.x;
+            zl += f.y;
+            zl += f.z;
+            zl += f.w;
+            r.f[it] = f;
+        }
+        z = block_sum(zl, fs->red);
+    }
+}
+
+// Inverse-CDF pick (same rule and arithmetic as block_pick_cdf) over weights held in registers.
+__device__ int pick_regs(const RowRegs &w, int V, float u, FastScratch *fs, float *total_out)
+{
+    const int lane = threadIdx.x % WAVE, wv = threadIdx.x / WAVE;
+    if (threadIdx.x == 0) {
+        fs->pick = 0x7fffffff;
+        fs->last_pos = 0;
+    }
+    int lastp = -1;
+    float loc[ROW_NSEG];
+#pragma unroll
+    for (int it = 0; it < ROW_NSEG; it++) {
+        const int v = it * ROW_THREADS + threadIdx.x;
+        const float4 f = w.f[it];
+        if (f.x > 0.f) lastp = 4 * v;
+        if (f.y > 0.f) lastp = 4 * v + 1;
+        if (f.z > 0.f) lastp = 4 * v + 2;
+        if (f.w > 0.f) lastp = 4 * v + 3;
+        loc[it] = wave_sum(((f.x + f.y) + f.z) + f.w);
+    }
+    __syncthreads();
+    if (lane == 0) {
+#pragma unroll
+        for (int it = 0; it < ROW_NSEG; it++) fs->wsum[wv][it] = loc[it];
+    }
+    if (lastp >= 0) atomicMax(&fs->last_pos, lastp);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int nseg = ((V + 3) / 4 + ROW_THREADS - 1) / ROW_THREADS;
+        float Z = 0.f;
+        for (int it = 0; it < nseg; it++) {
+            float t = 0.f;
+            for (int i = 0; i < ROW_THREADS / WAVE; i++) t += fs->wsum[i][it];
+            fs->seg[it] = t;
+            Z += t;
+        }
+        const float target = u * Z;
+        float cum = 0.f;
+        int found = -1;
+        for (int it = 0; it < nseg; it++) {
+            if (cum + fs->seg[it] > target) {
+                found = it;
+                break;
+            }
+            cum += fs->seg[it];
+        }
+        fs->seg_idx = found;
+        fs->base = cum;
+        fs->target = target;
+        if (total_out) *total_out = Z;
+    }
+    __syncthreads();
+    const int sit = fs->seg_idx;
+    if (sit >= 0) {
+        float4 f = w.f[0];
+#pragma unroll
+        for (int it = 1; it < ROW_NSEG; it++)
+            if (it == sit) f = w.f[it];
+        const int v = sit * ROW_THREADS + threadIdx.x;
+        const float l4 = ((f.x + f.y) + f.z) + f.w;
+        const float pre = block_excl_scan(l4, fs->red);
+        float cum = fs->base + pre;
+        const float target = fs->target;
+        if (cum <= target) {
+            int k = -1;
+            cum += f.x;
+            if (cum > target) k = 4 * v;
+            else {
+                cum += f.y;
+                if (cum > target) k = 4 * v + 1;
+                else {
+                    cum += f.z;
+                    if (cum > target) k = 4 * v + 2;
+                    else {
+                        cum += f.w;
+                        if (cum > target) k = 4 * v + 3;
+                    }
+                }
+            }
+            if (k >= 0 && k < V) atomicMin(&fs->pick, k);
+        }
+    }
+    __syncthreads();
+    int pick = fs->pick;
+    if (pick == 0x7fffffff) pick = fs->last_pos;
+    __syncthreads();
+    return pick;
+}
+
+// e(x) -> probabilities e(x) * (1 / z), in place
+__device__ __forceinline__ void row_scale(RowRegs &r, float invZ)
+{
+#pragma unroll
+    for (int it = 0; it < ROW_NSEG; it++) {
+        r.f[it].x *= invZ;
+        r.f[it].y *= invZ;
+        r.f[it].z *= invZ;
+        r.f[it].w *= invZ;
+    }
+}
+
+__global__ __launch_bounds__(ROW_THREADS) void draft_sample_fast_kernel(const float *logits, int V, float T,
+                                                                         const float *u, int gamma, int idx,
+                                                                         int32_t *cand, float *q)
+{
+    __shared__ FastScratch fs;
+    const int j = blockIdx.x;
+    RowRegs r;
+    row_load(logits + (size_t)j * V, V, -3.0e38f, r);
+    float mx, z;
+    int am;
+    row_stats_regs(r, T > 0.f ? 1.0f / T : 0.f, &fs, mx, am, z);
+    if (T == 0.f) {
+        if (threadIdx.x == 0) cand[j * gamma + idx] = am;
+        return;
+    }
+    row_scale(r, 1.0f / z);
+    float *qrow = q + ((size_t)j * gamma + idx) * V;
+    const int nvec = (V + 3) / 4;
+#pragma unroll
+    for (int it = 0; it < ROW_NSEG; it++) {
+        const int v = it * ROW_THREADS + threadIdx.x;
+        const float4 p = r.f[it];
+        if (4 * v + 3 < V) *(float4 *)(qrow + 4 * v) = p;
+        else if (v < nvec) {
+            if (4 * v < V) qrow[4 * v] = p.x;
+            if (4 * v + 1 < V) qrow[4 * v + 1] = p.y;
+            if (4 * v + 2 < V) qrow[4 * v + 2] = p.z;
+        }
+    }
+    const int pick = pick_regs(r, V, u[j * gamma + idx], &fs, nullptr);
+    if (threadIdx.x == 0) cand[j * gamma + idx] = pick;
+}
+
 // ---------------------------------------------------------------- draft: softmax + sample
 // One block per sequence.  T > 0: q = softmax(logits / T) is written in full and
 // the candidate drawn by inverse CDF; T == 0: candidate = argmax.
@@ -736,7 +939,11 @@ __global__ __launch_bounds__(1024) void draft_sample_kernel(const float *logits,
 hipError_t launch_draft_sample(hipStream_t s, const float *logits, int n_seq, int V, float T, const float *u,
                                int gamma, int idx, int32_t *cand, float *q)
 {
-    hipLaunchKernelGGL(draft_sample_kernel, dim3(n_seq), dim3(1024), 0, s, logits, V, T, u, gamma, idx, cand, q);
+    if (V <= ROW_NSEG * ROW_THREADS * 4)
+        hipLaunchKernelGGL(draft_sample_fast_kernel, dim3(n_seq), dim3(ROW_THREADS), 0, s, logits, V, T, u, gamma, idx,
+                           cand, q);
+    else
+        hipLaunchKernelGGL(draft_sample_kernel, dim3(n_seq), dim3(1024), 0, s, logits, V, T, u, gamma, idx, cand, q);
     return hipGetLastError();
 }
 
@@ -882,12 +1089,123 @@ __global__ __launch_bounds__(1024) void verify_tail_kernel(const float *logits, 
     }
 }
 
+// Same decisions as verify_tail_kernel in two launches.  verify_stats_kernel: one block per logits row
+// (n_seq * (gamma + 1) blocks, so the exponentials of the rows run on different compute units), each row
+// read once into registers; writes max, z and argmax per row.  verify_decide_kernel: one block per
+// sequence; the gamma acceptance tests are evaluated by gamma threads in parallel and scanned by
+// thread 0, then the deciding row is read once more for the resample.
+__global__ __launch_bounds__(ROW_THREADS) void verify_stats_kernel(const float *logits, int V, float T, float *stats)
+{
+    __shared__ FastScratch fs;
+    RowRegs r;
+    row_load(logits + (size_t)blockIdx.x * V, V, -3.0e38f, r);
+    float mx, z;
+    int am;
+    row_stats_regs(r, T > 0.f ? 1.0f / T : 0.f, &fs, mx, am, z);
+    if (threadIdx.x == 0) {
+        stats[3 * blockIdx.x] = mx;
+        stats[3 * blockIdx.x + 1] = z;
+        stats[3 * blockIdx.x + 2] = __int_as_float(am);
+    }
+}
+
+__global__ __launch_bounds__(ROW_THREADS) void verify_decide_kernel(const float *logits, const float *stats, int gamma,
+                                                                     int V, float T, const int32_t *cand,
+                                                                     const float *q, const float *u,
+                                                                     const int32_t *seq_ids, int32_t *n_acc_out,
+                                                                     int32_t *next_out, int commit, CtxView cv)
+{
+    __shared__ FastScratch fs;
+    __shared__ int s_ok[SD_MAX_GAMMA];
+    __shared__ int s_nacc;
+    __shared__ float s_zr;
+    const int j = blockIdx.x;
+    const float *rows = logits + (size_t)j * (gamma + 1) * V;
+    const float *st = stats + (size_t)j * (gamma + 1) * 3;
+    const int32_t *cj = cand + (size_t)j * gamma;
+    const float invT = T > 0.f ? 1.0f / T : 0.f;
+    if ((int)threadIdx.x < gamma) {
+        const int i = threadIdx.x;
+        const int c = cj[i];
+        bool ok;
+        if (T == 0.f) ok = c == __float_as_int(st[3 * i + 2]);
+        else if (c < 0 || c >= V) ok = false;
+        else {
+            const float p = expf((rows[(size_t)i * V + c] - st[3 * i]) * invT) / st[3 * i + 1];
+            float qc = q[((size_t)j * gamma + i) * V + c];
+            qc = fmaxf(qc, 1.17549435e-38f);
+            ok = u[j * (gamma + 1) + i] < p / qc;
+        }
+        s_ok[i] = ok ? 1 : 0;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int n = 0;
+        while (n < gamma && s_ok[n]) n++;
+        s_nacc = n;
+    }
+    __syncthreads();
+    const int n_acc = s_nacc;
+    int next;
+    if (T == 0.f) {
+        next = __float_as_int(st[3 * n_acc + 2]);
+    } else {
+        const float mx = st[3 * n_acc], invZ = 1.0f / st[3 * n_acc + 1];
+        const float uu = u[j * (gamma + 1) + gamma];
+        RowRegs r;
+        row_load(rows + (size_t)n_acc * V, V, -3.0e38f, r);
+#pragma unroll
+        for (int it = 0; it < ROW_NSEG; it++) {
+            float4 f = r.f[it];
+            f.x = expf((f.x - mx) * invT) * invZ;
+            f.y = expf((f.y - mx) * invT) * invZ;
+            f.z = expf((f.z - mx) * invT) * invZ;
+            f.w = expf((f.w - mx) * invT) * invZ;
+            r.f[it] = f;
+        }
+        bool use_p = n_acc >= gamma;
+        next = 0;
+        if (!use_p) {
+            RowRegs w;
+            row_load(q + ((size_t)j * gamma + n_acc) * V, V, 0.f, w);
+#pragma unroll
+            for (int it = 0; it < ROW_NSEG; it++) {
+                w.f[it].x = fmaxf(r.f[it].x - w.f[it].x, 0.f);
+                w.f[it].y = fmaxf(r.f[it].y - w.f[it].y, 0.f);
+                w.f[it].z = fmaxf(r.f[it].z - w.f[it].z, 0.f);
+                w.f[it].w = fmaxf(r.f[it].w - w.f[it].w, 0.f);
+            }
+            float zr = 0.f;
+            next = pick_regs(w, V, uu, &fs, &zr);
+            if (threadIdx.x == 0) s_zr = zr;
+            __syncthreads();
+            if (!(s_zr > 0.f)) use_p = true; // numerically empty residual: draw from p
+            __syncthreads();
+        }
+        if (use_p) next = pick_regs(r, V, uu, &fs, nullptr);
+    }
+    if (threadIdx.x == 0) {
+        n_acc_out[j] = n_acc;
+        next_out[j] = next;
+        if (commit) {
+            const int b = seq_ids ? seq_ids[j] : j;
+            if (b >= 0 && b < cv.B) commit_one(cv, b, gamma, cj, n_acc, next);
+            else atomicOr(cv.status, 4);
+        }
+    }
+}
+
 hipError_t launch_verify_tail(hipStream_t s, const float *logits, int n_seq, int gamma, int V, float T,
                               const int32_t *cand, const float *q, const float *u, const int32_t *seq_ids,
-                              int32_t *n_acc, int32_t *next_tok, int commit, CtxView cv)
+                              int32_t *n_acc, int32_t *next_tok, int commit, CtxView cv, float *stats)
 {
-    hipLaunchKernelGGL(verify_tail_kernel, dim3(n_seq), dim3(1024), 0, s, logits, gamma, V, T, cand, q, u, seq_ids,
-                       n_acc, next_tok, commit, cv);
+    if (V <= ROW_NSEG * ROW_THREADS * 4 && stats) {
+        hipLaunchKernelGGL(verify_stats_kernel, dim3(n_seq * (gamma + 1)), dim3(ROW_THREADS), 0, s, logits, V, T, stats);
+        hipLaunchKernelGGL(verify_decide_kernel, dim3(n_seq), dim3(ROW_THREADS), 0, s, logits, stats, gamma, V, T, cand, q,
+                           u, seq_ids, n_acc, next_tok, commit, cv);
+    } else
+        hipLaunchKernelGGL(verify_tail_kernel, dim3(n_seq), dim3(1024), 0, s, logits, gamma, V, T, cand, q, u, seq_ids,
+                           n_acc, next_tok, commit, cv);
     return hipGetLastError();
 }
 

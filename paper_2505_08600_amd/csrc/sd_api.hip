@@ -214,6 +214,7 @@ extern "C" int sd_load_model(const sd_model_config *cfg, const sd_weights *w, sd
     alloc(&m->obuf, planes * M * d * m->esz + act_pad);
     alloc(&m->act, planes * M * (size_t)c.d_ffn * m->esz + act_pad);
     alloc((void **)&m->logits, M * (size_t)c.vocab * 4);
+    alloc((void **)&m->vstats, M * 3 * sizeof(float));
     alloc((void **)&m->part, m->part_floats * 4);
     m->gpart_q_floats = 8 * M * 3 * d;
     m->gpart_r_floats = 8 * M * d;
@@ -261,6 +262,7 @@ extern "C" int sd_free_model(sd_model *m)
     (void)hipFree(m->obuf);
     (void)hipFree(m->act);
     (void)hipFree(m->logits);
+    (void)hipFree(m->vstats);
     (void)hipFree(m->part);
     (void)hipFree(m->gpart_q);
     (void)hipFree(m->gpart_r);
@@ -737,7 +739,7 @@ extern "C" int sd_verify(sd_model *target, sd_ctx *c, const int32_t *seq_ids, in
     if (rc) return rc;
     ProfScope ps(T_TAIL, s);
     hipError_t e = launch_verify_tail(s, target->logits, n_seq, gamma, target->cfg.vocab, temperature, cand, q,
-                                      uniforms, seq_ids, n_accepted, next_token, commit, c->view());
+                                      uniforms, seq_ids, n_accepted, next_token, commit, c->view(), target->vstats);
     if (e != hipSuccess) return sd_fail(SD_EHIP, std::string("sd_verify: tail: ") + hipGetErrorString(e));
     if (commit) c->len_upper += gamma + 1;
     return SD_OK;

@@ -156,6 +156,7 @@ struct sd_model {
     void *act;      // [planes][max_rows][d_ffn]
     size_t plane_d, plane_f; // element offsets between the planes
     float *logits;  // [max_rows][vocab]
+    float *vstats;  // [max_rows][3] per-row (max, sum of exponentials, argmax) of the verify tail
     float *part;    // split-KV partial results of the attention kernel
     float *gpart_q, *gpart_r; // split-K partial slabs of the weight-streaming GEMMs (QKV; O / down)
     size_t gpart_q_floats, gpart_r_floats;
@@ -229,7 +230,7 @@ hipError_t launch_draft_sample(hipStream_t s, const float *logits, int n_seq, in
                                int gamma, int idx, int32_t *cand, float *q);
 hipError_t launch_verify_tail(hipStream_t s, const float *logits, int n_seq, int gamma, int V, float T,
                               const int32_t *cand, const float *q, const float *u, const int32_t *seq_ids,
-                              int32_t *n_acc, int32_t *next_tok, int commit, CtxView cv);
+                              int32_t *n_acc, int32_t *next_tok, int commit, CtxView cv, float *stats);
 hipError_t launch_commit(hipStream_t s, CtxView cv, const int32_t *seq_ids, int n_seq, int gamma,
                          const int32_t *cand, const int32_t *n_acc, const int32_t *next_tok);
 hipError_t launch_route(hipStream_t s, const float *W, const float *b, int n_drafts, int emb, const float *e, int n,
