@@ -271,7 +271,7 @@ __global__ void attn_combine_kernel(const float *__restrict__ part, PlanView pv,
 // kernel plus its combine pass and the separate RoPE kernel are three latency-bound launches.
 // The block first adds the split-K slabs of the QKV GEMM for its head, rotates q and k, writes the new
 // K / V rows into the cache in place and q (hi, lo) into LDS; after a barrier its 8 waves stream the
-// cache (including the rows just written) tile by tile, and merge pairwise, then four ways, in LDS.
+// cache (including the rows just written) tile by tile, and merge their partial results in LDS.
 #define AF_WAVES 8
 template <int HD>
 __global__ __launch_bounds__(AF_WAVES * 64) void attn_fused_kernel(const float *__restrict__ qkv, int n_slabs,
@@ -283,8 +283,8 @@ __global__ __launch_bounds__(AF_WAVES * 64) void attn_fused_kernel(const float *
 {
     constexpr int ND = HD / 16;
     constexpr int HALF = HD / 2;
-    __shared__ float sO[4][ND][64][4];
-    __shared__ float sM[4][16], sL[4][16];
+    __shared__ float sO[AF_WAVES][ND][64][4];
+    __shared__ float sM[AF_WAVES][16], sL[AF_WAVES][16];
     __shared__ __attribute__((aligned(16))) uint16_t sQ[2][16][HD];
     const int h = blockIdx.x, j = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -357,40 +357,14 @@ __global__ __launch_bounds__(AF_WAVES * 64) void attn_fused_kernel(const float *
     attn_tiles<HD, true>(K, Vt, total_cap, qv, ql, vis, wave, n_tiles, AF_WAVES, m_run, l_run, o);
     l_run += __shfl_xor(l_run, 16, 64);
     l_run += __shfl_xor(l_run, 32, 64);
-    // ---- merge round 1: waves 4..7 hand their state to waves 0..3
-    if (wave >= 4) {
+    // ---- merge: every wave leaves its (max, sum, O) in LDS; after one barrier the block combines them
 #pragma unroll
-        for (int d = 0; d < ND; d++)
+    for (int d = 0; d < ND; d++)
 #pragma unroll
-            for (int r = 0; r < 4; r++) sO[wave - 4][d][lane][r] = o[d][r];
-        if (grp == 0) {
-            sM[wave - 4][qi] = m_run;
-            sL[wave - 4][qi] = l_run;
-        }
-    }
-    __syncthreads();
-    if (wave < 4) {
-        const float m2 = sM[wave][qi], l2 = sL[wave][qi];
-        const float M = fmaxf(m_run, m2);
-        const float f1 = fast_exp(m_run - M), f2 = fast_exp(m2 - M);
-#pragma unroll
-        for (int d = 0; d < ND; d++)
-#pragma unroll
-            for (int r = 0; r < 4; r++) o[d][r] = o[d][r] * f1 + sO[wave][d][lane][r] * f2;
-        l_run = l_run * f1 + l2 * f2;
-        m_run = M;
-    }
-    __syncthreads();
-    // ---- merge round 2: the four survivors meet in LDS
-    if (wave < 4) {
-#pragma unroll
-        for (int d = 0; d < ND; d++)
-#pragma unroll
-            for (int r = 0; r < 4; r++) sO[wave][d][lane][r] = o[d][r];
-        if (grp == 0) {
-            sM[wave][qi] = m_run;
-            sL[wave][qi] = l_run;
-        }
+        for (int r = 0; r < 4; r++) sO[wave][d][lane][r] = o[d][r];
+    if (grp == 0) {
+        sM[wave][qi] = m_run;
+        sL[wave][qi] = l_run;
     }
     __syncthreads();
     for (int e = threadIdx.x; e < ND * 256; e += AF_WAVES * 64) {
@@ -399,10 +373,10 @@ __global__ __launch_bounds__(AF_WAVES * 64) void attn_fused_kernel(const float *
         if (q >= R) continue;
         float M = AT_NEG;
 #pragma unroll
-        for (int w = 0; w < 4; w++) M = fmaxf(M, sM[w][q]);
+        for (int w = 0; w < AF_WAVES; w++) M = fmaxf(M, sM[w][q]);
         float O = 0.f, L = 0.f;
 #pragma unroll
-        for (int w = 0; w < 4; w++) {
+        for (int w = 0; w < AF_WAVES; w++) {
             const float f = fast_exp(sM[w][q] - M);
             O += sO[w][d][slot][r] * f;
             L += sL[w][q] * f;
