@@ -189,6 +189,15 @@ int sd_last_logits(sd_model *m, float *out, int32_t max_rows, int32_t *rows);
  * "x" (residual [rows][d_model]), "qkv" ([rows][3*d_model]), "q", "o", "a"
  * ([rows][d_model]) or "act" ([rows][d_ffn]).  Synchronises. */
 int sd_debug_read(sd_model *m, const char *name, float *out, int32_t rows);
+/* Host-only (no GPU call): element offset that the library's internal layouts assign.
+ * kind 0: tiled bf16 weight [N][K], a = row n, b = column k, c = K  (16-row x 128-column
+ *         tiles in MFMA operand order, see sd_load_model);
+ * kind 1: step-major activation plane, a = row m, b = column k, c = K, d = rows of the
+ *         forward;
+ * kind 2: value cache of one head, a = token row t, b = dimension, c = head_dim
+ *         (transposed 32-token tiles).
+ * Returns -1 for an unknown kind or arguments outside the layout's domain. */
+int64_t sd_debug_layout_index(int32_t kind, int64_t a, int64_t b, int64_t c, int64_t d);
 /* option "force_generic" = 1 routes every op through the simple reference kernels.
  * option "profile" = 1 starts bracketing every kernel launch of the forward with HIP
  * events on its stream (a measurement mode: it adds event overhead), 0 stops. */

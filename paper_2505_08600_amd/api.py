@@ -22,7 +22,7 @@ SD_FP32, SD_BF16 = 0, 1
 
 EXPORTS = ["sd_load_model", "sd_free_model", "sd_ctx_create", "sd_ctx_free", "sd_ctx_attach", "sd_ctx_set_tokens",
            "sd_prefill", "sd_draft", "sd_verify", "sd_commit", "sd_route", "sd_ctx_sync", "sd_ctx_get_tokens",
-           "sd_ctx_set_kv", "sd_ctx_truncate", "sd_debug_read", "sd_last_logits", "sd_set_option", "sd_profile_read", "sd_last_error"]
+           "sd_ctx_set_kv", "sd_ctx_truncate", "sd_debug_read", "sd_debug_layout_index", "sd_last_logits", "sd_set_option", "sd_profile_read", "sd_last_error"]
 
 
 class SdError(RuntimeError):
@@ -68,6 +68,8 @@ def lib():
         L.sd_ctx_set_kv.argtypes = [vp, vp, i32, i32, vp, vp, i32]
         L.sd_ctx_truncate.argtypes = [vp, vp, i32, i32]
         L.sd_debug_read.argtypes = [vp, C.c_char_p, vp, i32]
+        L.sd_debug_layout_index.argtypes = [i32, C.c_int64, C.c_int64, C.c_int64, C.c_int64]
+        L.sd_debug_layout_index.restype = C.c_int64
         L.sd_last_logits.argtypes = [vp, vp, i32, C.POINTER(i32)]
         L.sd_set_option.argtypes = [C.c_char_p, i32]
         L.sd_profile_read.argtypes = [i32, C.POINTER(C.c_char_p), C.POINTER(i32), C.POINTER(C.c_float)]
@@ -235,6 +237,11 @@ class Context:
         k, v = np.ascontiguousarray(k), np.ascontiguousarray(v)
         _check(lib().sd_ctx_set_kv(self.h, m.h, layer, seq, k.ctypes.data_as(C.c_void_p),
                                    v.ctypes.data_as(C.c_void_p), k.shape[0]))
+
+
+def layout_index(kind: int, a: int, b: int, c: int, d: int = 0) -> int:
+    """sd_debug_layout_index: 0 tiled weight (n, k, K), 1 step-major activation (m, k, K, rows), 2 value cache (t, dim, head_dim)."""
+    return int(lib().sd_debug_layout_index(kind, a, b, c, d))
 
 
 def sd_prefill(m: Model, ctx: Context, seq_ids: Optional[torch.Tensor], n_seq: int, max_new: int) -> None:

@@ -467,6 +467,19 @@ extern "C" int sd_ctx_truncate(sd_ctx *c, sd_model *m, int32_t seq, int32_t len)
     return SD_OK;
 }
 
+extern "C" int64_t sd_debug_layout_index(int32_t kind, int64_t a, int64_t b, int64_t c, int64_t d)
+{
+    if (a < 0 || b < 0 || c <= 0) return -1;
+    if (kind == 0) return (c % 128 == 0 && b < c && a < ((int64_t)1 << 30)) ? (int64_t)tiled_index((int)a, (int)b, (int)c) : -1;
+    if (kind == 1) {
+        if (c % 128 != 0 || b >= c || d <= 0 || a >= d) return -1;
+        const ActView av = {0, (int32_t)d, 1};
+        return (int64_t)act_index(av, (int)a, (int)b, (int)c);
+    }
+    if (kind == 2) return b < c ? (int64_t)vt_offset((int)c, a, (int)b) : -1;
+    return -1;
+}
+
 // Test hook: copy one workspace buffer of the last forward to the host as fp32.
 // name: "x" [rows][d], "qkv" [rows][3d], "q"/"o"/"a" [rows][d] (hi + lo summed), "act" [rows][d_ffn].
 extern "C" int sd_debug_read(sd_model *m, const char *name, float *out_host, int32_t rows)

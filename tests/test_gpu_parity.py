@@ -151,6 +151,41 @@ def test_small_bf16_mfma_matches_reference_kernels():
     pair.close()
 
 
+@pytest.mark.parametrize("B", [2, 3, 5, 8, 11, 16, 30])
+def test_small_bf16_every_gemm_row_class_matches_reference_kernels(B):
+    """Batched verify at gamma = 5 with B ragged sequences puts M = 6B rows through every GEMM: the packed
+    (M <= 8), 16- and 32-row few-row kernels, the 48-row blocks (M <= 64) and the 96-row blocks, with ragged
+    last blocks, plus batched prefill chunks.  The MFMA path must agree with the library's reference
+    kernels (which the oracle tests pin) far inside the bf16 tolerance: both feed hi + lo activations."""
+    _say(f"small bf16: batch {B} (M = {6 * B}) MFMA vs reference kernels")
+    st_ = dg.SHAPES["small_target_bf16"]
+    w = dg.make_weights(st_, 63, BF16_LM_SCALE)
+    gt = api.Model(st_, w, max_rows=max(32, 6 * B), max_pos=256)
+    lens = dg.make_prompt_lengths(63 + B, B, 5, 90)
+    prompts = [[int(t) for t in dg.make_prompt(63, b, int(lens[b]), st_.vocab)] for b in range(B)]
+    cand = H.dev(dg.make_prompt(64, B, 5 * B, st_.vocab).reshape(B, 5).astype(np.int32))
+    outs = []
+    for force in (0, 1):
+        api.set_option("force_generic", force)
+        try:
+            ctx = api.Context([int(l) + 16 for l in lens])
+            ctx.attach(gt)
+            H.gpu_prefill(ctx, [gt], prompts)
+            na = torch.zeros(B, dtype=torch.int32, device="cuda")
+            nx = torch.zeros(B, dtype=torch.int32, device="cuda")
+            api.sd_verify(gt, ctx, None, B, 5, 0.0, cand, None, None, na, nx, commit=False)
+            ctx.sync()
+            outs.append((gt.last_logits().cpu().numpy(), na.cpu().numpy().copy(), nx.cpu().numpy().copy()))
+            ctx.close()
+        finally:
+            api.set_option("force_generic", 0)
+    rel = np.abs(outs[0][0] - outs[1][0]).max() / np.abs(outs[1][0]).max()
+    _say(f"  rel diff {rel:.2e}")
+    assert outs[0][0].shape == (6 * B, st_.vocab) and np.isfinite(outs[0][0]).all()
+    assert rel < 2e-3
+    gt.close()
+
+
 def test_gamma_zero_is_autoregressive_decoding(tiny_pair):
     _say("gamma = 0")
     prompt = dg.make_prompt(11, 2, 12, TINY_T.vocab)
