@@ -62,7 +62,7 @@ __device__ __forceinline__ void store_act(bf16_t *b, size_t i, size_t plane, flo
 // rows of this forward are contiguous, [k/128][m][k%128].  A GEMM block then finds the rows it needs for
 // one K step in one contiguous piece instead of at a stride of 2K bytes (which lands on one L2 channel).
 // Row-blocked kernels read whole row blocks: activation buffers carry this many rows of slack at the end.
-#define SD_ACT_PAD_ROWS 64
+#define SD_ACT_PAD_ROWS 96
 struct ActView {
     size_t plane;  // element offset from the hi plane to the lo plane (unused for fp32)
     int32_t rows;  // rows of this forward (the row stride of a step in the step-major order)

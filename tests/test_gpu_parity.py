@@ -151,7 +151,7 @@ def test_small_bf16_mfma_matches_reference_kernels():
     pair.close()
 
 
-@pytest.mark.parametrize("B", [2, 3, 5, 8, 11, 16, 30])
+@pytest.mark.parametrize("B", [2, 3, 5, 8, 11, 16, 17, 30])
 def test_small_bf16_every_gemm_row_class_matches_reference_kernels(B):
     """Batched verify at gamma = 5 with B ragged sequences puts M = 6B rows through every GEMM: the packed
     (M <= 8), 16- and 32-row few-row kernels, the 48-row blocks (M <= 64) and the 96-row blocks, with ragged
