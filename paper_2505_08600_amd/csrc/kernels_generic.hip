@@ -333,6 +333,41 @@ hipError_t launch_gemm_generic(hipStream_t s, int dtype, int mode, const void *A
 }
 
 // ---------------------------------------------------------------- RoPE + KV append
+// Embedding gather fused with the first layer's RMSNorm: x[r] = E[token_r]; out[r] = rmsnorm(x[r]) * g.
+// Same element-to-thread assignment and reduction as rmsnorm_kernel, so the result is identical to the
+// two separate launches.
+template <typename T>
+__global__ __launch_bounds__(256) void embed_rmsnorm_kernel(const T *E, const int32_t *row_tok, int d, float *x,
+                                                            const float *g, float eps, T *out, ActView av)
+{
+    __shared__ float red[32];
+    const int r = blockIdx.x;
+    const T *src = E + (size_t)row_tok[r] * d;
+    float *xr = x + (size_t)r * d;
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < d; i += blockDim.x) {
+        const float v = to_float(src[i]);
+        xr[i] = v;
+        ss += v * v;
+    }
+    ss = block_sum(ss, red);
+    const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+    for (int i = threadIdx.x; i < d; i += blockDim.x)
+        store_act(out, act_index(av, r, i, d), av.plane, to_float(src[i]) * inv * g[i]);
+}
+
+hipError_t launch_embed_rmsnorm(hipStream_t s, int dtype, const void *E, const int32_t *row_tok, int M, int d, float *x,
+                                const float *g, float eps, void *out, ActView out_av)
+{
+    if (dtype == SD_BF16)
+        hipLaunchKernelGGL(embed_rmsnorm_kernel<bf16_t>, dim3(M), dim3(256), 0, s, (const bf16_t *)E, row_tok, d, x, g,
+                           eps, (bf16_t *)out, out_av);
+    else
+        hipLaunchKernelGGL(embed_rmsnorm_kernel<float>, dim3(M), dim3(256), 0, s, (const float *)E, row_tok, d, x, g,
+                           eps, (float *)out, out_av);
+    return hipGetLastError();
+}
+
 // qkv: fp32 [M][3*HD] (q | k | v).  Rotates q and k of every valid row at its
 // position (rotate-half pairing), writes q to qbuf and k, v into the cache in
 // place: K[head][off+pos][hd], V in 32-token transposed tiles (vt_offset).

@@ -590,12 +590,12 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
     hipError_t ge;
     { ProfScope ps(T_PLAN, s);
     FWD(launch_plan(s, mode, R, n_seq, seq_ids, cv, slot, upto_off, cand, gamma, cand_idx, V, pv)); }
-    { ProfScope ps(T_EMBED, s);
-    FWD(launch_embed(s, cf.dtype, m->embed, pv.row_tok, M, d, m->x)); }
+    { ProfScope ps(T_EMBED, s); // embedding gather + the first layer's norm in one launch
+    FWD(launch_embed_rmsnorm(s, cf.dtype, m->embed, pv.row_tok, M, d, m->x, m->norm_attn[0], cf.rms_eps, m->abuf, avd)); }
     int pending = 0; // split-K slabs of the previous down projection not yet added to x
     for (int l = 0; l < cf.n_layers; l++) {
         void *Kl = (char *)c->kcache[slot] + l * lstride, *Vtl = (char *)c->vcache[slot] + l * lstride;
-        { ProfScope ps(T_RMSNORM, s);
+        if (l > 0) { ProfScope ps(T_RMSNORM, s);
         if (pending)
             FWD(launch_add_rmsnorm(s, cf.dtype, m->x, m->gpart_r, pending, (size_t)M * d, m->norm_attn[l], nullptr, M, d,
                                    cf.rms_eps, m->abuf, avd));

@@ -213,6 +213,8 @@ extern int g_skinny_tune[3][2]; // per GEMM mode {column tiles per wave, waves p
 hipError_t launch_plan(hipStream_t s, int mode, int R, int n_seq, const int32_t *seq_ids, CtxView cv, int slot,
                        int upto_off, const int32_t *cand, int gamma, int cand_idx, int vocab, PlanView pv);
 hipError_t launch_embed(hipStream_t s, int dtype, const void *E, const int32_t *row_tok, int M, int d, float *x);
+hipError_t launch_embed_rmsnorm(hipStream_t s, int dtype, const void *E, const int32_t *row_tok, int M, int d, float *x,
+                                const float *g, float eps, void *out, ActView out_av);
 hipError_t launch_rmsnorm(hipStream_t s, int dtype, const float *x, const float *g, const int32_t *row_map,
                           int n_rows, int d, float eps, void *out, ActView out_av);
 // row-major bf16 [N][K] -> tiled order (N % 16 == 0, K % 128 == 0); src and dst must not overlap
