@@ -198,9 +198,13 @@ int sd_debug_read(sd_model *m, const char *name, float *out, int32_t rows);
  *         (transposed 32-token tiles).
  * Returns -1 for an unknown kind or arguments outside the layout's domain. */
 int64_t sd_debug_layout_index(int32_t kind, int64_t a, int64_t b, int64_t c, int64_t d);
-/* option "force_generic" = 1 routes every op through the simple reference kernels.
+/* option "force_generic" = 1 routes every op through the simple reference kernels
+ * (2: attention only, 0: off).
  * option "profile" = 1 starts bracketing every kernel launch of the forward with HIP
- * events on its stream (a measurement mode: it adds event overhead), 0 stops. */
+ * events on its stream (a measurement mode: it adds event overhead), 0 stops.
+ * option "gemm_splits" = mode*100 + s forces s K splits (1..8; 0 = automatic) for
+ * the bf16 GEMMs of mode 0 (plain / residual) or 2 (SwiGLU, ignored): a tuning knob.
+ * Unknown names and out-of-range values return SD_EINVAL. */
 int sd_set_option(const char *name, int32_t value);
 /* Per-kernel-class totals gathered under option "profile": idx = 0,1,.. until
  * SD_EINVAL; *name is a static string, *count launches, *total_ms their summed

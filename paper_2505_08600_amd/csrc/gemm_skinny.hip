@@ -395,15 +395,15 @@ static hipError_t tile_launch(hipStream_t s, const uint16_t *a, ActView a_av, We
     return hipGetLastError();
 }
 
-int g_skinny_tune[3][2] = {{4, 0}, {4, 0}, {4, 0}}; // [mode] -> {unused, K splits (0 = automatic)}
+int g_force_splits[3] = {0, 0, 0}; // [mode] -> K splits (0 = automatic); a tuning knob for sweeps
 
 // Number of K splits the launcher will use for this shape (the caller sizes and reduces the partials).
 int gemm_skinny_splits(int mode, int M, int N, int K)
 {
     if (mode == GEMM_SWIGLU || K < 128 || K % 128 != 0) return 1; // (the launcher rejects such K)
     int kps, ny;
-    if (g_skinny_tune[mode][1] > 0) {
-        split_geometry(K, g_skinny_tune[mode][1], &kps, &ny);
+    if (g_force_splits[mode] > 0) {
+        split_geometry(K, g_force_splits[mode], &kps, &ny);
         return ny;
     }
     const int steps = K / 128;

@@ -97,12 +97,10 @@ extern "C" int sd_set_option(const char *name, int32_t value)
         g_force_generic = value == 1 ? 3 : value;
         return SD_OK;
     }
-    if (!strcmp(name, "skinny_tune")) { // value = mode*10000 + tiles_per_wave*100 + waves_per_block (sweeps)
-        int mode = value / 10000, nt = (value / 100) % 100, wv = value % 100;
-        if (mode < 0 || mode > 2 || (nt != 1 && nt != 2 && nt != 4) || (wv != 4 && wv != 8 && wv != 16) || nt * wv > 32)
-            return sd_fail(SD_EINVAL, "sd_set_option: bad skinny_tune value");
-        g_skinny_tune[mode][0] = nt;
-        g_skinny_tune[mode][1] = wv;
+    if (!strcmp(name, "gemm_splits")) { // value = mode*100 + K splits of the few-row / row-blocked GEMM (0 = automatic)
+        const int mode = value / 100, ks = value % 100;
+        if (value < 0 || mode > 2 || ks > 8) return sd_fail(SD_EINVAL, "sd_set_option: bad gemm_splits value");
+        g_force_splits[mode] = ks;
         return SD_OK;
     }
     if (!strcmp(name, "profile")) { // 1: start a fresh measurement, 0: stop recording (totals stay readable)

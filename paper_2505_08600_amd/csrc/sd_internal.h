@@ -206,7 +206,7 @@ int sd_fail(int code, const std::string &s);
     } while (0)
 
 extern int g_force_generic;
-extern int g_skinny_tune[3][2]; // per GEMM mode {column tiles per wave, waves per block}
+extern int g_force_splits[3]; // per GEMM mode: K splits forced by option "gemm_splits" (0 = automatic)
 
 // ---------------------------------------------------------------- kernel launchers
 // (each returns a hipError_t from hipGetLastError after the launch)
