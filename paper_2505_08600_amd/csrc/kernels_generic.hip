@@ -415,10 +415,7 @@ __global__ __launch_bounds__(1024) void add_rmsnorm_kernel(float *x, const float
         const float4 a = it < KEEP ? keep[it] : *(const float4 *)(xr + 4 * v);
         const float4 gg = *(const float4 *)(g + 4 * v);
         const size_t o = act_index(av, j, 4 * v, d); // 4 consecutive columns stay inside one K step
-        store_act(out, o, av.plane, a.x * inv * gg.x);
-        store_act(out, o + 1, av.plane, a.y * inv * gg.y);
-        store_act(out, o + 2, av.plane, a.z * inv * gg.z);
-        store_act(out, o + 3, av.plane, a.w * inv * gg.w);
+        store_act4(out, o, av.plane, a.x * inv * gg.x, a.y * inv * gg.y, a.z * inv * gg.z, a.w * inv * gg.w);
     }
 }
 

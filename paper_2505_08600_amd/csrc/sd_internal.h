@@ -57,6 +57,24 @@ __device__ __forceinline__ void store_act(bf16_t *b, size_t i, size_t plane, flo
     b[i + plane].v = bf16_bits_rne(v - __uint_as_float((uint32_t)hi << 16));
 }
 
+// Four consecutive elements at an index that is a multiple of 4: one 8-byte store per bf16 plane.
+__device__ __forceinline__ void store_act4(float *b, size_t i, size_t, float v0, float v1, float v2, float v3)
+{
+    *(float4 *)(b + i) = make_float4(v0, v1, v2, v3);
+}
+__device__ __forceinline__ void store_act4(bf16_t *b, size_t i, size_t plane, float v0, float v1, float v2, float v3)
+{
+    const float v[4] = {v0, v1, v2, v3};
+    uint16_t hi[4], lo[4];
+#pragma unroll
+    for (int e = 0; e < 4; e++) {
+        hi[e] = bf16_bits_rne(v[e]);
+        lo[e] = bf16_bits_rne(v[e] - __uint_as_float((uint32_t)hi[e] << 16));
+    }
+    *(uint2 *)(b + i) = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
+    *(uint2 *)(b + i + plane) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
+}
+
 // Where element (row m, column k) of a GEMM-input activation buffer of width K lives.  Row-major, or
 // (bf16 buffers whose width is a multiple of 128) "step-major": the 128 columns of K step k/128 of all
 // rows of this forward are contiguous, [k/128][m][k%128].  A GEMM block then finds the rows it needs for
