@@ -367,25 +367,34 @@ __global__ __launch_bounds__(AF_WAVES * 64) void attn_fused_kernel(const float *
         sL[wave][qi] = l_run;
     }
     __syncthreads();
-    for (int e = threadIdx.x; e < ND * 256; e += AF_WAVES * 64) {
-        const int d = e >> 8, slot = (e >> 2) & 63, r = e & 3;
-        const int q = slot & 15, dim = 16 * d + 4 * (slot >> 4) + r;
+    // one thread per (d tile, lane slot): four consecutive head dimensions of one query row
+    for (int e = threadIdx.x; e < ND * 64; e += AF_WAVES * 64) {
+        const int d = e >> 6, slot = e & 63;
+        const int q = slot & 15, dim = 16 * d + 4 * (slot >> 4);
         if (q >= R) continue;
         float M = AT_NEG;
 #pragma unroll
         for (int w = 0; w < AF_WAVES; w++) M = fmaxf(M, sM[w][q]);
-        float O = 0.f, L = 0.f;
+        f32x4 O = {0.f, 0.f, 0.f, 0.f};
+        float L = 0.f;
 #pragma unroll
         for (int w = 0; w < AF_WAVES; w++) {
             const float f = fast_exp(sM[w][q] - M);
-            O += sO[w][d][slot][r] * f;
+            const f32x4 p = *(const f32x4 *)&sO[w][d][slot][0];
+            O += p * f;
             L += sL[w][q] * f;
         }
-        const float out = (q < nq && L > 0.f) ? O / L : 0.f;
-        const uint16_t hi = bf16_bits_rne(out);
-        const size_t oi = act_index(o_av, j * R + q, h * HD + dim, HDm);
-        obuf[oi] = hi;
-        obuf[oi + o_av.plane] = bf16_bits_rne(out - __uint_as_float((uint32_t)hi << 16));
+        const bool live = q < nq && L > 0.f;
+        uint16_t hi[4], lo[4];
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            const float out = live ? O[r] / L : 0.f;
+            hi[r] = bf16_bits_rne(out);
+            lo[r] = bf16_bits_rne(out - __uint_as_float((uint32_t)hi[r] << 16));
+        }
+        const size_t oi = act_index(o_av, j * R + q, h * HD + dim, HDm); // 4 columns inside one K step
+        *(uint2 *)(obuf + oi) = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
+        *(uint2 *)(obuf + oi + o_av.plane) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
     }
 }
 
