@@ -86,12 +86,14 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_tile_kernel(const uint16_t *A
             Wp[c] = (const uint16_t *)w.p[c & 1] + (size_t)(n0 / 16 + wave * (NT / 2) + (c >> 1)) * tile_elems +
                     (size_t)(kb >> 7) * 2048 + lane * 8;
     } else {
-        const int seg = n0 / w.n_per_seg;
-        const int nl = n0 - seg * w.n_per_seg;
+        const int seg_tiles = w.n_per_seg / 16; // a block's tiles may lie in different segments (q | k | v)
 #pragma unroll
-        for (int c = 0; c < NT; c++)
-            Wp[c] = (const uint16_t *)w.p[seg] + (size_t)(nl / 16 + wave * NT + c) * tile_elems +
-                    (size_t)(kb >> 7) * 2048 + lane * 8;
+        for (int c = 0; c < NT; c++) {
+            const int tile = n0 / 16 + wave * NT + c;
+            const int seg = tile / seg_tiles;
+            const uint16_t *base = (const uint16_t *)(seg == 0 ? w.p[0] : seg == 1 ? w.p[1] : w.p[2]);
+            Wp[c] = base + (size_t)(tile - seg * seg_tiles) * tile_elems + (size_t)(kb >> 7) * 2048 + lane * 8;
+        }
     }
     // cooperative staging of the activation chunk: vector v -> operand row v / VEC_PER_ROW.  Rows past M
     // are loaded like any other (the buffers are over-allocated by SD_ACT_PAD_ROWS rows, so the addresses
@@ -363,42 +365,73 @@ __global__ __launch_bounds__(256) void gemm_ksplit_kernel(const uint16_t *__rest
     }
 }
 
-// Row blocks of 96 rows x 256 columns (4 waves; chunks of half a K step) when there are more than 48 rows:
-// the bytes a block pulls through L2 per MFMA halve against the 48 x 128 shape, which is what bounds
-// these GEMMs; up to 48 rows one 48-row block (2 waves x 128 columns) wastes less.
-#define SD_TILE_BIG_COLS 256
-#define SD_TILE_SMALL_COLS 128
+// Block shapes of the row-blocked kernel.  More than 64 rows: 96 rows x 256 columns (4 waves x 4 tiles; chunks
+// of half a K step) - the bytes a block pulls through L2 per MFMA halve against 48 x 128, which is what
+// bounds these GEMMs - or x 192 columns (3 tiles per wave) where that fills the 256 compute units better
+// (QKV at M = 192: 128 blocks x 2 K splits instead of 96 x 2).  Up to 64 rows: 48-row blocks of 2 waves x
+// 128 columns, two resident per unit.  A block of the 96-row shapes has a compute unit to itself
+// (~500 registers per wave), so the K splits are chosen to cover the chip in one round of blocks.
+struct TileShape {
+    int cols;   // weight rows per block (0: shape not supported)
+    int bm;     // rows per block
+    int blocks; // blocks of one K split
+    int slots;  // blocks resident at once
+};
+static int one_round_splits(int blocks, int slots, int steps)
+{
+    int ks = 1;
+    while (ks < 8 && blocks * (ks + 1) <= slots && (steps + ks) / (ks + 1) >= 4) ks++;
+    return ks;
+}
+static TileShape tile_shape(int mode, int M, int N, int n_per_seg, int K)
+{
+    const int out_per_col = mode == GEMM_SWIGLU ? 2 : 1; // weight rows per output column
+    const int rows_w = N * out_per_col;                  // weight rows streamed
+    TileShape t = {0, 0, 0, 0};
+    if (M > 64) {
+        const int nmb = (M + 95) / 96, steps = K / 128;
+        const bool ok256 = rows_w % 256 == 0 && (mode == GEMM_SWIGLU || n_per_seg % 256 == 0);
+        const bool ok192 = mode == GEMM_STORE && rows_w % 192 == 0 && n_per_seg % 16 == 0;
+        auto fill = [&](int cols) { // fraction of the 256 units busy, averaged over the rounds of blocks
+            const int blocks = rows_w / cols * nmb;
+            const int tot = blocks * one_round_splits(blocks, 256, steps);
+            return (float)tot / (256.f * (float)((tot + 255) / 256));
+        };
+        int cols = 0;
+        if (ok256) cols = 256;
+        if (ok192 && (!ok256 || fill(192) > fill(256) + 0.1f)) cols = 192;
+        if (cols) return TileShape{cols, 96, rows_w / cols * nmb, 256};
+    }
+    if (rows_w % 128 == 0 && (mode == GEMM_SWIGLU || n_per_seg % 128 == 0))
+        t = TileShape{128, 48, rows_w / 128 * ((M + 47) / 48), 512};
+    return t;
+}
+
 template <int MODE>
 static hipError_t tile_launch(hipStream_t s, const uint16_t *a, ActView a_av, WeightSeg w, int M, int N, int K, int ks,
                               float *C, size_t c_split_stride, uint16_t *ca, ActView c_av)
 {
     int kps, ny;
     split_geometry(K, ks, &kps, &ny);
-    constexpr int OUT_PER_COL = MODE == GEMM_SWIGLU ? 2 : 1; // weight rows per output column
-    const bool big = M > 64 && N % (SD_TILE_BIG_COLS / OUT_PER_COL) == 0 &&
-                     (MODE == GEMM_SWIGLU || w.n_per_seg % SD_TILE_BIG_COLS == 0);
-    if (big) {
-        const int ntiles = N / (SD_TILE_BIG_COLS / OUT_PER_COL);
-        const int nmb = (M + 95) / 96;
-        const int gx = ((ntiles + 7) / 8) * 8 * nmb;
-        hipLaunchKernelGGL((gemm_tile_kernel<MODE, 96, 64, 4, 4, 3>), dim3(gx, ny), dim3(256), 0, s, a, a_av, w, M, N, K,
-                           kps, nmb, ntiles, C, c_split_stride, ca, c_av);
-    } else {
-        if (N % (SD_TILE_SMALL_COLS / OUT_PER_COL) != 0 || (MODE != GEMM_SWIGLU && w.n_per_seg % SD_TILE_SMALL_COLS != 0))
-            return hipErrorNotSupported;
-        const int ntiles = N / (SD_TILE_SMALL_COLS / OUT_PER_COL);
-        const int nmb = (M + 47) / 48;
-        const int gx = ((ntiles + 7) / 8) * 8 * nmb;
-        hipLaunchKernelGGL((gemm_tile_kernel<MODE, 48, 128, 4, 2, 3>), dim3(gx, ny), dim3(128), 0, s, a, a_av, w, M, N, K,
-                           kps, nmb, ntiles, C, c_split_stride, ca, c_av);
-    }
+    const TileShape t = tile_shape(MODE, M, N, w.n_per_seg, K);
+    if (!t.cols) return hipErrorNotSupported;
+    constexpr int OUT_PER_COL = MODE == GEMM_SWIGLU ? 2 : 1;
+    const int ntiles = N * OUT_PER_COL / t.cols, nmb = (M + t.bm - 1) / t.bm;
+    const int gx = ((ntiles + 7) / 8) * 8 * nmb;
+#define SD_TILE(BM, KC, NT, WAVES, NB)                                                                              \
+    hipLaunchKernelGGL((gemm_tile_kernel<MODE, BM, KC, NT, WAVES, NB>), dim3(gx, ny), dim3(WAVES * 64), 0, s, a, a_av, w, \
+                       M, N, K, kps, nmb, ntiles, C, c_split_stride, ca, c_av)
+    if (t.cols == 256) SD_TILE(96, 64, 4, 4, 3);
+    else if (t.cols == 192) {
+        if constexpr (MODE == GEMM_STORE) SD_TILE(96, 64, 3, 4, 3);
+    } else SD_TILE(48, 128, 4, 2, 3);
     return hipGetLastError();
 }
 
 int g_force_splits[3] = {0, 0, 0}; // [mode] -> K splits (0 = automatic); a tuning knob for sweeps
 
 // Number of K splits the launcher will use for this shape (the caller sizes and reduces the partials).
-int gemm_skinny_splits(int mode, int M, int N, int K)
+int gemm_skinny_splits(int mode, int M, int N, int K, int n_per_seg)
 {
     if (mode == GEMM_SWIGLU || K < 128 || K % 128 != 0) return 1; // (the launcher rejects such K)
     int kps, ny;
@@ -412,14 +445,10 @@ int gemm_skinny_splits(int mode, int M, int N, int K)
         const int blocks = N / 32;
         ks = steps >= 16 ? 2 : 1; // measured: two half-length blocks per tile stream faster than one
         while (blocks * ks < 256 && ks < 8 && steps / (ks * 2) >= 4) ks *= 2;
-    } else { // row-blocked kernel: one block per compute unit and round; partial slabs cost M*N*4 bytes each
-        const bool big = M > 64 && N % SD_TILE_BIG_COLS == 0;
-        const int blocks = big ? (N / SD_TILE_BIG_COLS) * ((M + 95) / 96) : (N / SD_TILE_SMALL_COLS) * ((M + 47) / 48);
-        const int slots = big ? 256 : 512; // blocks resident at once
-        // measured at M = 192: a block costs about five K steps of fixed time, so one round of blocks with the
-        // K range cut as finely as that allows beats several rounds of shorter blocks
-        ks = 1;
-        while (ks < 8 && blocks * (ks + 1) <= slots && (steps + ks) / (ks + 1) >= 4) ks++;
+    } else { // row-blocked kernel.  Measured at M = 192: a block costs about five K steps of fixed time, so one
+             // round of blocks with the K range cut as finely as that allows beats several rounds of shorter blocks
+        const TileShape t = tile_shape(mode, M, N, n_per_seg, K);
+        ks = t.cols ? one_round_splits(t.blocks, t.slots, steps) : 1;
     }
     split_geometry(K, ks, &kps, &ny);
     return ny;

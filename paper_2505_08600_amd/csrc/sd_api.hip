@@ -545,7 +545,7 @@ static int stream_gemm(sd_model *m, hipStream_t s, const void *A, ActView a_av, 
 {
     *err = hipSuccess;
     if (m->cfg.dtype != SD_BF16 || (g_force_generic & 1)) return 0;
-    int ns = force_splits > 0 ? force_splits : gemm_skinny_splits(GEMM_STORE, M, N, K);
+    int ns = force_splits > 0 ? force_splits : gemm_skinny_splits(GEMM_STORE, M, N, K, w.n_per_seg);
     if ((size_t)ns * M * N > slabs_floats || ns > 8) ns = 1;
     const ActView none = {0, 0, 0};
     hipError_t e = launch_gemm_skinny_bf16(s, GEMM_STORE, A, a_av, w, M, N, K, slabs, (size_t)M * N, ns, nullptr, none);

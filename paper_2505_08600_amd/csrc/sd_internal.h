@@ -261,7 +261,7 @@ hipError_t launch_set_kv(hipStream_t s, int dtype, const void *k_rows, const voi
 // optimised bf16 paths (return hipErrorNotSupported when the shape is outside their domain)
 // GEMM_STORE: C receives `splits` partial slabs (slab stride c_split_stride floats) that the consumer adds;
 // GEMM_SWIGLU: Cact receives the bf16 hi/lo planes.  gemm_skinny_splits tells how many slabs to expect.
-int gemm_skinny_splits(int mode, int M, int N, int K);
+int gemm_skinny_splits(int mode, int M, int N, int K, int n_per_seg);
 hipError_t launch_gemm_skinny_bf16(hipStream_t s, int mode, const void *A, ActView a_av, WeightSeg w, int M, int N,
                                    int K, float *C, size_t c_split_stride, int splits, void *Cact, ActView c_av);
 hipError_t launch_add_rmsnorm(hipStream_t s, int dtype, float *x, const float *part, int n_slabs, size_t slab_stride,
