@@ -195,7 +195,8 @@ int sd_debug_read(sd_model *m, const char *name, float *out, int32_t rows);
  * kind 1: step-major activation plane, a = row m, b = column k, c = K, d = rows of the
  *         forward;
  * kind 2: value cache of one head, a = token row t, b = dimension, c = head_dim
- *         (transposed 32-token tiles).
+ *         (transposed 32-token tiles);
+ * kind 3: key cache of one head, same arguments (32-token tiles in MFMA operand order).
  * Returns -1 for an unknown kind or arguments outside the layout's domain. */
 int64_t sd_debug_layout_index(int32_t kind, int64_t a, int64_t b, int64_t c, int64_t d);
 /* option "force_generic" = 1 routes every op through the simple reference kernels

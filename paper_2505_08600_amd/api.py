@@ -240,7 +240,7 @@ class Context:
 
 
 def layout_index(kind: int, a: int, b: int, c: int, d: int = 0) -> int:
-    """sd_debug_layout_index: 0 tiled weight (n, k, K), 1 step-major activation (m, k, K, rows), 2 value cache (t, dim, head_dim)."""
+    """sd_debug_layout_index: 0 tiled weight (n, k, K), 1 step-major activation (m, k, K, rows), 2 value cache / 3 key cache (t, dim, head_dim)."""
     return int(lib().sd_debug_layout_index(kind, a, b, c, d))
 
 

@@ -58,19 +58,17 @@ __device__ __forceinline__ void attn_tiles(const uint16_t *__restrict__ K, const
     const int qi = lane & 15, grp = lane >> 4;
     const float scale = 1.0f / sqrtf((float)HD);
     // K operand rows: lane row i holds token 8*(i/4) + i%4 (tile a) or that + 4 (tile b)
-    const int krow = 8 * (qi >> 2) + (qi & 3);
     // two register buffers: the loads of the next tile are in flight while the current one is consumed
     bf16x8 ka0[NC], kb0[NC], vv0[ND], ka1[NC], kb1[NC], vv1[ND];
     auto load_tile = [&](int t, bf16x8 *ka, bf16x8 *kb, bf16x8 *vv) {
         const int t0 = t * AT_TILE;
-        // MFMA c contracts head dimensions 32*c .. 32*c+31 (k-group grp takes 8 of them): each load
-        // instruction reads 64 contiguous bytes of every row
-        const uint16_t *kpa = K + (size_t)(t0 + krow) * HD + grp * 8;
-        const uint16_t *kpb = kpa + 4 * HD;
+        // MFMA c contracts head dimensions 32*c .. 32*c+31 (k-group grp takes 8 of them); the tile is stored
+        // in operand order (kt_offset), so every load instruction reads one contiguous KiB
+        const uint16_t *kp = K + (size_t)t * (AT_TILE * HD) + lane * 8;
 #pragma unroll
         for (int c = 0; c < NC; c++) {
-            ka[c] = *(const bf16x8 *)(kpa + c * 32);
-            kb[c] = *(const bf16x8 *)(kpb + c * 32);
+            ka[c] = *(const bf16x8 *)(kp + (2 * c) * 512);
+            kb[c] = *(const bf16x8 *)(kp + (2 * c + 1) * 512);
         }
 #pragma unroll
         for (int d = 0; d < ND; d++) vv[d] = *(const bf16x8 *)(Vt + (size_t)t * (AT_TILE * HD) + (d * 16 + qi) * AT_TILE + grp * 8);
@@ -332,9 +330,8 @@ __global__ __launch_bounds__(AF_WAVES * 64) void attn_fused_kernel(const float *
             const float ka = k0 * cs.x - k1 * cs.y, kb = k1 * cs.x + k0 * cs.y;
             q0 = qa;
             q1 = qb;
-            uint16_t *kd = K + (size_t)pos * HD;
-            kd[e] = bf16_bits_rne(ka);
-            kd[e + HALF] = bf16_bits_rne(kb);
+            K[kt_offset(HD, pos, e)] = bf16_bits_rne(ka);
+            K[kt_offset(HD, pos, e + HALF)] = bf16_bits_rne(kb);
             Vt[vt_offset(HD, pos, e)] = bf16_bits_rne(v0);
             Vt[vt_offset(HD, pos, e + HALF)] = bf16_bits_rne(v1);
         }

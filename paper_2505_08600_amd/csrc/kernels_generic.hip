@@ -370,7 +370,7 @@ hipError_t launch_embed_rmsnorm(hipStream_t s, int dtype, const void *E, const i
 
 // qkv: fp32 [M][3*HD] (q | k | v).  Rotates q and k of every valid row at its
 // position (rotate-half pairing), writes q to qbuf and k, v into the cache in
-// place: K[head][off+pos][hd], V in 32-token transposed tiles (vt_offset).
+// place: K in 32-token tiles in MFMA operand order (kt_offset), V in 32-token transposed tiles (vt_offset).
 // Residual update fused with the next RMSNorm: x[src] += sum of the split-K slabs of the
 // preceding GEMM (added in slab order), then out[j] = rmsnorm(x[src]) * g.  One block of 1024
 // threads per row; the loads of all slabs of an element are independent and go out together.
@@ -481,9 +481,9 @@ __global__ void rope_append_kernel(const float *qkv, int n_slabs, size_t slab_st
             }
         store_act(qbuf, act_index(q_av, r, h * hd + e, HD), q_av.plane, q0 * cs.x - q1 * cs.y);
         store_act(qbuf, act_index(q_av, r, h * hd + e + half, HD), q_av.plane, q1 * cs.x + q0 * cs.y);
-        T *kd = Kl + ((size_t)h * total_cap + off + pos) * hd;
-        kd[e] = from_float<T>(k0 * cs.x - k1 * cs.y);
-        kd[e + half] = from_float<T>(k1 * cs.x + k0 * cs.y);
+        T *kh = Kl + (size_t)h * total_cap * hd;
+        kh[kt_offset(hd, off + pos, e)] = from_float<T>(k0 * cs.x - k1 * cs.y);
+        kh[kt_offset(hd, off + pos, e + half)] = from_float<T>(k1 * cs.x + k0 * cs.y);
         T *vh = Vtl + (size_t)h * hd * total_cap;
         vh[vt_offset(hd, off + pos, e)] = from_float<T>(v0);
         vh[vt_offset(hd, off + pos, e + half)] = from_float<T>(v1);
@@ -526,16 +526,15 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const T *qbuf, ActVie
     int Lk = pv.seq_kv0[j] + i + 1;
     if (Lk > lds_len) Lk = lds_len; // host sizes lds_len from an upper bound; never exceeded
     int64_t off = cv.off[pv.seq_b[j]];
-    const T *K = Kl + ((size_t)h * total_cap + off) * hd;
+    const T *Kh = Kl + (size_t)h * total_cap * hd;
     const T *Vh = Vtl + (size_t)h * hd * total_cap;
     for (int d = threadIdx.x; d < hd; d += blockDim.x) qs[d] = load_act(qbuf, act_index(q_av, r, h * hd + d, HD), q_av.plane);
     __syncthreads();
     float scale = 1.0f / sqrtf((float)hd);
     float mx = -3.0e38f;
     for (int t = threadIdx.x; t < Lk; t += blockDim.x) {
-        const T *kt = K + (size_t)t * hd;
         float dot = 0.f;
-        for (int d = 0; d < hd; d++) dot += qs[d] * to_float(kt[d]);
+        for (int d = 0; d < hd; d++) dot += qs[d] * to_float(Kh[kt_offset(hd, off + t, d)]);
         dot *= scale;
         sc[t] = dot;
         mx = fmaxf(mx, dot);
@@ -1278,7 +1277,7 @@ __global__ void set_kv_kernel(const T *k_rows, const T *v_rows, int len, int H, 
         int d = i % hd;
         int h = (i / hd) % H;
         int t = i / ((size_t)hd * H);
-        Kl[((size_t)h * total_cap + seq_off + t) * hd + d] = k_rows[i];
+        Kl[(size_t)h * total_cap * hd + kt_offset(hd, seq_off + t, d)] = k_rows[i];
         Vtl[(size_t)h * hd * total_cap + vt_offset(hd, seq_off + t, d)] = v_rows[i];
     }
 }

@@ -475,6 +475,7 @@ extern "C" int64_t sd_debug_layout_index(int32_t kind, int64_t a, int64_t b, int
         return (int64_t)act_index(av, (int)a, (int)b, (int)c);
     }
     if (kind == 2) return b < c ? (int64_t)vt_offset((int)c, a, (int)b) : -1;
+    if (kind == 3) return (b < c && c % 8 == 0) ? (int64_t)kt_offset((int)c, a, (int)b) : -1;
     return -1;
 }
 

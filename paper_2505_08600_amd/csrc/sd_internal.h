@@ -99,6 +99,19 @@ __host__ __device__ __forceinline__ size_t vt_offset(int hd, int64_t t, int d)
     return (size_t)(t >> 5) * (size_t)(32 * hd) + (size_t)d * 32 + (size_t)(t & 31);
 }
 
+// Key cache of one head: 32-token tiles in the operand order of the score MFMAs.  The scores of a tile
+// come from two 16-row operands: operand a holds tokens 8*(i/4) + i%4 in its rows i = 0..15, operand b those
+// + 4 (this permutation is what lets the result feed the second product without a shuffle).  Piece
+// (c, ab, g, i) - dimensions 32c + 8g .. +8 of the token in row i of operand ab - sits at 16-byte slot
+// (2c + ab) * 64 + 16g + i of the tile, so each load instruction of a wave reads one contiguous KiB.
+__host__ __device__ __forceinline__ size_t kt_offset(int hd, int64_t t, int d)
+{
+    const int tok = (int)(t & 31);
+    const int ab = (tok >> 2) & 1, i = (tok >> 3) * 4 + (tok & 3);
+    const int G = (hd < 32 ? hd : 32) >> 3; // 8-dimension groups per 32-dimension chunk (4 unless head_dim < 32)
+    return (size_t)(t >> 5) * (size_t)(32 * hd) + (size_t)(((((d >> 5) * 2 + ab) * G + ((d >> 3) & 3)) * 16 + i) * 8 + (d & 7));
+}
+
 // ---------------------------------------------------------------- views passed to kernels
 // Device-side view of a context.  kvlen is [SD_MAX_SLOTS][B].
 struct CtxView {

@@ -49,3 +49,21 @@ def test_value_cache_tiles(hd):
         # transposed inside the tile: 32 tokens of one dimension are contiguous
         for d in range(hd):
             assert np.array_equal(blk[:, d], tile * 32 * hd + d * 32 + np.arange(32))
+
+
+@pytest.mark.parametrize("hd", [16, 32, 64, 128])
+def test_key_cache_tiles_are_in_score_operand_order(hd):
+    T = 64
+    idx = np.array([[api.layout_index(3, t, d, hd) for d in range(hd)] for t in range(T)])
+    assert sorted(idx.ravel().tolist()) == list(range(T * hd))
+    G = min(hd, 32) // 8
+    for tile in range(T // 32):
+        base = tile * 32 * hd
+        for c in range(max(1, hd // 32)):
+            for ab in range(2):
+                for g in range(G):
+                    for i in range(16):
+                        tok = 8 * (i // 4) + i % 4 + 4 * ab  # token held by row i of score operand a / b
+                        got = idx[tile * 32 + tok, 32 * c + 8 * g: 32 * c + 8 * g + 8]
+                        want = base + (((2 * c + ab) * G + g) * 16 + i) * 8 + np.arange(8)
+                        assert np.array_equal(got, want)
