@@ -131,7 +131,10 @@ int sd_prefill(sd_model *m, sd_ctx *c, const int32_t *seq_ids /*dev*/, int32_t n
  * == 0 (greedy): candidate = argmax (ties to the lowest id); q and uniforms are
  * not touched and may be NULL.  The last candidate is not fed to the draft.
  *   uniforms dev fp32 [n_seq][gamma], cand dev int32 [n_seq][gamma],
- *   q dev fp32 [n_seq][gamma][vocab].  1 <= gamma <= 15. */
+ *   q dev fp32 [n_seq][gamma][vocab].  1 <= gamma <= 15.
+ * sd_draft, sd_verify and sd_commit only enqueue kernels on `stream` (no allocation,
+ * copy, memset or host synchronisation; option "profile" off), so they may be
+ * captured into a HIP graph. */
 int sd_draft(sd_model *draft, sd_ctx *c, const int32_t *seq_ids /*dev*/, int32_t n_seq, int32_t gamma,
              float temperature, const float *uniforms, int32_t *cand, float *q, void *stream);
 

@@ -186,6 +186,70 @@ def test_small_bf16_every_gemm_row_class_matches_reference_kernels(B):
     gt.close()
 
 
+def test_draft_and_verify_are_graph_capturable_and_replays_match_eager():
+    """sd_draft and sd_verify launch kernels only (no allocation, copy, memset or host synchronisation), so a
+    caller may capture them into a HIP graph.  Every replay, with eager calls and synchronisations in
+    between, must reproduce the eager results bit for bit."""
+    _say("small bf16: graph capture of draft + verify")
+    st_, sd_ = dg.SHAPES["small_target_bf16"], dg.SHAPES["small_draft_bf16"]
+    pair = H.Pair(st_, sd_, seed=65, lm_scale=BF16_LM_SCALE, max_rows=32, max_pos=512)
+    V, gamma, T = st_.vocab, 5, 1.0
+    prompt = [int(t) for t in dg.make_prompt(65, 0, 100, V)]
+    ctx = api.Context([256])
+    ctx.attach(pair.gt)
+    ctx.attach(pair.gd)
+    H.gpu_prefill(ctx, [pair.gt, pair.gd], [prompt])
+    ud = H.dev(dg.make_uniforms(65, dg.DRAFT_STREAM, 0, 0, gamma)[None])
+    uv = H.dev(dg.make_uniforms(65, dg.VERIFY_STREAM, 0, 0, gamma + 1)[None])
+    cand = torch.zeros((1, gamma), dtype=torch.int32, device="cuda")
+    q = torch.zeros((1, gamma, V), dtype=torch.float32, device="cuda")
+    na = torch.zeros(1, dtype=torch.int32, device="cuda")
+    nx = torch.zeros(1, dtype=torch.int32, device="cuda")
+
+    def step():
+        api.sd_draft(pair.gd, ctx, None, 1, gamma, T, ud, cand, q)
+        api.sd_verify(pair.gt, ctx, None, 1, gamma, T, cand, q, uv, na, nx, commit=False)
+
+    def rollback():
+        torch.cuda.synchronize()
+        ctx.truncate(pair.gt, 0, len(prompt) - 1)
+        ctx.truncate(pair.gd, 0, len(prompt) - 1)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return (cand.cpu().numpy().copy(), q.cpu().numpy().copy(), int(na.item()), int(nx.item()),
+                pair.gt.last_logits().cpu().numpy().copy())
+
+    step()
+    ref = snapshot()
+    rollback()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step()  # warm-up on the capture stream
+        rollback()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    rollback()
+    for r in range(3):
+        for t in (cand, q, na, nx):
+            t.zero_()
+        graph.replay()
+        got = snapshot()
+        rollback()
+        for a, b in zip(ref, got):
+            assert np.array_equal(np.asarray(a), np.asarray(b)), f"replay {r} differs from the eager step"
+        step()  # the program's own eager work between replays
+        got = snapshot()
+        rollback()
+        for a, b in zip(ref, got):
+            assert np.array_equal(np.asarray(a), np.asarray(b))
+    ctx.sync()
+    ctx.close()
+    pair.close()
+
+
 def test_gamma_zero_is_autoregressive_decoding(tiny_pair):
     _say("gamma = 0")
     prompt = dg.make_prompt(11, 2, 12, TINY_T.vocab)
