@@ -786,10 +786,6 @@ __device__ void row_stats_regs(RowRegs &r, float invT, FastScratch *fs, float &m
 __device__ int pick_regs(const RowRegs &w, int V, float u, FastScratch *fs, float *total_out)
 {
     const int lane = threadIdx.x % WAVE, wv = threadIdx.x / WAVE;
-    if (threadIdx.x == 0) {
-        fs->pick = 0x7fffffff;
-        fs->last_pos = 0;
-    }
     int lastp = -1;
     float loc[ROW_NSEG];
 #pragma unroll
@@ -802,22 +798,25 @@ __device__ int pick_regs(const RowRegs &w, int V, float u, FastScratch *fs, floa
         if (f.w > 0.f) lastp = 4 * v + 3;
         loc[it] = wave_sum(((f.x + f.y) + f.z) + f.w);
     }
-    __syncthreads();
+#pragma unroll
+    for (int o = WAVE / 2; o > 0; o >>= 1) lastp = max(lastp, __shfl_xor(lastp, o, WAVE));
+    __syncthreads(); // the scratch may still be in use by a previous call
     if (lane == 0) {
 #pragma unroll
         for (int it = 0; it < ROW_NSEG; it++) fs->wsum[wv][it] = loc[it];
+        fs->redi[wv] = lastp;
     }
-    if (lastp >= 0) atomicMax(&fs->last_pos, lastp);
+    __syncthreads();
+    const int nseg = ((V + 3) / 4 + ROW_THREADS - 1) / ROW_THREADS;
+    if ((int)threadIdx.x < nseg) { // one thread per segment adds the wave sums in wave order
+        float t = 0.f;
+        for (int i = 0; i < ROW_THREADS / WAVE; i++) t += fs->wsum[i][threadIdx.x];
+        fs->seg[threadIdx.x] = t;
+    }
     __syncthreads();
     if (threadIdx.x == 0) {
-        const int nseg = ((V + 3) / 4 + ROW_THREADS - 1) / ROW_THREADS;
         float Z = 0.f;
-        for (int it = 0; it < nseg; it++) {
-            float t = 0.f;
-            for (int i = 0; i < ROW_THREADS / WAVE; i++) t += fs->wsum[i][it];
-            fs->seg[it] = t;
-            Z += t;
-        }
+        for (int it = 0; it < nseg; it++) Z += fs->seg[it];
         const float target = u * Z;
         float cum = 0.f;
         int found = -1;
@@ -828,9 +827,13 @@ __device__ int pick_regs(const RowRegs &w, int V, float u, FastScratch *fs, floa
             }
             cum += fs->seg[it];
         }
+        int lp = 0; // last index with a positive weight (0 if there is none)
+        for (int i = 0; i < ROW_THREADS / WAVE; i++) lp = max(lp, fs->redi[i]);
         fs->seg_idx = found;
         fs->base = cum;
         fs->target = target;
+        fs->pick = 0x7fffffff;
+        fs->last_pos = lp;
         if (total_out) *total_out = Z;
     }
     __syncthreads();
