@@ -190,7 +190,9 @@ int sd_ctx_truncate(sd_ctx *c, sd_model *m, int32_t seq, int32_t len);
 int sd_last_logits(sd_model *m, float *out, int32_t max_rows, int32_t *rows);
 /* Copy one activation buffer of model m's last forward to out (HOST, fp32): name is
  * "x" (residual [rows][d_model]), "qkv" ([rows][3*d_model]), "q", "o", "a"
- * ([rows][d_model]) or "act" ([rows][d_ffn]).  Synchronises. */
+ * ([rows][d_model]) or "act" ([rows][d_ffn]); "seq_order" / "seq_len" give, for the
+ * first `rows` sequences of the last forward, the order attention blocks start in
+ * (longest first) and the cache length after that forward.  Synchronises. */
 int sd_debug_read(sd_model *m, const char *name, float *out, int32_t rows);
 /* Host-only (no GPU call): element offset that the library's internal layouts assign.
  * kind 0: tiled bf16 weight [N][K], a = row n, b = column k, c = K  (16-row x 128-column
@@ -208,6 +210,8 @@ int64_t sd_debug_layout_index(int32_t kind, int64_t a, int64_t b, int64_t c, int
  * events on its stream (a measurement mode: it adds event overhead), 0 stops.
  * option "gemm_splits" = mode*100 + s forces s K splits (1..8; 0 = automatic) for
  * the bf16 GEMMs of mode 0 (plain / residual) or 2 (SwiGLU, ignored): a tuning knob.
+ * option "attn_waves" = 4 or 8 forces the block shape of the fused attention kernel
+ * (0 = automatic: 4-wave blocks once (sequence, head) pairs oversubscribe the chip).
  * Unknown names and out-of-range values return SD_EINVAL. */
 int sd_set_option(const char *name, int32_t value);
 /* Per-kernel-class totals gathered under option "profile": idx = 0,1,.. until

@@ -163,9 +163,10 @@ class Model:
             pass
 
     def debug_read(self, name: str, rows: int) -> np.ndarray:
-        """Host copy (fp32) of a workspace buffer of the last forward: x, qkv, q, o, a, act."""
-        width = {"x": self.shape.d_model, "qkv": 3 * self.shape.d_model, "act": self.shape.d_ffn}.get(
-            name, self.shape.d_model)
+        """Host copy (fp32) of a workspace buffer of the last forward: x, qkv, q, o, a, act; or, with
+        rows = number of sequences, the last plan's seq_order / seq_len as one column."""
+        width = {"x": self.shape.d_model, "qkv": 3 * self.shape.d_model, "act": self.shape.d_ffn,
+                 "seq_order": 1, "seq_len": 1}.get(name, self.shape.d_model)
         out = np.empty((rows, width), np.float32)
         _check(lib().sd_debug_read(self.h, name.encode(), out.ctypes.data_as(C.c_void_p), rows))
         return out

@@ -151,7 +151,8 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restri
     constexpr int ND = HD / 16; // 16-row tiles of V^T / O^T
     __shared__ float sO[AT_WAVES][ND][64][4];
     __shared__ float sM[AT_WAVES][16], sL[AT_WAVES][16];
-    const int s = blockIdx.x, h = blockIdx.y, j = blockIdx.z;
+    const int s = blockIdx.x, h = blockIdx.y;
+    const int j = gridDim.z > 1 ? pv.seq_order[blockIdx.z] : 0; // longest sequences start first
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int qi = lane & 15, grp = lane >> 4;
     const int nq = pv.seq_nq[j], kv0 = pv.seq_kv0[j];
@@ -268,11 +269,12 @@ __global__ void attn_combine_kernel(const float *__restrict__ part, PlanView pv,
 // there are enough (sequence, head) pairs to fill the chip or the context is short, where the split
 // kernel plus its combine pass and the separate RoPE kernel are three latency-bound launches.
 // The block first adds the split-K slabs of the QKV GEMM for its head, rotates q and k, writes the new
-// K / V rows into the cache in place and q (hi, lo) into LDS; after a barrier its 8 waves stream the
-// cache (including the rows just written) tile by tile, and merge their partial results in LDS.
-#define AF_WAVES 8
-template <int HD>
-__global__ __launch_bounds__(AF_WAVES * 64) void attn_fused_kernel(const float *__restrict__ qkv, int n_slabs,
+// K / V rows into the cache in place and q (hi, lo) into LDS; after a barrier its waves stream the cache
+// (including the rows just written) tile by tile, and merge their partial results in LDS.
+// WAVES = 8: one block per compute unit (few blocks, each as parallel as possible); WAVES = 4: two
+// resident blocks per unit, so one block's prologue and merge overlap the other's streaming (many blocks).
+template <int HD, int WAVES>
+__global__ __launch_bounds__(WAVES * 64, 2) void attn_fused_kernel(const float *__restrict__ qkv, int n_slabs,
                                                                    size_t slab_stride, PlanView pv, CtxView cv, int R,
                                                                    int H, const float2 *__restrict__ rope, int max_pos,
                                                                    uint16_t *__restrict__ Kl, uint16_t *__restrict__ Vtl,
@@ -281,10 +283,11 @@ __global__ __launch_bounds__(AF_WAVES * 64) void attn_fused_kernel(const float *
 {
     constexpr int ND = HD / 16;
     constexpr int HALF = HD / 2;
-    __shared__ float sO[AF_WAVES][ND][64][4];
-    __shared__ float sM[AF_WAVES][16], sL[AF_WAVES][16];
+    __shared__ float sO[WAVES][ND][64][4];
+    __shared__ float sM[WAVES][16], sL[WAVES][16];
     __shared__ __attribute__((aligned(16))) uint16_t sQ[2][16][HD];
-    const int h = blockIdx.x, j = blockIdx.y;
+    const int h = blockIdx.x;
+    const int j = gridDim.y > 1 ? pv.seq_order[blockIdx.y] : 0; // longest sequences start first
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int qi = lane & 15, grp = lane >> 4;
     const int nq = pv.seq_nq[j], kv0 = pv.seq_kv0[j];
@@ -294,52 +297,54 @@ __global__ __launch_bounds__(AF_WAVES * 64) void attn_fused_kernel(const float *
     uint16_t *K = Kl + ((size_t)h * total_cap + off) * HD;
     uint16_t *Vt = Vtl + ((size_t)h * total_cap + off) * HD; // this sequence's first 32-token tile
     // ---- prologue: slabs -> q, k, v of this head; RoPE; append
-    for (int idx = threadIdx.x; idx < 16 * HALF; idx += AF_WAVES * 64) {
-        const int r = idx / HALF, e = idx % HALF;
-        const int row = j * R + (r < R ? r : 0);
-        const int pos = kv0 + r;
-        bool valid = r < nq && pos < max_pos;
-        if (r < nq && pos >= max_pos && e == 0) atomicOr(cv.status, 8);
-        float q0 = 0.f, q1 = 0.f, k0 = 0.f, k1 = 0.f, v0 = 0.f, v1 = 0.f;
-        if (valid) {
-            const float *base = qkv + (size_t)row * 3 * HDm + h * HD + e;
-            float ld[8][6];
+    {
+        for (int idx = threadIdx.x; idx < 16 * HALF; idx += WAVES * 64) {
+            const int r = idx / HALF, e = idx % HALF;
+            const int row = j * R + (r < R ? r : 0);
+            const int pos = kv0 + r;
+            bool valid = r < nq && pos < max_pos;
+            if (r < nq && pos >= max_pos && e == 0) atomicOr(cv.status, 8);
+            float q0 = 0.f, q1 = 0.f, k0 = 0.f, k1 = 0.f, v0 = 0.f, v1 = 0.f;
+            if (valid) {
+                const float *base = qkv + (size_t)row * 3 * HDm + h * HD + e;
+                float ld[8][6];
 #pragma unroll
-            for (int sl = 0; sl < 8; sl++)
-                if (sl < n_slabs) {
-                    const float *rs = base + (size_t)sl * slab_stride;
-                    ld[sl][0] = rs[0];
-                    ld[sl][1] = rs[HALF];
-                    ld[sl][2] = rs[HDm];
-                    ld[sl][3] = rs[HDm + HALF];
-                    ld[sl][4] = rs[2 * HDm];
-                    ld[sl][5] = rs[2 * HDm + HALF];
-                }
+                for (int sl = 0; sl < 8; sl++)
+                    if (sl < n_slabs) {
+                        const float *rs = base + (size_t)sl * slab_stride;
+                        ld[sl][0] = rs[0];
+                        ld[sl][1] = rs[HALF];
+                        ld[sl][2] = rs[HDm];
+                        ld[sl][3] = rs[HDm + HALF];
+                        ld[sl][4] = rs[2 * HDm];
+                        ld[sl][5] = rs[2 * HDm + HALF];
+                    }
 #pragma unroll
-            for (int sl = 0; sl < 8; sl++)
-                if (sl < n_slabs) {
-                    q0 += ld[sl][0];
-                    q1 += ld[sl][1];
-                    k0 += ld[sl][2];
-                    k1 += ld[sl][3];
-                    v0 += ld[sl][4];
-                    v1 += ld[sl][5];
-                }
-            const float2 cs = rope[(size_t)pos * HALF + e];
-            const float qa = q0 * cs.x - q1 * cs.y, qb = q1 * cs.x + q0 * cs.y;
-            const float ka = k0 * cs.x - k1 * cs.y, kb = k1 * cs.x + k0 * cs.y;
-            q0 = qa;
-            q1 = qb;
-            K[kt_offset(HD, pos, e)] = bf16_bits_rne(ka);
-            K[kt_offset(HD, pos, e + HALF)] = bf16_bits_rne(kb);
-            Vt[vt_offset(HD, pos, e)] = bf16_bits_rne(v0);
-            Vt[vt_offset(HD, pos, e + HALF)] = bf16_bits_rne(v1);
+                for (int sl = 0; sl < 8; sl++)
+                    if (sl < n_slabs) {
+                        q0 += ld[sl][0];
+                        q1 += ld[sl][1];
+                        k0 += ld[sl][2];
+                        k1 += ld[sl][3];
+                        v0 += ld[sl][4];
+                        v1 += ld[sl][5];
+                    }
+                const float2 cs = rope[(size_t)pos * HALF + e];
+                const float qa = q0 * cs.x - q1 * cs.y, qb = q1 * cs.x + q0 * cs.y;
+                const float ka = k0 * cs.x - k1 * cs.y, kb = k1 * cs.x + k0 * cs.y;
+                q0 = qa;
+                q1 = qb;
+                K[kt_offset(HD, pos, e)] = bf16_bits_rne(ka);
+                K[kt_offset(HD, pos, e + HALF)] = bf16_bits_rne(kb);
+                Vt[vt_offset(HD, pos, e)] = bf16_bits_rne(v0);
+                Vt[vt_offset(HD, pos, e + HALF)] = bf16_bits_rne(v1);
+            }
+            const uint16_t h0 = bf16_bits_rne(q0), h1 = bf16_bits_rne(q1);
+            sQ[0][r][e] = h0;
+            sQ[0][r][e + HALF] = h1;
+            sQ[1][r][e] = bf16_bits_rne(q0 - __uint_as_float((uint32_t)h0 << 16));
+            sQ[1][r][e + HALF] = bf16_bits_rne(q1 - __uint_as_float((uint32_t)h1 << 16));
         }
-        const uint16_t h0 = bf16_bits_rne(q0), h1 = bf16_bits_rne(q1);
-        sQ[0][r][e] = h0;
-        sQ[0][r][e + HALF] = h1;
-        sQ[1][r][e] = bf16_bits_rne(q0 - __uint_as_float((uint32_t)h0 << 16));
-        sQ[1][r][e + HALF] = bf16_bits_rne(q1 - __uint_as_float((uint32_t)h1 << 16));
     }
     __syncthreads(); // q in LDS; the new cache rows are visible to this block's later loads
     // the Q^T operand stays in LDS: lane (q, grp) reads Q[q][32*c + 8*grp .. +8] per tile
@@ -351,7 +356,7 @@ __global__ __launch_bounds__(AF_WAVES * 64) void attn_fused_kernel(const float *
     f32x4 o[ND];
 #pragma unroll
     for (int d = 0; d < ND; d++) o[d] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    attn_tiles<HD, true>(K, Vt, total_cap, qv, ql, vis, wave, n_tiles, AF_WAVES, m_run, l_run, o);
+    attn_tiles<HD, true>(K, Vt, total_cap, qv, ql, vis, wave, n_tiles, WAVES, m_run, l_run, o);
     l_run += __shfl_xor(l_run, 16, 64);
     l_run += __shfl_xor(l_run, 32, 64);
     // ---- merge: every wave leaves its (max, sum, O) in LDS; after one barrier the block combines them
@@ -365,17 +370,17 @@ __global__ __launch_bounds__(AF_WAVES * 64) void attn_fused_kernel(const float *
     }
     __syncthreads();
     // one thread per (d tile, lane slot): four consecutive head dimensions of one query row
-    for (int e = threadIdx.x; e < ND * 64; e += AF_WAVES * 64) {
+    for (int e = threadIdx.x; e < ND * 64; e += WAVES * 64) {
         const int d = e >> 6, slot = e & 63;
         const int q = slot & 15, dim = 16 * d + 4 * (slot >> 4);
         if (q >= R) continue;
         float M = AT_NEG;
 #pragma unroll
-        for (int w = 0; w < AF_WAVES; w++) M = fmaxf(M, sM[w][q]);
+        for (int w = 0; w < WAVES; w++) M = fmaxf(M, sM[w][q]);
         f32x4 O = {0.f, 0.f, 0.f, 0.f};
         float L = 0.f;
 #pragma unroll
-        for (int w = 0; w < AF_WAVES; w++) {
+        for (int w = 0; w < WAVES; w++) {
             const float f = fast_exp(sM[w][q] - M);
             const f32x4 p = *(const f32x4 *)&sO[w][d][slot][0];
             O += p * f;
@@ -395,6 +400,8 @@ __global__ __launch_bounds__(AF_WAVES * 64) void attn_fused_kernel(const float *
     }
 }
 
+int g_force_attn_waves = 0;
+
 // Returns hipErrorNotSupported when the split path (RoPE kernel + split attention + combine) should run.
 hipError_t launch_attn_fused_bf16(hipStream_t s, const float *qkv, int n_slabs, size_t slab_stride, PlanView pv,
                                   CtxView cv, int R, int n_seq, int H, int hd, const float2 *rope, int max_pos,
@@ -405,14 +412,22 @@ hipError_t launch_attn_fused_bf16(hipStream_t s, const float *qkv, int n_slabs, 
     const int tiles_upper = (len_upper + AT_TILE - 1) / AT_TILE;
     // one block per (sequence, head): fine when those alone fill the chip, or when every wave has
     // at most a few tiles anyway
-    if (!((long)n_seq * H >= 512 || tiles_upper <= 6 * AF_WAVES)) return hipErrorNotSupported;
-    dim3 grid(H, n_seq), block(AF_WAVES * 64);
-    if (hd == 128)
-        hipLaunchKernelGGL(attn_fused_kernel<128>, grid, block, 0, s, qkv, n_slabs, slab_stride, pv, cv, R, H, rope,
-                           max_pos, (uint16_t *)Kl, (uint16_t *)Vtl, total_cap, (uint16_t *)obuf, o_av);
-    else
-        hipLaunchKernelGGL(attn_fused_kernel<64>, grid, block, 0, s, qkv, n_slabs, slab_stride, pv, cv, R, H, rope,
-                           max_pos, (uint16_t *)Kl, (uint16_t *)Vtl, total_cap, (uint16_t *)obuf, o_av);
+    if (!((long)n_seq * H >= 512 || tiles_upper <= 48)) return hipErrorNotSupported;
+    // with more than two blocks per compute unit the 4-wave shape (two resident blocks per unit) hides
+    // each block's prologue and merge behind its neighbour's streaming
+    const bool many = g_force_attn_waves ? g_force_attn_waves == 4 : (long)n_seq * H >= 512;
+    dim3 grid(H, n_seq), block(many ? 256 : 512);
+#define SD_FUSED(HD_, WAVES_)                                                                                          \
+    hipLaunchKernelGGL((attn_fused_kernel<HD_, WAVES_>), grid, block, 0, s, qkv, n_slabs, slab_stride, pv, cv, R, H,   \
+                       rope, max_pos, (uint16_t *)Kl, (uint16_t *)Vtl, total_cap, (uint16_t *)obuf, o_av)
+    if (hd == 128) {
+        if (many) SD_FUSED(128, 4);
+        else SD_FUSED(128, 8);
+    } else {
+        if (many) SD_FUSED(64, 4);
+        else SD_FUSED(64, 8);
+    }
+#undef SD_FUSED
     return hipGetLastError();
 }
 

@@ -97,9 +97,13 @@ __device__ float block_excl_scan(float v, float *scratch)
 // ---------------------------------------------------------------- row plan
 // Builds the row list of one forward from the device-resident sequence state and
 // advances the model's cache length.  One thread per selected sequence.
+#define PLAN_THREADS 256
 __global__ void plan_kernel(int mode, int R, int n_seq, const int32_t *seq_ids, CtxView cv, int slot, int upto_off,
                             const int32_t *cand, int gamma, int cand_idx, int vocab, PlanView pv)
 {
+    __shared__ int s_len[PLAN_THREADS]; // cache length after this forward, per sequence slot (single-block launches)
+    if (threadIdx.x < PLAN_THREADS) s_len[threadIdx.x] = -1;
+    __syncthreads();
     for (int j = blockIdx.x * blockDim.x + threadIdx.x; j < n_seq; j += gridDim.x * blockDim.x) {
         int b = seq_ids ? seq_ids[j] : j;
         if (b < 0 || b >= cv.B) { // refuse out-of-range ids: mark every row unused
@@ -107,6 +111,8 @@ __global__ void plan_kernel(int mode, int R, int n_seq, const int32_t *seq_ids, 
             pv.seq_b[j] = 0;
             pv.seq_kv0[j] = 0;
             pv.seq_nq[j] = 0;
+            if (gridDim.x > 1 || n_seq == 1) pv.seq_order[j] = j;
+            else s_len[j] = 0;
             for (int r = 0; r < R; r++) {
                 pv.row_tok[j * R + r] = 0;
                 pv.row_pos[j * R + r] = 0;
@@ -163,6 +169,8 @@ __global__ void plan_kernel(int mode, int R, int n_seq, const int32_t *seq_ids, 
         pv.seq_b[j] = b;
         pv.seq_kv0[j] = kv0;
         pv.seq_nq[j] = nq;
+        if (gridDim.x > 1 || n_seq == 1) pv.seq_order[j] = j;
+        else s_len[j] = nq > 0 ? kv0 + nq : 0;
         if (mode == PLAN_VERIFY) {
             for (int r = 0; r < R; r++) pv.lm_row[j * R + r] = j * R + r;
         } else {
@@ -170,12 +178,24 @@ __global__ void plan_kernel(int mode, int R, int n_seq, const int32_t *seq_ids, 
         }
         *kvp = kv0 + nq;
     }
+    // Longest sequences first: attention blocks start in seq_order, so the blocks still running when the
+    // grid drains are the short ones.  (A launch of several blocks wrote the identity order above.)
+    if (gridDim.x == 1 && n_seq > 1) {
+        __syncthreads();
+        const int j = threadIdx.x;
+        if (j < n_seq) {
+            const int mine = s_len[j];
+            int rank = 0;
+            for (int i = 0; i < n_seq; i++) rank += (s_len[i] > mine) || (s_len[i] == mine && i < j);
+            pv.seq_order[rank] = j;
+        }
+    }
 }
 
 hipError_t launch_plan(hipStream_t s, int mode, int R, int n_seq, const int32_t *seq_ids, CtxView cv, int slot,
                        int upto_off, const int32_t *cand, int gamma, int cand_idx, int vocab, PlanView pv)
 {
-    int threads = 256, blocks = (n_seq + threads - 1) / threads;
+    int threads = PLAN_THREADS, blocks = (n_seq + threads - 1) / threads;
     hipLaunchKernelGGL(plan_kernel, dim3(blocks), dim3(threads), 0, s, mode, R, n_seq, seq_ids, cv, slot, upto_off,
                        cand, gamma, cand_idx, vocab, pv);
     return hipGetLastError();

@@ -103,6 +103,11 @@ extern "C" int sd_set_option(const char *name, int32_t value)
         g_force_splits[mode] = ks;
         return SD_OK;
     }
+    if (!strcmp(name, "attn_waves")) { // waves per block of the fused attention kernel: 4, 8, or 0 = automatic
+        if (value != 0 && value != 4 && value != 8) return sd_fail(SD_EINVAL, "sd_set_option: attn_waves is 0, 4 or 8");
+        g_force_attn_waves = value;
+        return SD_OK;
+    }
     if (!strcmp(name, "profile")) { // 1: start a fresh measurement, 0: stop recording (totals stay readable)
         prof_fold();
         if (value) {
@@ -219,7 +224,7 @@ extern "C" int sd_load_model(const sd_model_config *cfg, const sd_weights *w, sd
     alloc((void **)&m->gpart_q, m->gpart_q_floats * 4);
     alloc((void **)&m->gpart_r, m->gpart_r_floats * 4);
     alloc((void **)&m->rope, (size_t)c.max_pos * (c.head_dim / 2) * sizeof(float2));
-    alloc((void **)&m->plan_mem, (5 * M + 3 * M) * sizeof(int32_t));
+    alloc((void **)&m->plan_mem, (5 * M + 4 * M) * sizeof(int32_t));
     if (e != hipSuccess) {
         sd_free_model(m);
         return sd_fail(SD_EHIP, std::string("sd_load_model: hipMalloc: ") + hipGetErrorString(e));
@@ -233,6 +238,7 @@ extern "C" int sd_load_model(const sd_model_config *cfg, const sd_weights *w, sd
     m->plan.seq_b = pm + 5 * M;
     m->plan.seq_kv0 = pm + 6 * M;
     m->plan.seq_nq = pm + 7 * M;
+    m->plan.seq_order = pm + 8 * M;
     // rotary table in double on the host: angle = pos * base^(-2i/hd)
     int half = c.head_dim / 2;
     std::vector<float2> tab((size_t)c.max_pos * half);
@@ -480,7 +486,8 @@ extern "C" int64_t sd_debug_layout_index(int32_t kind, int64_t a, int64_t b, int
 }
 
 // Test hook: copy one workspace buffer of the last forward to the host as fp32.
-// name: "x" [rows][d], "qkv" [rows][3d], "q"/"o"/"a" [rows][d] (hi + lo summed), "act" [rows][d_ffn].
+// name: "x" [rows][d], "qkv" [rows][3d], "q"/"o"/"a" [rows][d] (hi + lo summed), "act" [rows][d_ffn];
+// "seq_order" / "seq_len" [rows]: the last plan's block order and cache lengths (rows = sequences).
 extern "C" int sd_debug_read(sd_model *m, const char *name, float *out_host, int32_t rows)
 {
     if (!m || !name || !out_host || rows < 0 || rows > m->cfg.max_rows) return sd_fail(SD_EINVAL, "sd_debug_read: bad argument");
@@ -489,6 +496,14 @@ extern "C" int sd_debug_read(sd_model *m, const char *name, float *out_host, int
     if (!strcmp(name, "x") || !strcmp(name, "qkv")) {
         size_t w = !strcmp(name, "x") ? d : 3 * d;
         SD_HIP(hipMemcpy(out_host, !strcmp(name, "x") ? m->x : m->qkv, rows * w * 4, hipMemcpyDeviceToHost));
+        return SD_OK;
+    }
+    if (!strcmp(name, "seq_order") || !strcmp(name, "seq_len")) { // per sequence slot of the last plan, as floats
+        std::vector<int32_t> a(rows), b(rows);
+        const bool order = !strcmp(name, "seq_order");
+        SD_HIP(hipMemcpy(a.data(), order ? m->plan.seq_order : m->plan.seq_kv0, rows * 4, hipMemcpyDeviceToHost));
+        SD_HIP(hipMemcpy(b.data(), m->plan.seq_nq, rows * 4, hipMemcpyDeviceToHost));
+        for (int r = 0; r < rows; r++) out_host[r] = order ? (float)a[r] : (float)(b[r] > 0 ? a[r] + b[r] : 0);
         return SD_OK;
     }
     const void *src = nullptr;

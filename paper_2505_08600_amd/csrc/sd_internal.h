@@ -134,6 +134,7 @@ struct PlanView {
     int32_t *seq_b;     // [n_seq]
     int32_t *seq_kv0;   // [n_seq] cache length before this forward
     int32_t *seq_nq;    // [n_seq] valid rows of this sequence
+    int32_t *seq_order; // [n_seq] sequence slots by decreasing cache length: the order attention blocks start in
     int32_t *lm_row;    // [n_lm] source row of each logits row
 };
 
@@ -237,6 +238,7 @@ int sd_fail(int code, const std::string &s);
     } while (0)
 
 extern int g_force_generic;
+extern int g_force_attn_waves; // fused attention block shape forced by option "attn_waves" (0 = automatic)
 extern int g_force_splits[3]; // per GEMM mode: K splits forced by option "gemm_splits" (0 = automatic)
 
 // ---------------------------------------------------------------- kernel launchers

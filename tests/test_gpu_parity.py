@@ -176,6 +176,11 @@ def test_small_bf16_every_gemm_row_class_matches_reference_kernels(B):
             api.sd_verify(gt, ctx, None, B, 5, 0.0, cand, None, None, na, nx, commit=False)
             ctx.sync()
             outs.append((gt.last_logits().cpu().numpy(), na.cpu().numpy().copy(), nx.cpu().numpy().copy()))
+            if force == 0:  # attention blocks start longest sequence first (ties: lower slot first)
+                order = gt.debug_read("seq_order", B)[:, 0].astype(int)
+                ln = gt.debug_read("seq_len", B)[:, 0].astype(int)
+                assert (ln == lens - 1 + 6).all()
+                assert order.tolist() == sorted(range(B), key=lambda b: (-ln[b], b))
             ctx.close()
         finally:
             api.set_option("force_generic", 0)
@@ -183,6 +188,42 @@ def test_small_bf16_every_gemm_row_class_matches_reference_kernels(B):
     _say(f"  rel diff {rel:.2e}")
     assert outs[0][0].shape == (6 * B, st_.vocab) and np.isfinite(outs[0][0]).all()
     assert rel < 2e-3
+    gt.close()
+
+
+@pytest.mark.parametrize("waves", [4, 8])
+def test_small_bf16_both_fused_attention_block_shapes_match_reference_kernels(waves):
+    """The fused attention kernel runs as 8-wave blocks (few sequences) or 4-wave blocks (many); the
+    library picks by batch size, so each shape is forced here on the same ragged batch and compared with
+    the reference kernels."""
+    _say(f"small bf16: fused attention forced to {waves}-wave blocks vs reference kernels")
+    st_ = dg.SHAPES["small_target_bf16"]
+    w = dg.make_weights(st_, 65, BF16_LM_SCALE)
+    B = 6
+    gt = api.Model(st_, w, max_rows=6 * B, max_pos=256)
+    lens = dg.make_prompt_lengths(70, B, 5, 200)
+    prompts = [[int(t) for t in dg.make_prompt(65, b, int(lens[b]), st_.vocab)] for b in range(B)]
+    cand = H.dev(dg.make_prompt(66, B, 5 * B, st_.vocab).reshape(B, 5).astype(np.int32))
+    outs = []
+    for force in (0, 1):
+        api.set_option("force_generic", force)
+        api.set_option("attn_waves", 0 if force else waves)
+        try:
+            ctx = api.Context([int(l) + 16 for l in lens])
+            ctx.attach(gt)
+            H.gpu_prefill(ctx, [gt], prompts)
+            na = torch.zeros(B, dtype=torch.int32, device="cuda")
+            nx = torch.zeros(B, dtype=torch.int32, device="cuda")
+            api.sd_verify(gt, ctx, None, B, 5, 0.0, cand, None, None, na, nx, commit=False)
+            ctx.sync()
+            outs.append(gt.last_logits().cpu().numpy())
+            ctx.close()
+        finally:
+            api.set_option("force_generic", 0)
+            api.set_option("attn_waves", 0)
+    rel = np.abs(outs[0] - outs[1]).max() / np.abs(outs[1]).max()
+    _say(f"  rel diff {rel:.2e}")
+    assert np.isfinite(outs[0]).all() and rel < 2e-3
     gt.close()
 
 
