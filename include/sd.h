@@ -210,6 +210,8 @@ int64_t sd_debug_layout_index(int32_t kind, int64_t a, int64_t b, int64_t c, int
  * events on its stream (a measurement mode: it adds event overhead), 0 stops.
  * option "gemm_splits" = mode*100 + s forces s K splits (1..8; 0 = automatic) for
  * the bf16 GEMMs of mode 0 (plain / residual) or 2 (SwiGLU, ignored): a tuning knob.
+ * option "gemm_tile_cols" = 192 or 256 forces the block width (in weight rows) of the
+ * row-blocked GEMM for more than 64 rows where the shape allows it (0 = automatic).
  * option "attn_waves" = 4 or 8 forces the block shape of the fused attention kernel
  * (0 = automatic: 4-wave blocks once (sequence, head) pairs oversubscribe the chip).
  * Unknown names and out-of-range values return SD_EINVAL. */

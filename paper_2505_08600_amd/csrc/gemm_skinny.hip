@@ -39,8 +39,10 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 #define GS_PAD 8 // row padding in LDS (16 bytes): operand rows fall into distinct banks
 
 // Row-blocked GEMM for M > 32 (batched verify, prefill chunks of many sequences).
-// MODE: GEMM_STORE (C = acc, or partial sums when grid.y > 1) / GEMM_SWIGLU (tiles 2j, 2j+1 of a wave are
-// the gate and up tile of the same columns).  A block owns BM rows (hi plane in operand rows 0..BM-1, lo
+// MODE: GEMM_STORE (C = acc, or partial sums when grid.y > 1) / GEMM_SWIGLU (the block's WAVES * NT tiles are,
+// alternately, the gate and the up tile of WAVES * NT / 2 groups of 16 output columns; tile q belongs to wave
+// q / NT, so with an odd NT every second pair straddles two waves and the gate accumulators change wave
+// through LDS before the epilogue; a last block may hold fewer pairs than the others).  A block owns BM rows (hi plane in operand rows 0..BM-1, lo
 // plane in BM..2BM-1 of the staged chunk) and WAVES * NT 16-column weight tiles; every wave keeps its NT
 // weight fragments of a 128-element K step in registers (loaded straight from the tiled weights, two steps
 // in flight) and all waves share the activation chunk, staged once per block in LDS (double buffered).
@@ -64,8 +66,12 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_tile_kernel(const uint16_t *A
     constexpr int NVEC = OPROWS * VEC_PER_ROW;
     constexpr int LPT = NVEC / THREADS;
     static_assert(NVEC % THREADS == 0, "staging must divide evenly");
-    constexpr int COLS = (MODE == GEMM_SWIGLU ? NT / 2 : NT) * 16 * WAVES;
+    constexpr bool SW = MODE == GEMM_SWIGLU;
+    constexpr bool XCH = SW && (NT & 1); // gate/up pairs straddle waves
+    static_assert(!SW || (NT * WAVES) % 2 == 0, "gate and up tiles come in pairs");
+    constexpr int COLS = SW ? NT * WAVES * 8 : NT * 16 * WAVES; // output columns of a block
     __shared__ __attribute__((aligned(16))) uint16_t sA[2][OPROWS][LDROW];
+    __shared__ f32x4 xch[XCH ? WAVES * MT * 64 : 1];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int row = lane & 15, grp = lane >> 4;
     const int r8 = blockIdx.x >> 3;
@@ -80,11 +86,14 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_tile_kernel(const uint16_t *A
     // this lane's 16 bytes inside the first K step of each of the wave's weight tiles
     const size_t tile_elems = (size_t)(K >> 7) * 2048;
     const uint16_t *Wp[NT];
-    if (MODE == GEMM_SWIGLU) {
+    if (SW) {
+        const int last_pair = N / 16 - 1; // pairs past the end (last block) re-read the last one; never stored
 #pragma unroll
-        for (int c = 0; c < NT; c++)
-            Wp[c] = (const uint16_t *)w.p[c & 1] + (size_t)(n0 / 16 + wave * (NT / 2) + (c >> 1)) * tile_elems +
+        for (int c = 0; c < NT; c++) {
+            const int q = wave * NT + c;
+            Wp[c] = (const uint16_t *)w.p[q & 1] + (size_t)min(n0 / 16 + (q >> 1), last_pair) * tile_elems +
                     (size_t)(kb >> 7) * 2048 + lane * 8;
+        }
     } else {
         const int seg_tiles = w.n_per_seg / 16; // a block's tiles may lie in different segments (q | k | v)
 #pragma unroll
@@ -206,18 +215,36 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_tile_kernel(const uint16_t *A
     }
 k_done:
     // epilogue: lane (m' = row, grp) holds D[n = 4*grp + r][m'] of each of its tiles
+    f32x4 gin[MT]; // gate accumulators of the pair whose up tile is this wave's first tile
+#pragma unroll
+    for (int t = 0; t < MT; t++) gin[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    if (XCH) { // every wave passed the loop's last barrier: sA and xch are free
+        if (((wave * NT + NT - 1) & 1) == 0) {
+#pragma unroll
+            for (int t = 0; t < MT; t++) xch[(wave * MT + t) * 64 + lane] = acc[NT - 1][t];
+        }
+        __syncthreads();
+        if ((wave * NT) & 1) {
+#pragma unroll
+            for (int t = 0; t < MT; t++) gin[t] = xch[((wave - 1) * MT + t) * 64 + lane];
+        }
+    }
 #pragma unroll
     for (int t = 0; t < MT; t++) {
         const int m = m0 + t * 16 + row;
         if (m >= M) continue;
-        if (MODE == GEMM_SWIGLU) {
+        if (SW) {
 #pragma unroll
-            for (int j = 0; j < NT / 2; j++) {
-                const size_t o = act_index(c_av, m, n0 + (wave * (NT / 2) + j) * 16 + 4 * grp, N);
+            for (int c = 0; c < NT; c++) { // the wave that holds a pair's up tile writes the pair
+                const int q = wave * NT + c;
+                const int n = n0 + (q >> 1) * 16;
+                if (!(q & 1) || n >= N) continue;
+                const f32x4 g = c > 0 ? acc[c > 0 ? c - 1 : 0][t] : gin[t];
+                const size_t o = act_index(c_av, m, n + 4 * grp, N);
 #pragma unroll
                 for (int r = 0; r < 4; r++) {
-                    const float g0 = acc[2 * j][t][r];
-                    const float y = g0 / (1.0f + expf(-g0)) * acc[2 * j + 1][t][r];
+                    const float g0 = g[r];
+                    const float y = g0 / (1.0f + expf(-g0)) * acc[c][t][r];
                     const uint16_t hi = bf16_bits_rne(y);
                     Cact[o + r] = hi;
                     Cact[c_av.plane + o + r] = bf16_bits_rne(y - __uint_as_float((uint32_t)hi << 16));
@@ -383,6 +410,7 @@ static int one_round_splits(int blocks, int slots, int steps)
     while (ks < 8 && blocks * (ks + 1) <= slots && (steps + ks) / (ks + 1) >= 4) ks++;
     return ks;
 }
+int g_force_tile_cols = 0; // weight rows per 96-row block forced by option "gemm_tile_cols" (0 = automatic)
 static TileShape tile_shape(int mode, int M, int N, int n_per_seg, int K)
 {
     const int out_per_col = mode == GEMM_SWIGLU ? 2 : 1; // weight rows per output column
@@ -391,16 +419,19 @@ static TileShape tile_shape(int mode, int M, int N, int n_per_seg, int K)
     if (M > 64) {
         const int nmb = (M + 95) / 96, steps = K / 128;
         const bool ok256 = rows_w % 256 == 0 && (mode == GEMM_SWIGLU || n_per_seg % 256 == 0);
-        const bool ok192 = mode == GEMM_STORE && rows_w % 192 == 0 && n_per_seg % 16 == 0;
+        // (SwiGLU blocks of 192 weight rows = 96 output columns may end in a partial block)
+        const bool ok192 = mode == GEMM_SWIGLU || (rows_w % 192 == 0 && n_per_seg % 16 == 0);
         auto fill = [&](int cols) { // fraction of the 256 units busy, averaged over the rounds of blocks
-            const int blocks = rows_w / cols * nmb;
-            const int tot = blocks * one_round_splits(blocks, 256, steps);
+            const int blocks = (rows_w + cols - 1) / cols * nmb;
+            const int tot = blocks * (mode == GEMM_SWIGLU ? 1 : one_round_splits(blocks, 256, steps));
             return (float)tot / (256.f * (float)((tot + 255) / 256));
         };
         int cols = 0;
         if (ok256) cols = 256;
         if (ok192 && (!ok256 || fill(192) > fill(256) + 0.1f)) cols = 192;
-        if (cols) return TileShape{cols, 96, rows_w / cols * nmb, 256};
+        if (g_force_tile_cols == 256 && ok256) cols = 256;
+        if (g_force_tile_cols == 192 && ok192) cols = 192;
+        if (cols) return TileShape{cols, 96, (rows_w + cols - 1) / cols * nmb, 256};
     }
     if (rows_w % 128 == 0 && (mode == GEMM_SWIGLU || n_per_seg % 128 == 0))
         t = TileShape{128, 48, rows_w / 128 * ((M + 47) / 48), 512};
@@ -416,15 +447,14 @@ static hipError_t tile_launch(hipStream_t s, const uint16_t *a, ActView a_av, We
     const TileShape t = tile_shape(MODE, M, N, w.n_per_seg, K);
     if (!t.cols) return hipErrorNotSupported;
     constexpr int OUT_PER_COL = MODE == GEMM_SWIGLU ? 2 : 1;
-    const int ntiles = N * OUT_PER_COL / t.cols, nmb = (M + t.bm - 1) / t.bm;
+    const int ntiles = (N * OUT_PER_COL + t.cols - 1) / t.cols, nmb = (M + t.bm - 1) / t.bm;
     const int gx = ((ntiles + 7) / 8) * 8 * nmb;
 #define SD_TILE(BM, KC, NT, WAVES, NB)                                                                              \
     hipLaunchKernelGGL((gemm_tile_kernel<MODE, BM, KC, NT, WAVES, NB>), dim3(gx, ny), dim3(WAVES * 64), 0, s, a, a_av, w, \
                        M, N, K, kps, nmb, ntiles, C, c_split_stride, ca, c_av)
     if (t.cols == 256) SD_TILE(96, 64, 4, 4, 3);
-    else if (t.cols == 192) {
-        if constexpr (MODE == GEMM_STORE) SD_TILE(96, 64, 3, 4, 3);
-    } else SD_TILE(48, 128, 4, 2, 3);
+    else if (t.cols == 192) SD_TILE(96, 64, 3, 4, 3);
+    else SD_TILE(48, 128, 4, 2, 3);
     return hipGetLastError();
 }
 

@@ -238,6 +238,7 @@ int sd_fail(int code, const std::string &s);
     } while (0)
 
 extern int g_force_generic;
+extern int g_force_tile_cols;  // 96-row GEMM block width forced by option "gemm_tile_cols" (0 = automatic)
 extern int g_force_attn_waves; // fused attention block shape forced by option "attn_waves" (0 = automatic)
 extern int g_force_splits[3]; // per GEMM mode: K splits forced by option "gemm_splits" (0 = automatic)
 

@@ -191,6 +191,43 @@ def test_small_bf16_every_gemm_row_class_matches_reference_kernels(B):
     gt.close()
 
 
+@pytest.mark.parametrize("cols,B", [(192, 16), (192, 30), (256, 30)])
+def test_small_bf16_row_blocked_gemm_block_widths_match_reference_kernels(cols, B):
+    """The 96-row GEMM blocks are 256 or 192 weight rows wide; the library picks by how well the blocks fill
+    the chip, so each width is forced here.  d_ffn = 896 gives the 192-row SwiGLU blocks (96 output
+    columns, gate/up pairs straddling waves) a partial last block: 896 = 9 * 96 + 32."""
+    import dataclasses
+    _say(f"small bf16: 96-row GEMM blocks forced to {cols} weight rows, batch {B}, d_ffn 896")
+    st_ = dataclasses.replace(dg.SHAPES["small_target_bf16"], d_ffn=896, name="small_target_bf16_f896")
+    w = dg.make_weights(st_, 67, BF16_LM_SCALE)
+    gt = api.Model(st_, w, max_rows=6 * B, max_pos=256)
+    lens = dg.make_prompt_lengths(71 + B, B, 5, 90)
+    prompts = [[int(t) for t in dg.make_prompt(67, b, int(lens[b]), st_.vocab)] for b in range(B)]
+    cand = H.dev(dg.make_prompt(68, B, 5 * B, st_.vocab).reshape(B, 5).astype(np.int32))
+    outs = []
+    for force in (0, 1):
+        api.set_option("force_generic", force)
+        api.set_option("gemm_tile_cols", 0 if force else cols)
+        try:
+            ctx = api.Context([int(l) + 16 for l in lens])
+            ctx.attach(gt)
+            H.gpu_prefill(ctx, [gt], prompts)
+            na = torch.zeros(B, dtype=torch.int32, device="cuda")
+            nx = torch.zeros(B, dtype=torch.int32, device="cuda")
+            api.sd_verify(gt, ctx, None, B, 5, 0.0, cand, None, None, na, nx, commit=False)
+            ctx.sync()
+            outs.append((gt.last_logits().cpu().numpy(), gt.debug_read("act", 6 * B)))
+            ctx.close()
+        finally:
+            api.set_option("force_generic", 0)
+            api.set_option("gemm_tile_cols", 0)
+    rel = np.abs(outs[0][0] - outs[1][0]).max() / np.abs(outs[1][0]).max()
+    rel_act = np.abs(outs[0][1] - outs[1][1]).max() / np.abs(outs[1][1]).max()
+    _say(f"  rel diff logits {rel:.2e}, SwiGLU output of the last layer {rel_act:.2e}")
+    assert np.isfinite(outs[0][0]).all() and rel < 2e-3 and rel_act < 2e-3
+    gt.close()
+
+
 @pytest.mark.parametrize("waves", [4, 8])
 def test_small_bf16_both_fused_attention_block_shapes_match_reference_kernels(waves):
     """The fused attention kernel runs as 8-wave blocks (few sequences) or 4-wave blocks (many); the
