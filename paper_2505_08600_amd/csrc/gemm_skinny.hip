@@ -218,7 +218,7 @@ k_done:
     f32x4 gin[MT]; // gate accumulators of the pair whose up tile is this wave's first tile
 #pragma unroll
     for (int t = 0; t < MT; t++) gin[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    if (XCH) { // every wave passed the loop's last barrier: sA and xch are free
+    if (XCH) { // xch is used nowhere else; every wave is past the loop's last barrier
         if (((wave * NT + NT - 1) & 1) == 0) {
 #pragma unroll
             for (int t = 0; t < MT; t++) xch[(wave * MT + t) * 64 + lane] = acc[NT - 1][t];
@@ -395,7 +395,8 @@ __global__ __launch_bounds__(256) void gemm_ksplit_kernel(const uint16_t *__rest
 // Block shapes of the row-blocked kernel.  More than 64 rows: 96 rows x 256 columns (4 waves x 4 tiles; chunks
 // of half a K step) - the bytes a block pulls through L2 per MFMA halve against 48 x 128, which is what
 // bounds these GEMMs - or x 192 columns (3 tiles per wave) where that fills the 256 compute units better
-// (QKV at M = 192: 128 blocks x 2 K splits instead of 96 x 2).  Up to 64 rows: 48-row blocks of 2 waves x
+// (QKV at M = 192: 128 blocks x 2 K splits instead of 96 x 2); 64-row blocks of the same widths where they
+// pad M less (M = 128).  Up to 64 rows: 48-row blocks of 2 waves x
 // 128 columns, two resident per unit.  A block of the 96-row shapes has a compute unit to itself
 // (~500 registers per wave), so the K splits are chosen to cover the chip in one round of blocks.
 struct TileShape {
@@ -431,7 +432,15 @@ static TileShape tile_shape(int mode, int M, int N, int n_per_seg, int K)
         if (ok192 && (!ok256 || fill(192) > fill(256) + 0.1f)) cols = 192;
         if (g_force_tile_cols == 256 && ok256) cols = 256;
         if (g_force_tile_cols == 192 && ok192) cols = 192;
-        if (cols) return TileShape{cols, 96, (rows_w + cols - 1) / cols * nmb, 256};
+        if (cols) {
+            // 64-row blocks when they pad M less (M = 128: 2 x 64 instead of 96 + 32) and do not cost more rounds
+            const int ncol = (rows_w + cols - 1) / cols, nmb64 = (M + 63) / 64;
+            auto rounds = [&](int blocks) {
+                return (blocks * (mode == GEMM_SWIGLU ? 1 : one_round_splits(blocks, 256, steps)) + 255) / 256;
+            };
+            const bool use64 = nmb64 * 64 < nmb * 96 && rounds(ncol * nmb64) * 64 <= rounds(ncol * nmb) * 96;
+            return use64 ? TileShape{cols, 64, ncol * nmb64, 256} : TileShape{cols, 96, ncol * nmb, 256};
+        }
     }
     if (rows_w % 128 == 0 && (mode == GEMM_SWIGLU || n_per_seg % 128 == 0))
         t = TileShape{128, 48, rows_w / 128 * ((M + 47) / 48), 512};
@@ -452,8 +461,10 @@ static hipError_t tile_launch(hipStream_t s, const uint16_t *a, ActView a_av, We
 #define SD_TILE(BM, KC, NT, WAVES, NB)                                                                              \
     hipLaunchKernelGGL((gemm_tile_kernel<MODE, BM, KC, NT, WAVES, NB>), dim3(gx, ny), dim3(WAVES * 64), 0, s, a, a_av, w, \
                        M, N, K, kps, nmb, ntiles, C, c_split_stride, ca, c_av)
-    if (t.cols == 256) SD_TILE(96, 64, 4, 4, 3);
-    else if (t.cols == 192) SD_TILE(96, 64, 3, 4, 3);
+    if (t.cols == 256 && t.bm == 96) SD_TILE(96, 64, 4, 4, 3);
+    else if (t.cols == 192 && t.bm == 96) SD_TILE(96, 64, 3, 4, 3);
+    else if (t.cols == 256) SD_TILE(64, 64, 4, 4, 3);
+    else if (t.cols == 192) SD_TILE(64, 64, 3, 4, 3);
     else SD_TILE(48, 128, 4, 2, 3);
     return hipGetLastError();
 }
