@@ -381,19 +381,41 @@ def test_batched_sequences_with_seq_ids(tiny_pair):
     ctx.close()
 
 
-@pytest.mark.parametrize("rho", [0.0, 0.5, 0.9])
-def test_verify_tail_full_vocabulary_synthetic_q(rho):
+@pytest.mark.parametrize("rho,vocab", [(0.0, 32000), (0.5, 32000), (0.9, 32000), (0.5, 50000)])
+def test_verify_tail_full_vocabulary_synthetic_q(rho, vocab):
     """Config-5 style stress of the fused softmax/accept/residual/resample kernel at the
     real vocabulary (32000) in fp32, where logits agree to ~1e-7 and every decision must
     match the oracle to the 1e-5 base threshold: batch of 8 ragged sequences, gamma = 8,
     draft distributions q = softmax(rho * target logits + (1 - rho) * 4 * N(0,1)), candidates
-    drawn from q, built position by position with the oracle only."""
-    _say(f"verify tail, V=32000, rho={rho}")
-    shape = dg.ModelShape("wide_vocab_fp32", 1, 64, 1, 64, 128, 32000, dg.FP32)
+    drawn from q, built position by position with the oracle only.  A vocabulary of 50000 does
+    not fit the register-resident row kernels (32768 entries) and takes the strided ones, in the
+    verify tail and in the draft's sampling (checked here too, with the model drafting for itself)."""
+    _say(f"verify tail, V={vocab}, rho={rho}")
+    shape = dg.ModelShape("wide_vocab_fp32", 1, 64, 1, 64, 128, vocab, dg.FP32)
     w = dg.make_weights(shape, 71, lm_head_scale=20.0)   # logit std 0.02*20*8 = 3.2
     om = oracle.OracleModel(shape, w)
     gm = api.Model(shape, w, max_rows=72, max_pos=128)
     B, gamma, T, V = 8, 8, 1.0, shape.vocab
+    if vocab > 32768:   # the draft's sampling kernel on the same wide rows
+        pr = [dg.make_prompt(72, b, 5 + 7 * b, V) for b in range(3)]
+        c2 = api.Context([64] * 3)
+        c2.attach(gm)
+        H.gpu_prefill(c2, [gm], [list(p) for p in pr])
+        ud = np.stack([dg.make_uniforms(72, dg.DRAFT_STREAM, b, 0, 4) for b in range(3)])
+        cand_g = torch.zeros((3, 4), dtype=torch.int32, device="cuda")
+        q_g = torch.zeros((3, 4, V), dtype=torch.float32, device="cuda")
+        api.sd_draft(gm, c2, None, 3, 4, T, H.dev(ud), cand_g, q_g)
+        for b in range(3):
+            seq = om.new_seq(64)
+            oracle.prefill(seq, [int(t) for t in pr[b]])
+            r_c, r_q, mg = seq.draft([int(t) for t in pr[b]], 4, T, ud[b])
+            got = cand_g[b].cpu().numpy()
+            if not np.array_equal(got, r_c):   # only a draw within 1e-5 of a CDF step may differ
+                k = int(np.argmax(got != r_c))
+                assert mg[k] < 1e-5, (b, got, r_c, mg)
+            else:
+                assert np.abs(q_g[b].cpu().numpy() - r_q).max() < 1e-6
+        c2.close()
     lens = dg.make_prompt_lengths(71, B, 3, 40)
     prompts = [dg.make_prompt(71, b, int(lens[b]), V) for b in range(B)]
     cands, qs, us, refs = [], [], [], []
