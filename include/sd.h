@@ -27,7 +27,8 @@
  *   - a model owns one activation workspace: at most one forward of a given model
  *     may be in flight at a time (calls on one stream are naturally ordered).
  *   - seq_ids (dev, int32[n_seq], or NULL for 0..n_seq-1) selects the sequences of
- *     the context a call works on; ids must be distinct.
+ *     the context a call works on; ids must be distinct.  1 <= n_seq <= the context's
+ *     sequence count: an empty batch is SD_EINVAL, not a no-op.
  */
 #ifndef SD_H
 #define SD_H

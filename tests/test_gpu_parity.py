@@ -487,8 +487,12 @@ def test_capacity_and_state_errors_are_reported_not_faulted(tiny_pair):
     with pytest.raises(api.SdError) as ei:
         api.sd_verify(tiny_pair.gd, ctx, None, 1, 2, 0.0, na, None, None, na, nx)  # draft was never attached
     assert ei.value.code == api.SD_EINVAL
-    # run the sequence into its capacity: the kernels refuse the rows and raise the flag
     cand = torch.zeros((1, 4), dtype=torch.int32, device="cuda")
+    for bad_n in (0, 2):   # an empty batch, and more sequences than the context holds
+        with pytest.raises(api.SdError) as ei:
+            api.sd_verify(tiny_pair.gt, ctx, None, bad_n, 4, 0.0, cand, None, None, na, nx)
+        assert ei.value.code == api.SD_EINVAL
+    # run the sequence into its capacity: the kernels refuse the rows and raise the flag
     for _ in range(70):
         api.sd_verify(tiny_pair.gt, ctx, None, 1, 4, 0.0, cand, None, None, na, nx, commit=True)
     with pytest.raises(api.SdError) as ei:
