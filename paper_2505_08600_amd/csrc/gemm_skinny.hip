@@ -144,30 +144,28 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_tile_kernel(const uint16_t *A
 #pragma unroll
             for (int i = 0; i < NI; i++) wv[b][c][i] = *(const bf16x8 *)(Wp[c] + ((size_t)cc * NI + i) * 512);
     };
-    auto compute = [&](int b, int lb) {
+    // Activation fragments: two register sets used alternately by the MFMA groups of a chunk (group i
+    // contracts elements 32*i .. 32*i+31 and reads set i & 1); the fragments of group i+1 are read from LDS
+    // while group i runs.
+    static_assert(NI % 2 == 0, "the last MFMA group of a chunk uses fragment set 1");
+    bf16x8 fh[2][MT], fl[2][MT];
+    auto frags = [&](int lb, int i, int fb) {
         const uint16_t *sa = &sA[lb][0][0] + row * LDROW + grp * 8;
-        // activation fragments of MFMA i+1 are read from LDS while MFMA group i runs
-        bf16x8 fh[2][MT], fl[2][MT];
-        auto frags = [&](int i, int fb) {
 #pragma unroll
-            for (int t = 0; t < MT; t++) {
-                fh[fb][t] = *(const bf16x8 *)(sa + t * 16 * LDROW + i * 32);
-                fl[fb][t] = *(const bf16x8 *)(sa + (BM + t * 16) * LDROW + i * 32);
-            }
-        };
-        frags(0, 0);
+        for (int t = 0; t < MT; t++) {
+            fh[fb][t] = *(const bf16x8 *)(sa + t * 16 * LDROW + i * 32);
+            fl[fb][t] = *(const bf16x8 *)(sa + (BM + t * 16) * LDROW + i * 32);
+        }
+    };
+    auto mfma_group = [&](int b, int i) {
 #pragma unroll
-        for (int i = 0; i < NI; i++) { // MFMA group i contracts elements 32*i .. 32*i+31 of the chunk
-            if (i < NI - 1) frags(i + 1, (i + 1) & 1);
+        for (int t = 0; t < MT; t++) {
 #pragma unroll
-            for (int t = 0; t < MT; t++) {
+            for (int c = 0; c < NT; c++)
+                acc[c][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv[b][c][i], fh[i & 1][t], acc[c][t], 0, 0, 0);
 #pragma unroll
-                for (int c = 0; c < NT; c++)
-                    acc[c][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv[b][c][i], fh[i & 1][t], acc[c][t], 0, 0, 0);
-#pragma unroll
-                for (int c = 0; c < NT; c++)
-                    acc[c][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv[b][c][i], fl[i & 1][t], acc[c][t], 0, 0, 0);
-            }
+            for (int c = 0; c < NT; c++)
+                acc[c][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv[b][c][i], fl[i & 1][t], acc[c][t], 0, 0, 0);
         }
     };
     // Pipeline, iteration ch (weight buffer b = ch % NB):
@@ -176,9 +174,13 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_tile_kernel(const uint16_t *A
     //   2. chunk ch is multiplied, and in between its MFMAs the loads of later chunks are issued: the
     //      activation rows of chunk ch+2 first, then the weights of chunk ch+NB-1 into the buffer that
     //      iteration ch-1 released (so NB-1 weight chunks are in flight or in use at any time);
-    //   3. barrier.
+    //   3. barrier.  With EARLY the barrier stands before the last MFMA group instead, and the first
+    //      fragments of chunk ch+1 are read from LDS behind it, under that group's MFMAs: no MFMA then
+    //      waits for the LDS round trip that follows a barrier (it costs 8 more registers of live range,
+    //      which only the 3-tile shape has to spare).
     // Every iteration issues the same loads in the same order, activation rows before weights: waiting
     // for the rows never waits for the (much slower) weight stream, and the wait counts stay exact.
+    constexpr bool EARLY = BM == 96 && NT == 3;
     a_fetch(0);
     SD_ORDER();
     w_issue(0, 0);
@@ -190,6 +192,10 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_tile_kernel(const uint16_t *A
     for (int b = 1; b < NB - 1; b++) w_issue(b, b);
     SD_ORDER();
     __syncthreads();
+    if (EARLY) {
+        frags(0, 0, 0);
+        SD_ORDER();
+    }
     for (int ch0 = 0; ch0 < nchunks; ch0 += NB) {
 #pragma unroll
         for (int b = 0; b < NB; b++) {
@@ -199,18 +205,33 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_tile_kernel(const uint16_t *A
             SD_ORDER();
             a_fetch(ch + 2);
             w_issue(ch + NB - 1, (b + NB - 1) % NB);
-            compute(b, ch & 1);
-            // instruction order of this block: the LDS reads of the first fragment group, then one global
-            // load (activation rows first) and one LDS read after every third MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 2 * MT, 0);
+            if (!EARLY) frags(ch & 1, 0, 0);
 #pragma unroll
-            for (int k = 0; k < (NT * MT * 2 * NI) / 3; k++) {
+            for (int i = 0; i < (EARLY ? NI - 1 : NI); i++) {
+                if (i < NI - 1) frags(ch & 1, i + 1, (i + 1) & 1);
+                mfma_group(b, i);
+            }
+            // instruction order of this stretch: (the LDS reads of the first fragment group, then) one
+            // global load (activation rows first) and one LDS read after every third MFMA
+            if (!EARLY) __builtin_amdgcn_sched_group_barrier(0x100, 2 * MT, 0);
+#pragma unroll
+            for (int k = 0; k < (NT * MT * 2 * (EARLY ? NI - 1 : NI)) / 3; k++) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 3, 0); // MFMA
                 if (k < LPT + NT * NI) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);     // VMEM read
                 if (k < 2 * MT * (NI - 1)) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); // DS read
             }
             SD_ORDER();
             __syncthreads();
+            if (EARLY) {
+                frags((ch + 1) & 1, 0, 0); // (after the last chunk: a stale buffer, never used)
+                mfma_group(b, NI - 1);
+#pragma unroll
+                for (int k = 0; k < (NT * MT * 2) / 3; k++) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 3, 0); // MFMA
+                    if (k < 2 * MT) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); // DS read
+                }
+                SD_ORDER();
+            }
         }
     }
 k_done:
@@ -240,15 +261,17 @@ k_done:
                 const int n = n0 + (q >> 1) * 16;
                 if (!(q & 1) || n >= N) continue;
                 const f32x4 g = c > 0 ? acc[c > 0 ? c - 1 : 0][t] : gin[t];
-                const size_t o = act_index(c_av, m, n + 4 * grp, N);
+                const size_t o = act_index(c_av, m, n + 4 * grp, N); // 4 columns inside one K step: contiguous
+                uint16_t hi[4], lo[4];
 #pragma unroll
                 for (int r = 0; r < 4; r++) {
                     const float g0 = g[r];
                     const float y = g0 / (1.0f + expf(-g0)) * acc[c][t][r];
-                    const uint16_t hi = bf16_bits_rne(y);
-                    Cact[o + r] = hi;
-                    Cact[c_av.plane + o + r] = bf16_bits_rne(y - __uint_as_float((uint32_t)hi << 16));
+                    hi[r] = bf16_bits_rne(y);
+                    lo[r] = bf16_bits_rne(y - __uint_as_float((uint32_t)hi[r] << 16));
                 }
+                *(uint2 *)(Cact + o) = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
+                *(uint2 *)(Cact + c_av.plane + o) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
             }
         } else {
             float *Cs = C + (size_t)blockIdx.y * c_split_stride;
@@ -507,7 +530,7 @@ hipError_t launch_gemm_skinny_bf16(hipStream_t s, int mode, const void *A, ActVi
         if (w.p[i] && ((uintptr_t)w.p[i] & 15)) return hipErrorNotSupported;
     if (((uintptr_t)A & 15) || (a_av.plane & 7) || (N & 3) || !a_av.sm || a_av.rows < M) return hipErrorNotSupported;
     if (2 * a_av.plane + (size_t)SD_ACT_PAD_ROWS * 128 >= ((size_t)1 << 32)) return hipErrorNotSupported; // 32-bit offsets
-    if (mode == GEMM_SWIGLU && (!c_av.sm || (c_av.plane & 7) || N % 128 != 0)) return hipErrorNotSupported;
+    if (mode == GEMM_SWIGLU && (!c_av.sm || (c_av.plane & 7) || N % 128 != 0 || ((uintptr_t)Cact & 15))) return hipErrorNotSupported;
     const uint16_t *a = (const uint16_t *)A;
     uint16_t *ca = (uint16_t *)Cact;
     if (M > 32) { // row-blocked
