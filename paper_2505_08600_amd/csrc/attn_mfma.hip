@@ -61,7 +61,6 @@ __device__ __forceinline__ void attn_tiles(const uint16_t *__restrict__ K, const
     // two register buffers: the loads of the next tile are in flight while the current one is consumed
     bf16x8 ka0[NC], kb0[NC], vv0[ND], ka1[NC], kb1[NC], vv1[ND];
     auto load_tile = [&](int t, bf16x8 *ka, bf16x8 *kb, bf16x8 *vv) {
-        const int t0 = t * AT_TILE;
         // MFMA c contracts head dimensions 32*c .. 32*c+31 (k-group grp takes 8 of them); the tile is stored
         // in operand order (kt_offset), so every load instruction reads one contiguous KiB
         const uint16_t *kp = K + (size_t)t * (AT_TILE * HD) + lane * 8;
