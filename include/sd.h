@@ -214,7 +214,8 @@ int64_t sd_debug_layout_index(int32_t kind, int64_t a, int64_t b, int64_t c, int
  * option "gemm_tile_cols" = 192 or 256 forces the block width (in weight rows) of the
  * row-blocked GEMM for more than 64 rows where the shape allows it (0 = automatic).
  * option "attn_waves" = 4 or 8 forces the block shape of the fused attention kernel
- * (0 = automatic: 4-wave blocks once (sequence, head) pairs oversubscribe the chip).
+ * (0 = automatic: 4-wave blocks when (sequence, head) pairs oversubscribe the chip and
+ * contexts are short).
  * Unknown names and out-of-range values return SD_EINVAL. */
 int sd_set_option(const char *name, int32_t value);
 /* Per-kernel-class totals gathered under option "profile": idx = 0,1,.. until

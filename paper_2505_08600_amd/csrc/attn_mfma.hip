@@ -412,9 +412,11 @@ hipError_t launch_attn_fused_bf16(hipStream_t s, const float *qkv, int n_slabs, 
     // one block per (sequence, head): fine when those alone fill the chip, or when every wave has
     // at most a few tiles anyway
     if (!((long)n_seq * H >= 512 || tiles_upper <= 48)) return hipErrorNotSupported;
-    // with more than two blocks per compute unit the 4-wave shape (two resident blocks per unit) hides
-    // each block's prologue and merge behind its neighbour's streaming
-    const bool many = g_force_attn_waves ? g_force_attn_waves == 4 : (long)n_seq * H >= 512;
+    // with more than two blocks per compute unit and short contexts the 4-wave shape (two resident blocks
+    // per unit) hides each block's prologue and merge behind its neighbour's streaming; from about 40 tiles
+    // per block on, the 8-wave shape streams faster (measured: 4.9 against 4.6 TB/s at 2048 tokens, 5.5
+    // against 5.2 at 1024..8192)
+    const bool many = g_force_attn_waves ? g_force_attn_waves == 4 : ((long)n_seq * H >= 512 && tiles_upper <= 40);
     dim3 grid(H, n_seq), block(many ? 256 : 512);
 #define SD_FUSED(HD_, WAVES_)                                                                                          \
     hipLaunchKernelGGL((attn_fused_kernel<HD_, WAVES_>), grid, block, 0, s, qkv, n_slabs, slab_stride, pv, cv, R, H,   \
