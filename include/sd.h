@@ -117,10 +117,11 @@ int sd_ctx_set_tokens(sd_ctx *c, const int32_t *tokens, const int32_t *lens, con
                       int32_t n_seq);
 
 /* Feed model m with every token of the selected sequences that its cache does
- * not cover yet, except the pending last one (the step before the hot path; here
- * it reuses the verify kernels in row chunks).  max_new (host) is the largest
- * number of tokens any selected sequence still has to feed; it fixes the number
- * of chunks.  Enqueues on stream. */
+ * not cover yet, except the pending last one (the step before the hot path).  Each
+ * forward takes as many 16-token groups per sequence as the model's max_rows allows
+ * (max_rows / (16 * n_seq), at least one), so a larger max_rows means fewer passes
+ * over the weights.  max_new (host) is the largest number of tokens any selected
+ * sequence still has to feed; it fixes the number of forwards.  Enqueues on stream. */
 int sd_prefill(sd_model *m, sd_ctx *c, const int32_t *seq_ids /*dev*/, int32_t n_seq, int32_t max_new,
                void *stream);
 

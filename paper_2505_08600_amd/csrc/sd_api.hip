@@ -590,12 +590,16 @@ static int stream_gemm(sd_model *m, hipStream_t s, const void *A, ActView a_av, 
 // append (adds the slabs) -> attention -> O GEMM (slabs) -> add + rmsnorm -> gate/up GEMM with SwiGLU
 // epilogue -> down GEMM (slabs, added by the next layer's add + rmsnorm).  Shapes outside the MFMA
 // kernels' domain, and fp32 models, take the reference kernels with the same data flow.
+// One forward over R rows for each of n_seq sequences - or, for prefill (mode PLAN_CATCHUP, G > 1), over G
+// groups of R rows per sequence, each group a plan slot of its own.
 static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, int R, int n_seq,
                    const int32_t *seq_ids, int upto_off, const int32_t *cand, int gamma, int cand_idx,
-                   bool want_logits)
+                   bool want_logits, int G = 1)
 {
     const sd_model_config &cf = m->cfg;
-    const int M = n_seq * R, d = cf.d_model, H = cf.n_heads, hd = cf.head_dim, F = cf.d_ffn, V = cf.vocab;
+    const int n_slots = n_seq * G; // plan slots: what the attention kernels see as sequences
+    const int M = n_slots * R, d = cf.d_model, H = cf.n_heads, hd = cf.head_dim, F = cf.d_ffn, V = cf.vocab;
+    if (G < 1 || (G > 1 && mode != PLAN_CATCHUP)) return sd_fail(SD_EINVAL, "forward: row groups are for prefill only");
     if (M > cf.max_rows) return sd_fail(SD_ECAP, "forward: rows exceed the model's max_rows");
     // activation buffers of bf16 models are step-major when their width allows it
     const int sm_d = cf.dtype == SD_BF16 && d % 128 == 0, sm_f = cf.dtype == SD_BF16 && F % 128 == 0;
@@ -608,7 +612,8 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
     size_t lstride = (size_t)d * c->total_cap * m->esz;
     hipError_t ge;
     { ProfScope ps(T_PLAN, s);
-    FWD(launch_plan(s, mode, R, n_seq, seq_ids, cv, slot, upto_off, cand, gamma, cand_idx, V, pv)); }
+    if (G > 1) FWD(launch_plan_prefill(s, R, G, n_seq, seq_ids, cv, slot, upto_off, V, pv));
+    else FWD(launch_plan(s, mode, R, n_seq, seq_ids, cv, slot, upto_off, cand, gamma, cand_idx, V, pv)); }
     { ProfScope ps(T_EMBED, s); // embedding gather + the first layer's norm in one launch
     FWD(launch_embed_rmsnorm(s, cf.dtype, m->embed, pv.row_tok, M, d, m->x, m->norm_attn[0], cf.rms_eps, m->abuf, avd)); }
     int pending = 0; // split-K slabs of the previous down projection not yet added to x
@@ -635,7 +640,9 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
             qkv_src = m->qkv;
         } }
         hipError_t ea = hipErrorNotSupported;
-        if (cf.dtype == SD_BF16 && !(g_force_generic & 2)) { // RoPE + append + attention in one launch
+        // RoPE + append + attention in one launch - unless a sequence spans several slots (prefill): their
+        // rows must all be in the cache before any slot's attention starts
+        if (cf.dtype == SD_BF16 && !(g_force_generic & 2) && G == 1) {
             ProfScope ps(T_ATTN, s);
             ea = launch_attn_fused_bf16(s, qkv_src, nq_slabs, (size_t)M * 3 * d, pv, cv, R, n_seq, H, hd, m->rope,
                                         cf.max_pos, Kl, Vtl, c->total_cap, kv_upper, m->obuf, avd);
@@ -646,10 +653,10 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
                                    cf.max_pos, m->qbuf, avd, Kl, Vtl, c->total_cap)); }
             ProfScope ps(T_ATTN, s);
             if (cf.dtype == SD_BF16 && !(g_force_generic & 2))
-                ea = launch_attn_mfma_bf16(s, m->qbuf, avd, Kl, Vtl, pv, cv, R, n_seq, H, hd, c->total_cap,
+                ea = launch_attn_mfma_bf16(s, m->qbuf, avd, Kl, Vtl, pv, cv, R, n_slots, H, hd, c->total_cap,
                                            kv_upper, m->part, m->part_floats, m->obuf, avd);
             if (ea == hipErrorNotSupported)
-                ea = launch_attn_generic(s, cf.dtype, m->qbuf, avd, Kl, Vtl, pv, cv, R, n_seq, H, hd,
+                ea = launch_attn_generic(s, cf.dtype, m->qbuf, avd, Kl, Vtl, pv, cv, R, n_slots, H, hd,
                                          c->total_cap, kv_upper, m->obuf, avd);
         }
         if (ea == hipErrorNotSupported) return sd_fail(SD_ECAP, "forward: context too long for the generic attention kernel");
@@ -721,8 +728,11 @@ extern "C" int sd_prefill(sd_model *m, sd_ctx *c, const int32_t *seq_ids, int32_
     if (max_new < 0) return sd_fail(SD_EINVAL, "sd_prefill: max_new < 0");
     int R = std::min(m->cfg.max_rows / n_seq, 16);
     if (R < 1) return sd_fail(SD_ECAP, "sd_prefill: n_seq exceeds the model's max_rows");
-    for (int done = 0; done < max_new; done += R) {
-        rc = forward(m, c, slot, (hipStream_t)stream, PLAN_CATCHUP, R, n_seq, seq_ids, 1, nullptr, 0, 0, false);
+    // as many 16-row groups per sequence and forward as the workspace holds: the GEMMs then run at
+    // M = n_seq * 16 * G rows and stream the weights once per 16 * G tokens instead of once per 16
+    int G = R == 16 ? std::max(1, std::min(m->cfg.max_rows / (16 * n_seq), (max_new + 15) / 16)) : 1;
+    for (int done = 0; done < max_new; done += R * G) {
+        rc = forward(m, c, slot, (hipStream_t)stream, PLAN_CATCHUP, R, n_seq, seq_ids, 1, nullptr, 0, 0, false, G);
         if (rc) return rc;
     }
     return SD_OK;

@@ -246,6 +246,8 @@ extern int g_force_splits[3]; // per GEMM mode: K splits forced by option "gemm_
 // (each returns a hipError_t from hipGetLastError after the launch)
 hipError_t launch_plan(hipStream_t s, int mode, int R, int n_seq, const int32_t *seq_ids, CtxView cv, int slot,
                        int upto_off, const int32_t *cand, int gamma, int cand_idx, int vocab, PlanView pv);
+hipError_t launch_plan_prefill(hipStream_t s, int R, int G, int n_seq, const int32_t *seq_ids, CtxView cv, int slot,
+                               int upto_off, int vocab, PlanView pv);
 hipError_t launch_embed(hipStream_t s, int dtype, const void *E, const int32_t *row_tok, int M, int d, float *x);
 hipError_t launch_embed_rmsnorm(hipStream_t s, int dtype, const void *E, const int32_t *row_tok, int M, int d, float *x,
                                 const float *g, float eps, void *out, ActView out_av);

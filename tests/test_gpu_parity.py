@@ -328,6 +328,43 @@ def test_draft_and_verify_are_graph_capturable_and_replays_match_eager():
     pair.close()
 
 
+@pytest.mark.parametrize("shape_name,tol", [("tiny_target", 1e-4), ("small_target_bf16", 2e-2)])
+def test_prefill_in_row_groups_matches_oracle(shape_name, tol):
+    """With a workspace of 96 rows sd_prefill feeds three ragged prompts in groups of 16 rows, two groups
+    per sequence and forward (plan slots), through the separate cache-append and attention kernels; prompt
+    lengths cover an empty second group, a partial one and several forwards.  The cache it leaves must
+    give the oracle's logits in the verify pass that follows, and the oracle's decisions."""
+    _say(f"prefill in row groups, {shape_name}")
+    st_ = dg.SHAPES[shape_name]
+    w = dg.make_weights(st_, 81, BF16_LM_SCALE if st_.dtype == dg.BF16 else 1.0)
+    om = oracle.OracleModel(st_, w)
+    gm = api.Model(st_, w, max_rows=96, max_pos=256)
+    lens, gamma, V = [9, 41, 150], 3, st_.vocab
+    prompts = [[int(t) for t in dg.make_prompt(81, b, n, V)] for b, n in enumerate(lens)]
+    ctx = api.Context([n + 16 for n in lens])
+    ctx.attach(gm)
+    H.gpu_prefill(ctx, [gm], prompts)
+    nt, kv = ctx.sync(gm)
+    assert list(nt) == lens and list(kv) == [n - 1 for n in lens]
+    cand = dg.make_prompt(82, 0, 3 * gamma, V).reshape(3, gamma).astype(np.int32)
+    na = torch.zeros(3, dtype=torch.int32, device="cuda")
+    nx = torch.zeros(3, dtype=torch.int32, device="cuda")
+    api.sd_verify(gm, ctx, None, 3, gamma, 0.0, H.dev(cand), None, None, na, nx, commit=False)
+    lg = gm.last_logits().cpu().numpy().reshape(3, gamma + 1, V)
+    for b in range(3):
+        seq = om.new_seq(lens[b] + 16)
+        oracle.prefill(seq, prompts[b])
+        r_na, r_nx, mg, r_lg = seq.verify(prompts[b], gamma, 0.0, cand[b], None, np.zeros(gamma + 1, np.float32),
+                                          want_logits=True)
+        rel = np.abs(lg[b] - r_lg).max() / np.abs(r_lg).max()
+        _say(f"  sequence {b} (prompt {lens[b]}): logits rel err {rel:.2e}")
+        assert rel < tol
+        if (int(na[b]), int(nx[b])) != (r_na, r_nx):
+            assert st_.dtype == dg.BF16 and mg[:min(r_na, int(na[b])) + 1].min() < 0.05, (b, na[b], nx[b], r_na, r_nx, mg)
+    ctx.close()
+    gm.close()
+
+
 def test_gamma_zero_is_autoregressive_decoding(tiny_pair):
     _say("gamma = 0")
     prompt = dg.make_prompt(11, 2, 12, TINY_T.vocab)
