@@ -175,10 +175,10 @@ def main():
     verify_frac = verify_bytes / (t_verify * 1e-3) / 1e9 / HBM_PEAK_GBS
 
     tau = float(np.mean(n_acc + 1))
-    examined = np.where(n_acc < gamma, n_acc + 1, gamma).sum()
-    alpha_hat = float(n_acc.sum() / max(examined, 1))
+    alpha_hat = api.alpha_hat(n_acc.reshape(-1).tolist(), gamma)
     c_ratio = (t_draft / gamma) / t_verify
-    eq1 = ((1 - alpha_hat ** (gamma + 1)) / (1 - alpha_hat) if alpha_hat < 1 else gamma + 1) / (gamma * c_ratio + 1)
+    eq1 = api.eq1_speedup(alpha_hat, gamma, c_ratio)
+    best_gamma, best_eq1 = api.choose_gamma(alpha_hat, c_ratio, 15)   # Equation 1's optimum for this pair
 
     out = {
         "metric": "verified candidate tokens/s + accepted tokens/s, 7B-shape target, gamma=5, batch 1",
@@ -196,6 +196,7 @@ def main():
         "ms_draft": t_draft, "ms_verify": t_verify,
         "acceptance_rate_eq2": float(n_acc.sum() / (K * gamma)), "tau": tau, "alpha_hat": alpha_hat,
         "c_draft_over_target": c_ratio, "eq1_speedup_model": eq1,
+        "eq1_best_gamma": best_gamma, "eq1_best_speedup": best_eq1,
         "verify_hbm_frac": verify_frac,
         "roofline": {"bound": "hbm", "kernel": "gemm_ksplit_kernel<2,true,1,2,1> (gate/up + SiLU*mul) M=%d N=%d K=%d" % (M, st.d_ffn, st.d_model),
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,

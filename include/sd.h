@@ -171,6 +171,23 @@ int sd_commit(sd_ctx *c, const int32_t *seq_ids /*dev*/, int32_t n_seq, int32_t 
 int sd_route(const float *W, const float *b, int32_t n_drafts, int32_t emb_dim, const float *prompt_emb,
              int32_t n, int32_t *draft_id, void *stream);
 
+/* ---- candidate-count policy (host only: no GPU call, plain host pointers) ---- */
+
+/* Equation 1 (Section 1): the expected speed-up over autoregressive decoding with gamma
+ * candidates per step, per-token acceptance probability alpha in [0, 1] and draft/target
+ * cost ratio c >= 0:  (1 - alpha^(gamma+1)) / ((1 - alpha) (gamma c + 1)), whose numerator
+ * is gamma + 1 at alpha = 1.  Returns a NaN for arguments outside those ranges. */
+double sd_eq1_speedup(double alpha, int32_t gamma, double c);
+/* The gamma in [0, gamma_max] (gamma_max <= 15) that maximises Equation 1, the smallest
+ * one on ties; 0 means plain autoregressive decoding.  *speedup (may be NULL) receives the
+ * maximum.  Returns -1 (and sets the error string) for arguments out of range. */
+int32_t sd_choose_gamma(double alpha, double c, int32_t gamma_max, double *speedup);
+/* Running estimate of Equation 1's alpha from the n_accepted values of n_steps verify calls
+ * at `gamma` candidates: accepted candidates over examined ones, a step that rejects at
+ * position k having examined k + 1 (Equation 2's rate counts all gamma instead).  Returns
+ * a NaN when nothing was examined or a value is outside [0, gamma]. */
+double sd_alpha_hat(const int32_t *n_accepted /*host*/, int32_t n_steps, int32_t gamma);
+
 /* ---- inspection and test hooks (synchronising; not on the hot path) ---- */
 
 /* Copy token counts (and model m's cache lengths, if m and kv_len are non-NULL) to

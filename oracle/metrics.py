@@ -39,3 +39,10 @@ def expected_tau(alpha: float, gamma: int) -> float:
 def eq1_speedup(alpha: float, gamma: int, c: float) -> float:
     """Equation 1."""
     return expected_tau(alpha, gamma) / (gamma * c + 1.0)
+
+
+def best_gamma(alpha: float, c: float, gamma_max: int) -> int:
+    """The candidate count in [0, gamma_max] with the largest Equation 1 value (the smallest
+    such count on ties), by trying every one."""
+    values = [eq1_speedup(alpha, g, c) for g in range(gamma_max + 1)]
+    return values.index(max(values))

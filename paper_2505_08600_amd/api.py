@@ -22,7 +22,8 @@ SD_FP32, SD_BF16 = 0, 1
 
 EXPORTS = ["sd_load_model", "sd_free_model", "sd_ctx_create", "sd_ctx_free", "sd_ctx_attach", "sd_ctx_set_tokens",
            "sd_prefill", "sd_draft", "sd_verify", "sd_commit", "sd_route", "sd_ctx_sync", "sd_ctx_get_tokens",
-           "sd_ctx_set_kv", "sd_ctx_truncate", "sd_debug_read", "sd_debug_layout_index", "sd_last_logits", "sd_set_option", "sd_profile_read", "sd_last_error"]
+           "sd_ctx_set_kv", "sd_ctx_truncate", "sd_debug_read", "sd_debug_layout_index", "sd_last_logits", "sd_set_option", "sd_profile_read", "sd_last_error",
+           "sd_eq1_speedup", "sd_choose_gamma", "sd_alpha_hat"]
 
 
 class SdError(RuntimeError):
@@ -74,6 +75,12 @@ def lib():
         L.sd_set_option.argtypes = [C.c_char_p, i32]
         L.sd_profile_read.argtypes = [i32, C.POINTER(C.c_char_p), C.POINTER(i32), C.POINTER(C.c_float)]
         L.sd_last_error.restype = C.c_char_p
+        L.sd_eq1_speedup.argtypes = [C.c_double, i32, C.c_double]
+        L.sd_eq1_speedup.restype = C.c_double
+        L.sd_choose_gamma.argtypes = [C.c_double, C.c_double, i32, C.POINTER(C.c_double)]
+        L.sd_choose_gamma.restype = i32
+        L.sd_alpha_hat.argtypes = [vp, i32, i32]
+        L.sd_alpha_hat.restype = C.c_double
         _lib = L
     return _lib
 
@@ -268,6 +275,26 @@ def sd_commit(ctx: Context, seq_ids: Optional[torch.Tensor], n_seq: int, gamma: 
               n_accepted: torch.Tensor, next_token: torch.Tensor) -> None:
     _check(lib().sd_commit(ctx.h, _dp(seq_ids), n_seq, gamma, _dp(cand), _dp(n_accepted), _dp(next_token),
                            _stream()))
+
+
+def eq1_speedup(alpha: float, gamma: int, c: float) -> float:
+    """sd_eq1_speedup: Equation 1 (host only)."""
+    return float(lib().sd_eq1_speedup(alpha, gamma, c))
+
+
+def choose_gamma(alpha: float, c: float, gamma_max: int = 15):
+    """sd_choose_gamma: (gamma maximising Equation 1, that maximum)."""
+    v = C.c_double()
+    g = lib().sd_choose_gamma(alpha, c, gamma_max, C.byref(v))
+    if g < 0:
+        raise SdError(SD_EINVAL, lib().sd_last_error().decode())
+    return int(g), float(v.value)
+
+
+def alpha_hat(n_accepted: Sequence[int], gamma: int) -> float:
+    """sd_alpha_hat: accepted over examined candidates (host only)."""
+    a = _np_i32(n_accepted)
+    return float(lib().sd_alpha_hat(a.ctypes.data_as(C.c_void_p), len(a), gamma))
 
 
 def sd_route(W: torch.Tensor, b: Optional[torch.Tensor], prompt_emb: torch.Tensor, draft_id: torch.Tensor) -> None:

@@ -6,6 +6,7 @@
 #include <algorithm>
 
 #include "sd_internal.h"
+#include <cmath>
 
 static thread_local std::string g_err;
 int g_force_generic = 0;
@@ -122,6 +123,48 @@ extern "C" int sd_set_option(const char *name, int32_t value)
         return SD_OK;
     }
     return sd_fail(SD_EINVAL, std::string("sd_set_option: unknown option ") + name);
+}
+
+// ---------------------------------------------------------------- candidate-count policy (Equation 1)
+extern "C" double sd_eq1_speedup(double alpha, int32_t gamma, double c)
+{
+    if (!(alpha >= 0.0 && alpha <= 1.0) || !(c >= 0.0) || gamma < 0) return std::nan("");
+    // tokens per step: 1 + alpha + ... + alpha^gamma, summed directly (no cancellation near alpha = 1)
+    double tokens = 0.0, term = 1.0;
+    for (int i = 0; i <= gamma; i++) {
+        tokens += term;
+        term *= alpha;
+    }
+    return tokens / (gamma * c + 1.0);
+}
+
+extern "C" int32_t sd_choose_gamma(double alpha, double c, int32_t gamma_max, double *speedup)
+{
+    if (!(alpha >= 0.0 && alpha <= 1.0) || !(c >= 0.0) || gamma_max < 0 || gamma_max > SD_MAX_GAMMA) {
+        sd_fail(SD_EINVAL, "sd_choose_gamma: alpha in [0,1], c >= 0, 0 <= gamma_max <= 15");
+        return -1;
+    }
+    int best = 0;
+    double best_v = sd_eq1_speedup(alpha, 0, c);
+    for (int g = 1; g <= gamma_max; g++) {
+        const double v = sd_eq1_speedup(alpha, g, c);
+        if (v > best_v) best = g, best_v = v;
+    }
+    if (speedup) *speedup = best_v;
+    return best;
+}
+
+extern "C" double sd_alpha_hat(const int32_t *n_accepted, int32_t n_steps, int32_t gamma)
+{
+    if (!n_accepted || n_steps < 1 || gamma < 1) return std::nan("");
+    long accepted = 0, examined = 0;
+    for (int i = 0; i < n_steps; i++) {
+        const int a = n_accepted[i];
+        if (a < 0 || a > gamma) return std::nan("");
+        accepted += a;
+        examined += a < gamma ? a + 1 : gamma;
+    }
+    return examined ? (double)accepted / (double)examined : std::nan("");
 }
 
 // ---------------------------------------------------------------- model
