@@ -540,6 +540,62 @@ def test_capacity_and_state_errors_are_reported_not_faulted(tiny_pair):
     ctx.close()
 
 
+def test_draft_groups_on_separate_streams_match_sequential_calls():
+    """The drafts of a routed batch are independent models with workspaces of their own, so their sd_draft
+    calls may run on different streams at the same time (all at the default priority).  Four drafts of
+    different shapes, two sequences each: candidates and q from the concurrent calls must equal, bit for
+    bit, those of the same calls issued one after the other."""
+    _say("draft groups on four streams")
+    gamma, T, B, seed = 5, 0.7, 8, 93
+    V = 2048
+    dshapes = [dg.ModelShape("d_a", 1, 128, 2, 64, 384, V, dg.BF16), dg.ModelShape("d_b", 2, 128, 2, 64, 256, V, dg.BF16),
+               dg.ModelShape("d_c", 1, 256, 4, 64, 512, V, dg.BF16), dg.ModelShape("d_d", 1, 64, 1, 64, 128, V, dg.BF16)]
+    gds = [api.Model(sh, dg.make_weights(sh, seed + i, BF16_LM_SCALE), max_rows=16, max_pos=256) for i, sh in enumerate(dshapes)]
+    groups = [[g, g + 4] for g in range(4)]
+    lens = dg.make_prompt_lengths(seed, B, 8, 100)
+    prompts = [[int(t) for t in dg.make_prompt(seed, b, int(lens[b]), V)] for b in range(B)]
+    ctx = api.Context([int(l) + 32 for l in lens])
+    for gd in gds:
+        ctx.attach(gd)
+    ctx.set_tokens(prompts)
+    gid = [H.dev(np.array(g, np.int32)) for g in groups]
+    for g in range(4):
+        api.sd_prefill(gds[g], ctx, gid[g], 2, max(int(lens[b]) for b in groups[g]) - 1)
+    ud = [H.dev(np.stack([dg.make_uniforms(seed, dg.DRAFT_STREAM, b, 0, gamma) for b in groups[g]])) for g in range(4)]
+
+    def fresh():
+        return ([torch.zeros((2, gamma), dtype=torch.int32, device="cuda") for _ in range(4)],
+                [torch.zeros((2, gamma, V), dtype=torch.float32, device="cuda") for _ in range(4)])
+
+    def rewind():   # back to the state after prefill: each draft's cache length = tokens - 1
+        torch.cuda.synchronize()
+        for g in range(4):
+            for b in groups[g]:
+                ctx.truncate(gds[g], b, int(lens[b]) - 1)
+
+    cand_a, q_a = fresh()
+    for g in range(4):
+        api.sd_draft(gds[g], ctx, gid[g], 2, gamma, T, ud[g], cand_a[g], q_a[g])
+    rewind()
+    cand_b, q_b = fresh()
+    main = torch.cuda.current_stream()
+    streams = [torch.cuda.Stream() for _ in range(4)]
+    for g in range(4):
+        streams[g].wait_stream(main)
+        with torch.cuda.stream(streams[g]):
+            api.sd_draft(gds[g], ctx, gid[g], 2, gamma, T, ud[g], cand_b[g], q_b[g])
+    for g in range(4):
+        main.wait_stream(streams[g])
+    torch.cuda.synchronize()
+    for g in range(4):
+        assert torch.equal(cand_a[g], cand_b[g]) and torch.equal(q_a[g], q_b[g]), g
+        assert int(cand_a[g].min()) >= 0 and float(q_a[g].sum(-1).min()) > 0.999
+    ctx.sync()
+    ctx.close()
+    for gd in gds:
+        gd.close()
+
+
 def test_config3_routed_heterogeneous_drafts_small():
     """BASELINE config 3's structure at small widths: a batch of ragged prompts, each routed by the
     linear classifier to one of four drafts of different shapes; every draft decodes its group
