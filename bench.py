@@ -74,7 +74,8 @@ def main():
     V = st.vocab
     K, W = args.steps, args.warmup
     n_total = K + W + 8
-    cap = args.prompt + n_total * (gamma + 1) + 16
+    AR_STEPS = 16  # plain autoregressive decoding with the same library (gamma = 0), timed after the main loop
+    cap = args.prompt + n_total * (gamma + 1) + 16 + AR_STEPS
 
     t0 = time.time()
     wt = dg.make_weights(st, seed, threads=16)
@@ -206,6 +207,23 @@ def main():
                      "us_per_launch": gu_ms * 1e3, "algorithmic_bytes": gu_bytes},
         "kernel_ms_per_verify": {k: v[1] / 3.0 for k, v in vprof.items() if v[0]},
     }
+
+    # ---- Equation 1 against a measurement: plain autoregressive decoding of the same target through the
+    # same library (verify with gamma = 0: one row, one token per call).  Last use of this context: the
+    # draft's cache is left behind.
+    u_ar = uv[0][:, :1].contiguous()
+    for r in range(AR_STEPS + 2):
+        if r == 2:
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+        api.sd_verify(gt, ctx, None, B, 0, T, None, None, u_ar if T > 0 else None, na, nx, True)
+    torch.cuda.synchronize()
+    ms_ar = (time.perf_counter() - t0) / AR_STEPS * 1e3
+    ctx.sync()
+    emitted_per_s = float((n_acc + 1).sum() / dt)
+    out["ar_baseline"] = {"ms_per_token": ms_ar, "tokens_per_s": B / (ms_ar * 1e-3),
+                          "measured_speedup": emitted_per_s / (B / (ms_ar * 1e-3)),
+                          "eq1_with_measured_alpha_c": eq1}
 
     if not args.no_batch32:
         out["batch32_verify"] = batch32_verify(api, dg, torch, np, gt, st, seed, B32, LEN32, gamma)
