@@ -328,17 +328,19 @@ def test_draft_and_verify_are_graph_capturable_and_replays_match_eager():
     pair.close()
 
 
-@pytest.mark.parametrize("shape_name,tol", [("tiny_target", 1e-4), ("small_target_bf16", 2e-2)])
-def test_prefill_in_row_groups_matches_oracle(shape_name, tol):
+@pytest.mark.parametrize("shape_name,tol,max_rows", [("tiny_target", 1e-4, 96), ("small_target_bf16", 2e-2, 96),
+                                                     ("small_target_bf16", 2e-2, 144), ("small_target_bf16", 2e-2, 192)])
+def test_prefill_in_row_groups_matches_oracle(shape_name, tol, max_rows):
     """With a workspace of 96 rows sd_prefill feeds three ragged prompts in groups of 16 rows, two groups
     per sequence and forward (plan slots), through the separate cache-append and attention kernels; prompt
     lengths cover an empty second group, a partial one and several forwards.  The cache it leaves must
-    give the oracle's logits in the verify pass that follows, and the oracle's decisions."""
-    _say(f"prefill in row groups, {shape_name}")
+    give the oracle's logits in the verify pass that follows, and the oracle's decisions.  With 144 and 192
+    rows there are three and four groups per sequence."""
+    _say(f"prefill in row groups, {shape_name}, workspace {max_rows} rows")
     st_ = dg.SHAPES[shape_name]
     w = dg.make_weights(st_, 81, BF16_LM_SCALE if st_.dtype == dg.BF16 else 1.0)
     om = oracle.OracleModel(st_, w)
-    gm = api.Model(st_, w, max_rows=96, max_pos=256)
+    gm = api.Model(st_, w, max_rows=max_rows, max_pos=256)
     lens, gamma, V = [9, 41, 150], 3, st_.vocab
     prompts = [[int(t) for t in dg.make_prompt(81, b, n, V)] for b, n in enumerate(lens)]
     ctx = api.Context([n + 16 for n in lens])
