@@ -41,6 +41,7 @@ __device__ __forceinline__ float fast_exp(float x) { return __builtin_amdgcn_exp
 union Pack8 {
     bf16x8 v;
     uint16_t u[8];
+    uint32_t w[4];
 };
 
 // Online-softmax pass of one wave over the KV tiles t_begin, t_begin + t_stride, ... < t_end.
@@ -102,23 +103,26 @@ __device__ __forceinline__ void attn_tiles(const uint16_t *__restrict__ K, const
         Pack8 ph, pl;
         float psum = 0.f;
 #pragma unroll
-        for (int e = 0; e < 8; e++) {
-            float p = sc[e] > 0.5f * AT_NEG ? fast_exp(sc[e] - m_new) : 0.f;
-            psum += p;
-            uint16_t hi = bf16_bits_rne(p);
-            float rem = p - __uint_as_float((uint32_t)hi << 16);
-            ph.u[e] = hi;
-            pl.u[e] = bf16_bits_rne(rem);
+        for (int e = 0; e < 8; e += 2) {
+            const float p0 = sc[e] > 0.5f * AT_NEG ? fast_exp(sc[e] - m_new) : 0.f;
+            const float p1 = sc[e + 1] > 0.5f * AT_NEG ? fast_exp(sc[e + 1] - m_new) : 0.f;
+            psum += p0;
+            psum += p1;
+            bf16x2_split(p0, p1, ph.w[e >> 1], pl.w[e >> 1]);
         }
         l_run = l_run * corr + psum;
         m_run = m_new;
+        // once the running maxima have settled corr is exactly 1 in every lane: skip the 4 * ND multiplies
+        const bool rescale = __any(corr != 1.0f);
 #pragma unroll
         for (int d = 0; d < ND; d++) {
             f32x4 acc = o[d];
-            acc[0] *= corr;
-            acc[1] *= corr;
-            acc[2] *= corr;
-            acc[3] *= corr;
+            if (rescale) {
+                acc[0] *= corr;
+                acc[1] *= corr;
+                acc[2] *= corr;
+                acc[3] *= corr;
+            }
             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv[d], ph.v, acc, 0, 0, 0);
             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv[d], pl.v, acc, 0, 0, 0);
             o[d] = acc;
@@ -386,16 +390,15 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_fused_kernel(const float *
             L += sL[w][q] * f;
         }
         const bool live = q < nq && L > 0.f;
-        uint16_t hi[4], lo[4];
+        float out[4];
 #pragma unroll
-        for (int r = 0; r < 4; r++) {
-            const float out = live ? O[r] / L : 0.f;
-            hi[r] = bf16_bits_rne(out);
-            lo[r] = bf16_bits_rne(out - __uint_as_float((uint32_t)hi[r] << 16));
-        }
+        for (int r = 0; r < 4; r++) out[r] = live ? O[r] / L : 0.f;
+        uint32_t h0, l0, h1, l1;
+        bf16x2_split(out[0], out[1], h0, l0);
+        bf16x2_split(out[2], out[3], h1, l1);
         const size_t oi = act_index(o_av, j * R + q, h * HD + dim, HDm); // 4 columns inside one K step
-        *(uint2 *)(obuf + oi) = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
-        *(uint2 *)(obuf + oi + o_av.plane) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
+        *(uint2 *)(obuf + oi) = make_uint2(h0, h1);
+        *(uint2 *)(obuf + oi + o_av.plane) = make_uint2(l0, l1);
     }
 }
 

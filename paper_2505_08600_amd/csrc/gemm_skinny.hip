@@ -262,16 +262,17 @@ k_done:
                 if (!(q & 1) || n >= N) continue;
                 const f32x4 g = c > 0 ? acc[c > 0 ? c - 1 : 0][t] : gin[t];
                 const size_t o = act_index(c_av, m, n + 4 * grp, N); // 4 columns inside one K step: contiguous
-                uint16_t hi[4], lo[4];
+                float y[4];
 #pragma unroll
                 for (int r = 0; r < 4; r++) {
                     const float g0 = g[r];
-                    const float y = g0 / (1.0f + expf(-g0)) * acc[c][t][r];
-                    hi[r] = bf16_bits_rne(y);
-                    lo[r] = bf16_bits_rne(y - __uint_as_float((uint32_t)hi[r] << 16));
+                    y[r] = g0 / (1.0f + expf(-g0)) * acc[c][t][r];
                 }
-                *(uint2 *)(Cact + o) = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
-                *(uint2 *)(Cact + c_av.plane + o) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
+                uint32_t h0, l0, h1, l1;
+                bf16x2_split(y[0], y[1], h0, l0);
+                bf16x2_split(y[2], y[3], h1, l1);
+                *(uint2 *)(Cact + o) = make_uint2(h0, h1);
+                *(uint2 *)(Cact + c_av.plane + o) = make_uint2(l0, l1);
             }
         } else {
             float *Cs = C + (size_t)blockIdx.y * c_split_stride;

@@ -20,12 +20,27 @@ struct bf16_t {
 __device__ __forceinline__ float to_float(float x) { return x; }
 __device__ __forceinline__ float to_float(bf16_t x) { return __uint_as_float((uint32_t)x.v << 16); }
 
-// fp32 -> bf16, round to nearest, ties to even (finite inputs).
+// fp32 -> bf16, round to nearest, ties to even: the hardware conversion (v_cvt_pk_bf16_f32), which gives,
+// for every non-NaN fp32 value, the bits of the integer formula  (u + 0x7fff + ((u >> 16) & 1)) >> 16
+// (checked exhaustively on the device).
 __device__ __forceinline__ uint16_t bf16_bits_rne(float f)
 {
-    uint32_t u = __float_as_uint(f);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    const __bf16 b = (__bf16)f;
+    return __builtin_bit_cast(uint16_t, b);
+}
+// Two values at once: a in the low half, b in the high half of the result.
+__device__ __forceinline__ uint32_t bf16x2_bits_rne(float a, float b)
+{
+    typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+    const f32x2_t v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+// hi + lo split of two values: hi = bf16(x), lo = bf16(x - hi), both packed like bf16x2_bits_rne.
+__device__ __forceinline__ void bf16x2_split(float a, float b, uint32_t &hi, uint32_t &lo)
+{
+    hi = bf16x2_bits_rne(a, b);
+    lo = bf16x2_bits_rne(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xffff0000u));
 }
 
 template <typename T>
@@ -64,15 +79,11 @@ __device__ __forceinline__ void store_act4(float *b, size_t i, size_t, float v0,
 }
 __device__ __forceinline__ void store_act4(bf16_t *b, size_t i, size_t plane, float v0, float v1, float v2, float v3)
 {
-    const float v[4] = {v0, v1, v2, v3};
-    uint16_t hi[4], lo[4];
-#pragma unroll
-    for (int e = 0; e < 4; e++) {
-        hi[e] = bf16_bits_rne(v[e]);
-        lo[e] = bf16_bits_rne(v[e] - __uint_as_float((uint32_t)hi[e] << 16));
-    }
-    *(uint2 *)(b + i) = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
-    *(uint2 *)(b + i + plane) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
+    uint32_t h0, l0, h1, l1;
+    bf16x2_split(v0, v1, h0, l0);
+    bf16x2_split(v2, v3, h1, l1);
+    *(uint2 *)(b + i) = make_uint2(h0, h1);
+    *(uint2 *)(b + i + plane) = make_uint2(l0, l1);
 }
 
 // Where element (row m, column k) of a GEMM-input activation buffer of width K lives.  Row-major, or
