@@ -40,6 +40,8 @@ def _load():
         lib.orc_seq_new.argtypes = [vp, C.c_int]
         lib.orc_seq_free.argtypes = [vp]
         lib.orc_seq_len.argtypes = [vp]
+        lib.orc_model_set_lora.argtypes = [vp, C.c_int, C.c_int, C.c_double] + [pp] * 8
+        lib.orc_seq_set_adapter.argtypes = [vp, vp, C.c_int]
         lib.orc_seq_truncate.argtypes = [vp, C.c_int]
         lib.orc_seq_set_kv.argtypes = [vp, vp, C.c_int, vp, vp, C.c_int]
         lib.orc_forward.argtypes = [vp, vp, vp, C.c_int, vp, C.c_int]
@@ -105,8 +107,30 @@ class OracleModel:
             _lib.orc_model_free(self.h)
             self.h = None
 
-    def new_seq(self, cap: int) -> "OracleSeq":
-        return OracleSeq(self, cap)
+    def set_lora(self, lora: Dict[str, object], scale: float) -> None:
+        """Attach adapters from datagen.make_lora (arrays are borrowed): y = W x + scale * B_a (A_a x) on
+        the q, k, v, o projections for sequences that choose adapter a."""
+        L = self.shape.n_layers
+        self._lora_keep = lora
+        arrs = []
+        for pnm in ("q", "k", "v", "o"):
+            for ab in ("a_", "b_"):
+                lst = lora.get(ab + pnm)
+                if lst is None:
+                    arrs.append(None)
+                    continue
+                for a in lst:
+                    assert a.flags["C_CONTIGUOUS"]
+                arrs.append((C.c_void_p * L)(*[a.ctypes.data for a in lst]))
+        self._lora_arrs = arrs
+        if _load().orc_model_set_lora(self.h, lora["n_adapters"], lora["rank"], float(scale), *arrs) != 0:
+            raise ValueError("oracle set_lora failed")
+
+    def new_seq(self, cap: int, adapter: int = -1) -> "OracleSeq":
+        s = OracleSeq(self, cap)
+        if adapter >= 0:
+            s.set_adapter(adapter)
+        return s
 
 
 class OracleSeq:
@@ -128,6 +152,10 @@ class OracleSeq:
     def truncate(self, n: int) -> None:
         if _load().orc_seq_truncate(self.h, n) != 0:
             raise ValueError("truncate beyond length")
+
+    def set_adapter(self, adapter: int) -> None:
+        if _load().orc_seq_set_adapter(self.model.h, self.h, adapter) != 0:
+            raise ValueError("adapter out of range")
 
     def set_kv(self, layer: int, k: np.ndarray, v: np.ndarray) -> None:
         k, v = np.ascontiguousarray(k), np.ascontiguousarray(v)

@@ -57,19 +57,33 @@ typedef struct {
     double rope_base, rms_eps;
 } orc_config;
 
+/* Low-rank adapters on the attention projections (Section 2.3: the heterogeneous drafts are LoRA
+ * fine-tunes of one base model).  For projection P in {q, k, v, o} of layer l and adapter a:
+ *   y = W x + scale * B[a] (A[a] x),  A[a]: [rank][in], B[a]: [out][rank],
+ * stored per layer as [n_adapters][rank][in] and [n_adapters][out][rank] in the model's dtype.
+ * A NULL pointer array means that projection is not adapted. */
+typedef struct {
+    int n_adapters, rank;
+    double scale;
+    const void **a[4], **b[4]; /* q, k, v, o */
+} orc_lora;
+
 typedef struct {
     orc_config c;
     const void *embed, *lm_head;
     const float *final_norm;
     const void **wq, **wk, **wv, **wo, **wgate, **wup, **wdown;
     const float **norm_attn, **norm_ffn;
+    orc_lora lora; /* n_adapters == 0: none */
 } orc_model;
 
 /* One sequence's KV cache for one model: k, v are [n_layers][cap][n_heads*head_dim],
- * holding values already rounded to the model's storage type. */
+ * holding values already rounded to the model's storage type.  adapter: the sequence's
+ * low-rank adapter for this model (-1: the base weights alone). */
 typedef struct {
     int cap, len;
     float *k, *v;
+    int adapter;
 } orc_seq;
 
 /* ---------- rounding points ---------- */
@@ -165,6 +179,27 @@ static void matvec(const void *W, int dtype, int N, int K, const double *a, doub
     }
 }
 
+/* y[n] += scale * sum_j B[n][j] * (sum_k A[j][k] * x[k]): the low-rank update of one projection,
+ * A: [rank][K], B: [N][rank] of the sequence's adapter. */
+static void lora_add(const orc_lora *lo, int proj, int layer, int adapter, int dtype, int N, int K, const double *x,
+                     double *y)
+{
+    if (lo->n_adapters == 0 || adapter < 0 || !lo->a[proj] || !lo->b[proj]) return;
+    const int r = lo->rank;
+    const size_t a0 = (size_t)adapter * r * K, b0 = (size_t)adapter * N * r;
+    double t[64];
+    for (int j = 0; j < r; j++) {
+        double acc = 0.0;
+        for (int k = 0; k < K; k++) acc += weight_at(lo->a[proj][layer], dtype, a0 + (size_t)j * K + k) * x[k];
+        t[j] = acc;
+    }
+    for (int n = 0; n < N; n++) {
+        double acc = 0.0;
+        for (int j = 0; j < r; j++) acc += weight_at(lo->b[proj][layer], dtype, b0 + (size_t)n * r + j) * t[j];
+        y[n] += lo->scale * acc;
+    }
+}
+
 /* Temperature softmax of one fp32 logit row, in fp64; p is stored as fp32. */
 void orc_softmax_T(const float *logits, int V, double T, float *p)
 {
@@ -254,9 +289,32 @@ orc_model *orc_model_new(const orc_config *c, const void *embed, const void *lm_
     return m;
 }
 
+/* Attach adapters: a_q .. b_o are [n_layers] pointer arrays (or NULL); rank <= 64. */
+int orc_model_set_lora(orc_model *m, int n_adapters, int rank, double scale, const void *const *a_q,
+                       const void *const *b_q, const void *const *a_k, const void *const *b_k, const void *const *a_v,
+                       const void *const *b_v, const void *const *a_o, const void *const *b_o)
+{
+    if (n_adapters < 0 || rank < 1 || rank > 64) return -1;
+    const void *const *as[4] = {a_q, a_k, a_v, a_o}, *const *bs[4] = {b_q, b_k, b_v, b_o};
+    for (int p = 0; p < 4; p++) {
+        free(m->lora.a[p]);
+        free(m->lora.b[p]);
+        m->lora.a[p] = as[p] ? copy_ptrs(as[p], m->c.n_layers) : NULL;
+        m->lora.b[p] = bs[p] ? copy_ptrs(bs[p], m->c.n_layers) : NULL;
+    }
+    m->lora.n_adapters = n_adapters;
+    m->lora.rank = rank;
+    m->lora.scale = scale;
+    return 0;
+}
+
 void orc_model_free(orc_model *m)
 {
     if (!m) return;
+    for (int p = 0; p < 4; p++) {
+        free(m->lora.a[p]);
+        free(m->lora.b[p]);
+    }
     free(m->wq); free(m->wk); free(m->wv); free(m->wo);
     free(m->wgate); free(m->wup); free(m->wdown);
     free(m->norm_attn); free(m->norm_ffn);
@@ -269,6 +327,7 @@ orc_seq *orc_seq_new(const orc_model *m, int cap)
     size_t n = (size_t)m->c.n_layers * cap * m->c.n_heads * m->c.head_dim;
     s->cap = cap;
     s->len = 0;
+    s->adapter = -1;
     s->k = (float *)calloc(n, sizeof(float));
     s->v = (float *)calloc(n, sizeof(float));
     return s;
@@ -283,6 +342,15 @@ void orc_seq_free(orc_seq *s)
 }
 
 int orc_seq_len(const orc_seq *s) { return s->len; }
+
+/* Choose the sequence's adapter for its model (-1: none).  Cache rows already written keep
+ * the values they were computed with. */
+int orc_seq_set_adapter(const orc_model *m, orc_seq *s, int adapter)
+{
+    if (adapter < -1 || adapter >= m->lora.n_adapters) return -1;
+    s->adapter = adapter;
+    return 0;
+}
 
 /* KV rollback: rows at index >= len are dead; nothing moves. */
 int orc_seq_truncate(orc_seq *s, int len)
@@ -343,12 +411,15 @@ int orc_forward(const orc_model *m, orc_seq *s, const int32_t *tokens, int n_row
             orc_rmsnorm(h + (size_t)r * d, m->norm_attn[l], d, c->rms_eps, a);
             for (int i = 0; i < d; i++) a[i] = round_act(a[i], dt);
             matvec(m->wq[l], dt, HD, d, a, tmp);
+            lora_add(&m->lora, 0, l, s->adapter, dt, HD, d, a, tmp);
             for (int hh = 0; hh < H; hh++) orc_rope(tmp + hh * hd, hd, pos, c->rope_base);
             for (int i = 0; i < HD; i++) qb[(size_t)r * HD + i] = round_act(tmp[i], dt);
             matvec(m->wk[l], dt, HD, d, a, tmp);
+            lora_add(&m->lora, 1, l, s->adapter, dt, HD, d, a, tmp);
             for (int hh = 0; hh < H; hh++) orc_rope(tmp + hh * hd, hd, pos, c->rope_base);
             for (int i = 0; i < HD; i++) Kc[(size_t)pos * HD + i] = (float)round_storage(tmp[i], dt);
             matvec(m->wv[l], dt, HD, d, a, tmp);
+            lora_add(&m->lora, 2, l, s->adapter, dt, HD, d, a, tmp);
             for (int i = 0; i < HD; i++) Vc[(size_t)pos * HD + i] = (float)round_storage(tmp[i], dt);
         }
         for (int r = 0; r < n_rows; r++) {
@@ -375,6 +446,7 @@ int orc_forward(const orc_model *m, orc_seq *s, const int32_t *tokens, int n_row
                 }
             }
             matvec(m->wo[l], dt, d, HD, ob, y);
+            lora_add(&m->lora, 3, l, s->adapter, dt, d, HD, ob, y);
             double *hr = h + (size_t)r * d;
             for (int i = 0; i < d; i++) hr[i] += y[i];
             /* SwiGLU feed-forward */

@@ -137,6 +137,27 @@ def make_weights(shape: ModelShape, seed: int, lm_head_scale: float = 1.0, threa
     return w
 
 
+LORA_PROJ = ("q", "k", "v", "o")
+
+
+def make_lora(shape: ModelShape, seed: int, n_adapters: int, rank: int, std_a: float = 0.02,
+              std_b: float = 0.02) -> Dict[str, object]:
+    """Random low-rank adapters on the attention projections (Section 2.3: the heterogeneous drafts are
+    LoRA fine-tunes of one base model): per layer and projection P in q, k, v, o
+    "a_P": [n_adapters][rank][in] and "b_P": [n_adapters][out][rank], in the model's dtype
+    (float32 arrays or bf16 bit patterns).  Both factors are random - a trained adapter has B != 0."""
+    d, hd_all = shape.d_model, shape.n_heads * shape.head_dim
+    dims = {"q": (hd_all, d), "k": (hd_all, d), "v": (hd_all, d), "o": (d, hd_all)}
+    w: Dict[str, object] = {"n_adapters": n_adapters, "rank": rank}
+    for j, pnm in enumerate(LORA_PROJ):
+        n_out, n_in = dims[pnm]
+        w["a_" + pnm] = [_normal_tensor(seed, 5000 + 16 * l + 2 * j, (n_adapters, rank, n_in), std_a, shape.dtype, 1.0)
+                         for l in range(shape.n_layers)]
+        w["b_" + pnm] = [_normal_tensor(seed, 5001 + 16 * l + 2 * j, (n_adapters, n_out, rank), std_b, shape.dtype, 1.0)
+                         for l in range(shape.n_layers)]
+    return w
+
+
 def perturbed_copy(weights: Dict[str, object], shape: ModelShape, seed: int, rel: float) -> Dict[str, object]:
     """A draft that is the same model with every matrix perturbed by rel * N(0, 0.02).
 
