@@ -98,6 +98,23 @@ typedef struct {
 int sd_load_model(const sd_model_config *cfg, const sd_weights *w, sd_model **out);
 int sd_free_model(sd_model *m);
 
+/* Low-rank adapters (Section 2.3: the heterogeneous drafts are LoRA fine-tunes of one base
+ * model).  For the attention projections P in {q, k, v, o} of every layer and adapter a,
+ *     y = W_P x + scale * B_P[a] (A_P[a] x),
+ * the adapter being chosen per sequence (sd_ctx_set_adapters), so that sequences routed to
+ * different drafts run as ONE batch of the base model.  a_P / b_P are HOST arrays of n_layers
+ * HOST pointers to [n_adapters][rank][d_model] / [n_adapters][d_model][rank] in the model's
+ * dtype (fp32 values or bf16 bit patterns); a NULL array leaves that projection unadapted.
+ * The factors are copied (as fp32) into device memory the model owns; the low-rank products
+ * are computed in fp32.  1 <= rank <= 16.  Replaces adapters set before; n_adapters = 0
+ * removes them.  Synchronises. */
+typedef struct {
+    int32_t n_adapters, rank;
+    float scale;
+    const void *const *a_q, *const *b_q, *const *a_k, *const *b_k, *const *a_v, *const *b_v, *const *a_o, *const *b_o;
+} sd_lora_weights;
+int sd_model_set_lora(sd_model *m, const sd_lora_weights *w);
+
 /* A context of `batch` sequences; caps (host, int32[batch]) is each sequence's
  * capacity in tokens (prompt + everything generated + gamma + 1 slack).  Allocates
  * the token buffers.  Synchronises. */
@@ -115,6 +132,11 @@ int sd_ctx_attach(sd_ctx *c, sd_model *m);
  * every attached model's cache length for them to 0.  Synchronises. */
 int sd_ctx_set_tokens(sd_ctx *c, const int32_t *tokens, const int32_t *lens, const int32_t *seq_ids,
                       int32_t n_seq);
+
+/* Adapter of every sequence of the context for model m (attached): adapter_ids is a HOST
+ * int32[B] with values in [-1, n_adapters), -1 = the base weights alone (the default).
+ * Cache rows already written keep the values they were computed with.  Synchronises. */
+int sd_ctx_set_adapters(sd_ctx *c, sd_model *m, const int32_t *adapter_ids);
 
 /* Feed model m with every token of the selected sequences that its cache does
  * not cover yet, except the pending last one (the step before the hot path).  Each

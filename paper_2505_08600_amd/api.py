@@ -23,7 +23,7 @@ SD_FP32, SD_BF16 = 0, 1
 EXPORTS = ["sd_load_model", "sd_free_model", "sd_ctx_create", "sd_ctx_free", "sd_ctx_attach", "sd_ctx_set_tokens",
            "sd_prefill", "sd_draft", "sd_verify", "sd_commit", "sd_route", "sd_ctx_sync", "sd_ctx_get_tokens",
            "sd_ctx_set_kv", "sd_ctx_truncate", "sd_debug_read", "sd_debug_layout_index", "sd_last_logits", "sd_set_option", "sd_profile_read", "sd_last_error",
-           "sd_eq1_speedup", "sd_choose_gamma", "sd_alpha_hat"]
+           "sd_eq1_speedup", "sd_choose_gamma", "sd_alpha_hat", "sd_model_set_lora", "sd_ctx_set_adapters"]
 
 
 class SdError(RuntimeError):
@@ -42,6 +42,11 @@ class _Weights(C.Structure):
     _fields_ = [("embed", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p)] + \
                [(n, C.POINTER(C.c_void_p)) for n in ("wq", "wk", "wv", "wo", "wgate", "wup", "wdown",
                                                      "norm_attn", "norm_ffn")]
+
+
+class _LoraW(C.Structure):
+    _fields_ = [("n_adapters", C.c_int32), ("rank", C.c_int32), ("scale", C.c_float)] + \
+               [(n, C.POINTER(C.c_void_p)) for n in ("a_q", "b_q", "a_k", "b_k", "a_v", "b_v", "a_o", "b_o")]
 
 
 def lib():
@@ -75,6 +80,8 @@ def lib():
         L.sd_set_option.argtypes = [C.c_char_p, i32]
         L.sd_profile_read.argtypes = [i32, C.POINTER(C.c_char_p), C.POINTER(i32), C.POINTER(C.c_float)]
         L.sd_last_error.restype = C.c_char_p
+        L.sd_model_set_lora.argtypes = [vp, C.POINTER(_LoraW)]
+        L.sd_ctx_set_adapters.argtypes = [vp, vp, vp]
         L.sd_eq1_speedup.argtypes = [C.c_double, i32, C.c_double]
         L.sd_eq1_speedup.restype = C.c_double
         L.sd_choose_gamma.argtypes = [C.c_double, C.c_double, i32, C.POINTER(C.c_double)]
@@ -158,6 +165,24 @@ class Model:
         self.t.clear()
         self._arrs.clear()
 
+    def set_lora(self, lora: Dict[str, object], scale: float) -> None:
+        """sd_model_set_lora: adapters from datagen.make_lora (host numpy arrays; the library copies them)."""
+        L = self.shape.n_layers
+        w = _LoraW()
+        w.n_adapters, w.rank, w.scale = lora["n_adapters"], lora["rank"], float(scale)
+        keep = []
+        for pnm in ("q", "k", "v", "o"):
+            for ab in ("a_", "b_"):
+                lst = lora.get(ab + pnm)
+                if lst is None:
+                    continue
+                arrs = [np.ascontiguousarray(a) for a in lst]
+                ptrs = (C.c_void_p * L)(*[a.ctypes.data for a in arrs])
+                keep.append((arrs, ptrs))
+                setattr(w, ab + pnm, C.cast(ptrs, C.POINTER(C.c_void_p)))
+        with torch.cuda.device(self.device):
+            _check(lib().sd_model_set_lora(self.h, C.byref(w)))
+
     def close(self):
         if getattr(self, "h", None):
             lib().sd_free_model(self.h)
@@ -232,6 +257,12 @@ class Context:
         n = C.c_int32()
         _check(lib().sd_ctx_get_tokens(self.h, seq, out.ctypes.data_as(C.c_void_p), out.shape[0], C.byref(n)))
         return out[:n.value].copy()
+
+    def set_adapters(self, m: Model, adapter_ids: Sequence[int]) -> None:
+        """sd_ctx_set_adapters: the low-rank adapter of every sequence for model m (-1: none)."""
+        a = _np_i32(adapter_ids)
+        assert len(a) == self.B
+        _check(lib().sd_ctx_set_adapters(self.h, m.h, a.ctypes.data_as(C.c_void_p)))
 
     def truncate(self, m: Model, seq: int, length: int) -> None:
         _check(lib().sd_ctx_truncate(self.h, m.h, seq, length))

@@ -521,6 +521,112 @@ hipError_t launch_add_rmsnorm(hipStream_t s, int dtype, float *x, const float *p
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------- low-rank adapters
+// One block per row.  The row (hi + lo summed) goes to LDS; the 4 waves share the n_proj * rank dot
+// products with the A factors; every thread then produces outputs n = tid, tid + 256, ...
+#define LORA_MAX_RANK 16
+#define LORA_MAX_K 8192
+struct LoraPtrs {
+    const float *a[3], *b[3];
+};
+template <typename T>
+__global__ __launch_bounds__(256) void lora_delta_kernel(const T *X, ActView x_av, int K, int N, int n_proj, PlanView pv,
+                                                         const int32_t *adapter, int n_adapters, int rank, float scale,
+                                                         LoraPtrs lp, float *out, int accumulate)
+{
+    __shared__ __attribute__((aligned(16))) float sx[LORA_MAX_K];
+    __shared__ float st[3][LORA_MAX_RANK];
+    const int r = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int a = pv.row_valid[r] ? adapter[pv.row_b[r]] : -1;
+    if (a >= n_adapters) a = -1;
+    float *orow = out + (size_t)r * n_proj * N;
+    if (a < 0) {
+        if (!accumulate)
+            for (int n = threadIdx.x; n < n_proj * N; n += 256) orow[n] = 0.f;
+        return;
+    }
+    for (int k = threadIdx.x; k < K; k += 256) sx[k] = load_act(X, act_index(x_av, r, k, K), x_av.plane);
+    __syncthreads();
+    // wave w takes the dot products pj = w, w + 4, ...: six at a time, so that their loads are in flight together
+    constexpr int PJ = 6;
+    for (int pj0 = wave; pj0 < n_proj * rank; pj0 += 4 * PJ) {
+        const float *arow[PJ];
+        float acc[PJ];
+#pragma unroll
+        for (int u = 0; u < PJ; u++) {
+            const int pj = pj0 + 4 * u;
+            const int p = pj < n_proj * rank ? pj / rank : 0, j = pj % rank;
+            arow[u] = pj < n_proj * rank && lp.a[p] ? lp.a[p] + ((size_t)a * rank + j) * K : nullptr;
+            acc[u] = 0.f;
+        }
+#pragma unroll 2
+        for (int k = 4 * lane; k < K; k += 256) { // 16 bytes per lane and load (K is a multiple of 4)
+            const float4 xv = *(const float4 *)&sx[k];
+#pragma unroll
+            for (int u = 0; u < PJ; u++)
+                if (arow[u]) {
+                    const float4 av = *(const float4 *)(arow[u] + k);
+                    acc[u] += av.x * xv.x + av.y * xv.y + av.z * xv.z + av.w * xv.w;
+                }
+        }
+#pragma unroll
+        for (int u = 0; u < PJ; u++) {
+            float v = acc[u];
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+            const int pj = pj0 + 4 * u;
+            if (lane == 0 && pj < n_proj * rank) st[pj / rank][pj % rank] = v;
+        }
+    }
+    __syncthreads();
+    // outputs n = tid, tid + 256, ...: four at a time (independent loads of the B rows)
+    const int n_out = n_proj * N;
+    for (int n0 = threadIdx.x; n0 < n_out; n0 += 4 * 256) {
+        float acc[4], old[4];
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            const int n = n0 + 256 * u;
+            acc[u] = 0.f;
+            old[u] = 0.f;
+            if (n < n_out) {
+                const int p = n / N, nn = n % N;
+                if (accumulate) old[u] = orow[n];
+                if (lp.a[p] && lp.b[p]) {
+                    const float *brow = lp.b[p] + ((size_t)a * N + nn) * rank;
+                    float bv[LORA_MAX_RANK]; // all loads of the row go out before the first is used
+#pragma unroll
+                    for (int j = 0; j < LORA_MAX_RANK; j++) bv[j] = j < rank ? brow[j] : 0.f;
+#pragma unroll
+                    for (int j = 0; j < LORA_MAX_RANK; j++)
+                        if (j < rank) acc[u] += bv[j] * st[p][j];
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            const int n = n0 + 256 * u;
+            if (n < n_out) orow[n] = old[u] + scale * acc[u];
+        }
+    }
+}
+
+hipError_t launch_lora_delta(hipStream_t s, int dtype, const void *X, ActView x_av, int M, int K, int N, int n_proj,
+                             PlanView pv, const int32_t *adapter, int n_adapters, int rank, float scale,
+                             const float *const *A, const float *const *B, float *out, int accumulate)
+{
+    if (M < 1 || K < 4 || (K & 3) || K > LORA_MAX_K || n_proj < 1 || n_proj > 3 || rank < 1 || rank > LORA_MAX_RANK || !adapter)
+        return hipErrorInvalidValue;
+    LoraPtrs lp;
+    for (int p = 0; p < 3; p++) lp.a[p] = p < n_proj ? A[p] : nullptr, lp.b[p] = p < n_proj ? B[p] : nullptr;
+    if (dtype == SD_BF16)
+        hipLaunchKernelGGL(lora_delta_kernel<bf16_t>, dim3(M), dim3(256), 0, s, (const bf16_t *)X, x_av, K, N, n_proj, pv,
+                           adapter, n_adapters, rank, scale, lp, out, accumulate);
+    else
+        hipLaunchKernelGGL(lora_delta_kernel<float>, dim3(M), dim3(256), 0, s, (const float *)X, x_av, K, N, n_proj, pv,
+                           adapter, n_adapters, rank, scale, lp, out, accumulate);
+    return hipGetLastError();
+}
+
 template <typename T>
 __global__ void rope_append_kernel(const float *qkv, int n_slabs, size_t slab_stride, PlanView pv, CtxView cv, int H,
                                    int hd, const float2 *rope,

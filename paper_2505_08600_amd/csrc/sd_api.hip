@@ -23,9 +23,9 @@ extern "C" const char *sd_last_error(void) { return g_err.c_str(); }
 // ---------------------------------------------------------------- per-kernel timing (option "profile")
 // When enabled, every launch of the forward is bracketed by two HIP events on the
 // stream it runs on; sd_profile_read folds them into per-kernel-class totals.
-enum ProfTag { T_PLAN, T_EMBED, T_RMSNORM, T_QKV, T_ROPE, T_ATTN, T_OPROJ, T_GATEUP, T_DOWN, T_LMHEAD, T_SAMPLE, T_TAIL, T_COUNT };
+enum ProfTag { T_PLAN, T_EMBED, T_RMSNORM, T_QKV, T_ROPE, T_ATTN, T_OPROJ, T_GATEUP, T_DOWN, T_LMHEAD, T_SAMPLE, T_TAIL, T_LORA, T_COUNT };
 static const char *g_tag_names[T_COUNT] = {"plan", "embed", "rmsnorm", "gemm_qkv", "rope_append", "attention", "gemm_o",
-                                           "gemm_gateup", "gemm_down", "gemm_lmhead", "draft_sample", "verify_tail"};
+                                           "gemm_gateup", "gemm_down", "gemm_lmhead", "draft_sample", "verify_tail", "lora"};
 struct ProfRec {
     int tag;
     hipEvent_t e0, e1;
@@ -193,6 +193,10 @@ extern "C" int sd_load_model(const sd_model_config *cfg, const sd_weights *w, sd
     sd_model *m = new sd_model();
     m->cfg = c;
     m->esz = c.dtype == SD_BF16 ? 2 : 4;
+    m->lora_n = 0;
+    m->lora_rank = 0;
+    m->lora_scale = 0.f;
+    m->lora_mem = nullptr;
     // ---- weights: one arena owned by the model.  bf16 matrices whose shape allows it are re-ordered into
     // 16 x 128 tiles on the way (the streaming GEMMs read those); everything else is copied as is.
     {
@@ -321,7 +325,66 @@ extern "C" int sd_free_model(sd_model *m)
     (void)hipFree(m->rope);
     (void)hipFree(m->plan_mem);
     (void)hipFree(m->wmem);
+    (void)hipFree(m->lora_mem);
     delete m;
+    return SD_OK;
+}
+
+// ---------------------------------------------------------------- low-rank adapters (Section 2.3)
+extern "C" int sd_model_set_lora(sd_model *m, const sd_lora_weights *w)
+{
+    if (!m || !w) return sd_fail(SD_EINVAL, "sd_model_set_lora: null argument");
+    if (w->n_adapters < 0 || (w->n_adapters > 0 && (w->rank < 1 || w->rank > 16)))
+        return sd_fail(SD_EINVAL, "sd_model_set_lora: n_adapters >= 0, 1 <= rank <= 16");
+    if (m->cfg.d_model > 8192) return sd_fail(SD_EINVAL, "sd_model_set_lora: d_model above 8192");
+    SD_HIP(hipDeviceSynchronize());
+    (void)hipFree(m->lora_mem);
+    m->lora_mem = nullptr;
+    m->lora_n = 0;
+    for (int p = 0; p < 4; p++) m->lora_a[p].clear(), m->lora_b[p].clear();
+    if (w->n_adapters == 0) return SD_OK;
+    const int L = m->cfg.n_layers, n = w->n_adapters, r = w->rank;
+    const size_t d = m->cfg.d_model, per = (size_t)n * r * d; // floats of one factor of one layer
+    const void *const *src_a[4] = {w->a_q, w->a_k, w->a_v, w->a_o}, *const *src_b[4] = {w->b_q, w->b_k, w->b_v, w->b_o};
+    size_t total = 0;
+    for (int p = 0; p < 4; p++) {
+        if ((src_a[p] == nullptr) != (src_b[p] == nullptr))
+            return sd_fail(SD_EINVAL, "sd_model_set_lora: a projection needs both factors or neither");
+        if (src_a[p]) total += 2 * per * L;
+    }
+    if (!total) return SD_OK;
+    SD_HIP(hipMalloc(&m->lora_mem, total * sizeof(float)));
+    std::vector<float> host(per);
+    float *dst = (float *)m->lora_mem;
+    auto upload = [&](const void *src) -> hipError_t { // one factor of one layer: to fp32, then to the device
+        if (m->cfg.dtype == SD_BF16) {
+            const uint16_t *b = (const uint16_t *)src;
+            for (size_t i = 0; i < per; i++) {
+                const uint32_t u = (uint32_t)b[i] << 16;
+                memcpy(&host[i], &u, 4);
+            }
+        } else {
+            memcpy(host.data(), src, per * sizeof(float));
+        }
+        return hipMemcpy(dst, host.data(), per * sizeof(float), hipMemcpyHostToDevice);
+    };
+    for (int p = 0; p < 4; p++) {
+        m->lora_a[p].assign(L, nullptr);
+        m->lora_b[p].assign(L, nullptr);
+        if (!src_a[p]) continue;
+        for (int l = 0; l < L; l++) {
+            if (!src_a[p][l] || !src_b[p][l]) return sd_fail(SD_EINVAL, "sd_model_set_lora: null factor of a layer");
+            SD_HIP(upload(src_a[p][l]));
+            m->lora_a[p][l] = dst;
+            dst += per;
+            SD_HIP(upload(src_b[p][l]));
+            m->lora_b[p][l] = dst;
+            dst += per;
+        }
+    }
+    m->lora_n = n;
+    m->lora_rank = r;
+    m->lora_scale = w->scale;
     return SD_OK;
 }
 
@@ -352,6 +415,7 @@ extern "C" int sd_ctx_create(int32_t batch, const int32_t *caps, sd_ctx **out)
     if (e == hipSuccess) e = hipMalloc((void **)&c->d_ntok, sizeof(int32_t) * batch);
     if (e == hipSuccess) e = hipMalloc((void **)&c->d_kvlen, sizeof(int32_t) * batch * SD_MAX_SLOTS);
     if (e == hipSuccess) e = hipMalloc((void **)&c->d_status, sizeof(int32_t));
+    if (e == hipSuccess) e = hipMalloc((void **)&c->d_adapter, sizeof(int32_t) * batch * SD_MAX_SLOTS);
     if (e != hipSuccess) {
         delete c;
         return sd_fail(SD_EHIP, std::string("sd_ctx_create: hipMalloc: ") + hipGetErrorString(e));
@@ -362,6 +426,7 @@ extern "C" int sd_ctx_create(int32_t batch, const int32_t *caps, sd_ctx **out)
     SD_HIP(hipMemset(c->d_ntok, 0, sizeof(int32_t) * batch));
     SD_HIP(hipMemset(c->d_kvlen, 0, sizeof(int32_t) * batch * SD_MAX_SLOTS));
     SD_HIP(hipMemset(c->d_status, 0, sizeof(int32_t)));
+    SD_HIP(hipMemset(c->d_adapter, 0xff, sizeof(int32_t) * batch * SD_MAX_SLOTS)); // -1: no adapter
     SD_HIP(hipDeviceSynchronize());
     *out = c;
     return SD_OK;
@@ -381,6 +446,7 @@ extern "C" int sd_ctx_free(sd_ctx *c)
     (void)hipFree(c->d_ntok);
     (void)hipFree(c->d_kvlen);
     (void)hipFree(c->d_status);
+    (void)hipFree(c->d_adapter);
     delete c;
     return SD_OK;
 }
@@ -390,6 +456,19 @@ static int find_slot(const sd_ctx *c, const sd_model *m)
     for (int s = 0; s < c->n_slots; s++)
         if (c->models[s] == m) return s;
     return -1;
+}
+
+extern "C" int sd_ctx_set_adapters(sd_ctx *c, sd_model *m, const int32_t *adapter_ids)
+{
+    if (!c || !m || !adapter_ids) return sd_fail(SD_EINVAL, "sd_ctx_set_adapters: null argument");
+    const int slot = find_slot(c, m);
+    if (slot < 0) return sd_fail(SD_EINVAL, "sd_ctx_set_adapters: model not attached to this context");
+    for (int b = 0; b < c->B; b++)
+        if (adapter_ids[b] < -1 || adapter_ids[b] >= m->lora_n)
+            return sd_fail(SD_EINVAL, "sd_ctx_set_adapters: adapter id outside [-1, n_adapters)");
+    SD_HIP(hipDeviceSynchronize());
+    SD_HIP(hipMemcpy(c->d_adapter + (size_t)slot * c->B, adapter_ids, sizeof(int32_t) * c->B, hipMemcpyHostToDevice));
+    return SD_OK;
 }
 
 extern "C" int sd_ctx_attach(sd_ctx *c, sd_model *m)
@@ -605,12 +684,14 @@ static hipError_t gemm_generic(sd_model *m, hipStream_t s, int mode, const void 
 // Weight-streaming path for a GEMM whose fp32 result is consumed as split-K slabs.  Returns the number
 // of slabs written to `slabs` (slab stride M*N floats), 0 if the shape is outside the kernel's domain.
 static int stream_gemm(sd_model *m, hipStream_t s, const void *A, ActView a_av, WeightSeg w, int M, int N, int K,
-                       float *slabs, size_t slabs_floats, int force_splits, hipError_t *err)
+                       float *slabs, size_t slabs_floats, int force_splits, hipError_t *err, int extra_slabs = 0)
 {
     *err = hipSuccess;
     if (m->cfg.dtype != SD_BF16 || (g_force_generic & 1)) return 0;
     int ns = force_splits > 0 ? force_splits : gemm_skinny_splits(GEMM_STORE, M, N, K, w.n_per_seg);
-    if ((size_t)ns * M * N > slabs_floats || ns > 8) ns = 1;
+    // (extra_slabs: slabs the caller appends after the GEMM's own, e.g. a low-rank update)
+    if ((size_t)(ns + extra_slabs) * M * N > slabs_floats || ns + extra_slabs > 8) ns = 1;
+    if ((size_t)(ns + extra_slabs) * M * N > slabs_floats) return 0;
     const ActView none = {0, 0, 0};
     hipError_t e = launch_gemm_skinny_bf16(s, GEMM_STORE, A, a_av, w, M, N, K, slabs, (size_t)M * N, ns, nullptr, none);
     if (e == hipErrorNotSupported) return 0;
@@ -673,15 +754,29 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
         WeightSeg wqkv = {{m->wq[l], m->wk[l], m->wv[l]}, d, m->tiled_dd};
         int nq_slabs;
         const float *qkv_src;
+        // low-rank adapters (sequences of one batch may use different ones): their update of q, k, v is one more
+        // slab for the consumer to add - or is added in place where the GEMM left a single full result
+        const bool lora_qkv = m->lora_n > 0 && (m->lora_a[0][l] || m->lora_a[1][l] || m->lora_a[2][l]);
+        const bool lora_o = m->lora_n > 0 && m->lora_a[3][l];
+        bool qkv_in_place = false;
         { ProfScope ps(T_QKV, s);
-        nq_slabs = stream_gemm(m, s, m->abuf, avd, wqkv, M, 3 * d, d, m->gpart_q, m->gpart_q_floats, 0, &ge);
+        nq_slabs = stream_gemm(m, s, m->abuf, avd, wqkv, M, 3 * d, d, m->gpart_q, m->gpart_q_floats, 0, &ge, lora_qkv ? 1 : 0);
         FWD(ge);
         qkv_src = m->gpart_q;
         if (!nq_slabs) {
             FWD(gemm_generic(m, s, GEMM_STORE, m->abuf, avd, wqkv, M, 3 * d, d, m->qkv, nullptr, av0));
             nq_slabs = 1;
             qkv_src = m->qkv;
+            qkv_in_place = true;
         } }
+        if (lora_qkv) { ProfScope ps(T_LORA, s);
+            const float *A3[3] = {m->lora_a[0][l], m->lora_a[1][l], m->lora_a[2][l]};
+            const float *B3[3] = {m->lora_b[0][l], m->lora_b[1][l], m->lora_b[2][l]};
+            float *dst = qkv_in_place ? m->qkv : m->gpart_q + (size_t)nq_slabs * M * 3 * d;
+            FWD(launch_lora_delta(s, cf.dtype, m->abuf, avd, M, d, d, 3, pv, cv.adapter + (size_t)slot * cv.B, m->lora_n,
+                                  m->lora_rank, m->lora_scale, A3, B3, dst, qkv_in_place ? 1 : 0));
+            if (!qkv_in_place) nq_slabs++;
+        }
         hipError_t ea = hipErrorNotSupported;
         // RoPE + append + attention in one launch - unless a sequence spans several slots (prefill): their
         // rows must all be in the cache before any slot's attention starts
@@ -707,9 +802,16 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
         WeightSeg wo = {{m->wo[l], nullptr, nullptr}, d, m->tiled_dd};
         int no_slabs;
         { ProfScope ps(T_OPROJ, s);
-        no_slabs = stream_gemm(m, s, m->obuf, avd, wo, M, d, d, m->gpart_r, m->gpart_r_floats, 0, &ge);
+        no_slabs = stream_gemm(m, s, m->obuf, avd, wo, M, d, d, m->gpart_r, m->gpart_r_floats, 0, &ge, lora_o ? 1 : 0);
         FWD(ge);
         if (!no_slabs) FWD(gemm_generic(m, s, GEMM_RESID, m->obuf, avd, wo, M, d, d, m->x, nullptr, av0)); }
+        if (lora_o) { ProfScope ps(T_LORA, s); // (without slabs the projection was added to x directly: so is its update)
+            const float *A1[1] = {m->lora_a[3][l]}, *B1[1] = {m->lora_b[3][l]};
+            float *dst = no_slabs ? m->gpart_r + (size_t)no_slabs * M * d : m->x;
+            FWD(launch_lora_delta(s, cf.dtype, m->obuf, avd, M, d, d, 1, pv, cv.adapter + (size_t)slot * cv.B, m->lora_n,
+                                  m->lora_rank, m->lora_scale, A1, B1, dst, no_slabs ? 0 : 1));
+            if (no_slabs) no_slabs++;
+        }
         { ProfScope ps(T_RMSNORM, s);
         if (no_slabs)
             FWD(launch_add_rmsnorm(s, cf.dtype, m->x, m->gpart_r, no_slabs, (size_t)M * d, m->norm_ffn[l], nullptr, M, d,

@@ -134,6 +134,7 @@ struct CtxView {
     int32_t *ntok;      // [B]
     int32_t *kvlen;     // [SD_MAX_SLOTS][B]
     int32_t *status;    // [1] sticky error bits
+    const int32_t *adapter; // [SD_MAX_SLOTS][B] low-rank adapter of each sequence per model slot (-1: none)
 };
 
 // Row plan of one forward: R row slots per selected sequence j (rows j*R .. j*R+R-1).
@@ -187,6 +188,11 @@ struct sd_model {
     const void *embed, *lm_head;
     const float *final_norm;
     void *wmem;     // arena holding the model's own copy of every weight
+    // low-rank adapters on q, k, v, o (fp32 on the device): a[p][layer] -> [n][rank][d], b[p][layer] -> [n][d][rank]
+    int lora_n, lora_rank;
+    float lora_scale;
+    std::vector<const float *> lora_a[4], lora_b[4];
+    void *lora_mem;
     int tiled_dd, tiled_fd, tiled_df, tiled_lm; // tile order used for [d][d], [F][d], [d][F], [V][d] matrices
     int esz; // bytes per weight / activation element
     // workspace (device)
@@ -217,7 +223,7 @@ struct sd_ctx {
     std::vector<int32_t> cap;
     std::vector<int64_t> off;
     int64_t *d_off;
-    int32_t *d_cap, *d_tokens, *d_ntok, *d_kvlen, *d_status;
+    int32_t *d_cap, *d_tokens, *d_ntok, *d_kvlen, *d_status, *d_adapter;
     int n_slots;
     sd_model *models[SD_MAX_SLOTS];
     void *kcache[SD_MAX_SLOTS];
@@ -234,6 +240,7 @@ struct sd_ctx {
         v.ntok = d_ntok;
         v.kvlen = d_kvlen;
         v.status = d_status;
+        v.adapter = d_adapter;
         return v;
     }
 };
@@ -255,6 +262,12 @@ extern int g_force_splits[3]; // per GEMM mode: K splits forced by option "gemm_
 
 // ---------------------------------------------------------------- kernel launchers
 // (each returns a hipError_t from hipGetLastError after the launch)
+// Low-rank update of n_proj (<= 3) projections that share the input rows X: for row r of a sequence with
+// adapter a >= 0, out[r][p * N + n] (+)= scale * sum_j B[p][a][n][j] * (sum_k A[p][a][j][k] * X[r][k]); rows
+// without an adapter (and projections whose factors are NULL) get 0 (or are left alone when accumulating).
+hipError_t launch_lora_delta(hipStream_t s, int dtype, const void *X, ActView x_av, int M, int K, int N, int n_proj,
+                             PlanView pv, const int32_t *adapter, int n_adapters, int rank, float scale,
+                             const float *const *A, const float *const *B, float *out, int accumulate);
 hipError_t launch_plan(hipStream_t s, int mode, int R, int n_seq, const int32_t *seq_ids, CtxView cv, int slot,
                        int upto_off, const int32_t *cand, int gamma, int cand_idx, int vocab, PlanView pv);
 hipError_t launch_plan_prefill(hipStream_t s, int R, int G, int n_seq, const int32_t *seq_ids, CtxView cv, int slot,

@@ -45,6 +45,8 @@ def test_argument_errors_do_not_need_a_gpu():
     assert L.sd_commit(None, None, 1, 4, None, None, None, None) == api.SD_EINVAL
     assert L.sd_route(None, None, 4, 256, None, 1, None, None) == api.SD_EINVAL
     assert L.sd_prefill(None, None, None, 1, 1, None) == api.SD_EINVAL
+    assert L.sd_model_set_lora(None, None) == api.SD_EINVAL
+    assert L.sd_ctx_set_adapters(None, None, None) == api.SD_EINVAL
     assert L.sd_free_model(None) == api.SD_OK and L.sd_ctx_free(None) == api.SD_OK
 
 

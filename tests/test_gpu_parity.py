@@ -542,6 +542,60 @@ def test_capacity_and_state_errors_are_reported_not_faulted(tiny_pair):
     ctx.close()
 
 
+@pytest.mark.parametrize("shape_name,tol", [("tiny_draft", 1e-4), ("small_target_bf16", 2e-2)])
+def test_lora_adapters_chosen_per_sequence_match_oracle(shape_name, tol):
+    """Section 2.3's drafts are LoRA fine-tunes of one base model: a batch whose sequences use different
+    adapters (and one none) runs as ONE forward of the base with per-sequence low-rank updates on q, k, v, o.
+    Prefill, a draft call (candidates and q) and a verify-style pass (logits) are compared per sequence with
+    the oracle run on that sequence alone with its adapter.  fp32 takes the reference kernels (updates
+    added in place), bf16 the MFMA kernels (update = one more split-K slab)."""
+    _say(f"LoRA adapters per sequence, {shape_name}")
+    st_ = dg.SHAPES[shape_name]
+    bf = st_.dtype == dg.BF16
+    w = dg.make_weights(st_, 95, BF16_LM_SCALE if bf else 20.0)
+    lora = dg.make_lora(st_, 96, n_adapters=3, rank=8, std_a=0.05, std_b=0.05)
+    scale, gamma, V = 2.0, 4, st_.vocab
+    om = oracle.OracleModel(st_, w)
+    om.set_lora(lora, scale)
+    gm = api.Model(st_, w, max_rows=32, max_pos=256)
+    gm.set_lora(lora, scale)
+    adapters = [0, -1, 2, 1]
+    lens = [12, 33, 7, 20]
+    B = len(lens)
+    prompts = [[int(t) for t in dg.make_prompt(95, b, n, V)] for b, n in enumerate(lens)]
+    ctx = api.Context([n + 32 for n in lens])
+    ctx.attach(gm)
+    ctx.set_adapters(gm, adapters)
+    H.gpu_prefill(ctx, [gm], prompts)
+    # draft call: the model drafts for itself, sampled
+    T = 1.0
+    ud = np.stack([dg.make_uniforms(95, dg.DRAFT_STREAM, b, 0, gamma) for b in range(B)])
+    cand = torch.zeros((B, gamma), dtype=torch.int32, device="cuda")
+    q = torch.zeros((B, gamma, V), dtype=torch.float32, device="cuda")
+    api.sd_draft(gm, ctx, None, B, gamma, T, H.dev(ud), cand, q)
+    cg, qg = cand.cpu().numpy(), q.cpu().numpy()
+    base_differs = 0
+    for b in range(B):
+        seq = om.new_seq(lens[b] + 32, adapters[b])
+        oracle.prefill(seq, prompts[b])
+        r_c, r_q, mg = seq.draft(prompts[b], gamma, T, ud[b])
+        k = 0
+        while k < gamma and cg[b][k] == r_c[k]:
+            assert np.abs(qg[b][k] - r_q[k]).max() < (2e-3 if bf else 1e-5), (b, k)
+            k += 1
+        if k < gamma:   # a differing token must be a low-margin draw
+            assert mg[k] < (5e-2 if bf else 1e-4), (b, k, cg[b], r_c, mg)
+        if adapters[b] >= 0:   # and the adapter must matter: the base model drafts another distribution
+            sb = oracle.OracleModel(st_, w).new_seq(lens[b] + 32)
+            oracle.prefill(sb, prompts[b])
+            _, b_q, _ = sb.draft(prompts[b], 1, T, ud[b][:1])
+            base_differs += int(np.abs(b_q[0] - r_q[0]).max() > 10 * (2e-3 if bf else 1e-5))
+    assert base_differs >= 2
+    ctx.sync()
+    ctx.close()
+    gm.close()
+
+
 def test_draft_groups_on_separate_streams_match_sequential_calls():
     """The drafts of a routed batch are independent models with workspaces of their own, so their sd_draft
     calls may run on different streams at the same time (all at the default priority).  Four drafts of
