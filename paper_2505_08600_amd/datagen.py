@@ -229,3 +229,56 @@ def make_kv_rows(seed: int, layer: int, seq: int, length: int, n_heads: int, hea
 def make_logit_noise(seed: int, seq: int, pos: int, vocab: int) -> np.ndarray:
     """N(0,1) noise row used to build synthetic draft logits (verify stress case)."""
     return _rng(seed, 40, seq, pos).standard_normal(vocab, dtype=np.float32)
+
+
+@dataclasses.dataclass(frozen=True)
+class ClassifierShape:
+    """Prompt classifier (Sections 2.4, 3.3.3): embedding, one selective state-space layer,
+    average pooling, a fully connected layer.  The paper gives no widths; the defaults put the
+    model near the size Table 2 reports with a 30522-entry word-piece vocabulary."""
+
+    name: str = "classifier"
+    vocab: int = 30522
+    d_model: int = 96
+    d_inner: int = 192
+    d_state: int = 16
+    dt_rank: int = 6
+    d_conv: int = 4
+    n_classes: int = 4
+
+
+CLASSIFIER_TINY = ClassifierShape("classifier_tiny", vocab=97, d_model=24, d_inner=64, d_state=5, dt_rank=3,
+                                  d_conv=3, n_classes=3)
+
+
+def make_classifier(shape: ClassifierShape, seed: int) -> Dict[str, np.ndarray]:
+    """Random fp32 classifier weights, each matrix stored [in features][out features] except
+    w_fc, which is [n_classes][d_model].  Step sizes start between about 1e-3 and 0.1 and the
+    state matrix is negative, as such layers are usually initialised."""
+    g = _rng(seed, 50)
+    s = shape
+    n = lambda *dims, std=1.0: (g.standard_normal(dims) * std).astype(np.float32)
+    return {
+        "emb": n(s.vocab, s.d_model),
+        "w_in": n(s.d_model, 2 * s.d_inner, std=s.d_model ** -0.5),
+        "conv_w": g.uniform(-0.5, 0.5, (s.d_inner, s.d_conv)).astype(np.float32),
+        "conv_b": n(s.d_inner, std=0.1),
+        "w_x": n(s.d_inner, s.dt_rank + 2 * s.d_state, std=s.d_inner ** -0.5),
+        "w_dt": n(s.dt_rank, s.d_inner, std=s.dt_rank ** -0.5),
+        "b_dt": g.uniform(-6.0, -2.0, s.d_inner).astype(np.float32),
+        "a_log": g.uniform(0.0, np.log(s.d_state), (s.d_inner, s.d_state)).astype(np.float32),
+        "d": (1.0 + 0.1 * g.standard_normal(s.d_inner)).astype(np.float32),
+        "w_out": n(s.d_inner, s.d_model, std=s.d_inner ** -0.5),
+        "w_fc": n(s.n_classes, s.d_model),
+        "b_fc": n(s.n_classes, std=0.1),
+    }
+
+
+def make_classifier_prompts(seed: int, n: int, vocab: int, max_len: int, median: float = 24.0):
+    """n prompts after stop-word removal: lengths log-normal around `median` tokens, clipped to
+    [1, max_len]; ids uniform.  Returns (tokens int32 [n][max_len], zero padded, lens int32 [n])."""
+    g = _rng(seed, 51)
+    lens = np.clip(np.rint(median * np.exp(0.6 * g.standard_normal(n))), 1, max_len).astype(np.int32)
+    tokens = g.integers(0, vocab, size=(n, max_len), dtype=np.int32)
+    tokens[np.arange(max_len)[None, :] >= lens[:, None]] = 0
+    return tokens, lens
