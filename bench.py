@@ -45,6 +45,8 @@ def main():
     ap.add_argument("--prompt", type=int, default=512)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy three times (known traffic, to scale HBM counters)")
+    ap.add_argument("--classifier", action="store_true",
+                    help="side measurement: route 400 synthetic prompts with the prompt classifier (own JSON line)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (sequences are independent; "
@@ -68,6 +70,9 @@ def main():
         print(json.dumps({"copy_bytes_read": n, "copy_bytes_written": n, "launches": 3}))
         return
     api.lib()
+    if args.classifier:
+        classifier_bench(api, dg, torch, np, args)
+        return
     seed, gamma, T, B = 2025, 5, float(args.temperature), 1
     st = dg.SHAPES["t7b"] if not args.layers else dg.with_layers(dg.SHAPES["t7b"], args.layers)
     sd_ = dg.SHAPES["draft_a"]
@@ -269,6 +274,45 @@ def batch32_verify(api, dg, torch, np, gt, st, seed, B, len_range, gamma, T=0.7,
             "rows": M, "ms_verify": ms, "candidates_per_s": B * gamma / (ms * 1e-3),
             "mfma_tflops": flops / (ms * 1e-3) / 1e12, "mfma_peak_tflops": 2500.0,
             "mfma_frac": flops / (ms * 1e-3) / 1e12 / 2500.0}
+
+
+def classifier_bench(api, dg, torch, np, args):
+    """Routing by the prompt classifier (Sections 2.4, 3.3.3): 400 prompts, the size of the paper's
+    classifier test set (Table 2), of log-normal length around 24 tokens after stop-word removal,
+    default classifier shape, random weights.  One launch routes the whole batch."""
+    shape, n, max_len, seed = dg.ClassifierShape(), 400, 128, 2025
+    w = dg.make_classifier(shape, seed)
+    tokens, lens = dg.make_classifier_prompts(seed, n, shape.vocab, max_len)
+    cls = api.Classifier(shape, w)
+    t, l = torch.from_numpy(tokens).cuda(), torch.from_numpy(lens).cuda()
+    ids = torch.zeros(n, dtype=torch.int32, device="cuda")
+    for _ in range(args.warmup):
+        cls.route(t, l, ids)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        cls.route(t, l, ids)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    out = {"metric": "classifier_prompts_per_s", "value": n / ms * 1e3, "unit": "prompts/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "dtype": "f32",
+           "data": "synthetic", "vs_baseline": None,
+           "config": {"workload": f"{n} prompts, {int(lens.sum())} tokens, longest {int(lens.max())}, "
+                                  f"d_model {shape.d_model}, d_inner {shape.d_inner}, d_state {shape.d_state}"},
+           "tokens_per_s": float(lens.sum()) / ms * 1e3}
+    if not args.no_cpu_baseline:
+        from oracle import mamba
+        sample = 100
+        t0 = time.time()
+        ref = [mamba.classify(w, tokens[i, :lens[i]])[1] for i in range(sample)]
+        dt = time.time() - t0
+        got = ids.cpu().numpy()[:sample]
+        out["cpu_baseline"] = {"value": sample / dt, "unit": "prompts/s", "cores": 1, "kind": "oracle",
+                               "sample": f"the first {sample} prompts", "labels_equal": int((got == np.array(ref)).sum())}
+    cls.close()
+    print(json.dumps(out))
 
 
 def cpu_baseline(st, sd_, wt, wd, n_ctx, gamma, T, seed):

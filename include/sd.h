@@ -193,6 +193,66 @@ int sd_commit(sd_ctx *c, const int32_t *seq_ids /*dev*/, int32_t n_seq, int32_t 
 int sd_route(const float *W, const float *b, int32_t n_drafts, int32_t emb_dim, const float *prompt_emb,
              int32_t n, int32_t *draft_id, void *stream);
 
+/* ---- prompt classifier (Sections 2.4, 3.3.3): the second routing backend ----
+ *
+ * The classifier the paper describes: an embedding, one selective state-space ("Mamba")
+ * sequence layer, average pooling over the prompt's tokens and a linear layer, whose arg
+ * max names the draft.  For an embedded prompt u [L][d_model]:
+ *   (x, z)  = u W_in                               halves of width d_inner
+ *   x_t     = SiLU(b_conv + sum_j w_conv[:, j] x_{t-(d_conv-1)+j})   causal, zero history
+ *   (r,B,C) = x_t W_x                              widths dt_rank, d_state, d_state
+ *   Delta_t = softplus(r W_dt + b_dt)
+ *   h_t     = exp(Delta_t A) h_{t-1} + Delta_t B_t x_t,   A = -exp(a_log),  h_{-1} = 0
+ *   y_t     = (C_t . h_t + D x_t) SiLU(z_t),   o_t = y_t W_out
+ *   logits  = W_fc mean_t(o_t) + b_fc
+ * All arithmetic is fp32.  No normalisation and no residual surround the layer.  u W_in depends on
+ * the token id alone, so the library multiplies the embedding and W_in out once, at creation,
+ * into a [vocab][2 d_inner] table (device memory: 8 vocab d_inner bytes). */
+typedef struct sd_classifier sd_classifier; /* opaque: the classifier's weights on one device */
+
+typedef struct sd_classifier_shape {
+    int32_t vocab;     /* >= 1 */
+    int32_t d_model;   /* 1..512 */
+    int32_t d_inner;   /* a multiple of 64 in 64..512; d_inner * (dt_rank + 2 d_state + 16) + d_model floats must fit
+                          64 KB of LDS (else SD_EINVAL) */
+    int32_t d_state;   /* 1..16 */
+    int32_t dt_rank;   /* 1..16 */
+    int32_t d_conv;    /* 1..4 */
+    int32_t n_classes; /* 1..64 */
+} sd_classifier_shape;
+
+/* Host pointers, fp32, read before sd_classifier_create returns (the library keeps its own
+ * device copy).  Matrices are [in features][out features] unless stated. */
+typedef struct sd_classifier_weights {
+    const float *emb;    /* [vocab][d_model] */
+    const float *w_in;   /* [d_model][2 d_inner]: x columns first, then z */
+    const float *conv_w; /* [d_inner][d_conv]: the last tap meets the current token */
+    const float *conv_b; /* [d_inner] */
+    const float *w_x;    /* [d_inner][dt_rank + 2 d_state]: r, then B, then C */
+    const float *w_dt;   /* [dt_rank][d_inner] */
+    const float *b_dt;   /* [d_inner] */
+    const float *a_log;  /* [d_inner][d_state] */
+    const float *d;      /* [d_inner] */
+    const float *w_out;  /* [d_inner][d_model] */
+    const float *w_fc;   /* [n_classes][d_model] */
+    const float *b_fc;   /* [n_classes] */
+} sd_classifier_weights;
+
+/* Builds a classifier on the current device.  SD_EINVAL for a null pointer or a shape outside
+ * the ranges above, SD_EHIP if the device copy fails; *out is NULL on failure. */
+int sd_classifier_create(const sd_classifier_shape *shape, const sd_classifier_weights *w, sd_classifier **out);
+void sd_classifier_destroy(sd_classifier *c); /* NULL is a no-op; synchronise the streams that use it first */
+
+/* Routing by the classifier: draft_id[i] = arg max of prompt i's logits, ties to the lowest id.
+ *   tokens  dev int32 [n][max_len]: prompt i's ids in its first lens[i] slots (the rest is ignored)
+ *   lens    dev int32 [n], clamped to [0, max_len]; an empty prompt pools to zero (logits = b_fc)
+ *   logits  dev fp32 [n][n_classes], or NULL if not wanted
+ *   draft_id dev int32 [n]; -1 for a prompt holding an id outside [0, vocab) (such a token is
+ *            embedded as zero and the prompt's logits are still written)
+ * Only enqueues one kernel on `stream` (one workgroup per prompt); never synchronises or allocates. */
+int sd_route_classifier(const sd_classifier *c, const int32_t *tokens, const int32_t *lens, int32_t n,
+                        int32_t max_len, float *logits, int32_t *draft_id, void *stream);
+
 /* ---- candidate-count policy (host only: no GPU call, plain host pointers) ---- */
 
 /* Equation 1 (Section 1): the expected speed-up over autoregressive decoding with gamma

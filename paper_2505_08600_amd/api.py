@@ -23,7 +23,8 @@ SD_FP32, SD_BF16 = 0, 1
 EXPORTS = ["sd_load_model", "sd_free_model", "sd_ctx_create", "sd_ctx_free", "sd_ctx_attach", "sd_ctx_set_tokens",
            "sd_prefill", "sd_draft", "sd_verify", "sd_commit", "sd_route", "sd_ctx_sync", "sd_ctx_get_tokens",
            "sd_ctx_set_kv", "sd_ctx_truncate", "sd_debug_read", "sd_debug_layout_index", "sd_last_logits", "sd_set_option", "sd_profile_read", "sd_last_error",
-           "sd_eq1_speedup", "sd_choose_gamma", "sd_alpha_hat", "sd_model_set_lora", "sd_ctx_set_adapters"]
+           "sd_eq1_speedup", "sd_choose_gamma", "sd_alpha_hat", "sd_model_set_lora", "sd_ctx_set_adapters",
+           "sd_classifier_create", "sd_classifier_destroy", "sd_route_classifier"]
 
 
 class SdError(RuntimeError):
@@ -47,6 +48,17 @@ class _Weights(C.Structure):
 class _LoraW(C.Structure):
     _fields_ = [("n_adapters", C.c_int32), ("rank", C.c_int32), ("scale", C.c_float)] + \
                [(n, C.POINTER(C.c_void_p)) for n in ("a_q", "b_q", "a_k", "b_k", "a_v", "b_v", "a_o", "b_o")]
+
+
+CLASSIFIER_WEIGHTS = ("emb", "w_in", "conv_w", "conv_b", "w_x", "w_dt", "b_dt", "a_log", "d", "w_out", "w_fc", "b_fc")
+
+
+class _ClsShape(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("vocab", "d_model", "d_inner", "d_state", "dt_rank", "d_conv", "n_classes")]
+
+
+class _ClsWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in CLASSIFIER_WEIGHTS]
 
 
 def lib():
@@ -82,6 +94,10 @@ def lib():
         L.sd_last_error.restype = C.c_char_p
         L.sd_model_set_lora.argtypes = [vp, C.POINTER(_LoraW)]
         L.sd_ctx_set_adapters.argtypes = [vp, vp, vp]
+        L.sd_classifier_create.argtypes = [C.POINTER(_ClsShape), C.POINTER(_ClsWeights), C.POINTER(vp)]
+        L.sd_classifier_destroy.argtypes = [vp]
+        L.sd_classifier_destroy.restype = None
+        L.sd_route_classifier.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp]
         L.sd_eq1_speedup.argtypes = [C.c_double, i32, C.c_double]
         L.sd_eq1_speedup.restype = C.c_double
         L.sd_choose_gamma.argtypes = [C.c_double, C.c_double, i32, C.POINTER(C.c_double)]
@@ -326,6 +342,38 @@ def alpha_hat(n_accepted: Sequence[int], gamma: int) -> float:
     """sd_alpha_hat: accepted over examined candidates (host only)."""
     a = _np_i32(n_accepted)
     return float(lib().sd_alpha_hat(a.ctypes.data_as(C.c_void_p), len(a), gamma))
+
+
+class Classifier:
+    """sd_classifier: the prompt classifier of Sections 2.4 and 3.3.3 on one device."""
+
+    def __init__(self, shape, weights: Dict[str, np.ndarray], device: int = 0):
+        self.shape, self.device = shape, device
+        s = _ClsShape(*[getattr(shape, n) for n, _ in _ClsShape._fields_])
+        arrs = {n: np.ascontiguousarray(weights[n], dtype=np.float32) for n in CLASSIFIER_WEIGHTS}
+        w = _ClsWeights(*[arrs[n].ctypes.data for n in CLASSIFIER_WEIGHTS])
+        h = C.c_void_p()
+        with torch.cuda.device(device):
+            _check(lib().sd_classifier_create(C.byref(s), C.byref(w), C.byref(h)))
+        self.h = h
+
+    def route(self, tokens: torch.Tensor, lens: torch.Tensor, draft_id: torch.Tensor,
+              logits: Optional[torch.Tensor] = None) -> None:
+        """sd_route_classifier on the current stream; tokens int32 [n][max_len], lens int32 [n]."""
+        with torch.cuda.device(self.device):
+            _check(lib().sd_route_classifier(self.h, _dp(tokens), _dp(lens), tokens.shape[0], tokens.shape[1],
+                                             _dp(logits), _dp(draft_id), _stream()))
+
+    def close(self):
+        if getattr(self, "h", None):
+            lib().sd_classifier_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 def sd_route(W: torch.Tensor, b: Optional[torch.Tensor], prompt_emb: torch.Tensor, draft_id: torch.Tensor) -> None:

@@ -48,6 +48,16 @@ def test_argument_errors_do_not_need_a_gpu():
     assert L.sd_model_set_lora(None, None) == api.SD_EINVAL
     assert L.sd_ctx_set_adapters(None, None, None) == api.SD_EINVAL
     assert L.sd_free_model(None) == api.SD_OK and L.sd_ctx_free(None) == api.SD_OK
+    assert L.sd_classifier_create(None, None, None) == api.SD_EINVAL
+    assert L.sd_route_classifier(None, None, None, 1, 1, None, None, None) == api.SD_EINVAL
+    L.sd_classifier_destroy(None)
+    shape = api._ClsShape(100, 32, 96, 8, 4, 4, 3)              # d_inner not a multiple of 64
+    cw, ch = api._ClsWeights(), C.c_void_p(1)
+    assert L.sd_classifier_create(C.byref(shape), C.byref(cw), C.byref(ch)) == api.SD_EINVAL and not ch.value
+    assert b"d_inner" in L.sd_last_error()
+    shape.d_inner = 128
+    assert L.sd_classifier_create(C.byref(shape), C.byref(cw), C.byref(ch)) == api.SD_EINVAL  # null weights
+    assert b"null weight" in L.sd_last_error()
 
 
 def test_product_package_does_not_import_the_oracle():
