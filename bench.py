@@ -49,8 +49,8 @@ def main():
                     help="side measurement: route 400 synthetic prompts with the prompt classifier (own JSON line)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU only: this build has no multi-GPU path (sequences are independent; "
-              "see DESIGN.md for how it would shard). Run with --gpus 1.", file=sys.stderr)
+        print("bench.py measures one GPU only: this build has no multi-GPU path (sequences are independent, so a "
+              "batch would shard by sequence with no communication inside a step). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
