@@ -103,7 +103,7 @@ classifier_kernel(ClsView v, const int32_t *__restrict__ tokens, const int32_t *
     }
 #pragma unroll
     for (int n = 0; n < CLS_MAX_STATE; ++n) {
-        A[n] = n < v.d_state ? -expf(v.a_log[c * v.d_state + n]) : 0.f;
+        A[n] = n < v.d_state ? -expf(v.a_log[c * v.d_state + n]) * 1.44269504088896f : 0.f; // times log2(e): decay = 2^(Delta A)
         h[n] = 0.f;
     }
 #pragma unroll
@@ -150,7 +150,7 @@ classifier_kernel(ClsView v, const int32_t *__restrict__ tokens, const int32_t *
             float pre = cb;
 #pragma unroll
             for (int j = 0; j < CLS_MAX_CONV; ++j) pre = fmaf(cw[j], xh[j], pre);
-            x[t] = __fdividef(pre, 1.f + __expf(-pre));
+            x[t] = pre * __builtin_amdgcn_rcpf(1.f + __expf(-pre));
             z[t] = nz[t];
         }
         *(float4 *)(s_x + c * CLS_TC) = make_float4(x[0], x[1], x[2], x[3]);
@@ -196,15 +196,17 @@ classifier_kernel(ClsView v, const int32_t *__restrict__ tokens, const int32_t *
             float dt = bdt;
 #pragma unroll
             for (int r = 0; r < CLS_MAX_RANK; ++r) dt = fmaf(dbc[r], wdt[r], dt);
-            const float delta = dt > 20.f ? dt : log1pf(__expf(dt));
+            // softplus = log1p(e^dt): log(u) e / (u - 1) with u = 1 + e undoes the rounding of u (steps are ~1e-3..0.1)
+            const float e = __expf(dt), u = 1.f + e;
+            const float delta = dt > 20.f ? dt : (u == 1.f ? e : logf(u) * e * __builtin_amdgcn_rcpf(u - 1.f));
             const float dx = delta * x[t];
             float acc = 0.f;
 #pragma unroll
             for (int n = 0; n < CLS_MAX_STATE; ++n) {
-                h[n] = fmaf(__expf(delta * A[n]), h[n], dx * dbc[16 + n]);
+                h[n] = fmaf(__builtin_amdgcn_exp2f(delta * A[n]), h[n], dx * dbc[16 + n]);
                 acc = fmaf(dbc[32 + n], h[n], acc);
             }
-            pooled += (acc + D * x[t]) * __fdividef(z[t], 1.f + __expf(-z[t]));
+            pooled += (acc + D * x[t]) * z[t] * __builtin_amdgcn_rcpf(1.f + __expf(-z[t]));
         }
     }
     if (bad) s_bad = 1;
