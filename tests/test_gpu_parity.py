@@ -596,6 +596,87 @@ def test_lora_adapters_chosen_per_sequence_match_oracle(shape_name, tol):
     gm.close()
 
 
+def test_online_path_classifier_routes_to_adapters_of_one_base_draft():
+    """The whole online path in its shared-base form (Sections 2.3, 2.4): the prompt classifier labels each
+    prompt from its token ids, the label names the low-rank adapter of the one base draft (the last class
+    means the plain base), ALL sequences draft in one batch, the target verifies them in one call.  Every
+    sequence must behave as it does alone in the oracle with the adapter the oracle's classifier picks."""
+    from oracle import mamba
+    _say("online path: classifier -> adapters -> one draft batch -> verify")
+    gamma, T, B, n_tok, seed = 4, 0.8, 9, 14, 97
+    st_ = dg.SHAPES["small_target_bf16"]
+    V = st_.vocab
+    sd_ = dg.ModelShape("d_shared", 2, 128, 2, 64, 384, V, dg.BF16)
+    cs = dataclasses.replace(dg.CLASSIFIER_TINY, name="classifier_online", vocab=V, n_classes=4)
+    wt = dg.make_weights(st_, seed, BF16_LM_SCALE)
+    wd = dg.make_weights(sd_, seed + 1, BF16_LM_SCALE)
+    lora = dg.make_lora(sd_, seed + 2, n_adapters=3, rank=8, std_a=0.05, std_b=0.05)
+    wc = dg.make_classifier(cs, 103)     # a seed whose labels cover all four classes with clear margins
+    lens = dg.make_prompt_lengths(seed, B, 16, 90)
+    prompts = [[int(t) for t in dg.make_prompt(seed, b, int(lens[b]), V)] for b in range(B)]
+    # routing on both sides
+    max_len = int(lens.max())
+    tok = np.zeros((B, max_len), np.int32)
+    for b in range(B):
+        tok[b, :lens[b]] = prompts[b]
+    ids_g = torch.zeros(B, dtype=torch.int32, device="cuda")
+    cls = api.Classifier(cs, wc)
+    cls.route(H.dev(tok), H.dev(lens.astype(np.int32)), ids_g)
+    labels = [mamba.classify(wc, prompts[b])[1] for b in range(B)]
+    assert ids_g.cpu().numpy().tolist() == labels and len(set(labels)) == 4, labels
+    cls.close()
+    adapters = [l if l < 3 else -1 for l in labels]
+    # oracle: every sequence on its own, with its adapter
+    ot, od = oracle.OracleModel(st_, wt), oracle.OracleModel(sd_, wd)
+    od.set_lora(lora, 2.0)
+    trajs = []
+    for b in range(B):
+        cap = len(prompts[b]) + n_tok + 2 * gamma + 4
+        _, steps = oracle.sd_generate(ot.new_seq(cap), od.new_seq(cap, adapters[b]), prompts[b], gamma, T, n_tok,
+                                      H.uf(seed, dg.DRAFT_STREAM, b), H.uf(seed, dg.VERIFY_STREAM, b), keep_logits=True)
+        trajs.append(steps)
+    n_steps = min(len(t) for t in trajs)
+    gt = api.Model(st_, wt, max_rows=B * (gamma + 1), max_pos=256)
+    gd = api.Model(sd_, wd, max_rows=2 * B, max_pos=256)
+    gd.set_lora(lora, 2.0)
+    ctx = api.Context([len(p) + (n_steps + 1) * (gamma + 1) + 8 for p in prompts])
+    ctx.attach(gt)
+    ctx.attach(gd)
+    ctx.set_adapters(gd, adapters)
+    H.gpu_prefill(ctx, [gt, gd], prompts)
+    na = torch.zeros(B, dtype=torch.int32, device="cuda")
+    nx = torch.zeros(B, dtype=torch.int32, device="cuda")
+    cand = torch.zeros((B, gamma), dtype=torch.int32, device="cuda")
+    q = torch.zeros((B, gamma, V), dtype=torch.float32, device="cuda")
+    flagged = 0
+    for k in range(n_steps):
+        api.sd_draft(gd, ctx, None, B, gamma, T, H.dev(np.stack([trajs[b][k].u_draft for b in range(B)])), cand, q)
+        cg, qg = cand.cpu().numpy(), q.cpu().numpy()
+        for b in range(B):
+            f, first_bad, _ = H.check_draft_step(trajs[b][k], cg[b], qg[b], T, dg.BF16, V)
+            flagged += int(f)
+            assert first_bad is None, "a flagged draft candidate would need a per-sequence re-feed here"
+        cand_all = H.dev(np.stack([trajs[b][k].cand for b in range(B)]).astype(np.int32))
+        q_all = H.dev(np.stack([trajs[b][k].q for b in range(B)]))
+        uv = H.dev(np.stack([trajs[b][k].u_verify for b in range(B)]))
+        api.sd_verify(gt, ctx, None, B, gamma, T, cand_all, q_all, uv, na, nx, commit=False)
+        lg = gt.last_logits().cpu().numpy().reshape(B, gamma + 1, V)
+        na_h, nx_h = na.cpu().numpy(), nx.cpu().numpy()
+        for b in range(B):
+            f, _, _ = H.check_verify_step(trajs[b][k], int(na_h[b]), int(nx_h[b]), lg[b], T, dg.BF16, V)
+            flagged += int(f)
+        api.sd_commit(ctx, None, B, gamma, cand_all, H.dev(np.array([trajs[b][k].n_acc for b in range(B)], np.int32)),
+                      H.dev(np.array([trajs[b][k].next_token for b in range(B)], np.int32)))
+    nt, kv = ctx.sync(gt)
+    for b in range(B):
+        assert nt[b] == len(prompts[b]) + sum(s.n_acc + 1 for s in trajs[b][:n_steps]) and kv[b] == nt[b] - 1
+    _say(f"  labels={labels} steps={n_steps} flagged={flagged}")
+    assert flagged <= 2
+    ctx.close()
+    gt.close()
+    gd.close()
+
+
 def test_draft_groups_on_separate_streams_match_sequential_calls():
     """The drafts of a routed batch are independent models with workspaces of their own, so their sd_draft
     calls may run on different streams at the same time (all at the default priority).  Four drafts of
