@@ -249,7 +249,8 @@ void sd_classifier_destroy(sd_classifier *c); /* NULL is a no-op; synchronise th
  *   logits  dev fp32 [n][n_classes], or NULL if not wanted
  *   draft_id dev int32 [n]; -1 for a prompt holding an id outside [0, vocab) (such a token is
  *            embedded as zero and the prompt's logits are still written)
- * Only enqueues one kernel on `stream` (one workgroup per prompt); never synchronises or allocates. */
+ * Only enqueues one kernel on `stream` (one workgroup per prompt); never synchronises or allocates.
+ * SD_EINVAL for a null pointer, n or max_len below 1, or a current device other than the classifier's. */
 int sd_route_classifier(const sd_classifier *c, const int32_t *tokens, const int32_t *lens, int32_t n,
                         int32_t max_len, float *logits, int32_t *draft_id, void *stream);
 

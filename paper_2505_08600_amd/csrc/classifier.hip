@@ -318,6 +318,9 @@ extern "C" int sd_route_classifier(const sd_classifier *c, const int32_t *tokens
 {
     if (!c || !tokens || !lens || !draft_id) return sd_fail(SD_EINVAL, "sd_route_classifier: null argument");
     if (n < 1 || max_len < 1) return sd_fail(SD_EINVAL, "sd_route_classifier: non-positive size");
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != c->device)
+        return sd_fail(SD_EINVAL, "sd_route_classifier: the classifier was created on another device");
     hipLaunchKernelGGL(classifier_kernel, dim3(n), dim3(c->v.d_inner), c->lds_bytes, (hipStream_t)stream, c->v, tokens,
                        lens, max_len, logits, draft_id);
     hipError_t e = hipGetLastError();
