@@ -277,3 +277,62 @@ def free_running(pair: Pair, prompt, gamma, T, n_tokens, seed):
     toks = ctx.get_tokens(0)[len(prompt):len(prompt) + n_tokens]
     ctx.close()
     return [int(t) for t in toks], steps, [int(t.item()) for t in n_acc_log]
+
+
+def batched_teacher_forced(gt, gd, ot, od, prompts, gamma, T, n_tok, seed, dtype, adapters=None):
+    """A ragged batch through ONE draft model and the target: every sequence's oracle trajectory is
+    computed on its own (with its adapter, if any); the HIP path drafts all sequences in one call and
+    verifies them in one call, step by step along those trajectories.  -> (steps, flagged)"""
+    B = len(prompts)
+    V = gt.shape.vocab
+    trajs = []
+    for b in range(B):
+        cap = len(prompts[b]) + n_tok + 2 * gamma + 4
+        dseq = od.new_seq(cap, adapters[b]) if adapters is not None else od.new_seq(cap)
+        _, steps = oracle.sd_generate(ot.new_seq(cap), dseq, prompts[b], gamma, T, n_tok,
+                                      uf(seed, dg.DRAFT_STREAM, b), uf(seed, dg.VERIFY_STREAM, b), keep_logits=True)
+        trajs.append(steps)
+    n_steps = min(len(t) for t in trajs)
+    ctx = api.Context([len(p) + (n_steps + 1) * (gamma + 1) + 8 for p in prompts])
+    ctx.attach(gt)
+    ctx.attach(gd)
+    if adapters is not None:
+        ctx.set_adapters(gd, adapters)
+    gpu_prefill(ctx, [gt, gd], prompts)
+    na = torch.zeros(B, dtype=torch.int32, device="cuda")
+    nx = torch.zeros(B, dtype=torch.int32, device="cuda")
+    cand = torch.zeros((B, gamma), dtype=torch.int32, device="cuda")
+    q = torch.zeros((B, gamma, V), dtype=torch.float32, device="cuda") if T > 0 else None
+    flagged = 0
+    for k in range(n_steps):
+        ud = dev(np.stack([trajs[b][k].u_draft for b in range(B)])) if T > 0 else None
+        api.sd_draft(gd, ctx, None, B, gamma, T, ud, cand, q)
+        cg = cand.cpu().numpy()
+        qg = q.cpu().numpy() if T > 0 else None
+        refeed = []
+        for b in range(B):
+            f, first_bad, _ = check_draft_step(trajs[b][k], cg[b], qg[b] if T > 0 else None, T, dtype, V)
+            flagged += int(f)
+            if first_bad is not None:
+                refeed.append((b, trajs[b][k].n_ctx - 1 + first_bad))
+        cand_all = dev(np.stack([trajs[b][k].cand for b in range(B)]).astype(np.int32))
+        q_all = dev(np.stack([trajs[b][k].q for b in range(B)])) if T > 0 else None
+        uv = dev(np.stack([trajs[b][k].u_verify for b in range(B)])) if T > 0 else None
+        api.sd_verify(gt, ctx, None, B, gamma, T, cand_all, q_all, uv, na, nx, commit=False)
+        lg = gt.last_logits().cpu().numpy().reshape(B, gamma + 1, V)
+        na_h, nx_h = na.cpu().numpy(), nx.cpu().numpy()
+        for b in range(B):
+            f, _, _ = check_verify_step(trajs[b][k], int(na_h[b]), int(nx_h[b]), lg[b], T, dtype, V)
+            flagged += int(f)
+        api.sd_commit(ctx, None, B, gamma, cand_all, dev(np.array([trajs[b][k].n_acc for b in range(B)], np.int32)),
+                      dev(np.array([trajs[b][k].next_token for b in range(B)], np.int32)))
+        for b, keep in refeed:   # that draft cache holds rows of other candidates: roll back and re-feed
+            torch.cuda.synchronize()
+            ctx.truncate(gd, b, keep)
+            api.sd_prefill(gd, ctx, dev(np.array([b], np.int32)), 1, gamma + 2)
+    nt, kv = ctx.sync(gt)
+    for b in range(B):
+        assert nt[b] == len(prompts[b]) + sum(s.n_acc + 1 for s in trajs[b][:n_steps]) and kv[b] == nt[b] - 1
+    ctx.close()
+    return n_steps, flagged
+
