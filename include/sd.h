@@ -55,7 +55,9 @@ enum { SD_FP32 = 0, SD_BF16 = 1 };
 /* LLaMA-style decoder shape (Section 3.1 "Models"): pre-norm blocks with RMSNorm,
  * rotary embedding (rotate-half pairing, angle pos * rope_base^(-2i/head_dim)),
  * multi-head causal attention (n_kv_heads == n_heads), SwiGLU FFN, untied LM head,
- * no biases.  n_heads * head_dim must equal d_model; head_dim is 64 or 128.
+ * no biases.  n_heads * head_dim must equal d_model; head_dim is 16, 32, 64 or 128 (the
+ * matrix-core attention kernels take 64 and 128, the others run on the plain kernels);
+ * vocab is a multiple of 4.
  * dtype SD_BF16: weights, KV cache and GEMM input activations are bf16, all
  * accumulation, the residual stream, softmax and logits are fp32.
  * dtype SD_FP32: everything fp32.
@@ -121,10 +123,12 @@ int sd_model_set_lora(sd_model *m, const sd_lora_weights *w);
 int sd_ctx_create(int32_t batch, const int32_t *caps, sd_ctx **out);
 int sd_ctx_free(sd_ctx *c);
 
-/* Allocate model m's KV cache for every sequence of the context (K as
- * [layer][head][token][head_dim], V transposed as [layer][head][head_dim][token],
- * tokens of all sequences concatenated at their capacity offsets).  At most 8
- * models per context.  Synchronises. */
+/* Allocate model m's KV cache for every sequence of the context: per layer and head,
+ * the tokens of all sequences concatenated at their capacity offsets, K and V each in
+ * 32-token tiles stored in the order the attention kernels' matrix-core operands read
+ * them (V transposed within a tile).  The layout is internal: caches are filled by the
+ * forward passes, or by sd_ctx_set_kv from plain [token][head][head_dim] rows.  At most
+ * 8 models per context.  Synchronises. */
 int sd_ctx_attach(sd_ctx *c, sd_model *m);
 
 /* Replace the tokens of sequences seq_ids (HOST int32[n_seq], or NULL) with the
