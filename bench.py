@@ -9,6 +9,9 @@ by sd_verify (gamma+1 rows, accept/resample, commit).  Inputs (weights, prompt,
 uniforms, KV cache of the prefilled prompt) are resident in HBM before the timed
 region starts.
 
+Secondary objects on the same line: the verify pass alone and the whole routed step (four drafts of
+different shapes) at batch 32, plain autoregressive decoding through the same library, and the CPU oracle.
+
 Prints ONE JSON line.  `value` is verified candidate tokens per second over the
 whole step, B*gamma*K / t.  `roofline` is for the dominant kernel (the SwiGLU
 gate/up weight-streaming GEMM), timed live with HIP events on the launch stream in
@@ -232,6 +235,7 @@ def main():
 
     if not args.no_batch32:
         out["batch32_verify"] = batch32_verify(api, dg, torch, np, gt, st, seed, B32, LEN32, gamma)
+        out["batch32_step"] = batch32_step(api, dg, torch, np, gt, st, seed, B32, LEN32, gamma)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(st, sd_, wt, wd, args.prompt, gamma, T, seed)
     print(json.dumps(out))
@@ -274,6 +278,87 @@ def batch32_verify(api, dg, torch, np, gt, st, seed, B, len_range, gamma, T=0.7,
             "rows": M, "ms_verify": ms, "candidates_per_s": B * gamma / (ms * 1e-3),
             "mfma_tflops": flops / (ms * 1e-3) / 1e12, "mfma_peak_tflops": 2500.0,
             "mfma_frac": flops / (ms * 1e-3) / 1e12 / 2500.0}
+
+
+def batch32_step(api, dg, torch, np, gt, st, seed, B, len_range, gamma, T=0.7, steps=10, warmup=2):
+    """The whole step at config 3's batch: B prompts routed by the linear classifier to four drafts of different
+    shapes (68M shape; 4 and 6 layers of width 1024; 2 layers of width 2048), sequences ordered by draft so that
+    every group is a contiguous slice of the batch; a step = one sd_draft per group (each group on a stream of
+    its own) + one sd_verify (commit fused) over all B sequences.  Same candidate-token accounting as the headline value."""
+    V = st.vocab
+    shapes = [dg.SHAPES[n] for n in ("draft_a", "draft_b", "draft_c", "draft_d")]
+    Wr, br = dg.make_router(seed + 8)
+    emb = dg.make_prompt_embeddings(seed + 8, B)
+    ids = torch.zeros(B, dtype=torch.int32, device="cuda")
+    api.sd_route(torch.from_numpy(Wr).cuda(), torch.from_numpy(br).cuda(), torch.from_numpy(emb).cuda(), ids)
+    route = np.sort(ids.cpu().numpy(), kind="stable")     # batch order = by routed draft
+    bounds = [(int(np.searchsorted(route, g, "left")), int(np.searchsorted(route, g, "right"))) for g in range(4)]
+    lens = dg.make_prompt_lengths(seed + 8, B, len_range[0], len_range[1])
+    prompts = [[int(t) for t in dg.make_prompt(seed + 8, b, int(lens[b]), V)] for b in range(B)]
+    n_total = steps + warmup
+    gds = [api.Model(sh, dg.make_weights(sh, seed + 20 + i, threads=16), max_rows=2 * B,
+                     max_pos=len_range[1] + n_total * (gamma + 1) + 64) for i, sh in enumerate(shapes)]
+    ctx = api.Context([int(l) + n_total * (gamma + 1) + 16 for l in lens])
+    ctx.attach(gt)
+    for gd in gds:
+        ctx.attach(gd)
+    ctx.set_tokens(prompts)
+    api.sd_prefill(gt, ctx, None, B, int(lens.max()) - 1)
+    gid = [torch.arange(a, b, dtype=torch.int32, device="cuda") for a, b in bounds]
+    for g, (a, b) in enumerate(bounds):
+        if b > a:
+            api.sd_prefill(gds[g], ctx, gid[g], b - a, int(lens[a:b].max()) - 1)
+    torch.cuda.synchronize()
+    gen = torch.Generator(device="cuda").manual_seed(seed + 8)
+    ud = torch.rand((n_total, B, gamma), device="cuda", generator=gen)
+    uv = torch.rand((n_total, B, gamma + 1), device="cuda", generator=gen)
+    cand = torch.zeros((B, gamma), dtype=torch.int32, device="cuda")
+    q = torch.zeros((B, gamma, V), dtype=torch.float32, device="cuda")
+    na = torch.zeros(B, dtype=torch.int32, device="cuda")
+    nx = torch.zeros(B, dtype=torch.int32, device="cuda")
+    na_log = torch.zeros((n_total, B), dtype=torch.int32, device="cuda")
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n_total)]
+
+    # the groups' drafts are independent models: one stream each (default priority), joined before the verify
+    main = torch.cuda.current_stream()
+    streams = [torch.cuda.Stream() for _ in range(4)]
+
+    def step(k):
+        ev[k][0].record()
+        for g, (a, b) in enumerate(bounds):
+            if b > a:
+                streams[g].wait_stream(main)
+                with torch.cuda.stream(streams[g]):
+                    api.sd_draft(gds[g], ctx, gid[g], b - a, gamma, T, ud[k, a:b], cand[a:b], q[a:b])
+        for g, (a, b) in enumerate(bounds):
+            if b > a:
+                main.wait_stream(streams[g])
+        ev[k][1].record()
+        api.sd_verify(gt, ctx, None, B, gamma, T, cand, q, uv[k], na, nx, True)
+        na_log[k].copy_(na)
+        ev[k][2].record()
+
+    for k in range(warmup):
+        step(k)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(warmup, n_total):
+        step(k)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ctx.sync()
+    acc = int(na_log[warmup:].sum().item())
+    ms_d = sum(ev[k][0].elapsed_time(ev[k][1]) for k in range(warmup, n_total)) / steps
+    ms_v = sum(ev[k][1].elapsed_time(ev[k][2]) for k in range(warmup, n_total)) / steps
+    out = {"workload": "config 3: %d prompts, lengths U[%d,%d], four routed drafts (groups of %s), gamma %d, T=%g" %
+                       (B, len_range[0], len_range[1], "/".join(str(b - a) for a, b in bounds), gamma, T),
+           "steps": steps, "ms_per_step": dt / steps * 1e3, "ms_draft_phase": ms_d, "ms_verify": ms_v,
+           "candidates_per_s": B * gamma * steps / dt, "accepted_tokens_per_s": acc / dt,
+           "emitted_tokens_per_s": (acc + B * steps) / dt, "acceptance_rate_eq2": acc / (B * gamma * steps)}
+    ctx.close()
+    for gd in gds:
+        gd.close()
+    return out
 
 
 def classifier_bench(api, dg, torch, np, args):
