@@ -68,3 +68,12 @@ def test_product_package_does_not_import_the_oracle():
         if f.endswith((".py", ".hip", ".h", ".cpp")):
             src = open(f).read()
             assert "oracle" not in src.lower() or f.endswith("datagen.py"), f
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU only: asking bench.py for more exits with a message instead of running."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2 and "one GPU only" in r.stderr and r.stdout.strip() == ""
