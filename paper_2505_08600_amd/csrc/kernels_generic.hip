@@ -909,10 +909,10 @@ __device__ float row_sumexp(const float *row, int V, float mx, float invT, float
 
 // ---------------------------------------------------------------- register-resident vocabulary rows
 // For V <= 32768 a 1024-thread block holds a whole fp32 row in registers: thread t keeps the float4s
-// number it*1024 + t, it < ROW_NSEG - the same element-to-thread assignment, and therefore the same
-// summation order, as the strided loops of the general kernels above, so both give identical results.
-// One pass over memory per row and a handful of barriers instead of one block reduction per 4096
-// elements.
+// number it*1024 + t, it < ROW_NSEG - the same element-to-thread assignment as the strided loops of the
+// general kernels above; the block-wide sums are added as trees here, so the two paths agree to rounding
+// (and exactly in the maximum and the arg max).  One pass over memory per row and a handful of barriers
+// instead of one block reduction per 4096 elements.
 #define ROW_NSEG 8
 #define ROW_THREADS 1024
 struct RowRegs {
@@ -920,12 +920,101 @@ struct RowRegs {
 };
 struct FastScratch {
     float wsum[ROW_THREADS / WAVE][ROW_NSEG];
-    float seg[ROW_NSEG];
     float red[32];
     int redi[32];
-    float base, target;
-    int seg_idx, pick, last_pos;
+    int pick;
 };
+static_assert(ROW_THREADS / WAVE == 16, "the cross-wave steps below read one LDS entry per lane of a 16-lane row");
+
+// A block of 16 waves on one compute unit spends its time in these reductions waiting, not computing, so
+// they use the cross-lane data path of the vector ALU (DPP) instead of LDS shuffles, and barriers that
+// wait for LDS traffic only: the q row a sampler has just stored (128 KB from one unit) then drains
+// while the inverse-CDF search runs instead of stalling its first barrier.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+template <int CTRL> __device__ __forceinline__ int dpp_i(int v) { return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true); }
+template <int CTRL> __device__ __forceinline__ float dpp_f(float v) { return __int_as_float(dpp_i<CTRL>(__float_as_int(v))); }
+__device__ __forceinline__ float lane_f(float v, int l) { return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l)); }
+// DPP controls: quad_perm [1,0,3,2] = 0xB1, [2,3,0,1] = 0x4E; row_half_mirror = 0x141; row_mirror = 0x140;
+// row_shr:n = 0x110 + n (lanes without a source read 0).
+// Sum over each 16-lane row, left in every lane of the row (both sides of each exchange add the same two
+// numbers, so all lanes agree bit for bit).
+__device__ __forceinline__ float row16_sum(float v)
+{
+    v += dpp_f<0xB1>(v);
+    v += dpp_f<0x4E>(v);
+    v += dpp_f<0x141>(v);
+    v += dpp_f<0x140>(v);
+    return v;
+}
+__device__ __forceinline__ int row16_max(int v)
+{
+    v = max(v, dpp_i<0xB1>(v));
+    v = max(v, dpp_i<0x4E>(v));
+    v = max(v, dpp_i<0x141>(v));
+    v = max(v, dpp_i<0x140>(v));
+    return v;
+}
+// largest value, lowest index among equals
+__device__ __forceinline__ void take_better(float &v, int &i, float ov, int oi)
+{
+    if (ov > v || (ov == v && oi < i)) {
+        v = ov;
+        i = oi;
+    }
+}
+__device__ __forceinline__ void row16_argmax(float &v, int &i)
+{
+    take_better(v, i, dpp_f<0xB1>(v), dpp_i<0xB1>(i));
+    take_better(v, i, dpp_f<0x4E>(v), dpp_i<0x4E>(i));
+    take_better(v, i, dpp_f<0x141>(v), dpp_i<0x141>(i));
+    take_better(v, i, dpp_f<0x140>(v), dpp_i<0x140>(i));
+}
+__device__ __forceinline__ float wave_sum_dpp(float v)
+{
+    v = row16_sum(v);
+    return (lane_f(v, 0) + lane_f(v, 16)) + (lane_f(v, 32) + lane_f(v, 48));
+}
+// Inclusive prefix sum over the 64 lanes: four shifted adds inside each row, then the totals of the rows before.
+__device__ __forceinline__ float wave_incl_scan_dpp(float v, int lane)
+{
+    v += dpp_f<0x111>(v);
+    v += dpp_f<0x112>(v);
+    v += dpp_f<0x114>(v);
+    v += dpp_f<0x118>(v);
+    const float t0 = lane_f(v, 15), t1 = lane_f(v, 31), t2 = lane_f(v, 47);
+    const int row = lane >> 4;
+    const float off = row == 0 ? 0.f : row == 1 ? t0 : row == 2 ? t0 + t1 : (t0 + t1) + t2;
+    return off + v;
+}
+// Block-wide arg max / sum for ROW_THREADS threads; every thread gets the result.
+__device__ void block_argmax_rows(float &v, int &idx, FastScratch *fs)
+{
+    const int w = threadIdx.x / WAVE, l = threadIdx.x % WAVE;
+    row16_argmax(v, idx);
+    float bv = lane_f(v, 0);
+    int bi = __builtin_amdgcn_readlane(idx, 0);
+    take_better(bv, bi, lane_f(v, 16), __builtin_amdgcn_readlane(idx, 16));
+    take_better(bv, bi, lane_f(v, 32), __builtin_amdgcn_readlane(idx, 32));
+    take_better(bv, bi, lane_f(v, 48), __builtin_amdgcn_readlane(idx, 48));
+    lds_barrier();
+    if (l == 0) {
+        fs->red[w] = bv;
+        fs->redi[w] = bi;
+    }
+    lds_barrier();
+    v = fs->red[l & 15];
+    idx = fs->redi[l & 15];
+    row16_argmax(v, idx);
+}
+__device__ float block_sum_rows(float v, FastScratch *fs)
+{
+    const int w = threadIdx.x / WAVE, l = threadIdx.x % WAVE;
+    v = wave_sum_dpp(v);
+    lds_barrier();
+    if (l == 0) fs->red[w] = v;
+    lds_barrier();
+    return row16_sum(fs->red[l & 15]);
+}
 
 __device__ __forceinline__ void row_load(const float *row, int V, float fill, RowRegs &r)
 {
@@ -953,7 +1042,7 @@ __device__ void row_stats_regs(RowRegs &r, float invT, FastScratch *fs, float &m
         if (f.z > bv) { bv = f.z; bi = 4 * v + 2; }
         if (f.w > bv) { bv = f.w; bi = 4 * v + 3; }
     }
-    block_argmax(bv, bi, fs->red, fs->redi);
+    block_argmax_rows(bv, bi, fs);
     mx = bv;
     am = bi;
     z = 1.f;
@@ -972,13 +1061,16 @@ __device__ void row_stats_regs(RowRegs &r, float invT, FastScratch *fs, float &m
             zl += f.w;
             r.f[it] = f;
         }
-        z = block_sum(zl, fs->red);
+        z = block_sum_rows(zl, fs);
     }
 }
 
-// Inverse-CDF pick (same rule and arithmetic as block_pick_cdf) over weights held in registers.
+// Inverse-CDF pick (same rule as block_pick_cdf) over weights held in registers.
 __device__ int pick_regs(const RowRegs &w, int V, float u, FastScratch *fs, float *total_out)
 {
+    // Index order is (segment it, thread t, component c).  Segment totals are the waves' totals added as a
+    // tree; every thread works out the total Z, the segment holding u * Z and the sum before it for itself
+    // (no single-thread phase), then one block-wide scan of that segment's float4 sums places the element.
     const int lane = threadIdx.x % WAVE, wv = threadIdx.x / WAVE;
     int lastp = -1;
     float loc[ROW_NSEG];
@@ -990,58 +1082,50 @@ __device__ int pick_regs(const RowRegs &w, int V, float u, FastScratch *fs, floa
         if (f.y > 0.f) lastp = 4 * v + 1;
         if (f.z > 0.f) lastp = 4 * v + 2;
         if (f.w > 0.f) lastp = 4 * v + 3;
-        loc[it] = wave_sum(((f.x + f.y) + f.z) + f.w);
+        loc[it] = wave_sum_dpp(((f.x + f.y) + f.z) + f.w);
     }
-#pragma unroll
-    for (int o = WAVE / 2; o > 0; o >>= 1) lastp = max(lastp, __shfl_xor(lastp, o, WAVE));
-    __syncthreads(); // the scratch may still be in use by a previous call
+    lastp = row16_max(lastp);
+    lastp = max(max(__builtin_amdgcn_readlane(lastp, 0), __builtin_amdgcn_readlane(lastp, 16)),
+                max(__builtin_amdgcn_readlane(lastp, 32), __builtin_amdgcn_readlane(lastp, 48)));
+    lds_barrier(); // the scratch may still be in use by a previous call
     if (lane == 0) {
 #pragma unroll
         for (int it = 0; it < ROW_NSEG; it++) fs->wsum[wv][it] = loc[it];
         fs->redi[wv] = lastp;
     }
-    __syncthreads();
+    if (threadIdx.x == 0) fs->pick = 0x7fffffff;
+    lds_barrier();
     const int nseg = ((V + 3) / 4 + ROW_THREADS - 1) / ROW_THREADS;
-    if ((int)threadIdx.x < nseg) { // one thread per segment adds the wave sums in wave order
-        float t = 0.f;
-        for (int i = 0; i < ROW_THREADS / WAVE; i++) t += fs->wsum[i][threadIdx.x];
-        fs->seg[threadIdx.x] = t;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        float Z = 0.f;
-        for (int it = 0; it < nseg; it++) Z += fs->seg[it];
-        const float target = u * Z;
-        float cum = 0.f;
-        int found = -1;
-        for (int it = 0; it < nseg; it++) {
-            if (cum + fs->seg[it] > target) {
-                found = it;
-                break;
-            }
-            cum += fs->seg[it];
+    float seg[ROW_NSEG];
+#pragma unroll
+    for (int it = 0; it < ROW_NSEG; it++) seg[it] = row16_sum(fs->wsum[lane & 15][it]);
+    const int lp = max(row16_max(fs->redi[lane & 15]), 0); // last index with a positive weight (0 if there is none)
+    float Z = 0.f;
+#pragma unroll
+    for (int it = 0; it < ROW_NSEG; it++)
+        if (it < nseg) Z += seg[it];
+    const float target = u * Z;
+    float base = 0.f;
+    int sit = -1;
+#pragma unroll
+    for (int it = 0; it < ROW_NSEG; it++)
+        if (it < nseg && sit < 0) {
+            if (base + seg[it] > target) sit = it;
+            else base += seg[it];
         }
-        int lp = 0; // last index with a positive weight (0 if there is none)
-        for (int i = 0; i < ROW_THREADS / WAVE; i++) lp = max(lp, fs->redi[i]);
-        fs->seg_idx = found;
-        fs->base = cum;
-        fs->target = target;
-        fs->pick = 0x7fffffff;
-        fs->last_pos = lp;
-        if (total_out) *total_out = Z;
-    }
-    __syncthreads();
-    const int sit = fs->seg_idx;
-    if (sit >= 0) {
+    if (total_out) *total_out = Z;
+    if (sit >= 0) { // uniform over the block
         float4 f = w.f[0];
 #pragma unroll
         for (int it = 1; it < ROW_NSEG; it++)
             if (it == sit) f = w.f[it];
         const int v = sit * ROW_THREADS + threadIdx.x;
         const float l4 = ((f.x + f.y) + f.z) + f.w;
-        const float pre = block_excl_scan(l4, fs->red);
-        float cum = fs->base + pre;
-        const float target = fs->target;
+        const float inc = wave_incl_scan_dpp(l4, lane);
+        if (lane == WAVE - 1) fs->red[wv] = inc; // red was last read before the barrier above
+        lds_barrier();
+        const float before = row16_sum((lane & 15) < wv ? fs->red[lane & 15] : 0.f);
+        float cum = base + (before + inc - l4);
         if (cum <= target) {
             int k = -1;
             cum += f.x;
@@ -1061,10 +1145,10 @@ __device__ int pick_regs(const RowRegs &w, int V, float u, FastScratch *fs, floa
             if (k >= 0 && k < V) atomicMin(&fs->pick, k);
         }
     }
-    __syncthreads();
+    lds_barrier();
     int pick = fs->pick;
-    if (pick == 0x7fffffff) pick = fs->last_pos;
-    __syncthreads();
+    if (pick == 0x7fffffff) pick = lp;
+    lds_barrier();
     return pick;
 }
 
