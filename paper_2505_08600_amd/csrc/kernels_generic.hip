@@ -24,6 +24,79 @@ __device__ __forceinline__ float wave_max(float v)
     return v;
 }
 
+// The one-block-per-row kernels (norms, samplers, the verify tail) spend their time waiting in block
+// reductions, not computing.  These variants use the cross-lane data path of the vector ALU (DPP) instead
+// of LDS shuffles, combine the 16 waves' partial results one entry per lane, and use barriers that wait
+// for LDS traffic only, so that global stores issued before a reduction (the updated residual row, the q
+// row a sampler has just written) drain behind it instead of stalling its first barrier.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+template <int CTRL> __device__ __forceinline__ int dpp_i(int v) { return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true); }
+template <int CTRL> __device__ __forceinline__ float dpp_f(float v) { return __int_as_float(dpp_i<CTRL>(__float_as_int(v))); }
+__device__ __forceinline__ float lane_f(float v, int l) { return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l)); }
+// DPP controls: quad_perm [1,0,3,2] = 0xB1, [2,3,0,1] = 0x4E; row_half_mirror = 0x141; row_mirror = 0x140;
+// row_shr:n = 0x110 + n (lanes without a source read 0).
+// Sum over each 16-lane row, left in every lane of the row (both sides of each exchange add the same two
+// numbers, so all lanes agree bit for bit).
+__device__ __forceinline__ float row16_sum(float v)
+{
+    v += dpp_f<0xB1>(v);
+    v += dpp_f<0x4E>(v);
+    v += dpp_f<0x141>(v);
+    v += dpp_f<0x140>(v);
+    return v;
+}
+__device__ __forceinline__ int row16_max(int v)
+{
+    v = max(v, dpp_i<0xB1>(v));
+    v = max(v, dpp_i<0x4E>(v));
+    v = max(v, dpp_i<0x141>(v));
+    v = max(v, dpp_i<0x140>(v));
+    return v;
+}
+// largest value, lowest index among equals
+__device__ __forceinline__ void take_better(float &v, int &i, float ov, int oi)
+{
+    if (ov > v || (ov == v && oi < i)) {
+        v = ov;
+        i = oi;
+    }
+}
+__device__ __forceinline__ void row16_argmax(float &v, int &i)
+{
+    take_better(v, i, dpp_f<0xB1>(v), dpp_i<0xB1>(i));
+    take_better(v, i, dpp_f<0x4E>(v), dpp_i<0x4E>(i));
+    take_better(v, i, dpp_f<0x141>(v), dpp_i<0x141>(i));
+    take_better(v, i, dpp_f<0x140>(v), dpp_i<0x140>(i));
+}
+__device__ __forceinline__ float wave_sum_dpp(float v)
+{
+    v = row16_sum(v);
+    return (lane_f(v, 0) + lane_f(v, 16)) + (lane_f(v, 32) + lane_f(v, 48));
+}
+// Inclusive prefix sum over the 64 lanes: four shifted adds inside each row, then the totals of the rows before.
+__device__ __forceinline__ float wave_incl_scan_dpp(float v, int lane)
+{
+    v += dpp_f<0x111>(v);
+    v += dpp_f<0x112>(v);
+    v += dpp_f<0x114>(v);
+    v += dpp_f<0x118>(v);
+    const float t0 = lane_f(v, 15), t1 = lane_f(v, 31), t2 = lane_f(v, 47);
+    const int row = lane >> 4;
+    const float off = row == 0 ? 0.f : row == 1 ? t0 : row == 2 ? t0 + t1 : (t0 + t1) + t2;
+    return off + v;
+}
+// Sum over a block of exactly 16 waves; every thread gets the result.  red: 16 floats of LDS.
+__device__ __forceinline__ float block_sum16(float v, float *red)
+{
+    const int w = threadIdx.x / WAVE, l = threadIdx.x % WAVE;
+    v = wave_sum_dpp(v);
+    lds_barrier();
+    if (l == 0) red[w] = v;
+    lds_barrier();
+    return row16_sum(red[l & 15]);
+}
+
+
 // Sum over the block; every thread gets the result.  red: >= 32 floats of LDS.
 __device__ float block_sum(float v, float *red)
 {
@@ -468,7 +541,7 @@ __global__ __launch_bounds__(1024) void add_rmsnorm_kernel(float *x, const float
                                                            const float *g, const int32_t *row_map, int d, float eps,
                                                            T *out, ActView av)
 {
-    __shared__ float red[32];
+    __shared__ float red[16];
     int j = blockIdx.x;
     int src = row_map ? row_map[j] : j;
     float *xr = x + (size_t)src * d;
@@ -476,7 +549,7 @@ __global__ __launch_bounds__(1024) void add_rmsnorm_kernel(float *x, const float
     float ss = 0.f;
     const int nvec = d / 4; // d is a multiple of 4 (checked at load)
     constexpr int KEEP = 2; // vectors of the row a thread keeps in registers (d <= 8192)
-    float4 keep[KEEP];
+    float4 keep[KEEP], gain[KEEP];
     int it = 0;
     for (int v = threadIdx.x; v < nvec; v += blockDim.x, it++) {
         float4 a = *(const float4 *)(xr + 4 * v);
@@ -484,6 +557,8 @@ __global__ __launch_bounds__(1024) void add_rmsnorm_kernel(float *x, const float
 #pragma unroll
         for (int s = 0; s < ADDNORM_MAX_SLABS; s++)
             if (s < n_slabs) p[s] = *(const float4 *)(pr + (size_t)s * slab_stride + 4 * v);
+        // the gains are needed only after the reduction; loaded there they would add a memory round trip
+        if (it < KEEP) gain[it] = *(const float4 *)(g + 4 * v);
 #pragma unroll
         for (int s = 0; s < ADDNORM_MAX_SLABS; s++)
             if (s < n_slabs) {
@@ -496,12 +571,13 @@ __global__ __launch_bounds__(1024) void add_rmsnorm_kernel(float *x, const float
         if (it < KEEP) keep[it] = a;
         ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
     }
-    ss = block_sum(ss, red);
+    ss = block_sum16(ss, red); // 1024 threads; does not wait for the residual stores above
+    if (nvec > KEEP * (int)blockDim.x) __syncthreads(); // wider rows are read back below: let the stores land
     float inv = 1.0f / sqrtf(ss / (float)d + eps);
     it = 0;
     for (int v = threadIdx.x; v < nvec; v += blockDim.x, it++) {
         const float4 a = it < KEEP ? keep[it] : *(const float4 *)(xr + 4 * v);
-        const float4 gg = *(const float4 *)(g + 4 * v);
+        const float4 gg = it < KEEP ? gain[it] : *(const float4 *)(g + 4 * v);
         const size_t o = act_index(av, j, 4 * v, d); // 4 consecutive columns stay inside one K step
         store_act4(out, o, av.plane, a.x * inv * gg.x, a.y * inv * gg.y, a.z * inv * gg.z, a.w * inv * gg.w);
     }
@@ -926,66 +1002,6 @@ struct FastScratch {
 };
 static_assert(ROW_THREADS / WAVE == 16, "the cross-wave steps below read one LDS entry per lane of a 16-lane row");
 
-// A block of 16 waves on one compute unit spends its time in these reductions waiting, not computing, so
-// they use the cross-lane data path of the vector ALU (DPP) instead of LDS shuffles, and barriers that
-// wait for LDS traffic only: the q row a sampler has just stored (128 KB from one unit) then drains
-// while the inverse-CDF search runs instead of stalling its first barrier.
-__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
-template <int CTRL> __device__ __forceinline__ int dpp_i(int v) { return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true); }
-template <int CTRL> __device__ __forceinline__ float dpp_f(float v) { return __int_as_float(dpp_i<CTRL>(__float_as_int(v))); }
-__device__ __forceinline__ float lane_f(float v, int l) { return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l)); }
-// DPP controls: quad_perm [1,0,3,2] = 0xB1, [2,3,0,1] = 0x4E; row_half_mirror = 0x141; row_mirror = 0x140;
-// row_shr:n = 0x110 + n (lanes without a source read 0).
-// Sum over each 16-lane row, left in every lane of the row (both sides of each exchange add the same two
-// numbers, so all lanes agree bit for bit).
-__device__ __forceinline__ float row16_sum(float v)
-{
-    v += dpp_f<0xB1>(v);
-    v += dpp_f<0x4E>(v);
-    v += dpp_f<0x141>(v);
-    v += dpp_f<0x140>(v);
-    return v;
-}
-__device__ __forceinline__ int row16_max(int v)
-{
-    v = max(v, dpp_i<0xB1>(v));
-    v = max(v, dpp_i<0x4E>(v));
-    v = max(v, dpp_i<0x141>(v));
-    v = max(v, dpp_i<0x140>(v));
-    return v;
-}
-// largest value, lowest index among equals
-__device__ __forceinline__ void take_better(float &v, int &i, float ov, int oi)
-{
-    if (ov > v || (ov == v && oi < i)) {
-        v = ov;
-        i = oi;
-    }
-}
-__device__ __forceinline__ void row16_argmax(float &v, int &i)
-{
-    take_better(v, i, dpp_f<0xB1>(v), dpp_i<0xB1>(i));
-    take_better(v, i, dpp_f<0x4E>(v), dpp_i<0x4E>(i));
-    take_better(v, i, dpp_f<0x141>(v), dpp_i<0x141>(i));
-    take_better(v, i, dpp_f<0x140>(v), dpp_i<0x140>(i));
-}
-__device__ __forceinline__ float wave_sum_dpp(float v)
-{
-    v = row16_sum(v);
-    return (lane_f(v, 0) + lane_f(v, 16)) + (lane_f(v, 32) + lane_f(v, 48));
-}
-// Inclusive prefix sum over the 64 lanes: four shifted adds inside each row, then the totals of the rows before.
-__device__ __forceinline__ float wave_incl_scan_dpp(float v, int lane)
-{
-    v += dpp_f<0x111>(v);
-    v += dpp_f<0x112>(v);
-    v += dpp_f<0x114>(v);
-    v += dpp_f<0x118>(v);
-    const float t0 = lane_f(v, 15), t1 = lane_f(v, 31), t2 = lane_f(v, 47);
-    const int row = lane >> 4;
-    const float off = row == 0 ? 0.f : row == 1 ? t0 : row == 2 ? t0 + t1 : (t0 + t1) + t2;
-    return off + v;
-}
 // Block-wide arg max / sum for ROW_THREADS threads; every thread gets the result.
 __device__ void block_argmax_rows(float &v, int &idx, FastScratch *fs)
 {
@@ -1006,15 +1022,7 @@ __device__ void block_argmax_rows(float &v, int &idx, FastScratch *fs)
     idx = fs->redi[l & 15];
     row16_argmax(v, idx);
 }
-__device__ float block_sum_rows(float v, FastScratch *fs)
-{
-    const int w = threadIdx.x / WAVE, l = threadIdx.x % WAVE;
-    v = wave_sum_dpp(v);
-    lds_barrier();
-    if (l == 0) fs->red[w] = v;
-    lds_barrier();
-    return row16_sum(fs->red[l & 15]);
-}
+__device__ float block_sum_rows(float v, FastScratch *fs) { return block_sum16(v, fs->red); }
 
 __device__ __forceinline__ void row_load(const float *row, int V, float fill, RowRegs &r)
 {
