@@ -48,6 +48,11 @@ def main():
     ap.add_argument("--prompt", type=int, default=512)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy three times (known traffic, to scale HBM counters)")
+    ap.add_argument("--prefill-bench", action="store_true",
+                    help="side measurement: prompt prefill of the 7B-shape target at 512 / 2048 / 8192 tokens (own JSON line)")
+    ap.add_argument("--multi-lora", action="store_true",
+                    help="side measurement: draft phase of 32 routed sequences as four group calls vs one batch of the "
+                         "shared base with per-sequence adapters (own JSON line)")
     ap.add_argument("--classifier", action="store_true",
                     help="side measurement: route 400 synthetic prompts with the prompt classifier (own JSON line)")
     args = ap.parse_args()
@@ -75,6 +80,12 @@ def main():
     api.lib()
     if args.classifier:
         classifier_bench(api, dg, torch, np, args)
+        return
+    if args.prefill_bench:
+        prefill_bench(api, dg, torch, np, args)
+        return
+    if args.multi_lora:
+        multi_lora_bench(api, dg, torch, np, args)
         return
     seed, gamma, T, B = 2025, 5, float(args.temperature), 1
     st = dg.SHAPES["t7b"] if not args.layers else dg.with_layers(dg.SHAPES["t7b"], args.layers)
@@ -359,6 +370,102 @@ def batch32_step(api, dg, torch, np, gt, st, seed, B, len_range, gamma, T=0.7, s
     for gd in gds:
         gd.close()
     return out
+
+
+def prefill_bench(api, dg, torch, np, args):
+    """The step before the hot path: sd_prefill of one prompt into the 7B-shape target, for two workspace sizes
+    (max_rows decides how many 16-row groups one forward carries).  Issued MFMA work counts the hi and the lo
+    plane of every row (4 flops per parameter and token); attention is not counted."""
+    st = dg.SHAPES["t7b"] if not args.layers else dg.with_layers(dg.SHAPES["t7b"], args.layers)
+    wt = dg.make_weights(st, 2025, threads=16)
+    res = []
+    for max_rows in (192, 576):
+        gt = api.Model(st, wt, max_rows, 8300)
+        for n in (512, 2048, 8192):
+            prompt = [[int(t) for t in dg.make_prompt(2025, 0, n, st.vocab)]]
+            ctx = api.Context([n + 64])
+            ctx.attach(gt)
+            for rep in range(2):      # the second pass is the measured one
+                ctx.set_tokens(prompt)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                api.sd_prefill(gt, ctx, None, 1, n - 1)
+                torch.cuda.synchronize()
+                dt = time.perf_counter() - t0
+            ctx.sync()
+            res.append({"max_rows": max_rows, "prompt": n, "ms": dt * 1e3, "tokens_per_s": (n - 1) / dt,
+                        "mfma_tflops": 4.0 * (n - 1) * st.n_streamed_params() / dt / 1e12})
+            ctx.close()
+        gt.close()
+    best = max(r["tokens_per_s"] for r in res)
+    print(json.dumps({"metric": "prefill_tokens_per_s", "value": best, "unit": "tokens/s", "n_gpus": 1, "dtype": "bf16",
+                      "data": "synthetic", "higher_is_better": True, "vs_baseline": None,
+                      "config": {"workload": "prefill of one prompt, 7B-shape target, batch 1"}, "cases": res}))
+
+
+def multi_lora_bench(api, dg, torch, np, args):
+    """Draft phase of config 3's batch (32 prompts of 128..1024 tokens, gamma 5, T = 0.7) with the 68M-shape base
+    draft: one batch without adapters, four calls on the routed groups (what separate per-task drafts of this
+    shape cost), and one batch with four rank-8 adapters chosen per sequence (Section 2.3)."""
+    B, gamma, T, seed = 32, 5, 0.7, 2025
+    sh = dg.SHAPES["draft_a"]
+    V = sh.vocab
+    gd = api.Model(sh, dg.make_weights(sh, seed, threads=16), max_rows=2 * B, max_pos=1200)
+    lora = dg.make_lora(sh, seed + 1, n_adapters=4, rank=8)
+    Wr, br = dg.make_router(seed)
+    ids = torch.zeros(B, dtype=torch.int32, device="cuda")
+    api.sd_route(torch.from_numpy(Wr).cuda(), torch.from_numpy(br).cuda(),
+                 torch.from_numpy(dg.make_prompt_embeddings(seed, B)).cuda(), ids)
+    route = np.sort(ids.cpu().numpy(), kind="stable")
+    bounds = [(int(np.searchsorted(route, g, "left")), int(np.searchsorted(route, g, "right"))) for g in range(4)]
+    lens = dg.make_prompt_lengths(seed, B, 128, 1024)
+    prompts = [[int(t) for t in dg.make_prompt(seed, b, int(lens[b]), V)] for b in range(B)]
+    ctx = api.Context([int(l) + 64 for l in lens])
+    ctx.attach(gd)
+    ctx.set_tokens(prompts)
+    api.sd_prefill(gd, ctx, None, B, int(lens.max()) - 1)
+    torch.cuda.synchronize()
+    gen = torch.Generator(device="cuda").manual_seed(seed)
+    ud = torch.rand((B, gamma), device="cuda", generator=gen)
+    cand = torch.zeros((B, gamma), dtype=torch.int32, device="cuda")
+    q = torch.zeros((B, gamma, V), device="cuda")
+    gid = [torch.arange(a, b, dtype=torch.int32, device="cuda") for a, b in bounds]
+
+    def timed(fn):
+        ts = []
+        for rep in range(args.warmup + args.steps):
+            torch.cuda.synchronize()
+            for b in range(B):            # every repetition drafts from the same cache state
+                ctx.truncate(gd, b, int(lens[b]) - 1)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        return float(np.median(ts[args.warmup:]))
+
+    def groups():
+        for g, (a, b) in enumerate(bounds):
+            if b > a:
+                api.sd_draft(gd, ctx, gid[g], b - a, gamma, T, ud[a:b], cand[a:b], q[a:b])
+
+    ms_base = timed(lambda: api.sd_draft(gd, ctx, None, B, gamma, T, ud, cand, q))
+    ms_groups = timed(groups)
+    gd.set_lora(lora, 2.0)
+    ctx.set_adapters(gd, route.tolist())
+    ms_lora = timed(lambda: api.sd_draft(gd, ctx, None, B, gamma, T, ud, cand, q))
+    ctx.sync()
+    print(json.dumps({"metric": "multi_lora_draft_candidates_per_s", "value": B * gamma / ms_lora * 1e3,
+                      "unit": "candidate tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+                      "ms_per_step": ms_lora, "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+                      "vs_baseline": None,
+                      "config": {"workload": "draft phase, 32 sequences (groups of %s), 68M-shape base, gamma 5, T=0.7, "
+                                             "four rank-8 adapters on q,k,v,o" % "/".join(str(b - a) for a, b in bounds)},
+                      "ms_one_batch_no_adapters": ms_base, "ms_four_group_calls": ms_groups,
+                      "ms_one_batch_with_adapters": ms_lora}))
+    ctx.close()
+    gd.close()
 
 
 def classifier_bench(api, dg, torch, np, args):
