@@ -50,6 +50,9 @@ def main():
                     help="only run a plain 1 GiB device copy three times (known traffic, to scale HBM counters)")
     ap.add_argument("--prefill-bench", action="store_true",
                     help="side measurement: prompt prefill of the 7B-shape target at 512 / 2048 / 8192 tokens (own JSON line)")
+    ap.add_argument("--long-context", action="store_true",
+                    help="side measurement: the verify pass of configs 4 (13B shape, batch 32, context 2048) and 5 "
+                         "(7B shape, batch 64, contexts 1024..8192) with prefilled caches (own JSON line; minutes)")
     ap.add_argument("--multi-lora", action="store_true",
                     help="side measurement: draft phase of 32 routed sequences as four group calls vs one batch of the "
                          "shared base with per-sequence adapters (own JSON line)")
@@ -86,6 +89,9 @@ def main():
         return
     if args.multi_lora:
         multi_lora_bench(api, dg, torch, np, args)
+        return
+    if args.long_context:
+        long_context_bench(api, dg, torch, np, args)
         return
     seed, gamma, T, B = 2025, 5, float(args.temperature), 1
     st = dg.SHAPES["t7b"] if not args.layers else dg.with_layers(dg.SHAPES["t7b"], args.layers)
@@ -401,6 +407,58 @@ def prefill_bench(api, dg, torch, np, args):
     print(json.dumps({"metric": "prefill_tokens_per_s", "value": best, "unit": "tokens/s", "n_gpus": 1, "dtype": "bf16",
                       "data": "synthetic", "higher_is_better": True, "vs_baseline": None,
                       "config": {"workload": "prefill of one prompt, 7B-shape target, batch 1"}, "cases": res}))
+
+
+def long_context_bench(api, dg, torch, np, args):
+    """The verify pass of the two long-context configurations, caches filled by real prefills: config 4 (13B-shape
+    target, 32 sequences at context 2048, gamma 3 / 5 / 8) and config 5 (7B-shape target, 64 sequences with
+    contexts uniform in [1024, 8192], gamma 8).  Bytes = streamed weights + live KV of the call."""
+    res = []
+    for name, shape, B, lens, gammas in (("config 4", "t13b", 32, np.full(32, 2048, np.int32), (3, 5, 8)),
+                                         ("config 5", "t7b", 64, dg.make_prompt_lengths(5055, 64, 1024, 8192), (8,))):
+        st = dg.SHAPES[shape] if not args.layers else dg.with_layers(dg.SHAPES[shape], args.layers)
+        V, T = st.vocab, 1.0
+        t0 = time.time()
+        wt = dg.make_weights(st, 2025, threads=16)
+        gt = api.Model(st, wt, max(16 * B, B * (max(gammas) + 1)), int(lens.max()) + 64)   # 16 prompt rows per sequence and forward
+        del wt
+        prompts = [[int(t) for t in dg.make_prompt(2025, b, int(lens[b]), V)] for b in range(B)]
+        ctx = api.Context([int(l) + 64 for l in lens])
+        ctx.attach(gt)
+        ctx.set_tokens(prompts)
+        api.sd_prefill(gt, ctx, None, B, int(lens.max()) - 1)
+        torch.cuda.synchronize()
+        log(f"[bench] {name}: weights, upload and prefill of {int(lens.sum())} tokens in {time.time() - t0:.1f}s")
+        g = torch.Generator(device="cuda").manual_seed(2025)
+        for gamma in gammas:
+            cand = torch.randint(0, V, (B, gamma), dtype=torch.int32, device="cuda", generator=g)
+            q = torch.softmax(torch.randn((B, gamma, V), device="cuda", generator=g), dim=-1).contiguous()
+            u = torch.rand((B, gamma + 1), device="cuda", generator=g)
+            na = torch.zeros(B, dtype=torch.int32, device="cuda")
+            nx = torch.zeros(B, dtype=torch.int32, device="cuda")
+            ms, reps = 0.0, 5
+            for r in range(reps + 2):   # commit = False, then the cache lengths are rolled back
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                api.sd_verify(gt, ctx, None, B, gamma, T, cand, q, u, na, nx, False)
+                e1.record()
+                torch.cuda.synchronize()
+                if r >= 2:
+                    ms += e0.elapsed_time(e1) / reps
+                for b in range(B):
+                    ctx.truncate(gt, b, int(lens[b]) - 1)
+            M = B * (gamma + 1)
+            nbytes = st.n_streamed_params() * 2 + float(lens.sum()) * st.kv_bytes_per_token()
+            res.append({"config": name, "rows": M, "gamma": gamma, "ms_verify": ms, "bytes_gb": nbytes / 1e9,
+                        "tb_per_s": nbytes / ms / 1e9, "mfma_tflops": 4.0 * M * st.n_streamed_params() / ms / 1e9,
+                        "candidates_per_s": B * gamma / ms * 1e3})
+        ctx.sync()
+        ctx.close()
+        gt.close()
+    print(json.dumps({"metric": "long_context_verify_candidates_per_s", "value": res[-1]["candidates_per_s"],
+                      "unit": "candidate tokens/s", "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
+                      "higher_is_better": True, "vs_baseline": None,
+                      "config": {"workload": "verify pass of configs 4 and 5 (value: config 5)"}, "cases": res}))
 
 
 def multi_lora_bench(api, dg, torch, np, args):
