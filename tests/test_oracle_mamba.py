@@ -200,3 +200,58 @@ def test_unused_history_and_rank_slots_do_not_matter(field, axis):
         wx = w["w_x"]
         w2["w_x"] = np.concatenate([wx[:, :TINY.dt_rank], np.ones((TINY.d_inner, 2)), wx[:, TINY.dt_rank:]], axis=1)
     np.testing.assert_allclose(mamba.classify(w2, tok)[0], base, rtol=1e-12, atol=1e-14)
+
+
+# ---- planted mistakes: each plausible slip in the layer must be caught by at least one pin above
+
+_PINS = [test_scan_equals_the_unrolled_sum_with_cumulative_step_sizes,
+         test_time_invariant_case_reduces_to_library_filters,
+         test_two_token_prompt_by_hand,
+         test_layer_is_causal_and_prefix_consistent,
+         test_state_carries_information_beyond_the_convolution_window,
+         test_pooling_is_the_mean_over_tokens_and_labels_follow_the_logits]
+
+_MISTAKES = {
+    "convolution taps in reverse order": ('f["conv_w"][:, j] * x_in[s]', 'f["conv_w"][:, d_conv - 1 - j] * x_in[s]'),
+    "convolution looks ahead": ("s = t - (d_conv - 1) + j", "s = t + j"),
+    "convolution bias dropped": ('acc = f["conv_b"].copy()', 'acc = np.zeros_like(f["conv_b"])'),
+    "B and C exchanged": ("B = proj[:, dt_rank:dt_rank + d_state]\n    C = proj[:, dt_rank + d_state:]",
+                          "C = proj[:, dt_rank:dt_rank + d_state]\n    B = proj[:, dt_rank + d_state:]"),
+    "step size without its bias": ('softplus(r @ f["w_dt"] + f["b_dt"])', 'softplus(r @ f["w_dt"])'),
+    "exp instead of softplus": ('delta = softplus(r @ f["w_dt"] + f["b_dt"])', 'delta = np.exp(r @ f["w_dt"] + f["b_dt"])'),
+    "growing instead of decaying state": ('A = -np.exp(f["a_log"])', 'A = np.exp(f["a_log"])'),
+    "A used without the exponential": ('A = -np.exp(f["a_log"])', 'A = -f["a_log"]'),
+    "input not scaled by the step size": ("(delta[t] * x[t])[:, None] * B[t][None, :]", "x[t][:, None] * B[t][None, :]"),
+    "state read before it is updated": ("h = decay * h + (delta[t] * x[t])[:, None] * B[t][None, :]\n        y[t] = (h @ C[t]",
+                                        "y[t] = (h @ C[t]"),
+    "skip term dropped": ('(h @ C[t] + f["d"] * x[t])', "(h @ C[t])"),
+    "gate without SiLU": ("* silu(z[t])", "* z[t]"),
+    "gate and input halves exchanged": ("x_in, z = xz[:, :d_inner], xz[:, d_inner:]", "z, x_in = xz[:, :d_inner], xz[:, d_inner:]"),
+    "decay applied to the new input as well":
+        ("h = decay * h + (delta[t] * x[t])[:, None] * B[t][None, :]", "h = decay * (h + (delta[t] * x[t])[:, None] * B[t][None, :])"),
+}
+
+
+@pytest.mark.parametrize("name", sorted(_MISTAKES))
+def test_planted_mistake_is_caught(name, monkeypatch):
+    import inspect
+    old, new = _MISTAKES[name]
+    src = inspect.getsource(mamba.mamba_layer)
+    assert src.count(old) == 1, f"the oracle no longer contains the text this mistake replaces: {old!r}"
+    scope = dict(vars(mamba))
+    exec(src.replace(old, new), scope)
+    broken = scope["mamba_layer"]
+    u = np.asarray(_weights()["emb"][_prompt(TINY, 1, 9)])
+    try:
+        changed = not np.allclose(broken(_weights(), u)["o"], mamba.mamba_layer(_weights(), u)["o"], rtol=1e-9, atol=1e-12)
+    except IndexError:      # e.g. a convolution that reads past the end of the prompt
+        return
+    assert changed, "this edit does not change the result on the test input"
+    monkeypatch.setattr(mamba, "mamba_layer", broken)
+    caught = []
+    for pin in _PINS:
+        try:
+            pin()
+        except (AssertionError, IndexError):
+            caught.append(pin.__name__)
+    assert caught, f"no pin notices: {name}"
