@@ -15,7 +15,11 @@ _lib = None
 
 
 def build(force: bool = False) -> str:
-    """Compile the oracle with gcc (plain -O2, OpenMP over output rows)."""
+    """Compile the oracle with gcc (plain -O2, OpenMP over output rows).  SD_ORACLE_LIB names a library to load
+    instead: the test that plants mistakes points it at deliberately broken copies it has built."""
+    override = os.environ.get("SD_ORACLE_LIB")
+    if override:
+        return override
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-o", _LIB, _SRC, "-lm"])
     return _LIB
