@@ -1172,9 +1172,58 @@ __device__ __forceinline__ void row_scale(RowRegs &r, float invZ)
     }
 }
 
+// The single-row plan (PLAN_CAND, R = 1) of sequence slot j for the forward that feeds `tok`: the same entries,
+// checks and cache-length update as plan_kernel makes for that mode, written by the sampler block that has
+// just drawn the token.  seq_order keeps the order the catch-up plan of this draft call left (every
+// sequence grows by one row, so the ranking by length does not change).  One thread calls this.
+__device__ void plan_next_cand(const NextPlan &np, int j, int tok)
+{
+    const PlanView &pv = np.pv;
+    const CtxView &cv = np.cv;
+    const int b = np.seq_ids ? np.seq_ids[j] : j;
+    if (b < 0 || b >= cv.B) { // refuse out-of-range ids: the row stays unused
+        atomicOr(cv.status, 4);
+        pv.seq_b[j] = 0;
+        pv.seq_kv0[j] = 0;
+        pv.seq_nq[j] = 0;
+        pv.row_tok[j] = 0;
+        pv.row_pos[j] = 0;
+        pv.row_b[j] = 0;
+        pv.row_valid[j] = 0;
+        pv.lm_row[j] = j;
+        return;
+    }
+    const int n = cv.ntok[b];
+    int *kvp = cv.kvlen + (size_t)np.slot * cv.B + b;
+    int kv0 = *kvp, nq = 1;
+    const int cap = cv.cap[b];
+    if (n < 1) { // an empty sequence has no pending token
+        atomicOr(cv.status, 2);
+        nq = 0;
+    }
+    if (kv0 < 0) kv0 = 0;
+    if (kv0 + nq > cap) { // never write beyond the sequence's cache rows
+        atomicOr(cv.status, 1);
+        nq = cap - kv0 > 0 ? cap - kv0 : 0;
+    }
+    if (nq > 0 && (tok < 0 || tok >= np.vocab)) { // never index the embedding table out of range
+        atomicOr(cv.status, 16);
+        tok = 0;
+    }
+    pv.row_tok[j] = nq > 0 ? tok : 0;
+    pv.row_pos[j] = kv0;
+    pv.row_b[j] = b;
+    pv.row_valid[j] = nq > 0;
+    pv.seq_b[j] = b;
+    pv.seq_kv0[j] = kv0;
+    pv.seq_nq[j] = nq;
+    pv.lm_row[j] = j;
+    *kvp = kv0 + nq;
+}
+
 __global__ __launch_bounds__(ROW_THREADS) void draft_sample_fast_kernel(const float *logits, int V, float T,
                                                                          const float *u, int gamma, int idx,
-                                                                         int32_t *cand, float *q)
+                                                                         int32_t *cand, float *q, NextPlan next)
 {
     __shared__ FastScratch fs;
     const int j = blockIdx.x;
@@ -1184,7 +1233,10 @@ __global__ __launch_bounds__(ROW_THREADS) void draft_sample_fast_kernel(const fl
     int am;
     row_stats_regs(r, T > 0.f ? 1.0f / T : 0.f, &fs, mx, am, z);
     if (T == 0.f) {
-        if (threadIdx.x == 0) cand[j * gamma + idx] = am;
+        if (threadIdx.x == 0) {
+            cand[j * gamma + idx] = am;
+            if (next.enabled) plan_next_cand(next, j, am);
+        }
         return;
     }
     row_scale(r, 1.0f / z);
@@ -1202,14 +1254,17 @@ __global__ __launch_bounds__(ROW_THREADS) void draft_sample_fast_kernel(const fl
         }
     }
     const int pick = pick_regs(r, V, u[j * gamma + idx], &fs, nullptr);
-    if (threadIdx.x == 0) cand[j * gamma + idx] = pick;
+    if (threadIdx.x == 0) {
+        cand[j * gamma + idx] = pick;
+        if (next.enabled) plan_next_cand(next, j, pick);
+    }
 }
 
 // ---------------------------------------------------------------- draft: softmax + sample
 // One block per sequence.  T > 0: q = softmax(logits / T) is written in full and
 // the candidate drawn by inverse CDF; T == 0: candidate = argmax.
 __global__ __launch_bounds__(1024) void draft_sample_kernel(const float *logits, int V, float T, const float *u,
-                                                            int gamma, int idx, int32_t *cand, float *q)
+                                                            int gamma, int idx, int32_t *cand, float *q, NextPlan next)
 {
     __shared__ PickScratch ps;
     __shared__ float redv[32];
@@ -1220,7 +1275,10 @@ __global__ __launch_bounds__(1024) void draft_sample_kernel(const float *logits,
     int am;
     row_max_argmax(row, V, redv, redi, mx, am);
     if (T == 0.f) {
-        if (threadIdx.x == 0) cand[j * gamma + idx] = am;
+        if (threadIdx.x == 0) {
+            cand[j * gamma + idx] = am;
+            if (next.enabled) plan_next_cand(next, j, am);
+        }
         return;
     }
     float invT = 1.0f / T;
@@ -1253,17 +1311,21 @@ __global__ __launch_bounds__(1024) void draft_sample_kernel(const float *logits,
         return p;
     };
     int pick = block_pick_cdf(wfun, V, u[j * gamma + idx], &ps, nullptr);
-    if (threadIdx.x == 0) cand[j * gamma + idx] = pick;
+    if (threadIdx.x == 0) {
+        cand[j * gamma + idx] = pick;
+        if (next.enabled) plan_next_cand(next, j, pick);
+    }
 }
 
 hipError_t launch_draft_sample(hipStream_t s, const float *logits, int n_seq, int V, float T, const float *u,
-                               int gamma, int idx, int32_t *cand, float *q)
+                               int gamma, int idx, int32_t *cand, float *q, const NextPlan &next)
 {
     if (V <= ROW_NSEG * ROW_THREADS * 4)
         hipLaunchKernelGGL(draft_sample_fast_kernel, dim3(n_seq), dim3(ROW_THREADS), 0, s, logits, V, T, u, gamma, idx,
-                           cand, q);
+                           cand, q, next);
     else
-        hipLaunchKernelGGL(draft_sample_kernel, dim3(n_seq), dim3(1024), 0, s, logits, V, T, u, gamma, idx, cand, q);
+        hipLaunchKernelGGL(draft_sample_kernel, dim3(n_seq), dim3(1024), 0, s, logits, V, T, u, gamma, idx, cand, q,
+                           next);
     return hipGetLastError();
 }
 

@@ -718,7 +718,7 @@ static int stream_gemm(sd_model *m, hipStream_t s, const void *A, ActView a_av, 
 // groups of R rows per sequence, each group a plan slot of its own.
 static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, int R, int n_seq,
                    const int32_t *seq_ids, int upto_off, const int32_t *cand, int gamma, int cand_idx,
-                   bool want_logits, int G = 1)
+                   bool want_logits, int G = 1, bool plan_ready = false)
 {
     const sd_model_config &cf = m->cfg;
     const int n_slots = n_seq * G; // plan slots: what the attention kernels see as sequences
@@ -735,7 +735,7 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
     int kv_upper = c->len_upper + SD_MAX_GAMMA + 1;
     size_t lstride = (size_t)d * c->total_cap * m->esz;
     hipError_t ge;
-    { ProfScope ps(T_PLAN, s);
+    if (!plan_ready) { ProfScope ps(T_PLAN, s); // (the draft sampler lays out the single-row forwards that follow it)
     if (G > 1) FWD(launch_plan_prefill(s, R, G, n_seq, seq_ids, cv, slot, upto_off, V, pv));
     else FWD(launch_plan(s, mode, R, n_seq, seq_ids, cv, slot, upto_off, cand, gamma, cand_idx, V, pv)); }
     { ProfScope ps(T_EMBED, s); // embedding gather + the first layer's norm in one launch
@@ -897,11 +897,14 @@ extern "C" int sd_draft(sd_model *draft, sd_ctx *c, const int32_t *seq_ids, int3
     hipStream_t s = (hipStream_t)stream;
     for (int i = 0; i < gamma; i++) {
         if (i == 0) rc = forward(draft, c, slot, s, PLAN_CATCHUP, 2, n_seq, seq_ids, 0, nullptr, gamma, 0, true);
-        else rc = forward(draft, c, slot, s, PLAN_CAND, 1, n_seq, seq_ids, 0, cand, gamma, i - 1, true);
+        else rc = forward(draft, c, slot, s, PLAN_CAND, 1, n_seq, seq_ids, 0, cand, gamma, i - 1, true, 1, true);
         if (rc) return rc;
         ProfScope ps(T_SAMPLE, s);
+        // every sampler but the last also writes the plan of the forward that feeds its token (the last
+        // candidate is never fed)
+        const NextPlan next = {draft->plan, c->view(), seq_ids, slot, draft->cfg.vocab, i + 1 < gamma ? 1 : 0};
         hipError_t e = launch_draft_sample(s, draft->logits, n_seq, draft->cfg.vocab, temperature, uniforms, gamma, i,
-                                           cand, q);
+                                           cand, q, next);
         if (e != hipSuccess) return sd_fail(SD_EHIP, std::string("sd_draft: sample: ") + hipGetErrorString(e));
     }
     return SD_OK;

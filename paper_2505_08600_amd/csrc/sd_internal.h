@@ -152,6 +152,16 @@ struct PlanView {
 
 enum PlanMode { PLAN_CATCHUP = 0, PLAN_CAND = 1, PLAN_VERIFY = 2 };
 
+// What the draft sampler needs to lay out the next single-row forward (PLAN_CAND) itself: its block of
+// sequence j knows the token just drawn, so it writes that sequence's plan entries and advances the cache
+// length, and the forward that follows starts without a plan launch.  enabled = 0: do nothing.
+struct NextPlan {
+    PlanView pv;
+    CtxView cv;
+    const int32_t *seq_ids;
+    int32_t slot, vocab, enabled;
+};
+
 struct WeightSeg { // up to three matrices stacked along N (q,k,v or gate,up)
     const void *p[3];
     int32_t n_per_seg;
@@ -289,7 +299,7 @@ hipError_t launch_attn_generic(hipStream_t s, int dtype, const void *qbuf, ActVi
                                const void *Vtl, PlanView pv, CtxView cv, int R, int n_seq, int H, int hd,
                                int64_t total_cap, int len_upper, void *obuf, ActView o_av);
 hipError_t launch_draft_sample(hipStream_t s, const float *logits, int n_seq, int V, float T, const float *u,
-                               int gamma, int idx, int32_t *cand, float *q);
+                               int gamma, int idx, int32_t *cand, float *q, const NextPlan &next);
 hipError_t launch_verify_tail(hipStream_t s, const float *logits, int n_seq, int gamma, int V, float T,
                               const int32_t *cand, const float *q, const float *u, const int32_t *seq_ids,
                               int32_t *n_acc, int32_t *next_tok, int commit, CtxView cv, float *stats);
