@@ -57,9 +57,13 @@ enum { SD_FP32 = 0, SD_BF16 = 1 };
  * multi-head causal attention (n_kv_heads == n_heads), SwiGLU FFN, untied LM head,
  * no biases.  n_heads * head_dim must equal d_model; head_dim is 16, 32, 64 or 128 (the
  * matrix-core attention kernels take 64 and 128, the others run on the plain kernels);
- * vocab is a multiple of 4.
- * dtype SD_BF16: weights, KV cache and GEMM input activations are bf16, all
- * accumulation, the residual stream, softmax and logits are fp32.
+ * vocab is a multiple of 4, at most 262144.
+ * dtype SD_BF16: weights, the embedding table and the KV cache are bf16.  Every activation
+ * that enters a contraction (normed hidden state, rotated query, attention output and
+ * probabilities, SwiGLU product) is fed to the matrix cores as TWO bf16 terms, hi = bf16(x)
+ * and lo = bf16(x - hi), i.e. about 16 mantissa bits: with single-bf16 activations two
+ * correct implementations that add in different orders drift apart by more than the logit
+ * tolerance over 32 layers.  Accumulation, the residual stream, softmax and logits are fp32.
  * dtype SD_FP32: everything fp32.
  * max_rows: largest number of token rows one forward may carry
  *           (verify: n_seq * (gamma + 1); draft: 2 * n_seq; prefill chunks adapt).
@@ -160,9 +164,14 @@ int sd_prefill(sd_model *m, sd_ctx *c, const int32_t *seq_ids /*dev*/, int32_t n
  * not touched and may be NULL.  The last candidate is not fed to the draft.
  *   uniforms dev fp32 [n_seq][gamma], cand dev int32 [n_seq][gamma],
  *   q dev fp32 [n_seq][gamma][vocab].  1 <= gamma <= 15.
+ * The draft's cache must be within two tokens of the sequence (sd_prefill it first): a
+ * cache further behind raises the device status flag (SD_ESTATE at the next sd_ctx_sync).
  * sd_draft, sd_verify and sd_commit only enqueue kernels on `stream` (no allocation,
  * copy, memset or host synchronisation; option "profile" off), so they may be
- * captured into a HIP graph. */
+ * captured into a HIP graph and the graph replayed while the sequences grow: results never
+ * depend on the host-side length bound of capture time (it only sizes launches; the
+ * matrix-core attention kernels read the lengths on the device, the plain one sizes its
+ * score buffer from the largest sequence capacity). */
 int sd_draft(sd_model *draft, sd_ctx *c, const int32_t *seq_ids /*dev*/, int32_t n_seq, int32_t gamma,
              float temperature, const float *uniforms, int32_t *cand, float *q, void *stream);
 

@@ -204,6 +204,12 @@ __global__ void plan_kernel(int mode, int R, int n_seq, const int32_t *seq_ids, 
         if (mode == PLAN_CATCHUP) {
             int avail = (n - upto_off) - kv;
             nq = avail < 0 ? 0 : (avail > R ? R : avail);
+            // a draft call (upto_off == 0) needs the pending token in its last row: a cache further behind
+            // than R tokens would draw its candidates from another position - refuse and flag it
+            if (upto_off == 0 && avail > R) {
+                atomicOr(cv.status, 64);
+                nq = 0;
+            }
         } else if (mode == PLAN_CAND) {
             nq = 1;
         } else { // PLAN_VERIFY: rows (pending token, candidates) at positions n-1 ..
@@ -776,7 +782,7 @@ hipError_t launch_rope_append(hipStream_t s, int dtype, const float *qkv, int n_
 
 // ---------------------------------------------------------------- generic attention
 // One block per (row slot i, head, selected sequence): query row i sees cache rows
-// [0, kv0 + i].  Scores live in dynamic LDS (len_upper floats).
+// [0, kv0 + i].  Scores live in dynamic LDS (lds_len floats: the largest sequence capacity).
 template <typename T>
 __global__ __launch_bounds__(256) void attn_generic_kernel(const T *qbuf, ActView q_av, const T *Kl, const T *Vtl,
                                                            PlanView pv, CtxView cv, int R, int H, int hd,
@@ -794,7 +800,10 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const T *qbuf, ActVie
         return;
     }
     int Lk = pv.seq_kv0[j] + i + 1;
-    if (Lk > lds_len) Lk = lds_len; // host sizes lds_len from an upper bound; never exceeded
+    if (Lk > lds_len) { // the launch was sized for fewer rows than the cache holds: flag it, do not read on
+        if (threadIdx.x == 0) atomicOr(cv.status, 32);
+        Lk = lds_len;
+    }
     int64_t off = cv.off[pv.seq_b[j]];
     const T *Kh = Kl + (size_t)h * total_cap * hd;
     const T *Vh = Vtl + (size_t)h * hd * total_cap;
@@ -835,7 +844,15 @@ hipError_t launch_attn_generic(hipStream_t s, int dtype, const void *qbuf, ActVi
                                int64_t total_cap, int len_upper, void *obuf, ActView o_av)
 {
     size_t lds = ((size_t)len_upper + 256 + hd + 32) * sizeof(float);
-    if (lds > 64 * 1024) return hipErrorNotSupported;
+    if (lds > 160 * 1024) return hipErrorNotSupported;
+    if (lds > 64 * 1024) { // beyond the default limit: ask for the larger LDS allocation this part has
+        hipError_t ea = dtype == SD_BF16
+                            ? hipFuncSetAttribute((const void *)attn_generic_kernel<bf16_t>,
+                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
+                            : hipFuncSetAttribute((const void *)attn_generic_kernel<float>,
+                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (ea != hipSuccess) return hipErrorNotSupported;
+    }
     dim3 grid(R, H, n_seq), block(256);
     if (dtype == SD_BF16)
         hipLaunchKernelGGL(attn_generic_kernel<bf16_t>, grid, block, lds, s, (const bf16_t *)qbuf, q_av,

@@ -180,6 +180,8 @@ extern "C" int sd_load_model(const sd_model_config *cfg, const sd_weights *w, sd
     if (c.head_dim != 16 && c.head_dim != 32 && c.head_dim != 64 && c.head_dim != 128)
         return sd_fail(SD_EINVAL, "sd_load_model: head_dim must be 16, 32, 64 or 128");
     if (c.vocab % 4 != 0) return sd_fail(SD_EINVAL, "sd_load_model: vocab must be a multiple of 4");
+    if (c.vocab > 262144) // the samplers search 64 segments of 4096 entries
+        return sd_fail(SD_EINVAL, "sd_load_model: vocab above 262144");
     if (c.dtype != SD_FP32 && c.dtype != SD_BF16) return sd_fail(SD_EINVAL, "sd_load_model: bad dtype");
     if (c.max_rows < 2 || c.max_pos < 2) return sd_fail(SD_EINVAL, "sd_load_model: max_rows/max_pos too small");
     if (!(c.rope_base > 1.f) || !(c.rms_eps >= 0.f)) return sd_fail(SD_EINVAL, "sd_load_model: bad rope_base/rms_eps");
@@ -408,6 +410,7 @@ extern "C" int sd_ctx_create(int32_t batch, const int32_t *caps, sd_ctx **out)
         tot += cp;
     }
     c->total_cap = tot;
+    c->max_cap = *std::max_element(c->cap.begin(), c->cap.end());
     for (int s = 0; s < SD_MAX_SLOTS; s++) c->models[s] = nullptr, c->kcache[s] = c->vcache[s] = nullptr;
     hipError_t e = hipMalloc((void **)&c->d_off, sizeof(int64_t) * batch);
     if (e == hipSuccess) e = hipMalloc((void **)&c->d_cap, sizeof(int32_t) * batch);
@@ -540,6 +543,8 @@ extern "C" int sd_ctx_sync(sd_ctx *c, sd_model *m, int32_t *n_tokens, int32_t *k
         if (st & 4) msg += " sequence id out of range;";
         if (st & 8) msg += " position beyond the rotary table;";
         if (st & 16) msg += " token id outside the vocabulary;";
+        if (st & 32) msg += " cache length beyond the bound the attention launch was sized for;";
+        if (st & 64) msg += " draft cache more than two tokens behind its sequence (prefill it first);";
         return sd_fail(SD_ESTATE, msg);
     }
     return SD_OK;
@@ -732,7 +737,7 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
     m->last_a_rows = M;
     CtxView cv = c->view();
     PlanView pv = m->plan;
-    int kv_upper = c->len_upper + SD_MAX_GAMMA + 1;
+    int kv_upper = std::min(c->len_upper + SD_MAX_GAMMA + 1, c->max_cap);
     size_t lstride = (size_t)d * c->total_cap * m->esz;
     hipError_t ge;
     if (!plan_ready) { ProfScope ps(T_PLAN, s); // (the draft sampler lays out the single-row forwards that follow it)
@@ -794,8 +799,10 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
                 ea = launch_attn_mfma_bf16(s, m->qbuf, avd, Kl, Vtl, pv, cv, R, n_slots, H, hd, c->total_cap,
                                            kv_upper, m->part, m->part_floats, m->obuf, avd);
             if (ea == hipErrorNotSupported)
+                // (its score buffer is sized from the largest capacity, which never changes: a captured graph
+                // stays valid however far the sequences have grown since the capture)
                 ea = launch_attn_generic(s, cf.dtype, m->qbuf, avd, Kl, Vtl, pv, cv, R, n_slots, H, hd,
-                                         c->total_cap, kv_upper, m->obuf, avd);
+                                         c->total_cap, c->max_cap, m->obuf, avd);
         }
         if (ea == hipErrorNotSupported) return sd_fail(SD_ECAP, "forward: context too long for the generic attention kernel");
         FWD(ea);
@@ -931,7 +938,7 @@ extern "C" int sd_verify(sd_model *target, sd_ctx *c, const int32_t *seq_ids, in
     hipError_t e = launch_verify_tail(s, target->logits, n_seq, gamma, target->cfg.vocab, temperature, cand, q,
                                       uniforms, seq_ids, n_accepted, next_token, commit, c->view(), target->vstats);
     if (e != hipSuccess) return sd_fail(SD_EHIP, std::string("sd_verify: tail: ") + hipGetErrorString(e));
-    if (commit) c->len_upper += gamma + 1;
+    if (commit) c->len_upper = std::min(c->len_upper + gamma + 1, c->max_cap);
     return SD_OK;
 }
 
@@ -942,7 +949,7 @@ extern "C" int sd_commit(sd_ctx *c, const int32_t *seq_ids, int32_t n_seq, int32
     if (n_seq < 1 || n_seq > c->B || gamma < 0 || gamma > SD_MAX_GAMMA) return sd_fail(SD_EINVAL, "sd_commit: bad n_seq or gamma");
     hipError_t e = launch_commit((hipStream_t)stream, c->view(), seq_ids, n_seq, gamma, cand, n_accepted, next_token);
     if (e != hipSuccess) return sd_fail(SD_EHIP, std::string("sd_commit: ") + hipGetErrorString(e));
-    c->len_upper += gamma + 1;
+    c->len_upper = std::min(c->len_upper + gamma + 1, c->max_cap);
     return SD_OK;
 }
 

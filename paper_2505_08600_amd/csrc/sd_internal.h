@@ -238,7 +238,8 @@ struct sd_ctx {
     sd_model *models[SD_MAX_SLOTS];
     void *kcache[SD_MAX_SLOTS];
     void *vcache[SD_MAX_SLOTS];
-    int len_upper; // host upper bound of the longest sequence (tokens)
+    int len_upper; // host upper bound of the longest sequence (tokens): sizes launches, never decides results
+    int max_cap;   // largest sequence capacity (tokens)
     CtxView view() const
     {
         CtxView v;

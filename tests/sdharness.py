@@ -2,26 +2,21 @@
 teacher-force the HIP path along it step by step.
 
 Parity bar: candidate ids, n_accepted and next tokens bit-exact; a step may be
-*flagged* instead only when the oracle's own decision margin is below a
+*flagged* instead only when the ORACLE's own decision margin is below a fixed
 threshold.  Logits: max |gpu - oracle| / max |oracle| per row below the dtype's
 tolerance.  No expected value ever comes from the HIP path: after every step the
 HIP context is committed with the ORACLE's result.
 
-Thresholds.  The base threshold (probability units) is 1e-3 for bf16 and 1e-5 for
-fp32.  On top of it a decision is allowed to differ exactly as far as the logits
-of that step were measured to differ, because a decision taken on other logits
-is a different decision, not an error of the decision kernel:
-  if |dlogit| <= delta then p_gpu / p_oracle lies in exp(+-2 delta / T) =: 1 +- eta, so
-  - accept test:      |u - ratio| may be below base + ratio * eta,
-  - inverse-CDF draw: u may lie base + L1(w_gpu, w_oracle) / Z outside the HIP token's
-                      interval, with L1 <= eta for p and <= eta for max(p - q, 0),
-  - greedy:           the argmax may flip when the top-1/top-2 gap is below 2 delta.
-With fp32 models delta ~ 1e-6 and the base threshold decides; with bf16 models two
-correct implementations that sum in a different order drift apart to about one
-bf16 ulp per activation (each differing rounding feeds the next), i.e. delta is a
-few 1e-3 of the logit range, which is what the 2e-2 logits tolerance allows for.
-The decision kernels themselves are pinned by the fp32 cases, where they must
-reproduce the oracle to the base threshold at the same vocabulary sizes.
+The flag rule is flat: nothing measured on the HIP side widens it.
+  - accept test (T > 0):  flagged only if |u - p/q| < 1e-3 (bf16) or 1e-5 (fp32);
+  - inverse-CDF draw:     the HIP token is valid only if u lies within that same
+                          threshold (as a fraction of the total mass) of the token's
+                          interval of the oracle's CDF - judged in CDF space because
+                          with 32000 tokens almost every u is within 1e-3 of *some* edge;
+  - greedy:               the argmax may differ only if the oracle's top-1/top-2 gap,
+                          relative to the row's largest |logit|, is below the threshold;
+  - draft q rows:         |q_gpu - q_oracle| <= the threshold, element-wise.
+A decision that differs with a larger margin is a failure, whatever the logits did.
 """
 from __future__ import annotations
 
@@ -37,9 +32,14 @@ from paper_2505_08600_amd import datagen as dg
 
 LOGIT_TOL = {dg.FP32: 1e-4, dg.BF16: 2e-2}     # max relative error of a logits row
 MARGIN_THR = {dg.FP32: 1e-5, dg.BF16: 1e-3}    # probability-space decision margins
-# greedy draft candidates (draft logits are not read back): the argmax may flip when the oracle's
-# top-1/top-2 gap is below twice the logit deviation the dtype shows at these tests' logit scales
-GREEDY_GAP_THR = {dg.FP32: 2.5e-3, dg.BF16: 0.1}
+# greedy draft candidates: the draft's logits are not read back, so the oracle's top-1/top-2 gap is judged in
+# absolute logit units (the test models' logits are O(1..10))
+GREEDY_GAP_THR = {dg.FP32: 1e-4, dg.BF16: 1e-2}
+
+
+def flag_cap(steps: int) -> int:
+    """How many steps of a run may be flagged (measured: 0-4 in 1453 steps of the random-shape sweep)."""
+    return max(1, steps // 50)
 
 
 @dataclasses.dataclass
@@ -48,7 +48,6 @@ class ParityStats:
     flagged: int = 0
     max_logit_rel: float = 0.0
     max_q_abs: float = 0.0
-    beyond_base: int = 0   # flagged steps whose margin exceeded the base threshold
     n_acc: List[int] = dataclasses.field(default_factory=list)
 
     def merge_logits(self, gpu: np.ndarray, ref: np.ndarray):
@@ -155,11 +154,10 @@ def check_draft_step(s, cg, qg, T, dtype, V):
             first_bad = i
             break
     if first_bad is not None:
-        if T > 0:  # valid iff u is within base + L1(q_gpu, q_oracle) of the HIP token's interval
-            l1 = float(np.abs(qg[first_bad].astype(np.float64) - s.q[first_bad]).sum())
+        if T > 0:  # valid iff u is within the threshold of the HIP token's interval of the oracle's CDF
             mg = oracle.cdf_distance(s.q[first_bad], s.u_draft[first_bad], int(cg[first_bad])) \
                 if 0 <= cg[first_bad] < V else 1.0
-            lim = thr + l1
+            lim = thr
         else:
             mg, lim = s.draft_margins[first_bad], GREEDY_GAP_THR[dtype]
         assert mg < lim, f"draft candidate {first_bad} differs ({cg} vs {s.cand}), margin {mg} lim {lim}"
@@ -167,35 +165,33 @@ def check_draft_step(s, cg, qg, T, dtype, V):
     if T > 0:
         upto = gamma if first_bad is None else first_bad + 1
         dq = float(np.abs(qg[:upto] - s.q[:upto]).max())
-        assert dq <= 50 * LOGIT_TOL[dtype], f"draft q differs by {dq}"
+        assert dq <= thr, f"draft q differs by {dq}"
     return first_bad is not None, first_bad, dq
 
 
 def check_verify_step(s, na, nx, lg, T, dtype, V):
     """Compare one sequence's HIP verify output (n_acc, next token, logits [gamma+1][V]) with the
-    oracle's step record.  -> (flagged, margin beyond the base threshold, logits rel err)"""
+    oracle's step record.  -> (flagged, logits rel err)"""
     thr = MARGIN_THR[dtype]
     gamma = len(s.cand)
     ref = s.logits.astype(np.float64)
     rel = float(np.max(np.abs(lg.astype(np.float64) - ref) / np.max(np.abs(ref), axis=-1, keepdims=True)))
     assert rel <= LOGIT_TOL[dtype], f"logits rel err {rel}"
     if (na, nx) == (s.n_acc, s.next_token):
-        return False, False, rel
-    delta = float(np.abs(lg.astype(np.float64) - ref).max())
-    eta = float(np.expm1(2.0 * delta / T)) if T > 0 else 0.0
+        return False, rel
     if na != s.n_acc:      # the accept test (or argmax match) at the first differing position
         i = min(s.n_acc, na)
         mg = float(s.verify_margins[i])
-        lim = thr + (float(s.u_verify[i]) + mg) * eta if T > 0 else 2.0 * delta
+        lim = thr if T > 0 else thr * float(np.abs(ref[i]).max())
     elif T > 0:            # same prefix, other next token
         w = oracle.next_weights(s.logits, s.q, s.n_acc, T)
         mg = oracle.cdf_distance(w, s.u_verify[gamma], nx) if 0 <= nx < V else 1.0
-        lim = thr + 2.0 * eta / float(w.sum())
+        lim = thr
     else:
-        mg, lim = float(s.verify_margins[gamma]), 2.0 * delta
+        mg, lim = float(s.verify_margins[gamma]), thr * float(np.abs(ref[s.n_acc]).max())
     assert mg < lim, (f"verify differs: gpu ({na},{nx}) oracle ({s.n_acc},{s.next_token}), "
-                      f"margin {mg} lim {lim} delta {delta}")
-    return True, mg >= (thr if T > 0 else 0.0), rel
+                      f"margin {mg} lim {lim}")
+    return True, rel
 
 
 def lockstep(pair: Pair, ctx: api.Context, steps, gamma, T) -> ParityStats:
@@ -227,11 +223,10 @@ def lockstep(pair: Pair, ctx: api.Context, steps, gamma, T) -> ParityStats:
         na, nx = int(nacc_g.item()), int(next_g.item())
         lg = pair.gt.last_logits().cpu().numpy()
         try:
-            f2, beyond, rel = check_verify_step(s, na, nx, lg, T, dtype, V)
+            f2, rel = check_verify_step(s, na, nx, lg, T, dtype, V)
         except AssertionError as e:
             raise AssertionError(f"step {k}: {e}") from None
         st.max_logit_rel = max(st.max_logit_rel, rel)
-        st.beyond_base += int(beyond)
         # ---- commit the oracle's result (teacher forcing)
         api.sd_commit(ctx, None, 1, gamma, cand_in, dev(np.array([s.n_acc], np.int32)),
                       dev(np.array([s.next_token], np.int32)))
@@ -322,7 +317,7 @@ def batched_teacher_forced(gt, gd, ot, od, prompts, gamma, T, n_tok, seed, dtype
         lg = gt.last_logits().cpu().numpy().reshape(B, gamma + 1, V)
         na_h, nx_h = na.cpu().numpy(), nx.cpu().numpy()
         for b in range(B):
-            f, _, _ = check_verify_step(trajs[b][k], int(na_h[b]), int(nx_h[b]), lg[b], T, dtype, V)
+            f, _ = check_verify_step(trajs[b][k], int(na_h[b]), int(nx_h[b]), lg[b], T, dtype, V)
             flagged += int(f)
         api.sd_commit(ctx, None, B, gamma, cand_all, dev(np.array([trajs[b][k].n_acc for b in range(B)], np.int32)),
                       dev(np.array([trajs[b][k].next_token for b in range(B)], np.int32)))

@@ -105,7 +105,7 @@ def test_tiny_bf16_teacher_forced(tiny_pair_bf16, T):
     prompt = dg.make_prompt(12, 0, 32, TINY_T.vocab)
     st = H.teacher_forced_parity(tiny_pair_bf16, prompt, gamma=4, T=T, n_tokens=64, seed=12)
     _say(f"  steps={st.steps} flagged={st.flagged} logit_rel={st.max_logit_rel:.2e} q_abs={st.max_q_abs:.2e}")
-    assert st.flagged <= max(3, st.steps // 4) and st.max_logit_rel < 2e-2
+    assert st.flagged <= H.flag_cap(st.steps) and st.max_logit_rel < 2e-2
 
 
 @pytest.mark.parametrize("T,plen,gamma", [(0.0, 70, 5), (1.0, 70, 5), (1.0, 300, 8), (0.0, 33, 15)])
@@ -118,8 +118,7 @@ def test_small_bf16_mfma_kernels_teacher_forced(T, plen, gamma):
     prompt = dg.make_prompt(61, plen, plen, st_.vocab)
     st = H.teacher_forced_parity(pair, prompt, gamma=gamma, T=T, n_tokens=40, seed=61 + plen)
     _say(f"  steps={st.steps} flagged={st.flagged} logit_rel={st.max_logit_rel:.2e} q_abs={st.max_q_abs:.2e}")
-    _say(f"  beyond_base={st.beyond_base}")
-    assert st.flagged <= max(3, st.steps // 4) and st.max_logit_rel < 2e-2
+    assert st.flagged <= H.flag_cap(st.steps) and st.max_logit_rel < 2e-2
     pair.close()
 
 
@@ -675,7 +674,7 @@ def test_random_shapes_single_sequence_and_ragged_batches():
         pair.close()
     _say(f"  steps={steps} flagged={flagged} worst logit error bf16 {worst[dg.BF16]:.2e} fp32 {worst[dg.FP32]:.2e}")
     assert worst[dg.BF16] <= 2e-2 and worst[dg.FP32] <= 1e-4
-    assert flagged <= max(3, steps // 50)
+    assert flagged <= H.flag_cap(steps)
 
 
 def test_draft_groups_on_separate_streams_match_sequential_calls():
@@ -805,7 +804,7 @@ def test_config3_routed_heterogeneous_drafts_small():
         lg = gt.last_logits().cpu().numpy().reshape(B, gamma + 1, V)
         na_h, nx_h = na.cpu().numpy(), nx.cpu().numpy()
         for b in range(B):
-            f, _, _ = H.check_verify_step(trajs[b][k], int(na_h[b]), int(nx_h[b]), lg[b], T, dg.BF16, V)
+            f, _ = H.check_verify_step(trajs[b][k], int(na_h[b]), int(nx_h[b]), lg[b], T, dg.BF16, V)
             flagged += int(f)
         api.sd_commit(ctx, None, B, gamma, cand_all, H.dev(np.array([trajs[b][k].n_acc for b in range(B)], np.int32)),
                       H.dev(np.array([trajs[b][k].next_token for b in range(B)], np.int32)))

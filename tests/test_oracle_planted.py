@@ -13,6 +13,7 @@ SRC = os.path.join(ROOT, "oracle", "sd_oracle.c")
 # name -> (list of (old, new) replacements, pin files to run - the ones expected to notice, fastest first)
 FWD = ["tests/test_oracle_forward.py"]
 ACC = ["tests/test_oracle_accept.py", "tests/test_oracle_sd.py"]
+BF = ["tests/test_oracle_bf16.py"]
 MISTAKES = {
     "residual is |p - q| instead of max(0, p - q)": ([("w[x] = r > 0.0 ? r : 0.0;", "w[x] = r > 0.0 ? r : -r;")], ACC),
     "acceptance ratio inverted": ([("float ratio = p[cand[i]] / qc;", "float ratio = qc / p[cand[i]];")], ACC),
@@ -30,6 +31,25 @@ MISTAKES = {
                                                         "double g = tmp2[i];\n                a[i] = round_act(g / (1.0 + exp(-g)) * tmp[i], dt);")], FWD),
     "feed-forward output not added to the residual": ([("matvec(m->wdown[l], dt, d, F, a, y);\n            for (int i = 0; i < d; i++) hr[i] += y[i];",
                                                         "matvec(m->wdown[l], dt, d, F, a, y);\n            for (int i = 0; i < d; i++) hr[i] = y[i];")], FWD),
+    # the bf16 contract's rounding points, the synthetic-cache loader and adapters with bf16 factors
+    "lo term of a two-term activation dropped": ([("return (double)hi + (double)lo;", "return (double)hi;")], BF),
+    "attention output not rounded": ([("ob[hh * hd + i] = round_act(acc / z, dt);", "ob[hh * hd + i] = acc / z;")], BF),
+    "rotated query not rounded": ([("qb[(size_t)r * HD + i] = round_act(tmp[i], dt);", "qb[(size_t)r * HD + i] = tmp[i];")], BF),
+    "key cache stored as two terms": ([("Kc[(size_t)pos * HD + i] = (float)round_storage(tmp[i], dt);",
+                                        "Kc[(size_t)pos * HD + i] = (float)round_act(tmp[i], dt);")], BF),
+    "value cache stored as two terms": ([("Vc[(size_t)pos * HD + i] = (float)round_storage(tmp[i], dt);",
+                                          "Vc[(size_t)pos * HD + i] = (float)round_act(tmp[i], dt);")], BF),
+    "SwiGLU product rounded to one term": ([("a[i] = round_act(g / (1.0 + exp(-g)) * tmp2[i], dt);",
+                                             "a[i] = round_storage(g / (1.0 + exp(-g)) * tmp2[i], dt);")], BF),
+    "final norm not rounded": ([("for (int i = 0; i < d; i++) a[i] = round_act(a[i], dt);\n        matvec(m->lm_head",
+                                 "matvec(m->lm_head")], BF),
+    "synthetic cache rows read as [dim][token]": ([("kd[i] = (float)weight_at(k, m->c.dtype, i);",
+                                                    "kd[i] = (float)weight_at(k, m->c.dtype, (i % HD) * (size_t)len + i / HD);")], BF),
+    "synthetic value rows loaded from the key rows": ([("vd[i] = (float)weight_at(v, m->c.dtype, i);",
+                                                        "vd[i] = (float)weight_at(k, m->c.dtype, i);")], BF),
+    "adapter's B factor read as [rank][out]": ([("b0 + (size_t)n * r + j)", "b0 + (size_t)j * N + n)")],
+                                               BF + ["tests/test_oracle_lora.py"]),
+    "adapter scale dropped": ([("y[n] += lo->scale * acc;", "y[n] += acc;")], BF + ["tests/test_oracle_lora.py"]),
 }
 
 
