@@ -193,6 +193,17 @@ int sd_verify(sd_model *target, sd_ctx *c, const int32_t *seq_ids /*dev*/, int32
               float temperature, const int32_t *cand, const float *q, const float *uniforms,
               int32_t *n_accepted, int32_t *next_token, int32_t commit, void *stream);
 
+/* The acceptance rule alone (Section 3.1; the last stage of sd_verify) on logits the caller holds:
+ * the same softmax / accept scan / residual / resample kernels, no model, no context, no commit.
+ *   logits dev fp32 [n_seq][gamma+1][vocab] (16-byte aligned); cand, q, uniforms, n_accepted,
+ *   next_token as for sd_verify (q 16-byte aligned);
+ *   workspace dev fp32 [3 * n_seq * (gamma+1)]: per-row (max, sum of exponentials, argmax) passed
+ *   from the first kernel to the second; contents on entry do not matter.
+ * vocab a multiple of 4 in [4, 262144]; 0 <= gamma <= 15.  Only enqueues kernels on `stream`. */
+int sd_accept(const float *logits, int32_t n_seq, int32_t gamma, int32_t vocab, float temperature,
+              const int32_t *cand, const float *q, const float *uniforms, int32_t *n_accepted,
+              int32_t *next_token, float *workspace, void *stream);
+
 /* Commit / KV rollback: append cand[0..n_accepted) and next_token to each selected
  * sequence, then set every attached model's cache length to
  * min(its length, new token count - 1).  No cache data moves: rows of rejected
