@@ -204,6 +204,17 @@ int sd_accept(const float *logits, int32_t n_seq, int32_t gamma, int32_t vocab, 
               const int32_t *cand, const float *q, const float *uniforms, int32_t *n_accepted,
               int32_t *next_token, float *workspace, void *stream);
 
+/* sd_accept for callers that cannot allocate or carry a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): same arguments and results, but the
+ * per-row statistics live in a fixed device array inside the library (48 KiB per GPU, held until
+ * the process ends) instead of a caller's workspace.  Calls no allocating routine; the first call
+ * on a device only looks up that device's address of the array.
+ * n_seq * (gamma + 1) <= 4096, else SD_ECAP (nothing is enqueued).  All calls on one GPU share the
+ * array: two calls whose kernels may overlap on that GPU (different streams) race - serialise them. */
+int sd_accept_static(const float *logits, int32_t n_seq, int32_t gamma, int32_t vocab, float temperature,
+                     const int32_t *cand, const float *q, const float *uniforms, int32_t *n_accepted,
+                     int32_t *next_token, void *stream);
+
 /* Commit / KV rollback: append cand[0..n_accepted) and next_token to each selected
  * sequence, then set every attached model's cache length to
  * min(its length, new token count - 1).  No cache data moves: rows of rejected

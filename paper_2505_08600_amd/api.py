@@ -24,7 +24,8 @@ EXPORTS = ["sd_load_model", "sd_free_model", "sd_ctx_create", "sd_ctx_free", "sd
            "sd_prefill", "sd_draft", "sd_verify", "sd_commit", "sd_route", "sd_ctx_sync", "sd_ctx_get_tokens",
            "sd_ctx_set_kv", "sd_ctx_truncate", "sd_debug_read", "sd_debug_layout_index", "sd_last_logits", "sd_set_option", "sd_profile_read", "sd_last_error",
            "sd_eq1_speedup", "sd_choose_gamma", "sd_alpha_hat", "sd_model_set_lora", "sd_ctx_set_adapters",
-           "sd_classifier_create", "sd_classifier_destroy", "sd_route_classifier", "sd_accept"]
+           "sd_classifier_create", "sd_classifier_destroy", "sd_route_classifier", "sd_accept",
+           "sd_accept_static"]
 
 
 class SdError(RuntimeError):
@@ -81,6 +82,7 @@ def lib():
         L.sd_verify.argtypes = [vp, vp, vp, i32, i32, C.c_float, vp, vp, vp, vp, vp, i32, vp]
         L.sd_commit.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp]
         L.sd_accept.argtypes = [vp, i32, i32, i32, C.c_float, vp, vp, vp, vp, vp, vp, vp]
+        L.sd_accept_static.argtypes = [vp, i32, i32, i32, C.c_float, vp, vp, vp, vp, vp, vp]
         L.sd_route.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp]
         L.sd_ctx_sync.argtypes = [vp, vp, vp, vp]
         L.sd_ctx_get_tokens.argtypes = [vp, i32, vp, i32, C.POINTER(i32)]
@@ -327,6 +329,16 @@ def sd_accept(logits: torch.Tensor, gamma: int, temperature: float, cand: Option
     assert rows == gamma + 1 and workspace.numel() >= 3 * n_seq * rows and workspace.dtype == torch.float32
     _check(lib().sd_accept(_dp(logits), n_seq, gamma, vocab, temperature, _dp(cand), _dp(q), _dp(uniforms),
                            _dp(n_accepted), _dp(next_token), _dp(workspace), _stream()))
+
+
+def sd_accept_static(logits: torch.Tensor, gamma: int, temperature: float, cand: Optional[torch.Tensor],
+                     q: Optional[torch.Tensor], uniforms: Optional[torch.Tensor], n_accepted: torch.Tensor,
+                     next_token: torch.Tensor) -> None:
+    """sd_accept_static: sd_accept without a workspace argument and without any allocation."""
+    n_seq, rows, vocab = logits.shape
+    assert rows == gamma + 1
+    _check(lib().sd_accept_static(_dp(logits), n_seq, gamma, vocab, temperature, _dp(cand), _dp(q), _dp(uniforms),
+                                  _dp(n_accepted), _dp(next_token), _stream()))
 
 
 def sd_commit(ctx: Context, seq_ids: Optional[torch.Tensor], n_seq: int, gamma: int, cand: Optional[torch.Tensor],

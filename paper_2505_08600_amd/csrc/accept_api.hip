@@ -43,3 +43,49 @@ extern "C" int sd_accept(const float *logits, int32_t n_seq, int32_t gamma, int3
     return run_accept("sd_accept", logits, n_seq, gamma, vocab, temperature, cand, q, uniforms, n_accepted, next_token,
                       workspace, (hipStream_t)stream);
 }
+
+// ---------------------------------------------------------------- the same call without any allocation
+// For callers that cannot allocate or carry a workspace (code under graph capture, tight serving loops):
+// the per-row statistics that sd_accept passes between its two kernels through `workspace` live in a
+// file-scope device array instead.  Every device the library runs on holds its own copy of the array at
+// its own address for the life of the process; the address is looked up once per device and kept.
+#define SD_ACCEPT_STATIC_MAX_ROWS 4096 // n_seq * (gamma + 1); 48 KiB of device memory per GPU
+#define SD_MAX_DEVICES 64
+static __device__ __align__(256) float scratch[3 * SD_ACCEPT_STATIC_MAX_ROWS];
+
+static std::mutex g_scratch_mutex;
+static float *g_scratch_ptr[SD_MAX_DEVICES]; // device address of `scratch` per device, nullptr until first use
+
+// Device address of this device's copy of `scratch` (the array's name is only a host-side handle).
+static int scratch_on_current_device(float **out)
+{
+    int dev = -1;
+    SD_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= SD_MAX_DEVICES) return sd_fail(SD_EINVAL, "sd_accept_static: device ordinal above 63");
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        SD_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return sd_fail(SD_EHIP, "sd_accept_static: hipGetSymbolAddress returned a null address");
+        g_scratch_ptr[dev] = (float *)p;
+    }
+    *out = g_scratch_ptr[dev];
+    return SD_OK;
+}
+
+extern "C" int sd_accept_static(const float *logits, int32_t n_seq, int32_t gamma, int32_t vocab, float temperature,
+                                const int32_t *cand, const float *q, const float *uniforms, int32_t *n_accepted,
+                                int32_t *next_token, void *stream)
+{
+    int rc = check_accept("sd_accept_static", logits, n_seq, gamma, vocab, temperature, cand, q, uniforms, n_accepted,
+                          next_token);
+    if (rc) return rc;
+    if ((int64_t)n_seq * (gamma + 1) > SD_ACCEPT_STATIC_MAX_ROWS)
+        return sd_fail(SD_ECAP, "sd_accept_static: n_seq * (gamma + 1) exceeds 4096 rows (use sd_accept with a workspace)");
+    float *stats = nullptr;
+    rc = scratch_on_current_device(&stats);
+    if (rc) return rc;
+    // (nothing to clear: the first kernel writes all 3 * n_seq * (gamma + 1) entries the second one reads)
+    return run_accept("sd_accept_static", logits, n_seq, gamma, vocab, temperature, cand, q, uniforms, n_accepted,
+                      next_token, stats, (hipStream_t)stream);
+}
