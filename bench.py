@@ -44,6 +44,13 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="debug: reduce target depth (invalidates the number)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-batch32", action="store_true", help="skip the secondary batch-32 verify measurement")
+    ap.add_argument("--no-long-context", action="store_true", help="skip the verify passes of configs 4 and 5")
+    ap.add_argument("--batch32-only", action="store_true",
+                    help="only the batch-32 verify pass (config 3 shape), a few repetitions: the command the "
+                         "batch-32 rocprofv3 summaries under profiles/ are taken from (own JSON line)")
+    ap.add_argument("--stream-probe", action="store_true",
+                    help="only a plain streaming read of 33.6 / 100.7 / 180.4 / 262.1 MB / 1 GiB buffers (the sizes of "
+                         "the 7B shape's weight matrices): the practical HBM read ceiling (own JSON line)")
     ap.add_argument("--temperature", type=float, default=1.0)
     ap.add_argument("--prompt", type=int, default=512)
     ap.add_argument("--copy-calibration", action="store_true",
@@ -84,6 +91,18 @@ def main():
     if args.classifier:
         classifier_bench(api, dg, torch, np, args)
         return
+    if args.stream_probe:
+        stream_probe(api, torch, np)
+        return
+    if args.batch32_only:
+        st = dg.SHAPES["t7b"] if not args.layers else dg.with_layers(dg.SHAPES["t7b"], args.layers)
+        gt = api.Model(st, dg.make_weights(st, 2025, threads=16), max_rows=192, max_pos=1200)
+        res = batch32_verify(api, dg, torch, np, gt, st, 2025, 32, (128, 1024), 5, reps=max(3, args.steps if args.steps != 40 else 5))
+        print(json.dumps({"metric": "batch32_verify_candidates_per_s", "value": res["candidates_per_s"],
+                          "unit": "candidate tokens/s", "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
+                          "higher_is_better": True, "vs_baseline": None, "config": {"workload": res["workload"]},
+                          "batch32_verify": res}))
+        return
     if args.prefill_bench:
         prefill_bench(api, dg, torch, np, args)
         return
@@ -98,7 +117,8 @@ def main():
     sd_ = dg.SHAPES["draft_a"]
     V = st.vocab
     K, W = args.steps, args.warmup
-    n_total = K + W + 8
+    DIST_STEPS = max(50, K)   # steps timed one by one for the median / p10 / p90 (whatever --steps says)
+    n_total = K + W + 8 + DIST_STEPS
     AR_STEPS = 16  # plain autoregressive decoding with the same library (gamma = 0), timed after the main loop
     cap = args.prompt + n_total * (gamma + 1) + 16 + AR_STEPS
 
@@ -149,6 +169,16 @@ def main():
     ms_per_step = dt / K * 1e3
     n_acc = na_log[W:W + K, 0].cpu().numpy()
     ctx.sync()  # raises if a kernel flagged an inconsistency
+
+    # ---- the same step timed one at a time (events on the launch stream around each step): spread of the step time
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(DIST_STEPS)]
+    for i, k in enumerate(range(W + K + 8, W + K + 8 + DIST_STEPS)):
+        evs[i][0].record()
+        step(k)
+        evs[i][1].record()
+    torch.cuda.synchronize()
+    step_ms = np.array([a.elapsed_time(b) for a, b in evs])
+    ctx.sync()
 
     # ---- phase split: draft-only and verify-only timings (same state machine, separate loops)
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -219,6 +249,8 @@ def main():
         "emitted_tokens_per_s": float((n_acc + 1).sum() / dt),
         "accepted_tokens_per_s": float(n_acc.sum() / dt),
         "verify_only_candidates_per_s": B * gamma / (t_verify * 1e-3),
+        "step_ms_distribution": {"n": int(DIST_STEPS), "median": float(np.median(step_ms)),
+                                 "p10": float(np.percentile(step_ms, 10)), "p90": float(np.percentile(step_ms, 90))},
         "ms_draft": t_draft, "ms_verify": t_verify,
         "acceptance_rate_eq2": float(n_acc.sum() / (K * gamma)), "tau": tau, "alpha_hat": alpha_hat,
         "c_draft_over_target": c_ratio, "eq1_speedup_model": eq1,
@@ -253,6 +285,13 @@ def main():
     if not args.no_batch32:
         out["batch32_verify"] = batch32_verify(api, dg, torch, np, gt, st, seed, B32, LEN32, gamma)
         out["batch32_step"] = batch32_step(api, dg, torch, np, gt, st, seed, B32, LEN32, gamma)
+    ctx.close()
+    gd.close()
+    gt.close()
+    del gt, gd
+    torch.cuda.empty_cache()
+    if not args.no_long_context and not args.layers:
+        out["long_context"] = long_context_cases(api, dg, torch, np, args)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(st, sd_, wt, wd, args.prompt, gamma, T, seed)
     print(json.dumps(out))
@@ -277,24 +316,53 @@ def batch32_verify(api, dg, torch, np, gt, st, seed, B, len_range, gamma, T=0.7,
     na = torch.zeros(B, dtype=torch.int32, device="cuda")
     nx = torch.zeros(B, dtype=torch.int32, device="cuda")
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    ms = 0.0
+    ts = []
     for r in range(reps + 2):  # commit=False, then roll the cache lengths back: every repetition verifies the same state
         ev0.record()
         api.sd_verify(gt, ctx, None, B, gamma, T, cand, q, u, na, nx, False)
         ev1.record()
         torch.cuda.synchronize()
         if r >= 2:
-            ms += ev0.elapsed_time(ev1) / reps
+            ts.append(ev0.elapsed_time(ev1))
         for b in range(B):
             ctx.truncate(gt, b, int(lens[b]) - 1)
+    ms = float(np.mean(ts))
+    # per-kernel-class times of one more call (HIP events around every launch; adds ~2 us per launch)
+    api.set_option("profile", 1)
+    api.sd_verify(gt, ctx, None, B, gamma, T, cand, q, u, na, nx, False)
+    torch.cuda.synchronize()
+    api.set_option("profile", 0)
+    prof = api.profile_read()
     ctx.sync()
+    ctx.close()
     M = B * (gamma + 1)
-    flops = 4.0 * M * st.n_streamed_params()
+    # the method's own work: 2 flops per streamed parameter and row.  The kernels issue twice that, because every
+    # activation row enters the matrix cores as two bf16 terms (hi + lo).
+    useful = 2.0 * M * st.n_streamed_params()
+    d, F, V_ = st.d_model, st.d_ffn, st.vocab
+    per_class = {}
+    for name, params in (("gemm_qkv", 3 * d * d), ("gemm_o", d * d), ("gemm_gateup", 2 * F * d), ("gemm_down", F * d),
+                         ("gemm_lmhead", V_ * d)):
+        cnt, tot = prof.get(name, (0, 0.0))
+        if cnt:
+            us = tot / cnt * 1e3
+            per_class[name] = {"us_per_launch": us, "mfma_frac_useful": 2.0 * M * params / (us * 1e-6) / 2.5e15,
+                               "mfma_frac_issued": 4.0 * M * params / (us * 1e-6) / 2.5e15,
+                               "weight_gb_per_s": params * 2 / (us * 1e-6) / 1e9}
+    for name in ("attention", "rmsnorm", "verify_tail"):
+        cnt, tot = prof.get(name, (0, 0.0))
+        if cnt:
+            per_class[name] = {"us_per_launch": tot / cnt * 1e3, "launches": cnt}
+    kv_bytes = float(lens.sum()) * st.kv_bytes_per_token()
     return {"workload": "config 3 shape: %d prompts, lengths U[%d,%d], gamma %d, T=%g, verify pass only" %
                         (B, len_range[0], len_range[1], gamma, T),
-            "rows": M, "ms_verify": ms, "candidates_per_s": B * gamma / (ms * 1e-3),
-            "mfma_tflops": flops / (ms * 1e-3) / 1e12, "mfma_peak_tflops": 2500.0,
-            "mfma_frac": flops / (ms * 1e-3) / 1e12 / 2500.0}
+            "rows": M, "ms_verify": ms, "ms_verify_median": float(np.median(ts)), "reps": len(ts),
+            "candidates_per_s": B * gamma / (ms * 1e-3),
+            "mfma_peak_tflops": 2500.0,
+            "mfma_frac_useful": useful / (ms * 1e-3) / 2.5e15,      # headline: 2*M flops per parameter
+            "mfma_frac_issued": 2.0 * useful / (ms * 1e-3) / 2.5e15,  # hi and lo plane: 4*M flops per parameter
+            "hbm_frac": (st.n_streamed_params() * 2 + kv_bytes) / (ms * 1e-3) / 8e12,
+            "kv_gb": kv_bytes / 1e9, "kernels": per_class}
 
 
 def batch32_step(api, dg, torch, np, gt, st, seed, B, len_range, gamma, T=0.7, steps=10, warmup=2):
@@ -410,6 +478,14 @@ def prefill_bench(api, dg, torch, np, args):
 
 
 def long_context_bench(api, dg, torch, np, args):
+    res = long_context_cases(api, dg, torch, np, args)
+    print(json.dumps({"metric": "long_context_verify_candidates_per_s", "value": res[-1]["candidates_per_s"],
+                      "unit": "candidate tokens/s", "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
+                      "higher_is_better": True, "vs_baseline": None,
+                      "config": {"workload": "verify pass of configs 4 and 5 (value: config 5)"}, "cases": res}))
+
+
+def long_context_cases(api, dg, torch, np, args):
     """The verify pass of the two long-context configurations, caches filled by real prefills: config 4 (13B-shape
     target, 32 sequences at context 2048, gamma 3 / 5 / 8) and config 5 (7B-shape target, 64 sequences with
     contexts uniform in [1024, 8192], gamma 8).  Bytes = streamed weights + live KV of the call."""
@@ -450,15 +526,16 @@ def long_context_bench(api, dg, torch, np, args):
             M = B * (gamma + 1)
             nbytes = st.n_streamed_params() * 2 + float(lens.sum()) * st.kv_bytes_per_token()
             res.append({"config": name, "rows": M, "gamma": gamma, "ms_verify": ms, "bytes_gb": nbytes / 1e9,
-                        "tb_per_s": nbytes / ms / 1e9, "mfma_tflops": 4.0 * M * st.n_streamed_params() / ms / 1e9,
+                        "tb_per_s": nbytes / ms / 1e9, "hbm_frac": nbytes / ms / 1e9 / 8.0,
+                        "mfma_frac_useful": 2.0 * M * st.n_streamed_params() / (ms * 1e-3) / 2.5e15,
+                        "mfma_frac_issued": 4.0 * M * st.n_streamed_params() / (ms * 1e-3) / 2.5e15,
                         "candidates_per_s": B * gamma / ms * 1e3})
         ctx.sync()
         ctx.close()
         gt.close()
-    print(json.dumps({"metric": "long_context_verify_candidates_per_s", "value": res[-1]["candidates_per_s"],
-                      "unit": "candidate tokens/s", "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
-                      "higher_is_better": True, "vs_baseline": None,
-                      "config": {"workload": "verify pass of configs 4 and 5 (value: config 5)"}, "cases": res}))
+        del gt
+        torch.cuda.empty_cache()
+    return res
 
 
 def multi_lora_bench(api, dg, torch, np, args):
@@ -565,7 +642,53 @@ def classifier_bench(api, dg, torch, np, args):
     print(json.dumps(out))
 
 
-def cpu_baseline(st, sd_, wt, wd, n_ctx, gamma, T, seed):
+def stream_probe(api, torch, np):
+    """A kernel that only reads: buffers of the 7B shape's weight-matrix sizes (a fresh region of a 4 GiB pool every
+    launch, so nothing is cache resident) and one 1 GiB read."""
+    pool = torch.ones(1 << 32, dtype=torch.uint8, device="cuda")
+    word = torch.zeros(1, dtype=torch.int32, device="cuda")
+    res = []
+    for mb in (33.6, 100.7, 180.4, 262.1, 1073.7):
+        nbytes = int(mb * 1e6) // 4096 * 4096
+        n_regions = max(1, (1 << 32) // nbytes)
+        reps = min(n_regions, 12)
+        views = [pool[i * nbytes:(i + 1) * nbytes] for i in range(n_regions)]
+        api.stream_read(views[-1], word)
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for i in range(reps):
+            evs[i][0].record()
+            api.stream_read(views[i % n_regions], word)
+            evs[i][1].record()
+        torch.cuda.synchronize()
+        us = float(np.median([a.elapsed_time(b) for a, b in evs])) * 1e3
+        res.append({"mb": nbytes / 1e6, "us": us, "gb_per_s": nbytes / us / 1e3, "frac_of_8_tb_s": nbytes / us / 1e3 / 8000.0})
+    print(json.dumps({"metric": "stream_read_gb_per_s", "value": res[-1]["gb_per_s"], "unit": "GB/s", "n_gpus": 1,
+                      "dtype": "u8", "data": "synthetic", "higher_is_better": True, "vs_baseline": None,
+                      "config": {"workload": "plain streaming read, one launch per buffer"}, "cases": res}))
+
+
+def _cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def _omp_set_threads(n):
+    """Thread count of the oracle's OpenMP loops for the calls that follow (the oracle itself is left as it is)."""
+    import ctypes
+    try:
+        ctypes.CDLL("libgomp.so.1").omp_set_num_threads(int(n))
+        return True
+    except OSError:
+        return False
+
+
+def cpu_baseline(st, sd_, wt, wd, n_ctx, gamma, T, seed, reps=3):
     """Time the CPU oracle (as it stands) on ONE draft+verify step of the same shapes, with the
     caches holding synthetic rows for the n_ctx-token context (filling them by the oracle's own
     prefill would take minutes)."""
@@ -584,14 +707,49 @@ def cpu_baseline(st, sd_, wt, wd, n_ctx, gamma, T, seed):
     ctx_t = [int(t) for t in dg.make_prompt(seed, 0, n_ctx, st.vocab)]
     ud = dg.make_uniforms(seed, dg.DRAFT_STREAM, 0, 0, gamma)
     uv = dg.make_uniforms(seed, dg.VERIFY_STREAM, 0, 0, gamma + 1)
-    t0 = time.perf_counter()
-    cand, q, _ = dseq.draft(ctx_t, gamma, T, ud)
-    t1 = time.perf_counter()
-    tseq.verify(ctx_t, gamma, T, cand, q, uv)
-    t2 = time.perf_counter()
-    return {"value": gamma / (t2 - t0), "unit": "candidate tokens/s", "cores": threads, "kind": "oracle",
-            "sample": "one draft+verify step (gamma=5, batch 1) at context %d with synthetic cache rows, "
-                      "%d target layers; draft %.2fs, verify %.2fs" % (n_ctx, st.n_layers, t1 - t0, t2 - t1)}
+    _omp_set_threads(threads)
+    td, tv = [], []
+    for r in range(reps):   # the same step every time: both caches are rolled back to the context
+        t0 = time.perf_counter()
+        cand, q, _ = dseq.draft(ctx_t, gamma, T, ud)
+        t1 = time.perf_counter()
+        tseq.verify(ctx_t, gamma, T, cand, q, uv)
+        t2 = time.perf_counter()
+        td.append(t1 - t0)
+        tv.append(t2 - t1)
+        dseq.truncate(n_ctx - 1)
+        tseq.truncate(n_ctx - 1)
+    step_s = float(np.median(np.array(td) + np.array(tv)))
+    out = {"value": gamma / step_s, "unit": "candidate tokens/s", "cores": threads, "kind": "oracle",
+           "cpu_model": _cpu_model(), "repetitions": reps,
+           "sample": "one draft+verify step (gamma=%d, batch 1) at context %d with synthetic cache rows, %d target "
+                     "layers, median of %d repetitions; draft %.2fs, verify %.2fs" %
+                     (gamma, n_ctx, st.n_layers, reps, float(np.median(td)), float(np.median(tv)))}
+    # one thread: the same step with a 2-layer target of the same widths (all layers would take minutes), beside
+    # the same 2-layer step on all threads - the ratio is the oracle's thread scaling
+    st2 = dg.with_layers(st, 2)
+    w2 = dict(wt)
+    for k_ in ("wq", "wk", "wv", "wo", "wgate", "wup", "wdown", "norm_attn", "norm_ffn"):
+        w2[k_] = wt[k_][:2]
+    o2 = oracle.OracleModel(st2, w2)
+    s2 = o2.new_seq(n_ctx + 16)
+    for l in range(2):
+        k, v = dg.make_kv_rows(seed, l, 0, n_ctx - 1, st.n_heads, st.head_dim, st.dtype)
+        s2.set_kv(l, k, v)
+    t_l2 = {}
+    for nthr in (threads, 1):
+        if not _omp_set_threads(nthr):
+            break
+        t0 = time.perf_counter()
+        s2.verify(ctx_t, gamma, T, cand, q, uv)
+        t_l2[nthr] = time.perf_counter() - t0
+        s2.truncate(n_ctx - 1)
+    _omp_set_threads(threads)
+    if 1 in t_l2:
+        out["one_thread"] = {"sample": "the verify call alone with a 2-layer target of the same widths (LM head included)",
+                             "seconds_1_thread": t_l2[1], "seconds_%d_threads" % threads: t_l2[threads],
+                             "candidates_per_s_1_thread": gamma / t_l2[1]}
+    return out
 
 
 if __name__ == "__main__":

@@ -341,6 +341,10 @@ int sd_debug_read(sd_model *m, const char *name, float *out, int32_t rows);
  * kind 3: key cache of one head, same arguments (32-token tiles in MFMA operand order).
  * Returns -1 for an unknown kind or arguments outside the layout's domain. */
 int64_t sd_debug_layout_index(int32_t kind, int64_t a, int64_t b, int64_t c, int64_t d);
+/* Measurement helper: one kernel that only reads `bytes` bytes (16-byte aligned, dev) once with 16-byte loads,
+ * the practical ceiling that the weight-streaming kernels are compared with.  scratch_word: dev uint32, may be
+ * written.  Only enqueues on `stream`. */
+int sd_debug_stream_read(const void *buf, size_t bytes, uint32_t *scratch_word, void *stream);
 /* option "force_generic" = 1 routes every op through the simple reference kernels
  * (2: attention only, 0: off).
  * option "profile" = 1 starts bracketing every kernel launch of the forward with HIP

@@ -25,7 +25,7 @@ EXPORTS = ["sd_load_model", "sd_free_model", "sd_ctx_create", "sd_ctx_free", "sd
            "sd_ctx_set_kv", "sd_ctx_truncate", "sd_debug_read", "sd_debug_layout_index", "sd_last_logits", "sd_set_option", "sd_profile_read", "sd_last_error",
            "sd_eq1_speedup", "sd_choose_gamma", "sd_alpha_hat", "sd_model_set_lora", "sd_ctx_set_adapters",
            "sd_classifier_create", "sd_classifier_destroy", "sd_route_classifier", "sd_accept",
-           "sd_accept_static"]
+           "sd_accept_static", "sd_debug_stream_read"]
 
 
 class SdError(RuntimeError):
@@ -82,6 +82,7 @@ def lib():
         L.sd_verify.argtypes = [vp, vp, vp, i32, i32, C.c_float, vp, vp, vp, vp, vp, i32, vp]
         L.sd_commit.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp]
         L.sd_accept.argtypes = [vp, i32, i32, i32, C.c_float, vp, vp, vp, vp, vp, vp, vp]
+        L.sd_debug_stream_read.argtypes = [vp, C.c_size_t, vp, vp]
         L.sd_accept_static.argtypes = [vp, i32, i32, i32, C.c_float, vp, vp, vp, vp, vp, vp]
         L.sd_route.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp]
         L.sd_ctx_sync.argtypes = [vp, vp, vp, vp]
@@ -339,6 +340,11 @@ def sd_accept_static(logits: torch.Tensor, gamma: int, temperature: float, cand:
     assert rows == gamma + 1
     _check(lib().sd_accept_static(_dp(logits), n_seq, gamma, vocab, temperature, _dp(cand), _dp(q), _dp(uniforms),
                                   _dp(n_accepted), _dp(next_token), _stream()))
+
+
+def stream_read(buf: torch.Tensor, scratch: torch.Tensor) -> None:
+    """sd_debug_stream_read: one plain read of the whole buffer on the current stream."""
+    _check(lib().sd_debug_stream_read(_dp(buf), buf.numel() * buf.element_size(), _dp(scratch), _stream()))
 
 
 def sd_commit(ctx: Context, seq_ids: Optional[torch.Tensor], n_seq: int, gamma: int, cand: Optional[torch.Tensor],

@@ -1665,3 +1665,29 @@ hipError_t launch_set_kv(hipStream_t s, int dtype, const void *k_rows, const voi
                            (const float *)v_rows, len, H, hd, seq_off, total_cap, (float *)Kl, (float *)Vtl);
     return hipGetLastError();
 }
+
+// ---------------------------------------------------------------- measurement helper: a plain streaming read
+// Reads `n_vec` 16-byte vectors once, four loads in flight per thread, and folds them into one word (written only if
+// it hits a magic value, so that the loads cannot be dropped): what the memory system gives a kernel that does
+// nothing but read, the practical ceiling the weight-streaming GEMMs are held against.
+__global__ __launch_bounds__(256) void stream_read_kernel(const uint4 *__restrict__ p, size_t n_vec, uint32_t *out)
+{
+    const size_t tid = (size_t)blockIdx.x * 256 + threadIdx.x, stride = (size_t)gridDim.x * 256;
+    uint32_t acc = 0;
+    size_t i = tid;
+    for (; i + 3 * stride < n_vec; i += 4 * stride) {
+        const uint4 a = p[i], b = p[i + stride], c = p[i + 2 * stride], d = p[i + 3 * stride];
+        acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+    }
+    for (; i < n_vec; i += stride) {
+        const uint4 a = p[i];
+        acc ^= a.x ^ a.y ^ a.z ^ a.w;
+    }
+    if (acc == 0x9e3779b9u) out[0] = acc;
+}
+
+hipError_t launch_stream_read(hipStream_t s, const void *buf, size_t bytes, uint32_t *out)
+{
+    hipLaunchKernelGGL(stream_read_kernel, dim3(2048), dim3(256), 0, s, (const uint4 *)buf, bytes / 16, out);
+    return hipGetLastError();
+}

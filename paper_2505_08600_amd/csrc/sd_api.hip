@@ -953,6 +953,14 @@ extern "C" int sd_commit(sd_ctx *c, const int32_t *seq_ids, int32_t n_seq, int32
     return SD_OK;
 }
 
+extern "C" int sd_debug_stream_read(const void *buf, size_t bytes, uint32_t *scratch_word, void *stream)
+{
+    if (!buf || !scratch_word || bytes < 16 || ((uintptr_t)buf & 15)) return sd_fail(SD_EINVAL, "sd_debug_stream_read: bad argument");
+    hipError_t e = launch_stream_read((hipStream_t)stream, buf, bytes, scratch_word);
+    if (e != hipSuccess) return sd_fail(SD_EHIP, std::string("sd_debug_stream_read: ") + hipGetErrorString(e));
+    return SD_OK;
+}
+
 extern "C" int sd_route(const float *W, const float *b, int32_t n_drafts, int32_t emb_dim, const float *prompt_emb,
                         int32_t n, int32_t *draft_id, void *stream)
 {

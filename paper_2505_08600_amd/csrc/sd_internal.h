@@ -311,6 +311,8 @@ hipError_t launch_route(hipStream_t s, const float *W, const float *b, int n_dra
 hipError_t launch_set_kv(hipStream_t s, int dtype, const void *k_rows, const void *v_rows, int len, int H, int hd,
                          int64_t seq_off, int64_t total_cap, void *Kl, void *Vtl);
 
+hipError_t launch_stream_read(hipStream_t s, const void *buf, size_t bytes, uint32_t *out);
+
 // optimised bf16 paths (return hipErrorNotSupported when the shape is outside their domain)
 // GEMM_STORE: C receives `splits` partial slabs (slab stride c_split_stride floats) that the consumer adds;
 // GEMM_SWIGLU: Cact receives the bf16 hi/lo planes.  gemm_skinny_splits tells how many slabs to expect.

@@ -784,6 +784,7 @@ def test_config3_routed_heterogeneous_drafts_small():
     nx = torch.zeros(B, dtype=torch.int32, device="cuda")
     flagged = 0
     for k in range(n_steps):
+        refeed = []
         for g in range(4):
             if not groups[g]:
                 continue
@@ -796,7 +797,8 @@ def test_config3_routed_heterogeneous_drafts_small():
             for j, b in enumerate(groups[g]):
                 f, first_bad, _ = H.check_draft_step(trajs[b][k], cg[j], qg[j], T, dg.BF16, V)
                 flagged += int(f)
-                assert first_bad is None, "a flagged draft candidate would need a per-sequence re-feed here"
+                if first_bad is not None:   # that draft cache holds rows of other candidates from here on
+                    refeed.append((g, b, trajs[b][k].n_ctx - 1 + first_bad))
         cand_all = H.dev(np.stack([trajs[b][k].cand for b in range(B)]).astype(np.int32))
         q_all = H.dev(np.stack([trajs[b][k].q for b in range(B)]))
         uv = H.dev(np.stack([trajs[b][k].u_verify for b in range(B)]))
@@ -808,6 +810,10 @@ def test_config3_routed_heterogeneous_drafts_small():
             flagged += int(f)
         api.sd_commit(ctx, None, B, gamma, cand_all, H.dev(np.array([trajs[b][k].n_acc for b in range(B)], np.int32)),
                       H.dev(np.array([trajs[b][k].next_token for b in range(B)], np.int32)))
+        for g, b, keep in refeed:   # roll that sequence's draft cache back and re-feed the committed tokens
+            torch.cuda.synchronize()
+            ctx.truncate(gds[g], b, keep)
+            api.sd_prefill(gds[g], ctx, H.dev(np.array([b], np.int32)), 1, gamma + 2)
     nt, kv = ctx.sync(gt)
     for b in range(B):
         assert nt[b] == len(prompts[b]) + sum(s.n_acc + 1 for s in trajs[b][:n_steps]) and kv[b] == nt[b] - 1
