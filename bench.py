@@ -282,6 +282,35 @@ def main():
                           "measured_speedup": emitted_per_s / (B / (ms_ar * 1e-3)),
                           "eq1_with_measured_alpha_c": eq1}
 
+    # ---- the step at the candidate count Equation 1 picks for the measured (alpha, c): same loop, other gamma
+    if best_gamma >= 1 and best_gamma != gamma:
+        g2, n2 = best_gamma, 24
+        ud2 = [dev(dg.make_uniforms(seed + 1, dg.DRAFT_STREAM, 0, k, g2)[None]) for k in range(n2)]
+        uv2 = [dev(dg.make_uniforms(seed + 1, dg.VERIFY_STREAM, 0, k, g2 + 1)[None]) for k in range(n2)]
+        cand2 = torch.zeros((B, g2), dtype=torch.int32, device="cuda")
+        q2 = torch.zeros((B, g2, V), dtype=torch.float32, device="cuda")
+        ctx2 = api.Context([args.prompt + n2 * (g2 + 1) + 16])
+        ctx2.attach(gt)
+        ctx2.attach(gd)
+        ctx2.set_tokens([prompt])
+        api.sd_prefill(gt, ctx2, None, 1, len(prompt) - 1)
+        api.sd_prefill(gd, ctx2, None, 1, len(prompt) - 1)
+        na2 = torch.zeros((n2, B), dtype=torch.int32, device="cuda")
+        for k in range(n2):
+            if k == 4:
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+            api.sd_draft(gd, ctx2, None, B, g2, T, ud2[k] if T > 0 else None, cand2, q2 if T > 0 else None)
+            api.sd_verify(gt, ctx2, None, B, g2, T, cand2, q2 if T > 0 else None, uv2[k] if T > 0 else None, na, nx, True)
+            na2[k].copy_(na)
+        torch.cuda.synchronize()
+        dt2 = time.perf_counter() - t0
+        ctx2.sync()
+        ctx2.close()
+        acc2 = na2[4:, 0].cpu().numpy()
+        out["step_at_eq1_gamma"] = {"gamma": g2, "steps": n2 - 4, "ms_per_step": dt2 / (n2 - 4) * 1e3,
+                                    "emitted_tokens_per_s": float((acc2 + 1).sum() / dt2),
+                                    "emitted_tokens_per_s_at_gamma_5": emitted_per_s}
     if not args.no_batch32:
         out["batch32_verify"] = batch32_verify(api, dg, torch, np, gt, st, seed, B32, LEN32, gamma)
         out["batch32_step"] = batch32_step(api, dg, torch, np, gt, st, seed, B32, LEN32, gamma)

@@ -306,6 +306,30 @@ int32_t sd_choose_gamma(double alpha, double c, int32_t gamma_max, double *speed
  * a NaN when nothing was examined or a value is outside [0, gamma]. */
 double sd_alpha_hat(const int32_t *n_accepted /*host*/, int32_t n_steps, int32_t gamma);
 
+/* ---- candidate counts per sequence: Equation 1 inside the loop ----
+ *
+ * A context keeps, per sequence, the accepted and the examined candidates so far (updated on the device by every
+ * commit; reset by sd_ctx_set_tokens): their ratio is the running estimate of Equation 1's alpha.  It can also
+ * carry a candidate count per sequence.  While it does, sd_draft / sd_verify / sd_commit called with `gamma` row
+ * slots let sequence b draft, verify and commit g_b = min(count_b, gamma) candidates: the draft leaves
+ * cand[j][g_b..] and q[j][g_b..] untouched, the verify feeds g_b + 1 rows of it, tests uniforms[j][0..g_b) and
+ * draws the next token with uniforms[j][g_b]; g_b = 0 is a plain autoregressive step of that sequence.  Array
+ * strides stay those of `gamma`.  The batch still moves in lockstep: no host synchronisation is added. */
+
+/* Counts given by the host: gammas host int32[B], each in [0, 15]; NULL switches per-sequence counts off (the
+ * default).  Synchronises. */
+int sd_policy_set(sd_ctx *c, const int32_t *gammas);
+/* Counts chosen on the device for the selected sequences (seq_ids dev, or NULL): for each, alpha = accepted /
+ * examined (alpha0 while nothing was examined) and the count in [0, gamma_max] that maximises Equation 1 with
+ * cost ratio c_ratio, the smallest on ties - the same arithmetic, operation by operation, as sd_choose_gamma.
+ * Switches per-sequence counts on (sequences never chosen for keep gamma_max).  gammas_out: dev int32[n_seq], or
+ * NULL.  Enqueues one kernel on `stream` (the first call after sd_policy_set(NULL) also synchronises). */
+int sd_policy_choose(sd_ctx *c, const int32_t *seq_ids /*dev*/, int32_t n_seq, double c_ratio, int32_t gamma_max,
+                     double alpha0, int32_t *gammas_out, void *stream);
+/* Host copies (int32[B] each, any may be NULL) of the counts and of the accepted / examined totals.  Returns 1 if
+ * per-sequence counts are on, 0 if off, a negative sd_status on failure.  Synchronises. */
+int sd_policy_read(sd_ctx *c, int32_t *gammas, int32_t *accepted, int32_t *examined);
+
 /* ---- inspection and test hooks (synchronising; not on the hot path) ---- */
 
 /* Copy token counts (and model m's cache lengths, if m and kv_len are non-NULL) to

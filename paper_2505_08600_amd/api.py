@@ -25,7 +25,8 @@ EXPORTS = ["sd_load_model", "sd_free_model", "sd_ctx_create", "sd_ctx_free", "sd
            "sd_ctx_set_kv", "sd_ctx_truncate", "sd_debug_read", "sd_debug_layout_index", "sd_last_logits", "sd_set_option", "sd_profile_read", "sd_last_error",
            "sd_eq1_speedup", "sd_choose_gamma", "sd_alpha_hat", "sd_model_set_lora", "sd_ctx_set_adapters",
            "sd_classifier_create", "sd_classifier_destroy", "sd_route_classifier", "sd_accept",
-           "sd_accept_static", "sd_debug_stream_read"]
+           "sd_accept_static", "sd_debug_stream_read",
+           "sd_policy_set", "sd_policy_choose", "sd_policy_read"]
 
 
 class SdError(RuntimeError):
@@ -82,6 +83,9 @@ def lib():
         L.sd_verify.argtypes = [vp, vp, vp, i32, i32, C.c_float, vp, vp, vp, vp, vp, i32, vp]
         L.sd_commit.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp]
         L.sd_accept.argtypes = [vp, i32, i32, i32, C.c_float, vp, vp, vp, vp, vp, vp, vp]
+        L.sd_policy_set.argtypes = [vp, vp]
+        L.sd_policy_choose.argtypes = [vp, vp, i32, C.c_double, i32, C.c_double, vp, vp]
+        L.sd_policy_read.argtypes = [vp, vp, vp, vp]
         L.sd_debug_stream_read.argtypes = [vp, C.c_size_t, vp, vp]
         L.sd_accept_static.argtypes = [vp, i32, i32, i32, C.c_float, vp, vp, vp, vp, vp, vp]
         L.sd_route.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp]
@@ -283,6 +287,29 @@ class Context:
         a = _np_i32(adapter_ids)
         assert len(a) == self.B
         _check(lib().sd_ctx_set_adapters(self.h, m.h, a.ctypes.data_as(C.c_void_p)))
+
+    def policy_set(self, gammas: Optional[Sequence[int]]) -> None:
+        """sd_policy_set: candidate count per sequence (None: off)."""
+        if gammas is None:
+            _check(lib().sd_policy_set(self.h, None))
+            return
+        g = _np_i32(gammas)
+        assert len(g) == self.B
+        _check(lib().sd_policy_set(self.h, g.ctypes.data_as(C.c_void_p)))
+
+    def policy_choose(self, seq_ids: Optional[torch.Tensor], n_seq: int, c_ratio: float, gamma_max: int, alpha0: float,
+                      gammas_out: Optional[torch.Tensor] = None) -> None:
+        """sd_policy_choose: counts from Equation 1 and the running acceptance estimate, on the device."""
+        _check(lib().sd_policy_choose(self.h, _dp(seq_ids), n_seq, c_ratio, gamma_max, alpha0, _dp(gammas_out), _stream()))
+
+    def policy_read(self):
+        """-> (per-sequence counts on?, gammas[B], accepted[B], examined[B])"""
+        g, a, e = (np.zeros(self.B, np.int32) for _ in range(3))
+        rc = lib().sd_policy_read(self.h, g.ctypes.data_as(C.c_void_p), a.ctypes.data_as(C.c_void_p),
+                                  e.ctypes.data_as(C.c_void_p))
+        if rc < 0:
+            _check(rc)
+        return bool(rc), g, a, e
 
     def truncate(self, m: Model, seq: int, length: int) -> None:
         _check(lib().sd_ctx_truncate(self.h, m.h, seq, length))

@@ -210,10 +210,12 @@ __global__ void plan_kernel(int mode, int R, int n_seq, const int32_t *seq_ids, 
                 atomicOr(cv.status, 64);
                 nq = 0;
             }
+            // (a sequence whose candidate count is 0 still feeds its catch-up rows, so that its draft cache
+            // stays within two tokens of the sequence; its sampler draws nothing)
         } else if (mode == PLAN_CAND) {
             nq = 1;
         } else { // PLAN_VERIFY: rows (pending token, candidates) at positions n-1 ..
-            nq = R;
+            nq = seq_gamma(cv, b, gamma) + 1; // (= R unless the context carries per-sequence candidate counts)
             if (kv != n - 1) atomicOr(cv.status, 2);
             kv0 = n - 1;
         }
@@ -225,7 +227,7 @@ __global__ void plan_kernel(int mode, int R, int n_seq, const int32_t *seq_ids, 
         if (kv0 + nq > cap) { // never write beyond the sequence's cache rows
             atomicOr(cv.status, 1);
             nq = cap - kv0 > 0 ? cap - kv0 : 0;
-            if (mode == PLAN_VERIFY && nq < R) nq = 0;
+            if (mode == PLAN_VERIFY) nq = 0;
         }
         for (int r = 0; r < R; r++) {
             int row = j * R + r;
@@ -1214,6 +1216,7 @@ __device__ void plan_next_cand(const NextPlan &np, int j, int tok)
     int *kvp = cv.kvlen + (size_t)np.slot * cv.B + b;
     int kv0 = *kvp, nq = 1;
     const int cap = cv.cap[b];
+    if (np.next_idx >= seq_gamma(cv, b, np.gamma)) nq = 0; // the sequence has drawn all its candidates
     if (n < 1) { // an empty sequence has no pending token
         atomicOr(cv.status, 2);
         nq = 0;
@@ -1238,12 +1241,27 @@ __device__ void plan_next_cand(const NextPlan &np, int j, int tok)
     *kvp = kv0 + nq;
 }
 
+// Does sequence slot j draw candidate idx in this draft call?  With per-sequence candidate counts a sequence that
+// has drawn all of its own sits the remaining forwards out: its rows are unused, nothing of it is written (the
+// sampler that drew its last candidate has already left its plan entry empty).
+__device__ __forceinline__ bool draft_seq_active(const NextPlan &np, int j, int gamma, int idx)
+{
+    if (!np.cv.gam) return true;
+    const int b = np.seq_ids ? np.seq_ids[j] : j;
+    if (b < 0 || b >= np.cv.B) return true; // (the plan has flagged it; behave as without counts)
+    return idx < seq_gamma(np.cv, b, gamma);
+}
+
 __global__ __launch_bounds__(ROW_THREADS) void draft_sample_fast_kernel(const float *logits, int V, float T,
                                                                          const float *u, int gamma, int idx,
                                                                          int32_t *cand, float *q, NextPlan next)
 {
     __shared__ FastScratch fs;
     const int j = blockIdx.x;
+    if (!draft_seq_active(next, j, gamma, idx)) { // (uniform over the block) nothing to draw: keep its plan entry empty
+        if (threadIdx.x == 0 && next.enabled) plan_next_cand(next, j, 0);
+        return;
+    }
     RowRegs r;
     row_load(logits + (size_t)j * V, V, -3.0e38f, r);
     float mx, z;
@@ -1287,6 +1305,10 @@ __global__ __launch_bounds__(1024) void draft_sample_kernel(const float *logits,
     __shared__ float redv[32];
     __shared__ int redi[32];
     int j = blockIdx.x;
+    if (!draft_seq_active(next, j, gamma, idx)) { // (uniform over the block) nothing to draw: keep its plan entry empty
+        if (threadIdx.x == 0 && next.enabled) plan_next_cand(next, j, 0);
+        return;
+    }
     const float *row = logits + (size_t)j * V;
     float mx;
     int am;
@@ -1360,6 +1382,10 @@ __device__ void commit_one(CtxView cv, int b, int gamma, const int32_t *cand_j, 
     }
     for (int i = 0; i < n_acc; i++) cv.tokens[off + n + i] = cand_j[i];
     cv.tokens[off + n + n_acc] = next_tok;
+    // running estimate of Equation 1's alpha: accepted over examined candidates (a step that rejects at
+    // position k has examined k + 1 of them)
+    cv.pol[b] += n_acc;
+    cv.pol[cv.B + b] += n_acc < gamma ? n_acc + 1 : gamma;
     int nn = n + n_acc + 1;
     cv.ntok[b] = nn;
     for (int sl = 0; sl < cv.n_slots; sl++) {
@@ -1378,7 +1404,47 @@ __global__ void commit_kernel(CtxView cv, const int32_t *seq_ids, int n_seq, int
         atomicOr(cv.status, 4);
         return;
     }
-    commit_one(cv, b, gamma, cand + (size_t)j * gamma, n_acc[j], next_tok[j]);
+    commit_one(cv, b, seq_gamma(cv, b, gamma), cand + (size_t)j * gamma, n_acc[j], next_tok[j]);
+}
+
+// Candidate-count policy on the device (Section 1, Equation 1): for each selected sequence, alpha = accepted / examined so
+// far (alpha0 before anything was examined) and gamma = the count in [0, gamma_max] that maximises
+// (1 - alpha^(gamma+1)) / ((1 - alpha) (gamma c + 1)), the smallest on ties.  Written out operation by operation
+// (no fused multiply-add), in the order the host function sd_choose_gamma uses, so both pick the same count.
+__global__ void policy_choose_kernel(CtxView cv, const int32_t *seq_ids, int n_seq, double c_ratio, int gamma_max,
+                                     double alpha0, int32_t *gamma_all, int32_t *gammas_out)
+{
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= n_seq) return;
+    const int b = seq_ids ? seq_ids[j] : j;
+    if (b < 0 || b >= cv.B) {
+        atomicOr(cv.status, 4);
+        if (gammas_out) gammas_out[j] = 0;
+        return;
+    }
+    const int acc = cv.pol[b], exam = cv.pol[cv.B + b];
+    const double alpha = exam > 0 ? __ddiv_rn((double)acc, (double)exam) : alpha0;
+    int best = 0;
+    double best_v = -1.0;
+    for (int g = 0; g <= gamma_max; g++) {
+        double tokens = 0.0, term = 1.0;
+        for (int i = 0; i <= g; i++) {
+            tokens = __dadd_rn(tokens, term);
+            term = __dmul_rn(term, alpha);
+        }
+        const double v = __ddiv_rn(tokens, __dadd_rn(__dmul_rn((double)g, c_ratio), 1.0));
+        if (v > best_v) best = g, best_v = v;
+    }
+    gamma_all[b] = best;
+    if (gammas_out) gammas_out[j] = best;
+}
+
+hipError_t launch_policy_choose(hipStream_t s, CtxView cv, const int32_t *seq_ids, int n_seq, double c_ratio, int gamma_max,
+                                double alpha0, int32_t *gamma_all, int32_t *gammas_out)
+{
+    hipLaunchKernelGGL(policy_choose_kernel, dim3((n_seq + 255) / 256), dim3(256), 0, s, cv, seq_ids, n_seq, c_ratio, gamma_max,
+                       alpha0, gamma_all, gammas_out);
+    return hipGetLastError();
 }
 
 hipError_t launch_commit(hipStream_t s, CtxView cv, const int32_t *seq_ids, int n_seq, int gamma,
@@ -1410,6 +1476,11 @@ __global__ __launch_bounds__(1024) void verify_tail_kernel(const float *logits, 
     const float *rows = logits + (size_t)j * (gamma + 1) * V;
     const int32_t *cj = cand + (size_t)j * gamma;
     float invT = T > 0.f ? 1.0f / T : 0.f;
+    const int stride_g = gamma; // row slots of the call: strides of cand, q and u
+    {   // with per-sequence candidate counts this sequence has gj <= gamma candidates (and gj + 1 live rows)
+        const int bb = seq_ids ? seq_ids[j] : j;
+        if (cv.gam && bb >= 0 && bb < cv.B) gamma = seq_gamma(cv, bb, gamma);
+    }
     for (int i = 0; i <= gamma; i++) {
         float mx;
         int am;
@@ -1432,9 +1503,9 @@ __global__ __launch_bounds__(1024) void verify_tail_kernel(const float *logits, 
             else if (c < 0 || c >= V) ok = false;
             else {
                 float p = expf((rows[(size_t)i * V + c] - s_mx[i]) * invT) / s_z[i];
-                float qc = q[((size_t)j * gamma + i) * V + c];
+                float qc = q[((size_t)j * stride_g + i) * V + c];
                 qc = fmaxf(qc, 1.17549435e-38f);
-                ok = u[j * (gamma + 1) + i] < p / qc;
+                ok = u[j * (stride_g + 1) + i] < p / qc;
             }
             if (!ok) break;
             n_acc++;
@@ -1449,7 +1520,7 @@ __global__ __launch_bounds__(1024) void verify_tail_kernel(const float *logits, 
     } else {
         const float *row = rows + (size_t)n_acc * V;
         float mx = s_mx[n_acc], invZ = 1.0f / s_z[n_acc];
-        float uu = u[j * (gamma + 1) + gamma];
+        float uu = u[j * (stride_g + 1) + gamma];
         auto pfun = [&](int v) {
             float4 f = load4_guard(row, v, V, -3.0e38f);
             float4 p;
@@ -1461,7 +1532,7 @@ __global__ __launch_bounds__(1024) void verify_tail_kernel(const float *logits, 
         };
         bool use_p = n_acc >= gamma;
         if (!use_p) {
-            const float *qrow = q + ((size_t)j * gamma + n_acc) * V;
+            const float *qrow = q + ((size_t)j * stride_g + n_acc) * V;
             auto rfun = [&](int v) {
                 float4 p = pfun(v);
                 float4 qq = load4_guard(qrow, v, V, 0.f);
@@ -1523,6 +1594,11 @@ __global__ __launch_bounds__(ROW_THREADS) void verify_decide_kernel(const float 
     const float *st = stats + (size_t)j * (gamma + 1) * 3;
     const int32_t *cj = cand + (size_t)j * gamma;
     const float invT = T > 0.f ? 1.0f / T : 0.f;
+    const int stride_g = gamma; // row slots of the call: strides of cand, q and u
+    {   // with per-sequence candidate counts this sequence has gj <= gamma candidates (and gj + 1 live rows)
+        const int bb = seq_ids ? seq_ids[j] : j;
+        if (cv.gam && bb >= 0 && bb < cv.B) gamma = seq_gamma(cv, bb, gamma);
+    }
     if ((int)threadIdx.x < gamma) {
         const int i = threadIdx.x;
         const int c = cj[i];
@@ -1531,9 +1607,9 @@ __global__ __launch_bounds__(ROW_THREADS) void verify_decide_kernel(const float 
         else if (c < 0 || c >= V) ok = false;
         else {
             const float p = expf((rows[(size_t)i * V + c] - st[3 * i]) * invT) / st[3 * i + 1];
-            float qc = q[((size_t)j * gamma + i) * V + c];
+            float qc = q[((size_t)j * stride_g + i) * V + c];
             qc = fmaxf(qc, 1.17549435e-38f);
-            ok = u[j * (gamma + 1) + i] < p / qc;
+            ok = u[j * (stride_g + 1) + i] < p / qc;
         }
         s_ok[i] = ok ? 1 : 0;
     }
@@ -1550,7 +1626,7 @@ __global__ __launch_bounds__(ROW_THREADS) void verify_decide_kernel(const float 
         next = __float_as_int(st[3 * n_acc + 2]);
     } else {
         const float mx = st[3 * n_acc], invZ = 1.0f / st[3 * n_acc + 1];
-        const float uu = u[j * (gamma + 1) + gamma];
+        const float uu = u[j * (stride_g + 1) + gamma];
         RowRegs r;
         row_load(rows + (size_t)n_acc * V, V, -3.0e38f, r);
 #pragma unroll
@@ -1566,7 +1642,7 @@ __global__ __launch_bounds__(ROW_THREADS) void verify_decide_kernel(const float 
         next = 0;
         if (!use_p) {
             RowRegs w;
-            row_load(q + ((size_t)j * gamma + n_acc) * V, V, 0.f, w);
+            row_load(q + ((size_t)j * stride_g + n_acc) * V, V, 0.f, w);
 #pragma unroll
             for (int it = 0; it < ROW_NSEG; it++) {
                 w.f[it].x = fmaxf(r.f[it].x - w.f[it].x, 0.f);

@@ -419,6 +419,9 @@ extern "C" int sd_ctx_create(int32_t batch, const int32_t *caps, sd_ctx **out)
     if (e == hipSuccess) e = hipMalloc((void **)&c->d_kvlen, sizeof(int32_t) * batch * SD_MAX_SLOTS);
     if (e == hipSuccess) e = hipMalloc((void **)&c->d_status, sizeof(int32_t));
     if (e == hipSuccess) e = hipMalloc((void **)&c->d_adapter, sizeof(int32_t) * batch * SD_MAX_SLOTS);
+    c->use_gamma = 0;
+    if (e == hipSuccess) e = hipMalloc((void **)&c->d_gamma, sizeof(int32_t) * batch);
+    if (e == hipSuccess) e = hipMalloc((void **)&c->d_policy, sizeof(int32_t) * batch * 2);
     if (e != hipSuccess) {
         delete c;
         return sd_fail(SD_EHIP, std::string("sd_ctx_create: hipMalloc: ") + hipGetErrorString(e));
@@ -430,6 +433,8 @@ extern "C" int sd_ctx_create(int32_t batch, const int32_t *caps, sd_ctx **out)
     SD_HIP(hipMemset(c->d_kvlen, 0, sizeof(int32_t) * batch * SD_MAX_SLOTS));
     SD_HIP(hipMemset(c->d_status, 0, sizeof(int32_t)));
     SD_HIP(hipMemset(c->d_adapter, 0xff, sizeof(int32_t) * batch * SD_MAX_SLOTS)); // -1: no adapter
+    SD_HIP(hipMemset(c->d_gamma, 0, sizeof(int32_t) * batch));
+    SD_HIP(hipMemset(c->d_policy, 0, sizeof(int32_t) * batch * 2));
     SD_HIP(hipDeviceSynchronize());
     *out = c;
     return SD_OK;
@@ -450,6 +455,8 @@ extern "C" int sd_ctx_free(sd_ctx *c)
     (void)hipFree(c->d_kvlen);
     (void)hipFree(c->d_status);
     (void)hipFree(c->d_adapter);
+    (void)hipFree(c->d_gamma);
+    (void)hipFree(c->d_policy);
     delete c;
     return SD_OK;
 }
@@ -513,6 +520,8 @@ extern "C" int sd_ctx_set_tokens(sd_ctx *c, const int32_t *tokens, const int32_t
         SD_HIP(hipMemcpy(c->d_ntok + b, &lens[j], sizeof(int32_t), hipMemcpyHostToDevice));
         for (int s = 0; s < SD_MAX_SLOTS; s++)
             SD_HIP(hipMemcpy(c->d_kvlen + (size_t)s * c->B + b, &zero[0], sizeof(int32_t), hipMemcpyHostToDevice));
+        for (int h = 0; h < 2; h++) // a new sequence starts without acceptance history
+            SD_HIP(hipMemcpy(c->d_policy + (size_t)h * c->B + b, &zero[0], sizeof(int32_t), hipMemcpyHostToDevice));
         pos += lens[j];
         c->len_upper = std::max(c->len_upper, lens[j]);
     }
@@ -909,7 +918,7 @@ extern "C" int sd_draft(sd_model *draft, sd_ctx *c, const int32_t *seq_ids, int3
         ProfScope ps(T_SAMPLE, s);
         // every sampler but the last also writes the plan of the forward that feeds its token (the last
         // candidate is never fed)
-        const NextPlan next = {draft->plan, c->view(), seq_ids, slot, draft->cfg.vocab, i + 1 < gamma ? 1 : 0};
+        const NextPlan next = {draft->plan, c->view(), seq_ids, slot, draft->cfg.vocab, i + 1 < gamma ? 1 : 0, gamma, i + 1};
         hipError_t e = launch_draft_sample(s, draft->logits, n_seq, draft->cfg.vocab, temperature, uniforms, gamma, i,
                                            cand, q, next);
         if (e != hipSuccess) return sd_fail(SD_EHIP, std::string("sd_draft: sample: ") + hipGetErrorString(e));
@@ -951,6 +960,51 @@ extern "C" int sd_commit(sd_ctx *c, const int32_t *seq_ids, int32_t n_seq, int32
     if (e != hipSuccess) return sd_fail(SD_EHIP, std::string("sd_commit: ") + hipGetErrorString(e));
     c->len_upper = std::min(c->len_upper + gamma + 1, c->max_cap);
     return SD_OK;
+}
+
+// ---------------------------------------------------------------- per-sequence candidate counts (Equation 1 in the loop)
+extern "C" int sd_policy_set(sd_ctx *c, const int32_t *gammas)
+{
+    if (!c) return sd_fail(SD_EINVAL, "sd_policy_set: null context");
+    SD_HIP(hipDeviceSynchronize());
+    if (!gammas) {
+        c->use_gamma = 0;
+        return SD_OK;
+    }
+    for (int b = 0; b < c->B; b++)
+        if (gammas[b] < 0 || gammas[b] > SD_MAX_GAMMA) return sd_fail(SD_EINVAL, "sd_policy_set: gamma outside [0, 15]");
+    SD_HIP(hipMemcpy(c->d_gamma, gammas, sizeof(int32_t) * c->B, hipMemcpyHostToDevice));
+    c->use_gamma = 1;
+    return SD_OK;
+}
+
+extern "C" int sd_policy_choose(sd_ctx *c, const int32_t *seq_ids, int32_t n_seq, double c_ratio, int32_t gamma_max,
+                                double alpha0, int32_t *gammas_out, void *stream)
+{
+    if (!c) return sd_fail(SD_EINVAL, "sd_policy_choose: null context");
+    if (n_seq < 1 || n_seq > c->B) return sd_fail(SD_EINVAL, "sd_policy_choose: n_seq out of range");
+    if (!(c_ratio >= 0.0) || !(alpha0 >= 0.0 && alpha0 <= 1.0) || gamma_max < 0 || gamma_max > SD_MAX_GAMMA)
+        return sd_fail(SD_EINVAL, "sd_policy_choose: c >= 0, alpha0 in [0,1], 0 <= gamma_max <= 15");
+    if (!c->use_gamma) { // sequences outside this selection keep the largest count until they are chosen for
+        std::vector<int32_t> all(c->B, gamma_max);
+        SD_HIP(hipMemcpyAsync(c->d_gamma, all.data(), sizeof(int32_t) * c->B, hipMemcpyHostToDevice, (hipStream_t)stream));
+        SD_HIP(hipStreamSynchronize((hipStream_t)stream));
+        c->use_gamma = 1;
+    }
+    hipError_t e = launch_policy_choose((hipStream_t)stream, c->view(), seq_ids, n_seq, c_ratio, gamma_max, alpha0, c->d_gamma,
+                                        gammas_out);
+    if (e != hipSuccess) return sd_fail(SD_EHIP, std::string("sd_policy_choose: ") + hipGetErrorString(e));
+    return SD_OK;
+}
+
+extern "C" int sd_policy_read(sd_ctx *c, int32_t *gammas, int32_t *accepted, int32_t *examined)
+{
+    if (!c) return sd_fail(SD_EINVAL, "sd_policy_read: null context");
+    SD_HIP(hipDeviceSynchronize());
+    if (gammas) SD_HIP(hipMemcpy(gammas, c->d_gamma, sizeof(int32_t) * c->B, hipMemcpyDeviceToHost));
+    if (accepted) SD_HIP(hipMemcpy(accepted, c->d_policy, sizeof(int32_t) * c->B, hipMemcpyDeviceToHost));
+    if (examined) SD_HIP(hipMemcpy(examined, c->d_policy + c->B, sizeof(int32_t) * c->B, hipMemcpyDeviceToHost));
+    return c->use_gamma ? 1 : 0;
 }
 
 extern "C" int sd_debug_stream_read(const void *buf, size_t bytes, uint32_t *scratch_word, void *stream)

@@ -135,7 +135,16 @@ struct CtxView {
     int32_t *kvlen;     // [SD_MAX_SLOTS][B]
     int32_t *status;    // [1] sticky error bits
     const int32_t *adapter; // [SD_MAX_SLOTS][B] low-rank adapter of each sequence per model slot (-1: none)
+    const int32_t *gam;     // [B] candidates per step of each sequence, or nullptr: the call's gamma for all
+    int32_t *pol;           // [2][B] accepted / examined candidates so far (the running estimate of Equation 1's alpha)
 };
+// candidates sequence b drafts / has verified in a call made with `gamma` row slots
+__device__ __forceinline__ int seq_gamma(const CtxView &cv, int b, int gamma)
+{
+    if (!cv.gam) return gamma;
+    const int g = cv.gam[b];
+    return g < 0 ? 0 : (g > gamma ? gamma : g);
+}
 
 // Row plan of one forward: R row slots per selected sequence j (rows j*R .. j*R+R-1).
 struct PlanView {
@@ -160,6 +169,7 @@ struct NextPlan {
     CtxView cv;
     const int32_t *seq_ids;
     int32_t slot, vocab, enabled;
+    int32_t gamma, next_idx; // row slots of the draft call; index of the candidate the planned forward leads to
 };
 
 struct WeightSeg { // up to three matrices stacked along N (q,k,v or gate,up)
@@ -234,6 +244,8 @@ struct sd_ctx {
     std::vector<int64_t> off;
     int64_t *d_off;
     int32_t *d_cap, *d_tokens, *d_ntok, *d_kvlen, *d_status, *d_adapter;
+    int32_t *d_gamma, *d_policy; // per-sequence candidate counts [B] (used when use_gamma) and accepted / examined [2][B]
+    int use_gamma;
     int n_slots;
     sd_model *models[SD_MAX_SLOTS];
     void *kcache[SD_MAX_SLOTS];
@@ -252,6 +264,8 @@ struct sd_ctx {
         v.kvlen = d_kvlen;
         v.status = d_status;
         v.adapter = d_adapter;
+        v.gam = use_gamma ? d_gamma : nullptr;
+        v.pol = d_policy;
         return v;
     }
 };
@@ -304,6 +318,8 @@ hipError_t launch_draft_sample(hipStream_t s, const float *logits, int n_seq, in
 hipError_t launch_verify_tail(hipStream_t s, const float *logits, int n_seq, int gamma, int V, float T,
                               const int32_t *cand, const float *q, const float *u, const int32_t *seq_ids,
                               int32_t *n_acc, int32_t *next_tok, int commit, CtxView cv, float *stats);
+hipError_t launch_policy_choose(hipStream_t s, CtxView cv, const int32_t *seq_ids, int n_seq, double c_ratio, int gamma_max,
+                                double alpha0, int32_t *gamma_all, int32_t *gammas_out);
 hipError_t launch_commit(hipStream_t s, CtxView cv, const int32_t *seq_ids, int n_seq, int gamma,
                          const int32_t *cand, const int32_t *n_acc, const int32_t *next_tok);
 hipError_t launch_route(hipStream_t s, const float *W, const float *b, int n_drafts, int emb, const float *e, int n,
