@@ -327,20 +327,24 @@ def test_draft_and_verify_are_graph_capturable_and_replays_match_eager():
     pair.close()
 
 
-@pytest.mark.parametrize("shape_name,tol,max_rows", [("tiny_target", 1e-4, 96), ("small_target_bf16", 2e-2, 96),
-                                                     ("small_target_bf16", 2e-2, 144), ("small_target_bf16", 2e-2, 192)])
-def test_prefill_in_row_groups_matches_oracle(shape_name, tol, max_rows):
+@pytest.mark.parametrize("shape_name,tol,max_rows,lens", [
+    ("tiny_target", 1e-4, 96, [9, 41, 150]), ("small_target_bf16", 2e-2, 96, [9, 41, 150]),
+    ("small_target_bf16", 2e-2, 144, [9, 41, 150]), ("small_target_bf16", 2e-2, 192, [9, 41, 150]),
+    ("small_target_bf16", 2e-2, 576, [1000, 333, 17]),   # 12 groups per sequence and forward
+    ("small_draft_bf16", 2e-2, 192, [1000, 70, 129])])   # head width 64, several forwards
+def test_prefill_in_row_groups_matches_oracle(shape_name, tol, max_rows, lens):
     """With a workspace of 96 rows sd_prefill feeds three ragged prompts in groups of 16 rows, two groups
     per sequence and forward (plan slots), through the separate cache-append and attention kernels; prompt
     lengths cover an empty second group, a partial one and several forwards.  The cache it leaves must
     give the oracle's logits in the verify pass that follows, and the oracle's decisions.  With 144 and 192
-    rows there are three and four groups per sequence."""
-    _say(f"prefill in row groups, {shape_name}, workspace {max_rows} rows")
+    rows there are three and four groups per sequence; the 1000-token prompts take several forwards of up to
+    twelve groups."""
+    _say(f"prefill in row groups, {shape_name}, workspace {max_rows} rows, prompts {lens}")
     st_ = dg.SHAPES[shape_name]
     w = dg.make_weights(st_, 81, BF16_LM_SCALE if st_.dtype == dg.BF16 else 1.0)
     om = oracle.OracleModel(st_, w)
-    gm = api.Model(st_, w, max_rows=max_rows, max_pos=256)
-    lens, gamma, V = [9, 41, 150], 3, st_.vocab
+    gm = api.Model(st_, w, max_rows=max_rows, max_pos=max(lens) + 64)
+    gamma, V = 3, st_.vocab
     prompts = [[int(t) for t in dg.make_prompt(81, b, n, V)] for b, n in enumerate(lens)]
     ctx = api.Context([n + 16 for n in lens])
     ctx.attach(gm)
@@ -360,8 +364,9 @@ def test_prefill_in_row_groups_matches_oracle(shape_name, tol, max_rows):
         rel = np.abs(lg[b] - r_lg).max() / np.abs(r_lg).max()
         _say(f"  sequence {b} (prompt {lens[b]}): logits rel err {rel:.2e}")
         assert rel < tol
-        if (int(na[b]), int(nx[b])) != (r_na, r_nx):
-            assert st_.dtype == dg.BF16 and mg[:min(r_na, int(na[b])) + 1].min() < 0.05, (b, na[b], nx[b], r_na, r_nx, mg)
+        if (int(na[b]), int(nx[b])) != (r_na, r_nx):   # greedy: only a top-1/top-2 gap below the flat threshold may flip
+            i = min(r_na, int(na[b]))
+            assert mg[i] < H.MARGIN_THR[st_.dtype] * np.abs(r_lg[i]).max(), (b, na[b], nx[b], r_na, r_nx, mg)
     ctx.close()
     gm.close()
 
