@@ -327,6 +327,69 @@ def test_draft_and_verify_are_graph_capturable_and_replays_match_eager():
     pair.close()
 
 
+def test_committing_graph_replayed_far_past_its_capture_time_lengths():
+    """A graph of one committing greedy step (draft + verify with commit) of the fp32 pair - whose attention runs on
+    the plain kernel, the one that sizes a score buffer on the host - is captured when the sequence holds 20 tokens
+    and replayed until it holds more than three times that.  Launch sizes are those of capture time; results must
+    not depend on them: the replays emit exactly the tokens of the same steps launched eagerly (which are the
+    target's own greedy decoding, checked against the oracle), and no status flag is raised."""
+    _say("fp32: committing graph replayed past the capture-time lengths")
+    st_, sd_ = TINY_T, dg.SHAPES["tiny_draft"]
+    wt = dg.make_weights(st_, 45, 20.0)
+    pair = H.Pair(st_, st_, 45, target_weights=wt, draft_weights=dg.perturbed_copy(wt, st_, seed=46, rel=0.1))
+    gamma, n_steps, V = 3, 24, st_.vocab
+    prompt = [int(t) for t in dg.make_prompt(45, 0, 20, V)]
+    cand = torch.zeros((1, gamma), dtype=torch.int32, device="cuda")
+    na = torch.zeros(1, dtype=torch.int32, device="cuda")
+    nx = torch.zeros(1, dtype=torch.int32, device="cuda")
+
+    def new_ctx():
+        c = api.Context([160])
+        c.attach(pair.gt)
+        c.attach(pair.gd)
+        H.gpu_prefill(c, [pair.gt, pair.gd], [prompt])
+        return c
+
+    def step(c):
+        api.sd_draft(pair.gd, c, None, 1, gamma, 0.0, None, cand, None)
+        api.sd_verify(pair.gt, c, None, 1, gamma, 0.0, cand, None, None, na, nx, commit=True)
+
+    ce = new_ctx()
+    for _ in range(n_steps):
+        step(ce)
+    ce.sync()
+    eager = list(ce.get_tokens(0))
+    ce.close()
+    cg = new_ctx()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step(cg)
+    for r in range(n_steps):
+        graph.replay()
+        if r % 5 == 4:   # eager work and synchronisations of the program between replays
+            torch.cuda.synchronize()
+            _ = cand.cpu()
+    torch.cuda.synchronize()
+    nt, kv = cg.sync(pair.gt)           # raises on any status flag
+    got = list(cg.get_tokens(0))
+    assert nt[0] == len(got) and kv[0] == nt[0] - 1
+    assert len(got) >= 3 * len(prompt) or len(got) >= len(prompt) + n_steps
+    assert got == eager, "graph replays and eager steps emitted different tokens"
+    # and the tokens are the target's own greedy continuation (up to the oracle's first near-tie)
+    ar, margins = oracle.ar_generate(pair.ot.new_seq(200), prompt, 0.0, len(got) - len(prompt), H.uf(45, dg.VERIFY_STREAM))
+    safe = 0
+    for mg in margins:
+        if mg < H.GREEDY_GAP_THR[dg.FP32]:
+            break
+        safe += 1
+    assert safe >= 20 and got[len(prompt):len(prompt) + safe] == ar[:safe]
+    cg.close()
+    pair.close()
+
+
 @pytest.mark.parametrize("shape_name,tol,max_rows,lens", [
     ("tiny_target", 1e-4, 96, [9, 41, 150]), ("small_target_bf16", 2e-2, 96, [9, 41, 150]),
     ("small_target_bf16", 2e-2, 144, [9, 41, 150]), ("small_target_bf16", 2e-2, 192, [9, 41, 150]),
