@@ -673,28 +673,34 @@ def classifier_bench(api, dg, torch, np, args):
 
 def stream_probe(api, torch, np):
     """A kernel that only reads: buffers of the 7B shape's weight-matrix sizes (a fresh region of a 4 GiB pool every
-    launch, so nothing is cache resident) and one 1 GiB read."""
+    launch, so nothing is cache resident) and one 1 GiB read, in two patterns: every block reading one contiguous
+    range with the nontemporal hint (what the weight-streaming kernels use) and a grid-strided read with ordinary loads."""
     pool = torch.ones(1 << 32, dtype=torch.uint8, device="cuda")
     word = torch.zeros(1, dtype=torch.int32, device="cuda")
     res = []
-    for mb in (33.6, 100.7, 180.4, 262.1, 1073.7):
-        nbytes = int(mb * 1e6) // 4096 * 4096
-        n_regions = max(1, (1 << 32) // nbytes)
-        reps = min(n_regions, 12)
-        views = [pool[i * nbytes:(i + 1) * nbytes] for i in range(n_regions)]
-        api.stream_read(views[-1], word)
-        torch.cuda.synchronize()
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-        for i in range(reps):
-            evs[i][0].record()
-            api.stream_read(views[i % n_regions], word)
-            evs[i][1].record()
-        torch.cuda.synchronize()
-        us = float(np.median([a.elapsed_time(b) for a, b in evs])) * 1e3
-        res.append({"mb": nbytes / 1e6, "us": us, "gb_per_s": nbytes / us / 1e3, "frac_of_8_tb_s": nbytes / us / 1e3 / 8000.0})
-    print(json.dumps({"metric": "stream_read_gb_per_s", "value": res[-1]["gb_per_s"], "unit": "GB/s", "n_gpus": 1,
+    for nt in (1, 0):
+        api.set_option("stream_read_nt", nt)
+        for mb in (33.6, 100.7, 180.4, 262.1, 1073.7):
+            nbytes = int(mb * 1e6) // 4096 * 4096
+            n_regions = max(1, (1 << 32) // nbytes)
+            reps = min(n_regions, 12)
+            views = [pool[i * nbytes:(i + 1) * nbytes] for i in range(n_regions)]
+            api.stream_read(views[-1], word)
+            torch.cuda.synchronize()
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+            for i in range(reps):
+                evs[i][0].record()
+                api.stream_read(views[i % n_regions], word)
+                evs[i][1].record()
+            torch.cuda.synchronize()
+            us = float(np.median([a.elapsed_time(b) for a, b in evs])) * 1e3
+            res.append({"pattern": "contiguous ranges, nontemporal" if nt else "grid-strided, ordinary loads", "mb": nbytes / 1e6,
+                        "us": us, "gb_per_s": nbytes / us / 1e3, "frac_of_8_tb_s": nbytes / us / 1e3 / 8000.0})
+    api.set_option("stream_read_nt", 1)
+    print(json.dumps({"metric": "stream_read_gb_per_s", "value": res[4]["gb_per_s"], "unit": "GB/s", "n_gpus": 1,
                       "dtype": "u8", "data": "synthetic", "higher_is_better": True, "vs_baseline": None,
-                      "config": {"workload": "plain streaming read, one launch per buffer"}, "cases": res}))
+                      "config": {"workload": "plain streaming read, one launch per buffer (value: 1 GiB, contiguous ranges with the nontemporal hint)"},
+                      "cases": res}))
 
 
 def _cpu_model():

@@ -380,6 +380,9 @@ int sd_debug_stream_read(const void *buf, size_t bytes, uint32_t *scratch_word, 
  * option "attn_waves" = 4 or 8 forces the block shape of the fused attention kernel
  * (0 = automatic: 4-wave blocks when (sequence, head) pairs oversubscribe the chip and
  * contexts are short).
+ * option "stream_read_nt" = 0 makes sd_debug_stream_read a grid-strided read with ordinary loads;
+ * 1 (the default) gives every block one contiguous range and reads it with the nontemporal hint,
+ * the fastest pattern measured on this part.
  * Unknown names and out-of-range values return SD_EINVAL. */
 int sd_set_option(const char *name, int32_t value);
 /* Per-kernel-class totals gathered under option "profile": idx = 0,1,.. until

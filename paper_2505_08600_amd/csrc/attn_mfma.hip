@@ -48,7 +48,7 @@ union Pack8 {
 // qv/ql: hi and lo planes of the Q^T operand; vis: last visible token of this lane's query row.
 // With Q_LDS the two planes are re-read from shared memory for every tile instead of living in
 // registers (32 registers less, which is what lets an 8-wave block keep two tile buffers unspilled).
-template <int HD, bool Q_LDS = false>
+template <int HD, bool NT_HINT, bool Q_LDS = false>
 __device__ __forceinline__ void attn_tiles(const uint16_t *__restrict__ K, const uint16_t *__restrict__ Vt,
                                            int64_t total_cap, const bf16x8 *qv, const bf16x8 *ql, int vis, int t_begin,
                                            int t_end, int t_stride, float &m_run, float &l_run, f32x4 *o)
@@ -67,11 +67,12 @@ __device__ __forceinline__ void attn_tiles(const uint16_t *__restrict__ K, const
         const uint16_t *kp = K + (size_t)t * (AT_TILE * HD) + lane * 8;
 #pragma unroll
         for (int c = 0; c < NC; c++) {
-            ka[c] = *(const bf16x8 *)(kp + (2 * c) * 512);
-            kb[c] = *(const bf16x8 *)(kp + (2 * c + 1) * 512);
+            ka[c] = ld_stream<NT_HINT>((const bf16x8 *)(kp + (2 * c) * 512));
+            kb[c] = ld_stream<NT_HINT>((const bf16x8 *)(kp + (2 * c + 1) * 512));
         }
 #pragma unroll
-        for (int d = 0; d < ND; d++) vv[d] = *(const bf16x8 *)(Vt + (size_t)t * (AT_TILE * HD) + (d * 16 + qi) * AT_TILE + grp * 8);
+        for (int d = 0; d < ND; d++)
+            vv[d] = ld_stream<NT_HINT>((const bf16x8 *)(Vt + (size_t)t * (AT_TILE * HD) + (d * 16 + qi) * AT_TILE + grp * 8));
     };
     auto compute_tile = [&](int t, const bf16x8 *ka, const bf16x8 *kb, const bf16x8 *vv) {
         const int t0 = t * AT_TILE;
@@ -142,7 +143,7 @@ __device__ __forceinline__ void attn_tiles(const uint16_t *__restrict__ K, const
     }
 }
 
-template <int HD>
+template <int HD, bool NT_HINT>
 __global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restrict__ qbuf, ActView q_av,
                                                         const uint16_t *__restrict__ Kl,
                                                         const uint16_t *__restrict__ Vtl, PlanView pv, CtxView cv,
@@ -183,7 +184,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restri
     f32x4 o[ND];
 #pragma unroll
     for (int d = 0; d < ND; d++) o[d] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    attn_tiles<HD>(K, Vt, total_cap, qv, ql, vis, t_begin + wave, t_end, AT_WAVES, m_run, l_run, o);
+    attn_tiles<HD, NT_HINT>(K, Vt, total_cap, qv, ql, vis, t_begin + wave, t_end, AT_WAVES, m_run, l_run, o);
     // row sums were kept per k-group: finish them
     l_run += __shfl_xor(l_run, 16, 64);
     l_run += __shfl_xor(l_run, 32, 64);
@@ -276,7 +277,7 @@ __global__ void attn_combine_kernel(const float *__restrict__ part, PlanView pv,
 // (including the rows just written) tile by tile, and merge their partial results in LDS.
 // WAVES = 8: one block per compute unit (few blocks, each as parallel as possible); WAVES = 4: two
 // resident blocks per unit, so one block's prologue and merge overlap the other's streaming (many blocks).
-template <int HD, int WAVES>
+template <int HD, int WAVES, bool NT_HINT>
 __global__ __launch_bounds__(WAVES * 64, 2) void attn_fused_kernel(const float *__restrict__ qkv, int n_slabs,
                                                                    size_t slab_stride, PlanView pv, CtxView cv, int R,
                                                                    int H, const float2 *__restrict__ rope, int max_pos,
@@ -359,7 +360,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_fused_kernel(const float *
     f32x4 o[ND];
 #pragma unroll
     for (int d = 0; d < ND; d++) o[d] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    attn_tiles<HD, true>(K, Vt, total_cap, qv, ql, vis, wave, n_tiles, WAVES, m_run, l_run, o);
+    attn_tiles<HD, NT_HINT, true>(K, Vt, total_cap, qv, ql, vis, wave, n_tiles, WAVES, m_run, l_run, o);
     l_run += __shfl_xor(l_run, 16, 64);
     l_run += __shfl_xor(l_run, 32, 64);
     // ---- merge: every wave leaves its (max, sum, O) in LDS; after one barrier the block combines them
@@ -407,7 +408,8 @@ int g_force_attn_waves = 0;
 // Returns hipErrorNotSupported when the split path (RoPE kernel + split attention + combine) should run.
 hipError_t launch_attn_fused_bf16(hipStream_t s, const float *qkv, int n_slabs, size_t slab_stride, PlanView pv,
                                   CtxView cv, int R, int n_seq, int H, int hd, const float2 *rope, int max_pos,
-                                  void *Kl, void *Vtl, int64_t total_cap, int len_upper, void *obuf, ActView o_av)
+                                  void *Kl, void *Vtl, int64_t total_cap, int len_upper, void *obuf, ActView o_av,
+                                  int stream_nt)
 {
     if (R < 1 || R > 16 || (hd != 64 && hd != 128) || n_slabs < 1 || n_slabs > 8) return hipErrorNotSupported;
     if (n_seq > 65535 || H > 65535) return hipErrorNotSupported;
@@ -422,8 +424,16 @@ hipError_t launch_attn_fused_bf16(hipStream_t s, const float *qkv, int n_slabs, 
     const bool many = g_force_attn_waves ? g_force_attn_waves == 4 : ((long)n_seq * H >= 512 && tiles_upper <= 40);
     dim3 grid(H, n_seq), block(many ? 256 : 512);
 #define SD_FUSED(HD_, WAVES_)                                                                                          \
-    hipLaunchKernelGGL((attn_fused_kernel<HD_, WAVES_>), grid, block, 0, s, qkv, n_slabs, slab_stride, pv, cv, R, H,   \
-                       rope, max_pos, (uint16_t *)Kl, (uint16_t *)Vtl, total_cap, (uint16_t *)obuf, o_av)
+    do {                                                                                                               \
+        if (stream_nt)                                                                                                 \
+            hipLaunchKernelGGL((attn_fused_kernel<HD_, WAVES_, true>), grid, block, 0, s, qkv, n_slabs, slab_stride,   \
+                               pv, cv, R, H, rope, max_pos, (uint16_t *)Kl, (uint16_t *)Vtl, total_cap,                \
+                               (uint16_t *)obuf, o_av);                                                                \
+        else                                                                                                           \
+            hipLaunchKernelGGL((attn_fused_kernel<HD_, WAVES_, false>), grid, block, 0, s, qkv, n_slabs, slab_stride,  \
+                               pv, cv, R, H, rope, max_pos, (uint16_t *)Kl, (uint16_t *)Vtl, total_cap,                \
+                               (uint16_t *)obuf, o_av);                                                                \
+    } while (0)
     if (hd == 128) {
         if (many) SD_FUSED(128, 4);
         else SD_FUSED(128, 8);
@@ -437,7 +447,7 @@ hipError_t launch_attn_fused_bf16(hipStream_t s, const float *qkv, int n_slabs, 
 
 hipError_t launch_attn_mfma_bf16(hipStream_t s, const void *qbuf, ActView q_av, const void *Kl, const void *Vtl,
                                  PlanView pv, CtxView cv, int R, int n_seq, int H, int hd, int64_t total_cap,
-                                 int len_upper, float *part, size_t part_floats, void *obuf, ActView o_av)
+                                 int len_upper, float *part, size_t part_floats, void *obuf, ActView o_av, int stream_nt)
 {
     if (R < 1 || R > 16 || (hd != 64 && hd != 128)) return hipErrorNotSupported;
     if (n_seq > 65535 || H > 65535) return hipErrorNotSupported;
@@ -449,14 +459,18 @@ hipError_t launch_attn_mfma_bf16(hipStream_t s, const void *qbuf, ActView q_av, 
     while (S > 1 && (size_t)n_seq * H * S * 16 * (hd + 2) > part_floats) S--;
     if (S < 1) S = 1;
     dim3 grid(S, H, n_seq), block(256);
-    if (hd == 128)
-        hipLaunchKernelGGL(attn_mfma_kernel<128>, grid, block, 0, s, (const uint16_t *)qbuf, q_av,
-                           (const uint16_t *)Kl, (const uint16_t *)Vtl, pv, cv, R, H, total_cap, S, part,
-                           (uint16_t *)obuf, o_av);
-    else
-        hipLaunchKernelGGL(attn_mfma_kernel<64>, grid, block, 0, s, (const uint16_t *)qbuf, q_av,
-                           (const uint16_t *)Kl, (const uint16_t *)Vtl, pv, cv, R, H, total_cap, S, part,
-                           (uint16_t *)obuf, o_av);
+#define SD_SPLIT_ATTN(HD_, NT_)                                                                                      \
+    hipLaunchKernelGGL((attn_mfma_kernel<HD_, NT_>), grid, block, 0, s, (const uint16_t *)qbuf, q_av,                \
+                       (const uint16_t *)Kl, (const uint16_t *)Vtl, pv, cv, R, H, total_cap, S, part, (uint16_t *)obuf, \
+                       o_av)
+    if (hd == 128) {
+        if (stream_nt) SD_SPLIT_ATTN(128, true);
+        else SD_SPLIT_ATTN(128, false);
+    } else {
+        if (stream_nt) SD_SPLIT_ATTN(64, true);
+        else SD_SPLIT_ATTN(64, false);
+    }
+#undef SD_SPLIT_ATTN
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || S == 1) return e;
     if (hd == 128)

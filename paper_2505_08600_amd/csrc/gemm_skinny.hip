@@ -300,7 +300,7 @@ static void split_geometry(int K, int ks, int *kps, int *ny)
 // complete sums, so there grid.y is 1).  The waves interleave the 128-element K steps, fetch their
 // activation fragments straight from global memory (L2) - no barrier inside the K loop - and keep the
 // loads of U steps in flight in registers; the four partial accumulators meet in LDS.
-template <int NMAT, bool PACKED, int MT, int U, int NTW>
+template <int NMAT, bool PACKED, int MT, int U, int NTW, bool NT_HINT>
 __global__ __launch_bounds__(256) void gemm_ksplit_kernel(const uint16_t *__restrict__ A, ActView a_av, WeightSeg w,
                                                           int M, int N, int K, int steps_per_split,
                                                           float *__restrict__ C, size_t c_split_stride,
@@ -356,7 +356,7 @@ __global__ __launch_bounds__(256) void gemm_ksplit_kernel(const uint16_t *__rest
         for (int c = 0; c < NW; c++)
 #pragma unroll
             for (int i = 0; i < 4; i++)
-                wv[b][c][i] = *(const bf16x8 *)(Wp[c % NMAT] + (size_t)(c / NMAT) * tile_elems + (size_t)st * 2048 + i * 512);
+                wv[b][c][i] = ld_stream<NT_HINT>((const bf16x8 *)(Wp[c % NMAT] + (size_t)(c / NMAT) * tile_elems + (size_t)st * 2048 + i * 512));
     };
 #pragma unroll
     for (int u = 0; u < U; u++)
@@ -538,9 +538,15 @@ hipError_t launch_gemm_skinny_bf16(hipStream_t s, int mode, const void *A, ActVi
         if (mode == GEMM_SWIGLU) return tile_launch<GEMM_SWIGLU>(s, a, a_av, w, M, N, K, 1, C, 0, ca, c_av);
         return tile_launch<GEMM_STORE>(s, a, a_av, w, M, N, K, splits, C, c_split_stride, ca, c_av);
     }
-#define SD_KSPLIT(NMAT, PACKED, MT, U, NTW, GRID, SPS)                                                              \
-    hipLaunchKernelGGL((gemm_ksplit_kernel<NMAT, PACKED, MT, U, NTW>), GRID, dim3(256), 0, s, a, a_av, w, M, N, K, \
-                       SPS, C, c_split_stride, ca, c_av)
+#define SD_KSPLIT(NMAT, PACKED, MT, U, NTW, GRID, SPS)                                                                   \
+    do {                                                                                                                  \
+        if (w.nt)                                                                                                         \
+            hipLaunchKernelGGL((gemm_ksplit_kernel<NMAT, PACKED, MT, U, NTW, true>), GRID, dim3(256), 0, s, a, a_av, w, M, \
+                               N, K, SPS, C, c_split_stride, ca, c_av);                                                   \
+        else                                                                                                              \
+            hipLaunchKernelGGL((gemm_ksplit_kernel<NMAT, PACKED, MT, U, NTW, false>), GRID, dim3(256), 0, s, a, a_av, w,  \
+                               M, N, K, SPS, C, c_split_stride, ca, c_av);                                                \
+    } while (0)
     if (mode == GEMM_SWIGLU) { // K split inside the block only
         if (N % 16 != 0) return hipErrorNotSupported;
         dim3 grid(N / 16);

@@ -114,6 +114,10 @@ extern "C" int sd_set_option(const char *name, int32_t value)
         g_force_attn_waves = value;
         return SD_OK;
     }
+    if (!strcmp(name, "stream_read_nt")) { // pattern of sd_debug_stream_read: 1 = contiguous ranges, nontemporal hint (default); 0 = grid-strided
+        g_stream_read_nt = value != 0;
+        return SD_OK;
+    }
     if (!strcmp(name, "profile")) { // 1: start a fresh measurement, 0: stop recording (totals stay readable)
         prof_fold();
         if (value) {
@@ -211,6 +215,8 @@ extern "C" int sd_load_model(const sd_model_config *cfg, const sd_weights *w, sd
         auto pad = [](size_t b) { return (b + 255) & ~(size_t)255; };
         const size_t b_dd = pad(d * d * esz), b_fd = pad(F * d * esz), b_vd = pad(V * d * esz), b_g = pad(d * 4);
         const size_t total = 2 * b_vd + b_g + (size_t)c.n_layers * (4 * b_dd + 3 * b_fd + 2 * b_g);
+        // weights that cannot stay in the 256 MB memory-side cache from one forward to the next are streamed past it
+        m->stream_nt = total > ((size_t)256 << 20);
         hipError_t we = hipMalloc(&m->wmem, total);
         if (we != hipSuccess) {
             delete m;
@@ -765,7 +771,7 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
             FWD(launch_rmsnorm(s, cf.dtype, m->x, m->norm_attn[l], nullptr, M, d, cf.rms_eps, m->abuf, avd));
         }
         pending = 0;
-        WeightSeg wqkv = {{m->wq[l], m->wk[l], m->wv[l]}, d, m->tiled_dd};
+        WeightSeg wqkv = {{m->wq[l], m->wk[l], m->wv[l]}, d, m->tiled_dd, m->stream_nt};
         int nq_slabs;
         const float *qkv_src;
         // low-rank adapters (sequences of one batch may use different ones): their update of q, k, v is one more
@@ -797,7 +803,7 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
         if (cf.dtype == SD_BF16 && !(g_force_generic & 2) && G == 1) {
             ProfScope ps(T_ATTN, s);
             ea = launch_attn_fused_bf16(s, qkv_src, nq_slabs, (size_t)M * 3 * d, pv, cv, R, n_seq, H, hd, m->rope,
-                                        cf.max_pos, Kl, Vtl, c->total_cap, kv_upper, m->obuf, avd);
+                                        cf.max_pos, Kl, Vtl, c->total_cap, kv_upper, m->obuf, avd, m->stream_nt);
         }
         if (ea == hipErrorNotSupported) {
             { ProfScope ps(T_ROPE, s);
@@ -806,7 +812,7 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
             ProfScope ps(T_ATTN, s);
             if (cf.dtype == SD_BF16 && !(g_force_generic & 2))
                 ea = launch_attn_mfma_bf16(s, m->qbuf, avd, Kl, Vtl, pv, cv, R, n_slots, H, hd, c->total_cap,
-                                           kv_upper, m->part, m->part_floats, m->obuf, avd);
+                                           kv_upper, m->part, m->part_floats, m->obuf, avd, m->stream_nt);
             if (ea == hipErrorNotSupported)
                 // (its score buffer is sized from the largest capacity, which never changes: a captured graph
                 // stays valid however far the sequences have grown since the capture)
@@ -815,7 +821,7 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
         }
         if (ea == hipErrorNotSupported) return sd_fail(SD_ECAP, "forward: context too long for the generic attention kernel");
         FWD(ea);
-        WeightSeg wo = {{m->wo[l], nullptr, nullptr}, d, m->tiled_dd};
+        WeightSeg wo = {{m->wo[l], nullptr, nullptr}, d, m->tiled_dd, m->stream_nt};
         int no_slabs;
         { ProfScope ps(T_OPROJ, s);
         no_slabs = stream_gemm(m, s, m->obuf, avd, wo, M, d, d, m->gpart_r, m->gpart_r_floats, 0, &ge, lora_o ? 1 : 0);
@@ -835,7 +841,7 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
         else
             FWD(launch_rmsnorm(s, cf.dtype, m->x, m->norm_ffn[l], nullptr, M, d, cf.rms_eps, m->abuf, avd));
         }
-        WeightSeg wgu = {{m->wgate[l], m->wup[l], nullptr}, F, m->tiled_fd};
+        WeightSeg wgu = {{m->wgate[l], m->wup[l], nullptr}, F, m->tiled_fd, m->stream_nt};
         { ProfScope ps(T_GATEUP, s);
         hipError_t eg = hipErrorNotSupported;
         if (cf.dtype == SD_BF16 && !(g_force_generic & 1))
@@ -844,7 +850,7 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
         if (eg == hipErrorNotSupported)
             eg = gemm_generic(m, s, GEMM_SWIGLU, m->abuf, avd, wgu, M, F, d, nullptr, m->act, avf);
         FWD(eg); }
-        WeightSeg wd = {{m->wdown[l], nullptr, nullptr}, d, m->tiled_df};
+        WeightSeg wd = {{m->wdown[l], nullptr, nullptr}, d, m->tiled_df, m->stream_nt};
         { ProfScope ps(T_DOWN, s);
         pending = stream_gemm(m, s, m->act, avf, wd, M, d, F, m->gpart_r, m->gpart_r_floats, 0, &ge);
         FWD(ge);
@@ -861,7 +867,7 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
         else
             FWD(launch_rmsnorm(s, cf.dtype, m->x, m->final_norm, pv.lm_row, n_lm, d, cf.rms_eps, m->abuf, avlm));
         }
-        WeightSeg wl = {{m->lm_head, nullptr, nullptr}, V, m->tiled_lm};
+        WeightSeg wl = {{m->lm_head, nullptr, nullptr}, V, m->tiled_lm, m->stream_nt};
         { ProfScope ps(T_LMHEAD, s);
         int nl = stream_gemm(m, s, m->abuf, avlm, wl, n_lm, V, d, m->logits, (size_t)cf.max_rows * V, 1, &ge);
         FWD(ge);
