@@ -812,7 +812,8 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
             ProfScope ps(T_ATTN, s);
             if (cf.dtype == SD_BF16 && !(g_force_generic & 2))
                 ea = launch_attn_mfma_bf16(s, m->qbuf, avd, Kl, Vtl, pv, cv, R, n_slots, H, hd, c->total_cap,
-                                           kv_upper, m->part, m->part_floats, m->obuf, avd, m->stream_nt);
+                                           kv_upper, m->part, m->part_floats, m->obuf, avd,
+                                           m->stream_nt && G == 1); // (the row groups of a prefill re-read one prefix: let it stay cached)
             if (ea == hipErrorNotSupported)
                 // (its score buffer is sized from the largest capacity, which never changes: a captured graph
                 // stays valid however far the sequences have grown since the capture)
