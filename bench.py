@@ -224,6 +224,23 @@ def main():
     vprof = api.profile_read()
     gcnt, gms = vprof["gemm_gateup"]
     gu_ms = gms / max(gcnt, 1)
+    # the draft alone, same way: launches and time per class of one sd_draft call (the draft is bound by the
+    # number of dependent launches; its one bandwidth-shaped kernel is the LM head)
+    n_tok0, kv0 = ctx.sync(gd)
+    api.set_option("profile", 1)
+    for k in range(3):
+        api.sd_draft(gd, ctx, None, B, gamma, T, ud[k] if T > 0 else None, cand, q if T > 0 else None)
+        torch.cuda.synchronize()
+        ctx.truncate(gd, 0, int(kv0[0]))
+    api.set_option("profile", 0)
+    dprof = api.profile_read()
+    d_launches = sum(v[0] for v in dprof.values())
+    lm_cnt, lm_ms = dprof.get("gemm_lmhead", (0, 0.0))
+    lm_us = lm_ms / max(lm_cnt, 1) * 1e3
+    draft_obj = {"us_per_token": t_draft / gamma * 1e3, "launches_per_token": d_launches / (3.0 * gamma),
+                 "lm_head_us_per_launch": lm_us, "lm_head_mb": sd_.vocab * sd_.d_model * 2 / 1e6,
+                 "lm_head_gb_per_s": sd_.vocab * sd_.d_model * 2 / max(lm_us, 1e-9) / 1e3,
+                 "kernel_us_per_token": {k: v[1] * 1e3 / (3.0 * gamma) for k, v in dprof.items() if v[0]}}
     achieved = gu_bytes / (gu_ms * 1e-3) / 1e9
     # whole verify call against its own algorithmic traffic
     n_ctx = int(ctx.sync()[0][0])
@@ -263,6 +280,7 @@ def main():
                      "traffic": GATEUP_TRAFFIC_BYTES if (not args.layers and args.prompt == 512) else None,
                      "us_per_launch": gu_ms * 1e3, "algorithmic_bytes": gu_bytes},
         "kernel_ms_per_verify": {k: v[1] / 3.0 for k, v in vprof.items() if v[0]},
+        "draft": draft_obj,
     }
 
     # ---- Equation 1 against a measurement: plain autoregressive decoding of the same target through the
