@@ -382,7 +382,9 @@ int sd_debug_stream_read(const void *buf, size_t bytes, uint32_t *scratch_word, 
  * contexts are short).
  * option "stream_read_nt" = 0 makes sd_debug_stream_read a grid-strided read with ordinary loads;
  * 1 (the default) gives every block one contiguous range and reads it with the nontemporal hint,
- * the fastest pattern measured on this part.
+ * the fastest pattern measured on this part; adding 2 to either turns on a checking mode in which the XOR
+ * of every 32-bit word read is folded into *scratch_word (which the caller zeroes), so that a test can
+ * tell whether every vector was read exactly once.
  * Unknown names and out-of-range values return SD_EINVAL. */
 int sd_set_option(const char *name, int32_t value);
 /* Per-kernel-class totals gathered under option "profile": idx = 0,1,.. until

@@ -114,8 +114,10 @@ extern "C" int sd_set_option(const char *name, int32_t value)
         g_force_attn_waves = value;
         return SD_OK;
     }
-    if (!strcmp(name, "stream_read_nt")) { // pattern of sd_debug_stream_read: 1 = contiguous ranges, nontemporal hint (default); 0 = grid-strided
-        g_stream_read_nt = value != 0;
+    if (!strcmp(name, "stream_read_nt")) { // pattern of sd_debug_stream_read: 1 = contiguous ranges, nontemporal hint (default);
+                                           // 0 = grid-strided; + 2 = checking mode (XOR of every word read is folded into the scratch word)
+        if (value < 0 || value > 3) return sd_fail(SD_EINVAL, "sd_set_option: stream_read_nt is 0..3");
+        g_stream_read_nt = value;
         return SD_OK;
     }
     if (!strcmp(name, "profile")) { // 1: start a fresh measurement, 0: stop recording (totals stay readable)

@@ -82,3 +82,28 @@ def test_accept_argument_errors():
     assert L.sd_accept(p(x), 1, 1, 6, 1.0, p(i), p(x), p(x), p(i), p(i), p(x), None) == api.SD_EINVAL
     assert L.sd_accept(p(x), 1, 1, 8, 1.0, p(i), None, p(x), p(i), p(i), p(x), None) == api.SD_EINVAL
     assert L.sd_accept(p(x), 1, 1, 8, 1.0, p(i), p(x), p(x), p(i), p(i), None, None) == api.SD_EINVAL
+
+
+@pytest.mark.parametrize("nt", [1, 0])
+def test_stream_read_probe_reads_every_word_exactly_once(nt):
+    """In its checking mode the read probe folds every 32-bit word it reads into the scratch word with XOR: the
+    result equals the XOR of the buffer iff both patterns cover every 16-byte vector exactly once, for sizes on
+    and off the grid's granularity; and in measuring mode the word is left alone."""
+    print(f"stream read probe, nontemporal pattern = {nt}", flush=True)
+    try:
+        rng = np.random.default_rng(7)
+        for n_words in (4, 4 * 255, 4 * 2048 + 4, 4 * 65536 * 3 + 12, 1 << 22):
+            w = rng.integers(0, 1 << 32, n_words, dtype=np.uint64).astype(np.uint32)
+            buf = torch.from_numpy(w.view(np.int32)).cuda()
+            word = torch.zeros(1, dtype=torch.int32, device="cuda")
+            api.set_option("stream_read_nt", nt + 2)
+            api.stream_read(buf, word)
+            torch.cuda.synchronize()
+            assert int(word.item()) & 0xffffffff == int(np.bitwise_xor.reduce(w)), f"{n_words} words: a vector was skipped or read twice"
+            api.set_option("stream_read_nt", nt)
+            word.zero_()
+            api.stream_read(buf, word)
+            torch.cuda.synchronize()
+            assert int(word.item()) == 0
+    finally:
+        api.set_option("stream_read_nt", 1)
