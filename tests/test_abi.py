@@ -39,6 +39,10 @@ def test_argument_errors_do_not_need_a_gpu():
     cfg.n_heads = 3
     assert L.sd_load_model(C.byref(cfg), C.byref(w), C.byref(h)) == api.SD_EINVAL
     assert b"n_heads" in L.sd_last_error()
+    big = api._Config(2, 64, 4, 16, 96, 262148, 0, 10000.0, 1e-5, 16, 64)   # the samplers' segment table ends at 262144
+    assert L.sd_load_model(C.byref(big), C.byref(w), C.byref(h)) == api.SD_EINVAL
+    assert b"vocab above 262144" in L.sd_last_error()
+    assert L.sd_set_option(b"stream_read_nt", 4) == api.SD_EINVAL
     assert L.sd_ctx_create(0, None, None) == api.SD_EINVAL
     assert L.sd_draft(None, None, None, 1, 4, 1.0, None, None, None, None) == api.SD_EINVAL
     assert L.sd_verify(None, None, None, 1, 4, 1.0, None, None, None, None, None, 1, None) == api.SD_EINVAL
