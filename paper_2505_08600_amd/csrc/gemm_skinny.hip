@@ -196,45 +196,49 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_tile_kernel(const uint16_t *A
         frags(0, 0, 0);
         SD_ORDER();
     }
-    for (int ch0 = 0; ch0 < nchunks; ch0 += NB) {
+    auto chunk = [&](int ch, int b) {
+        a_commit((ch + 1) & 1);
+        SD_ORDER();
+        a_fetch(ch + 2);
+        w_issue(ch + NB - 1, (b + NB - 1) % NB);
+        if (!EARLY) frags(ch & 1, 0, 0);
 #pragma unroll
-        for (int b = 0; b < NB; b++) {
-            const int ch = ch0 + b;
-            if (ch >= nchunks) goto k_done; // leaves the loop: no path merges back into the steady state
-            a_commit((ch + 1) & 1);
-            SD_ORDER();
-            a_fetch(ch + 2);
-            w_issue(ch + NB - 1, (b + NB - 1) % NB);
-            if (!EARLY) frags(ch & 1, 0, 0);
-#pragma unroll
-            for (int i = 0; i < (EARLY ? NI - 1 : NI); i++) {
-                if (i < NI - 1) frags(ch & 1, i + 1, (i + 1) & 1);
-                mfma_group(b, i);
-            }
-            // instruction order of this stretch: (the LDS reads of the first fragment group, then) one
-            // global load (activation rows first) and one LDS read after every third MFMA
-            if (!EARLY) __builtin_amdgcn_sched_group_barrier(0x100, 2 * MT, 0);
-#pragma unroll
-            for (int k = 0; k < (NT * MT * 2 * (EARLY ? NI - 1 : NI)) / 3; k++) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 3, 0); // MFMA
-                if (k < LPT + NT * NI) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);     // VMEM read
-                if (k < 2 * MT * (NI - 1)) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); // DS read
-            }
-            SD_ORDER();
-            __syncthreads();
-            if (EARLY) {
-                frags((ch + 1) & 1, 0, 0); // (after the last chunk: a stale buffer, never used)
-                mfma_group(b, NI - 1);
-#pragma unroll
-                for (int k = 0; k < (NT * MT * 2) / 3; k++) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 3, 0); // MFMA
-                    if (k < 2 * MT) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); // DS read
-                }
-                SD_ORDER();
-            }
+        for (int i = 0; i < (EARLY ? NI - 1 : NI); i++) {
+            if (i < NI - 1) frags(ch & 1, i + 1, (i + 1) & 1);
+            mfma_group(b, i);
         }
+        // instruction order of this stretch: (the LDS reads of the first fragment group, then) one
+        // global load (activation rows first) and one LDS read after every third MFMA
+        if (!EARLY) __builtin_amdgcn_sched_group_barrier(0x100, 2 * MT, 0);
+#pragma unroll
+        for (int k = 0; k < (NT * MT * 2 * (EARLY ? NI - 1 : NI)) / 3; k++) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 3, 0); // MFMA
+            if (k < LPT + NT * NI) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);     // VMEM read
+            if (k < 2 * MT * (NI - 1)) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); // DS read
+        }
+        SD_ORDER();
+        __syncthreads();
+        if (EARLY) {
+            frags((ch + 1) & 1, 0, 0); // (after the last chunk: a stale buffer, never used)
+            mfma_group(b, NI - 1);
+#pragma unroll
+            for (int k = 0; k < (NT * MT * 2) / 3; k++) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 3, 0); // MFMA
+                if (k < 2 * MT) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); // DS read
+            }
+            SD_ORDER();
+        }
+    };
+    // whole rounds of NB chunks in one loop with a single exit (exits inside the unrolled round make the register
+    // allocator copy accumulators from round to round), then the at most NB - 1 chunks that remain
+    const int n_main = nchunks / NB * NB;
+    for (int ch0 = 0; ch0 < n_main; ch0 += NB) {
+#pragma unroll
+        for (int b = 0; b < NB; b++) chunk(ch0 + b, b);
     }
-k_done:
+#pragma unroll
+    for (int b = 0; b < NB - 1; b++)
+        if (n_main + b < nchunks) chunk(n_main + b, b);
     // epilogue: lane (m' = row, grp) holds D[n = 4*grp + r][m'] of each of its tiles
     f32x4 gin[MT]; // gate accumulators of the pair whose up tile is this wave's first tile
 #pragma unroll
