@@ -370,7 +370,10 @@ int64_t sd_debug_layout_index(int32_t kind, int64_t a, int64_t b, int64_t c, int
  * written.  Only enqueues on `stream`. */
 int sd_debug_stream_read(const void *buf, size_t bytes, uint32_t *scratch_word, void *stream);
 /* option "force_generic" = 1 routes every op through the simple reference kernels
- * (2: attention only, 0: off).
+ * (2: attention only; 4: only the draft sampler - one block reads the whole logits row
+ * instead of starting from the softmax partials the LM head leaves per 32 columns; 8: only
+ * the output projection of small models - a GEMM launch of its own instead of a last step of
+ * the attention blocks; 0: off).
  * option "profile" = 1 starts bracketing every kernel launch of the forward with HIP
  * events on its stream (a measurement mode: it adds event overhead), 0 stops.
  * option "gemm_splits" = mode*100 + s forces s K splits (1..8; 0 = automatic) for

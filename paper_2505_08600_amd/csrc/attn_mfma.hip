@@ -277,13 +277,25 @@ __global__ void attn_combine_kernel(const float *__restrict__ part, PlanView pv,
 // (including the rows just written) tile by tile, and merge their partial results in LDS.
 // WAVES = 8: one block per compute unit (few blocks, each as parallel as possible); WAVES = 4: two
 // resident blocks per unit, so one block's prologue and merge overlap the other's streaming (many blocks).
-template <int HD, int WAVES, bool NT_HINT>
+// OPROJ (small models, few blocks): the block goes on to multiply its head's output rows with the head's
+// HD columns of the output projection - Wo[:, h * HD .. + HD], tiled order - and stores the [R][d_model] partial
+// sums as slab h of `oslab`; the add + norm kernel that follows adds the H slabs to the residual.  The separate
+// projection launch and the round trip of the attention output through memory disappear, which is what such a
+// forward spends its time on; a head's slice of Wo is d_model * HD * 2 bytes (98 KB for 768 x 64).  The output
+// rows are split into hi + lo exactly as they are when stored for the GEMM.
+struct OProj {
+    const uint16_t *Wo; // tiled [d_model][d_model]
+    float *oslab;       // [H][rows][d_model]
+    size_t slab_stride; // rows * d_model
+    int32_t d_model;
+};
+template <int HD, int WAVES, bool NT_HINT, bool OPROJ>
 __global__ __launch_bounds__(WAVES * 64, 2) void attn_fused_kernel(const float *__restrict__ qkv, int n_slabs,
                                                                    size_t slab_stride, PlanView pv, CtxView cv, int R,
                                                                    int H, const float2 *__restrict__ rope, int max_pos,
                                                                    uint16_t *__restrict__ Kl, uint16_t *__restrict__ Vtl,
                                                                    int64_t total_cap, uint16_t *__restrict__ obuf,
-                                                                   ActView o_av)
+                                                                   ActView o_av, OProj op)
 {
     constexpr int ND = HD / 16;
     constexpr int HALF = HD / 2;
@@ -363,6 +375,24 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_fused_kernel(const float *
     attn_tiles<HD, NT_HINT, true>(K, Vt, total_cap, qv, ql, vis, wave, n_tiles, WAVES, m_run, l_run, o);
     l_run += __shfl_xor(l_run, 16, 64);
     l_run += __shfl_xor(l_run, 32, 64);
+    // OPROJ: this wave's 16-column tiles of the projection are wave, wave + WAVES, ...; their weight fragments
+    // (operand order: one contiguous KiB per instruction) are requested now and arrive during the merge
+    constexpr int OPF = OPROJ ? (HD == 64 ? 8 : 4) : 1, OKI = HD / 32;
+    bf16x8 wf[OPF][OKI];
+    if (OPROJ) {
+        const int n_ot = op.d_model >> 4;
+#pragma unroll
+        for (int t = 0; t < OPF; t++) {
+            const int nt = wave + t * WAVES;
+#pragma unroll
+            for (int i = 0; i < OKI; i++) {
+                const int kabs = h * HD + 32 * i;
+                const uint16_t *wp = op.Wo + ((size_t)(nt < n_ot ? nt : 0) * (op.d_model >> 7) + (kabs >> 7)) * 2048 +
+                                     ((kabs & 127) >> 5) * 512 + lane * 8;
+                wf[t][i] = *(const bf16x8 *)wp;
+            }
+        }
+    }
     // ---- merge: every wave leaves its (max, sum, O) in LDS; after one barrier the block combines them
 #pragma unroll
     for (int d = 0; d < ND; d++)
@@ -397,9 +427,34 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_fused_kernel(const float *
         uint32_t h0, l0, h1, l1;
         bf16x2_split(out[0], out[1], h0, l0);
         bf16x2_split(out[2], out[3], h1, l1);
-        const size_t oi = act_index(o_av, j * R + q, h * HD + dim, HDm); // 4 columns inside one K step
-        *(uint2 *)(obuf + oi) = make_uint2(h0, h1);
-        *(uint2 *)(obuf + oi + o_av.plane) = make_uint2(l0, l1);
+        if (OPROJ) { // (q no longer needed: its LDS rows take the output rows, same [plane][row][dim] layout)
+            *(uint2 *)&sQ[0][q][dim] = make_uint2(h0, h1);
+            *(uint2 *)&sQ[1][q][dim] = make_uint2(l0, l1);
+        } else {
+            const size_t oi = act_index(o_av, j * R + q, h * HD + dim, HDm); // 4 columns inside one K step
+            *(uint2 *)(obuf + oi) = make_uint2(h0, h1);
+            *(uint2 *)(obuf + oi + o_av.plane) = make_uint2(l0, l1);
+        }
+    }
+    if (OPROJ) {
+        __syncthreads();
+        // D[n][m] = sum_k Wo[n][h * HD + k] * out[m][k]: weights as the first operand, lane (m = qi, grp) of the
+        // second holds out[m][32 i + 8 grp .. + 8]; the result leaves n = 4 grp + r, m = qi in acc[r]
+        const int n_ot = op.d_model >> 4;
+        float *dst = op.oslab + (size_t)h * op.slab_stride + (size_t)(j * R + qi) * op.d_model + 4 * grp;
+#pragma unroll
+        for (int t = 0; t < OPF; t++) {
+            const int nt = wave + t * WAVES;
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int i = 0; i < OKI; i++) {
+                const bf16x8 ah = *(const lds_bf16x8 *)&sQ[0][qi][32 * i + grp * 8];
+                const bf16x8 al = *(const lds_bf16x8 *)&sQ[1][qi][32 * i + grp * 8];
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[t][i], ah, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[t][i], al, acc, 0, 0, 0);
+            }
+            if (nt < n_ot && qi < R) *(f32x4 *)(dst + nt * 16) = acc;
+        }
     }
 }
 
@@ -409,8 +464,10 @@ int g_force_attn_waves = 0;
 hipError_t launch_attn_fused_bf16(hipStream_t s, const float *qkv, int n_slabs, size_t slab_stride, PlanView pv,
                                   CtxView cv, int R, int n_seq, int H, int hd, const float2 *rope, int max_pos,
                                   void *Kl, void *Vtl, int64_t total_cap, int len_upper, void *obuf, ActView o_av,
-                                  int stream_nt)
+                                  int stream_nt, const void *wo_tiled, int d_model, float *oslab, size_t oslab_floats,
+                                  int *oproj_done)
 {
+    if (oproj_done) *oproj_done = 0;
     if (R < 1 || R > 16 || (hd != 64 && hd != 128) || n_slabs < 1 || n_slabs > 8) return hipErrorNotSupported;
     if (n_seq > 65535 || H > 65535) return hipErrorNotSupported;
     const int tiles_upper = (len_upper + AT_TILE - 1) / AT_TILE;
@@ -423,16 +480,33 @@ hipError_t launch_attn_fused_bf16(hipStream_t s, const float *qkv, int n_slabs, 
     // against 5.2 at 1024..8192)
     const bool many = g_force_attn_waves ? g_force_attn_waves == 4 : ((long)n_seq * H >= 512 && tiles_upper <= 40);
     dim3 grid(H, n_seq), block(many ? 256 : 512);
+    // output projection inside the block: small models in few blocks (each block reads its head's slice of Wo;
+    // 8 waves x 8 (head width 64) or 4 (128) column tiles bound d_model), H slabs for the add + norm kernel
+    const size_t rows = (size_t)n_seq * R;
+    const bool oproj = wo_tiled && oslab && !many && stream_nt == 0 && d_model % 128 == 0 && d_model == H * hd &&
+                       d_model <= 16 * 8 * (hd == 64 ? 8 : 4) && H <= SD_OPROJ_MAX_HEADS && (long)n_seq * H < 512 &&
+                       (size_t)H * rows * d_model <= oslab_floats && ((uintptr_t)wo_tiled & 15) == 0;
+    const OProj op = {(const uint16_t *)wo_tiled, oslab, rows * (size_t)d_model, d_model};
+    if (oproj) {
+        if (hd == 128)
+            hipLaunchKernelGGL((attn_fused_kernel<128, 8, false, true>), grid, block, 0, s, qkv, n_slabs, slab_stride, pv, cv,
+                               R, H, rope, max_pos, (uint16_t *)Kl, (uint16_t *)Vtl, total_cap, (uint16_t *)obuf, o_av, op);
+        else
+            hipLaunchKernelGGL((attn_fused_kernel<64, 8, false, true>), grid, block, 0, s, qkv, n_slabs, slab_stride, pv, cv,
+                               R, H, rope, max_pos, (uint16_t *)Kl, (uint16_t *)Vtl, total_cap, (uint16_t *)obuf, o_av, op);
+        if (oproj_done) *oproj_done = 1;
+        return hipGetLastError();
+    }
 #define SD_FUSED(HD_, WAVES_)                                                                                          \
     do {                                                                                                               \
         if (stream_nt)                                                                                                 \
-            hipLaunchKernelGGL((attn_fused_kernel<HD_, WAVES_, true>), grid, block, 0, s, qkv, n_slabs, slab_stride,   \
-                               pv, cv, R, H, rope, max_pos, (uint16_t *)Kl, (uint16_t *)Vtl, total_cap,                \
-                               (uint16_t *)obuf, o_av);                                                                \
+            hipLaunchKernelGGL((attn_fused_kernel<HD_, WAVES_, true, false>), grid, block, 0, s, qkv, n_slabs,         \
+                               slab_stride, pv, cv, R, H, rope, max_pos, (uint16_t *)Kl, (uint16_t *)Vtl, total_cap,   \
+                               (uint16_t *)obuf, o_av, op);                                                            \
         else                                                                                                           \
-            hipLaunchKernelGGL((attn_fused_kernel<HD_, WAVES_, false>), grid, block, 0, s, qkv, n_slabs, slab_stride,  \
-                               pv, cv, R, H, rope, max_pos, (uint16_t *)Kl, (uint16_t *)Vtl, total_cap,                \
-                               (uint16_t *)obuf, o_av);                                                                \
+            hipLaunchKernelGGL((attn_fused_kernel<HD_, WAVES_, false, false>), grid, block, 0, s, qkv, n_slabs,        \
+                               slab_stride, pv, cv, R, H, rope, max_pos, (uint16_t *)Kl, (uint16_t *)Vtl, total_cap,   \
+                               (uint16_t *)obuf, o_av, op);                                                            \
     } while (0)
     if (hd == 128) {
         if (many) SD_FUSED(128, 4);

@@ -308,7 +308,7 @@ template <int NMAT, bool PACKED, int MT, int U, int NTW, bool NT_HINT>
 __global__ __launch_bounds__(256) void gemm_ksplit_kernel(const uint16_t *__restrict__ A, ActView a_av, WeightSeg w,
                                                           int M, int N, int K, int steps_per_split,
                                                           float *__restrict__ C, size_t c_split_stride,
-                                                          uint16_t *__restrict__ Cact, ActView c_av)
+                                                          uint16_t *__restrict__ Cact, ActView c_av, LmStats ls)
 {
     constexpr int WAVES = 4;
     constexpr int NW = NMAT * NTW; // weight tiles per wave and step
@@ -416,6 +416,28 @@ __global__ __launch_bounds__(256) void gemm_ksplit_kernel(const uint16_t *__rest
             Cact[c_av.plane + o] = bf16_bits_rne(y - __uint_as_float((uint32_t)hi << 16));
         } else {
             C[(size_t)blockIdx.y * c_split_stride + (size_t)m * N + n0 + j * 16 + nn] = v[0];
+            if (NTW == 2 && ls.p) { // (uniform) the block's 32 columns of row m sit in the 32 lanes of a half wave
+                float mx = v[0];
+                int ai = n0 + j * 16 + nn;
+#pragma unroll
+                for (int o = 16; o > 0; o >>= 1) {
+                    const float ov = __shfl_xor(mx, o, 64);
+                    const int oi = __shfl_xor(ai, o, 64);
+                    if (ov > mx || (ov == mx && oi < ai)) {
+                        mx = ov;
+                        ai = oi;
+                    }
+                }
+                float ex = ls.invT > 0.f ? expf((v[0] - mx) * ls.invT) : 0.f;
+#pragma unroll
+                for (int o = 16; o > 0; o >>= 1) ex += __shfl_xor(ex, o, 64);
+                if ((e & 31) == 0) {
+                    float *sp = ls.p + ((size_t)m * gridDim.x + blockIdx.x) * 3;
+                    sp[0] = mx;
+                    sp[1] = ex;
+                    sp[2] = __int_as_float(ai);
+                }
+            }
         }
     }
 }
@@ -527,8 +549,11 @@ int gemm_skinny_splits(int mode, int M, int N, int K, int n_per_seg)
 // mode GEMM_SWIGLU: Cact receives the bf16 hi/lo planes.  GEMM_RESID is expressed by the caller as a
 // store into partial slabs followed by the fused add + norm kernel.
 hipError_t launch_gemm_skinny_bf16(hipStream_t s, int mode, const void *A, ActView a_av, WeightSeg w, int M, int N,
-                                   int K, float *C, size_t c_split_stride, int splits, void *Cact, ActView c_av)
+                                   int K, float *C, size_t c_split_stride, int splits, void *Cact, ActView c_av,
+                                   LmStats ls, int *ls_done)
 {
+    if (ls_done) *ls_done = 0;
+    const LmStats no_ls = {nullptr, 0.f};
     if (M < 1 || K % 128 != 0 || K < 128 || (mode != GEMM_STORE && mode != GEMM_SWIGLU)) return hipErrorNotSupported;
     if (!w.tiled) return hipErrorNotSupported; // these kernels read the 16 x 128 tile order only
     for (int i = 0; i < 3; i++)
@@ -542,35 +567,37 @@ hipError_t launch_gemm_skinny_bf16(hipStream_t s, int mode, const void *A, ActVi
         if (mode == GEMM_SWIGLU) return tile_launch<GEMM_SWIGLU>(s, a, a_av, w, M, N, K, 1, C, 0, ca, c_av);
         return tile_launch<GEMM_STORE>(s, a, a_av, w, M, N, K, splits, C, c_split_stride, ca, c_av);
     }
-#define SD_KSPLIT(NMAT, PACKED, MT, U, NTW, GRID, SPS)                                                                   \
+#define SD_KSPLIT(NMAT, PACKED, MT, U, NTW, GRID, SPS, LS)                                                               \
     do {                                                                                                                  \
         if (w.nt)                                                                                                         \
             hipLaunchKernelGGL((gemm_ksplit_kernel<NMAT, PACKED, MT, U, NTW, true>), GRID, dim3(256), 0, s, a, a_av, w, M, \
-                               N, K, SPS, C, c_split_stride, ca, c_av);                                                   \
+                               N, K, SPS, C, c_split_stride, ca, c_av, LS);                                               \
         else                                                                                                              \
             hipLaunchKernelGGL((gemm_ksplit_kernel<NMAT, PACKED, MT, U, NTW, false>), GRID, dim3(256), 0, s, a, a_av, w,  \
-                               M, N, K, SPS, C, c_split_stride, ca, c_av);                                                \
+                               M, N, K, SPS, C, c_split_stride, ca, c_av, LS);                                            \
     } while (0)
     if (mode == GEMM_SWIGLU) { // K split inside the block only
         if (N % 16 != 0) return hipErrorNotSupported;
         dim3 grid(N / 16);
-        if (M <= 8) SD_KSPLIT(2, true, 1, 2, 1, grid, K / 128);
-        else if (M <= 16) SD_KSPLIT(2, false, 1, 2, 1, grid, K / 128);
-        else SD_KSPLIT(2, false, 2, 1, 1, grid, K / 128);
+        if (M <= 8) SD_KSPLIT(2, true, 1, 2, 1, grid, K / 128, no_ls);
+        else if (M <= 16) SD_KSPLIT(2, false, 1, 2, 1, grid, K / 128, no_ls);
+        else SD_KSPLIT(2, false, 2, 1, 1, grid, K / 128, no_ls);
         return hipGetLastError();
     }
     int kps, ny;
     split_geometry(K, splits, &kps, &ny);
     if (N % 32 == 0 && w.n_per_seg % 32 == 0) {
         dim3 grid(N / 32, ny);
-        if (M <= 8) SD_KSPLIT(1, true, 1, 2, 2, grid, kps / 128);
-        else if (M <= 16) SD_KSPLIT(1, false, 1, 2, 2, grid, kps / 128);
-        else SD_KSPLIT(1, false, 2, 1, 2, grid, kps / 128);
+        const LmStats lsk = ny == 1 ? ls : no_ls; // (partial sums of a K split have no softmax)
+        if (ls_done && lsk.p) *ls_done = 1;
+        if (M <= 8) SD_KSPLIT(1, true, 1, 2, 2, grid, kps / 128, lsk);
+        else if (M <= 16) SD_KSPLIT(1, false, 1, 2, 2, grid, kps / 128, lsk);
+        else SD_KSPLIT(1, false, 2, 1, 2, grid, kps / 128, lsk);
     } else if (N % 16 == 0 && w.n_per_seg % 16 == 0) {
         dim3 grid(N / 16, ny);
-        if (M <= 8) SD_KSPLIT(1, true, 1, 2, 1, grid, kps / 128);
-        else if (M <= 16) SD_KSPLIT(1, false, 1, 2, 1, grid, kps / 128);
-        else SD_KSPLIT(1, false, 2, 1, 1, grid, kps / 128);
+        if (M <= 8) SD_KSPLIT(1, true, 1, 2, 1, grid, kps / 128, no_ls);
+        else if (M <= 16) SD_KSPLIT(1, false, 1, 2, 1, grid, kps / 128, no_ls);
+        else SD_KSPLIT(1, false, 2, 1, 1, grid, kps / 128, no_ls);
     } else {
         return hipErrorNotSupported;
     }

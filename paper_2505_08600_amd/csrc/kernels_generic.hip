@@ -505,13 +505,12 @@ hipError_t launch_gemm_generic(hipStream_t s, int dtype, int mode, const void *A
 // Embedding gather fused with the first layer's RMSNorm: x[r] = E[token_r]; out[r] = rmsnorm(x[r]) * g.
 // Same element-to-thread assignment and reduction as rmsnorm_kernel, so the result is identical to the
 // two separate launches.
+// Row r of one forward, by a whole block (red: 32 floats of LDS).
 template <typename T>
-__global__ __launch_bounds__(256) void embed_rmsnorm_kernel(const T *E, const int32_t *row_tok, int d, float *x,
-                                                            const float *g, float eps, T *out, ActView av)
+__device__ void embed_rmsnorm_row(const T *E, int tok, int r, int d, float *x, const float *g, float eps, T *out,
+                                  ActView av, float *red)
 {
-    __shared__ float red[32];
-    const int r = blockIdx.x;
-    const T *src = E + (size_t)row_tok[r] * d;
+    const T *src = E + (size_t)tok * d;
     float *xr = x + (size_t)r * d;
     float ss = 0.f;
     for (int i = threadIdx.x; i < d; i += blockDim.x) {
@@ -523,6 +522,14 @@ __global__ __launch_bounds__(256) void embed_rmsnorm_kernel(const T *E, const in
     const float inv = 1.0f / sqrtf(ss / (float)d + eps);
     for (int i = threadIdx.x; i < d; i += blockDim.x)
         store_act(out, act_index(av, r, i, d), av.plane, to_float(src[i]) * inv * g[i]);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void embed_rmsnorm_kernel(const T *E, const int32_t *row_tok, int d, float *x,
+                                                            const float *g, float eps, T *out, ActView av)
+{
+    __shared__ float red[32];
+    embed_rmsnorm_row(E, row_tok[blockIdx.x], blockIdx.x, d, x, g, eps, out, av, red);
 }
 
 hipError_t launch_embed_rmsnorm(hipStream_t s, int dtype, const void *E, const int32_t *row_tok, int M, int d, float *x,
@@ -543,8 +550,10 @@ hipError_t launch_embed_rmsnorm(hipStream_t s, int dtype, const void *E, const i
 // Residual update fused with the next RMSNorm: x[src] += sum of the split-K slabs of the
 // preceding GEMM (added in slab order), then out[j] = rmsnorm(x[src]) * g.  One block of 1024
 // threads per row; the loads of all slabs of an element are independent and go out together.
-#define ADDNORM_MAX_SLABS 8
-template <typename T>
+#define ROPE_MAX_SLABS 8
+// (MAX_SLABS: 8 covers the K splits of the GEMMs; 16 the per-head slabs an attention kernel that applies the
+// output projection itself leaves for a small model)
+template <typename T, int ADDNORM_MAX_SLABS>
 __global__ __launch_bounds__(1024) void add_rmsnorm_kernel(float *x, const float *part, int n_slabs, size_t slab_stride,
                                                            const float *g, const int32_t *row_map, int d, float eps,
                                                            T *out, ActView av)
@@ -595,13 +604,18 @@ hipError_t launch_add_rmsnorm(hipStream_t s, int dtype, float *x, const float *p
                               const float *g, const int32_t *row_map, int n_rows, int d, float eps, void *out,
                               ActView out_av)
 {
-    if (n_slabs > ADDNORM_MAX_SLABS || (d & 3)) return hipErrorInvalidValue;
-    if (dtype == SD_BF16)
-        hipLaunchKernelGGL(add_rmsnorm_kernel<bf16_t>, dim3(n_rows), dim3(1024), 0, s, x, part, n_slabs, slab_stride, g,
-                           row_map, d, eps, (bf16_t *)out, out_av);
+    if (n_slabs > 16 || (d & 3)) return hipErrorInvalidValue;
+    if (dtype == SD_BF16 && n_slabs > 8)
+        hipLaunchKernelGGL((add_rmsnorm_kernel<bf16_t, 16>), dim3(n_rows), dim3(1024), 0, s, x, part, n_slabs, slab_stride,
+                           g, row_map, d, eps, (bf16_t *)out, out_av);
+    else if (dtype == SD_BF16)
+        hipLaunchKernelGGL((add_rmsnorm_kernel<bf16_t, 8>), dim3(n_rows), dim3(1024), 0, s, x, part, n_slabs, slab_stride,
+                           g, row_map, d, eps, (bf16_t *)out, out_av);
+    else if (n_slabs > 8)
+        return hipErrorInvalidValue;
     else
-        hipLaunchKernelGGL(add_rmsnorm_kernel<float>, dim3(n_rows), dim3(1024), 0, s, x, part, n_slabs, slab_stride, g,
-                           row_map, d, eps, (float *)out, out_av);
+        hipLaunchKernelGGL((add_rmsnorm_kernel<float, 8>), dim3(n_rows), dim3(1024), 0, s, x, part, n_slabs, slab_stride,
+                           g, row_map, d, eps, (float *)out, out_av);
     return hipGetLastError();
 }
 
@@ -735,9 +749,9 @@ __global__ void rope_append_kernel(const float *qkv, int n_slabs, size_t slab_st
         }
         float2 cs = rope[(size_t)pos * half + e];
         float q0 = 0.f, q1 = 0.f, k0 = 0.f, k1 = 0.f, v0 = 0.f, v1 = 0.f;
-        float ld[ADDNORM_MAX_SLABS][6];
+        float ld[ROPE_MAX_SLABS][6];
 #pragma unroll
-        for (int sl = 0; sl < ADDNORM_MAX_SLABS; sl++) // split-K slabs of the QKV GEMM: all loads go out first
+        for (int sl = 0; sl < ROPE_MAX_SLABS; sl++) // split-K slabs of the QKV GEMM: all loads go out first
             if (sl < n_slabs) {
                 const float *rs = row + (size_t)sl * slab_stride;
                 ld[sl][0] = rs[h * hd + e];
@@ -748,7 +762,7 @@ __global__ void rope_append_kernel(const float *qkv, int n_slabs, size_t slab_st
                 ld[sl][5] = rs[2 * HD + h * hd + e + half];
             }
 #pragma unroll
-        for (int sl = 0; sl < ADDNORM_MAX_SLABS; sl++) // ... and are added in slab order
+        for (int sl = 0; sl < ROPE_MAX_SLABS; sl++) // ... and are added in slab order
             if (sl < n_slabs) {
                 q0 += ld[sl][0];
                 q1 += ld[sl][1];
@@ -772,7 +786,7 @@ hipError_t launch_rope_append(hipStream_t s, int dtype, const float *qkv, int n_
                               CtxView cv, int M, int H, int hd, const float2 *rope, int max_pos, void *qbuf,
                               ActView q_av, void *Kl, void *Vtl, int64_t total_cap)
 {
-    if (n_slabs > ADDNORM_MAX_SLABS) return hipErrorInvalidValue;
+    if (n_slabs > ROPE_MAX_SLABS) return hipErrorInvalidValue;
     if (dtype == SD_BF16)
         hipLaunchKernelGGL(rope_append_kernel<bf16_t>, dim3(M), dim3(1024), 0, s, qkv, n_slabs, slab_stride, pv, cv, H,
                            hd, rope, max_pos, (bf16_t *)qbuf, q_av, (bf16_t *)Kl, (bf16_t *)Vtl, total_cap);
@@ -1195,7 +1209,7 @@ __device__ __forceinline__ void row_scale(RowRegs &r, float invZ)
 // checks and cache-length update as plan_kernel makes for that mode, written by the sampler block that has
 // just drawn the token.  seq_order keeps the order the catch-up plan of this draft call left (every
 // sequence grows by one row, so the ranking by length does not change).  One thread calls this.
-__device__ void plan_next_cand(const NextPlan &np, int j, int tok)
+__device__ int plan_next_cand(const NextPlan &np, int j, int tok)
 {
     const PlanView &pv = np.pv;
     const CtxView &cv = np.cv;
@@ -1210,7 +1224,7 @@ __device__ void plan_next_cand(const NextPlan &np, int j, int tok)
         pv.row_b[j] = 0;
         pv.row_valid[j] = 0;
         pv.lm_row[j] = j;
-        return;
+        return 0;
     }
     const int n = cv.ntok[b];
     int *kvp = cv.kvlen + (size_t)np.slot * cv.B + b;
@@ -1239,6 +1253,7 @@ __device__ void plan_next_cand(const NextPlan &np, int j, int tok)
     pv.seq_nq[j] = nq;
     pv.lm_row[j] = j;
     *kvp = kv0 + nq;
+    return nq > 0 ? tok : 0; // (= row_tok[j]: what the planned forward embeds)
 }
 
 // Does sequence slot j draw candidate idx in this draft call?  With per-sequence candidate counts a sequence that
@@ -1293,6 +1308,193 @@ __global__ __launch_bounds__(ROW_THREADS) void draft_sample_fast_kernel(const fl
         cand[j * gamma + idx] = pick;
         if (next.enabled) plan_next_cand(next, j, pick);
     }
+}
+
+// ---- samplers that start from the LM head's per-block softmax partials (LmStats: 32 columns per entry)
+// A row's vocabulary is cut into slices of DS_SLICE columns, one 256-thread block each.  Every block reads all
+// the row's partials (a few KB) and derives from them, in the same order and therefore to the same bits as
+// every other block of the row: the row maximum, the mass of every slice (one wave-wide sum of the slice's 64
+// entries), the normaliser Z (the slice masses added in order) and the slice in which the running sum first
+// exceeds u * Z.  It then writes its own slice of q = exp((x - max) / T) / Z, and the one block that owns the
+// slice holding u * Z places the candidate inside it with a block-wide scan (same rule as block_pick_cdf:
+// first index whose inclusive sum exceeds the target, else the last index of positive weight).  No block waits
+// for another.  The owner also lays out the next single-row forward and, if asked, runs its first step
+// (embedding row + first norm).
+#define DS_SLICE 2048
+#define DS_MAX_SLICES 32
+struct SplitScratch {
+    float red[32];
+    float wmax[4];
+    float slice[DS_MAX_SLICES];
+    float wtot[2][4];
+    int pick, lastp, tok;
+};
+
+__device__ void next_forward_first_step(const NextPlan &next, int j, int tok, SplitScratch *ss)
+{
+    // (all threads of the block) thread 0 plans; then the block gathers and norms the row
+    if (threadIdx.x == 0) ss->tok = next.enabled ? plan_next_cand(next, j, tok) : 0;
+    if (!next.enabled || !next.embed) return;
+    __syncthreads();
+    embed_rmsnorm_row((const bf16_t *)next.E, ss->tok, j, next.d, next.x, next.g, next.eps, (bf16_t *)next.out, next.av,
+                      ss->red);
+}
+
+__global__ __launch_bounds__(256) void draft_sample_split_kernel(const float *logits, const float *stats, int nb, int V,
+                                                                  float T, const float *u, int gamma, int idx,
+                                                                  int32_t *cand, float *q, NextPlan next)
+{
+    __shared__ SplitScratch ss;
+    const int j = blockIdx.y, k = blockIdx.x, n_slices = gridDim.x;
+    const int lane = threadIdx.x % WAVE, wv = threadIdx.x / WAVE;
+    if (!draft_seq_active(next, j, gamma, idx)) { // (uniform over the block) nothing to draw: keep its plan entry empty
+        if (k == 0) next_forward_first_step(next, j, 0, &ss);
+        return;
+    }
+    const float invT = 1.0f / T;
+    const float *st = stats + (size_t)j * nb * 3;
+    // this block's slice of the logits row: requested first, needed only once the maximum and Z are known
+    const float *row = logits + (size_t)j * V;
+    float4 e[2];
+#pragma unroll
+    for (int it = 0; it < 2; it++) {
+        const int v = k * (DS_SLICE / 4) + it * 256 + threadIdx.x; // (V is a multiple of 32: whole float4s only)
+        e[it] = 4 * v < V ? *(const float4 *)(row + 4 * v) : make_float4(-3.0e38f, -3.0e38f, -3.0e38f, -3.0e38f);
+    }
+    // wave w holds the entries of slices w, w + 4, ...: lane l entry 64 * slice + l
+    float em[DS_MAX_SLICES / 4], es[DS_MAX_SLICES / 4];
+    float mx = -3.0e38f;
+#pragma unroll
+    for (int i = 0; i < DS_MAX_SLICES / 4; i++) {
+        const int b = (4 * i + wv) * 64 + lane;
+        const bool in = 4 * i + wv < n_slices && b < nb;
+        em[i] = in ? st[3 * b] : -3.0e38f;
+        es[i] = in ? st[3 * b + 1] : 0.f;
+        mx = fmaxf(mx, em[i]);
+    }
+    mx = wave_max(mx);
+    if (lane == 0) ss.wmax[wv] = mx;
+    if (threadIdx.x == 0) {
+        ss.pick = 0x7fffffff;
+        ss.lastp = -1;
+    }
+    __syncthreads();
+    mx = fmaxf(fmaxf(ss.wmax[0], ss.wmax[1]), fmaxf(ss.wmax[2], ss.wmax[3]));
+#pragma unroll
+    for (int i = 0; i < DS_MAX_SLICES / 4; i++) {
+        const float mass = wave_sum_dpp(es[i] * expf((em[i] - mx) * invT)); // (entries past the row: 0 * 0)
+        if (lane == 0 && 4 * i + wv < n_slices) ss.slice[4 * i + wv] = mass;
+    }
+    __syncthreads();
+    float Z = 0.f, base = 0.f;
+    for (int s = 0; s < n_slices; s++) {
+        if (s == k) base = Z;
+        Z += ss.slice[s];
+    }
+    const float target = u[j * gamma + idx] * Z;
+    int owner = -1, last_pos = 0;
+    {
+        float cum = 0.f;
+        for (int s = 0; s < n_slices; s++) {
+            const float m = ss.slice[s];
+            cum += m;
+            if (m > 0.f) last_pos = s;
+            if (owner < 0 && cum > target) owner = s;
+        }
+        if (owner < 0) owner = last_pos;
+    }
+    // this block's slice of q
+    const float invZ = 1.0f / Z;
+    float *qrow = q + ((size_t)j * gamma + idx) * V;
+#pragma unroll
+    for (int it = 0; it < 2; it++) {
+        const int v = k * (DS_SLICE / 4) + it * 256 + threadIdx.x;
+        if (4 * v < V) {
+            float4 f = e[it];
+            f.x = expf((f.x - mx) * invT);
+            f.y = expf((f.y - mx) * invT);
+            f.z = expf((f.z - mx) * invT);
+            f.w = expf((f.w - mx) * invT);
+            e[it] = f;
+            *(float4 *)(qrow + 4 * v) = make_float4(f.x * invZ, f.y * invZ, f.z * invZ, f.w * invZ);
+        } else {
+            e[it] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    }
+    if (k != owner) return; // (uniform over the block)
+    // place the target inside the slice: index order is (it, thread, component)
+    float l4[2], inc[2];
+    int lastp = -1;
+#pragma unroll
+    for (int it = 0; it < 2; it++) {
+        const int v = k * (DS_SLICE / 4) + it * 256 + threadIdx.x;
+        const float4 f = e[it];
+        if (f.x > 0.f) lastp = 4 * v;
+        if (f.y > 0.f) lastp = 4 * v + 1;
+        if (f.z > 0.f) lastp = 4 * v + 2;
+        if (f.w > 0.f) lastp = 4 * v + 3;
+        l4[it] = ((f.x + f.y) + f.z) + f.w;
+        inc[it] = wave_incl_scan_dpp(l4[it], lane);
+        if (lane == WAVE - 1) ss.wtot[it][wv] = inc[it];
+    }
+    if (lastp >= 0) atomicMax(&ss.lastp, lastp);
+    __syncthreads();
+    float seg_before = base;
+#pragma unroll
+    for (int it = 0; it < 2; it++) {
+        float before = seg_before;
+        for (int w = 0; w < 4; w++) {
+            if (w < wv) before += ss.wtot[it][w];
+            seg_before += ss.wtot[it][w];
+        }
+        const int v = k * (DS_SLICE / 4) + it * 256 + threadIdx.x;
+        const float4 f = e[it];
+        float cum = before + (inc[it] - l4[it]);
+        if (cum <= target) {
+            int pk = -1;
+            cum += f.x;
+            if (cum > target) pk = 4 * v;
+            else {
+                cum += f.y;
+                if (cum > target) pk = 4 * v + 1;
+                else {
+                    cum += f.z;
+                    if (cum > target) pk = 4 * v + 2;
+                    else {
+                        cum += f.w;
+                        if (cum > target) pk = 4 * v + 3;
+                    }
+                }
+            }
+            if (pk >= 0 && pk < V) atomicMin(&ss.pick, pk);
+        }
+    }
+    __syncthreads();
+    int pick = ss.pick;
+    if (pick == 0x7fffffff) pick = max(ss.lastp, 0);
+    if (threadIdx.x == 0) cand[j * gamma + idx] = pick;
+    next_forward_first_step(next, j, pick, &ss);
+}
+
+// Greedy candidate from the partials: the largest block maximum, lowest column among equals.
+__global__ __launch_bounds__(256) void draft_argmax_split_kernel(const float *stats, int nb, int gamma, int idx,
+                                                                  int32_t *cand, NextPlan next)
+{
+    __shared__ SplitScratch ss;
+    __shared__ int redi[32];
+    const int j = blockIdx.x;
+    if (!draft_seq_active(next, j, gamma, idx)) {
+        next_forward_first_step(next, j, 0, &ss);
+        return;
+    }
+    const float *st = stats + (size_t)j * nb * 3;
+    float bv = -3.0e38f;
+    int bi = 0x7fffffff;
+    for (int b = threadIdx.x; b < nb; b += 256) take_better(bv, bi, st[3 * b], __float_as_int(st[3 * b + 2]));
+    block_argmax(bv, bi, ss.red, redi);
+    if (threadIdx.x == 0) cand[j * gamma + idx] = bi;
+    __syncthreads(); // (block_argmax read ss.red last)
+    next_forward_first_step(next, j, bi, &ss);
 }
 
 // ---------------------------------------------------------------- draft: softmax + sample
@@ -1357,8 +1559,21 @@ __global__ __launch_bounds__(1024) void draft_sample_kernel(const float *logits,
 }
 
 hipError_t launch_draft_sample(hipStream_t s, const float *logits, int n_seq, int V, float T, const float *u,
-                               int gamma, int idx, int32_t *cand, float *q, const NextPlan &next)
+                               int gamma, int idx, int32_t *cand, float *q, const NextPlan &next, const float *stats,
+                               int stats_nb, int *did_embed)
 {
+    if (did_embed) *did_embed = 0;
+    const int n_slices = (V + DS_SLICE - 1) / DS_SLICE;
+    if (stats && stats_nb > 0 && stats_nb * 32 == V && n_slices <= DS_MAX_SLICES && n_seq <= 65535) {
+        if (did_embed) *did_embed = next.enabled && next.embed;
+        if (T > 0.f)
+            hipLaunchKernelGGL(draft_sample_split_kernel, dim3(n_slices, n_seq), dim3(256), 0, s, logits, stats, stats_nb,
+                               V, T, u, gamma, idx, cand, q, next);
+        else
+            hipLaunchKernelGGL(draft_argmax_split_kernel, dim3(n_seq), dim3(256), 0, s, stats, stats_nb, gamma, idx, cand,
+                               next);
+        return hipGetLastError();
+    }
     if (V <= ROW_NSEG * ROW_THREADS * 4)
         hipLaunchKernelGGL(draft_sample_fast_kernel, dim3(n_seq), dim3(ROW_THREADS), 0, s, logits, V, T, u, gamma, idx,
                            cand, q, next);

@@ -94,8 +94,9 @@ extern "C" int sd_profile_read(int32_t idx, const char **name, int32_t *count, f
 extern "C" int sd_set_option(const char *name, int32_t value)
 {
     if (!name) return sd_fail(SD_EINVAL, "sd_set_option: null name");
-    if (!strcmp(name, "force_generic")) { // bit 0: GEMMs, bit 1: attention; 1 means both
-        g_force_generic = value == 1 ? 3 : value;
+    if (!strcmp(name, "force_generic")) { // bit 0: GEMMs, bit 1: attention, bit 2: draft sampler that reads whole rows,
+                                          // bit 3: output projection as a launch of its own; 1 means all
+        g_force_generic = value == 1 ? 15 : value;
         return SD_OK;
     }
     if (!strcmp(name, "gemm_splits")) { // value = mode*100 + K splits of the few-row / row-blocked GEMM (0 = automatic)
@@ -280,9 +281,12 @@ extern "C" int sd_load_model(const sd_model_config *cfg, const sd_weights *w, sd
     alloc(&m->act, planes * M * (size_t)c.d_ffn * m->esz + act_pad);
     alloc((void **)&m->logits, M * (size_t)c.vocab * 4);
     alloc((void **)&m->vstats, M * 3 * sizeof(float));
+    alloc((void **)&m->lm_stats, M * (size_t)(c.vocab / 32 + 1) * 3 * sizeof(float));
+    m->lm_stats_nb = 0;
     alloc((void **)&m->part, m->part_floats * 4);
     m->gpart_q_floats = 8 * M * 3 * d;
-    m->gpart_r_floats = 8 * M * d;
+    // (a small model's attention blocks may leave one slab per head instead: see launch_attn_fused_bf16)
+    m->gpart_r_floats = (size_t)(d <= 1024 && c.n_heads <= SD_OPROJ_MAX_HEADS ? std::max(8, c.n_heads) : 8) * M * d;
     alloc((void **)&m->gpart_q, m->gpart_q_floats * 4);
     alloc((void **)&m->gpart_r, m->gpart_r_floats * 4);
     alloc((void **)&m->rope, (size_t)c.max_pos * (c.head_dim / 2) * sizeof(float2));
@@ -329,6 +333,7 @@ extern "C" int sd_free_model(sd_model *m)
     (void)hipFree(m->act);
     (void)hipFree(m->logits);
     (void)hipFree(m->vstats);
+    (void)hipFree(m->lm_stats);
     (void)hipFree(m->part);
     (void)hipFree(m->gpart_q);
     (void)hipFree(m->gpart_r);
@@ -706,8 +711,10 @@ static hipError_t gemm_generic(sd_model *m, hipStream_t s, int mode, const void 
 // Weight-streaming path for a GEMM whose fp32 result is consumed as split-K slabs.  Returns the number
 // of slabs written to `slabs` (slab stride M*N floats), 0 if the shape is outside the kernel's domain.
 static int stream_gemm(sd_model *m, hipStream_t s, const void *A, ActView a_av, WeightSeg w, int M, int N, int K,
-                       float *slabs, size_t slabs_floats, int force_splits, hipError_t *err, int extra_slabs = 0)
+                       float *slabs, size_t slabs_floats, int force_splits, hipError_t *err, int extra_slabs = 0,
+                       LmStats ls = {nullptr, 0.f}, int *ls_done = nullptr)
 {
+    if (ls_done) *ls_done = 0;
     *err = hipSuccess;
     if (m->cfg.dtype != SD_BF16 || (g_force_generic & 1)) return 0;
     int ns = force_splits > 0 ? force_splits : gemm_skinny_splits(GEMM_STORE, M, N, K, w.n_per_seg);
@@ -715,7 +722,8 @@ static int stream_gemm(sd_model *m, hipStream_t s, const void *A, ActView a_av, 
     if ((size_t)(ns + extra_slabs) * M * N > slabs_floats || ns + extra_slabs > 8) ns = 1;
     if ((size_t)(ns + extra_slabs) * M * N > slabs_floats) return 0;
     const ActView none = {0, 0, 0};
-    hipError_t e = launch_gemm_skinny_bf16(s, GEMM_STORE, A, a_av, w, M, N, K, slabs, (size_t)M * N, ns, nullptr, none);
+    hipError_t e = launch_gemm_skinny_bf16(s, GEMM_STORE, A, a_av, w, M, N, K, slabs, (size_t)M * N, ns, nullptr, none,
+                                           ls, ls_done);
     if (e == hipErrorNotSupported) return 0;
     *err = e;
     return ns;
@@ -740,8 +748,12 @@ static int stream_gemm(sd_model *m, hipStream_t s, const void *A, ActView a_av, 
 // groups of R rows per sequence, each group a plan slot of its own.
 static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, int R, int n_seq,
                    const int32_t *seq_ids, int upto_off, const int32_t *cand, int gamma, int cand_idx,
-                   bool want_logits, int G = 1, bool plan_ready = false)
+                   bool want_logits, int G = 1, bool plan_ready = false, bool embed_ready = false,
+                   float lm_invT = -1.f)
 {
+    // plan_ready / embed_ready: the draft sampler of the previous token has laid out this single-row forward /
+    // has also gathered and normed its rows.  lm_invT >= 0: leave the LM head's per-block softmax partials
+    // (1 / temperature, 0 for greedy) for the sampler that follows, where the LM-head kernel can.
     const sd_model_config &cf = m->cfg;
     const int n_slots = n_seq * G; // plan slots: what the attention kernels see as sequences
     const int M = n_slots * R, d = cf.d_model, H = cf.n_heads, hd = cf.head_dim, F = cf.d_ffn, V = cf.vocab;
@@ -760,7 +772,7 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
     if (!plan_ready) { ProfScope ps(T_PLAN, s); // (the draft sampler lays out the single-row forwards that follow it)
     if (G > 1) FWD(launch_plan_prefill(s, R, G, n_seq, seq_ids, cv, slot, upto_off, V, pv));
     else FWD(launch_plan(s, mode, R, n_seq, seq_ids, cv, slot, upto_off, cand, gamma, cand_idx, V, pv)); }
-    { ProfScope ps(T_EMBED, s); // embedding gather + the first layer's norm in one launch
+    if (!embed_ready) { ProfScope ps(T_EMBED, s); // embedding gather + the first layer's norm in one launch
     FWD(launch_embed_rmsnorm(s, cf.dtype, m->embed, pv.row_tok, M, d, m->x, m->norm_attn[0], cf.rms_eps, m->abuf, avd)); }
     int pending = 0; // split-K slabs of the previous down projection not yet added to x
     for (int l = 0; l < cf.n_layers; l++) {
@@ -800,12 +812,15 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
             if (!qkv_in_place) nq_slabs++;
         }
         hipError_t ea = hipErrorNotSupported;
+        int oproj_done = 0; // the attention blocks applied the output projection themselves: H slabs in gpart_r
         // RoPE + append + attention in one launch - unless a sequence spans several slots (prefill): their
         // rows must all be in the cache before any slot's attention starts
         if (cf.dtype == SD_BF16 && !(g_force_generic & 2) && G == 1) {
             ProfScope ps(T_ATTN, s);
+            const bool try_oproj = !lora_o && m->tiled_dd && !(g_force_generic & (1 | 8));
             ea = launch_attn_fused_bf16(s, qkv_src, nq_slabs, (size_t)M * 3 * d, pv, cv, R, n_seq, H, hd, m->rope,
-                                        cf.max_pos, Kl, Vtl, c->total_cap, kv_upper, m->obuf, avd, m->stream_nt);
+                                        cf.max_pos, Kl, Vtl, c->total_cap, kv_upper, m->obuf, avd, m->stream_nt,
+                                        try_oproj ? m->wo[l] : nullptr, d, m->gpart_r, m->gpart_r_floats, &oproj_done);
         }
         if (ea == hipErrorNotSupported) {
             { ProfScope ps(T_ROPE, s);
@@ -825,8 +840,8 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
         if (ea == hipErrorNotSupported) return sd_fail(SD_ECAP, "forward: context too long for the generic attention kernel");
         FWD(ea);
         WeightSeg wo = {{m->wo[l], nullptr, nullptr}, d, m->tiled_dd, m->stream_nt};
-        int no_slabs;
-        { ProfScope ps(T_OPROJ, s);
+        int no_slabs = H;
+        if (!oproj_done) { ProfScope ps(T_OPROJ, s);
         no_slabs = stream_gemm(m, s, m->obuf, avd, wo, M, d, d, m->gpart_r, m->gpart_r_floats, 0, &ge, lora_o ? 1 : 0);
         FWD(ge);
         if (!no_slabs) FWD(gemm_generic(m, s, GEMM_RESID, m->obuf, avd, wo, M, d, d, m->x, nullptr, av0)); }
@@ -872,8 +887,11 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
         }
         WeightSeg wl = {{m->lm_head, nullptr, nullptr}, V, m->tiled_lm, m->stream_nt};
         { ProfScope ps(T_LMHEAD, s);
-        int nl = stream_gemm(m, s, m->abuf, avlm, wl, n_lm, V, d, m->logits, (size_t)cf.max_rows * V, 1, &ge);
+        const LmStats ls = {lm_invT >= 0.f && V % 32 == 0 ? m->lm_stats : nullptr, lm_invT >= 0.f ? lm_invT : 0.f};
+        int ls_done = 0;
+        int nl = stream_gemm(m, s, m->abuf, avlm, wl, n_lm, V, d, m->logits, (size_t)cf.max_rows * V, 1, &ge, 0, ls, &ls_done);
         FWD(ge);
+        m->lm_stats_nb = nl && ls_done ? V / 32 : 0;
         if (!nl) FWD(gemm_generic(m, s, GEMM_STORE, m->abuf, avlm, wl, n_lm, V, d, m->logits, nullptr, av0)); }
         m->last_lm_rows = n_lm;
     }
@@ -920,16 +938,30 @@ extern "C" int sd_draft(sd_model *draft, sd_ctx *c, const int32_t *seq_ids, int3
     if (temperature > 0.f && (!uniforms || !q)) return sd_fail(SD_EINVAL, "sd_draft: sampling needs uniforms and q");
     if (2 * n_seq > draft->cfg.max_rows) return sd_fail(SD_ECAP, "sd_draft: 2*n_seq exceeds the model's max_rows");
     hipStream_t s = (hipStream_t)stream;
+    const sd_model_config &cf = draft->cfg;
+    const float lm_invT = temperature > 0.f ? 1.0f / temperature : 0.f;
+    int embedded = 0; // the previous sampler has run the first step of this forward
     for (int i = 0; i < gamma; i++) {
-        if (i == 0) rc = forward(draft, c, slot, s, PLAN_CATCHUP, 2, n_seq, seq_ids, 0, nullptr, gamma, 0, true);
-        else rc = forward(draft, c, slot, s, PLAN_CAND, 1, n_seq, seq_ids, 0, cand, gamma, i - 1, true, 1, true);
+        if (i == 0) rc = forward(draft, c, slot, s, PLAN_CATCHUP, 2, n_seq, seq_ids, 0, nullptr, gamma, 0, true, 1, false, false, lm_invT);
+        else rc = forward(draft, c, slot, s, PLAN_CAND, 1, n_seq, seq_ids, 0, cand, gamma, i - 1, true, 1, true, embedded != 0, lm_invT);
         if (rc) return rc;
         ProfScope ps(T_SAMPLE, s);
         // every sampler but the last also writes the plan of the forward that feeds its token (the last
-        // candidate is never fed)
-        const NextPlan next = {draft->plan, c->view(), seq_ids, slot, draft->cfg.vocab, i + 1 < gamma ? 1 : 0, gamma, i + 1};
-        hipError_t e = launch_draft_sample(s, draft->logits, n_seq, draft->cfg.vocab, temperature, uniforms, gamma, i,
-                                           cand, q, next);
+        // candidate is never fed) - and, where it works from the LM head's partials, runs that forward's
+        // first step (its rows: one per sequence)
+        NextPlan next = {draft->plan, c->view(), seq_ids, slot, cf.vocab, i + 1 < gamma ? 1 : 0, gamma, i + 1};
+        next.embed = cf.dtype == SD_BF16 && !(g_force_generic & 4);
+        next.d = cf.d_model;
+        next.E = draft->embed;
+        next.x = draft->x;
+        next.g = draft->norm_attn[0];
+        next.eps = cf.rms_eps;
+        next.out = draft->abuf;
+        next.av = ActView{draft->plane_d, n_seq, cf.dtype == SD_BF16 && cf.d_model % 128 == 0};
+        const bool use_stats = draft->lm_stats_nb > 0 && !(g_force_generic & 4);
+        hipError_t e = launch_draft_sample(s, draft->logits, n_seq, cf.vocab, temperature, uniforms, gamma, i, cand, q,
+                                           next, use_stats ? draft->lm_stats : nullptr, use_stats ? draft->lm_stats_nb : 0,
+                                           &embedded);
         if (e != hipSuccess) return sd_fail(SD_EHIP, std::string("sd_draft: sample: ") + hipGetErrorString(e));
     }
     return SD_OK;

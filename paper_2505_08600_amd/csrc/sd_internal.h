@@ -170,6 +170,16 @@ struct NextPlan {
     const int32_t *seq_ids;
     int32_t slot, vocab, enabled;
     int32_t gamma, next_idx; // row slots of the draft call; index of the candidate the planned forward leads to
+    // (samplers that run 256-thread blocks only) the planned forward's first step as well: embedding row of the
+    // token into x[j] and the first layer's norm of it into the activation buffer, as embed_rmsnorm_kernel does
+    int32_t embed; // 0: the forward gathers and norms the row itself
+    int32_t d;
+    const void *E;  // bf16 [vocab][d]
+    float *x;
+    const float *g; // first layer's attention-norm gains
+    float eps;
+    void *out;
+    ActView av;
 };
 
 struct WeightSeg { // up to three matrices stacked along N (q,k,v or gate,up)
@@ -212,6 +222,15 @@ __host__ __device__ __forceinline__ size_t weight_index(int n, int k, int K, int
 
 enum GemmMode { GEMM_STORE = 0, GEMM_RESID = 1, GEMM_SWIGLU = 2 };
 
+// Softmax partials the few-row GEMM can leave beside an LM head's logits, so that the draft sampler needs no pass
+// over the whole row before it can place its uniform: for logits row m and block b (32 consecutive columns)
+// p[(m * n_blocks + b) * 3 + {0, 1, 2}] = max, sum of exp((x - max) * invT) (0 when invT is 0: greedy), and the
+// lowest column holding the max (an int stored bit for bit).
+struct LmStats {
+    float *p;   // nullptr: none wanted
+    float invT; // 1 / temperature, or 0
+};
+
 // ---------------------------------------------------------------- host-side objects
 struct sd_model {
     sd_model_config cfg;
@@ -239,6 +258,8 @@ struct sd_model {
     size_t plane_d, plane_f; // element offsets between the planes
     float *logits;  // [max_rows][vocab]
     float *vstats;  // [max_rows][3] per-row (max, sum of exponentials, argmax) of the verify tail
+    float *lm_stats; // [max_rows][vocab / 32][3] per-block softmax partials of the last LM head (see LmStats)
+    int lm_stats_nb; // blocks per row the last forward's LM head left there (0: none)
     float *part;    // split-KV partial results of the attention kernel
     float *gpart_q, *gpart_r; // split-K partial slabs of the weight-streaming GEMMs (QKV; O / down)
     size_t gpart_q_floats, gpart_r_floats;
@@ -327,8 +348,12 @@ hipError_t launch_rope_append(hipStream_t s, int dtype, const float *qkv, int n_
 hipError_t launch_attn_generic(hipStream_t s, int dtype, const void *qbuf, ActView q_av, const void *Kl,
                                const void *Vtl, PlanView pv, CtxView cv, int R, int n_seq, int H, int hd,
                                int64_t total_cap, int len_upper, void *obuf, ActView o_av);
+// stats / stats_nb: the per-block softmax partials the LM head left (LmStats), stats_nb blocks of 32 columns per
+// row (0: none - the one-block-per-row samplers read the whole row first).  *did_embed: whether the sampler
+// honoured next.embed (only the kernels that work from the partials do).
 hipError_t launch_draft_sample(hipStream_t s, const float *logits, int n_seq, int V, float T, const float *u,
-                               int gamma, int idx, int32_t *cand, float *q, const NextPlan &next);
+                               int gamma, int idx, int32_t *cand, float *q, const NextPlan &next,
+                               const float *stats = nullptr, int stats_nb = 0, int *did_embed = nullptr);
 hipError_t launch_verify_tail(hipStream_t s, const float *logits, int n_seq, int gamma, int V, float T,
                               const int32_t *cand, const float *q, const float *u, const int32_t *seq_ids,
                               int32_t *n_acc, int32_t *next_tok, int commit, CtxView cv, float *stats);
@@ -347,15 +372,23 @@ hipError_t launch_stream_read(hipStream_t s, const void *buf, size_t bytes, uint
 // GEMM_STORE: C receives `splits` partial slabs (slab stride c_split_stride floats) that the consumer adds;
 // GEMM_SWIGLU: Cact receives the bf16 hi/lo planes.  gemm_skinny_splits tells how many slabs to expect.
 int gemm_skinny_splits(int mode, int M, int N, int K, int n_per_seg);
+// ls: softmax partials wanted beside the result (GEMM_STORE without K splits only); *ls_done tells whether the
+// kernel chosen for the shape wrote them.
 hipError_t launch_gemm_skinny_bf16(hipStream_t s, int mode, const void *A, ActView a_av, WeightSeg w, int M, int N,
-                                   int K, float *C, size_t c_split_stride, int splits, void *Cact, ActView c_av);
+                                   int K, float *C, size_t c_split_stride, int splits, void *Cact, ActView c_av,
+                                   LmStats ls = {nullptr, 0.f}, int *ls_done = nullptr);
 hipError_t launch_add_rmsnorm(hipStream_t s, int dtype, float *x, const float *part, int n_slabs, size_t slab_stride,
                               const float *g, const int32_t *row_map, int n_rows, int d, float eps, void *out,
                               ActView out_av);
+// wo_tiled / oslab (optional): let the attention blocks of a small model apply their head's columns of the
+// output projection themselves and leave H partial slabs [H][n_seq * R][d_model] in oslab; *oproj_done tells
+// whether they did (then obuf is not written and the projection launch is skipped).
+#define SD_OPROJ_MAX_HEADS 16
 hipError_t launch_attn_fused_bf16(hipStream_t s, const float *qkv, int n_slabs, size_t slab_stride, PlanView pv,
                                   CtxView cv, int R, int n_seq, int H, int hd, const float2 *rope, int max_pos,
                                   void *Kl, void *Vtl, int64_t total_cap, int len_upper, void *obuf, ActView o_av,
-                                  int stream_nt);
+                                  int stream_nt, const void *wo_tiled = nullptr, int d_model = 0, float *oslab = nullptr,
+                                  size_t oslab_floats = 0, int *oproj_done = nullptr);
 hipError_t launch_attn_mfma_bf16(hipStream_t s, const void *qbuf, ActView q_av, const void *Kl, const void *Vtl,
                                  PlanView pv, CtxView cv, int R, int n_seq, int H, int hd, int64_t total_cap,
                                  int len_upper, float *part, size_t part_floats, void *obuf, ActView o_av, int stream_nt);

@@ -263,6 +263,95 @@ def test_small_bf16_both_fused_attention_block_shapes_match_reference_kernels(wa
     gt.close()
 
 
+@pytest.mark.parametrize("shape_name,B", [("small_target_bf16", 1), ("small_target_bf16", 5), ("small_draft_bf16", 3),
+                                          ("draft_a_1layer", 1), ("draft_a_1layer", 2)])
+def test_attention_blocks_applying_the_output_projection_match_the_separate_launch(shape_name, B):
+    """For small models in few blocks the fused attention kernel multiplies its head's output rows with that
+    head's columns of the output projection and leaves one partial slab per head for the add + norm kernel
+    (head widths 128 and 64; 2, 2 and 12 heads).  Option force_generic = 8 takes the projection out again as a
+    GEMM launch of its own; both orders of the same fp32 sums must agree far inside the bf16 tolerance."""
+    import dataclasses
+    _say(f"{shape_name}: output projection inside the attention blocks vs its own launch, batch {B}")
+    st_ = (dataclasses.replace(dg.SHAPES["draft_a"], n_layers=1, vocab=2048, name="draft_a_1layer")
+           if shape_name == "draft_a_1layer" else dg.SHAPES[shape_name])
+    w = dg.make_weights(st_, 81, BF16_LM_SCALE)
+    gt = api.Model(st_, w, max_rows=max(16, 6 * B), max_pos=256)
+    lens = dg.make_prompt_lengths(81 + B, B, 5, 150)
+    prompts = [[int(t) for t in dg.make_prompt(81, b, int(lens[b]), st_.vocab)] for b in range(B)]
+    cand = H.dev(dg.make_prompt(82, B, 5 * B, st_.vocab).reshape(B, 5).astype(np.int32))
+    outs = []
+    for force in (0, 8):
+        api.set_option("force_generic", force)
+        try:
+            ctx = api.Context([int(l) + 16 for l in lens])
+            ctx.attach(gt)
+            H.gpu_prefill(ctx, [gt], prompts)
+            na = torch.zeros(B, dtype=torch.int32, device="cuda")
+            nx = torch.zeros(B, dtype=torch.int32, device="cuda")
+            api.sd_verify(gt, ctx, None, B, 5, 0.0, cand, None, None, na, nx, commit=False)
+            ctx.sync()
+            outs.append(gt.last_logits().cpu().numpy())
+            ctx.close()
+        finally:
+            api.set_option("force_generic", 0)
+    rel = np.abs(outs[0] - outs[1]).max() / np.abs(outs[1]).max()
+    _say(f"  rel diff {rel:.2e}")
+    assert outs[0].shape == (6 * B, st_.vocab) and np.isfinite(outs[0]).all() and rel < 2e-4
+    assert not np.array_equal(outs[0], outs[1]), "the option did not change the path"
+    gt.close()
+
+
+@pytest.mark.parametrize("T", [0.0, 0.9])
+def test_draft_sampler_from_the_lm_heads_partials_matches_the_whole_row_sampler(T):
+    """The LM head of a bf16 model leaves (max, sum of exponentials, arg-max) per 32 columns; the draft sampler
+    then runs one block per 2048-column slice, none waiting for another, and the block that draws the token also
+    gathers and norms the next forward's row.  Option force_generic = 4 brings back the sampler in which one
+    block reads the whole row, and the embedding launch.  Vocabulary 6176 = 3 slices + 32 columns; three
+    sequences, one of them with fewer candidates of its own; two draft calls in a row."""
+    import dataclasses
+    _say(f"small bf16 draft: sampler from LM-head partials vs whole-row sampler, T={T}")
+    sd_ = dataclasses.replace(dg.SHAPES["small_draft_bf16"], vocab=6176, name="small_draft_v6176")
+    w = dg.make_weights(sd_, 83, BF16_LM_SCALE)
+    gd = api.Model(sd_, w, max_rows=16, max_pos=256)
+    B, gamma, V = 3, 4, sd_.vocab
+    prompts = [[int(t) for t in dg.make_prompt(83, b, 20 + 7 * b, V)] for b in range(B)]
+    u = H.dev(np.stack([np.stack([dg.make_uniforms(83, dg.DRAFT_STREAM, b, k, gamma) for b in range(B)]) for k in range(2)]))
+    outs = []
+    for force in (0, 4):
+        api.set_option("force_generic", force)
+        try:
+            ctx = api.Context([64] * B)
+            ctx.attach(gd)
+            H.gpu_prefill(ctx, [gd], prompts)
+            ctx.policy_set([4, 2, 4])
+            res = []
+            for k in range(2):
+                cand = torch.full((B, gamma), -1, dtype=torch.int32, device="cuda")
+                q = torch.zeros((B, gamma, V), dtype=torch.float32, device="cuda")
+                api.sd_draft(gd, ctx, None, B, gamma, T, u[k] if T > 0 else None, cand, q if T > 0 else None)
+                ctx.sync()
+                res.append((cand.cpu().numpy().copy(), q.cpu().numpy().copy(), gd.last_logits().cpu().numpy().copy()))
+                for b in range(B):  # roll the draft cache back: the second call drafts from the same state
+                    ctx.truncate(gd, b, len(prompts[b]) - 1)
+            outs.append(res)
+            ctx.close()
+        finally:
+            api.set_option("force_generic", 0)
+    for k in range(2):
+        (c0, q0, l0), (c1, q1, l1) = outs[0][k], outs[1][k]
+        counts = [4, 2, 4]
+        for b in range(B):
+            assert (c0[b, :counts[b]] == c1[b, :counts[b]]).all(), (k, b, c0[b], c1[b])
+            assert ((0 <= c0[b, :counts[b]]) & (c0[b, :counts[b]] < V)).all()
+        assert np.array_equal(l0, l1), "the logits of the last forward must not depend on the sampler"
+        if T > 0:
+            for b in range(B):
+                dq = np.abs(q0[b, :counts[b]] - q1[b, :counts[b]]).max()
+                assert dq < 1e-6, (k, b, dq)
+                assert np.abs(q0[b, :counts[b]].sum(-1) - 1.0).max() < 1e-4
+    gd.close()
+
+
 def test_draft_and_verify_are_graph_capturable_and_replays_match_eager():
     """sd_draft and sd_verify launch kernels only (no allocation, copy, memset or host synchronisation), so a
     caller may capture them into a HIP graph.  Every replay, with eager calls and synchronisations in
