@@ -353,7 +353,10 @@ int sd_last_logits(sd_model *m, float *out, int32_t max_rows, int32_t *rows);
  * "x" (residual [rows][d_model]), "qkv" ([rows][3*d_model]), "q", "o", "a"
  * ([rows][d_model]) or "act" ([rows][d_ffn]); "seq_order" / "seq_len" give, for the
  * first `rows` sequences of the last forward, the order attention blocks start in
- * (longest first) and the cache length after that forward.  Synchronises. */
+ * (longest first) and the cache length after that forward.  Synchronises.  Buffers a
+ * fused kernel skipped hold older data: "qkv" and "q" whenever attention consumes the
+ * QKV GEMM's partial sums directly, "o" when a small model's attention blocks apply the
+ * output projection themselves (option "force_generic" selects the unfused kernels). */
 int sd_debug_read(sd_model *m, const char *name, float *out, int32_t rows);
 /* Host-only (no GPU call): element offset that the library's internal layouts assign.
  * kind 0: tiled bf16 weight [N][K], a = row n, b = column k, c = K  (16-row x 128-column
