@@ -503,13 +503,66 @@ hipError_t launch_gemm_generic(hipStream_t s, int dtype, int mode, const void *A
 
 // ---------------------------------------------------------------- RoPE + KV append
 // Embedding gather fused with the first layer's RMSNorm: x[r] = E[token_r]; out[r] = rmsnorm(x[r]) * g.
-// Same element-to-thread assignment and reduction as rmsnorm_kernel, so the result is identical to the
-// two separate launches.
-// Row r of one forward, by a whole block (red: 32 floats of LDS).
+// Row r of one forward, by a whole block (red: 32 floats of LDS).  The element-wise form has the same
+// element-to-thread assignment and reduction as rmsnorm_kernel (identical to the two separate launches); the
+// vector form sums the squares in another order.
+// bf16 rows whose width is a multiple of 8: 16-byte loads and stores, the row kept in registers between the two
+// passes (a thread's 8 columns stay inside one 128-column step of the step-major order).
+__device__ void embed_rmsnorm_row_vec(const bf16_t *E, int tok, int r, int d, float *x, const float *g, float eps,
+                                      bf16_t *out, ActView av, float *red)
+{
+    constexpr int KEEP = 4; // 8-column pieces a thread holds (d <= 8 * KEEP * blockDim.x, else the rest is re-read)
+    const uint4 *src = (const uint4 *)(E + (size_t)tok * d);
+    float *xr = x + (size_t)r * d;
+    const int npiece = d >> 3;
+    float v[KEEP][8];
+    float ss = 0.f;
+    int it = 0;
+    for (int p = threadIdx.x; p < npiece; p += blockDim.x, it++) {
+        const uint4 w = src[p];
+        const uint32_t ws[4] = {w.x, w.y, w.z, w.w};
+        float f[8];
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            f[2 * e] = __uint_as_float(ws[e] << 16);
+            f[2 * e + 1] = __uint_as_float(ws[e] & 0xffff0000u);
+        }
+        *(float4 *)(xr + 8 * p) = make_float4(f[0], f[1], f[2], f[3]);
+        *(float4 *)(xr + 8 * p + 4) = make_float4(f[4], f[5], f[6], f[7]);
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+            ss += f[e] * f[e];
+            if (it < KEEP) v[it < KEEP ? it : 0][e] = f[e];
+        }
+    }
+    ss = block_sum(ss, red); // (its barriers also make the x row visible to the re-reads below)
+    const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+    it = 0;
+    for (int p = threadIdx.x; p < npiece; p += blockDim.x, it++) {
+        float f[8];
+        if (it < KEEP) {
+#pragma unroll
+            for (int e = 0; e < 8; e++) f[e] = v[it < KEEP ? it : 0][e];
+        } else {
+            const float4 a = *(const float4 *)(xr + 8 * p), b = *(const float4 *)(xr + 8 * p + 4);
+            f[0] = a.x, f[1] = a.y, f[2] = a.z, f[3] = a.w, f[4] = b.x, f[5] = b.y, f[6] = b.z, f[7] = b.w;
+        }
+        const float4 g0 = *(const float4 *)(g + 8 * p), g1 = *(const float4 *)(g + 8 * p + 4);
+        const size_t o = act_index(av, r, 8 * p, d);
+        store_act4(out, o, av.plane, f[0] * inv * g0.x, f[1] * inv * g0.y, f[2] * inv * g0.z, f[3] * inv * g0.w);
+        store_act4(out, o + 4, av.plane, f[4] * inv * g1.x, f[5] * inv * g1.y, f[6] * inv * g1.z, f[7] * inv * g1.w);
+    }
+}
 template <typename T>
 __device__ void embed_rmsnorm_row(const T *E, int tok, int r, int d, float *x, const float *g, float eps, T *out,
                                   ActView av, float *red)
 {
+    if constexpr (sizeof(T) == 2) {
+        if ((d & 7) == 0) { // (uniform)
+            embed_rmsnorm_row_vec(E, tok, r, d, x, g, eps, out, av, red);
+            return;
+        }
+    }
     const T *src = E + (size_t)tok * d;
     float *xr = x + (size_t)r * d;
     float ss = 0.f;
