@@ -64,6 +64,8 @@ enum { SD_FP32 = 0, SD_BF16 = 1 };
  * and lo = bf16(x - hi), i.e. about 16 mantissa bits: with single-bf16 activations two
  * correct implementations that add in different orders drift apart by more than the logit
  * tolerance over 32 layers.  Accumulation, the residual stream, softmax and logits are fp32.
+ * (The normed hidden state is split into its two terms either after the division by rms or,
+ * where option "norm_fold" applies, before it - the division then scales the fp32 sums.)
  * dtype SD_FP32: everything fp32.
  * max_rows: largest number of token rows one forward may carry
  *           (verify: n_seq * (gamma + 1); draft: 2 * n_seq; prefill chunks adapt).
@@ -383,6 +385,12 @@ int sd_debug_stream_read(const void *buf, size_t bytes, uint32_t *scratch_word, 
  * the bf16 GEMMs of mode 0 (plain / residual) or 2 (SwiGLU, ignored): a tuning knob.
  * option "gemm_tile_cols" = 192 or 256 forces the block width (in weight rows) of the
  * row-blocked GEMM for more than 64 rows where the shape allows it (0 = automatic).
+ * option "norm_fold": with at most 32 rows in a forward, the add + RMSNorm launches of a
+ * layer can be split between the projection before them (adds the residual, applies the gains,
+ * leaves per-block sums of squares) and the GEMM after them (scales its sums by 1 / rms); the
+ * operand is then rounded to its two bf16 terms before the division by rms instead of after.
+ * 0 = automatic (models whose weights exceed the memory-side cache), 1 = wherever the shapes
+ * allow, 2 = never.
  * option "attn_waves" = 4 or 8 forces the block shape of the fused attention kernel
  * (0 = automatic: 4-wave blocks when (sequence, head) pairs oversubscribe the chip and
  * contexts are short).

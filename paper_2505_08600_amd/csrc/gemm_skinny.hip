@@ -304,15 +304,17 @@ static void split_geometry(int K, int ks, int *kps, int *ny)
 // complete sums, so there grid.y is 1).  The waves interleave the 128-element K steps, fetch their
 // activation fragments straight from global memory (L2) - no barrier inside the K loop - and keep the
 // loads of U steps in flight in registers; the four partial accumulators meet in LDS.
-template <int NMAT, bool PACKED, int MT, int U, int NTW, bool NT_HINT>
-__global__ __launch_bounds__(256) void gemm_ksplit_kernel(const uint16_t *__restrict__ A, ActView a_av, WeightSeg w,
+template <int NMAT, bool PACKED, int MT, int U, int NTW, bool NT_HINT, int WAVES = 4>
+__global__ __launch_bounds__(WAVES * 64) void gemm_ksplit_kernel(const uint16_t *__restrict__ A, ActView a_av, WeightSeg w,
                                                           int M, int N, int K, int steps_per_split,
                                                           float *__restrict__ C, size_t c_split_stride,
-                                                          uint16_t *__restrict__ Cact, ActView c_av, LmStats ls)
+                                                          uint16_t *__restrict__ Cact, ActView c_av, LmStats ls,
+                                                          NormFold nf)
 {
-    constexpr int WAVES = 4;
+    constexpr int THREADS = WAVES * 64;
     constexpr int NW = NMAT * NTW; // weight tiles per wave and step
     __shared__ float red[WAVES][NW][MT][64][4];
+    __shared__ float s_inv[32]; // consumer side of a split norm: 1 / rms of every output row
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int row = lane & 15, grp = lane >> 4;
     const int n0 = blockIdx.x * 16 * NTW;
@@ -333,9 +335,23 @@ __global__ __launch_bounds__(256) void gemm_ksplit_kernel(const uint16_t *__rest
     for (int t = 0; t < MT; t++) {
         const int m = PACKED ? (row & 7) : t * 16 + row;
         a_live[t] = m < M;
+        const int src = !a_live[t] ? 0 : nf.row_map ? nf.row_map[m] : m;
         // step-major activations: row m of K step st starts at (st * rows + m) * 128
-        Ap[t] = A + ((PACKED && row >= 8) ? a_av.plane : 0) + (size_t)(a_live[t] ? m : 0) * 128 + grp * 8;
+        Ap[t] = A + ((PACKED && row >= 8) ? a_av.plane : 0) + (size_t)src * 128 + grp * 8;
         Al[t] = Ap[t] + a_av.plane;
+    }
+    constexpr int ROWS_MAX = PACKED ? 8 : 16 * MT;
+    constexpr int SSR = (ROWS_MAX + WAVES - 1) / WAVES, SSB = SD_NORMFOLD_MAX_BLOCKS / 256; // (a lane loads 4 entries at once)
+    constexpr int EPI = (16 * NTW * ROWS_MAX + THREADS - 1) / THREADS; // epilogue elements per thread
+    float4 ssl[SSR][SSB]; // consumer side of a split norm: wave w sums the producer's per-block shares of rows w, w + 4, ...
+    int ss_src[SSR];
+    float xres[EPI], gval[EPI]; // producer side: residual and gain of this thread's epilogue elements
+    if (nf.ss_in) {
+#pragma unroll
+        for (int r = 0; r < SSR; r++) {
+            const int m = wave + r * WAVES;
+            ss_src[r] = m < M ? (nf.row_map ? nf.row_map[m] : m) : 0;
+        }
     }
     const size_t step_stride = (size_t)a_av.rows * 128;
     f32x4 acc[NW][MT];
@@ -362,6 +378,25 @@ __global__ __launch_bounds__(256) void gemm_ksplit_kernel(const uint16_t *__rest
             for (int i = 0; i < 4; i++)
                 wv[b][c][i] = ld_stream<NT_HINT>((const bf16x8 *)(Wp[c % NMAT] + (size_t)(c / NMAT) * tile_elems + (size_t)st * 2048 + i * 512));
     };
+    // the small loads of a split norm go out ahead of the weight stream (loads return in order: behind the
+    // first weight loads they would hold up everything issued after them for as long as they take) and are used
+    // after the K loop; every address is clamped into range, so the loads are unconditional
+    if (nf.ss_in) { // (uniform)
+#pragma unroll
+        for (int r = 0; r < SSR; r++)
+#pragma unroll
+            for (int i = 0; i < SSB; i++) // (entries past ss_nb are stale or never written: masked when summed)
+                ssl[r][i] = *(const float4 *)(nf.ss_in + ss_src[r] * SD_NORMFOLD_MAX_BLOCKS + 4 * (lane + 64 * i));
+    }
+    if (NMAT == 1 && nf.x) { // (uniform)
+#pragma unroll
+        for (int k = 0; k < EPI; k++) {
+            const int e = threadIdx.x + THREADS * k;
+            const int m = min(e / (16 * NTW), M - 1), n = n0 + (e & (16 * NTW - 1));
+            xres[k] = nf.x[(size_t)m * N + n];
+            gval[k] = nf.g[n];
+        }
+    }
 #pragma unroll
     for (int u = 0; u < U; u++)
         if (s_begin + wave + u * WAVES < s_end) issue(s_begin + wave + u * WAVES, u);
@@ -390,10 +425,28 @@ __global__ __launch_bounds__(256) void gemm_ksplit_kernel(const uint16_t *__rest
         for (int t = 0; t < MT; t++)
 #pragma unroll
             for (int r = 0; r < 4; r++) red[wave][c][t][lane][r] = acc[c][t][r];
+    if (nf.ss_in) {
+#pragma unroll
+        for (int r = 0; r < SSR; r++) {
+            float a = 0.f;
+#pragma unroll
+            for (int i = 0; i < SSB; i++) {
+                const int b = 4 * (lane + 64 * i);
+                a += b < nf.ss_nb ? ssl[r][i].x : 0.f;
+                a += b + 1 < nf.ss_nb ? ssl[r][i].y : 0.f;
+                a += b + 2 < nf.ss_nb ? ssl[r][i].z : 0.f;
+                a += b + 3 < nf.ss_nb ? ssl[r][i].w : 0.f;
+            }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) a += __shfl_xor(a, o, 64);
+            const int m = wave + r * WAVES;
+            if (lane == 0 && m < ROWS_MAX) s_inv[m] = 1.0f / sqrtf(a / (float)K + nf.eps);
+        }
+    }
     __syncthreads();
     // tile element D[n = 4*(slot/16) + r][m' = slot%16] sits at red[.][c][t][slot][r]
     constexpr int ROWS = PACKED ? 8 : 16 * MT;
-    for (int e = threadIdx.x; e < 16 * NTW * ROWS; e += 256) {
+    for (int e = threadIdx.x, ek = 0; e < 16 * NTW * ROWS; e += THREADS, ek++) {
         const int nn = e & 15, j = (e >> 4) % NTW, m = e / (16 * NTW);
         if (m >= M) continue;
         const int t = PACKED ? 0 : m >> 4;
@@ -407,6 +460,26 @@ __global__ __launch_bounds__(256) void gemm_ksplit_kernel(const uint16_t *__rest
                 v[c] += red[wv2][j * NMAT + c][t][slot][r];
                 if (PACKED) v[c] += red[wv2][j * NMAT + c][t][slot + 8][r];
             }
+            if (nf.ss_in) v[c] *= s_inv[m];
+        }
+        if (NMAT == 1 && nf.x) { // (uniform) producer side of a split norm; the launcher rules out K splits
+            const int n = n0 + j * 16 + nn;
+            float xr = xres[0], gg = gval[0];
+#pragma unroll
+            for (int k = 1; k < EPI; k++)
+                if (k == ek) xr = xres[k], gg = gval[k];
+            const float xn = xr + v[0];
+            nf.x[(size_t)m * N + n] = xn;
+            const float y = xn * gg;
+            const uint16_t hi = bf16_bits_rne(y);
+            const size_t o = act_index(c_av, m, n, N);
+            Cact[o] = hi;
+            Cact[c_av.plane + o] = bf16_bits_rne(y - __uint_as_float((uint32_t)hi << 16));
+            float sq = xn * xn; // the block's 16 * NTW columns of row m sit in adjacent lanes
+#pragma unroll
+            for (int o2 = 8 * NTW; o2 > 0; o2 >>= 1) sq += __shfl_xor(sq, o2, 64);
+            if ((e & (16 * NTW - 1)) == 0) nf.ss_out[m * SD_NORMFOLD_MAX_BLOCKS + blockIdx.x] = sq;
+            continue;
         }
         if (NMAT == 2) {
             const float y = v[0] / (1.0f + expf(-v[0])) * v[NMAT - 1];
@@ -545,15 +618,22 @@ int gemm_skinny_splits(int mode, int M, int N, int K, int n_per_seg)
     return ny;
 }
 
+// Blocks (= entries of NormFold::ss_out per row) of a producer launch with N output columns.
+int gemm_normfold_blocks(int N) { return N % 32 == 0 && N / 32 >= 256 ? N / 32 : N / 16; }
+
 // mode GEMM_STORE: C receives `splits` partial slabs [split][M][N] (split stride c_split_stride floats);
 // mode GEMM_SWIGLU: Cact receives the bf16 hi/lo planes.  GEMM_RESID is expressed by the caller as a
 // store into partial slabs followed by the fused add + norm kernel.
 hipError_t launch_gemm_skinny_bf16(hipStream_t s, int mode, const void *A, ActView a_av, WeightSeg w, int M, int N,
                                    int K, float *C, size_t c_split_stride, int splits, void *Cact, ActView c_av,
-                                   LmStats ls, int *ls_done)
+                                   LmStats ls, int *ls_done, NormFold nf)
 {
     if (ls_done) *ls_done = 0;
     const LmStats no_ls = {nullptr, 0.f};
+    const bool folded = nf.ss_in || nf.x || nf.row_map;
+    if (folded && (M > 32 || nf.ss_nb > SD_NORMFOLD_MAX_BLOCKS)) return hipErrorNotSupported;
+    if (nf.x && (mode != GEMM_STORE || splits != 1 || !c_av.sm || N % 128 != 0 || N / 16 > SD_NORMFOLD_MAX_BLOCKS))
+        return hipErrorNotSupported;
     if (M < 1 || K % 128 != 0 || K < 128 || (mode != GEMM_STORE && mode != GEMM_SWIGLU)) return hipErrorNotSupported;
     if (!w.tiled) return hipErrorNotSupported; // these kernels read the 16 x 128 tile order only
     for (int i = 0; i < 3; i++)
@@ -571,10 +651,10 @@ hipError_t launch_gemm_skinny_bf16(hipStream_t s, int mode, const void *A, ActVi
     do {                                                                                                                  \
         if (w.nt)                                                                                                         \
             hipLaunchKernelGGL((gemm_ksplit_kernel<NMAT, PACKED, MT, U, NTW, true>), GRID, dim3(256), 0, s, a, a_av, w, M, \
-                               N, K, SPS, C, c_split_stride, ca, c_av, LS);                                               \
+                               N, K, SPS, C, c_split_stride, ca, c_av, LS, nf);                                           \
         else                                                                                                              \
             hipLaunchKernelGGL((gemm_ksplit_kernel<NMAT, PACKED, MT, U, NTW, false>), GRID, dim3(256), 0, s, a, a_av, w,  \
-                               M, N, K, SPS, C, c_split_stride, ca, c_av, LS);                                            \
+                               M, N, K, SPS, C, c_split_stride, ca, c_av, LS, nf);                                        \
     } while (0)
     if (mode == GEMM_SWIGLU) { // K split inside the block only
         if (N % 16 != 0) return hipErrorNotSupported;
@@ -586,7 +666,10 @@ hipError_t launch_gemm_skinny_bf16(hipStream_t s, int mode, const void *A, ActVi
     }
     int kps, ny;
     split_geometry(K, splits, &kps, &ny);
-    if (N % 32 == 0 && w.n_per_seg % 32 == 0) {
+    if (nf.x && ny != 1) return hipErrorNotSupported;
+    // (a producer of a split norm has no K split to fill the chip with: 16-column blocks where 32-column ones would
+    // leave compute units idle, and four K steps in flight per wave instead of two)
+    if (N % 32 == 0 && w.n_per_seg % 32 == 0 && !(nf.x && N / 32 < 256)) {
         dim3 grid(N / 32, ny);
         const LmStats lsk = ny == 1 ? ls : no_ls; // (partial sums of a K split have no softmax)
         if (ls_done && lsk.p) *ls_done = 1;
@@ -595,7 +678,8 @@ hipError_t launch_gemm_skinny_bf16(hipStream_t s, int mode, const void *A, ActVi
         else SD_KSPLIT(1, false, 2, 1, 2, grid, kps / 128, lsk);
     } else if (N % 16 == 0 && w.n_per_seg % 16 == 0) {
         dim3 grid(N / 16, ny);
-        if (M <= 8) SD_KSPLIT(1, true, 1, 2, 1, grid, kps / 128, no_ls);
+        if (M <= 8 && nf.x) SD_KSPLIT(1, true, 1, 4, 1, grid, kps / 128, no_ls);
+        else if (M <= 8) SD_KSPLIT(1, true, 1, 2, 1, grid, kps / 128, no_ls);
         else if (M <= 16) SD_KSPLIT(1, false, 1, 2, 1, grid, kps / 128, no_ls);
         else SD_KSPLIT(1, false, 2, 1, 1, grid, kps / 128, no_ls);
     } else {

@@ -10,6 +10,7 @@
 
 static thread_local std::string g_err;
 int g_force_generic = 0;
+static int g_norm_fold = 0; // option "norm_fold"
 
 void sd_set_error(const std::string &s) { g_err = s; }
 int sd_fail(int code, const std::string &s)
@@ -108,6 +109,12 @@ extern "C" int sd_set_option(const char *name, int32_t value)
     if (!strcmp(name, "gemm_tile_cols")) { // weight rows per block of the row-blocked GEMM: 192, 256, or 0 = automatic
         if (value != 0 && value != 192 && value != 256) return sd_fail(SD_EINVAL, "sd_set_option: gemm_tile_cols is 0, 192 or 256");
         g_force_tile_cols = value;
+        return SD_OK;
+    }
+    if (!strcmp(name, "norm_fold")) { // add + RMSNorm split between producer and consumer GEMM: 0 = automatic (models whose
+                                      // weights are streamed), 1 = wherever the shapes allow, 2 = never
+        if (value < 0 || value > 2) return sd_fail(SD_EINVAL, "sd_set_option: norm_fold is 0, 1 or 2");
+        g_norm_fold = value;
         return SD_OK;
     }
     if (!strcmp(name, "attn_waves")) { // waves per block of the fused attention kernel: 4, 8, or 0 = automatic
@@ -282,6 +289,7 @@ extern "C" int sd_load_model(const sd_model_config *cfg, const sd_weights *w, sd
     alloc((void **)&m->logits, M * (size_t)c.vocab * 4);
     alloc((void **)&m->vstats, M * 3 * sizeof(float));
     alloc((void **)&m->lm_stats, M * (size_t)(c.vocab / 32 + 1) * 3 * sizeof(float));
+    alloc((void **)&m->ss_part, (size_t)SD_NORMFOLD_MAX_BLOCKS * 32 * sizeof(float));
     m->lm_stats_nb = 0;
     alloc((void **)&m->part, m->part_floats * 4);
     m->gpart_q_floats = 8 * M * 3 * d;
@@ -334,6 +342,7 @@ extern "C" int sd_free_model(sd_model *m)
     (void)hipFree(m->logits);
     (void)hipFree(m->vstats);
     (void)hipFree(m->lm_stats);
+    (void)hipFree(m->ss_part);
     (void)hipFree(m->part);
     (void)hipFree(m->gpart_q);
     (void)hipFree(m->gpart_r);
@@ -710,9 +719,10 @@ static hipError_t gemm_generic(sd_model *m, hipStream_t s, int mode, const void 
 
 // Weight-streaming path for a GEMM whose fp32 result is consumed as split-K slabs.  Returns the number
 // of slabs written to `slabs` (slab stride M*N floats), 0 if the shape is outside the kernel's domain.
+static const NormFold kNoFold = {nullptr, 0, 0.f, nullptr, nullptr, nullptr, nullptr};
 static int stream_gemm(sd_model *m, hipStream_t s, const void *A, ActView a_av, WeightSeg w, int M, int N, int K,
                        float *slabs, size_t slabs_floats, int force_splits, hipError_t *err, int extra_slabs = 0,
-                       LmStats ls = {nullptr, 0.f}, int *ls_done = nullptr)
+                       LmStats ls = {nullptr, 0.f}, int *ls_done = nullptr, NormFold nf = kNoFold)
 {
     if (ls_done) *ls_done = 0;
     *err = hipSuccess;
@@ -723,7 +733,7 @@ static int stream_gemm(sd_model *m, hipStream_t s, const void *A, ActView a_av, 
     if ((size_t)(ns + extra_slabs) * M * N > slabs_floats) return 0;
     const ActView none = {0, 0, 0};
     hipError_t e = launch_gemm_skinny_bf16(s, GEMM_STORE, A, a_av, w, M, N, K, slabs, (size_t)M * N, ns, nullptr, none,
-                                           ls, ls_done);
+                                           ls, ls_done, nf);
     if (e == hipErrorNotSupported) return 0;
     *err = e;
     return ns;
@@ -769,6 +779,16 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
     int kv_upper = std::min(c->len_upper + SD_MAX_GAMMA + 1, c->max_cap);
     size_t lstride = (size_t)d * c->total_cap * m->esz;
     hipError_t ge;
+    // Few rows (the verify pass of a few sequences, draft tokens): the two add + RMSNorm launches of a layer are
+    // split between the projection before them and the GEMM after them (NormFold) - seven dependent launches
+    // per layer become five.  Needs every GEMM of the forward on the few-row kernels.
+    const bool fold = cf.dtype == SD_BF16 && !(g_force_generic & (1 | 16)) && g_norm_fold != 2 && G == 1 && M <= 32 &&
+                      m->lora_n == 0 && m->tiled_dd && m->tiled_fd && m->tiled_df && (!want_logits || m->tiled_lm) &&
+                      d % 128 == 0 && F % 128 == 0 && V % 16 == 0 && d / 16 <= SD_NORMFOLD_MAX_BLOCKS &&
+                      cf.n_layers >= 1 && (g_norm_fold == 1 || m->stream_nt);
+    const int fold_nb = gemm_normfold_blocks(d);
+    const NormFold nf_consume = {m->ss_part, fold_nb, cf.rms_eps, nullptr, nullptr, nullptr, nullptr};
+    bool a_scaled = false; // abuf holds rows scaled by the gains only; their sums of squares are in ss_part
     if (!plan_ready) { ProfScope ps(T_PLAN, s); // (the draft sampler lays out the single-row forwards that follow it)
     if (G > 1) FWD(launch_plan_prefill(s, R, G, n_seq, seq_ids, cv, slot, upto_off, V, pv));
     else FWD(launch_plan(s, mode, R, n_seq, seq_ids, cv, slot, upto_off, cand, gamma, cand_idx, V, pv)); }
@@ -777,7 +797,7 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
     int pending = 0; // split-K slabs of the previous down projection not yet added to x
     for (int l = 0; l < cf.n_layers; l++) {
         void *Kl = (char *)c->kcache[slot] + l * lstride, *Vtl = (char *)c->vcache[slot] + l * lstride;
-        if (l > 0) { ProfScope ps(T_RMSNORM, s);
+        if (l > 0 && !fold) { ProfScope ps(T_RMSNORM, s);
         if (pending)
             FWD(launch_add_rmsnorm(s, cf.dtype, m->x, m->gpart_r, pending, (size_t)M * d, m->norm_attn[l], nullptr, M, d,
                                    cf.rms_eps, m->abuf, avd));
@@ -794,9 +814,11 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
         const bool lora_o = m->lora_n > 0 && m->lora_a[3][l];
         bool qkv_in_place = false;
         { ProfScope ps(T_QKV, s);
-        nq_slabs = stream_gemm(m, s, m->abuf, avd, wqkv, M, 3 * d, d, m->gpart_q, m->gpart_q_floats, 0, &ge, lora_qkv ? 1 : 0);
+        nq_slabs = stream_gemm(m, s, m->abuf, avd, wqkv, M, 3 * d, d, m->gpart_q, m->gpart_q_floats, 0, &ge, lora_qkv ? 1 : 0,
+                               LmStats{nullptr, 0.f}, nullptr, a_scaled ? nf_consume : kNoFold);
         FWD(ge);
         qkv_src = m->gpart_q;
+        if (!nq_slabs && fold) return sd_fail(SD_EHIP, "forward: QKV shape left the few-row kernels under the split norm");
         if (!nq_slabs) {
             FWD(gemm_generic(m, s, GEMM_STORE, m->abuf, avd, wqkv, M, 3 * d, d, m->qkv, nullptr, av0));
             nq_slabs = 1;
@@ -817,7 +839,7 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
         // rows must all be in the cache before any slot's attention starts
         if (cf.dtype == SD_BF16 && !(g_force_generic & 2) && G == 1) {
             ProfScope ps(T_ATTN, s);
-            const bool try_oproj = !lora_o && m->tiled_dd && !(g_force_generic & (1 | 8));
+            const bool try_oproj = !fold && !lora_o && m->tiled_dd && !(g_force_generic & (1 | 8));
             ea = launch_attn_fused_bf16(s, qkv_src, nq_slabs, (size_t)M * 3 * d, pv, cv, R, n_seq, H, hd, m->rope,
                                         cf.max_pos, Kl, Vtl, c->total_cap, kv_upper, m->obuf, avd, m->stream_nt,
                                         try_oproj ? m->wo[l] : nullptr, d, m->gpart_r, m->gpart_r_floats, &oproj_done);
@@ -841,7 +863,13 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
         FWD(ea);
         WeightSeg wo = {{m->wo[l], nullptr, nullptr}, d, m->tiled_dd, m->stream_nt};
         int no_slabs = H;
-        if (!oproj_done) { ProfScope ps(T_OPROJ, s);
+        if (fold) { ProfScope ps(T_OPROJ, s); // projection + residual + the gains of the norm that follows
+            const NormFold nf_p = {nullptr, 0, 0.f, m->x, m->norm_ffn[l], m->ss_part, nullptr};
+            const hipError_t eo = launch_gemm_skinny_bf16(s, GEMM_STORE, m->obuf, avd, wo, M, d, d, nullptr, 0, 1, m->abuf, avd,
+                                                          LmStats{nullptr, 0.f}, nullptr, nf_p);
+            FWD(eo);
+            a_scaled = true;
+        } else if (!oproj_done) { ProfScope ps(T_OPROJ, s);
         no_slabs = stream_gemm(m, s, m->obuf, avd, wo, M, d, d, m->gpart_r, m->gpart_r_floats, 0, &ge, lora_o ? 1 : 0);
         FWD(ge);
         if (!no_slabs) FWD(gemm_generic(m, s, GEMM_RESID, m->obuf, avd, wo, M, d, d, m->x, nullptr, av0)); }
@@ -852,7 +880,7 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
                                   m->lora_rank, m->lora_scale, A1, B1, dst, no_slabs ? 0 : 1));
             if (no_slabs) no_slabs++;
         }
-        { ProfScope ps(T_RMSNORM, s);
+        if (!fold) { ProfScope ps(T_RMSNORM, s);
         if (no_slabs)
             FWD(launch_add_rmsnorm(s, cf.dtype, m->x, m->gpart_r, no_slabs, (size_t)M * d, m->norm_ffn[l], nullptr, M, d,
                                    cf.rms_eps, m->abuf, avd));
@@ -864,21 +892,30 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
         hipError_t eg = hipErrorNotSupported;
         if (cf.dtype == SD_BF16 && !(g_force_generic & 1))
             eg = launch_gemm_skinny_bf16(s, GEMM_SWIGLU, m->abuf, avd, wgu, M, F, d, nullptr, 0, 1, m->act,
-                                         avf);
+                                         avf, LmStats{nullptr, 0.f}, nullptr, a_scaled ? nf_consume : kNoFold);
+        if (eg == hipErrorNotSupported && fold)
+            return sd_fail(SD_EHIP, "forward: gate/up shape left the few-row kernels under the split norm");
         if (eg == hipErrorNotSupported)
             eg = gemm_generic(m, s, GEMM_SWIGLU, m->abuf, avd, wgu, M, F, d, nullptr, m->act, avf);
         FWD(eg); }
         WeightSeg wd = {{m->wdown[l], nullptr, nullptr}, d, m->tiled_df, m->stream_nt};
-        { ProfScope ps(T_DOWN, s);
+        if (fold) { ProfScope ps(T_DOWN, s); // projection + residual + the gains of the next layer's (or the final) norm
+            const float *g_next = l + 1 < cf.n_layers ? m->norm_attn[l + 1] : m->final_norm;
+            const NormFold nf_p = {nullptr, 0, 0.f, m->x, g_next, m->ss_part, nullptr};
+            const hipError_t ed = launch_gemm_skinny_bf16(s, GEMM_STORE, m->act, avf, wd, M, d, F, nullptr, 0, 1, m->abuf, avd,
+                                                          LmStats{nullptr, 0.f}, nullptr, nf_p);
+            FWD(ed);
+            pending = 0;
+        } else { ProfScope ps(T_DOWN, s);
         pending = stream_gemm(m, s, m->act, avf, wd, M, d, F, m->gpart_r, m->gpart_r_floats, 0, &ge);
         FWD(ge);
         if (!pending) FWD(gemm_generic(m, s, GEMM_RESID, m->act, avf, wd, M, d, F, m->x, nullptr, av0)); }
     }
     if (want_logits) {
         int n_lm = mode == PLAN_VERIFY ? M : n_seq;
-        const ActView avlm = {m->plane_d, n_lm, sm_d};
-        m->last_a_rows = n_lm;
-        { ProfScope ps(T_RMSNORM, s);
+        const ActView avlm = fold ? avd : ActView{m->plane_d, n_lm, sm_d}; // (split norm: the rows stay where the last down projection put them)
+        m->last_a_rows = fold ? M : n_lm;
+        if (!fold) { ProfScope ps(T_RMSNORM, s);
         if (pending)
             FWD(launch_add_rmsnorm(s, cf.dtype, m->x, m->gpart_r, pending, (size_t)M * d, m->final_norm, pv.lm_row, n_lm,
                                    d, cf.rms_eps, m->abuf, avlm));
@@ -889,8 +926,14 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
         { ProfScope ps(T_LMHEAD, s);
         const LmStats ls = {lm_invT >= 0.f && V % 32 == 0 ? m->lm_stats : nullptr, lm_invT >= 0.f ? lm_invT : 0.f};
         int ls_done = 0;
-        int nl = stream_gemm(m, s, m->abuf, avlm, wl, n_lm, V, d, m->logits, (size_t)cf.max_rows * V, 1, &ge, 0, ls, &ls_done);
+        NormFold nf_lm = kNoFold;
+        if (fold) { // (a_scaled: there is at least one layer)
+            nf_lm = nf_consume;
+            nf_lm.row_map = pv.lm_row;
+        }
+        int nl = stream_gemm(m, s, m->abuf, avlm, wl, n_lm, V, d, m->logits, (size_t)cf.max_rows * V, 1, &ge, 0, ls, &ls_done, nf_lm);
         FWD(ge);
+        if (!nl && fold) return sd_fail(SD_EHIP, "forward: LM head shape left the few-row kernels under the split norm");
         m->lm_stats_nb = nl && ls_done ? V / 32 : 0;
         if (!nl) FWD(gemm_generic(m, s, GEMM_STORE, m->abuf, avlm, wl, n_lm, V, d, m->logits, nullptr, av0)); }
         m->last_lm_rows = n_lm;

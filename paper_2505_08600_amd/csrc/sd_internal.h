@@ -222,6 +222,24 @@ __host__ __device__ __forceinline__ size_t weight_index(int n, int k, int K, int
 
 enum GemmMode { GEMM_STORE = 0, GEMM_RESID = 1, GEMM_SWIGLU = 2 };
 
+// RMSNorm split between the GEMM that produces a residual update and the GEMM that consumes the normed rows
+// (few-row kernels), so that no launch of its own stands between them.  Producer (GEMM_STORE without K split,
+// one block per group of output columns): x[m][n] += result; the operand buffer of the next GEMM receives
+// hi + lo of x[m][n] * g[n] - scaled by the gains but not yet by 1 / rms, which needs the whole row - and
+// ss_out[m * SD_NORMFOLD_MAX_BLOCKS + block] the block's share of sum_n x[m][n]^2.  Consumer: multiplies row m of
+// its sums by 1 / sqrt(sum_b ss_in[m * SD_NORMFOLD_MAX_BLOCKS + b] / K + eps).  The scaling commutes with the product; what moves is the
+// point where the operand is rounded to its two bf16 terms (before instead of after the division by rms).
+struct NormFold {
+    const float *ss_in;     // consumer: per-block sums of squares of the producer, [32][SD_NORMFOLD_MAX_BLOCKS] (nullptr: operand is already normed)
+    int32_t ss_nb;
+    float eps;
+    float *x;               // producer: residual rows [M][N], updated in place (nullptr: plain store)
+    const float *g;         // producer: gains of the norm that follows, [N]
+    float *ss_out;          // producer: [32][SD_NORMFOLD_MAX_BLOCKS], entry [m][block index]
+    const int32_t *row_map; // operand row (and row of ss_in) of output row m (nullptr: m)
+};
+#define SD_NORMFOLD_MAX_BLOCKS 512
+
 // Softmax partials the few-row GEMM can leave beside an LM head's logits, so that the draft sampler needs no pass
 // over the whole row before it can place its uniform: for logits row m and block b (32 consecutive columns)
 // p[(m * n_blocks + b) * 3 + {0, 1, 2}] = max, sum of exp((x - max) * invT) (0 when invT is 0: greedy), and the
@@ -258,6 +276,7 @@ struct sd_model {
     size_t plane_d, plane_f; // element offsets between the planes
     float *logits;  // [max_rows][vocab]
     float *vstats;  // [max_rows][3] per-row (max, sum of exponentials, argmax) of the verify tail
+    float *ss_part;  // [32][SD_NORMFOLD_MAX_BLOCKS] per-block sums of squares between a producer and its consumer (see NormFold)
     float *lm_stats; // [max_rows][vocab / 32][3] per-block softmax partials of the last LM head (see LmStats)
     int lm_stats_nb; // blocks per row the last forward's LM head left there (0: none)
     float *part;    // split-KV partial results of the attention kernel
@@ -372,11 +391,15 @@ hipError_t launch_stream_read(hipStream_t s, const void *buf, size_t bytes, uint
 // GEMM_STORE: C receives `splits` partial slabs (slab stride c_split_stride floats) that the consumer adds;
 // GEMM_SWIGLU: Cact receives the bf16 hi/lo planes.  gemm_skinny_splits tells how many slabs to expect.
 int gemm_skinny_splits(int mode, int M, int N, int K, int n_per_seg);
+int gemm_normfold_blocks(int N); // blocks of a NormFold producer launch with N output columns
 // ls: softmax partials wanted beside the result (GEMM_STORE without K splits only); *ls_done tells whether the
 // kernel chosen for the shape wrote them.
+// nf: norm split between producer and consumer (few-row kernels only: the launcher returns
+// hipErrorNotSupported for a shape it would send to the row-blocked kernel).
 hipError_t launch_gemm_skinny_bf16(hipStream_t s, int mode, const void *A, ActView a_av, WeightSeg w, int M, int N,
                                    int K, float *C, size_t c_split_stride, int splits, void *Cact, ActView c_av,
-                                   LmStats ls = {nullptr, 0.f}, int *ls_done = nullptr);
+                                   LmStats ls = {nullptr, 0.f}, int *ls_done = nullptr,
+                                   NormFold nf = {nullptr, 0, 0.f, nullptr, nullptr, nullptr, nullptr});
 hipError_t launch_add_rmsnorm(hipStream_t s, int dtype, float *x, const float *part, int n_slabs, size_t slab_stride,
                               const float *g, const int32_t *row_map, int n_rows, int d, float eps, void *out,
                               ActView out_av);

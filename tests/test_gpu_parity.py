@@ -263,6 +263,65 @@ def test_small_bf16_both_fused_attention_block_shapes_match_reference_kernels(wa
     gt.close()
 
 
+@pytest.mark.parametrize("T,plen,gamma", [(0.0, 70, 5), (1.0, 70, 5), (1.0, 300, 4), (0.0, 33, 7)])
+def test_small_bf16_norm_split_between_its_neighbour_gemms_matches_oracle(T, plen, gamma):
+    """With few rows the add + RMSNorm launches of a layer can be split between the projection before them (which
+    adds the residual, applies the gains and leaves per-block sums of squares) and the GEMM after them (which
+    scales its sums by 1 / rms): the operand is then rounded to its two bf16 terms before the division by rms
+    instead of after it.  The library does this by itself for models whose weights are streamed; option
+    norm_fold = 1 forces it here, and the same oracle comparison as for the default path must hold, with the same
+    limits (target and draft both take the path, draft rows included: 1-2 rows, LM head through a row map)."""
+    _say(f"small bf16, split norm, T={T} prompt={plen} gamma={gamma}")
+    st_, sd_ = dg.SHAPES["small_target_bf16"], dg.SHAPES["small_draft_bf16"]
+    pair = H.Pair(st_, sd_, seed=61, lm_scale=BF16_LM_SCALE, max_rows=32, max_pos=512)
+    prompt = dg.make_prompt(61, plen, plen, st_.vocab)
+    api.set_option("norm_fold", 1)
+    try:
+        st = H.teacher_forced_parity(pair, prompt, gamma=gamma, T=T, n_tokens=40, seed=61 + plen)
+    finally:
+        api.set_option("norm_fold", 0)
+    _say(f"  steps={st.steps} flagged={st.flagged} logit_rel={st.max_logit_rel:.2e} q_abs={st.max_q_abs:.2e}")
+    assert st.flagged <= H.flag_cap(st.steps) and st.max_logit_rel < 2e-2
+    pair.close()
+
+
+@pytest.mark.parametrize("shape_name,B", [("small_target_bf16", 1), ("small_target_bf16", 5), ("small_draft_bf16", 3),
+                                          ("draft_a_1layer", 1)])
+def test_norm_split_between_its_neighbour_gemms_matches_the_norm_launches(shape_name, B):
+    """The same forward with the split norm forced on and forced off (options norm_fold = 1 / 2): the logits differ
+    by the rounding of the operand at another point only - a few 1e-5 of their range at these widths, four orders
+    of magnitude inside the tolerance; 1 to 30 rows (packed, 16- and 32-row kernels)."""
+    import dataclasses
+    _say(f"{shape_name}: split norm vs norm launches, batch {B}")
+    st_ = (dataclasses.replace(dg.SHAPES["draft_a"], n_layers=1, vocab=2048, name="draft_a_1layer")
+           if shape_name == "draft_a_1layer" else dg.SHAPES[shape_name])
+    w = dg.make_weights(st_, 81, BF16_LM_SCALE)
+    gt = api.Model(st_, w, max_rows=max(16, 6 * B), max_pos=256)
+    lens = dg.make_prompt_lengths(81 + B, B, 5, 150)
+    prompts = [[int(t) for t in dg.make_prompt(81, b, int(lens[b]), st_.vocab)] for b in range(B)]
+    cand = H.dev(dg.make_prompt(82, B, 5 * B, st_.vocab).reshape(B, 5).astype(np.int32))
+    outs = []
+    for opt in (2, 1):
+        api.set_option("norm_fold", opt)
+        try:
+            ctx = api.Context([int(l) + 16 for l in lens])
+            ctx.attach(gt)
+            H.gpu_prefill(ctx, [gt], prompts)
+            na = torch.zeros(B, dtype=torch.int32, device="cuda")
+            nx = torch.zeros(B, dtype=torch.int32, device="cuda")
+            api.sd_verify(gt, ctx, None, B, 5, 0.0, cand, None, None, na, nx, commit=False)
+            ctx.sync()
+            outs.append(gt.last_logits().cpu().numpy())
+            ctx.close()
+        finally:
+            api.set_option("norm_fold", 0)
+    rel = np.abs(outs[0] - outs[1]).max() / np.abs(outs[0]).max()
+    _say(f"  rel diff {rel:.2e}")
+    assert np.isfinite(outs[1]).all() and rel < 2e-4
+    assert not np.array_equal(outs[0], outs[1]), "the option did not change the path"
+    gt.close()
+
+
 @pytest.mark.parametrize("shape_name,B", [("small_target_bf16", 1), ("small_target_bf16", 5), ("small_draft_bf16", 3),
                                           ("draft_a_1layer", 1), ("draft_a_1layer", 2)])
 def test_attention_blocks_applying_the_output_projection_match_the_separate_launch(shape_name, B):
