@@ -389,8 +389,8 @@ int sd_debug_stream_read(const void *buf, size_t bytes, uint32_t *scratch_word, 
  * layer can be split between the projection before them (adds the residual, applies the gains,
  * leaves per-block sums of squares) and the GEMM after them (scales its sums by 1 / rms); the
  * operand is then rounded to its two bf16 terms before the division by rms instead of after.
- * 0 = automatic (models whose weights exceed the memory-side cache), 1 = wherever the shapes
- * allow, 2 = never.
+ * 0 or 1 = wherever the shapes allow (bf16, no adapters loaded, widths multiples of 128: the
+ * default), 2 = never.
  * option "attn_waves" = 4 or 8 forces the block shape of the fused attention kernel
  * (0 = automatic: 4-wave blocks when (sequence, head) pairs oversubscribe the chip and
  * contexts are short).

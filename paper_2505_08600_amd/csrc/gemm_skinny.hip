@@ -400,6 +400,27 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_ksplit_kernel(const uint16_t 
 #pragma unroll
     for (int u = 0; u < U; u++)
         if (s_begin + wave + u * WAVES < s_end) issue(s_begin + wave + u * WAVES, u);
+    // The wave's rows of 1 / rms: summed once its first K step has been consumed - the small loads went out
+    // before that step's and have therefore arrived - so that nothing of it is left for the block's tail.
+    bool ss_pending = nf.ss_in != nullptr;
+    auto ss_reduce = [&]() {
+#pragma unroll
+        for (int r = 0; r < SSR; r++) {
+            float a = 0.f;
+#pragma unroll
+            for (int i = 0; i < SSB; i++) {
+                const int b = 4 * (lane + 64 * i);
+                a += b < nf.ss_nb ? ssl[r][i].x : 0.f;
+                a += b + 1 < nf.ss_nb ? ssl[r][i].y : 0.f;
+                a += b + 2 < nf.ss_nb ? ssl[r][i].z : 0.f;
+                a += b + 3 < nf.ss_nb ? ssl[r][i].w : 0.f;
+            }
+            a = wave_sum_dpp(a);
+            const int m = wave + r * WAVES;
+            if (lane == 0 && m < ROWS_MAX) s_inv[m] = 1.0f / sqrtf(a / (float)K + nf.eps);
+        }
+        ss_pending = false;
+    };
     for (int s = s_begin + wave; s < s_end; s += U * WAVES) {
 #pragma unroll
         for (int u = 0; u < U; u++) {
@@ -416,6 +437,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_ksplit_kernel(const uint16_t 
                                 acc[c][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv[u][c][i], al[u][t][i], acc[c][t], 0, 0, 0);
                         }
                 if (cur + U * WAVES < s_end) issue(cur + U * WAVES, u);
+                if (u == 0 && ss_pending) ss_reduce(); // (uniform; true in the first round only)
             }
         }
     }
@@ -425,24 +447,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_ksplit_kernel(const uint16_t 
         for (int t = 0; t < MT; t++)
 #pragma unroll
             for (int r = 0; r < 4; r++) red[wave][c][t][lane][r] = acc[c][t][r];
-    if (nf.ss_in) {
-#pragma unroll
-        for (int r = 0; r < SSR; r++) {
-            float a = 0.f;
-#pragma unroll
-            for (int i = 0; i < SSB; i++) {
-                const int b = 4 * (lane + 64 * i);
-                a += b < nf.ss_nb ? ssl[r][i].x : 0.f;
-                a += b + 1 < nf.ss_nb ? ssl[r][i].y : 0.f;
-                a += b + 2 < nf.ss_nb ? ssl[r][i].z : 0.f;
-                a += b + 3 < nf.ss_nb ? ssl[r][i].w : 0.f;
-            }
-#pragma unroll
-            for (int o = 32; o > 0; o >>= 1) a += __shfl_xor(a, o, 64);
-            const int m = wave + r * WAVES;
-            if (lane == 0 && m < ROWS_MAX) s_inv[m] = 1.0f / sqrtf(a / (float)K + nf.eps);
-        }
-    }
+    if (ss_pending) ss_reduce(); // (a wave without a K step of its own)
     __syncthreads();
     // tile element D[n = 4*(slot/16) + r][m' = slot%16] sits at red[.][c][t][slot][r]
     constexpr int ROWS = PACKED ? 8 : 16 * MT;
@@ -475,9 +480,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_ksplit_kernel(const uint16_t 
             const size_t o = act_index(c_av, m, n, N);
             Cact[o] = hi;
             Cact[c_av.plane + o] = bf16_bits_rne(y - __uint_as_float((uint32_t)hi << 16));
-            float sq = xn * xn; // the block's 16 * NTW columns of row m sit in adjacent lanes
-#pragma unroll
-            for (int o2 = 8 * NTW; o2 > 0; o2 >>= 1) sq += __shfl_xor(sq, o2, 64);
+            float sq = row16_sum(xn * xn); // the block's 16 * NTW columns of row m sit in adjacent lanes
+            if (NTW == 2) sq += __shfl_xor(sq, 16, 64);
             if ((e & (16 * NTW - 1)) == 0) nf.ss_out[m * SD_NORMFOLD_MAX_BLOCKS + blockIdx.x] = sq;
             continue;
         }

@@ -30,21 +30,6 @@ __device__ __forceinline__ float wave_max(float v)
 // for LDS traffic only, so that global stores issued before a reduction (the updated residual row, the q
 // row a sampler has just written) drain behind it instead of stalling its first barrier.
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
-template <int CTRL> __device__ __forceinline__ int dpp_i(int v) { return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true); }
-template <int CTRL> __device__ __forceinline__ float dpp_f(float v) { return __int_as_float(dpp_i<CTRL>(__float_as_int(v))); }
-__device__ __forceinline__ float lane_f(float v, int l) { return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l)); }
-// DPP controls: quad_perm [1,0,3,2] = 0xB1, [2,3,0,1] = 0x4E; row_half_mirror = 0x141; row_mirror = 0x140;
-// row_shr:n = 0x110 + n (lanes without a source read 0).
-// Sum over each 16-lane row, left in every lane of the row (both sides of each exchange add the same two
-// numbers, so all lanes agree bit for bit).
-__device__ __forceinline__ float row16_sum(float v)
-{
-    v += dpp_f<0xB1>(v);
-    v += dpp_f<0x4E>(v);
-    v += dpp_f<0x141>(v);
-    v += dpp_f<0x140>(v);
-    return v;
-}
 __device__ __forceinline__ int row16_max(int v)
 {
     v = max(v, dpp_i<0xB1>(v));
@@ -67,11 +52,6 @@ __device__ __forceinline__ void row16_argmax(float &v, int &i)
     take_better(v, i, dpp_f<0x4E>(v), dpp_i<0x4E>(i));
     take_better(v, i, dpp_f<0x141>(v), dpp_i<0x141>(i));
     take_better(v, i, dpp_f<0x140>(v), dpp_i<0x140>(i));
-}
-__device__ __forceinline__ float wave_sum_dpp(float v)
-{
-    v = row16_sum(v);
-    return (lane_f(v, 0) + lane_f(v, 16)) + (lane_f(v, 32) + lane_f(v, 48));
 }
 // Inclusive prefix sum over the 64 lanes: four shifted adds inside each row, then the totals of the rows before.
 __device__ __forceinline__ float wave_incl_scan_dpp(float v, int lane)

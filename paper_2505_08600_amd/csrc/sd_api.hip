@@ -111,8 +111,8 @@ extern "C" int sd_set_option(const char *name, int32_t value)
         g_force_tile_cols = value;
         return SD_OK;
     }
-    if (!strcmp(name, "norm_fold")) { // add + RMSNorm split between producer and consumer GEMM: 0 = automatic (models whose
-                                      // weights are streamed), 1 = wherever the shapes allow, 2 = never
+    if (!strcmp(name, "norm_fold")) { // add + RMSNorm split between producer and consumer GEMM: 0 or 1 = wherever the shapes
+                                      // allow (the default), 2 = never
         if (value < 0 || value > 2) return sd_fail(SD_EINVAL, "sd_set_option: norm_fold is 0, 1 or 2");
         g_norm_fold = value;
         return SD_OK;
@@ -281,7 +281,10 @@ extern "C" int sd_load_model(const sd_model_config *cfg, const sd_weights *w, sd
     m->plane_f = M * (size_t)c.d_ffn;
     alloc((void **)&m->x, M * d * 4);
     const size_t act_pad = (size_t)SD_ACT_PAD_ROWS * 128 * m->esz; // slack read (never used) by the row-blocked GEMM
-    alloc(&m->abuf, planes * M * d * m->esz + act_pad);
+    // (the per-block sums of squares of a split norm sit behind the operand rows their consumer reads anyway: the
+    // same pages)
+    const size_t abuf_bytes = (planes * M * d * m->esz + act_pad + 255) & ~(size_t)255;
+    alloc(&m->abuf, abuf_bytes + (size_t)SD_NORMFOLD_MAX_BLOCKS * 32 * sizeof(float));
     alloc((void **)&m->qkv, M * 3 * d * 4);
     alloc(&m->qbuf, planes * M * d * m->esz + act_pad);
     alloc(&m->obuf, planes * M * d * m->esz + act_pad);
@@ -289,7 +292,7 @@ extern "C" int sd_load_model(const sd_model_config *cfg, const sd_weights *w, sd
     alloc((void **)&m->logits, M * (size_t)c.vocab * 4);
     alloc((void **)&m->vstats, M * 3 * sizeof(float));
     alloc((void **)&m->lm_stats, M * (size_t)(c.vocab / 32 + 1) * 3 * sizeof(float));
-    alloc((void **)&m->ss_part, (size_t)SD_NORMFOLD_MAX_BLOCKS * 32 * sizeof(float));
+    m->ss_part = e == hipSuccess ? (float *)((char *)m->abuf + abuf_bytes) : nullptr;
     m->lm_stats_nb = 0;
     alloc((void **)&m->part, m->part_floats * 4);
     m->gpart_q_floats = 8 * M * 3 * d;
@@ -342,7 +345,6 @@ extern "C" int sd_free_model(sd_model *m)
     (void)hipFree(m->logits);
     (void)hipFree(m->vstats);
     (void)hipFree(m->lm_stats);
-    (void)hipFree(m->ss_part);
     (void)hipFree(m->part);
     (void)hipFree(m->gpart_q);
     (void)hipFree(m->gpart_r);
@@ -785,7 +787,7 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
     const bool fold = cf.dtype == SD_BF16 && !(g_force_generic & (1 | 16)) && g_norm_fold != 2 && G == 1 && M <= 32 &&
                       m->lora_n == 0 && m->tiled_dd && m->tiled_fd && m->tiled_df && (!want_logits || m->tiled_lm) &&
                       d % 128 == 0 && F % 128 == 0 && V % 16 == 0 && d / 16 <= SD_NORMFOLD_MAX_BLOCKS &&
-                      cf.n_layers >= 1 && (g_norm_fold == 1 || m->stream_nt);
+                      cf.n_layers >= 1;
     const int fold_nb = gemm_normfold_blocks(d);
     const NormFold nf_consume = {m->ss_part, fold_nb, cf.rms_eps, nullptr, nullptr, nullptr, nullptr};
     bool a_scaled = false; // abuf holds rows scaled by the gains only; their sums of squares are in ss_part

@@ -123,6 +123,28 @@ __host__ __device__ __forceinline__ size_t kt_offset(int hd, int64_t t, int d)
     return (size_t)(t >> 5) * (size_t)(32 * hd) + (size_t)(((((d >> 5) * 2 + ab) * G + ((d >> 3) & 3)) * 16 + i) * 8 + (d & 7));
 }
 
+// ---------------------------------------------------------------- cross-lane helpers (DPP: the vector ALU's own data path)
+template <int CTRL> __device__ __forceinline__ int dpp_i(int v) { return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true); }
+template <int CTRL> __device__ __forceinline__ float dpp_f(float v) { return __int_as_float(dpp_i<CTRL>(__float_as_int(v))); }
+__device__ __forceinline__ float lane_f(float v, int l) { return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l)); }
+// DPP controls: quad_perm [1,0,3,2] = 0xB1, [2,3,0,1] = 0x4E; row_half_mirror = 0x141; row_mirror = 0x140;
+// row_shr:n = 0x110 + n (lanes without a source read 0).
+// Sum over each 16-lane row, left in every lane of the row (both sides of each exchange add the same two
+// numbers, so all lanes agree bit for bit).
+__device__ __forceinline__ float row16_sum(float v)
+{
+    v += dpp_f<0xB1>(v);
+    v += dpp_f<0x4E>(v);
+    v += dpp_f<0x141>(v);
+    v += dpp_f<0x140>(v);
+    return v;
+}
+__device__ __forceinline__ float wave_sum_dpp(float v)
+{
+    v = row16_sum(v);
+    return (lane_f(v, 0) + lane_f(v, 16)) + (lane_f(v, 32) + lane_f(v, 48));
+}
+
 // ---------------------------------------------------------------- views passed to kernels
 // Device-side view of a context.  kvlen is [SD_MAX_SLOTS][B].
 struct CtxView {

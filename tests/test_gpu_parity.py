@@ -268,27 +268,28 @@ def test_small_bf16_norm_split_between_its_neighbour_gemms_matches_oracle(T, ple
     """With few rows the add + RMSNorm launches of a layer can be split between the projection before them (which
     adds the residual, applies the gains and leaves per-block sums of squares) and the GEMM after them (which
     scales its sums by 1 / rms): the operand is then rounded to its two bf16 terms before the division by rms
-    instead of after it.  The library does this by itself for models whose weights are streamed; option
-    norm_fold = 1 forces it here, and the same oracle comparison as for the default path must hold, with the same
-    limits (target and draft both take the path, draft rows included: 1-2 rows, LM head through a row map)."""
+    instead of after it.  This is the library's default where the shapes allow; option norm_fold = 2 switches it
+    off, and the same oracle comparison must hold both ways, with the same limits (target and draft both take
+    the path, draft rows included: 1-2 rows, LM head through a row map)."""
     _say(f"small bf16, split norm, T={T} prompt={plen} gamma={gamma}")
     st_, sd_ = dg.SHAPES["small_target_bf16"], dg.SHAPES["small_draft_bf16"]
     pair = H.Pair(st_, sd_, seed=61, lm_scale=BF16_LM_SCALE, max_rows=32, max_pos=512)
     prompt = dg.make_prompt(61, plen, plen, st_.vocab)
-    api.set_option("norm_fold", 1)
-    try:
-        st = H.teacher_forced_parity(pair, prompt, gamma=gamma, T=T, n_tokens=40, seed=61 + plen)
-    finally:
-        api.set_option("norm_fold", 0)
-    _say(f"  steps={st.steps} flagged={st.flagged} logit_rel={st.max_logit_rel:.2e} q_abs={st.max_q_abs:.2e}")
-    assert st.flagged <= H.flag_cap(st.steps) and st.max_logit_rel < 2e-2
+    for opt in (1, 2):
+        api.set_option("norm_fold", opt)
+        try:
+            st = H.teacher_forced_parity(pair, prompt, gamma=gamma, T=T, n_tokens=40, seed=61 + plen)
+        finally:
+            api.set_option("norm_fold", 0)
+        _say(f"  norm_fold={opt}: steps={st.steps} flagged={st.flagged} logit_rel={st.max_logit_rel:.2e} q_abs={st.max_q_abs:.2e}")
+        assert st.flagged <= H.flag_cap(st.steps) and st.max_logit_rel < 2e-2
     pair.close()
 
 
 @pytest.mark.parametrize("shape_name,B", [("small_target_bf16", 1), ("small_target_bf16", 5), ("small_draft_bf16", 3),
                                           ("draft_a_1layer", 1)])
 def test_norm_split_between_its_neighbour_gemms_matches_the_norm_launches(shape_name, B):
-    """The same forward with the split norm forced on and forced off (options norm_fold = 1 / 2): the logits differ
+    """The same forward with the split norm on (the default) and off (option norm_fold = 2): the logits differ
     by the rounding of the operand at another point only - a few 1e-5 of their range at these widths, four orders
     of magnitude inside the tolerance; 1 to 30 rows (packed, 16- and 32-row kernels)."""
     import dataclasses
@@ -341,6 +342,7 @@ def test_attention_blocks_applying_the_output_projection_match_the_separate_laun
     outs = []
     for force in (0, 8):
         api.set_option("force_generic", force)
+        api.set_option("norm_fold", 2)  # (with the split norm the projection is a launch of its own anyway)
         try:
             ctx = api.Context([int(l) + 16 for l in lens])
             ctx.attach(gt)
@@ -353,6 +355,7 @@ def test_attention_blocks_applying_the_output_projection_match_the_separate_laun
             ctx.close()
         finally:
             api.set_option("force_generic", 0)
+            api.set_option("norm_fold", 0)
     rel = np.abs(outs[0] - outs[1]).max() / np.abs(outs[1]).max()
     _say(f"  rel diff {rel:.2e}")
     assert outs[0].shape == (6 * B, st_.vocab) and np.isfinite(outs[0]).all() and rel < 2e-4
