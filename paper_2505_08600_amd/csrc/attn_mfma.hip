@@ -34,15 +34,81 @@ typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8; // explicit LDS add
 #define AT_TILE 32
 #define AT_NEG (-1.0e30f)
 
-// exp via the hardware 2^x: relative error of a few 1e-7 over the range softmax uses (arguments <= 0),
-// far below the 2^-16 of the hi/lo split the probabilities go through next; -1e30 gives exactly 0.
-__device__ __forceinline__ float fast_exp(float x) { return __builtin_amdgcn_exp2f(x * 1.44269504088896341f); }
+// Exponentials are the hardware 2^x (__builtin_amdgcn_exp2f): relative error of a few 1e-7 over the range softmax
+// uses (arguments <= 0), far below the 2^-16 of the hi/lo split the probabilities go through next; -1e30 gives
+// exactly 0.
 
 union Pack8 {
     bf16x8 v;
     uint16_t u[8];
     uint32_t w[4];
 };
+
+// Scores of one 32-token tile -> probabilities (hi + lo operand of the second product) and the running softmax
+// state of this lane's query row.  The scores arrive as S^T fragments: sa holds tokens tok0 + 0..3, sb tokens
+// tok0 + 4..7 (tok0 = tile start + 8 * k-group).  sl2 = log2(e) / sqrt(head_dim): maxima and exponents are kept in
+// the base-2 domain, p = 2^(s * sl2 - m), one multiply per score instead of two (every reader of m_run - the merges
+// below and attn_combine_kernel - uses 2^x as well).  MASKED: tokens beyond `vis` are excluded; only tiles that
+// reach into the new rows need it, and the others skip its compares and selects.  Returns the factor the
+// accumulated output has to be scaled by (1 when the maximum stood).
+// Maximum over the four 16-lane rows of a wave (lanes l, l ^ 16, l ^ 32, l ^ 48), left in every lane.  The two
+// row-swap instructions of this part exchange rows between two registers inside the vector ALU; with both
+// registers holding v, each lane ends up with its own value in one result and its partner's in the other.  (The
+// general lane shuffle goes through the LDS unit: an address computation and a round trip per step.)
+__device__ __forceinline__ float rows_max(float v)
+{
+    unsigned u = __float_as_uint(v);
+    const auto r16 = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    v = fmaxf(__uint_as_float(r16[0]), __uint_as_float(r16[1]));
+    u = __float_as_uint(v);
+    const auto r32 = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__uint_as_float(r32[0]), __uint_as_float(r32[1]));
+}
+
+template <bool MASKED>
+__device__ __forceinline__ float tile_softmax(const f32x4 &sa, const f32x4 &sb, float sl2, int tok0, int vis, float &m_run,
+                                              float &l_run, Pack8 &ph, Pack8 &pl)
+{
+    float sc[8];
+    float mx = AT_NEG;
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+        float v = (e < 4 ? sa[e] : sb[e - 4]) * sl2;
+        if (MASKED) v = tok0 + e <= vis ? v : AT_NEG;
+        sc[e] = v;
+        mx = fmaxf(mx, v);
+    }
+    mx = rows_max(mx);
+    const float m_new = fmaxf(m_run, mx);
+    const float corr = __builtin_amdgcn_exp2f(m_run - m_new); // 1 when nothing changed, 0 from the initial state
+    float psum = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; e += 2) {
+        float p0 = __builtin_amdgcn_exp2f(sc[e] - m_new), p1 = __builtin_amdgcn_exp2f(sc[e + 1] - m_new);
+        if (MASKED) { // (a row that has seen nothing yet has m_new = AT_NEG: its differences are 0, not -inf)
+            p0 = sc[e] > 0.5f * AT_NEG ? p0 : 0.f;
+            p1 = sc[e + 1] > 0.5f * AT_NEG ? p1 : 0.f;
+        }
+        psum += p0;
+        psum += p1;
+        bf16x2_split(p0, p1, ph.w[e >> 1], pl.w[e >> 1]);
+    }
+    l_run = l_run * corr + psum;
+    m_run = m_new;
+    return corr;
+}
+// acc *= corr for the ND output tiles, as a branch the compiler keeps (it turns a plain `if` over these
+// multiplies into selects that run for every tile, although the maxima settle after the first few)
+#define SD_RESCALE_IF(cond, o, ND_, corr)                  \
+    if (cond) {                                            \
+        asm volatile("" ::: "memory");                     \
+        _Pragma("unroll") for (int d_ = 0; d_ < ND_; d_++) { \
+            o[d_][0] *= corr;                              \
+            o[d_][1] *= corr;                              \
+            o[d_][2] *= corr;                              \
+            o[d_][3] *= corr;                              \
+        }                                                  \
+    }
 
 // Online-softmax pass of one wave over the KV tiles t_begin, t_begin + t_stride, ... < t_end.
 // qv/ql: hi and lo planes of the Q^T operand; vis: last visible token of this lane's query row.
@@ -57,7 +123,8 @@ __device__ __forceinline__ void attn_tiles(const uint16_t *__restrict__ K, const
     constexpr int ND = HD / 16;
     const int lane = threadIdx.x & 63;
     const int qi = lane & 15, grp = lane >> 4;
-    const float scale = 1.0f / sqrtf((float)HD);
+    const float sl2 = 1.44269504088896341f / sqrtf((float)HD);
+    const int vis0 = __builtin_amdgcn_readfirstlane(vis); // (lane 0 holds row 0: the first new position; tiles that end before it need no mask)
     // K operand rows: lane row i holds token 8*(i/4) + i%4 (tile a) or that + 4 (tile b)
     // two register buffers: the loads of the next tile are in flight while the current one is consumed
     bf16x8 ka0[NC], kb0[NC], vv0[ND], ka1[NC], kb1[NC], vv1[ND];
@@ -87,46 +154,15 @@ __device__ __forceinline__ void attn_tiles(const uint16_t *__restrict__ K, const
             sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb[c], qo, sb, 0, 0, 0);
         }
         // lane (q, grp) now holds scores of tokens t0 + 8*grp + e, e = 0..7 (sa: e<4, sb: e>=4)
-        float sc[8];
-        float mx = AT_NEG;
-#pragma unroll
-        for (int e = 0; e < 8; e++) {
-            float v = (e < 4 ? sa[e] : sb[e - 4]) * scale;
-            int tok = t0 + 8 * grp + e;
-            v = tok <= vis ? v : AT_NEG;
-            sc[e] = v;
-            mx = fmaxf(mx, v);
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run, mx);
-        const float corr = fast_exp(m_run - m_new); // 1 when nothing changed, 0 from the initial state
         Pack8 ph, pl;
-        float psum = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; e += 2) {
-            const float p0 = sc[e] > 0.5f * AT_NEG ? fast_exp(sc[e] - m_new) : 0.f;
-            const float p1 = sc[e + 1] > 0.5f * AT_NEG ? fast_exp(sc[e + 1] - m_new) : 0.f;
-            psum += p0;
-            psum += p1;
-            bf16x2_split(p0, p1, ph.w[e >> 1], pl.w[e >> 1]);
-        }
-        l_run = l_run * corr + psum;
-        m_run = m_new;
+        const float corr = t0 + AT_TILE - 1 > vis0 ? tile_softmax<true>(sa, sb, sl2, t0 + 8 * grp, vis, m_run, l_run, ph, pl)
+                                                   : tile_softmax<false>(sa, sb, sl2, t0 + 8 * grp, vis, m_run, l_run, ph, pl);
         // once the running maxima have settled corr is exactly 1 in every lane: skip the 4 * ND multiplies
-        const bool rescale = __any(corr != 1.0f);
+        SD_RESCALE_IF(__any(corr != 1.0f), o, ND, corr)
 #pragma unroll
         for (int d = 0; d < ND; d++) {
-            f32x4 acc = o[d];
-            if (rescale) {
-                acc[0] *= corr;
-                acc[1] *= corr;
-                acc[2] *= corr;
-                acc[3] *= corr;
-            }
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv[d], ph.v, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv[d], pl.v, acc, 0, 0, 0);
-            o[d] = acc;
+            o[d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv[d], ph.v, o[d], 0, 0, 0);
+            o[d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv[d], pl.v, o[d], 0, 0, 0);
         }
     };
     int t = t_begin;
@@ -207,7 +243,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restri
         float O = 0.f, L = 0.f;
 #pragma unroll
         for (int w = 0; w < AT_WAVES; w++) {
-            float f = fast_exp(sM[w][q] - M);
+            float f = __builtin_amdgcn_exp2f(sM[w][q] - M);
             O += sO[w][d][slot][r] * f;
             L += sL[w][q] * f;
         }
@@ -230,7 +266,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const uint16_t *__restri
 }
 
 // Merge the S split partials of each (sequence, head): one block per (head, sequence).
-template <int HD>
+template <int HD, int SMAX = SD_ATTN_MAX_SPLITS>
 __global__ void attn_combine_kernel(const float *__restrict__ part, PlanView pv, int R, int H, int S,
                                     uint16_t *__restrict__ obuf, ActView o_av)
 {
@@ -240,9 +276,9 @@ __global__ void attn_combine_kernel(const float *__restrict__ part, PlanView pv,
     for (int e = threadIdx.x; e < R * HD; e += blockDim.x) {
         const int q = e / HD, dim = e % HD;
         // all loads of the S (<= 32) partials are independent: issue them before the arithmetic
-        float ms[SD_ATTN_MAX_SPLITS], ls[SD_ATTN_MAX_SPLITS], os[SD_ATTN_MAX_SPLITS];
+        float ms[SMAX], ls[SMAX], os[SMAX];
 #pragma unroll
-        for (int s = 0; s < SD_ATTN_MAX_SPLITS; s++)
+        for (int s = 0; s < SMAX; s++)
             if (s < S) {
                 const float *pp = base + (size_t)s * 16 * (HD + 2);
                 ms[s] = pp[16 * HD + q];
@@ -251,13 +287,13 @@ __global__ void attn_combine_kernel(const float *__restrict__ part, PlanView pv,
             }
         float M = AT_NEG;
 #pragma unroll
-        for (int s = 0; s < SD_ATTN_MAX_SPLITS; s++)
+        for (int s = 0; s < SMAX; s++)
             if (s < S) M = fmaxf(M, ms[s]);
         float O = 0.f, L = 0.f;
 #pragma unroll
-        for (int s = 0; s < SD_ATTN_MAX_SPLITS; s++)
+        for (int s = 0; s < SMAX; s++)
             if (s < S) {
-                float f = fast_exp(ms[s] - M);
+                float f = __builtin_amdgcn_exp2f(ms[s] - M);
                 O += os[s] * f;
                 L += ls[s] * f;
             }
@@ -266,6 +302,169 @@ __global__ void attn_combine_kernel(const float *__restrict__ part, PlanView pv,
         size_t oi = act_index(o_av, j * R + q, h * HD + dim, H * HD);
         obuf[oi] = hi;
         obuf[oi + o_av.plane] = bf16_bits_rne(out - __uint_as_float((uint32_t)hi << 16));
+    }
+}
+
+// Causal attention of a prompt (prefill): WG consecutive 16-row groups of ONE sequence and head per block, one
+// group per wave.  With a block per group every group streams the whole prefix through L2 again (an 8192-token
+// prompt at head width 128: 1.1 TB per 32 layers, the ceiling of what the L2s deliver); here the block stages
+// each 32-token K / V tile in LDS once - double buffered, the loads of the next tile in flight while the
+// current one is consumed - and every wave takes its operands from there, at the offsets it would have used in
+// global memory (the tiles are stored in operand order, so the LDS reads are lane-linear), which divides the L2
+// traffic by WG and leaves a wave ~100 registers, so that several blocks share a compute unit and cover each
+// other's softmax and dependent MFMA chains.  The rows of all groups are in the cache before the launch
+// (rope_append_kernel); wave w sees tokens <= kv0_w + row.  No merge between waves: each owns its rows.  With
+// S > 1 the tile range is split over grid.z and attn_combine_kernel merges the partials (same layout as the
+// split kernel's).  Blocks start with the longest prefixes first.
+template <int HD, int WG>
+__global__ __launch_bounds__(WG * 64, 3) void attn_prefill_kernel(const uint16_t *__restrict__ qbuf, ActView q_av,
+                                                               const uint16_t *__restrict__ Kl,
+                                                               const uint16_t *__restrict__ Vtl, PlanView pv, CtxView cv,
+                                                               int R, int H, int G, int n_seq, int64_t total_cap, int S,
+                                                               float *__restrict__ part, uint16_t *__restrict__ obuf,
+                                                               ActView o_av)
+{
+    constexpr int NC = HD / 32, ND = HD / 16;
+    constexpr int TILE = AT_TILE * HD;                   // elements of one K (or V) tile
+    constexpr int NLD = (2 * TILE * 2) / (16 * WG * 64); // 16-byte pieces per thread and tile (K and V together)
+    static_assert(NLD >= 1 && NLD * 16 * WG * 64 == 2 * TILE * 2, "tile does not divide over the block");
+    __shared__ __attribute__((aligned(16))) uint16_t sKV[2][2 * TILE]; // [buffer][K tile, then V tile]
+    const int h = blockIdx.x;
+    const int n_gb = (G + WG - 1) / WG;
+    const int seq = blockIdx.y % n_seq, gb = n_gb - 1 - blockIdx.y / n_seq; // later groups (longer prefixes) first
+    const int s = blockIdx.z;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int qi = lane & 15, grp = lane >> 4;
+    const int j0 = seq * G + gb * WG;
+    const bool w_valid = gb * WG + wave < G;
+    const int j = w_valid ? j0 + wave : j0;
+    const int nq = w_valid ? pv.seq_nq[j] : 0, kv0 = pv.seq_kv0[j];
+    // the block's tile range: up to the last row of its last non-empty group
+    int lk_blk = 0;
+#pragma unroll
+    for (int w = 0; w < WG; w++)
+        if (gb * WG + w < G) {
+            const int nqw = pv.seq_nq[j0 + w];
+            if (nqw > 0) lk_blk = max(lk_blk, pv.seq_kv0[j0 + w] + nqw);
+        }
+    const int n_tiles = (lk_blk + AT_TILE - 1) / AT_TILE;
+    const int per = (n_tiles + S - 1) / S;
+    const int t_begin = s * per, t_end = min(n_tiles, t_begin + per);
+    const int64_t off = cv.off[pv.seq_b[j0]];
+    const int HDm = H * HD;
+    const uint16_t *K = Kl + ((size_t)h * total_cap + off) * HD;
+    const uint16_t *Vt = Vtl + ((size_t)h * total_cap + off) * HD;
+    // Q^T operand: lane (q, grp) holds Q[q][32*c + 8*grp .. +8]
+    bf16x8 qv[NC], ql[NC];
+    const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int c = 0; c < NC; c++) {
+        const bf16x8 *p = (const bf16x8 *)(qbuf + act_index(q_av, j * R + (qi < R ? qi : 0), h * HD + c * 32 + grp * 8, HDm));
+        qv[c] = qi < nq ? *p : zero;
+        ql[c] = qi < nq ? *(const bf16x8 *)((const uint16_t *)p + q_av.plane) : zero;
+    }
+    const int vis = kv0 + qi;             // last visible token of this lane's query row
+    const int vis_wave = nq > 0 ? kv0 + nq - 1 : -1; // ... of the wave's last row
+    const float sl2 = 1.44269504088896341f / sqrtf((float)HD);
+    float m_run = AT_NEG, l_run = 0.f;
+    f32x4 o[ND];
+#pragma unroll
+    for (int d = 0; d < ND; d++) o[d] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    // staging: piece c = threadIdx.x + k * threads of the tile pair; pieces 0 .. TILE/8-1 are K, the rest V.  Two
+    // register sets: the loads of tiles t + 1 and t + 2 are in flight while tile t is consumed (one tile ahead left
+    // every iteration waiting for most of a memory round trip)
+    bf16x8 st0[NLD], st1[NLD];
+    auto fetch = [&](int t, bf16x8 *st) {
+#pragma unroll
+        for (int k = 0; k < NLD; k++) {
+            const int c = threadIdx.x + k * (WG * 64);
+            const uint16_t *src = c < TILE / 8 ? K + (size_t)t * TILE + c * 8 : Vt + (size_t)t * TILE + (c - TILE / 8) * 8;
+            st[k] = *(const bf16x8 *)src;
+        }
+    };
+    // V^T rows are 64 bytes: the 16 lanes of one pass of a fragment read (rows qi = 0..15, one 16-byte piece each)
+    // would fall on 16 of the 64 banks, four deep.  Piece g of row r is therefore kept at position g ^ ((r >> 2) & 3)
+    // of its row, which spreads such a pass over all banks (the K tile is read lane-linear and stays as it is).
+    auto stash = [&](int b, const bf16x8 *st) {
+#pragma unroll
+        for (int k = 0; k < NLD; k++) {
+            int c = threadIdx.x + k * (WG * 64);
+            if (c >= TILE / 8) c ^= ((c - TILE / 8) >> 4) & 3; // (TILE / 8 is a multiple of 4: the XOR stays inside the row)
+            *(lds_bf16x8 *)(lds_bf16x8 *)&sKV[b][c * 8] = st[k];
+        }
+    };
+    auto consume = [&](int t, int b) {
+    if (t * AT_TILE <= vis_wave) { // (uniform over the wave) tiles past the wave's last row hold nothing it sees
+        const uint16_t *kp = &sKV[b][lane * 8];
+        const uint16_t *vp = &sKV[b][TILE + qi * AT_TILE + (grp ^ ((qi >> 2) & 3)) * 8]; // (rows 16 d + qi: same swizzle for every d)
+        f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < NC; c++) {
+            const bf16x8 ka = *(const lds_bf16x8 *)(const lds_bf16x8 *)(kp + (2 * c) * 512);
+            const bf16x8 kb = *(const lds_bf16x8 *)(const lds_bf16x8 *)(kp + (2 * c + 1) * 512);
+            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qv[c], sa, 0, 0, 0);
+            sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb, qv[c], sb, 0, 0, 0);
+            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, ql[c], sa, 0, 0, 0);
+            sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb, ql[c], sb, 0, 0, 0);
+        }
+        // lane (q, grp) holds the scores of tokens 32 t + 8 grp + e, e = 0..7 (sa: e < 4, sb: e >= 4)
+        const int t0 = t * AT_TILE;
+        Pack8 ph, pl;
+        const float corr = t0 + AT_TILE - 1 > kv0 ? tile_softmax<true>(sa, sb, sl2, t0 + 8 * grp, vis, m_run, l_run, ph, pl)
+                                                  : tile_softmax<false>(sa, sb, sl2, t0 + 8 * grp, vis, m_run, l_run, ph, pl);
+        SD_RESCALE_IF(__any(corr != 1.0f), o, ND, corr)
+#pragma unroll
+        for (int d = 0; d < ND; d++) {
+            const bf16x8 vv = *(const lds_bf16x8 *)(const lds_bf16x8 *)(vp + d * 16 * AT_TILE);
+            o[d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv, ph.v, o[d], 0, 0, 0);
+            o[d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv, pl.v, o[d], 0, 0, 0);
+        }
+    }
+    };
+    // one step: tile t sits in LDS buffer b; `nxt` holds tile t + 1 (requested earlier), `far` is free for tile t + 2
+    auto step = [&](int t, int b, bf16x8 *nxt, bf16x8 *far) {
+        fetch(min(t + 2, t_end - 1), far); // (always issued, so that the wait for `nxt` below counts exactly)
+        consume(t, b);
+        if (t + 1 < t_end) stash(b ^ 1, nxt);
+        __syncthreads(); // tile t + 1 is staged, and nobody reads buffer b any more
+    };
+    if (t_begin < t_end) {
+        fetch(t_begin, st0);
+        if (t_begin + 1 < t_end) fetch(t_begin + 1, st1);
+        stash(0, st0);
+    }
+    __syncthreads();
+    for (int t = t_begin; t < t_end; t += 2) {
+        step(t, 0, st1, st0);
+        if (t + 1 < t_end) step(t + 1, 1, st0, st1);
+    }
+    if (!w_valid) return;
+    l_run += __shfl_xor(l_run, 16, 64);
+    l_run += __shfl_xor(l_run, 32, 64);
+    // lane (q = qi, grp) holds O^T[dim = 16 d + 4 grp + r][q] in o[d][r]
+    if (qi >= R) return;
+    if (S == 1) {
+        const bool live = qi < nq && l_run > 0.f;
+#pragma unroll
+        for (int d = 0; d < ND; d++) {
+            float out[4];
+#pragma unroll
+            for (int r = 0; r < 4; r++) out[r] = live ? o[d][r] / l_run : 0.f;
+            uint32_t h0, l0, h1, l1;
+            bf16x2_split(out[0], out[1], h0, l0);
+            bf16x2_split(out[2], out[3], h1, l1);
+            const size_t oi = act_index(o_av, j * R + qi, h * HD + 16 * d + 4 * grp, HDm); // 4 columns inside one K step
+            *(uint2 *)(obuf + oi) = make_uint2(h0, h1);
+            *(uint2 *)(obuf + oi + o_av.plane) = make_uint2(l0, l1);
+        }
+    } else {
+        float *pp = part + ((size_t)(j * H + h) * S + s) * 16 * (HD + 2);
+#pragma unroll
+        for (int d = 0; d < ND; d++) *(f32x4 *)(pp + qi * HD + 16 * d + 4 * grp) = o[d];
+        if (grp == 0) {
+            pp[16 * HD + qi] = m_run;
+            pp[16 * HD + 16 + qi] = l_run;
+        }
     }
 }
 
@@ -415,7 +614,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void attn_fused_kernel(const float *
         float L = 0.f;
 #pragma unroll
         for (int w = 0; w < WAVES; w++) {
-            const float f = fast_exp(sM[w][q] - M);
+            const float f = __builtin_amdgcn_exp2f(sM[w][q] - M);
             const f32x4 p = *(const f32x4 *)&sO[w][d][slot][0];
             O += p * f;
             L += sL[w][q] * f;
@@ -553,5 +752,51 @@ hipError_t launch_attn_mfma_bf16(hipStream_t s, const void *qbuf, ActView q_av, 
     else
         hipLaunchKernelGGL(attn_combine_kernel<64>, dim3(H, n_seq), dim3(256), 0, s, part, pv, R, H, S,
                            (uint16_t *)obuf, o_av);
+    return hipGetLastError();
+}
+
+int g_prefill_attn = 1; // option "prefill_attn": 0 sends prefill forwards through the split kernel, one block set per group
+
+// Attention of a prefill forward (G > 1 groups of 16 rows per sequence; all rows already in the cache).
+hipError_t launch_attn_prefill_bf16(hipStream_t s, const void *qbuf, ActView q_av, const void *Kl, const void *Vtl,
+                                    PlanView pv, CtxView cv, int R, int n_seq, int G, int H, int hd, int64_t total_cap,
+                                    int len_upper, float *part, size_t part_floats, void *obuf, ActView o_av)
+{
+    if (!g_prefill_attn || R != 16 || G < 2 || (hd != 64 && hd != 128)) return hipErrorNotSupported;
+    constexpr int WG = 4;
+    const int n_gb = (G + WG - 1) / WG, n_slots = n_seq * G;
+    if ((long)n_seq * n_gb > 65535 || H > 65535) return hipErrorNotSupported;
+    const int tiles_upper = (len_upper + AT_TILE - 1) / AT_TILE;
+    // as many splits as keep all blocks resident at once (three per compute unit at head width 128), at least 8
+    // tiles per split, and partials that fit
+    int S = 768 / (H * n_seq * n_gb);
+    if (S > tiles_upper / 8) S = tiles_upper / 8;
+    if (S > SD_ATTN_MAX_SPLITS) S = SD_ATTN_MAX_SPLITS;
+    while (S > 1 && (size_t)n_slots * H * S * 16 * (hd + 2) > part_floats) S--;
+    if (S < 1) S = 1;
+    dim3 grid(H, n_seq * n_gb, S), block(WG * 64);
+    if (hd == 128)
+        hipLaunchKernelGGL((attn_prefill_kernel<128, WG>), grid, block, 0, s, (const uint16_t *)qbuf, q_av,
+                           (const uint16_t *)Kl, (const uint16_t *)Vtl, pv, cv, R, H, G, n_seq, total_cap, S, part,
+                           (uint16_t *)obuf, o_av);
+    else
+        hipLaunchKernelGGL((attn_prefill_kernel<64, WG>), grid, block, 0, s, (const uint16_t *)qbuf, q_av,
+                           (const uint16_t *)Kl, (const uint16_t *)Vtl, pv, cv, R, H, G, n_seq, total_cap, S, part,
+                           (uint16_t *)obuf, o_av);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || S == 1) return e;
+    // (the unrolled loops of the combine kernel cover its template's split count: a short one for the usual 2 - 4)
+    if (hd == 128 && S <= 4)
+        hipLaunchKernelGGL((attn_combine_kernel<128, 4>), dim3(H, n_slots), dim3(256), 0, s, part, pv, R, H, S, (uint16_t *)obuf,
+                           o_av);
+    else if (hd == 128)
+        hipLaunchKernelGGL((attn_combine_kernel<128>), dim3(H, n_slots), dim3(256), 0, s, part, pv, R, H, S, (uint16_t *)obuf,
+                           o_av);
+    else if (S <= 4)
+        hipLaunchKernelGGL((attn_combine_kernel<64, 4>), dim3(H, n_slots), dim3(256), 0, s, part, pv, R, H, S, (uint16_t *)obuf,
+                           o_av);
+    else
+        hipLaunchKernelGGL((attn_combine_kernel<64>), dim3(H, n_slots), dim3(256), 0, s, part, pv, R, H, S, (uint16_t *)obuf,
+                           o_av);
     return hipGetLastError();
 }

@@ -261,52 +261,56 @@ __global__ void plan_kernel(int mode, int R, int n_seq, const int32_t *seq_ids, 
 __global__ void plan_prefill_kernel(int R, int G, int n_seq, const int32_t *seq_ids, CtxView cv, int slot, int upto_off,
                                     int vocab, PlanView pv)
 {
-    for (int j = blockIdx.x * blockDim.x + threadIdx.x; j < n_seq; j += gridDim.x * blockDim.x) {
-        int b = seq_ids ? seq_ids[j] : j;
-        int total = 0, kv = 0;
-        int64_t off = 0;
-        int *kvp = nullptr;
-        if (b < 0 || b >= cv.B) { // refuse out-of-range ids: every group stays empty
-            atomicOr(cv.status, 4);
-            b = 0;
-        } else {
-            const int n = cv.ntok[b], cap = cv.cap[b];
-            kvp = cv.kvlen + (size_t)slot * cv.B + b;
-            kv = *kvp;
-            off = cv.off[b];
-            if (kv < 0) kv = 0;
-            total = (n - upto_off) - kv;
-            if (n < 1) atomicOr(cv.status, 2); // an empty sequence has nothing to feed
-            if (total < 0 || n < 1) total = 0;
-            if (kv + total > cap) { // never write beyond the sequence's cache rows
-                atomicOr(cv.status, 1);
-                total = cap - kv > 0 ? cap - kv : 0;
-            }
-            if (total > R * G) total = R * G;
+    // one block per sequence; its threads share out the (group, row) pairs
+    const int j = blockIdx.x;
+    int b = seq_ids ? seq_ids[j] : j;
+    int total = 0, kv = 0;
+    int64_t off = 0;
+    int *kvp = nullptr;
+    if (b < 0 || b >= cv.B) { // refuse out-of-range ids: every group stays empty
+        if (threadIdx.x == 0) atomicOr(cv.status, 4);
+        b = 0;
+    } else {
+        const int n = cv.ntok[b], cap = cv.cap[b];
+        kvp = cv.kvlen + (size_t)slot * cv.B + b;
+        kv = *kvp;
+        off = cv.off[b];
+        if (kv < 0) kv = 0;
+        total = (n - upto_off) - kv;
+        if (n < 1 && threadIdx.x == 0) atomicOr(cv.status, 2); // an empty sequence has nothing to feed
+        if (total < 0 || n < 1) total = 0;
+        if (kv + total > cap) { // never write beyond the sequence's cache rows
+            if (threadIdx.x == 0) atomicOr(cv.status, 1);
+            total = cap - kv > 0 ? cap - kv : 0;
         }
-        for (int g = 0; g < G; g++) {
-            const int sl = j * G + g, kv0 = kv + g * R;
-            const int nq = total - g * R < 0 ? 0 : (total - g * R > R ? R : total - g * R);
-            for (int r = 0; r < R; r++) {
-                const int row = sl * R + r, valid = r < nq;
-                int tok = 0;
-                if (valid) {
-                    tok = cv.tokens[off + kv0 + r];
-                    if (tok < 0 || tok >= vocab) { // never index the embedding table out of range
-                        atomicOr(cv.status, 16);
-                        tok = 0;
-                    }
-                }
-                pv.row_tok[row] = tok;
-                pv.row_pos[row] = kv0 + r;
-                pv.row_b[row] = b;
-                pv.row_valid[row] = valid;
+        if (total > R * G) total = R * G;
+    }
+    __syncthreads(); // every thread has read the cache length before thread 0 advances it
+    for (int i = threadIdx.x; i < G * R; i += blockDim.x) {
+        const int g = i / R, r = i % R;
+        const int sl = j * G + g, kv0 = kv + g * R;
+        const int nq = total - g * R < 0 ? 0 : (total - g * R > R ? R : total - g * R);
+        const int row = sl * R + r, valid = r < nq;
+        int tok = 0;
+        if (valid) {
+            tok = cv.tokens[off + kv0 + r];
+            if (tok < 0 || tok >= vocab) { // never index the embedding table out of range
+                atomicOr(cv.status, 16);
+                tok = 0;
             }
+        }
+        pv.row_tok[row] = tok;
+        pv.row_pos[row] = kv0 + r;
+        pv.row_b[row] = b;
+        pv.row_valid[row] = valid;
+        if (r == 0) {
             pv.seq_b[sl] = b;
             pv.seq_kv0[sl] = kv0;
             pv.seq_nq[sl] = nq;
             pv.seq_order[sl] = sl;
         }
+    }
+    if (threadIdx.x == 0) {
         pv.lm_row[j] = total > 0 ? (j * G + (total - 1) / R) * R + (total - 1) % R : j * G * R;
         if (kvp) *kvp = kv + total;
     }
@@ -315,8 +319,7 @@ __global__ void plan_prefill_kernel(int R, int G, int n_seq, const int32_t *seq_
 hipError_t launch_plan_prefill(hipStream_t s, int R, int G, int n_seq, const int32_t *seq_ids, CtxView cv, int slot,
                                int upto_off, int vocab, PlanView pv)
 {
-    int threads = PLAN_THREADS, blocks = (n_seq + threads - 1) / threads;
-    hipLaunchKernelGGL(plan_prefill_kernel, dim3(blocks), dim3(threads), 0, s, R, G, n_seq, seq_ids, cv, slot, upto_off,
+    hipLaunchKernelGGL(plan_prefill_kernel, dim3(n_seq), dim3(PLAN_THREADS), 0, s, R, G, n_seq, seq_ids, cv, slot, upto_off,
                        vocab, pv);
     return hipGetLastError();
 }

@@ -117,6 +117,12 @@ extern "C" int sd_set_option(const char *name, int32_t value)
         g_norm_fold = value;
         return SD_OK;
     }
+    if (!strcmp(name, "prefill_attn")) { // attention of prefill forwards: 1 = row groups of a prompt share staged K / V tiles
+                                         // (default), 0 = the split kernel, one set of blocks per group
+        if (value != 0 && value != 1) return sd_fail(SD_EINVAL, "sd_set_option: prefill_attn is 0 or 1");
+        g_prefill_attn = value;
+        return SD_OK;
+    }
     if (!strcmp(name, "attn_waves")) { // waves per block of the fused attention kernel: 4, 8, or 0 = automatic
         if (value != 0 && value != 4 && value != 8) return sd_fail(SD_EINVAL, "sd_set_option: attn_waves is 0, 4 or 8");
         g_force_attn_waves = value;
@@ -851,7 +857,10 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
             FWD(launch_rope_append(s, cf.dtype, qkv_src, nq_slabs, (size_t)M * 3 * d, pv, cv, M, H, hd, m->rope,
                                    cf.max_pos, m->qbuf, avd, Kl, Vtl, c->total_cap)); }
             ProfScope ps(T_ATTN, s);
-            if (cf.dtype == SD_BF16 && !(g_force_generic & 2))
+            if (cf.dtype == SD_BF16 && !(g_force_generic & 2) && G > 1) // a prompt's row groups share their K / V tiles
+                ea = launch_attn_prefill_bf16(s, m->qbuf, avd, Kl, Vtl, pv, cv, R, n_seq, G, H, hd, c->total_cap, kv_upper,
+                                              m->part, m->part_floats, m->obuf, avd);
+            if (ea == hipErrorNotSupported && cf.dtype == SD_BF16 && !(g_force_generic & 2))
                 ea = launch_attn_mfma_bf16(s, m->qbuf, avd, Kl, Vtl, pv, cv, R, n_slots, H, hd, c->total_cap,
                                            kv_upper, m->part, m->part_floats, m->obuf, avd,
                                            m->stream_nt && G == 1); // (the row groups of a prefill re-read one prefix: let it stay cached)

@@ -357,6 +357,7 @@ int sd_fail(int code, const std::string &s);
 
 extern int g_force_generic;
 extern int g_force_tile_cols;  // 96-row GEMM block width forced by option "gemm_tile_cols" (0 = automatic)
+extern int g_prefill_attn;     // option "prefill_attn": the prefill attention kernel (1, default) or the split kernel per group (0)
 extern int g_force_attn_waves; // fused attention block shape forced by option "attn_waves" (0 = automatic)
 extern int g_stream_read_nt;   // sd_debug_stream_read: 1 = contiguous ranges with the nontemporal hint, 0 = grid-strided ordinary loads
 extern int g_force_splits[3]; // per GEMM mode: K splits forced by option "gemm_splits" (0 = automatic)
@@ -437,3 +438,8 @@ hipError_t launch_attn_fused_bf16(hipStream_t s, const float *qkv, int n_slabs, 
 hipError_t launch_attn_mfma_bf16(hipStream_t s, const void *qbuf, ActView q_av, const void *Kl, const void *Vtl,
                                  PlanView pv, CtxView cv, int R, int n_seq, int H, int hd, int64_t total_cap,
                                  int len_upper, float *part, size_t part_floats, void *obuf, ActView o_av, int stream_nt);
+// Attention of a prefill forward: G > 1 groups of 16 rows per sequence (plan slots seq * G + g), rows already in the
+// cache.  Returns hipErrorNotSupported outside its domain (the caller then takes the split kernel).
+hipError_t launch_attn_prefill_bf16(hipStream_t s, const void *qbuf, ActView q_av, const void *Kl, const void *Vtl,
+                                    PlanView pv, CtxView cv, int R, int n_seq, int G, int H, int hd, int64_t total_cap,
+                                    int len_upper, float *part, size_t part_floats, void *obuf, ActView o_av);

@@ -545,6 +545,7 @@ def test_committing_graph_replayed_far_past_its_capture_time_lengths():
     ("tiny_target", 1e-4, 96, [9, 41, 150]), ("small_target_bf16", 2e-2, 96, [9, 41, 150]),
     ("small_target_bf16", 2e-2, 144, [9, 41, 150]), ("small_target_bf16", 2e-2, 192, [9, 41, 150]),
     ("small_target_bf16", 2e-2, 576, [1000, 333, 17]),   # 12 groups per sequence and forward
+    ("small_target_bf16", 2e-2, 288, [1000, 333, 17]),   # 6 groups: the second block of four holds two
     ("small_draft_bf16", 2e-2, 192, [1000, 70, 129])])   # head width 64, several forwards
 def test_prefill_in_row_groups_matches_oracle(shape_name, tol, max_rows, lens):
     """With a workspace of 96 rows sd_prefill feeds three ragged prompts in groups of 16 rows, two groups
@@ -582,6 +583,45 @@ def test_prefill_in_row_groups_matches_oracle(shape_name, tol, max_rows, lens):
             i = min(r_na, int(na[b]))
             assert mg[i] < H.MARGIN_THR[st_.dtype] * np.abs(r_lg[i]).max(), (b, na[b], nx[b], r_na, r_nx, mg)
     ctx.close()
+    gm.close()
+
+
+@pytest.mark.parametrize("shape_name,max_rows,lens", [("small_target_bf16", 112, [700]), ("draft_a_1layer", 160, [333, 650]),
+                                                      ("small_draft_bf16", 64, [200, 90])])
+def test_prefill_attention_sharing_tiles_between_row_groups_matches_the_split_kernel(shape_name, max_rows, lens):
+    """Prefill forwards send four 16-row groups of a prompt and head to one block, which stages every K / V
+    tile in LDS once for its four waves (and splits the tile range over several blocks plus a combine pass when
+    there are few blocks).  Option prefill_attn = 0 brings back one set of split-kernel blocks per group.  Both
+    compute the same softmax in other partitions: the verify logits after the prefill agree to rounding level.
+    Seven, five and two groups per sequence and forward: blocks whose last waves have no group, and whose
+    groups end at different tiles."""
+    import dataclasses
+    _say(f"{shape_name}: prefill attention with shared tiles vs split kernel, workspace {max_rows}, prompts {lens}")
+    st_ = (dataclasses.replace(dg.SHAPES["draft_a"], n_layers=1, vocab=2048, name="draft_a_1layer")
+           if shape_name == "draft_a_1layer" else dg.SHAPES[shape_name])
+    w = dg.make_weights(st_, 87, BF16_LM_SCALE)
+    gm = api.Model(st_, w, max_rows=max_rows, max_pos=max(lens) + 64)
+    B, gamma, V = len(lens), 3, st_.vocab
+    prompts = [[int(t) for t in dg.make_prompt(87, b, n, V)] for b, n in enumerate(lens)]
+    cand = H.dev(dg.make_prompt(88, 0, B * gamma, V).reshape(B, gamma).astype(np.int32))
+    outs = []
+    for opt in (0, 1):
+        api.set_option("prefill_attn", opt)
+        try:
+            ctx = api.Context([n + 16 for n in lens])
+            ctx.attach(gm)
+            H.gpu_prefill(ctx, [gm], prompts)
+            na = torch.zeros(B, dtype=torch.int32, device="cuda")
+            nx = torch.zeros(B, dtype=torch.int32, device="cuda")
+            api.sd_verify(gm, ctx, None, B, gamma, 0.0, cand, None, None, na, nx, commit=False)
+            ctx.sync()
+            outs.append(gm.last_logits().cpu().numpy())
+            ctx.close()
+        finally:
+            api.set_option("prefill_attn", 1)
+    rel = np.abs(outs[0] - outs[1]).max() / np.abs(outs[0]).max()
+    _say(f"  rel diff {rel:.2e}")
+    assert np.isfinite(outs[1]).all() and rel < 5e-4
     gm.close()
 
 
