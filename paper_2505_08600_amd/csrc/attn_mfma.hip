@@ -397,16 +397,26 @@ __global__ __launch_bounds__(WG * 64, 3) void attn_prefill_kernel(const uint16_t
     if (t * AT_TILE <= vis_wave) { // (uniform over the wave) tiles past the wave's last row hold nothing it sees
         const uint16_t *kp = &sKV[b][lane * 8];
         const uint16_t *vp = &sKV[b][TILE + qi * AT_TILE + (grp ^ ((qi >> 2) & 3)) * 8]; // (rows 16 d + qi: same swizzle for every d)
+        // all K fragments are requested before the first product, and half of the V fragments behind the score
+        // products (into the registers the K fragments leave), so that the LDS round trips run under the MFMAs and
+        // the softmax instead of in front of every pair of products
+        bf16x8 kf[2 * NC];
+#pragma unroll
+        for (int c = 0; c < 2 * NC; c++) kf[c] = *(const lds_bf16x8 *)(const lds_bf16x8 *)(kp + c * 512);
         f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int c = 0; c < NC; c++) {
-            const bf16x8 ka = *(const lds_bf16x8 *)(const lds_bf16x8 *)(kp + (2 * c) * 512);
-            const bf16x8 kb = *(const lds_bf16x8 *)(const lds_bf16x8 *)(kp + (2 * c + 1) * 512);
-            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qv[c], sa, 0, 0, 0);
-            sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb, qv[c], sb, 0, 0, 0);
-            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, ql[c], sa, 0, 0, 0);
-            sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb, ql[c], sb, 0, 0, 0);
+            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[2 * c], qv[c], sa, 0, 0, 0);
+            sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[2 * c + 1], qv[c], sb, 0, 0, 0);
+            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[2 * c], ql[c], sa, 0, 0, 0);
+            sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[2 * c + 1], ql[c], sb, 0, 0, 0);
         }
+        __builtin_amdgcn_sched_barrier(0);
+        constexpr int NVH = ND / 2; // (all of them would not fit three waves per SIMD without spilling)
+        bf16x8 vf[NVH];
+#pragma unroll
+        for (int d = 0; d < NVH; d++) vf[d] = *(const lds_bf16x8 *)(const lds_bf16x8 *)(vp + d * 16 * AT_TILE);
+        __builtin_amdgcn_sched_barrier(0);
         // lane (q, grp) holds the scores of tokens 32 t + 8 grp + e, e = 0..7 (sa: e < 4, sb: e >= 4)
         const int t0 = t * AT_TILE;
         Pack8 ph, pl;
@@ -415,7 +425,7 @@ __global__ __launch_bounds__(WG * 64, 3) void attn_prefill_kernel(const uint16_t
         SD_RESCALE_IF(__any(corr != 1.0f), o, ND, corr)
 #pragma unroll
         for (int d = 0; d < ND; d++) {
-            const bf16x8 vv = *(const lds_bf16x8 *)(const lds_bf16x8 *)(vp + d * 16 * AT_TILE);
+            const bf16x8 vv = d < NVH ? vf[d] : *(const lds_bf16x8 *)(const lds_bf16x8 *)(vp + d * 16 * AT_TILE);
             o[d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv, ph.v, o[d], 0, 0, 0);
             o[d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv, pl.v, o[d], 0, 0, 0);
         }
