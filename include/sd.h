@@ -391,6 +391,9 @@ int sd_debug_stream_read(const void *buf, size_t bytes, uint32_t *scratch_word, 
  * operand is then rounded to its two bf16 terms before the division by rms instead of after.
  * 0 or 1 = wherever the shapes allow (bf16, no adapters loaded, widths multiples of 128: the
  * default), 2 = never.
+ * option "rope_group": on the split attention path (prefill, long contexts) RoPE + cache append of a bf16 model
+ * runs one block per (head, group of up to 16 consecutive rows) with 16-byte stores (1, the default) or one block
+ * per row (0); both give the same bits.
  * option "prefill_attn": 1 (the default) lets four 16-row groups of a prompt share every K / V tile they
  * read in a prefill forward (one block per four groups and head, tiles staged in LDS); 0 gives every group
  * blocks of its own (the split kernel of the decode path).

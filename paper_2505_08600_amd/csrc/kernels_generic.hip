@@ -818,11 +818,133 @@ __global__ void rope_append_kernel(const float *qkv, int n_slabs, size_t slab_st
     }
 }
 
+// The same step for bf16 models with head width 64 or 128, one block per (head, group of up to 16 rows whose
+// positions follow each other).  The row-per-block kernel above writes every cache element with a 2-byte store
+// of its own - V elements of consecutive dimensions lie 64 bytes apart in the transposed tiles - and takes 27 us
+// for 576 rows of the 7B shape.  Here a thread owns 8 consecutive dimensions of both rotary halves of one row:
+// float4 loads of the slabs (added in slab order, like above: same bits), 16-byte stores of the two q planes and
+// of the K pieces (8 consecutive dimensions of a token are one piece of the operand-order tile); the V values go
+// through LDS so that a thread can write the 16 tokens of one dimension as 32 contiguous bytes when the group is
+// full and starts at a multiple of 16 (every prefill group of a fresh prompt), and token by token otherwise.
+template <int HD>
+__global__ __launch_bounds__(HD) void rope_append_group_kernel(const float *__restrict__ qkv, int n_slabs, size_t slab_stride,
+                                                               PlanView pv, CtxView cv, int R, int H,
+                                                               const float2 *__restrict__ rope, int max_pos,
+                                                               uint16_t *__restrict__ qbuf, ActView q_av,
+                                                               uint16_t *__restrict__ Kl, uint16_t *__restrict__ Vtl,
+                                                               int64_t total_cap)
+{
+    constexpr int HALF = HD / 2, GPR = HALF / 8; // 8-dimension groups per rotary half
+    __shared__ __attribute__((aligned(16))) uint16_t sV[16][HD + 8];
+    __shared__ int s_pos[16];
+    const int h = blockIdx.x, j = blockIdx.y;
+    const int i = threadIdx.x / GPR, g = threadIdx.x % GPR; // row of the group, dimension group
+    const int HDm = H * HD;
+    const int r = j * R + min(i, R - 1);
+    int valid = i < R && pv.row_valid[r];
+    const int pos = pv.row_pos[r];
+    if (valid && pos >= max_pos) {
+        if (g == 0 && h == 0) atomicOr(cv.status, 8);
+        valid = 0;
+    }
+    const int64_t off = cv.off[pv.row_b[r]];
+    const int d0 = 8 * g, d1 = HALF + 8 * g;
+    float q[16], k[16], v[16]; // [0..7]: dimensions d0.., [8..15]: d1..
+#pragma unroll
+    for (int e = 0; e < 16; e++) q[e] = k[e] = v[e] = 0.f;
+    if (valid) {
+        const float *base = qkv + (size_t)r * 3 * HDm + h * HD;
+        for (int sl = 0; sl < n_slabs; sl++) { // split-K slabs of the QKV GEMM, added in slab order
+            const float *rs = base + (size_t)sl * slab_stride;
+            float4 ld[12];
+#pragma unroll
+            for (int m = 0; m < 3; m++) {
+                ld[4 * m + 0] = *(const float4 *)(rs + m * HDm + d0);
+                ld[4 * m + 1] = *(const float4 *)(rs + m * HDm + d0 + 4);
+                ld[4 * m + 2] = *(const float4 *)(rs + m * HDm + d1);
+                ld[4 * m + 3] = *(const float4 *)(rs + m * HDm + d1 + 4);
+            }
+#pragma unroll
+            for (int c = 0; c < 4; c++) {
+                const float4 a = ld[c], b = ld[4 + c], w = ld[8 + c];
+                q[4 * c + 0] += a.x, q[4 * c + 1] += a.y, q[4 * c + 2] += a.z, q[4 * c + 3] += a.w;
+                k[4 * c + 0] += b.x, k[4 * c + 1] += b.y, k[4 * c + 2] += b.z, k[4 * c + 3] += b.w;
+                v[4 * c + 0] += w.x, v[4 * c + 1] += w.y, v[4 * c + 2] += w.z, v[4 * c + 3] += w.w;
+            }
+        }
+        const float2 *cs = rope + (size_t)pos * HALF + d0;
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+            const float2 c = cs[e];
+            const float qa = q[e] * c.x - q[8 + e] * c.y, qb = q[8 + e] * c.x + q[e] * c.y;
+            const float ka = k[e] * c.x - k[8 + e] * c.y, kb = k[8 + e] * c.x + k[e] * c.y;
+            q[e] = qa, q[8 + e] = qb, k[e] = ka, k[8 + e] = kb;
+        }
+    }
+    if (i < R) { // q planes (zeros for rows without a token), 8 consecutive columns inside one K step
+#pragma unroll
+        for (int hf = 0; hf < 2; hf++) {
+            uint32_t hi[4], lo[4];
+#pragma unroll
+            for (int e = 0; e < 4; e++) bf16x2_split(q[8 * hf + 2 * e], q[8 * hf + 2 * e + 1], hi[e], lo[e]);
+            const size_t o = act_index(q_av, r, h * HD + (hf ? d1 : d0), HDm);
+            *(uint4 *)(qbuf + o) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+            *(uint4 *)(qbuf + o + q_av.plane) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+        }
+    }
+    if (valid) {
+        uint16_t *kh = Kl + (size_t)h * total_cap * HD;
+#pragma unroll
+        for (int hf = 0; hf < 2; hf++) {
+            uint32_t p[4];
+#pragma unroll
+            for (int e = 0; e < 4; e++) p[e] = bf16x2_bits_rne(k[8 * hf + 2 * e], k[8 * hf + 2 * e + 1]);
+            *(uint4 *)(kh + kt_offset(HD, off + pos, hf ? d1 : d0)) = make_uint4(p[0], p[1], p[2], p[3]);
+#pragma unroll
+            for (int e = 0; e < 4; e++) p[e] = bf16x2_bits_rne(v[8 * hf + 2 * e], v[8 * hf + 2 * e + 1]);
+            *(uint4 *)&sV[i][hf ? d1 : d0] = make_uint4(p[0], p[1], p[2], p[3]);
+        }
+    }
+    if (g == 0) s_pos[i] = valid ? pos : -1;
+    __syncthreads();
+    // V: thread d writes dimension d of the group's tokens
+    const int d = threadIdx.x;
+    uint16_t *vh = Vtl + (size_t)h * HD * total_cap;
+    const int p0 = s_pos[0];
+    bool run16 = p0 >= 0 && (p0 & 15) == 0;
+#pragma unroll
+    for (int t = 1; t < 16; t++) run16 = run16 && s_pos[t] == p0 + t;
+    const int64_t off0 = cv.off[pv.row_b[j * R]]; // (one sequence per group)
+    if (run16) {
+        uint32_t p[8];
+#pragma unroll
+        for (int t = 0; t < 8; t++) p[t] = (uint32_t)sV[2 * t][d] | ((uint32_t)sV[2 * t + 1][d] << 16);
+        uint16_t *dst = vh + vt_offset(HD, off0 + p0, d); // 16 tokens inside one 32-token tile: 32 contiguous bytes
+        *(uint4 *)dst = make_uint4(p[0], p[1], p[2], p[3]);
+        *(uint4 *)(dst + 8) = make_uint4(p[4], p[5], p[6], p[7]);
+    } else {
+        for (int t = 0; t < 16; t++)
+            if (s_pos[t] >= 0) vh[vt_offset(HD, off0 + s_pos[t], d)] = sV[t][d];
+    }
+}
+
+int g_rope_group = 1; // option "rope_group": 0 keeps the row-per-block kernel for bf16 models too
 hipError_t launch_rope_append(hipStream_t s, int dtype, const float *qkv, int n_slabs, size_t slab_stride, PlanView pv,
-                              CtxView cv, int M, int H, int hd, const float2 *rope, int max_pos, void *qbuf,
+                              CtxView cv, int M, int R, int H, int hd, const float2 *rope, int max_pos, void *qbuf,
                               ActView q_av, void *Kl, void *Vtl, int64_t total_cap)
 {
     if (n_slabs > ROPE_MAX_SLABS) return hipErrorInvalidValue;
+    if (dtype == SD_BF16 && g_rope_group && R >= 1 && R <= 16 && M % R == 0 && (hd == 64 || hd == 128) && H <= 65535 &&
+        M / R <= 65535 && (q_av.plane & 7) == 0 && ((uintptr_t)qbuf & 15) == 0 && ((uintptr_t)Kl & 15) == 0 &&
+        ((uintptr_t)Vtl & 15) == 0 && ((uintptr_t)qkv & 15) == 0 && (slab_stride & 3) == 0 && total_cap % 64 == 0) {
+        if (hd == 128)
+            hipLaunchKernelGGL(rope_append_group_kernel<128>, dim3(H, M / R), dim3(128), 0, s, qkv, n_slabs, slab_stride, pv,
+                               cv, R, H, rope, max_pos, (uint16_t *)qbuf, q_av, (uint16_t *)Kl, (uint16_t *)Vtl, total_cap);
+        else
+            hipLaunchKernelGGL(rope_append_group_kernel<64>, dim3(H, M / R), dim3(64), 0, s, qkv, n_slabs, slab_stride, pv, cv,
+                               R, H, rope, max_pos, (uint16_t *)qbuf, q_av, (uint16_t *)Kl, (uint16_t *)Vtl, total_cap);
+        return hipGetLastError();
+    }
     if (dtype == SD_BF16)
         hipLaunchKernelGGL(rope_append_kernel<bf16_t>, dim3(M), dim3(1024), 0, s, qkv, n_slabs, slab_stride, pv, cv, H,
                            hd, rope, max_pos, (bf16_t *)qbuf, q_av, (bf16_t *)Kl, (bf16_t *)Vtl, total_cap);

@@ -117,6 +117,12 @@ extern "C" int sd_set_option(const char *name, int32_t value)
         g_norm_fold = value;
         return SD_OK;
     }
+    if (!strcmp(name, "rope_group")) { // RoPE + cache append of the split attention path: 1 = one block per (head, row group)
+                                       // with 16-byte stores (default), 0 = one block per row
+        if (value != 0 && value != 1) return sd_fail(SD_EINVAL, "sd_set_option: rope_group is 0 or 1");
+        g_rope_group = value;
+        return SD_OK;
+    }
     if (!strcmp(name, "prefill_attn")) { // attention of prefill forwards: 1 = row groups of a prompt share staged K / V tiles
                                          // (default), 0 = the split kernel, one set of blocks per group
         if (value != 0 && value != 1) return sd_fail(SD_EINVAL, "sd_set_option: prefill_attn is 0 or 1");
@@ -854,7 +860,7 @@ static int forward(sd_model *m, sd_ctx *c, int slot, hipStream_t s, int mode, in
         }
         if (ea == hipErrorNotSupported) {
             { ProfScope ps(T_ROPE, s);
-            FWD(launch_rope_append(s, cf.dtype, qkv_src, nq_slabs, (size_t)M * 3 * d, pv, cv, M, H, hd, m->rope,
+            FWD(launch_rope_append(s, cf.dtype, qkv_src, nq_slabs, (size_t)M * 3 * d, pv, cv, M, R, H, hd, m->rope,
                                    cf.max_pos, m->qbuf, avd, Kl, Vtl, c->total_cap)); }
             ProfScope ps(T_ATTN, s);
             if (cf.dtype == SD_BF16 && !(g_force_generic & 2) && G > 1) // a prompt's row groups share their K / V tiles

@@ -357,6 +357,7 @@ int sd_fail(int code, const std::string &s);
 
 extern int g_force_generic;
 extern int g_force_tile_cols;  // 96-row GEMM block width forced by option "gemm_tile_cols" (0 = automatic)
+extern int g_rope_group;       // option "rope_group": RoPE + cache append one block per (head, row group) for bf16 models (1, default)
 extern int g_prefill_attn;     // option "prefill_attn": the prefill attention kernel (1, default) or the split kernel per group (0)
 extern int g_force_attn_waves; // fused attention block shape forced by option "attn_waves" (0 = automatic)
 extern int g_stream_read_nt;   // sd_debug_stream_read: 1 = contiguous ranges with the nontemporal hint, 0 = grid-strided ordinary loads
@@ -383,8 +384,9 @@ hipError_t launch_rmsnorm(hipStream_t s, int dtype, const float *x, const float 
 hipError_t launch_retile_bf16(hipStream_t s, const void *src, void *dst, int N, int K);
 hipError_t launch_gemm_generic(hipStream_t s, int dtype, int mode, const void *A, ActView a_av, WeightSeg w, int M,
                                int N, int K, float *C, void *Cact, ActView c_av);
+// (R: rows per plan slot; the rows of a slot hold consecutive positions of one sequence)
 hipError_t launch_rope_append(hipStream_t s, int dtype, const float *qkv, int n_slabs, size_t slab_stride, PlanView pv,
-                              CtxView cv, int M, int H,
+                              CtxView cv, int M, int R, int H,
                               int hd, const float2 *rope, int max_pos, void *qbuf, ActView q_av, void *Kl, void *Vtl,
                               int64_t total_cap);
 hipError_t launch_attn_generic(hipStream_t s, int dtype, const void *qbuf, ActView q_av, const void *Kl,

@@ -44,6 +44,7 @@ def test_argument_errors_do_not_need_a_gpu():
     assert b"vocab above 262144" in L.sd_last_error()
     assert L.sd_set_option(b"stream_read_nt", 4) == api.SD_EINVAL
     assert L.sd_set_option(b"norm_fold", 3) == api.SD_EINVAL and L.sd_set_option(b"norm_fold", 0) == api.SD_OK
+    assert L.sd_set_option(b"rope_group", 2) == api.SD_EINVAL and L.sd_set_option(b"rope_group", 1) == api.SD_OK
     assert L.sd_set_option(b"prefill_attn", 2) == api.SD_EINVAL and L.sd_set_option(b"prefill_attn", 1) == api.SD_OK
     assert L.sd_ctx_create(0, None, None) == api.SD_EINVAL
     assert L.sd_draft(None, None, None, 1, 4, 1.0, None, None, None, None) == api.SD_EINVAL

@@ -625,6 +625,42 @@ def test_prefill_attention_sharing_tiles_between_row_groups_matches_the_split_ke
     gm.close()
 
 
+@pytest.mark.parametrize("shape_name,max_rows,lens", [("small_target_bf16", 112, [700, 45]), ("small_draft_bf16", 64, [1700]),
+                                                      ("draft_a_1layer", 160, [333, 650, 16])])
+def test_rope_and_cache_append_per_row_group_gives_the_bits_of_the_row_kernel(shape_name, max_rows, lens):
+    """On the split attention path (prefill, long contexts) a bf16 model's RoPE + cache append runs one block per
+    (head, group of up to 16 consecutive rows) with 16-byte stores; option rope_group = 0 brings back the block
+    per row with its 2-byte stores.  Same fp32 sums in the same order and the same roundings: the verify logits
+    after the prefill must be identical bit for bit.  Full groups at multiples of 16 (32-byte V runs), partial
+    last groups, and a 1700-token context whose verify pass (4 rows per group) takes the split path as well."""
+    import dataclasses
+    _say(f"{shape_name}: RoPE + append per row group vs per row, workspace {max_rows}, prompts {lens}")
+    st_ = (dataclasses.replace(dg.SHAPES["draft_a"], n_layers=1, vocab=2048, name="draft_a_1layer")
+           if shape_name == "draft_a_1layer" else dg.SHAPES[shape_name])
+    w = dg.make_weights(st_, 89, BF16_LM_SCALE)
+    gm = api.Model(st_, w, max_rows=max_rows, max_pos=max(lens) + 64)
+    B, gamma, V = len(lens), 3, st_.vocab
+    prompts = [[int(t) for t in dg.make_prompt(89, b, n, V)] for b, n in enumerate(lens)]
+    cand = H.dev(dg.make_prompt(90, 0, B * gamma, V).reshape(B, gamma).astype(np.int32))
+    outs = []
+    for opt in (0, 1):
+        api.set_option("rope_group", opt)
+        try:
+            ctx = api.Context([n + 16 for n in lens])
+            ctx.attach(gm)
+            H.gpu_prefill(ctx, [gm], prompts)
+            na = torch.zeros(B, dtype=torch.int32, device="cuda")
+            nx = torch.zeros(B, dtype=torch.int32, device="cuda")
+            api.sd_verify(gm, ctx, None, B, gamma, 0.0, cand, None, None, na, nx, commit=False)
+            ctx.sync()
+            outs.append(gm.last_logits().cpu().numpy())
+            ctx.close()
+        finally:
+            api.set_option("rope_group", 1)
+    assert np.isfinite(outs[1]).all() and np.array_equal(outs[0], outs[1])
+    gm.close()
+
+
 def test_gamma_zero_is_autoregressive_decoding(tiny_pair):
     _say("gamma = 0")
     prompt = dg.make_prompt(11, 2, 12, TINY_T.vocab)
