@@ -374,29 +374,30 @@ __global__ __launch_bounds__(WG * 64, 3) void attn_prefill_kernel(const uint16_t
     // register sets: the loads of tiles t + 1 and t + 2 are in flight while tile t is consumed (one tile ahead left
     // every iteration waiting for most of a memory round trip)
     bf16x8 st0[NLD], st1[NLD];
+    // The K tile is stored in operand order already: piece c goes to LDS position c and a fragment read is
+    // lane-linear.  The V^T tile is [dim][32 tokens] (64-byte rows), and lane (qi, grp) of a fragment read wants piece
+    // grp of row 16 d + qi: read from a row-major copy, such reads hit the banks unevenly (80 % of the LDS cycles were
+    // conflict cycles).  So the thread that fills LDS position 64 d + l of the V part fetches the piece lane l of
+    // fragment d will want - row 16 d + l % 16, piece l / 16.  The lanes of a wave still cover the same contiguous
+    // KiB of global memory, only in another order, and both the LDS writes and the fragment reads are linear.
     auto fetch = [&](int t, bf16x8 *st) {
 #pragma unroll
         for (int k = 0; k < NLD; k++) {
             const int c = threadIdx.x + k * (WG * 64);
-            const uint16_t *src = c < TILE / 8 ? K + (size_t)t * TILE + c * 8 : Vt + (size_t)t * TILE + (c - TILE / 8) * 8;
+            const int cv = c - TILE / 8, l = cv & 63;
+            const uint16_t *src = c < TILE / 8 ? K + (size_t)t * TILE + c * 8
+                                               : Vt + (size_t)t * TILE + ((((cv >> 6) * 16 + (l & 15)) << 2) + (l >> 4)) * 8;
             st[k] = *(const bf16x8 *)src;
         }
     };
-    // V^T rows are 64 bytes: the 16 lanes of one pass of a fragment read (rows qi = 0..15, one 16-byte piece each)
-    // would fall on 16 of the 64 banks, four deep.  Piece g of row r is therefore kept at position g ^ ((r >> 2) & 3)
-    // of its row, which spreads such a pass over all banks (the K tile is read lane-linear and stays as it is).
     auto stash = [&](int b, const bf16x8 *st) {
 #pragma unroll
-        for (int k = 0; k < NLD; k++) {
-            int c = threadIdx.x + k * (WG * 64);
-            if (c >= TILE / 8) c ^= ((c - TILE / 8) >> 4) & 3; // (TILE / 8 is a multiple of 4: the XOR stays inside the row)
-            *(lds_bf16x8 *)(lds_bf16x8 *)&sKV[b][c * 8] = st[k];
-        }
+        for (int k = 0; k < NLD; k++) *(lds_bf16x8 *)(lds_bf16x8 *)&sKV[b][(threadIdx.x + k * (WG * 64)) * 8] = st[k];
     };
     auto consume = [&](int t, int b) {
     if (t * AT_TILE <= vis_wave) { // (uniform over the wave) tiles past the wave's last row hold nothing it sees
         const uint16_t *kp = &sKV[b][lane * 8];
-        const uint16_t *vp = &sKV[b][TILE + qi * AT_TILE + (grp ^ ((qi >> 2) & 3)) * 8]; // (rows 16 d + qi: same swizzle for every d)
+        const uint16_t *vp = &sKV[b][TILE + lane * 8]; // (fragment d: + 512 d elements)
         // all K fragments are requested before the first product, and half of the V fragments behind the score
         // products (into the registers the K fragments leave), so that the LDS round trips run under the MFMAs and
         // the softmax instead of in front of every pair of products
@@ -415,7 +416,7 @@ __global__ __launch_bounds__(WG * 64, 3) void attn_prefill_kernel(const uint16_t
         constexpr int NVH = ND / 2; // (all of them would not fit three waves per SIMD without spilling)
         bf16x8 vf[NVH];
 #pragma unroll
-        for (int d = 0; d < NVH; d++) vf[d] = *(const lds_bf16x8 *)(const lds_bf16x8 *)(vp + d * 16 * AT_TILE);
+        for (int d = 0; d < NVH; d++) vf[d] = *(const lds_bf16x8 *)(const lds_bf16x8 *)(vp + d * 512);
         __builtin_amdgcn_sched_barrier(0);
         // lane (q, grp) holds the scores of tokens 32 t + 8 grp + e, e = 0..7 (sa: e < 4, sb: e >= 4)
         const int t0 = t * AT_TILE;
@@ -425,7 +426,7 @@ __global__ __launch_bounds__(WG * 64, 3) void attn_prefill_kernel(const uint16_t
         SD_RESCALE_IF(__any(corr != 1.0f), o, ND, corr)
 #pragma unroll
         for (int d = 0; d < ND; d++) {
-            const bf16x8 vv = d < NVH ? vf[d] : *(const lds_bf16x8 *)(const lds_bf16x8 *)(vp + d * 16 * AT_TILE);
+            const bf16x8 vv = d < NVH ? vf[d] : *(const lds_bf16x8 *)(const lds_bf16x8 *)(vp + d * 512);
             o[d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv, ph.v, o[d], 0, 0, 0);
             o[d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv, pl.v, o[d], 0, 0, 0);
         }
@@ -795,15 +796,21 @@ hipError_t launch_attn_prefill_bf16(hipStream_t s, const void *qbuf, ActView q_a
                            (uint16_t *)obuf, o_av);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || S == 1) return e;
-    // (the unrolled loops of the combine kernel cover its template's split count: a short one for the usual 2 - 4)
+    // (the unrolled loops of the combine kernel cover its template's split count: short ones for the usual 2 - 8)
     if (hd == 128 && S <= 4)
         hipLaunchKernelGGL((attn_combine_kernel<128, 4>), dim3(H, n_slots), dim3(256), 0, s, part, pv, R, H, S, (uint16_t *)obuf,
+                           o_av);
+    else if (hd == 128 && S <= 8)
+        hipLaunchKernelGGL((attn_combine_kernel<128, 8>), dim3(H, n_slots), dim3(256), 0, s, part, pv, R, H, S, (uint16_t *)obuf,
                            o_av);
     else if (hd == 128)
         hipLaunchKernelGGL((attn_combine_kernel<128>), dim3(H, n_slots), dim3(256), 0, s, part, pv, R, H, S, (uint16_t *)obuf,
                            o_av);
     else if (S <= 4)
         hipLaunchKernelGGL((attn_combine_kernel<64, 4>), dim3(H, n_slots), dim3(256), 0, s, part, pv, R, H, S, (uint16_t *)obuf,
+                           o_av);
+    else if (S <= 8)
+        hipLaunchKernelGGL((attn_combine_kernel<64, 8>), dim3(H, n_slots), dim3(256), 0, s, part, pv, R, H, S, (uint16_t *)obuf,
                            o_av);
     else
         hipLaunchKernelGGL((attn_combine_kernel<64>), dim3(H, n_slots), dim3(256), 0, s, part, pv, R, H, S, (uint16_t *)obuf,
