@@ -334,3 +334,49 @@ def test_config5_synthetic_q_long_contexts(config5_rig, rho):
         med = R.check_ids[1]
         if (med, 0.0) in R.n_acc_seen:
             assert R.n_acc_seen[(med, 0.9)] >= R.n_acc_seen[(med, 0.0)]
+
+
+@pytest.mark.timeout(900)
+def test_prefill_at_full_width_matches_oracle_and_the_split_kernels():
+    """The prefill path at the 7B shape's widths in the configuration bench.py --prefill-bench times (576-row
+    workspace: 36 row groups of one prompt per forward, nine blocks of four groups per head, tile ranges split
+    over blocks with the combine pass), cut to two layers so that the oracle can prefill the same 600-token prompt:
+    the verify pass that follows must give the oracle's logits.  The same prefill through the decode path's
+    split kernel per group (prefill_attn = 0) agrees to rounding level, and with the cache append one block per
+    row (rope_group = 0) bit for bit."""
+    seed, gamma, n_ctx = 2031, 5, 600
+    st_ = dg.with_layers(dg.SHAPES["t7b"], 2)
+    wt = dg.make_weights(st_, seed, threads=16)
+    om = oracle.OracleModel(st_, wt)
+    gm = api.Model(st_, wt, max_rows=576, max_pos=n_ctx + 64)
+    V = st_.vocab
+    prompt = [int(t) for t in dg.make_prompt(seed, 0, n_ctx, V)]
+    cand = dg.make_prompt(seed + 1, 0, gamma, V).astype(np.int32)
+    t0 = time.time()
+    seq = om.new_seq(n_ctx + 16)
+    oracle.prefill(seq, prompt)
+    r_na, r_nx, mg, r_lg = seq.verify(prompt, gamma, 0.0, cand, None, np.zeros(gamma + 1, np.float32), want_logits=True)
+    print(f"full-width prefill: oracle prefill + verify in {time.time() - t0:.1f}s", flush=True)
+    outs = {}
+    for name, opts in (("default", {}), ("split kernel per group", {"prefill_attn": 0}), ("append per row", {"rope_group": 0})):
+        for k, v in opts.items():
+            api.set_option(k, v)
+        try:
+            ctx = api.Context([n_ctx + 16])
+            ctx.attach(gm)
+            H.gpu_prefill(ctx, [gm], [prompt])
+            na = torch.zeros(1, dtype=torch.int32, device="cuda")
+            nx = torch.zeros(1, dtype=torch.int32, device="cuda")
+            api.sd_verify(gm, ctx, None, 1, gamma, 0.0, H.dev(cand[None]), None, None, na, nx, commit=False)
+            ctx.sync()
+            outs[name] = gm.last_logits().cpu().numpy()
+            ctx.close()
+        finally:
+            for k in opts:
+                api.set_option(k, 1)
+    rel = np.abs(outs["default"] - r_lg).max() / np.abs(r_lg).max()
+    rel_split = np.abs(outs["default"] - outs["split kernel per group"]).max() / np.abs(r_lg).max()
+    print(f"full-width prefill: logits vs oracle {rel:.2e}, vs split kernel per group {rel_split:.2e}", flush=True)
+    assert rel < 2e-2 and rel_split < 5e-4
+    assert np.array_equal(outs["default"], outs["append per row"])
+    gm.close()
