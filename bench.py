@@ -29,7 +29,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-GATEUP_TRAFFIC_BYTES = 181.2e6  # measured with rocprofv3 --pmc, see profiles/config2_b1_7b_hbm_traffic.md
+GATEUP_TRAFFIC_BYTES = 181.3e6  # FETCH_SIZE + WRITE_SIZE per launch (181.1 + 0.2 MB), rocprofv3 --pmc: profiles/config2_b1_7b_hbm_traffic.md
 
 
 def log(*a):
