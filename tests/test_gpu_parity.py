@@ -661,6 +661,44 @@ def test_rope_and_cache_append_per_row_group_gives_the_bits_of_the_row_kernel(sh
     gm.close()
 
 
+@pytest.mark.parametrize("shape_name,keep", [("small_target_bf16", 37), ("small_draft_bf16", 101), ("draft_a_1layer", 16)])
+def test_prefill_resumed_from_an_odd_cache_length_matches_the_prefill_from_zero(shape_name, keep):
+    """A prompt is prefilled, its cache cut back to `keep` rows (not a multiple of 16 or 32 in two of the cases) and
+    prefilled again: the row groups of the second pass start in the middle of a K / V tile, so the prefill attention
+    masks inside its first tiles, the cache append takes its token-by-token path, and the new rows share tiles with
+    old ones.  The rows written are the same as before, and the verify logits must agree with the untouched
+    prefill's to rounding level."""
+    import dataclasses
+    _say(f"{shape_name}: prefill resumed from cache length {keep}")
+    st_ = (dataclasses.replace(dg.SHAPES["draft_a"], n_layers=1, vocab=2048, name="draft_a_1layer")
+           if shape_name == "draft_a_1layer" else dg.SHAPES[shape_name])
+    w = dg.make_weights(st_, 93, BF16_LM_SCALE)
+    gm = api.Model(st_, w, max_rows=96, max_pos=512)
+    n, gamma, V = 333, 3, st_.vocab
+    prompt = [int(t) for t in dg.make_prompt(93, 0, n, V)]
+    cand = H.dev(dg.make_prompt(94, 0, gamma, V).reshape(1, gamma).astype(np.int32))
+    outs = []
+    for resume in (False, True):
+        ctx = api.Context([n + 16])
+        ctx.attach(gm)
+        H.gpu_prefill(ctx, [gm], [prompt])
+        if resume:
+            ctx.truncate(gm, 0, keep)
+            api.sd_prefill(gm, ctx, None, 1, n - 1 - keep)
+        nt, kv = ctx.sync(gm)
+        assert list(nt) == [n] and list(kv) == [n - 1]
+        na = torch.zeros(1, dtype=torch.int32, device="cuda")
+        nx = torch.zeros(1, dtype=torch.int32, device="cuda")
+        api.sd_verify(gm, ctx, None, 1, gamma, 0.0, cand, None, None, na, nx, commit=False)
+        ctx.sync()
+        outs.append(gm.last_logits().cpu().numpy())
+        ctx.close()
+    rel = np.abs(outs[0] - outs[1]).max() / np.abs(outs[0]).max()
+    _say(f"  rel diff {rel:.2e}")
+    assert np.isfinite(outs[1]).all() and rel < 5e-4
+    gm.close()
+
+
 def test_gamma_zero_is_autoregressive_decoding(tiny_pair):
     _say("gamma = 0")
     prompt = dg.make_prompt(11, 2, 12, TINY_T.vocab)
