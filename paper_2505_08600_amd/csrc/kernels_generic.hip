@@ -38,6 +38,44 @@ __device__ __forceinline__ int row16_max(int v)
     v = max(v, dpp_i<0x140>(v));
     return v;
 }
+// smallest value over the wave's 64 lanes (every lane gets it)
+__device__ __forceinline__ int wave_min_i(int v)
+{
+    int m = row16_max(~v); // ~ reverses the order of ints
+    m = max(max(__builtin_amdgcn_readlane(m, 0), __builtin_amdgcn_readlane(m, 16)),
+            max(__builtin_amdgcn_readlane(m, 32), __builtin_amdgcn_readlane(m, 48)));
+    return ~m;
+}
+__device__ __forceinline__ int wave_max_i(int v)
+{
+    const int m = row16_max(v);
+    return max(max(__builtin_amdgcn_readlane(m, 0), __builtin_amdgcn_readlane(m, 16)),
+               max(__builtin_amdgcn_readlane(m, 32), __builtin_amdgcn_readlane(m, 48)));
+}
+// Inverse-CDF placement inside one thread's four weights (indices i0 .. i0 + 3), the running sum continued from
+// `cum`: the first index of positive weight whose inclusive sum exceeds the target, 0x7fffffff if there is none.
+// Every thread of a scan evaluates it, whatever its starting sum, and the smallest index wins.  A thread's
+// starting sum comes out of a parallel scan and is not bit-equal to its predecessor's sequentially added final
+// sum, so a target within rounding of a thread boundary can be "not yet reached" at the end of one thread and
+// "already passed" at the start of the next: then the next index of positive weight is the answer (and, because
+// of the weight test, never an index the distribution gives no mass to).
+__device__ __forceinline__ int first_over(float cum, const float4 f, float target, int i0)
+{
+    int k = 0x7fffffff;
+    cum += f.x;
+    if (f.x > 0.f && cum > target) k = i0;
+    cum += f.y;
+    if (k == 0x7fffffff && f.y > 0.f && cum > target) k = i0 + 1;
+    cum += f.z;
+    if (k == 0x7fffffff && f.z > 0.f && cum > target) k = i0 + 2;
+    cum += f.w;
+    if (k == 0x7fffffff && f.w > 0.f && cum > target) k = i0 + 3;
+    return k;
+}
+__device__ __forceinline__ int last_positive(const float4 f, int i0)
+{
+    return f.w > 0.f ? i0 + 3 : f.z > 0.f ? i0 + 2 : f.y > 0.f ? i0 + 1 : f.x > 0.f ? i0 : -1;
+}
 // largest value, lowest index among equals
 __device__ __forceinline__ void take_better(float &v, int &i, float ov, int oi)
 {
@@ -1043,7 +1081,10 @@ hipError_t launch_attn_generic(hipStream_t s, int dtype, const void *qbuf, ActVi
 // Chooses the smallest index k with sum_{x<=k} w(x) > u * sum_x w(x) for weights
 // produced on the fly by wfun(v) -> float4 of elements 4v..4v+3 (zero beyond V).
 // All threads of a 1024-thread block must call it; the result is returned to all.
-// If rounding leaves no such k, the last index with positive weight is returned.
+// The sums are added in parallel (segment totals, then a scan inside the segment that holds u * Z), so where
+// rounding makes them disagree the answer is the nearest index of positive weight: see first_over; if no
+// running sum of the chosen segment exceeds the target, the segment's last index of positive weight; if
+// u * Z is not below Z at all, the row's last one.
 struct PickScratch {
     float seg[64];
     float red[32];
@@ -1052,6 +1093,7 @@ struct PickScratch {
     int seg_idx;
     int pick;
     int last_pos;
+    int seg_last; // last index of positive weight inside the segment that holds the target
 };
 
 template <typename F>
@@ -1063,6 +1105,7 @@ __device__ int block_pick_cdf(F wfun, int V, float u, PickScratch *ps, float *to
     if (threadIdx.x == 0) {
         ps->pick = 0x7fffffff;
         ps->last_pos = 0;
+        ps->seg_last = -1;
     }
     __syncthreads();
     int lastp = -1;
@@ -1104,29 +1147,20 @@ __device__ int block_pick_cdf(F wfun, int V, float u, PickScratch *ps, float *to
         float4 f = v < nvec ? wfun(v) : make_float4(0.f, 0.f, 0.f, 0.f);
         float loc = ((f.x + f.y) + f.z) + f.w;
         float pre = block_excl_scan(loc, ps->red);
-        float cum = ps->base + pre, target = ps->target;
-        if (cum <= target) {
-            int k = -1;
-            cum += f.x;
-            if (cum > target) k = 4 * v;
-            else {
-                cum += f.y;
-                if (cum > target) k = 4 * v + 1;
-                else {
-                    cum += f.z;
-                    if (cum > target) k = 4 * v + 2;
-                    else {
-                        cum += f.w;
-                        if (cum > target) k = 4 * v + 3;
-                    }
-                }
-            }
-            if (k >= 0 && k < V) atomicMin(&ps->pick, k);
+        int k = first_over(ps->base + pre, f, ps->target, 4 * v);
+        if (k >= V) k = 0x7fffffff;
+        k = wave_min_i(k);
+        const int ls = wave_max_i(last_positive(f, 4 * v));
+        if (threadIdx.x % WAVE == 0) {
+            if (k != 0x7fffffff) atomicMin(&ps->pick, k);
+            if (ls >= 0) atomicMax(&ps->seg_last, ls);
         }
     }
     __syncthreads();
     int pick = ps->pick;
-    if (pick == 0x7fffffff) pick = ps->last_pos;
+    // rounding left every running sum of the chosen segment at or below the target: its last index of positive
+    // weight; no segment chosen (u * Z not below Z): the last one of the row
+    if (pick == 0x7fffffff) pick = it >= 0 && ps->seg_last >= 0 ? min(ps->seg_last, V - 1) : ps->last_pos;
     __syncthreads();
     return pick;
 }
@@ -1190,6 +1224,7 @@ struct FastScratch {
     float red[32];
     int redi[32];
     int pick;
+    int seg_last; // last index of positive weight inside the segment that holds the target
 };
 static_assert(ROW_THREADS / WAVE == 16, "the cross-wave steps below read one LDS entry per lane of a 16-lane row");
 
@@ -1292,7 +1327,10 @@ __device__ int pick_regs(const RowRegs &w, int V, float u, FastScratch *fs, floa
         for (int it = 0; it < ROW_NSEG; it++) fs->wsum[wv][it] = loc[it];
         fs->redi[wv] = lastp;
     }
-    if (threadIdx.x == 0) fs->pick = 0x7fffffff;
+    if (threadIdx.x == 0) {
+        fs->pick = 0x7fffffff;
+        fs->seg_last = -1;
+    }
     lds_barrier();
     const int nseg = ((V + 3) / 4 + ROW_THREADS - 1) / ROW_THREADS;
     float seg[ROW_NSEG];
@@ -1324,29 +1362,20 @@ __device__ int pick_regs(const RowRegs &w, int V, float u, FastScratch *fs, floa
         if (lane == WAVE - 1) fs->red[wv] = inc; // red was last read before the barrier above
         lds_barrier();
         const float before = row16_sum((lane & 15) < wv ? fs->red[lane & 15] : 0.f);
-        float cum = base + (before + inc - l4);
-        if (cum <= target) {
-            int k = -1;
-            cum += f.x;
-            if (cum > target) k = 4 * v;
-            else {
-                cum += f.y;
-                if (cum > target) k = 4 * v + 1;
-                else {
-                    cum += f.z;
-                    if (cum > target) k = 4 * v + 2;
-                    else {
-                        cum += f.w;
-                        if (cum > target) k = 4 * v + 3;
-                    }
-                }
-            }
-            if (k >= 0 && k < V) atomicMin(&fs->pick, k);
+        int k = first_over(base + (before + inc - l4), f, target, 4 * v);
+        if (k >= V) k = 0x7fffffff;
+        k = wave_min_i(k);
+        const int ls = wave_max_i(last_positive(f, 4 * v));
+        if (lane == 0) {
+            if (k != 0x7fffffff) atomicMin(&fs->pick, k);
+            if (ls >= 0) atomicMax(&fs->seg_last, ls);
         }
     }
     lds_barrier();
     int pick = fs->pick;
-    if (pick == 0x7fffffff) pick = lp;
+    // rounding left every running sum of the chosen segment at or below the target: its last index of positive
+    // weight; no segment chosen (u * Z not below Z): the last one of the row
+    if (pick == 0x7fffffff) pick = sit >= 0 && fs->seg_last >= 0 ? min(fs->seg_last, V - 1) : lp;
     lds_barrier();
     return pick;
 }
@@ -1607,25 +1636,10 @@ __global__ __launch_bounds__(256) void draft_sample_split_kernel(const float *lo
         }
         const int v = k * (DS_SLICE / 4) + it * 256 + threadIdx.x;
         const float4 f = e[it];
-        float cum = before + (inc[it] - l4[it]);
-        if (cum <= target) {
-            int pk = -1;
-            cum += f.x;
-            if (cum > target) pk = 4 * v;
-            else {
-                cum += f.y;
-                if (cum > target) pk = 4 * v + 1;
-                else {
-                    cum += f.z;
-                    if (cum > target) pk = 4 * v + 2;
-                    else {
-                        cum += f.w;
-                        if (cum > target) pk = 4 * v + 3;
-                    }
-                }
-            }
-            if (pk >= 0 && pk < V) atomicMin(&ss.pick, pk);
-        }
+        int pk = first_over(before + (inc[it] - l4[it]), f, target, 4 * v);
+        if (pk >= V) pk = 0x7fffffff;
+        pk = wave_min_i(pk);
+        if (lane == 0 && pk != 0x7fffffff) atomicMin(&ss.pick, pk);
     }
     __syncthreads();
     int pick = ss.pick;

@@ -72,6 +72,66 @@ def test_accept_alone_matches_oracle(V, gamma, T, rho):
         assert len(set(na_h.tolist())) >= 2   # the case exercises accept, reject and the residual draw
 
 
+@pytest.mark.parametrize("V,gamma,n_trials", [(2772, 0, 1500), (2772, 1, 1500), (32000, 0, 900), (32000, 1, 600),
+                                              (50000, 0, 450)])
+def test_next_token_for_uniforms_on_the_boundaries_of_the_cdf(V, gamma, n_trials):
+    """The next token is the first index whose inclusive sum of weights exceeds u * Z (Section 3.1: a draw from p, or
+    from the normalised max(p - q, 0) after a rejection).  The kernels add those sums in parallel - per thread of four
+    consecutive weights, per wave, per segment - so the places where rounding can make two partial sums disagree are the
+    ends of those groups.  Here every trial is one sequence with the same logits row and a uniform that sits on such an
+    end of the exact CDF, or one or two float32 steps beside it: the token returned must always be one of the two that
+    meet there (within the fp32 band of the decision rule), never one from elsewhere in the row."""
+    print(f"boundary uniforms V={V} gamma={gamma} trials={n_trials}", flush=True)
+    T = 1.0
+    rng = np.random.default_rng(V + gamma)
+    row = (3.0 * dg.make_logit_noise(17, 0, 0, V)).astype(np.float32)
+    logits1 = np.stack([row] + [(3.0 * dg.make_logit_noise(17, 0, 1 + i, V)).astype(np.float32) for i in range(gamma)])
+    q1 = cand1 = None
+    if gamma:   # a candidate that is certainly rejected: q puts ten times the target's mass on it
+        p0 = oracle.softmax_T(row, T).astype(np.float64)
+        c = int(np.argsort(-p0)[3])
+        q1 = oracle.softmax_T((0.5 * row + 2.0 * dg.make_logit_noise(17, 1, 0, V)).astype(np.float32), T).astype(np.float64)
+        q1[c] = min(0.9, 10.0 * p0[c] + 0.05)
+        q1 = (q1 / q1.sum()).astype(np.float32)[None]
+        cand1 = np.array([c], np.int32)
+    w = np.asarray(oracle.next_weights(logits1, q1, 0, T), np.float64)
+    assert (w > 0).sum() > V // 8
+    cdf = np.cumsum(w) / w.sum()
+    # ends of a thread's four weights, of a wave's 256, of a segment's 4096; a third of the trials each
+    ends = np.concatenate([rng.choice(np.arange(3, V - 4, 4), n_trials // 9, replace=False),
+                           rng.choice(np.arange(255, V - 4, 256), n_trials // 9),
+                           rng.choice(np.arange(4095, V - 4, 4096), n_trials // 9) if V > 8192 else
+                           rng.choice(np.arange(3, V - 4, 4), n_trials // 9, replace=False)])
+    us = []
+    for k in ends:
+        u0 = np.float32(cdf[k])
+        us += [u0, np.nextafter(u0, np.float32(0)), np.nextafter(u0, np.float32(1))]
+    us = np.clip(np.array(us, np.float32), np.float32(2.0 ** -24), np.float32(1.0 - 2.0 ** -24))
+    B = len(us)
+    u = np.full((B, gamma + 1), 0.999, np.float32)   # (the candidate's own test: u = 0.999 against p / q <= 0.1)
+    u[:, gamma] = us
+    logits = np.broadcast_to(logits1, (B, gamma + 1, V)).copy()
+    q = np.broadcast_to(q1, (B, gamma, V)).copy() if gamma else None
+    cand = np.broadcast_to(cand1, (B, gamma)).copy() if gamma else None
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    na = torch.full((B,), -1, dtype=torch.int32, device="cuda")
+    nx = torch.full((B,), -1, dtype=torch.int32, device="cuda")
+    ws = torch.zeros(3 * B * (gamma + 1), device="cuda")
+    api.sd_accept(dev(logits), gamma, T, dev(cand) if gamma else None, dev(q) if gamma else None, dev(u), na, nx, ws)
+    torch.cuda.synchronize()
+    na_h, nx_h = na.cpu().numpy(), nx.cpu().numpy()
+    assert (na_h == 0).all()
+    other = 0
+    for b in range(B):
+        ref = oracle.sample_cdf(w, float(us[b]))[0]
+        if int(nx_h[b]) != ref:
+            other += 1
+            assert 0 <= nx_h[b] < V and w[nx_h[b]] > 0, (b, int(nx_h[b]), ref)
+            d = oracle.cdf_distance(w, float(us[b]), int(nx_h[b]))
+            assert d < 1e-5, (b, float(us[b]), int(nx_h[b]), ref, d)
+    print(f"  {B} uniforms, {other} resolved to the neighbouring token", flush=True)
+
+
 def test_accept_argument_errors():
     L = api.lib()
     x = torch.zeros(8, device="cuda")
