@@ -363,6 +363,65 @@ def test_attention_blocks_applying_the_output_projection_match_the_separate_laun
     gt.close()
 
 
+@pytest.mark.parametrize("force", [0, 4])
+def test_draft_candidates_for_uniforms_on_the_boundaries_of_q(force):
+    """Both draft samplers (one block per 2048-column slice working from the LM head's partials; one block per row,
+    option force_generic = 4) place u * Z with sums added in parallel - per thread of four consecutive columns, per
+    wave of 256, per slice - and where two partial sums disagree by rounding the candidate must still be one of the
+    two tokens whose intervals meet there (Section 3.1: candidates are draws from q).  30 sequences with the same
+    prompt give 30 draws from one q per call (few enough rows for the LM head to leave its partials); their uniforms sit on, or one float32 step beside, the thread, wave
+    and slice ends of the CDF of the q row the sampler itself wrote.  Each candidate must lie within 1e-5 of u in
+    that CDF and have positive q."""
+    import dataclasses
+    _say(f"small bf16 draft: candidates for uniforms on the ends of partial sums, force_generic={force}")
+    sd_ = dataclasses.replace(dg.SHAPES["small_draft_bf16"], vocab=6176, name="small_draft_v6176")
+    w = dg.make_weights(sd_, 84, BF16_LM_SCALE)
+    B, V, T = 30, sd_.vocab, 0.9
+    gd = api.Model(sd_, w, max_rows=2 * B, max_pos=64)
+    prompt = [int(t) for t in dg.make_prompt(84, 0, 23, V)]
+    rng = np.random.default_rng(84)
+    api.set_option("force_generic", force)
+    try:
+        ctx = api.Context([40] * B)
+        ctx.attach(gd)
+        H.gpu_prefill(ctx, [gd], [prompt] * B)
+        cand = torch.full((B, 1), -1, dtype=torch.int32, device="cuda")
+        q = torch.zeros((B, 1, V), dtype=torch.float32, device="cuda")
+
+        def draw(u):
+            api.sd_draft(gd, ctx, None, B, 1, T, H.dev(u.reshape(B, 1).astype(np.float32)), cand, q)
+            ctx.sync()
+            for b in range(B):
+                ctx.truncate(gd, b, len(prompt) - 1)
+            return cand.cpu().numpy()[:, 0].copy(), q.cpu().numpy()[:, 0].copy()
+
+        _, q0 = draw(np.full(B, 0.5))
+        assert all(np.array_equal(q0[b], q0[0]) for b in range(B)), "equal prompts must give equal q rows"
+        qd = q0[0].astype(np.float64)
+        cdf = np.cumsum(qd) / qd.sum()
+        other = trials = 0
+        for ends in (np.arange(3, V - 4, 4), np.arange(255, V - 4, 256), np.arange(2047, V - 4, 2048)) * 8:
+            ks = rng.choice(ends, B // 3)
+            us = np.concatenate([[np.float32(cdf[k]), np.nextafter(np.float32(cdf[k]), np.float32(0)),
+                                  np.nextafter(np.float32(cdf[k]), np.float32(1))] for k in ks]).astype(np.float32)
+            us = np.clip(us, np.float32(2.0 ** -24), np.float32(1.0 - 2.0 ** -24))
+            c, q1 = draw(us)
+            assert np.array_equal(q1, q0)
+            for b in range(B):
+                trials += 1
+                ref = oracle.sample_cdf(qd, float(us[b]))[0]
+                if int(c[b]) != ref:
+                    other += 1
+                    assert 0 <= c[b] < V and qd[c[b]] > 0, (b, int(c[b]), ref)
+                    d = oracle.cdf_distance(qd, float(us[b]), int(c[b]))
+                    assert d < 1e-5, (b, float(us[b]), int(c[b]), ref, d)
+        _say(f"  {trials} uniforms, {other} resolved to the neighbouring token")
+        ctx.close()
+    finally:
+        api.set_option("force_generic", 0)
+    gd.close()
+
+
 @pytest.mark.parametrize("T", [0.0, 0.9])
 def test_draft_sampler_from_the_lm_heads_partials_matches_the_whole_row_sampler(T):
     """The LM head of a bf16 model leaves (max, sum of exponentials, arg-max) per 32 columns; the draft sampler
