@@ -52,7 +52,7 @@ def check_against_oracle(logits, q, cand, u, T, na, nx, thr=1e-5):
 
 @pytest.mark.parametrize("V,gamma,T,rho", [(32000, 8, 1.0, 0.5), (32000, 8, 0.7, 0.9), (32000, 5, 1.0, 0.0),
                                            (32000, 5, 0.0, 0.9), (50000, 3, 1.0, 0.5), (1024, 4, 1.0, 0.5),
-                                           (32000, 0, 1.0, 0.0)])
+                                           (32000, 0, 1.0, 0.0), (262144, 2, 1.0, 0.5)])
 def test_accept_alone_matches_oracle(V, gamma, T, rho):
     print(f"sd_accept V={V} gamma={gamma} T={T} rho={rho}", flush=True)
     B = 6
@@ -73,7 +73,7 @@ def test_accept_alone_matches_oracle(V, gamma, T, rho):
 
 
 @pytest.mark.parametrize("V,gamma,n_trials", [(2772, 0, 1500), (2772, 1, 1500), (32000, 0, 900), (32000, 1, 600),
-                                              (50000, 0, 450)])
+                                              (50000, 0, 450), (262144, 0, 99)])
 def test_next_token_for_uniforms_on_the_boundaries_of_the_cdf(V, gamma, n_trials):
     """The next token is the first index whose inclusive sum of weights exceeds u * Z (Section 3.1: a draw from p, or
     from the normalised max(p - q, 0) after a rejection).  The kernels add those sums in parallel - per thread of four

@@ -122,6 +122,25 @@ def test_small_bf16_mfma_kernels_teacher_forced(T, plen, gamma):
     pair.close()
 
 
+@pytest.mark.parametrize("dtype,T", [(dg.FP32, 1.0), (dg.BF16, 1.0), (dg.BF16, 0.0)])
+def test_largest_vocabulary_teacher_forced(dtype, T):
+    """Vocabulary 262144, the largest sd_load_model accepts: the samplers' table of 64 segments of 4096 entries is
+    full, the draft sampler and the verify tail take their general (strided) kernels, a logits row is 1 MB.  One
+    layer of width 64, a few steps along the oracle's trajectory."""
+    _say(f"largest vocabulary, dtype={dtype} T={T}")
+    V = 262144
+    st_ = dg.ModelShape("vmax_t", 1, 64, 1, 64, 128, V, dtype)
+    sd_ = dg.ModelShape("vmax_d", 1, 64, 1, 64, 64, V, dtype)
+    pair = H.Pair(st_, sd_, seed=71, lm_scale=BF16_LM_SCALE if dtype == dg.BF16 else 20.0, max_rows=32, max_pos=128)
+    prompt = dg.make_prompt(71, 0, 19, V)
+    st = H.teacher_forced_parity(pair, prompt, gamma=3, T=T, n_tokens=10, seed=71)
+    _say(f"  steps={st.steps} flagged={st.flagged} logit_rel={st.max_logit_rel:.2e} q_abs={st.max_q_abs:.2e}")
+    # (a token of this vocabulary holds about 4e-6 of the mass, a few float32 steps of the running sum: a draw may
+    # land on the neighbouring token, which the decision rule allows and counts)
+    assert st.flagged <= 2 and st.max_logit_rel < (2e-2 if dtype == dg.BF16 else 1e-4)
+    pair.close()
+
+
 def test_small_bf16_mfma_matches_reference_kernels():
     """The MFMA kernels and the simple reference kernels of the library agree to bf16
     rounding on the same inputs (both are also compared with the oracle elsewhere)."""
