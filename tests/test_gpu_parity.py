@@ -723,6 +723,44 @@ def test_prefill_attention_sharing_tiles_between_row_groups_matches_the_split_ke
     gm.close()
 
 
+@pytest.mark.parametrize("shape_name,max_rows", [("small_target_bf16", 512), ("small_draft_bf16", 384)])
+def test_prefill_attention_at_every_prompt_length_matches_the_split_kernel(shape_name, max_rows):
+    """Prompt lengths 17 to 208, eight consecutive ones per batch (four or three 16-row groups per sequence and
+    forward): the last group of a prompt then ends at every offset inside a group and a 32-token tile, groups of a
+    block end at different tiles, and sequences finish in different forwards.  Shared-tile kernel against the split
+    kernel per group, verify logits of every sequence."""
+    _say(f"{shape_name}: prefill attention at prompt lengths 17..208, workspace {max_rows}")
+    st_ = dg.SHAPES[shape_name]
+    w = dg.make_weights(st_, 89, BF16_LM_SCALE)
+    gm = api.Model(st_, w, max_rows=max_rows, max_pos=256)
+    B, gamma, V = 8, 3, st_.vocab
+    cand = H.dev(dg.make_prompt(90, 0, B * gamma, V).reshape(B, gamma).astype(np.int32))
+    worst = 0.0
+    for n0 in range(17, 209, B):
+        lens = list(range(n0, n0 + B))
+        prompts = [[int(t) for t in dg.make_prompt(89, n, n, V)] for n in lens]
+        outs = []
+        for opt in (0, 1):
+            api.set_option("prefill_attn", opt)
+            try:
+                ctx = api.Context([n + 16 for n in lens])
+                ctx.attach(gm)
+                H.gpu_prefill(ctx, [gm], prompts)
+                na = torch.zeros(B, dtype=torch.int32, device="cuda")
+                nx = torch.zeros(B, dtype=torch.int32, device="cuda")
+                api.sd_verify(gm, ctx, None, B, gamma, 0.0, cand, None, None, na, nx, commit=False)
+                ctx.sync()
+                outs.append(gm.last_logits().cpu().numpy())
+                ctx.close()
+            finally:
+                api.set_option("prefill_attn", 1)
+        rel = np.abs(outs[0] - outs[1]).max() / np.abs(outs[0]).max()
+        assert np.isfinite(outs[1]).all() and rel < 5e-4, (n0, rel)
+        worst = max(worst, rel)
+    _say(f"  worst rel diff {worst:.2e}")
+    gm.close()
+
+
 @pytest.mark.parametrize("shape_name,max_rows,lens", [("small_target_bf16", 112, [700, 45]), ("small_draft_bf16", 64, [1700]),
                                                       ("draft_a_1layer", 160, [333, 650, 16])])
 def test_rope_and_cache_append_per_row_group_gives_the_bits_of_the_row_kernel(shape_name, max_rows, lens):
