@@ -132,6 +132,44 @@ def test_next_token_for_uniforms_on_the_boundaries_of_the_cdf(V, gamma, n_trials
     print(f"  {B} uniforms, {other} resolved to the neighbouring token", flush=True)
 
 
+@pytest.mark.parametrize("V", [1024, 32000, 50000])
+def test_greedy_rows_with_equal_maxima_take_the_lowest_index(V):
+    """T = 0: every logits row holds its largest value two to four times, at positions in different threads, waves
+    and 4096-column segments of the kernels' reductions; the arg max is the lowest of them (the oracle's rule), so
+    a candidate equal to a later copy is rejected and the next token is the first copy."""
+    print(f"greedy ties V={V}", flush=True)
+    B, gamma = 12, 3
+    rng = np.random.default_rng(V)
+    logits = rng.standard_normal((B, gamma + 1, V)).astype(np.float32)
+    cand = np.zeros((B, gamma), np.int32)
+    first = np.zeros((B, gamma + 1), np.int64)
+    for b in range(B):
+        for i in range(gamma + 1):
+            k = int(rng.integers(2, 5))
+            lo = int(rng.integers(0, V - 1))
+            pos = {lo, min(V - 1, lo + int(rng.choice([1, 3, 4, 255, 256, 4095, 4096])))}
+            while len(pos) < k:
+                pos.add(int(rng.integers(lo, V)))
+            pos = sorted(pos)
+            logits[b, i, pos] = 9.0
+            first[b, i] = pos[0]
+            if i < gamma:   # even sequences propose the first copy (accepted), odd ones a later copy (rejected)
+                cand[b, i] = pos[0] if (b + i) % 2 == 0 else pos[-1]
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    na = torch.full((B,), -1, dtype=torch.int32, device="cuda")
+    nx = torch.full((B,), -1, dtype=torch.int32, device="cuda")
+    ws = torch.zeros(3 * B * (gamma + 1), device="cuda")
+    api.sd_accept(dev(logits), gamma, 0.0, dev(cand), None, None, na, nx, ws)
+    torch.cuda.synchronize()
+    na_h, nx_h = na.cpu().numpy(), nx.cpu().numpy()
+    for b in range(B):
+        r_na, r_nx, _ = oracle.accept(logits[b], None, cand[b], np.zeros(gamma + 1, np.float32), 0.0)
+        want_na = next((i for i in range(gamma) if cand[b, i] != first[b, i]), gamma)
+        assert (r_na, r_nx) == (want_na, int(first[b, want_na]))          # the oracle follows the stated rule
+        assert (int(na_h[b]), int(nx_h[b])) == (r_na, r_nx), (b, int(na_h[b]), int(nx_h[b]), r_na, r_nx)
+    assert len(set(na_h.tolist())) >= 2
+
+
 def test_accept_argument_errors():
     L = api.lib()
     x = torch.zeros(8, device="cuda")

@@ -461,6 +461,51 @@ def test_draft_candidates_for_uniforms_on_the_boundaries_of_q(force):
     gd.close()
 
 
+@pytest.mark.parametrize("dist", [1, 32, 3088])
+@pytest.mark.parametrize("force", [0, 4])
+def test_greedy_draft_with_every_logit_twice_takes_the_lower_token(force, dist):
+    """T = 0 with an LM head in which token t + dist has the same row as token t (for every t whose index / dist is
+    even): every logit, the largest included, occurs twice - next to each other, one 32-column partial apart, or half
+    the vocabulary apart - and the greedy candidate must be the lower of the two, as the oracle's arg max is.  Both
+    draft samplers (from the LM head's partials; one block per row with option force_generic = 4)."""
+    import dataclasses
+    _say(f"small bf16 draft: greedy with duplicated logits at distance {dist}, force_generic={force}")
+    sd_ = dataclasses.replace(dg.SHAPES["small_draft_bf16"], vocab=6176, name="small_draft_v6176")
+    w = dict(dg.make_weights(sd_, 85, BF16_LM_SCALE))
+    V, B, gamma = sd_.vocab, 4, 6
+    lm = np.array(w["lm_head"], copy=True)
+    lower = (np.arange(V) // dist) % 2 == 0
+    lower &= np.arange(V) + dist < V
+    idx = np.nonzero(lower)[0]
+    lm[idx + dist] = lm[idx]
+    w["lm_head"] = lm
+    gd = api.Model(sd_, w, max_rows=16, max_pos=128)
+    od = oracle.OracleModel(sd_, w)
+    prompts = [[int(t) for t in dg.make_prompt(85, b, 11 + 9 * b, V)] for b in range(B)]
+    api.set_option("force_generic", force)
+    try:
+        ctx = api.Context([64] * B)
+        ctx.attach(gd)
+        H.gpu_prefill(ctx, [gd], prompts)
+        cand = torch.full((B, gamma), -1, dtype=torch.int32, device="cuda")
+        api.sd_draft(gd, ctx, None, B, gamma, 0.0, None, cand, None)
+        ctx.sync()
+        c = cand.cpu().numpy()
+        ctx.close()
+    finally:
+        api.set_option("force_generic", 0)
+    assert ((0 <= c) & (c < V)).all()
+    upper = np.zeros(V, bool)
+    upper[idx + dist] = True
+    assert not upper[c].any(), ("a duplicate's upper copy was chosen", c)
+    for b in range(B):   # and the candidates are the oracle's
+        seq = od.new_seq(64)
+        oracle.prefill(seq, prompts[b])
+        ref, _, _ = seq.draft(prompts[b], gamma, 0.0, np.zeros(gamma, np.float32))
+        assert list(c[b]) == [int(t) for t in ref], (b, c[b], ref)
+    gd.close()
+
+
 @pytest.mark.parametrize("T", [0.0, 0.9])
 def test_draft_sampler_from_the_lm_heads_partials_matches_the_whole_row_sampler(T):
     """The LM head of a bf16 model leaves (max, sum of exponentials, arg-max) per 32 columns; the draft sampler
