@@ -880,6 +880,44 @@ def test_prefill_resumed_from_an_odd_cache_length_matches_the_prefill_from_zero(
     gm.close()
 
 
+@pytest.mark.parametrize("shape_name", ["small_target_bf16", "small_draft_bf16", "tiny_target"])
+def test_the_same_call_twice_gives_the_same_bits(shape_name):
+    """Prefill in row groups, a sampled draft call and a verify pass of a ragged batch, run twice from fresh
+    contexts: logits, q, candidates and decisions must be bit-identical (no result depends on the order in which
+    blocks or atomics happen to finish)."""
+    _say(f"{shape_name}: repeatability")
+    st_ = dg.SHAPES[shape_name]
+    w = dg.make_weights(st_, 95, BF16_LM_SCALE if st_.dtype == dg.BF16 else 20.0)
+    gm = api.Model(st_, w, max_rows=96, max_pos=512)
+    B, gamma, V, T = 5, 4, st_.vocab, 0.8
+    lens = [300, 33, 170, 5, 64]
+    prompts = [[int(t) for t in dg.make_prompt(95, b, n, V)] for b, n in enumerate(lens)]
+    ud = H.dev(np.stack([dg.make_uniforms(95, dg.DRAFT_STREAM, b, 0, gamma) for b in range(B)]))
+    uv = H.dev(np.stack([dg.make_uniforms(95, dg.VERIFY_STREAM, b, 0, gamma + 1) for b in range(B)]))
+    runs = []
+    for rep in range(2):
+        ctx = api.Context([n + 16 for n in lens])
+        ctx.attach(gm)
+        H.gpu_prefill(ctx, [gm], prompts)
+        cand = torch.full((B, gamma), -1, dtype=torch.int32, device="cuda")
+        q = torch.zeros((B, gamma, V), dtype=torch.float32, device="cuda")
+        api.sd_draft(gm, ctx, None, B, gamma, T, ud, cand, q)
+        ctx.sync()
+        for b in range(B):
+            ctx.truncate(gm, b, lens[b] - 1)
+        na = torch.zeros(B, dtype=torch.int32, device="cuda")
+        nx = torch.zeros(B, dtype=torch.int32, device="cuda")
+        api.sd_verify(gm, ctx, None, B, gamma, T, cand, q, uv, na, nx, commit=True)
+        nt, kv = ctx.sync(gm)
+        runs.append((cand.cpu().numpy(), q.cpu().numpy(), gm.last_logits().cpu().numpy(), na.cpu().numpy(),
+                     nx.cpu().numpy(), np.array(nt), np.array(kv)))
+        ctx.close()
+    for a, b in zip(runs[0], runs[1]):
+        assert np.array_equal(a, b)
+    assert np.isfinite(runs[0][2]).all()
+    gm.close()
+
+
 def test_gamma_zero_is_autoregressive_decoding(tiny_pair):
     _say("gamma = 0")
     prompt = dg.make_prompt(11, 2, 12, TINY_T.vocab)
