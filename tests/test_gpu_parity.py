@@ -142,15 +142,16 @@ def test_largest_vocabulary_teacher_forced(dtype, T):
 
 
 def test_small_bf16_every_prompt_length_across_the_first_tiles():
-    """Every prompt length from 2 to 100 tokens: the cache length at the first verify pass takes every position
+    """Every prompt length from 1 (nothing to prefill: the first pass starts on an empty cache) to 100 tokens: the
+    cache length at the first verify pass takes every position
     inside the first three 32-token K / V tiles (tile starts and ends included), with gamma + 1 = 5 new rows that
     straddle a tile boundary in every fourth case; two steps each, teacher-forced, T = 1."""
-    _say("small bf16: prompt lengths 2..100")
+    _say("small bf16: prompt lengths 1..100")
     st_, sd_ = dg.SHAPES["small_target_bf16"], dg.SHAPES["small_draft_bf16"]
     pair = H.Pair(st_, sd_, seed=63, lm_scale=BF16_LM_SCALE, max_rows=32, max_pos=160)
     flagged = steps = 0
     worst = 0.0
-    for plen in range(2, 101):
+    for plen in range(1, 101):
         prompt = dg.make_prompt(63, plen, plen, st_.vocab)
         st = H.teacher_forced_parity(pair, prompt, gamma=4, T=1.0, n_tokens=4, seed=63 + plen)
         flagged += st.flagged
