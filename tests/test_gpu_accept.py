@@ -107,6 +107,7 @@ def test_next_token_for_uniforms_on_the_boundaries_of_the_cdf(V, gamma, n_trials
         u0 = np.float32(cdf[k])
         us += [u0, np.nextafter(u0, np.float32(0)), np.nextafter(u0, np.float32(1))]
     us = np.clip(np.array(us, np.float32), np.float32(2.0 ** -24), np.float32(1.0 - 2.0 ** -24))
+    us = np.concatenate([us, np.array([0.0, 2.0 ** -24, 1.0 - 2.0 ** -24], np.float32)])   # and the ends of the grid
     B = len(us)
     u = np.full((B, gamma + 1), 0.999, np.float32)   # (the candidate's own test: u = 0.999 against p / q <= 0.1)
     u[:, gamma] = us
