@@ -919,6 +919,28 @@ def test_the_same_call_twice_gives_the_same_bits(shape_name):
     gm.close()
 
 
+def test_small_bf16_ragged_batch_of_tiny_and_very_long_contexts():
+    """One batch whose contexts run from 3 to 4000 tokens (3, 9, 33, 40, 700, 1500, 2049, 4000): one to 126 K / V
+    tiles per sequence in the same attention launch, which therefore takes the split-KV kernel with most splits of
+    the short sequences empty; draft and verify compared with the oracle step by step along each sequence's own
+    trajectory, T = 1."""
+    _say("small bf16: ragged batch, contexts 3..4000")
+    st_, sd_ = dg.SHAPES["small_target_bf16"], dg.SHAPES["small_draft_bf16"]
+    seed, gamma = 97, 4
+    lens = [3, 4000, 40, 1500, 700, 9, 2049, 33]
+    V = st_.vocab
+    wt, wd = dg.make_weights(st_, seed, BF16_LM_SCALE), dg.make_weights(sd_, seed + 1, BF16_LM_SCALE)
+    ot, od = oracle.OracleModel(st_, wt), oracle.OracleModel(sd_, wd)
+    gt = api.Model(st_, wt, max_rows=64, max_pos=4200)
+    gd = api.Model(sd_, wd, max_rows=64, max_pos=4200)
+    prompts = [[int(t) for t in dg.make_prompt(seed, b, n, V)] for b, n in enumerate(lens)]
+    n, flagged = H.batched_teacher_forced(gt, gd, ot, od, prompts, gamma, 1.0, 24, seed, dg.BF16, None)
+    _say(f"  steps={n} flagged={flagged}")
+    assert n >= 5 and flagged <= H.flag_cap(n * len(lens))
+    gt.close()
+    gd.close()
+
+
 def test_gamma_zero_is_autoregressive_decoding(tiny_pair):
     _say("gamma = 0")
     prompt = dg.make_prompt(11, 2, 12, TINY_T.vocab)
