@@ -383,7 +383,7 @@ int sd_debug_stream_read(const void *buf, size_t bytes, uint32_t *scratch_word, 
  * events on its stream (a measurement mode: it adds event overhead), 0 stops.
  * option "gemm_splits" = mode*100 + s forces s K splits (1..8; 0 = automatic) for
  * the bf16 GEMMs of mode 0 (plain / residual) or 2 (SwiGLU, ignored): a tuning knob.
- * option "gemm_tile_cols" = 192 or 256 forces the block width (in weight rows) of the
+ * option "gemm_tile_cols" = 128, 192 or 256 forces the block width (in weight rows) of the
  * row-blocked GEMM for more than 64 rows where the shape allows it (0 = automatic).
  * option "norm_fold": with at most 32 rows in a forward, the add + RMSNorm launches of a
  * layer can be split between the projection before them (adds the residual, applies the gains,

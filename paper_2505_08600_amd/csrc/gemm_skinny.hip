@@ -557,8 +557,17 @@ static TileShape tile_shape(int mode, int M, int N, int n_per_seg, int K)
         int cols = 0;
         if (ok256) cols = 256;
         if (ok192 && (!ok256 || fill(192) > fill(256) + 0.1f)) cols = 192;
+        // a short K that 256-column blocks could only spread over the chip with the maximum of 8 splits of fewer than
+        // 8 steps each (the O projection of a 4096-wide model at M = 192): 128-column blocks cover it with 4 splits,
+        // which halves the fp32 slabs the add + norm launch behind it has to read
+        const bool ok128 = mode != GEMM_SWIGLU && rows_w % 128 == 0 && n_per_seg % 128 == 0;
+        if (cols == 256 && ok128 && steps < 64) {
+            const int b256 = rows_w / 256 * nmb, b128 = rows_w / 128 * nmb;
+            if (one_round_splits(b256, 256, steps) == 8 && one_round_splits(b128, 256, steps) * b128 >= 8 * b256) cols = 128;
+        }
         if (g_force_tile_cols == 256 && ok256) cols = 256;
         if (g_force_tile_cols == 192 && ok192) cols = 192;
+        if (g_force_tile_cols == 128 && ok128) cols = 128;
         if (cols) {
             // 64-row blocks when they pad M less (M = 128: 2 x 64 instead of 96 + 32) and do not cost more rounds
             const int ncol = (rows_w + cols - 1) / cols, nmb64 = (M + 63) / 64;
@@ -592,6 +601,8 @@ static hipError_t tile_launch(hipStream_t s, const uint16_t *a, ActView a_av, We
     else if (t.cols == 192 && t.bm == 96) SD_TILE(96, 64, 3, 4, 3);
     else if (t.cols == 256) SD_TILE(64, 64, 4, 4, 3);
     else if (t.cols == 192) SD_TILE(64, 64, 3, 4, 3);
+    else if (t.cols == 128 && t.bm == 96) SD_TILE(96, 64, 2, 4, 3);
+    else if (t.cols == 128 && t.bm == 64) SD_TILE(64, 64, 2, 4, 3);
     else SD_TILE(48, 128, 4, 2, 3);
     return hipGetLastError();
 }

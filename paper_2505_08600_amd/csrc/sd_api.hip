@@ -106,8 +106,9 @@ extern "C" int sd_set_option(const char *name, int32_t value)
         g_force_splits[mode] = ks;
         return SD_OK;
     }
-    if (!strcmp(name, "gemm_tile_cols")) { // weight rows per block of the row-blocked GEMM: 192, 256, or 0 = automatic
-        if (value != 0 && value != 192 && value != 256) return sd_fail(SD_EINVAL, "sd_set_option: gemm_tile_cols is 0, 192 or 256");
+    if (!strcmp(name, "gemm_tile_cols")) { // weight rows per block of the row-blocked GEMM: 128, 192, 256, or 0 = automatic
+        if (value != 0 && value != 128 && value != 192 && value != 256)
+            return sd_fail(SD_EINVAL, "sd_set_option: gemm_tile_cols is 0, 128, 192 or 256");
         g_force_tile_cols = value;
         return SD_OK;
     }

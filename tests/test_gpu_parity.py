@@ -230,10 +230,11 @@ def test_small_bf16_every_gemm_row_class_matches_reference_kernels(B):
     gt.close()
 
 
-@pytest.mark.parametrize("cols,B", [(192, 16), (192, 20), (192, 30), (256, 20), (256, 30)])
+@pytest.mark.parametrize("cols,B", [(192, 16), (192, 20), (192, 30), (256, 20), (256, 30), (128, 16), (128, 20), (128, 30)])
 def test_small_bf16_row_blocked_gemm_block_widths_match_reference_kernels(cols, B):
-    """The 96- and 64-row GEMM blocks (64 rows at batch 20: M = 120 pads less that way) are 256 or 192 weight
-    rows wide; the library picks by how well the blocks fill the chip, so each width is forced here.  d_ffn = 896 gives the 192-row SwiGLU blocks (96 output
+    """The 96- and 64-row GEMM blocks (64 rows at batch 20: M = 120 pads less that way) are 256, 192 or (plain
+    projections with a short K only) 128 weight rows wide; the library picks by how well the blocks fill the chip,
+    so each width is forced here.  d_ffn = 896 gives the 192-row SwiGLU blocks (96 output
     columns, gate/up pairs straddling waves) a partial last block: 896 = 9 * 96 + 32."""
     import dataclasses
     _say(f"small bf16: 96-row GEMM blocks forced to {cols} weight rows, batch {B}, d_ffn 896")
