@@ -557,13 +557,25 @@ static TileShape tile_shape(int mode, int M, int N, int n_per_seg, int K)
         int cols = 0;
         if (ok256) cols = 256;
         if (ok192 && (!ok256 || fill(192) > fill(256) + 0.1f)) cols = 192;
-        // a short K that 256-column blocks could only spread over the chip with the maximum of 8 splits of fewer than
-        // 8 steps each (the O projection of a 4096-wide model at M = 192): 128-column blocks cover it with 4 splits,
-        // which halves the fp32 slabs the add + norm launch behind it has to read
+        // Plain projections with few column blocks may do better with 128-column blocks.  A block's time is modelled as
+        // (K steps per split + 5 steps of fixed cost) x the cost of one of its steps (a 128-column step costs 0.68 of a
+        // 256-column one: half the weights and MFMAs, the same activation chunk) x the imbalance of its column tiles
+        // over the 8 dies (20 tiles of 256 columns at width 5120: 3 on four dies, 2 on the others); all blocks of the
+        // one round run side by side.  Against measurements at widths 4096 and 5120, M = 66 ... 288, the model picks the
+        // faster shape in every case tried: 128 columns for O and down at M <= 96 (twice the blocks in flight), for O at
+        // M = 192 (4 K splits of 8 steps instead of 8 of 4: also half the slabs for the add + norm launch behind it)
+        // and for the 5120-wide O at every M (31 against 44 us at M = 192); 256 columns for the down projection's long
+        // K at M > 96 and for QKV.
         const bool ok128 = mode != GEMM_SWIGLU && rows_w % 128 == 0 && n_per_seg % 128 == 0;
-        if (cols == 256 && ok128 && steps < 64) {
-            const int b256 = rows_w / 256 * nmb, b128 = rows_w / 128 * nmb;
-            if (one_round_splits(b256, 256, steps) == 8 && one_round_splits(b128, 256, steps) * b128 >= 8 * b256) cols = 128;
+        if (cols == 256 && ok128) {
+            auto est = [&](int c, float step_cost, int *total) {
+                const int ncol = rows_w / c, sp = one_round_splits(ncol * nmb, 256, steps);
+                *total = ncol * nmb * sp;
+                return (float)((ncol + 7) / 8 * 8) / (float)ncol * ((float)steps / (float)sp + 5.f) * step_cost;
+            };
+            int t256, t128;
+            const float e256 = est(256, 1.f, &t256), e128 = est(128, 0.68f, &t128);
+            if (t128 <= 256 && e128 < e256) cols = 128;
         }
         if (g_force_tile_cols == 256 && ok256) cols = 256;
         if (g_force_tile_cols == 192 && ok192) cols = 192;
