@@ -494,13 +494,14 @@ def batch32_step(api, dg, torch, np, gt, st, seed, B, len_range, gamma, T=0.7, s
 
 
 def prefill_bench(api, dg, torch, np, args):
-    """The step before the hot path: sd_prefill of one prompt into the 7B-shape target, for two workspace sizes
-    (max_rows decides how many 16-row groups one forward carries).  Issued MFMA work counts the hi and the lo
+    """The step before the hot path: sd_prefill of one prompt into the 7B-shape target, for four workspace sizes
+    (max_rows decides how many 16-row groups one forward carries; the GEMMs' blocks fill the chip in whole rounds
+    at 1024 and 2048 rows and in one and a half at 576).  Issued MFMA work counts the hi and the lo
     plane of every row (4 flops per parameter and token); attention is not counted."""
     st = dg.SHAPES["t7b"] if not args.layers else dg.with_layers(dg.SHAPES["t7b"], args.layers)
     wt = dg.make_weights(st, 2025, threads=16)
     res = []
-    for max_rows in (192, 576):
+    for max_rows in (192, 576, 1024, 2048):
         gt = api.Model(st, wt, max_rows, 8300)
         for n in (512, 2048, 8192):
             prompt = [[int(t) for t in dg.make_prompt(2025, 0, n, st.vocab)]]

@@ -337,18 +337,20 @@ def test_config5_synthetic_q_long_contexts(config5_rig, rho):
 
 
 @pytest.mark.timeout(900)
-def test_prefill_at_full_width_matches_oracle_and_the_split_kernels():
-    """The prefill path at the 7B shape's widths in the configuration bench.py --prefill-bench times (576-row
+@pytest.mark.parametrize("max_rows,n_ctx", [(576, 600), (1024, 1300)])
+def test_prefill_at_full_width_matches_oracle_and_the_split_kernels(max_rows, n_ctx):
+    """The prefill path at the 7B shape's widths in two of the configurations bench.py --prefill-bench times (576-row
     workspace: 36 row groups of one prompt per forward, nine blocks of four groups per head, tile ranges split
-    over blocks with the combine pass), cut to two layers so that the oracle can prefill the same 600-token prompt:
+    over blocks with the combine pass; 1024-row workspace: 64 groups, the GEMMs in 64-row blocks, a full forward
+    followed by a partial one), cut to two layers so that the oracle can prefill the same prompt:
     the verify pass that follows must give the oracle's logits.  The same prefill through the decode path's
     split kernel per group (prefill_attn = 0) agrees to rounding level, and with the cache append one block per
     row (rope_group = 0) bit for bit."""
-    seed, gamma, n_ctx = 2031, 5, 600
+    seed, gamma = 2031, 5
     st_ = dg.with_layers(dg.SHAPES["t7b"], 2)
     wt = dg.make_weights(st_, seed, threads=16)
     om = oracle.OracleModel(st_, wt)
-    gm = api.Model(st_, wt, max_rows=576, max_pos=n_ctx + 64)
+    gm = api.Model(st_, wt, max_rows=max_rows, max_pos=n_ctx + 64)
     V = st_.vocab
     prompt = [int(t) for t in dg.make_prompt(seed, 0, n_ctx, V)]
     cand = dg.make_prompt(seed + 1, 0, gamma, V).astype(np.int32)
