@@ -46,6 +46,9 @@ def test_argument_errors_do_not_need_a_gpu():
     assert L.sd_set_option(b"norm_fold", 3) == api.SD_EINVAL and L.sd_set_option(b"norm_fold", 0) == api.SD_OK
     assert L.sd_set_option(b"rope_group", 2) == api.SD_EINVAL and L.sd_set_option(b"rope_group", 1) == api.SD_OK
     assert L.sd_set_option(b"prefill_attn", 2) == api.SD_EINVAL and L.sd_set_option(b"prefill_attn", 1) == api.SD_OK
+    assert L.sd_set_option(b"gemm_tile_cols", 64) == api.SD_EINVAL and L.sd_set_option(b"gemm_tile_cols", 128) == api.SD_OK
+    assert L.sd_set_option(b"gemm_tile_cols", 0) == api.SD_OK
+    assert L.sd_set_option(b"no_such_option", 1) == api.SD_EINVAL
     assert L.sd_ctx_create(0, None, None) == api.SD_EINVAL
     assert L.sd_draft(None, None, None, 1, 4, 1.0, None, None, None, None) == api.SD_EINVAL
     assert L.sd_verify(None, None, None, 1, 4, 1.0, None, None, None, None, None, 1, None) == api.SD_EINVAL
