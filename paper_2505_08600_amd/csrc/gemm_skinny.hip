@@ -527,55 +527,58 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_ksplit_kernel(const uint16_t 
 // 128 columns, two resident per unit.  A block of the 96-row shapes has a compute unit to itself
 // (~500 registers per wave), so the K splits are chosen to cover the chip in one round of blocks.
 struct TileShape {
-    int cols;   // weight rows per block (0: shape not supported)
-    int bm;     // rows per block
-    int blocks; // blocks of one K split
-    int slots;  // blocks resident at once
+    int cols;  // weight rows per block (0: shape not supported)
+    int bm;    // rows per block
+    int ncol;  // column tiles
+    int nmb;   // row blocks
+    int slots; // blocks resident at once on the whole chip
 };
-static int one_round_splits(int blocks, int slots, int steps)
+// Column tile t runs on die t % 8 with all its row blocks and K splits (they share the die's L2), so the busiest
+// die carries ceil(ncol / 8) tiles: 20 tiles put 3 on four dies and 2 on the others.  A launch is one round of
+// blocks only if that die's share fits its eighth of the slots - counting blocks over the whole chip instead let
+// the 5120-wide projections run a second round on half the dies (44 against 31 us for the O projection at M = 192).
+static int die_blocks(int ncol, int nmb, int ks) { return (ncol + 7) / 8 * nmb * ks; }
+static int one_round_splits(int ncol, int nmb, int slots, int steps)
 {
     int ks = 1;
-    while (ks < 8 && blocks * (ks + 1) <= slots && (steps + ks) / (ks + 1) >= 4) ks++;
+    while (ks < 8 && die_blocks(ncol, nmb, ks + 1) * 8 <= slots && (steps + ks) / (ks + 1) >= 4) ks++;
     return ks;
 }
+static int die_rounds(int ncol, int nmb, int ks, int slots) { return (die_blocks(ncol, nmb, ks) * 8 + slots - 1) / slots; }
 int g_force_tile_cols = 0; // weight rows per 96-row block forced by option "gemm_tile_cols" (0 = automatic)
 static TileShape tile_shape(int mode, int M, int N, int n_per_seg, int K)
 {
     const int out_per_col = mode == GEMM_SWIGLU ? 2 : 1; // weight rows per output column
     const int rows_w = N * out_per_col;                  // weight rows streamed
-    TileShape t = {0, 0, 0, 0};
+    TileShape t = {0, 0, 0, 0, 0};
     if (M > 64) {
         const int nmb = (M + 95) / 96, steps = K / 128;
         const bool ok256 = rows_w % 256 == 0 && (mode == GEMM_SWIGLU || n_per_seg % 256 == 0);
         // (SwiGLU blocks of 192 weight rows = 96 output columns may end in a partial block)
         const bool ok192 = mode == GEMM_SWIGLU || (rows_w % 192 == 0 && n_per_seg % 16 == 0);
         auto fill = [&](int cols) { // fraction of the 256 units busy, averaged over the rounds of blocks
-            const int blocks = (rows_w + cols - 1) / cols * nmb;
-            const int tot = blocks * (mode == GEMM_SWIGLU ? 1 : one_round_splits(blocks, 256, steps));
-            return (float)tot / (256.f * (float)((tot + 255) / 256));
+            const int ncol = (rows_w + cols - 1) / cols;
+            const int ks = mode == GEMM_SWIGLU ? 1 : one_round_splits(ncol, nmb, 256, steps);
+            return (float)(ncol * nmb * ks) / (256.f * (float)die_rounds(ncol, nmb, ks, 256));
         };
         int cols = 0;
         if (ok256) cols = 256;
         if (ok192 && (!ok256 || fill(192) > fill(256) + 0.1f)) cols = 192;
-        // Plain projections with few column blocks may do better with 128-column blocks.  A block's time is modelled as
-        // (K steps per split + 5 steps of fixed cost) x the cost of one of its steps (a 128-column step costs 0.68 of a
-        // 256-column one: half the weights and MFMAs, the same activation chunk) x the imbalance of its column tiles
-        // over the 8 dies (20 tiles of 256 columns at width 5120: 3 on four dies, 2 on the others); all blocks of the
-        // one round run side by side.  Against measurements at widths 4096 and 5120, M = 66 ... 288, the model picks the
-        // faster shape in every case tried: 128 columns for O and down at M <= 96 (twice the blocks in flight), for O at
-        // M = 192 (4 K splits of 8 steps instead of 8 of 4: also half the slabs for the add + norm launch behind it)
-        // and for the 5120-wide O at every M (31 against 44 us at M = 192); 256 columns for the down projection's long
-        // K at M > 96 and for QKV.
+        // Plain projections with few column tiles may do better with 128-column blocks.  A block's time is modelled as
+        // rounds on the busiest die x (K steps per split + 5 steps of fixed cost) x the cost of one of its steps (a
+        // 128-column step costs 0.68 of a 256-column one: half the weights and MFMAs, the same activation chunk).
+        // Against measurements at widths 4096 and 5120, M = 66 ... 576, it picks 128 columns for O and down at M <= 96
+        // (twice the blocks in flight), for O at M = 192 (4 K splits of 8 steps instead of 8 of 4: also half the slabs
+        // for the add + norm launch behind it) and for the 5120-wide O and down where 20 wide tiles would leave four
+        // dies with half as much again as the others; 256 columns for the 4096-wide down projection at M > 96 and for
+        // QKV.
         const bool ok128 = mode != GEMM_SWIGLU && rows_w % 128 == 0 && n_per_seg % 128 == 0;
         if (cols == 256 && ok128) {
-            auto est = [&](int c, float step_cost, int *total) {
-                const int ncol = rows_w / c, sp = one_round_splits(ncol * nmb, 256, steps);
-                *total = ncol * nmb * sp;
-                return (float)((ncol + 7) / 8 * 8) / (float)ncol * ((float)steps / (float)sp + 5.f) * step_cost;
+            auto est = [&](int c, float step_cost) {
+                const int ncol = rows_w / c, sp = one_round_splits(ncol, nmb, 256, steps);
+                return (float)die_rounds(ncol, nmb, sp, 256) * ((float)steps / (float)sp + 5.f) * step_cost;
             };
-            int t256, t128;
-            const float e256 = est(256, 1.f, &t256), e128 = est(128, 0.68f, &t128);
-            if (t128 <= 256 && e128 < e256) cols = 128;
+            if (est(128, 0.68f) < est(256, 1.f)) cols = 128;
         }
         if (g_force_tile_cols == 256 && ok256) cols = 256;
         if (g_force_tile_cols == 192 && ok192) cols = 192;
@@ -583,15 +586,15 @@ static TileShape tile_shape(int mode, int M, int N, int n_per_seg, int K)
         if (cols) {
             // 64-row blocks when they pad M less (M = 128: 2 x 64 instead of 96 + 32) and do not cost more rounds
             const int ncol = (rows_w + cols - 1) / cols, nmb64 = (M + 63) / 64;
-            auto rounds = [&](int blocks) {
-                return (blocks * (mode == GEMM_SWIGLU ? 1 : one_round_splits(blocks, 256, steps)) + 255) / 256;
+            auto rounds = [&](int rb) {
+                return die_rounds(ncol, rb, mode == GEMM_SWIGLU ? 1 : one_round_splits(ncol, rb, 256, steps), 256);
             };
-            const bool use64 = nmb64 * 64 < nmb * 96 && rounds(ncol * nmb64) * 64 <= rounds(ncol * nmb) * 96;
-            return use64 ? TileShape{cols, 64, ncol * nmb64, 256} : TileShape{cols, 96, ncol * nmb, 256};
+            const bool use64 = nmb64 * 64 < nmb * 96 && rounds(nmb64) * 64 <= rounds(nmb) * 96;
+            return use64 ? TileShape{cols, 64, ncol, nmb64, 256} : TileShape{cols, 96, ncol, nmb, 256};
         }
     }
     if (rows_w % 128 == 0 && (mode == GEMM_SWIGLU || n_per_seg % 128 == 0))
-        t = TileShape{128, 48, rows_w / 128 * ((M + 47) / 48), 512};
+        t = TileShape{128, 48, rows_w / 128, (M + 47) / 48, 512};
     return t;
 }
 
@@ -639,7 +642,7 @@ int gemm_skinny_splits(int mode, int M, int N, int K, int n_per_seg)
     } else { // row-blocked kernel.  Measured at M = 192: a block costs about five K steps of fixed time, so one
              // round of blocks with the K range cut as finely as that allows beats several rounds of shorter blocks
         const TileShape t = tile_shape(mode, M, N, n_per_seg, K);
-        ks = t.cols ? one_round_splits(t.blocks, t.slots, steps) : 1;
+        ks = t.cols ? one_round_splits(t.ncol, t.nmb, t.slots, steps) : 1;
     }
     split_geometry(K, ks, &kps, &ny);
     return ny;
