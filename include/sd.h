@@ -372,6 +372,13 @@ int sd_debug_read(sd_model *m, const char *name, float *out, int32_t rows);
  * kind 3: key cache of one head, same arguments (32-token tiles in MFMA operand order).
  * Returns -1 for an unknown kind or arguments outside the layout's domain. */
 int64_t sd_debug_layout_index(int32_t kind, int64_t a, int64_t b, int64_t c, int64_t d);
+/* Host-only (no GPU call): the launch plan of a bf16 GEMM with more than 32 rows (the row-blocked kernel).
+ * mode 0 = plain projection, 2 = gate/up pair with the SwiGLU epilogue (n = output columns);
+ * n_per_seg = output columns per weight segment (n for one matrix, n / 3 for q | k | v).
+ * plan[0] = weight rows per block, [1] = rows per block, [2] = column tiles, [3] = row blocks,
+ * [4] = K splits, [5] = blocks on the busiest of the 8 dies (column tile t runs on die t mod 8).
+ * Returns 0, or SD_EINVAL when the kernel does not take the shape. */
+int sd_debug_gemm_plan(int32_t mode, int32_t m, int32_t n, int32_t k, int32_t n_per_seg, int32_t plan[6]);
 /* Measurement helper: one kernel that only reads `bytes` bytes (16-byte aligned, dev) once with 16-byte loads,
  * the practical ceiling that the weight-streaming kernels are compared with.  scratch_word: dev uint32, may be
  * written.  Only enqueues on `stream`. */

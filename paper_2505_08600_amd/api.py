@@ -25,7 +25,7 @@ EXPORTS = ["sd_load_model", "sd_free_model", "sd_ctx_create", "sd_ctx_free", "sd
            "sd_ctx_set_kv", "sd_ctx_truncate", "sd_debug_read", "sd_debug_layout_index", "sd_last_logits", "sd_set_option", "sd_profile_read", "sd_last_error",
            "sd_eq1_speedup", "sd_choose_gamma", "sd_alpha_hat", "sd_model_set_lora", "sd_ctx_set_adapters",
            "sd_classifier_create", "sd_classifier_destroy", "sd_route_classifier", "sd_accept",
-           "sd_accept_static", "sd_debug_stream_read",
+           "sd_accept_static", "sd_debug_stream_read", "sd_debug_gemm_plan",
            "sd_policy_set", "sd_policy_choose", "sd_policy_read"]
 
 
@@ -94,6 +94,7 @@ def lib():
         L.sd_ctx_set_kv.argtypes = [vp, vp, i32, i32, vp, vp, i32]
         L.sd_ctx_truncate.argtypes = [vp, vp, i32, i32]
         L.sd_debug_read.argtypes = [vp, C.c_char_p, vp, i32]
+        L.sd_debug_gemm_plan.argtypes = [i32, i32, i32, i32, i32, C.POINTER(C.c_int32)]
         L.sd_debug_layout_index.argtypes = [i32, C.c_int64, C.c_int64, C.c_int64, C.c_int64]
         L.sd_debug_layout_index.restype = C.c_int64
         L.sd_last_logits.argtypes = [vp, vp, i32, C.POINTER(i32)]
@@ -323,6 +324,15 @@ class Context:
         k, v = np.ascontiguousarray(k), np.ascontiguousarray(v)
         _check(lib().sd_ctx_set_kv(self.h, m.h, layer, seq, k.ctypes.data_as(C.c_void_p),
                                    v.ctypes.data_as(C.c_void_p), k.shape[0]))
+
+
+def gemm_plan(mode: int, m: int, n: int, k: int, n_per_seg: Optional[int] = None):
+    """sd_debug_gemm_plan -> (weight rows per block, rows per block, column tiles, row blocks, K splits, blocks on the
+    busiest die), or None when the row-blocked kernel does not take the shape."""
+    plan = (C.c_int32 * 6)()
+    if lib().sd_debug_gemm_plan(mode, m, n, k, n if n_per_seg is None else n_per_seg, plan) != SD_OK:
+        return None
+    return tuple(int(x) for x in plan)
 
 
 def layout_index(kind: int, a: int, b: int, c: int, d: int = 0) -> int:

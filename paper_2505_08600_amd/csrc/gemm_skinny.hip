@@ -648,6 +648,22 @@ int gemm_skinny_splits(int mode, int M, int N, int K, int n_per_seg)
     return ny;
 }
 
+// What tile_launch would do for this shape (host only; for tests of the choice itself).
+int gemm_tile_plan(int mode, int M, int N, int K, int n_per_seg, int plan[6])
+{
+    if (M <= 32 || K < 128 || K % 128 != 0 || (mode != GEMM_STORE && mode != GEMM_SWIGLU)) return -1;
+    const TileShape t = tile_shape(mode, M, N, n_per_seg, K);
+    if (!t.cols) return -1;
+    const int ks = gemm_skinny_splits(mode, M, N, K, n_per_seg);
+    plan[0] = t.cols;
+    plan[1] = t.bm;
+    plan[2] = t.ncol;
+    plan[3] = t.nmb;
+    plan[4] = ks;
+    plan[5] = die_blocks(t.ncol, t.nmb, ks);
+    return 0;
+}
+
 // Blocks (= entries of NormFold::ss_out per row) of a producer launch with N output columns.
 int gemm_normfold_blocks(int N) { return N % 32 == 0 && N / 32 >= 256 ? N / 32 : N / 16; }
 

@@ -649,6 +649,16 @@ extern "C" int sd_ctx_truncate(sd_ctx *c, sd_model *m, int32_t seq, int32_t len)
     return SD_OK;
 }
 
+extern "C" int sd_debug_gemm_plan(int32_t mode, int32_t m, int32_t n, int32_t k, int32_t n_per_seg, int32_t plan[6])
+{
+    if (!plan || m < 1 || n < 1 || k < 1 || n_per_seg < 1) return sd_fail(SD_EINVAL, "sd_debug_gemm_plan: bad argument");
+    int p[6];
+    if (gemm_tile_plan(mode, m, n, k, n_per_seg, p) != 0)
+        return sd_fail(SD_EINVAL, "sd_debug_gemm_plan: not a shape of the row-blocked kernel");
+    for (int i = 0; i < 6; i++) plan[i] = p[i];
+    return SD_OK;
+}
+
 extern "C" int64_t sd_debug_layout_index(int32_t kind, int64_t a, int64_t b, int64_t c, int64_t d)
 {
     if (a < 0 || b < 0 || c <= 0) return -1;

@@ -416,7 +416,8 @@ hipError_t launch_stream_read(hipStream_t s, const void *buf, size_t bytes, uint
 // GEMM_STORE: C receives `splits` partial slabs (slab stride c_split_stride floats) that the consumer adds;
 // GEMM_SWIGLU: Cact receives the bf16 hi/lo planes.  gemm_skinny_splits tells how many slabs to expect.
 int gemm_skinny_splits(int mode, int M, int N, int K, int n_per_seg);
-int gemm_normfold_blocks(int N); // blocks of a NormFold producer launch with N output columns
+int gemm_normfold_blocks(int N);
+int gemm_tile_plan(int mode, int M, int N, int K, int n_per_seg, int plan[6]); // host only: the row-blocked GEMM's launch plan // blocks of a NormFold producer launch with N output columns
 // ls: softmax partials wanted beside the result (GEMM_STORE without K splits only); *ls_done tells whether the
 // kernel chosen for the shape wrote them.
 // nf: norm split between producer and consumer (few-row kernels only: the launcher returns

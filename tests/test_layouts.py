@@ -67,3 +67,36 @@ def test_key_cache_tiles_are_in_score_operand_order(hd):
                         got = idx[tile * 32 + tok, 32 * c + 8 * g: 32 * c + 8 * g + 8]
                         want = base + (((2 * c + ab) * G + g) * 16 + i) * 8 + np.arange(8)
                         assert np.array_equal(got, want)
+
+
+def test_row_blocked_gemm_plans_fit_the_busiest_die_in_one_round():
+    """The launch plan of the row-blocked GEMM (host logic only).  Column tile t of a launch runs on die t mod 8 with
+    all its row blocks and K splits, so the busiest die carries ceil(tiles / 8) * row blocks * splits blocks; K is
+    split only as far as that die's 32 compute units (64 resident blocks for the 48-row shape) take in one round -
+    counted over the whole chip instead, the 20 wide tiles of a 5120-wide projection would put 36 blocks on four
+    dies.  Blocks cover the matrix, plain projections with few column tiles take the 128-column shape, and the shapes
+    of the measured configurations keep the plans they were measured with."""
+    for d, f in ((4096, 11008), (5120, 13824), (8192, 28672), (2048, 5632)):
+        for m in list(range(33, 200, 7)) + [256, 288, 384, 512, 576, 640, 768, 1024, 2048]:
+            for mode, n, k, seg in ((0, 3 * d, d, d), (0, d, d, d), (2, f, d, f), (0, d, f, d), (0, 32000, d, 32000)):
+                plan = api.gemm_plan(mode, m, n, k, seg)
+                assert plan is not None, (d, m, mode, n, k)
+                cols, bm, ncol, nmb, ks, die = plan
+                assert cols in (128, 192, 256) and bm in (48, 64, 96) and 1 <= ks <= 8
+                assert ncol * cols >= n * (2 if mode == 2 else 1) > (ncol - 1) * cols
+                assert nmb * bm >= m > (nmb - 1) * bm
+                assert die == -(-ncol // 8) * nmb * ks
+                if mode == 2:
+                    assert ks == 1          # silu(gate) * up needs complete sums
+                if ks > 1:
+                    assert die <= (64 if bm == 48 else 32), (d, m, mode, n, k, plan)
+                    assert k // 128 // ks >= 3      # no split shorter than about four K steps
+    assert api.gemm_plan(0, 32, 4096, 4096) is None and api.gemm_plan(0, 192, 4096, 4000) is None
+    # the shapes of config 3 (7B, M = 192) and config 4 (13B, M = 128 / 192 / 288)
+    assert api.gemm_plan(0, 192, 4096, 4096) == (128, 96, 32, 2, 4, 32)         # O: 4 splits of 8 steps, not 8 of 4
+    assert api.gemm_plan(0, 192, 4096, 11008) == (256, 96, 16, 2, 8, 32)        # down: the wide blocks
+    assert api.gemm_plan(0, 192, 12288, 4096, 4096) == (192, 96, 64, 2, 2, 32)  # QKV
+    assert api.gemm_plan(2, 192, 11008, 4096) == (192, 96, 115, 2, 1, 30)       # gate/up
+    assert api.gemm_plan(0, 192, 5120, 13824)[4:] == (5, 30)                    # 20 tiles: 3 on a die, so 5 splits, not 6
+    assert api.gemm_plan(0, 192, 5120, 5120)[0] == 128 and api.gemm_plan(0, 288, 5120, 13824)[0] == 128
+    assert api.gemm_plan(0, 96, 4096, 11008)[:1] + api.gemm_plan(0, 96, 4096, 11008)[4:] == (128, 8, 32)   # M <= 96: twice the blocks
