@@ -545,6 +545,24 @@ static int one_round_splits(int ncol, int nmb, int slots, int steps)
     return ks;
 }
 static int die_rounds(int ncol, int nmb, int ks, int slots) { return (die_blocks(ncol, nmb, ks) * 8 + slots - 1) / slots; }
+// K splits of a launch: as many as keep the busiest die at one round of blocks; where not even the unsplit launch fits one
+// round, the count that makes rounds x (K steps per split + 5 steps of fixed cost) smallest (by more than 5 %): the 96-row
+// QKV blocks of a 4096-wide model at M = 576 come to one and a half rounds, two splits to three full ones of half the
+// length (measured 120 -> 107 us; three and four splits 124 us, as the model has it).
+static int tile_splits(int ncol, int nmb, int slots, int steps)
+{
+    if (die_rounds(ncol, nmb, 1, slots) == 1) return one_round_splits(ncol, nmb, slots, steps);
+    int best = 1;
+    float best_cost = (float)die_rounds(ncol, nmb, 1, slots) * ((float)steps + 5.f);
+    for (int ks = 2; ks <= 8 && (steps + ks - 1) / ks >= 4; ks++) {
+        const float cost = (float)die_rounds(ncol, nmb, ks, slots) * ((float)steps / (float)ks + 5.f);
+        if (cost < 0.95f * best_cost) {
+            best = ks;
+            best_cost = cost;
+        }
+    }
+    return best;
+}
 int g_force_tile_cols = 0; // weight rows per 96-row block forced by option "gemm_tile_cols" (0 = automatic)
 static TileShape tile_shape(int mode, int M, int N, int n_per_seg, int K)
 {
@@ -642,7 +660,7 @@ int gemm_skinny_splits(int mode, int M, int N, int K, int n_per_seg)
     } else { // row-blocked kernel.  Measured at M = 192: a block costs about five K steps of fixed time, so one
              // round of blocks with the K range cut as finely as that allows beats several rounds of shorter blocks
         const TileShape t = tile_shape(mode, M, N, n_per_seg, K);
-        ks = t.cols ? one_round_splits(t.ncol, t.nmb, t.slots, steps) : 1;
+        ks = t.cols ? tile_splits(t.ncol, t.nmb, t.slots, steps) : 1;
     }
     split_geometry(K, ks, &kps, &ny);
     return ny;
