@@ -681,9 +681,12 @@ hipError_t launch_attn_fused_bf16(hipStream_t s, const float *qkv, int n_slabs, 
     if (R < 1 || R > 16 || (hd != 64 && hd != 128) || n_slabs < 1 || n_slabs > 8) return hipErrorNotSupported;
     if (n_seq > 65535 || H > 65535) return hipErrorNotSupported;
     const int tiles_upper = (len_upper + AT_TILE - 1) / AT_TILE;
-    // one block per (sequence, head): fine when those alone fill the chip, or when every wave has
-    // at most a few tiles anyway
-    if (!((long)n_seq * H >= 512 || tiles_upper <= 48)) return hipErrorNotSupported;
+    // one block per (sequence, head): fine when every wave has at most a few tiles anyway, or when those blocks
+    // alone fill the chip and the contexts stay below about 2000 tokens - beyond that the split kernel, whose blocks
+    // only stream, is faster even with its RoPE and combine launches (32 x 2048 tokens, 40 heads: 20.1 against
+    // 20.4 ms for the whole verify pass; 64 sequences of 1024 - 8192 tokens: 38.0 against 38.6; at 32 sequences of
+    // up to 1024 tokens the fused kernel wins, 8.26 against 8.50 ms)
+    if (!(tiles_upper <= 48 || ((long)n_seq * H >= 512 && tiles_upper < 64))) return hipErrorNotSupported;
     // with more than two blocks per compute unit and short contexts the 4-wave shape (two resident blocks
     // per unit) hides each block's prologue and merge behind its neighbour's streaming; from about 40 tiles
     // per block on, the 8-wave shape streams faster (measured: 4.9 against 4.6 TB/s at 2048 tokens, 5.5
